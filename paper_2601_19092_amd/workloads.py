@@ -1,0 +1,158 @@
+"""Seeded synthetic inputs for the five benchmark configurations.
+
+This module only draws random numbers and casts them to the storage formats; it holds none of
+the arithmetic of layout evaluation, relayout or GEMM, so that the HIP path and the CPU oracle
+can both be fed the very same bits.  Everything is generated on the host with
+numpy.random.Philox; the casts are PyTorch's CPU round-to-nearest-even conversions.
+
+The paper's own GEMM workload (batch 8192 against LLM weight shapes, Sec. 4.1) is only given
+in a figure; these synthetic shapes stand in for it.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional, Tuple
+
+import numpy as np
+import torch
+
+SEED_BASE = 19092
+
+
+def _rng(seed: int) -> np.random.Generator:
+    return np.random.Generator(np.random.Philox(seed))
+
+
+def to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> bf16 (round to nearest even) -> raw uint16 words."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.bfloat16)
+    return t.view(torch.int16).numpy().view(np.uint16).copy()
+
+
+def to_e4m3_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> clip to the finite range [-448, 448] -> OCP e4m3 (round to nearest even) -> raw bytes."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).clamp_(-448.0, 448.0)
+    return t.to(torch.float8_e4m3fn).view(torch.uint8).numpy().copy()
+
+
+def normal(seed: int, shape, std: float = 1.0) -> np.ndarray:
+    return (_rng(seed).standard_normal(shape, dtype=np.float32) * np.float32(std)).astype(np.float32)
+
+
+def uniform(seed: int, shape, lo: float, hi: float) -> np.ndarray:
+    return _rng(seed).uniform(lo, hi, size=shape).astype(np.float32)
+
+
+@dataclass
+class GemmInputs:
+    """A is logical (M, K) stored row-major; B is logical (K, N) stored column-major, i.e. the
+    array `b_nk` below is its memory image, a row-major (N, K) matrix."""
+    M: int
+    N: int
+    K: int
+    dtype: str                      # "bf16" | "fp8"
+    a_mk: np.ndarray                # raw words, shape (M, K)
+    b_nk: np.ndarray                # raw words, shape (N, K)
+    scale_a: Optional[np.ndarray] = None   # fp32 (ceil(M/128), ceil(K/128))
+    scale_b: Optional[np.ndarray] = None   # fp32 (ceil(N/128), ceil(K/128))
+    out_dtype: str = "bf16"         # "f32" | "bf16"
+
+
+def gemm_bf16(M: int, N: int, K: int, seed: int, std_a: float = 1.0, std_b: float = 1.0,
+              out_dtype: str = "bf16") -> GemmInputs:
+    a = to_bf16_bits(normal(seed, (M, K), std_a))
+    b = to_bf16_bits(normal(seed + 1000, (N, K), std_b))
+    return GemmInputs(M, N, K, "bf16", a, b, out_dtype=out_dtype)
+
+
+def gemm_fp8(M: int, N: int, K: int, seed: int, block: int = 128, scaled: bool = True) -> GemmInputs:
+    a = to_e4m3_bits(normal(seed, (M, K)))
+    b = to_e4m3_bits(normal(seed + 1000, (N, K)))
+    sa = sb = None
+    if scaled:
+        kb = -(-K // block)
+        sa = uniform(seed + 2000, (-(-M // block), kb), 0.5, 2.0)
+        sb = uniform(seed + 3000, (-(-N // block), kb), 0.5, 2.0)
+    return GemmInputs(M, N, K, "fp8", a, b, sa, sb, out_dtype="bf16")
+
+
+def relayout_words(rows: int, cols: int, seed: int, kind: str = "uniform") -> np.ndarray:
+    """Raw bf16 words of a (rows, cols) tensor.  kind="uniform": i.i.d. uniform[-1, 1] cast to
+    bf16; kind="index": word = (flat index * 40503) mod 65536, so that a misplaced chunk cannot
+    hide behind equal values."""
+    if kind == "uniform":
+        return to_bf16_bits(uniform(seed, (rows, cols), -1.0, 1.0))
+    if kind == "index":
+        idx = np.arange(rows * cols, dtype=np.uint64).reshape(rows, cols)
+        return ((idx * np.uint64(40503)) % np.uint64(65536)).astype(np.uint16)
+    raise ValueError(kind)
+
+
+# The five configurations --------------------------------------------------------------
+def config1() -> GemmInputs:
+    """bf16 GEMM M=N=K=256, entries N(0,1), fp32 output."""
+    return gemm_bf16(256, 256, 256, SEED_BASE + 1, out_dtype="f32")
+
+
+def config2(kind: str = "uniform", rows: int = 8192, cols: int = 8192) -> np.ndarray:
+    """bf16 tensor to be re-laid out from row-major to swizzled 128x64 tiles."""
+    return relayout_words(rows, cols, SEED_BASE + 2, kind)
+
+
+def config3(M: int = 8192, N: int = 8192, K: int = 8192) -> GemmInputs:
+    """bf16 GEMM 8192^3, entries N(0, sigma) with sigma = K^-1/2, bf16 output."""
+    s = float(K) ** -0.5
+    return gemm_bf16(M, N, K, SEED_BASE + 3, s, s)
+
+
+def config4(M: int = 4096, N: int = 3584, K: int = 8192) -> GemmInputs:
+    """One shard (of 8) of a tensor-parallel linear layer: activations N(0,1), weights N(0, 0.02)."""
+    return gemm_bf16(M, N, K, SEED_BASE + 4, 1.0, 0.02)
+
+
+def config5(M: int = 8192, N: int = 8192, K: int = 8192) -> GemmInputs:
+    """fp8 e4m3 GEMM with fp32 scales per 128x128 block, uniform[0.5, 2]."""
+    return gemm_fp8(M, N, K, SEED_BASE + 5)
+
+
+# Layout descriptions of the configurations (plain data; no layout arithmetic here) ------
+# A spec is {"D": [(extent, stride, axis), ...], "R": [...], "O": {axis: value},
+#            "swizzle": None | (axis, bits, base, shift)}.
+def spec(D, R=(), O=None, swizzle=None) -> dict:
+    return {"D": [tuple(i) for i in D], "R": [tuple(i) for i in R], "O": dict(O or {}), "swizzle": swizzle}
+
+
+def row_major_spec(rows: int, cols: int) -> dict:
+    return spec([(rows, cols, "m"), (cols, 1, "m")])
+
+
+def col_major_spec(rows: int, cols: int) -> dict:
+    """Logical (rows, cols) whose element (r, c) sits at c*rows + r."""
+    return spec([(rows, 1, "m"), (cols, rows, "m")])
+
+
+def blocked_swizzled_spec(rows: int, cols: int, tr: int = 128, tc: int = 64, swizzle: bool = True) -> dict:
+    """Logical (rows, cols) stored as a row-major grid of contiguous tr x tc row-major tiles,
+    the 16-byte chunk index inside each tile row XOR-ed with (row mod 8) -- 2-byte elements."""
+    if rows % tr or cols % tc:
+        raise ValueError("shape is not a multiple of the tile")
+    D = [(rows // tr, (cols // tc) * tr * tc, "m"), (tr, tc, "m"), (cols // tc, tr * tc, "m"), (tc, 1, "m")]
+    swz = None
+    if swizzle:
+        if tc != 64:
+            raise ValueError("the swizzle is stated for 64-element (128-byte) tile rows")
+        swz = ("m", 3, 3, 6)
+    return spec(D, swizzle=swz)
+
+
+def gemm_specs(g: "GemmInputs", device_axis: bool = False, shard: int = 0) -> Tuple[dict, dict, dict]:
+    """A (M,K) row-major, B (K,N) column-major, C (M,N) row-major.  With device_axis the weight
+    carries an extent-1 iter on a `gpuid` axis plus the shard number as its offset (one GPU's
+    shard of a column-parallel linear layer)."""
+    A = row_major_spec(g.M, g.K)
+    C = row_major_spec(g.M, g.N)
+    if device_axis:
+        B = spec([(g.K, 1, "m"), (1, 1, "gpuid"), (g.N, g.K, "m")], O={"gpuid": shard})
+    else:
+        B = col_major_spec(g.K, g.N)
+    return A, B, C
