@@ -1,0 +1,187 @@
+/* axe.h -- C ABI of the MI355X (gfx950) Axe-layout hot path.
+ *
+ * Three operations, each driven by Axe layouts (Sec. 2 of the paper: a layout is a shard list
+ * D of iters (extent, stride, named axis), a replica multiset R and a per-axis offset O; the
+ * induced map is f_L(x) = { f_D(x) + f_R(r) + O }):
+ *
+ *   axe_layout_eval   evaluate the induced map on the GPU                     (Sec. 2.3, Def. 2.3)
+ *   axe_relayout      copy one logical tensor from one layout to another      (Sec. 3.2, `copy` operator)
+ *   axe_gemm          layout-driven tiled dense GEMM, bf16 / block-scaled fp8 (Sec. 3.2 `gemm` operator,
+ *                                                                              Sec. 4.1 workloads)
+ *
+ * Conventions common to all entry points
+ *   - Pointers named d_* are DEVICE pointers (HIP global memory on the current device); every
+ *     other pointer is a HOST pointer.  The caller owns all of them; descriptors are read during
+ *     the call and never retained.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
+ *     asynchronously on it; the call returns without synchronising.
+ *   - Return value: AXE_OK (0) or a negative error code; nothing is launched when an error is
+ *     returned.  No call aborts or throws.  axe_strerror() names a code, axe_last_error() gives
+ *     the detailed message of the calling thread's last failure.
+ *   - The library keeps no global mutable state apart from that thread-local message, and
+ *     allocates no device memory.
+ *   - One GPU holds the whole tensor: an axis other than the memory axis may appear only with
+ *     total extent 1 (e.g. the extent-1 `gpuid` iter and `gpuid` offset of one shard of a
+ *     sharded tensor, Sec. 2.2); such iters are removed by canonicalisation rule D0 (App. A)
+ *     and offsets on such axes do not enter addresses.
+ */
+#ifndef AXE_H
+#define AXE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AXE_MAX_D     16   /* sharded iters per layout                 */
+#define AXE_MAX_R      8   /* replica iters per layout                 */
+#define AXE_MAX_AXES   8   /* named axes per layout                    */
+#define AXE_MAX_RANK   8   /* logical shape rank                       */
+
+enum {
+  AXE_OK           =  0,
+  AXE_EINVAL       = -1,  /* violates Def. 2.1 / 2.2: extent <= 0, stride == 0, n_d < 1, axis out of range,
+                             bad swizzle, NULL where a pointer is required, too many iters            */
+  AXE_ESHAPE       = -2,  /* shape not admitted (prod(shape) != E_D, Sec. 2.3) or shapes inconsistent  */
+  AXE_EALIAS       = -3,  /* a destination is not injective on the memory axis (two logical elements
+                             share an address), or a non-memory axis has extent > 1 on one GPU        */
+  AXE_ERANGE       = -4,  /* an address falls outside the declared buffer, or arithmetic overflows    */
+  AXE_EUNSUPPORTED = -5,  /* valid layouts outside the kernel families of this library               */
+  AXE_EHIP         = -6   /* HIP runtime failure (launch error)                                       */
+};
+
+/* Def. 2.1: f_I(x) = (x * stride) @ axis;  extent > 0, stride != 0, 0 <= axis < n_axes. */
+typedef struct {
+  int64_t extent;
+  int64_t stride;
+  int32_t axis;
+} axe_iter_t;
+
+/* Def. 2.2 plus the swizzle stage.
+ * D is ordered (first iter = slowest digit of the lexicographic unflattening); R is a multiset,
+ * evaluated in the order written (last iter fastest).  offset has n_axes entries or is NULL (all 0).
+ * Swizzle (Sec. 3.4 models the hardware swizzle as a separate innermost layout; here it is one
+ * stage applied to the coordinate on axis swz_axis after D + R + O):
+ *     y = x ^ (((x >> swz_shift) & (2^swz_bits - 1)) << swz_base),  swz_base + swz_bits <= swz_shift,
+ * swz_axis = -1 disables it.  The coordinate must be non-negative where a swizzle applies. */
+typedef struct {
+  int32_t           n_axes;      /* 1..AXE_MAX_AXES                                        */
+  const char* const* axis_names; /* n_axes labels for messages, or NULL                    */
+  int32_t           n_d;         /* 1..AXE_MAX_D                                           */
+  const axe_iter_t* d;
+  int32_t           n_r;         /* 0..AXE_MAX_R                                           */
+  const axe_iter_t* r;           /* may be NULL when n_r == 0                              */
+  const int64_t*    offset;
+  int32_t           swz_axis, swz_bits, swz_base, swz_shift;
+} axe_layout_t;
+
+/* ---------------------------------------------------------------------------------------------
+ * axe_layout_eval -- the induced map f_{L<S>} of Def. 2.3 / "Shape admission" (Sec. 2.3).
+ *
+ *   L, rank, shape : layout and a shape it admits (prod(shape) == E_D), rank 1..AXE_MAX_RANK.
+ *   n              : number of logical indices to evaluate.
+ *   d_flat_idx     : DEVICE, n row-major flattened logical indices in [0, E_D); NULL = 0..n-1
+ *                    (then n <= E_D is required).  Indices outside the range produce
+ *                    INT64_MIN in every output slot of that index (no out-of-bounds access).
+ *   d_out          : DEVICE, n * E_R * n_axes int64, laid out [index][replica][axis]; replica t
+ *                    enumerates R lexicographically in the order written (last iter fastest).
+ * Bit-exact integer arithmetic (int64, two's complement). */
+int axe_layout_eval(const axe_layout_t* L, int32_t rank, const int64_t* shape,
+                    int64_t n, const int64_t* d_flat_idx, int64_t* d_out, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * axe_relayout -- dst[f_dst(x)] = src[f_src(x)] for every logical index x of `shape`
+ * (the `copy` operator between two layouts of the same logical tensor, Sec. 3.2; blocked
+ * destinations are tile products, Sec. 3.3; swizzled ones use the stage above).
+ *
+ *   src, dst     : layouts admitting `shape`.  Addresses are the coordinates on axis `mem_axis`
+ *                  (same index in both layouts), in units of elements.
+ *   elem_bytes   : 1, 2, 4, 8 or 16.
+ *   d_src, d_dst : DEVICE buffers of src_elems / dst_elems elements, aligned to elem_bytes;
+ *                  they must not overlap.
+ * Semantics of replication: every replica address of dst is written; src is read at its first
+ * replica (all replica digits 0).  Words of dst no logical index maps to are left untouched.
+ * Data are moved as raw bits (no float interpretation).
+ * Errors: AXE_ESHAPE, AXE_EALIAS (dst's D part not provably injective -- the test is the
+ * sufficient one: iters on the memory axis sorted by |stride| must each step over the span of
+ * all smaller ones), AXE_ERANGE (some address outside [0, *_elems)), AXE_EINVAL. */
+int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank, const int64_t* shape,
+                 int32_t elem_bytes, int32_t mem_axis,
+                 const void* d_src, int64_t src_elems, void* d_dst, int64_t dst_elems, void* stream);
+
+/* ---------------------------------------------------------------------------------------------
+ * axe_gemm -- C[i][j] = sum_k A[i][k] * B[k][j], fp32 accumulation on the MFMA units
+ * (dense GEMM, Sec. 4.1; tiles are moved HBM -> LDS -> registers -> MFMA -> HBM following the
+ * layouts reported by axe_gemm_describe).
+ *
+ *   A : logical shape (M, K);  B : logical shape (K, N);  C : logical shape (M, N); each with its
+ *       layout on the memory axis `mem_axis`, addresses in elements of the tensor's dtype.
+ *   in_dtype  : AXE_BF16 (2 bytes) or AXE_FP8_E4M3 (1 byte, OCP e4m3: max 448, no inf).
+ *   out_dtype : AXE_F32 or AXE_BF16 (round to nearest even from the fp32 accumulator).
+ *   d_scale_a, d_scale_b : both NULL, or DEVICE fp32 arrays, row-major (ceil(M/sb), ceil(K/sb))
+ *       and (ceil(N/sb), ceil(K/sb)) with sb = scale_block (must be 128):
+ *       C[i][j] = sum_kb sA[i/sb][kb] * sB[j/sb][kb] * sum_{k in block kb} A[i][k] B[k][j]
+ *       (block-wise scaled GEMM, Sec. 4.1).  Only with AXE_FP8_E4M3.
+ *   a_elems, b_elems, c_elems : sizes of the device buffers in elements (range check).
+ * Supported family (else AXE_EUNSUPPORTED): after canonicalisation A and B have unit stride
+ * along k and C has unit stride along j (A row-major, B column-major, C row-major, any leading
+ * dimensions that are multiples of 16 bytes, any offsets that keep 16-byte alignment); K a
+ * multiple of 16 bytes' worth of elements.  d_C must not overlap d_A or d_B. */
+enum { AXE_BF16 = 1, AXE_FP8_E4M3 = 2, AXE_F32 = 3 };
+
+typedef struct {
+  int64_t      M, N, K;
+  int32_t      in_dtype, out_dtype;
+  axe_layout_t A, B, C;
+  int32_t      mem_axis;
+  int64_t      a_elems, b_elems, c_elems;
+  const float* d_scale_a;
+  const float* d_scale_b;
+  int32_t      scale_block;
+  int32_t      tile_hint;   /* 0 = library default; AXE_TILE_* forces a kernel (AXE_EUNSUPPORTED if
+                               the shape does not fit it)                                         */
+} axe_gemm_desc_t;
+
+enum { AXE_TILE_AUTO = 0, AXE_TILE_64x64x32 = 1, AXE_TILE_256x256x64 = 2 };
+
+int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d_C, void* stream);
+
+/* The kernel axe_gemm would launch for `g` (host only, device pointers not needed):
+ * returns AXE_TILE_64x64x32 or AXE_TILE_256x256x64, or the error axe_gemm would return. */
+int axe_gemm_tile(const axe_gemm_desc_t* g);
+
+/* ---------------------------------------------------------------------------------------------
+ * axe_gemm_describe -- the Axe layouts of every tile movement of the kernel axe_gemm would
+ * launch for `g` (Sec. 3.1 / Fig. 3: tensors in shared memory and registers carry layouts; tile
+ * composes register tile (x) lane (x) wave (x) workgroup, Sec. 3.3).  Host only, no device work.
+ *
+ *   which : AXE_DESC_*.
+ *   out   : receives the layout; its d / r / offset / axis_names pointers point into `arena`.
+ *   shape, rank : receive the logical shape the layout admits (up to AXE_MAX_RANK entries).
+ *   arena, arena_bytes : caller-provided HOST scratch (2 KiB is enough).
+ * Axis names used: "m" (HBM element address), "lds" (LDS element address), "wg", "wave", "lane",
+ * "reg" (index of the element inside the lane's fragment / accumulator / per-thread loop). */
+enum {
+  AXE_DESC_A_G2L_THREADS = 0, /* (BM, BK) tile of A  -> wave, lane, reg : who fetches which element  */
+  AXE_DESC_B_G2L_THREADS = 1,
+  AXE_DESC_A_LDS         = 2, /* (BM, BK) tile of A  -> lds (with swizzle) for one stage             */
+  AXE_DESC_B_LDS         = 3,
+  AXE_DESC_A_OPERAND     = 4, /* (BM, BK) tile of A  -> wave(s, replicated), lane, reg (MFMA operand)*/
+  AXE_DESC_B_OPERAND     = 5,
+  AXE_DESC_ACC           = 6, /* (M, N) of the whole problem -> wg, wave, lane, reg (accumulators)   */
+  AXE_DESC_C_STORE       = 7  /* (BM, BN) tile of C  -> wave, lane, reg : who stores which element   */
+};
+int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_layout_t* out,
+                      int64_t* shape, int32_t* rank, void* arena, size_t arena_bytes);
+
+const char* axe_strerror(int code);
+const char* axe_last_error(void);
+/* Library version: major * 10000 + minor * 100 + patch. */
+int32_t axe_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AXE_H */

@@ -1,0 +1,213 @@
+"""ctypes binding of libaxe_hip.so -- argument marshalling only.
+
+Every operation runs in the HIP kernels behind the C ABI declared in include/axe.h; nothing is
+computed here and there is no CPU fallback: if the shared library has not been built, loading
+fails with an error.  PyTorch tensors are used only as owners of device memory (data_ptr) and
+for the current HIP stream.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libaxe_hip.so")
+
+AXE_OK, AXE_EINVAL, AXE_ESHAPE, AXE_EALIAS, AXE_ERANGE, AXE_EUNSUPPORTED, AXE_EHIP = 0, -1, -2, -3, -4, -5, -6
+AXE_BF16, AXE_FP8_E4M3, AXE_F32 = 1, 2, 3
+AXE_TILE_AUTO, AXE_TILE_64x64x32, AXE_TILE_256x256x64 = 0, 1, 2
+(AXE_DESC_A_G2L_THREADS, AXE_DESC_B_G2L_THREADS, AXE_DESC_A_LDS, AXE_DESC_B_LDS, AXE_DESC_A_OPERAND,
+ AXE_DESC_B_OPERAND, AXE_DESC_ACC, AXE_DESC_C_STORE) = range(8)
+AXE_MAX_RANK = 8
+
+EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
+           "axe_last_error", "axe_version"]
+
+
+class axe_iter_t(C.Structure):
+    _fields_ = [("extent", C.c_int64), ("stride", C.c_int64), ("axis", C.c_int32)]
+
+
+class axe_layout_t(C.Structure):
+    _fields_ = [("n_axes", C.c_int32), ("axis_names", C.POINTER(C.c_char_p)),
+                ("n_d", C.c_int32), ("d", C.POINTER(axe_iter_t)),
+                ("n_r", C.c_int32), ("r", C.POINTER(axe_iter_t)),
+                ("offset", C.POINTER(C.c_int64)),
+                ("swz_axis", C.c_int32), ("swz_bits", C.c_int32), ("swz_base", C.c_int32), ("swz_shift", C.c_int32)]
+
+
+class axe_gemm_desc_t(C.Structure):
+    _fields_ = [("M", C.c_int64), ("N", C.c_int64), ("K", C.c_int64),
+                ("in_dtype", C.c_int32), ("out_dtype", C.c_int32),
+                ("A", axe_layout_t), ("B", axe_layout_t), ("C", axe_layout_t),
+                ("mem_axis", C.c_int32),
+                ("a_elems", C.c_int64), ("b_elems", C.c_int64), ("c_elems", C.c_int64),
+                ("d_scale_a", C.c_void_p), ("d_scale_b", C.c_void_p),
+                ("scale_block", C.c_int32), ("tile_hint", C.c_int32)]
+
+
+class AxeError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"axe error {code}: {message}")
+        self.code = code
+        self.message = message
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """Loads the HIP library (raises if it has not been built: there is no fallback)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_19092_amd.build` "
+                               "(or __graft_entry__.build()); this package has no CPU fallback")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+        LP = C.POINTER(axe_layout_t)
+        L.axe_layout_eval.restype = C.c_int
+        L.axe_layout_eval.argtypes = [LP, i32, C.POINTER(i64), i64, vp, vp, vp]
+        L.axe_relayout.restype = C.c_int
+        L.axe_relayout.argtypes = [LP, LP, i32, C.POINTER(i64), i32, i32, vp, i64, vp, i64, vp]
+        L.axe_gemm.restype = C.c_int
+        L.axe_gemm.argtypes = [C.POINTER(axe_gemm_desc_t), vp, vp, vp, vp]
+        L.axe_gemm_tile.restype = C.c_int
+        L.axe_gemm_tile.argtypes = [C.POINTER(axe_gemm_desc_t)]
+        L.axe_gemm_describe.restype = C.c_int
+        L.axe_gemm_describe.argtypes = [C.POINTER(axe_gemm_desc_t), i32, LP, C.POINTER(i64), C.POINTER(i32), vp,
+                                        C.c_size_t]
+        L.axe_strerror.restype = C.c_char_p
+        L.axe_strerror.argtypes = [C.c_int]
+        L.axe_last_error.restype = C.c_char_p
+        L.axe_version.restype = i32
+        _lib = L
+    return _lib
+
+
+def _check(rc: int) -> None:
+    if rc != 0:
+        L = lib()
+        msg = L.axe_last_error().decode() or L.axe_strerror(rc).decode()
+        raise AxeError(rc, msg)
+
+
+class Layout:
+    """Host-side holder of an axe_layout_t and of the ctypes arrays it points to.
+
+    spec = {"D": [(extent, stride, axis_name), ...], "R": [...], "O": {axis_name: value},
+            "swizzle": None | (axis_name, bits, base, shift)}; `axes` fixes the axis order
+    (default: order of first appearance in D, R, O, swizzle)."""
+
+    def __init__(self, spec: dict, axes: Optional[Sequence[str]] = None):
+        names: List[str] = list(axes) if axes is not None else []
+        def idx(a: str) -> int:
+            if a not in names:
+                if axes is not None:
+                    raise ValueError(f"axis {a!r} not in {axes}")
+                names.append(a)
+            return names.index(a)
+        D = [(int(e), int(s), idx(a)) for e, s, a in spec["D"]]
+        R = [(int(e), int(s), idx(a)) for e, s, a in spec.get("R", ())]
+        O = {idx(a): int(v) for a, v in (spec.get("O") or {}).items()}
+        z = spec.get("swizzle")
+        zi = (idx(z[0]), int(z[1]), int(z[2]), int(z[3])) if z else (-1, 0, 0, 0)
+        self.axes = names
+        self._d = (axe_iter_t * max(1, len(D)))(*[axe_iter_t(*t) for t in D])
+        self._r = (axe_iter_t * max(1, len(R)))(*[axe_iter_t(*t) for t in R])
+        self._o = (C.c_int64 * max(1, len(names)))(*[O.get(i, 0) for i in range(len(names))])
+        self._names = (C.c_char_p * max(1, len(names)))(*[n.encode() for n in names])
+        self.c = axe_layout_t(len(names), self._names, len(D), self._d, len(R), self._r, self._o, *zi)
+        self.E_R = 1
+        for e, _, _ in R:
+            self.E_R *= e
+
+    def axis(self, name: str) -> int:
+        return self.axes.index(name)
+
+
+def _stream_ptr(stream=None) -> int:
+    import torch
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def _shape_arr(shape: Sequence[int]):
+    return (C.c_int64 * len(shape))(*[int(s) for s in shape])
+
+
+def axe_layout_eval(layout: Layout, shape: Sequence[int], n: int, flat_idx=None, out=None, stream=None):
+    """Device evaluation of the induced map; returns an int64 CUDA tensor [n, E_R, n_axes]."""
+    import torch
+    if out is None:
+        out = torch.empty((n, layout.E_R, len(layout.axes)), dtype=torch.int64, device="cuda")
+    idx_ptr = None
+    if flat_idx is not None:
+        assert flat_idx.dtype == torch.int64 and flat_idx.is_cuda and flat_idx.is_contiguous() and flat_idx.numel() == n
+        idx_ptr = flat_idx.data_ptr()
+    assert out.dtype == torch.int64 and out.is_cuda and out.is_contiguous()
+    assert out.numel() == n * layout.E_R * len(layout.axes)
+    _check(lib().axe_layout_eval(C.byref(layout.c), len(shape), _shape_arr(shape), n, idx_ptr, out.data_ptr(),
+                                 _stream_ptr(stream)))
+    return out
+
+
+def axe_relayout(src: Layout, dst: Layout, shape: Sequence[int], src_buf, dst_buf, mem_axis: str = "m",
+                 elem_bytes: Optional[int] = None, stream=None):
+    """dst_buf[f_dst(x)] = src_buf[f_src(x)]; buffers are 1-D CUDA tensors of one element size."""
+    eb = elem_bytes if elem_bytes is not None else src_buf.element_size()
+    assert src_buf.is_cuda and dst_buf.is_cuda and src_buf.is_contiguous() and dst_buf.is_contiguous()
+    assert src.axes.index(mem_axis) == dst.axes.index(mem_axis), "memory axis must have the same index in both layouts"
+    s_elems = src_buf.numel() * src_buf.element_size() // eb
+    d_elems = dst_buf.numel() * dst_buf.element_size() // eb
+    _check(lib().axe_relayout(C.byref(src.c), C.byref(dst.c), len(shape), _shape_arr(shape), eb, src.axis(mem_axis),
+                              src_buf.data_ptr(), s_elems, dst_buf.data_ptr(), d_elems, _stream_ptr(stream)))
+    return dst_buf
+
+
+class GemmDesc:
+    """Holder of an axe_gemm_desc_t (keeps the three layouts alive)."""
+
+    def __init__(self, M: int, N: int, K: int, in_dtype: int, out_dtype: int, A: Layout, B: Layout, Cl: Layout,
+                 a_elems: int, b_elems: int, c_elems: int, scale_a=None, scale_b=None, scale_block: int = 128,
+                 tile_hint: int = AXE_TILE_AUTO, mem_axis: str = "m"):
+        ma = A.axis(mem_axis)
+        assert B.axis(mem_axis) == ma and Cl.axis(mem_axis) == ma, "memory axis must have the same index in A, B, C"
+        self.layouts = (A, B, Cl)
+        self.scales = (scale_a, scale_b)
+        self.c = axe_gemm_desc_t(M, N, K, in_dtype, out_dtype, A.c, B.c, Cl.c, ma, a_elems, b_elems, c_elems,
+                                 scale_a.data_ptr() if scale_a is not None else None,
+                                 scale_b.data_ptr() if scale_b is not None else None, scale_block, tile_hint)
+
+
+def axe_gemm(desc: GemmDesc, A_buf, B_buf, C_buf, stream=None):
+    assert A_buf.is_cuda and B_buf.is_cuda and C_buf.is_cuda
+    _check(lib().axe_gemm(C.byref(desc.c), A_buf.data_ptr(), B_buf.data_ptr(), C_buf.data_ptr(), _stream_ptr(stream)))
+    return C_buf
+
+
+def axe_gemm_tile(desc: GemmDesc) -> int:
+    rc = lib().axe_gemm_tile(C.byref(desc.c))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def axe_gemm_describe(desc: GemmDesc, which: int) -> Tuple[dict, Tuple[int, ...]]:
+    """Returns (spec, shape): the layout of one tile movement as plain data."""
+    out = axe_layout_t()
+    shape = (C.c_int64 * AXE_MAX_RANK)()
+    rank = C.c_int32(0)
+    arena = C.create_string_buffer(4096)
+    _check(lib().axe_gemm_describe(C.byref(desc.c), which, C.byref(out), shape, C.byref(rank), arena, len(arena)))
+    names = [out.axis_names[i].decode() for i in range(out.n_axes)]
+    spec = {"D": [(out.d[i].extent, out.d[i].stride, names[out.d[i].axis]) for i in range(out.n_d)],
+            "R": [(out.r[i].extent, out.r[i].stride, names[out.r[i].axis]) for i in range(out.n_r)],
+            "O": {names[a]: out.offset[a] for a in range(out.n_axes) if out.offset and out.offset[a] != 0},
+            "swizzle": (names[out.swz_axis], out.swz_bits, out.swz_base, out.swz_shift) if out.swz_axis >= 0 else None}
+    return spec, tuple(shape[i] for i in range(rank.value))
+
+
+def version() -> int:
+    return int(lib().axe_version())

@@ -1,0 +1,62 @@
+"""Builds the HIP library in-tree:  python -m paper_2601_19092_amd.build
+
+One shared object, gfx950 only.  The flag pair after -Xclang switches off packed-fp32 code
+generation (hipcc's host pass warns that it does not know the feature; that is harmless)."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libaxe_hip.so")
+SOURCES = ["api.cpp", "host_layout.cpp", "describe.cpp", "kernels_layout.hip", "kernels_gemm_small.hip",
+           "kernels_gemm_big.hip"]
+FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
+         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
+
+
+def build_library(verbose: bool = False, extra_flags=()) -> str:
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    objs = []
+    procs = []
+    os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
+    for src in SOURCES:
+        obj = os.path.join(HERE, "_build", src + ".o")
+        cmd = [hipcc, *FLAGS, *extra_flags, "-c", os.path.join(CSRC, src), "-o", obj]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
+        objs.append(obj)
+    failed = False
+    for src, p in procs:
+        out, _ = p.communicate()
+        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and "is not a recognized feature" not in l)
+        if p.returncode != 0:
+            failed = True
+            print(f"--- {src} failed:\n{out}", file=sys.stderr)
+        elif verbose and out.strip():
+            print(f"--- {src}:\n{out}")
+    if failed:
+        raise RuntimeError("hipcc failed")
+    cmd = [hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
+    subprocess.check_call(cmd)
+    return LIB
+
+
+def build_hostcheck() -> str:
+    """Test-only library: the host layer linked against host-memory stand-ins of the integer
+    kernels (csrc/cpu_emulation.cpp) so that planning can be checked without a GPU."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(HERE, "libaxe_hostcheck.so")
+    srcs = [os.path.join(CSRC, f) for f in ("api.cpp", "host_layout.cpp", "describe.cpp", "cpu_emulation.cpp")]
+    cmd = [hipcc, "-O1", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-x", "hip",
+           "-Wno-unused-command-line-argument", *srcs, "-o", out]
+    subprocess.check_call(cmd)
+    return out
+
+
+if __name__ == "__main__":
+    print(build_library(verbose="-v" in sys.argv))
+    print(build_hostcheck())

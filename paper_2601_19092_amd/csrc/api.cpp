@@ -1,0 +1,463 @@
+// C ABI of the library: argument validation, layout analysis, kernel choice, launch.
+#include <hip/hip_runtime.h>
+#include <stdlib.h>
+#include <string.h>
+
+#include <algorithm>
+
+#include "../../include/axe.h"
+#include "host_layout.h"
+#include "kernels.h"
+
+using namespace axe;
+
+namespace {
+
+int hip_fail(hipError_t e, const char* what) {
+  set_error("%s: HIP error %d (%s)", what, (int)e, hipGetErrorString(e));
+  return AXE_EHIP;
+}
+
+int ilog2(int64_t v) {
+  int l = 0;
+  while ((int64_t(1) << l) < v) ++l;
+  return l;
+}
+bool is_pow2(int64_t v) { return v > 0 && (v & (v - 1)) == 0; }
+
+int env_int(const char* name, int dflt) {
+  const char* s = getenv(name);
+  return s && *s ? atoi(s) : dflt;
+}
+
+}  // namespace
+
+extern "C" {
+
+int32_t axe_version(void) { return 100; }
+
+const char* axe_strerror(int code) {
+  switch (code) {
+    case AXE_OK: return "ok";
+    case AXE_EINVAL: return "invalid argument (violates the definition of an iter / layout)";
+    case AXE_ESHAPE: return "shape not admitted by the layout, or inconsistent shapes";
+    case AXE_EALIAS: return "destination not injective on the memory axis, or non-memory axis of extent > 1";
+    case AXE_ERANGE: return "address outside the declared buffer, or integer overflow";
+    case AXE_EUNSUPPORTED: return "layouts outside the supported kernel families";
+    case AXE_EHIP: return "HIP runtime failure";
+    default: return "unknown error code";
+  }
+}
+
+const char* axe_last_error(void) { return last_error(); }
+
+// ---------------------------------------------------------------------------------------------
+int axe_layout_eval(const axe_layout_t* L, int32_t rank, const int64_t* shape, int64_t n, const int64_t* d_flat_idx,
+                    int64_t* d_out, void* stream) {
+  HLayout h;
+  if (int rc = load_layout(L, h, "axe_layout_eval")) return rc;
+  if (int rc = check_shape(h, rank, shape, "axe_layout_eval")) return rc;
+  if (n < 0) {
+    set_error("axe_layout_eval: n = %lld is negative", (long long)n);
+    return AXE_EINVAL;
+  }
+  if (!d_flat_idx && n > h.E_D) {
+    set_error("axe_layout_eval: n = %lld exceeds E_D = %lld with implicit indices", (long long)n, (long long)h.E_D);
+    return AXE_ERANGE;
+  }
+  if (n > 0 && !d_out) {
+    set_error("axe_layout_eval: d_out is NULL");
+    return AXE_EINVAL;
+  }
+  int64_t per, total;
+  if (__builtin_mul_overflow(h.E_R, (int64_t)h.n_axes, &per) || __builtin_mul_overflow(per, n, &total) ||
+      total > (INT64_MAX >> 4)) {
+    set_error("axe_layout_eval: output size overflows");
+    return AXE_ERANGE;
+  }
+  if (n == 0) return AXE_OK;
+  EvalDesc d;
+  memset(&d, 0, sizeof d);
+  d.n_d = (int)h.D.size();
+  d.n_r = (int)h.R.size();
+  d.n_axes = h.n_axes;
+  d.use32 = h.E_D < (int64_t(1) << 31);
+  for (int k = 0; k < d.n_d; ++k) {
+    d.ext[k] = h.D[k].e;
+    d.str[k] = h.D[k].s;
+    d.axis[k] = h.D[k].axis;
+  }
+  for (int k = 0; k < d.n_r; ++k) {
+    d.rext[k] = h.R[k].e;
+    d.rstr[k] = h.R[k].s;
+    d.raxis[k] = h.R[k].axis;
+  }
+  for (int a = 0; a < h.n_axes; ++a) d.off[a] = h.off[a];
+  d.swz_axis = h.swz_axis;
+  d.swz = Swz{h.swz_axis >= 0 ? (1 << h.swz_bits) - 1 : 0, h.swz_base, h.swz_shift};
+  d.E_D = h.E_D;
+  d.E_R = h.E_R;
+  hipError_t e = launch_layout_eval(d, n, d_flat_idx, d_out, (hipStream_t)stream);
+  return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_layout_eval");
+}
+
+// ---------------------------------------------------------------------------------------------
+// Relayout planning.  The two shard lists are refined to one loop nest (a joint digit system);
+// the innermost unit-stride run common to both sides becomes the access width (up to 16 bytes);
+// the remaining digits are ordered so that neighbouring threads touch neighbouring memory on at
+// least one side, and a per-thread unroll digit is taken along the other side's fastest digit.
+int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank, const int64_t* shape,
+                 int32_t elem_bytes, int32_t mem_axis, const void* d_src, int64_t src_elems, void* d_dst,
+                 int64_t dst_elems, void* stream) {
+  HLayout hs, hd;
+  if (int rc = load_layout(src, hs, "axe_relayout(src)")) return rc;
+  if (int rc = load_layout(dst, hd, "axe_relayout(dst)")) return rc;
+  if (int rc = check_shape(hs, rank, shape, "axe_relayout(src)")) return rc;
+  if (int rc = check_shape(hd, rank, shape, "axe_relayout(dst)")) return rc;
+  if (!(elem_bytes == 1 || elem_bytes == 2 || elem_bytes == 4 || elem_bytes == 8 || elem_bytes == 16)) {
+    set_error("axe_relayout: elem_bytes = %d, must be 1, 2, 4, 8 or 16", elem_bytes);
+    return AXE_EINVAL;
+  }
+  MemLayout ms, md;
+  if (int rc = reduce_to_memory(hs, mem_axis, ms, "axe_relayout(src)")) return rc;
+  if (int rc = reduce_to_memory(hd, mem_axis, md, "axe_relayout(dst)")) return rc;
+  if (int rc = check_range(ms, src_elems, "axe_relayout(src)")) return rc;
+  if (int rc = check_range(md, dst_elems, "axe_relayout(dst)")) return rc;
+  if (!provably_injective(md)) {
+    set_error("axe_relayout(dst): two logical elements may share an address (strides do not nest)");
+    return AXE_EALIAS;
+  }
+  if (!d_src || !d_dst) {
+    set_error("axe_relayout: NULL device pointer");
+    return AXE_EINVAL;
+  }
+  if (((uintptr_t)d_src | (uintptr_t)d_dst) % (uintptr_t)elem_bytes) {
+    set_error("axe_relayout: buffers are not aligned to the element size");
+    return AXE_EINVAL;
+  }
+  {
+    const char* s0 = (const char*)d_src;
+    const char* d0 = (const char*)d_dst;
+    if (s0 < d0 + dst_elems * elem_bytes && d0 < s0 + src_elems * elem_bytes) {
+      set_error("axe_relayout: source and destination buffers overlap");
+      return AXE_EINVAL;
+    }
+  }
+  if (md.E_R > (int64_t(1) << 20)) {
+    set_error("axe_relayout(dst): %lld replicas", (long long)md.E_R);
+    return AXE_EUNSUPPORTED;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  const int64_t E = hs.E_D;
+
+  std::vector<JointIter> J;
+  bool joint = joint_refine(ms.D, md.D, J);
+  if (!joint) {
+    GenericRelayoutPlan p;
+    memset(&p, 0, sizeof p);
+    p.ns = (int)ms.D.size();
+    p.nd = (int)md.D.size();
+    for (int k = 0; k < p.ns; ++k) p.sext[k] = ms.D[k].e, p.sstr[k] = ms.D[k].s;
+    for (int k = 0; k < p.nd; ++k) p.dext[k] = md.D[k].e, p.dstr[k] = md.D[k].s;
+    p.s_off = ms.off;
+    p.d_off = md.off;
+    p.s_swz = ms.swz;
+    p.d_swz = md.swz;
+    p.n_r = (int)md.R.size();
+    for (int k = 0; k < p.n_r; ++k) p.rext[k] = (int32_t)md.R[k].e, p.rstr[k] = md.R[k].s;
+    p.E_R = md.E_R;
+    p.total = E;
+    hipError_t e = launch_relayout_generic(p, elem_bytes, d_src, d_dst, st);
+    return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_relayout");
+  }
+
+  // --- vector width: a joint digit with unit stride on both sides
+  int unit = elem_bytes;
+  int64_t v = 1;
+  int vec_k = -1;
+  for (size_t k = 0; k < J.size(); ++k)
+    if (J[k].ss == 1 && J[k].ds == 1) vec_k = (int)k;
+  if (vec_k >= 0) {
+    v = 16 / elem_bytes;
+    while (v > 1 && (J[vec_k].e % v)) v >>= 1;
+    auto fits = [&](int64_t w) {
+      for (size_t k = 0; k < J.size(); ++k)
+        if ((int)k != vec_k && ((J[k].ss % w) || (J[k].ds % w))) return false;
+      for (const HIter& it : md.R)
+        if (it.s % w) return false;
+      if ((ms.off % w) || (md.off % w)) return false;
+      if (ms.swz.mask && (int64_t(1) << ms.swz.base) % w) return false;
+      if (md.swz.mask && (int64_t(1) << md.swz.base) % w) return false;
+      if (((uintptr_t)d_src | (uintptr_t)d_dst) % (uintptr_t)(w * elem_bytes)) return false;
+      return true;
+    };
+    while (v > 1 && !fits(v)) v >>= 1;
+  }
+  if (v > 1) {
+    int lv = ilog2(v);
+    unit = elem_bytes * (int)v;
+    for (size_t k = 0; k < J.size(); ++k) {
+      if ((int)k == vec_k) {
+        J[k].e /= v;
+      } else {
+        J[k].ss /= v;
+        J[k].ds /= v;
+      }
+    }
+    for (HIter& it : md.R) it.s /= v;
+    ms.off /= v;
+    md.off /= v;
+    if (ms.swz.mask) ms.swz.base -= lv, ms.swz.shift -= lv;
+    if (md.swz.mask) md.swz.base -= lv, md.swz.shift -= lv;
+  }
+  J.erase(std::remove_if(J.begin(), J.end(), [](const JointIter& j) { return j.e == 1; }), J.end());
+
+  // --- loop order: fastest digit first, by the smaller of the two |strides|
+  auto mag = [](int64_t x) { return x < 0 ? -x : x; };
+  std::stable_sort(J.begin(), J.end(), [&](const JointIter& a, const JointIter& b) {
+    int64_t ka = std::min(mag(a.ss), mag(a.ds)), kb = std::min(mag(b.ss), mag(b.ds));
+    if (ka != kb) return ka < kb;
+    return std::max(mag(a.ss), mag(a.ds)) < std::max(mag(b.ss), mag(b.ds));
+  });
+  // --- unroll digit: the side the thread-fastest non-unit digit does not favour gets its own
+  //     fastest digit unrolled inside each thread (so both sides see long contiguous runs)
+  int U = 1;
+  int64_t us = 0, ud = 0;
+  int want_u = env_int("AXE_RELAYOUT_UNROLL", 4);
+  if (J.size() >= 2 && want_u > 1) {
+    size_t first = (mag(J[0].ss) == 1 && mag(J[0].ds) == 1) ? 1 : 0;   // first digit that favours one side
+    if (first < J.size()) {
+      bool favours_src = mag(J[first].ss) < mag(J[first].ds);
+      int best = -1;
+      for (size_t k = first + 1; k < J.size(); ++k) {
+        int64_t key = favours_src ? mag(J[k].ds) : mag(J[k].ss);
+        int64_t bk = best < 0 ? 0 : (favours_src ? mag(J[best].ds) : mag(J[best].ss));
+        if (best < 0 || key < bk) best = (int)k;
+      }
+      if (best < 0) best = (int)first;
+      int u = 1;
+      while (u * 2 <= want_u && u * 2 <= 8 && J[best].e % (u * 2) == 0) u *= 2;
+      if (u > 1) {
+        U = u;
+        us = J[best].ss;
+        ud = J[best].ds;
+        J[best].e /= u;
+        J[best].ss *= u;
+        J[best].ds *= u;
+      }
+    }
+  }
+  J.erase(std::remove_if(J.begin(), J.end(), [](const JointIter& j) { return j.e == 1; }), J.end());
+
+  RelayoutPlan p;
+  memset(&p, 0, sizeof p);
+  p.n = (int)J.size();
+  uint64_t threads = 1;
+  for (int k = 0; k < p.n; ++k) {
+    if (J[k].e >= (int64_t(1) << 31)) {
+      set_error("axe_relayout: digit extent %lld too large", (long long)J[k].e);
+      return AXE_EUNSUPPORTED;
+    }
+    p.ext[k] = (uint32_t)J[k].e;
+    p.shift[k] = is_pow2(J[k].e) ? ilog2(J[k].e) : -1;
+    p.ss[k] = J[k].ss;
+    p.ds[k] = J[k].ds;
+    threads *= (uint64_t)J[k].e;
+  }
+  if (threads >= (uint64_t(1) << 32) || (threads + 255) / 256 >= (uint64_t(1) << 31)) {
+    set_error("axe_relayout: %llu work items exceed one launch", (unsigned long long)threads);
+    return AXE_EUNSUPPORTED;
+  }
+  p.U = U;
+  p.us = us;
+  p.ud = ud;
+  p.s_off = ms.off;
+  p.d_off = md.off;
+  p.s_swz = ms.swz;
+  p.d_swz = md.swz;
+  p.n_r = (int)md.R.size();
+  for (int k = 0; k < p.n_r; ++k) p.rext[k] = (int32_t)md.R[k].e, p.rstr[k] = md.R[k].s;
+  p.E_R = md.E_R;
+  p.threads = threads;
+  hipError_t e = launch_relayout_joint(p, unit, d_src, d_dst, st);
+  return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_relayout");
+}
+
+// ---------------------------------------------------------------------------------------------
+// GEMM: recognise the supported family, pick the tile, launch.
+namespace {
+
+struct GemmPlan {
+  GemmArgs args;
+  bool fp8;
+  int tile;           // AXE_TILE_*
+};
+
+// A 2-D operand whose canonical memory layout is "unit stride along `inner`, pitch along
+// `outer`": returns pitch and offset.  `outer_first` tells which logical dim comes first.
+int strided_2d(const axe_layout_t* L, int mem_axis, int64_t d0, int64_t d1, bool inner_is_dim1, int64_t elems,
+               const char* what, int64_t* pitch, int64_t* offset) {
+  HLayout h;
+  if (int rc = load_layout(L, h, what)) return rc;
+  int64_t shape[2] = {d0, d1};
+  if (int rc = check_shape(h, 2, shape, what)) return rc;
+  MemLayout m;
+  if (int rc = reduce_to_memory(h, mem_axis, m, what)) return rc;
+  if (!m.R.empty()) {
+    set_error("%s: replicated GEMM operands are not supported", what);
+    return AXE_EUNSUPPORTED;
+  }
+  if (m.swz.mask) {
+    set_error("%s: swizzled HBM operands are not supported by axe_gemm", what);
+    return AXE_EUNSUPPORTED;
+  }
+  if (int rc = check_range(m, elems, what)) return rc;
+  const int64_t inner = inner_is_dim1 ? d1 : d0, outer = inner_is_dim1 ? d0 : d1;
+  // canonical forms accepted: [(outer, pitch), (inner, 1)] in logical order (or swapped when the
+  // inner dim is logical dim 0), or a single merged iter (outer*inner, 1) when pitch == inner
+  std::vector<HIter>& D = m.D;
+  int64_t p = 0;
+  bool ok = false;
+  if (D.empty()) {
+    ok = (d0 == 1 && d1 == 1);
+    p = inner;
+  } else if (D.size() == 1) {
+    if (D[0].s == 1 && D[0].e == d0 * d1 && (outer == 1 || inner_is_dim1)) ok = true, p = inner;      // contiguous
+    else if (inner == 1 && D[0].e == outer) ok = true, p = D[0].s;
+    else if (outer == 1 && D[0].e == inner && D[0].s == 1) ok = true, p = inner;
+  } else if (D.size() == 2) {
+    const HIter& a = D[0];
+    const HIter& b = D[1];
+    if (inner_is_dim1 && a.e == d0 && b.e == d1 && b.s == 1) ok = true, p = a.s;
+    if (!inner_is_dim1 && a.e == d0 && b.e == d1 && a.s == 1) ok = true, p = b.s;
+  }
+  if (!ok || p < inner) {
+    set_error("%s: layout is not a pitched matrix with unit stride along the %s dimension", what,
+              inner_is_dim1 ? "second" : "first");
+    return AXE_EUNSUPPORTED;
+  }
+  *pitch = p;
+  *offset = m.off;
+  return AXE_OK;
+}
+
+int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC, GemmPlan& P, bool need_ptrs) {
+  if (!g) {
+    set_error("axe_gemm: descriptor is NULL");
+    return AXE_EINVAL;
+  }
+  if (g->M <= 0 || g->N <= 0 || g->K <= 0) {
+    set_error("axe_gemm: M, N, K must be positive");
+    return AXE_EINVAL;
+  }
+  if (g->in_dtype != AXE_BF16 && g->in_dtype != AXE_FP8_E4M3) {
+    set_error("axe_gemm: in_dtype %d unknown", g->in_dtype);
+    return AXE_EINVAL;
+  }
+  if (g->out_dtype != AXE_F32 && g->out_dtype != AXE_BF16) {
+    set_error("axe_gemm: out_dtype %d unknown", g->out_dtype);
+    return AXE_EINVAL;
+  }
+  const bool fp8 = g->in_dtype == AXE_FP8_E4M3;
+  const int eb = fp8 ? 1 : 2, ob = g->out_dtype == AXE_F32 ? 4 : 2;
+  if ((g->d_scale_a == nullptr) != (g->d_scale_b == nullptr)) {
+    set_error("axe_gemm: scales must be given for both operands or neither");
+    return AXE_EINVAL;
+  }
+  if (g->d_scale_a && (!fp8 || g->scale_block != 128)) {
+    set_error("axe_gemm: block scales need in_dtype fp8 and scale_block 128");
+    return AXE_EUNSUPPORTED;
+  }
+  int64_t lda, ldb, ldc, oa, ob_, oc;
+  if (int rc = strided_2d(&g->A, g->mem_axis, g->M, g->K, true, g->a_elems, "axe_gemm(A)", &lda, &oa)) return rc;
+  if (int rc = strided_2d(&g->B, g->mem_axis, g->K, g->N, false, g->b_elems, "axe_gemm(B)", &ldb, &ob_)) return rc;
+  if (int rc = strided_2d(&g->C, g->mem_axis, g->M, g->N, true, g->c_elems, "axe_gemm(C)", &ldc, &oc)) return rc;
+  const int64_t vec = 16 / eb;
+  if ((g->K % vec) || (lda % vec) || (ldb % vec) || (oa % vec) || (ob_ % vec)) {
+    set_error("axe_gemm: K, leading dimensions and offsets of A and B must be multiples of %lld elements (16 bytes)",
+              (long long)vec);
+    return AXE_EUNSUPPORTED;
+  }
+  if ((oc * ob) % 16) {
+    set_error("axe_gemm: offset of C must keep 16-byte alignment");
+    return AXE_EUNSUPPORTED;
+  }
+  if (need_ptrs) {
+    if (!dA || !dB || !dC) {
+      set_error("axe_gemm: NULL device pointer");
+      return AXE_EINVAL;
+    }
+    if (((uintptr_t)dA | (uintptr_t)dB | (uintptr_t)dC) & 15) {
+      set_error("axe_gemm: device buffers must be 16-byte aligned");
+      return AXE_EINVAL;
+    }
+    const char* c0 = (const char*)dC;
+    const char* c1 = c0 + g->c_elems * ob;
+    const char* a0 = (const char*)dA;
+    const char* b0 = (const char*)dB;
+    if ((a0 < c1 && c0 < a0 + g->a_elems * eb) || (b0 < c1 && c0 < b0 + g->b_elems * eb)) {
+      set_error("axe_gemm: C overlaps an input buffer");
+      return AXE_EINVAL;
+    }
+  }
+  memset(&P.args, 0, sizeof P.args);
+  P.fp8 = fp8;
+  P.args.A = (const char*)dA + oa * eb;
+  P.args.B = (const char*)dB + ob_ * eb;
+  P.args.C = (char*)dC + oc * ob;
+  P.args.M = g->M;
+  P.args.N = g->N;
+  P.args.K = g->K;
+  P.args.lda = lda;
+  P.args.ldb = ldb;
+  P.args.ldc = ldc;
+  P.args.scale_a = g->d_scale_a;
+  P.args.scale_b = g->d_scale_b;
+  P.args.nkb = (int32_t)((g->K + 127) / 128);
+  P.args.out_bf16 = g->out_dtype == AXE_BF16;
+  const int64_t bk = fp8 ? 128 : 64;
+  const bool big_ok = (g->M % 256 == 0) && (g->N % 256 == 0) && (g->K % bk == 0) && (ldc % 8 == 0) &&
+                      P.args.out_bf16;
+  int tile = g->tile_hint;
+  if (tile == AXE_TILE_AUTO) tile = big_ok ? AXE_TILE_256x256x64 : AXE_TILE_64x64x32;
+  if (tile == AXE_TILE_256x256x64 && !big_ok) {
+    set_error("axe_gemm: the 256x256 tile needs M, N multiples of 256, K a multiple of %lld and bf16 output",
+              (long long)bk);
+    return AXE_EUNSUPPORTED;
+  }
+  if (tile != AXE_TILE_256x256x64 && tile != AXE_TILE_64x64x32) {
+    set_error("axe_gemm: unknown tile_hint %d", tile);
+    return AXE_EINVAL;
+  }
+  P.tile = tile;
+  const int64_t bt = tile == AXE_TILE_256x256x64 ? 256 : 64;
+  P.args.grid_m = (int32_t)((g->M + bt - 1) / bt);
+  P.args.grid_n = (int32_t)((g->N + bt - 1) / bt);
+  if (P.args.grid_m > 65535) {
+    set_error("axe_gemm: M too large for one launch");
+    return AXE_EUNSUPPORTED;
+  }
+  return AXE_OK;
+}
+
+}  // namespace
+
+int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d_C, void* stream) {
+  GemmPlan P;
+  if (int rc = plan_gemm(g, d_A, d_B, d_C, P, true)) return rc;
+  hipError_t e;
+  if (P.tile == AXE_TILE_256x256x64)
+    e = P.fp8 ? launch_gemm_fp8_256(P.args, (hipStream_t)stream) : launch_gemm_bf16_256(P.args, (hipStream_t)stream);
+  else
+    e = launch_gemm_small(P.args, P.fp8, (hipStream_t)stream);
+  return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm");
+}
+
+// Chosen kernel, for tests and tools: returns AXE_TILE_* or a negative error.
+int axe_gemm_tile(const axe_gemm_desc_t* g) {
+  GemmPlan P;
+  if (int rc = plan_gemm(g, nullptr, nullptr, nullptr, P, false)) return rc;
+  return P.tile;
+}
+
+}  // extern "C"

@@ -1,0 +1,77 @@
+// Plain-data descriptors handed from the host layer to the kernels by value (kernel arguments).
+#pragma once
+#include <stdint.h>
+
+namespace axe {
+
+constexpr int kMaxD = 16;
+constexpr int kMaxR = 8;
+constexpr int kMaxAxes = 8;
+constexpr int kMaxJoint = 24;   // common refinement of two D lists can be longer than either
+
+// XOR stage: y = x ^ (((x >> shift) & mask) << base); mask == 0 disables it.
+struct Swz {
+  int32_t mask, base, shift;
+};
+
+// Full layout for axe_layout_eval (all axes kept).
+struct EvalDesc {
+  int32_t n_d, n_r, n_axes;
+  int32_t use32;               // E_D < 2^31: digit arithmetic in 32 bits
+  int64_t ext[kMaxD], str[kMaxD];
+  int32_t axis[kMaxD];
+  int64_t rext[kMaxR], rstr[kMaxR];
+  int32_t raxis[kMaxR];
+  int64_t off[kMaxAxes];
+  int32_t swz_axis;
+  Swz swz;
+  int64_t E_D, E_R;
+};
+
+// Relayout plan: one loop nest shared by source and destination (their common refinement),
+// enumerated fastest digit first.  Addresses in units of `unit_bytes`.
+struct RelayoutPlan {
+  int32_t n;                       // loop digits decoded from the thread index
+  uint32_t ext[kMaxJoint];
+  int32_t shift[kMaxJoint];        // log2(ext) when ext is a power of two, else -1
+  int64_t ss[kMaxJoint], ds[kMaxJoint];
+  int32_t U;                       // per-thread unroll digit (extent U, strides us / ud)
+  int64_t us, ud;
+  int64_t s_off, d_off;
+  Swz s_swz, d_swz;
+  int32_t n_r;                     // destination replicas
+  int32_t rext[kMaxR];
+  int64_t rstr[kMaxR];
+  int64_t E_R;
+  uint64_t threads;                // total work items = elements / (vector width * U)
+};
+
+// Fallback when the two digit systems have no common refinement: decode each side separately.
+struct GenericRelayoutPlan {
+  int32_t ns, nd;
+  int64_t sext[kMaxD], sstr[kMaxD];
+  int64_t dext[kMaxD], dstr[kMaxD];
+  int64_t s_off, d_off;
+  Swz s_swz, d_swz;
+  int32_t n_r;
+  int32_t rext[kMaxR];
+  int64_t rstr[kMaxR];
+  int64_t E_R;
+  int64_t total;
+};
+
+// GEMM arguments (addresses in elements of the operand's dtype).
+struct GemmArgs {
+  const void* A;
+  const void* B;
+  void* C;
+  int64_t M, N, K;
+  int64_t lda, ldb, ldc;           // row pitch of A (per i), of B's memory image (per j), of C (per i)
+  const float* scale_a;            // (ceil(M/128), nkb) or null
+  const float* scale_b;            // (ceil(N/128), nkb) or null
+  int32_t nkb;
+  int32_t out_bf16;                // 0: fp32 output, 1: bf16 output
+  int32_t grid_m, grid_n;          // workgroup tiles along M and N
+};
+
+}  // namespace axe

@@ -1,0 +1,183 @@
+// Small-tile GEMM for gfx950: workgroup tile 64 x 64, K step of one LDS row (bf16: 32 elements
+// = 64 B, fp8: 128 elements = 128 B), 4 waves in a 2 x 2 grid, each wave a 32 x 32 sub-tile made
+// of 2 x 2 MFMA 16x16 fragments.  Ragged M / N are handled by zero-filled loads and guarded
+// stores, so this kernel serves every shape the library accepts; the large-tile kernel takes
+// over for big aligned problems.
+//
+// Tile movements (all K-contiguous, A row-major and B column-major):
+//   HBM -> VGPR : thread t fetches 16-byte chunk (row = t / CH, chunk = t % CH) of the tile
+//   VGPR -> LDS : row-major rows of ROWB bytes, 16-byte chunk index XOR-ed with row bits
+//   LDS -> VGPR : lane l reads row (l % 16) of a fragment, K chunk(s) (l / 16) -- the MFMA operand layout
+//   MFMA        : operands swapped (B rows as the first operand) so that the accumulator
+//                 fragment holds 4 consecutive columns of one C row per lane -> vector stores
+#include <hip/hip_runtime.h>
+
+#include "device_types.h"
+#include "kernels.h"
+
+namespace axe {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+__device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
+  __bf16 h = (__bf16)f;                       // v_cvt_pk_bf16_f32: round to nearest even
+  return __builtin_bit_cast(uint16_t, h);
+}
+
+template <bool FP8>
+__global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
+  constexpr int EB = FP8 ? 1 : 2;             // element bytes
+  constexpr int ROWB = FP8 ? 128 : 64;        // bytes of K per LDS row
+  constexpr int CH = ROWB / 16;               // 16-byte chunks per row
+  constexpr int BK = ROWB / EB;               // elements per K step
+  constexpr int PER = (64 * CH) / 256;        // chunks per thread per operand
+  constexpr int KEYSH = FP8 ? 1 : 2;          // swizzle key = (row >> KEYSH) & (CH - 1)
+
+  __shared__ __attribute__((aligned(16))) uint8_t lds[2][2][64 * ROWB];   // [stage][A|B]
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int wm = wave >> 1, wn = wave & 1;
+  const int64_t m0 = (int64_t)blockIdx.y * 64, n0 = (int64_t)blockIdx.x * 64;
+  const uint8_t* Ab = (const uint8_t*)g.A;
+  const uint8_t* Bb = (const uint8_t*)g.B;
+  const int64_t nk = (g.K + BK - 1) / BK;
+
+  uint4 ra[PER], rb[PER];
+  auto fetch = [&](int64_t kt) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int c = tid + p * 256;
+      int row = c / CH, ch = c % CH;
+      int64_t k = kt * BK + (int64_t)ch * (16 / EB);
+      uint4 z = {0, 0, 0, 0};
+      ra[p] = (m0 + row < g.M && k < g.K) ? *(const uint4*)(Ab + ((m0 + row) * g.lda + k) * EB) : z;
+      rb[p] = (n0 + row < g.N && k < g.K) ? *(const uint4*)(Bb + ((n0 + row) * g.ldb + k) * EB) : z;
+    }
+  };
+  auto stash = [&](int st) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int c = tid + p * 256;
+      int row = c / CH, ch = c % CH;
+      int pc = ch ^ ((row >> KEYSH) & (CH - 1));
+      *(uint4*)(&lds[st][0][row * ROWB + pc * 16]) = ra[p];
+      *(uint4*)(&lds[st][1][row * ROWB + pc * 16]) = rb[p];
+    }
+  };
+
+  f32x4 acc[2][2];
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int frow = lane & 15, fgrp = lane >> 4;
+  const int sa_row = (int)(m0 / 128), sb_row = (int)(n0 / 128);
+
+  fetch(0);
+  stash(0);
+  __syncthreads();
+  for (int64_t kt = 0; kt < nk; ++kt) {
+    const int st = (int)(kt & 1);
+    if (kt + 1 < nk) fetch(kt + 1);
+    if constexpr (!FP8) {
+      bf16x8 fa[2], fb[2];
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        int r = wm * 32 + f * 16 + frow;
+        fa[f] = *(const bf16x8*)(&lds[st][0][r * ROWB + ((fgrp ^ ((r >> KEYSH) & (CH - 1))) * 16)]);
+        r = wn * 32 + f * 16 + frow;
+        fb[f] = *(const bf16x8*)(&lds[st][1][r * ROWB + ((fgrp ^ ((r >> KEYSH) & (CH - 1))) * 16)]);
+      }
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+    } else {
+      i32x8 fa[2], fb[2];
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        int r = wm * 32 + f * 16 + frow;
+        int key = (r >> KEYSH) & (CH - 1);
+        i32x4 lo = *(const i32x4*)(&lds[st][0][r * ROWB + (((2 * fgrp) ^ key) * 16)]);
+        i32x4 hi = *(const i32x4*)(&lds[st][0][r * ROWB + (((2 * fgrp + 1) ^ key) * 16)]);
+        fa[f] = i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        r = wn * 32 + f * 16 + frow;
+        key = (r >> KEYSH) & (CH - 1);
+        lo = *(const i32x4*)(&lds[st][1][r * ROWB + (((2 * fgrp) ^ key) * 16)]);
+        hi = *(const i32x4*)(&lds[st][1][r * ROWB + (((2 * fgrp + 1) ^ key) * 16)]);
+        fb[f] = i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+      }
+      if (g.scale_a) {
+        // one K step is one 128-deep scale block: accumulate it alone, then scale and add
+        const float sc = g.scale_a[(int64_t)sa_row * g.nkb + kt] * g.scale_b[(int64_t)sb_row * g.nkb + kt];
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j) {
+            f32x4 part = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i], f32x4{0.f, 0.f, 0.f, 0.f},
+                                                                        0, 0, 0, 0, 0, 0);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = __builtin_fmaf(sc, part[e], acc[i][j][e]);
+          }
+      } else {
+#pragma unroll
+        for (int i = 0; i < 2; ++i)
+#pragma unroll
+          for (int j = 0; j < 2; ++j)
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i], acc[i][j], 0, 0, 0, 0, 0, 0);
+      }
+    }
+    if (kt + 1 < nk) stash(st ^ 1);
+    __syncthreads();
+  }
+
+  // accumulator fragment (operands swapped): lane holds C[m][n .. n+3], m = frag row base + lane % 16,
+  // n = frag col base + 4 * (lane / 16)
+#pragma unroll
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) {
+      int64_t m = m0 + wm * 32 + i * 16 + frow;
+      int64_t n = n0 + wn * 32 + j * 16 + 4 * fgrp;
+      if (m >= g.M) continue;
+      if (g.out_bf16) {
+        uint16_t* C = (uint16_t*)g.C + m * g.ldc + n;
+        uint16_t h[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16_rne(acc[i][j][e]);
+        if (n + 3 < g.N && ((g.ldc & 3) == 0)) {
+          *(uint2*)C = uint2{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < g.N) C[e] = h[e];
+        }
+      } else {
+        float* C = (float*)g.C + m * g.ldc + n;
+        if (n + 3 < g.N && ((g.ldc & 3) == 0)) {
+          *(float4*)C = float4{acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]};
+        } else {
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < g.N) C[e] = acc[i][j][e];
+        }
+      }
+    }
+}
+
+hipError_t launch_gemm_small(const GemmArgs& g, bool fp8, hipStream_t s) {
+  dim3 grid((unsigned)((g.N + 63) / 64), (unsigned)((g.M + 63) / 64));
+  if (fp8)
+    hipLaunchKernelGGL(gemm_small_kernel<true>, grid, dim3(256), 0, s, g);
+  else
+    hipLaunchKernelGGL(gemm_small_kernel<false>, grid, dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+}  // namespace axe

@@ -1,0 +1,221 @@
+// Integer kernels: layout evaluation (Def. 2.3) and relayout copies (`copy` operator, Sec. 3.2).
+// gfx950 only.  Bandwidth-bound: no LDS, 128-bit global accesses wherever the layouts allow.
+#include <hip/hip_runtime.h>
+
+#include "device_types.h"
+#include "kernels.h"
+
+namespace axe {
+
+__device__ __forceinline__ int64_t swz_apply(int64_t x, Swz z) {
+  return x ^ (((x >> z.shift) & (int64_t)z.mask) << z.base);
+}
+
+// ------------------------------------------------------------------------------------------
+// Layout evaluation: one thread per logical index.  Digits are peeled from the fastest iter
+// (d_i = floor(x / p_i) mod e_i, App. A), each contributes digit * stride to its axis.
+// ------------------------------------------------------------------------------------------
+template <typename IdxT>
+__global__ __launch_bounds__(256) void layout_eval_kernel(EvalDesc d, int64_t n, const int64_t* __restrict__ idx,
+                                                          int64_t* __restrict__ out) {
+  const int64_t per = d.E_R * d.n_axes;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += (int64_t)gridDim.x * blockDim.x) {
+    int64_t x = idx ? idx[i] : i;
+    int64_t* o = out + i * per;
+    if (x < 0 || x >= d.E_D) {
+      for (int64_t t = 0; t < per; ++t) o[t] = INT64_MIN;
+      continue;
+    }
+    int64_t c[kMaxAxes];
+#pragma unroll
+    for (int a = 0; a < kMaxAxes; ++a) c[a] = d.off[a];
+    IdxT rem = (IdxT)x;
+    for (int k = d.n_d - 1; k >= 0; --k) {
+      IdxT e = (IdxT)d.ext[k];
+      IdxT q = rem / e;
+      int64_t v = (int64_t)(rem - q * e) * d.str[k];
+      rem = q;
+      int ax = d.axis[k];
+#pragma unroll
+      for (int a = 0; a < kMaxAxes; ++a) c[a] += (a == ax) ? v : 0;
+    }
+    for (int64_t t = 0; t < d.E_R; ++t) {
+      int64_t r[kMaxAxes];
+#pragma unroll
+      for (int a = 0; a < kMaxAxes; ++a) r[a] = c[a];
+      int64_t tr = t;
+      for (int k = d.n_r - 1; k >= 0; --k) {
+        int64_t q = tr / d.rext[k];
+        int64_t v = (tr - q * d.rext[k]) * d.rstr[k];
+        tr = q;
+        int ax = d.raxis[k];
+#pragma unroll
+        for (int a = 0; a < kMaxAxes; ++a) r[a] += (a == ax) ? v : 0;
+      }
+#pragma unroll
+      for (int a = 0; a < kMaxAxes; ++a) {
+        if (a < d.n_axes) {
+          int64_t v = r[a];
+          if (a == d.swz_axis) v = swz_apply(v, d.swz);
+          o[t * d.n_axes + a] = v;
+        }
+      }
+    }
+  }
+}
+
+hipError_t launch_layout_eval(const EvalDesc& d, int64_t n, const int64_t* idx, int64_t* out, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  int64_t blocks = (n + 255) / 256;
+  if (blocks > 65536 * 4) blocks = 65536 * 4;
+  if (d.use32)
+    hipLaunchKernelGGL(layout_eval_kernel<uint32_t>, dim3((unsigned)blocks), dim3(256), 0, s, d, n, idx, out);
+  else
+    hipLaunchKernelGGL(layout_eval_kernel<uint64_t>, dim3((unsigned)blocks), dim3(256), 0, s, d, n, idx, out);
+  return hipGetLastError();
+}
+
+// ------------------------------------------------------------------------------------------
+// Relayout, joint loop nest.  Thread w decodes its digits (fastest first); its U unrolled
+// elements step along one more digit.  All loads are issued before the first store.
+// ------------------------------------------------------------------------------------------
+template <int BYTES> struct Word;
+template <> struct Word<1> { using T = uint8_t; };
+template <> struct Word<2> { using T = uint16_t; };
+template <> struct Word<4> { using T = uint32_t; };
+template <> struct Word<8> { using T = uint2; };
+template <> struct Word<16> { using T = uint4; };
+
+template <int BYTES, int U, bool REPL>
+__global__ __launch_bounds__(256) void relayout_joint_kernel(RelayoutPlan p, const void* __restrict__ src_,
+                                                             void* __restrict__ dst_) {
+  using T = typename Word<BYTES>::T;
+  const T* __restrict__ src = (const T*)src_;
+  T* __restrict__ dst = (T*)dst_;
+  uint64_t w64 = (uint64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (w64 >= p.threads) return;
+  uint32_t w = (uint32_t)w64;            // host guarantees threads < 2^32
+  int64_t s = p.s_off, d = p.d_off;
+  for (int k = 0; k < p.n; ++k) {
+    uint32_t dig;
+    if (p.shift[k] >= 0) {
+      dig = w & (p.ext[k] - 1);
+      w >>= p.shift[k];
+    } else {
+      uint32_t q = w / p.ext[k];
+      dig = w - q * p.ext[k];
+      w = q;
+    }
+    s += (int64_t)dig * p.ss[k];
+    d += (int64_t)dig * p.ds[k];
+  }
+  T v[U];
+#pragma unroll
+  for (int u = 0; u < U; ++u) v[u] = src[swz_apply(s + u * p.us, p.s_swz)];
+#pragma unroll
+  for (int u = 0; u < U; ++u) {
+    int64_t da = d + u * p.ud;
+    if (!REPL) {
+      dst[swz_apply(da, p.d_swz)] = v[u];
+    } else {
+      for (int64_t t = 0; t < p.E_R; ++t) {
+        int64_t tr = t, ra = da;
+        for (int k = p.n_r - 1; k >= 0; --k) {
+          int64_t q = tr / p.rext[k];
+          ra += (tr - q * p.rext[k]) * p.rstr[k];
+          tr = q;
+        }
+        dst[swz_apply(ra, p.d_swz)] = v[u];
+      }
+    }
+  }
+}
+
+template <int BYTES, int U>
+static hipError_t launch_joint_u(const RelayoutPlan& p, const void* src, void* dst, hipStream_t s) {
+  unsigned blocks = (unsigned)((p.threads + 255) / 256);
+  if (p.n_r > 0)
+    hipLaunchKernelGGL((relayout_joint_kernel<BYTES, U, true>), dim3(blocks), dim3(256), 0, s, p, src, dst);
+  else
+    hipLaunchKernelGGL((relayout_joint_kernel<BYTES, U, false>), dim3(blocks), dim3(256), 0, s, p, src, dst);
+  return hipGetLastError();
+}
+
+template <int BYTES>
+static hipError_t launch_joint_b(const RelayoutPlan& p, const void* src, void* dst, hipStream_t s) {
+  switch (p.U) {
+    case 1: return launch_joint_u<BYTES, 1>(p, src, dst, s);
+    case 2: return launch_joint_u<BYTES, 2>(p, src, dst, s);
+    case 4: return launch_joint_u<BYTES, 4>(p, src, dst, s);
+    case 8: return launch_joint_u<BYTES, 8>(p, src, dst, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+hipError_t launch_relayout_joint(const RelayoutPlan& p, int unit_bytes, const void* src, void* dst, hipStream_t s) {
+  if (p.threads == 0) return hipSuccess;
+  switch (unit_bytes) {
+    case 1: return launch_joint_b<1>(p, src, dst, s);
+    case 2: return launch_joint_b<2>(p, src, dst, s);
+    case 4: return launch_joint_b<4>(p, src, dst, s);
+    case 8: return launch_joint_b<8>(p, src, dst, s);
+    case 16: return launch_joint_b<16>(p, src, dst, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// Relayout, generic: one element per thread, source and destination decoded separately from
+// the logical index.  Correct for any pair of layouts; used when no joint loop nest exists.
+// ------------------------------------------------------------------------------------------
+template <int BYTES>
+__global__ __launch_bounds__(256) void relayout_generic_kernel(GenericRelayoutPlan p, const void* __restrict__ src_,
+                                                               void* __restrict__ dst_) {
+  using T = typename Word<BYTES>::T;
+  const T* __restrict__ src = (const T*)src_;
+  T* __restrict__ dst = (T*)dst_;
+  for (int64_t x = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; x < p.total; x += (int64_t)gridDim.x * blockDim.x) {
+    int64_t s = p.s_off, d = p.d_off;
+    uint64_t rem = (uint64_t)x;
+    for (int k = p.ns - 1; k >= 0; --k) {
+      uint64_t q = rem / (uint64_t)p.sext[k];
+      s += (int64_t)(rem - q * (uint64_t)p.sext[k]) * p.sstr[k];
+      rem = q;
+    }
+    rem = (uint64_t)x;
+    for (int k = p.nd - 1; k >= 0; --k) {
+      uint64_t q = rem / (uint64_t)p.dext[k];
+      d += (int64_t)(rem - q * (uint64_t)p.dext[k]) * p.dstr[k];
+      rem = q;
+    }
+    T v = src[swz_apply(s, p.s_swz)];
+    for (int64_t t = 0; t < p.E_R; ++t) {
+      int64_t tr = t, ra = d;
+      for (int k = p.n_r - 1; k >= 0; --k) {
+        int64_t q = tr / p.rext[k];
+        ra += (tr - q * p.rext[k]) * p.rstr[k];
+        tr = q;
+      }
+      dst[swz_apply(ra, p.d_swz)] = v;
+    }
+  }
+}
+
+hipError_t launch_relayout_generic(const GenericRelayoutPlan& p, int unit_bytes, const void* src, void* dst,
+                                   hipStream_t s) {
+  if (p.total <= 0) return hipSuccess;
+  int64_t blocks = (p.total + 255) / 256;
+  if (blocks > 65536 * 4) blocks = 65536 * 4;
+  dim3 g((unsigned)blocks), b(256);
+  switch (unit_bytes) {
+    case 1: hipLaunchKernelGGL(relayout_generic_kernel<1>, g, b, 0, s, p, src, dst); break;
+    case 2: hipLaunchKernelGGL(relayout_generic_kernel<2>, g, b, 0, s, p, src, dst); break;
+    case 4: hipLaunchKernelGGL(relayout_generic_kernel<4>, g, b, 0, s, p, src, dst); break;
+    case 8: hipLaunchKernelGGL(relayout_generic_kernel<8>, g, b, 0, s, p, src, dst); break;
+    case 16: hipLaunchKernelGGL(relayout_generic_kernel<16>, g, b, 0, s, p, src, dst); break;
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+}  // namespace axe

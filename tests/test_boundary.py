@@ -1,0 +1,141 @@
+"""The C-ABI boundary without a GPU: the shared library loads, exports every symbol include/axe.h
+declares, and turns malformed arguments into error codes before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_2601_19092_amd import binding as B
+from paper_2601_19092_amd import workloads as W
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "axe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(axe_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    L = B.lib()
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+    assert B.version() >= 100
+    assert b"shape" in L.axe_strerror(B.AXE_ESHAPE)
+
+
+def _eval_rc(spec, shape, n=None, axes=None):
+    L = B.Layout(spec, axes)
+    shp = (C.c_int64 * len(shape))(*shape)
+    n = 1 if n is None else n
+    # device pointers are never touched when validation fails; pass a dummy non-NULL address
+    return B.lib().axe_layout_eval(C.byref(L.c), len(shape), shp, n, None, 0x1000, None)
+
+
+def test_layout_eval_rejects_bad_layouts():
+    ok = W.spec([(4, 1, "m")])
+    assert _eval_rc(W.spec([(0, 1, "m")]), (1,)) == B.AXE_EINVAL            # extent must be > 0
+    assert _eval_rc(W.spec([(-3, 1, "m")]), (1,)) == B.AXE_EINVAL
+    assert _eval_rc(W.spec([(4, 0, "m")]), (4,)) == B.AXE_EINVAL            # stride must be != 0
+    assert _eval_rc(W.spec([(4, 1, "m")], R=[(2, 0, "m")]), (4,)) == B.AXE_EINVAL
+    assert _eval_rc(W.spec([]), (1,)) == B.AXE_EINVAL                       # n_D >= 1
+    assert _eval_rc(ok, (5,)) == B.AXE_ESHAPE                               # shape not admitted
+    assert _eval_rc(ok, (2, 3)) == B.AXE_ESHAPE
+    assert _eval_rc(ok, (4,), n=5) == B.AXE_ERANGE                          # implicit indices beyond E_D
+    assert _eval_rc(ok, (4,), n=-1) == B.AXE_EINVAL
+    assert _eval_rc(W.spec([(4, 1, "m")], swizzle=("m", 3, 2, 4)), (4,)) == B.AXE_EINVAL   # base+bits > shift
+    assert "swizzle" in B.lib().axe_last_error().decode()
+    # axis index out of range
+    L = B.Layout(ok)
+    L._d[0].axis = 3
+    shp = (C.c_int64 * 1)(4)
+    assert B.lib().axe_layout_eval(C.byref(L.c), 1, shp, 1, None, 0x1000, None) == B.AXE_EINVAL
+    # overflowing extents
+    big = W.spec([(2 ** 40, 1, "m"), (2 ** 40, 1, "m")])
+    assert _eval_rc(big, (1,)) == B.AXE_ERANGE
+    # n = 0 is a no-op that needs no device
+    assert _eval_rc(ok, (4,), n=0) == B.AXE_OK
+
+
+def _relayout_rc(src, dst, shape, eb=2, s_elems=None, d_elems=None, sp=0x10000, dp=0x9000000, axes=("m", "gpuid")):
+    Ls, Ld = B.Layout(src, axes), B.Layout(dst, axes)
+    n = 1
+    for s in shape:
+        n *= s
+    shp = (C.c_int64 * len(shape))(*shape)
+    return B.lib().axe_relayout(C.byref(Ls.c), C.byref(Ld.c), len(shape), shp, eb, 0, sp,
+                                n if s_elems is None else s_elems, dp, n if d_elems is None else d_elems, None)
+
+
+def test_relayout_rejects_before_launch():
+    rm = W.row_major_spec(8, 8)
+    assert _relayout_rc(rm, W.row_major_spec(4, 8), (8, 8)) == B.AXE_ESHAPE
+    assert _relayout_rc(rm, rm, (8, 8), eb=3) == B.AXE_EINVAL
+    # destination where two logical elements share an address
+    alias = W.spec([(8, 4, "m"), (8, 1, "m")])
+    assert _relayout_rc(rm, alias, (8, 8)) == B.AXE_EALIAS
+    # a sharded axis of extent > 1 cannot live on one GPU
+    sharded = W.spec([(2, 1, "gpuid"), (4, 8, "m"), (8, 1, "m")])
+    assert _relayout_rc(sharded, rm, (8, 8)) == B.AXE_EALIAS
+    # addresses beyond the declared buffers
+    assert _relayout_rc(rm, rm, (8, 8), d_elems=63) == B.AXE_ERANGE
+    assert _relayout_rc(rm, W.spec([(8, 8, "m"), (8, 1, "m")], O={"m": -1}), (8, 8)) == B.AXE_ERANGE
+    assert _relayout_rc(W.spec([(8, -8, "m"), (8, 1, "m")]), rm, (8, 8)) == B.AXE_ERANGE   # negative stride, no offset
+    # overlapping / misaligned / NULL buffers
+    assert _relayout_rc(rm, rm, (8, 8), sp=0x10000, dp=0x10040) == B.AXE_EINVAL
+    assert _relayout_rc(rm, rm, (8, 8), sp=0x10001) == B.AXE_EINVAL
+    assert _relayout_rc(rm, rm, (8, 8), sp=0) == B.AXE_EINVAL
+    # swizzle on a negative coordinate
+    neg = W.spec([(8, 8, "m"), (8, 1, "m")], O={"m": -64}, swizzle=("m", 1, 0, 3))
+    assert _relayout_rc(rm, neg, (8, 8)) == B.AXE_ERANGE
+
+
+def _gemm_desc(M=256, N=256, K=256, A=None, Bs=None, Cs=None, in_dtype=B.AXE_BF16, out_dtype=B.AXE_BF16,
+               tile=B.AXE_TILE_AUTO, a_elems=None, axes=("m", "gpuid")):
+    A = A or W.row_major_spec(M, K)
+    Bs = Bs or W.col_major_spec(K, N)
+    Cs = Cs or W.row_major_spec(M, N)
+    return B.GemmDesc(M, N, K, in_dtype, out_dtype, B.Layout(A, axes), B.Layout(Bs, axes), B.Layout(Cs, axes),
+                      M * K if a_elems is None else a_elems, N * K, M * N, tile_hint=tile)
+
+
+def _tile_rc(desc):
+    return B.lib().axe_gemm_tile(C.byref(desc.c))
+
+
+def test_gemm_family_matching_and_errors():
+    assert _tile_rc(_gemm_desc()) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(M=200)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(M=200, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
+    # the shard of a column-parallel layer: extent-1 device iter + device offset are dropped (rule D0)
+    g = W.gemm_bf16(256, 512, 256, 1)
+    _, Bshard, _ = W.gemm_specs(g, device_axis=True, shard=5)
+    assert _tile_rc(_gemm_desc(N=512, Bs=Bshard)) == B.AXE_TILE_256x256x64
+    # a weight still spread over 8 GPUs is not one GPU's tensor
+    spread = W.spec([(256, 1, "m"), (8, 1, "gpuid"), (64, 256, "m")])
+    assert _tile_rc(_gemm_desc(N=512, Bs=spread)) == B.AXE_EALIAS
+    # wrong shapes, wrong families
+    assert _tile_rc(_gemm_desc(A=W.row_major_spec(256, 128))) == B.AXE_ESHAPE
+    assert _tile_rc(_gemm_desc(A=W.col_major_spec(256, 256))) == B.AXE_EUNSUPPORTED     # A not K-contiguous
+    assert _tile_rc(_gemm_desc(Bs=W.row_major_spec(256, 256))) == B.AXE_EUNSUPPORTED    # B not K-contiguous
+    assert _tile_rc(_gemm_desc(K=250, A=W.row_major_spec(256, 250), Bs=W.col_major_spec(250, 256))) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(_gemm_desc(a_elems=100)) == B.AXE_ERANGE
+    assert _tile_rc(_gemm_desc(in_dtype=7)) == B.AXE_EINVAL
+    assert _tile_rc(_gemm_desc(M=0)) == B.AXE_EINVAL
+    # pitched operands (leading dimension larger than the row) are in the family
+    pitched = W.spec([(256, 264, "m"), (256, 1, "m")])
+    assert _tile_rc(_gemm_desc(A=pitched, a_elems=256 * 264)) == B.AXE_TILE_256x256x64
+    # NULL device pointers are refused by axe_gemm itself
+    d = _gemm_desc()
+    assert B.lib().axe_gemm(C.byref(d.c), None, None, None, None) == B.AXE_EINVAL
+
+
+def test_python_binding_raises_axe_error():
+    with pytest.raises(B.AxeError) as e:
+        B._check(B.AXE_EALIAS)
+    assert e.value.code == B.AXE_EALIAS

@@ -1,0 +1,303 @@
+"""Parity of the HIP path (through the C ABI) with the CPU oracle, element by element.
+
+Bars: layout evaluation and relayout bit-exact; GEMM relative Frobenius error <= 5e-3 (bf16
+inputs) / 3e-2 (fp8 inputs) against the fp64 oracle on the same quantised inputs, for the whole
+matrix and for every 128 x 128 tile of it (a single wrong tile cannot hide in the global norm)."""
+import itertools
+import random
+from math import prod
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import axe_layout as ax
+from oracle import axe_ref as R
+from oracle.axe_layout import Iter, Layout, Swizzle
+from paper_2601_19092_amd import binding as B
+from paper_2601_19092_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+BF16_TOL, FP8_TOL = 5e-3, 3e-2
+
+
+def dev(a: np.ndarray) -> torch.Tensor:
+    """Raw words -> CUDA tensor of the same bit width."""
+    a = np.ascontiguousarray(a)
+    view = {1: np.uint8, 2: np.int16, 4: np.int32, 8: np.int64}[a.dtype.itemsize] if a.dtype.kind in "ui" else a.dtype
+    return torch.from_numpy(a.view(view).copy()).cuda()
+
+
+def host_words(t: torch.Tensor, dtype) -> np.ndarray:
+    return t.cpu().numpy().view(dtype)
+
+
+def spec_of(L: Layout) -> dict:
+    z = L.swizzle
+    return W.spec([(i.extent, i.stride, i.axis) for i in L.D], [(i.extent, i.stride, i.axis) for i in L.R],
+                  dict(L.O), (z.axis, z.bits, z.base, z.shift) if z else None)
+
+
+# ----------------------------------------------------------------------------- layout evaluation
+def eval_both(L: Layout, shape, idx=None):
+    axes = L.axes()
+    bl = B.Layout(spec_of(L), axes)
+    n = L.E_D if idx is None else len(idx)
+    didx = None if idx is None else torch.from_numpy(np.asarray(idx, dtype=np.int64)).cuda()
+    got = B.axe_layout_eval(bl, shape, n, didx).cpu().numpy()
+    xs = np.arange(n) if idx is None else np.asarray(idx)
+    want = R.evaluate_np(L, xs, axes)
+    return got, want
+
+
+def test_eval_paper_examples(golden):
+    cases = []
+    g = golden["tensor_core_tile"]
+    cases.append((Layout.make(g["D"]["extents"], g["D"]["strides"], R=(g["R"]["extents"], g["R"]["strides"]), O=g["O"]), g["shape"]))
+    g = golden["mesh_fully_sharded"]
+    cases.append((Layout.make(g["D"]["extents"], g["D"]["strides"]), g["shape"]))
+    g = golden["mesh_shard_replica"]
+    cases.append((Layout.make(g["D"]["extents"], g["D"]["strides"], R=(g["R"]["extents"], g["R"]["strides"])), g["shape"]))
+    g = golden["cute_partition"]
+    cases.append((Layout.make(g["D"]["extents"], g["D"]["strides"], O=g["O"]), (16, 64)))
+    g = golden["triton_local"]
+    cases.append((Layout.make(g["D"]["extents"], g["D"]["strides"]), (16, 64)))
+    g = golden["tile_example"]
+    cases.append((Layout.make(g["T"]["extents"], g["T"]["strides"]), (16, 24)))
+    cases.append((Layout.make((24, 24), (1, 24)), (24, 24)))
+    for L, shape in cases:
+        got, want = eval_both(L, shape)
+        assert got.shape == want.shape and np.array_equal(got, want), repr(L)
+        # and against the scalar definition for a few points
+        for x in (0, L.E_D // 3, L.E_D - 1):
+            assert [tuple(r) for r in got[x]] == ax.evaluate(L, x, L.axes())
+
+
+def test_eval_random_layouts_and_explicit_indices():
+    rng = random.Random(21)
+    axes = ["m", "lane", "reg", "gpuid"]
+    for trial in range(40):
+        D = tuple(Iter(rng.randint(1, 7), rng.choice([1, 2, 3, 5, 8, 64, -4, -1, 1000003]), rng.choice(axes))
+                  for _ in range(rng.randint(1, 6)))
+        Rr = tuple(Iter(rng.randint(1, 3), rng.choice([1, 7, -2, 4096]), rng.choice(axes)) for _ in range(rng.randint(0, 2)))
+        O = {a: rng.randint(-9, 9) for a in axes if rng.random() < 0.5}
+        L = Layout(D, Rr, ax._norm_offset(O))
+        if trial % 3 == 0:
+            lo = int(R.evaluate_np(L, np.arange(L.E_D), L.axes())[:, :, L.axes().index(D[0].axis)].min())
+            L = L.with_(O={**L.offset, D[0].axis: L.offset.get(D[0].axis, 0) - min(lo, 0)}, swizzle=Swizzle(D[0].axis, 2, 1, 4))
+        got, want = eval_both(L, (L.E_D,))
+        assert np.array_equal(got, want), repr(L)
+        idx = [rng.randrange(L.E_D) for _ in range(17)]
+        got, want = eval_both(L, (L.E_D,), idx)
+        assert np.array_equal(got, want)
+    # out-of-range explicit indices give INT64_MIN, in-range neighbours are unaffected
+    L = Layout.make((4, 4), (4, 1))
+    bl = B.Layout(spec_of(L))
+    idx = torch.tensor([3, 16, -1, 15], dtype=torch.int64).cuda()
+    got = B.axe_layout_eval(bl, (4, 4), 4, idx).cpu().numpy().reshape(-1)
+    assert list(got) == [3, np.iinfo(np.int64).min, np.iinfo(np.int64).min, 15]
+
+
+def test_eval_large_blocked_swizzled_layout():
+    # the config-2 destination at full size: 2^26 points, compared on a strided sample plus both ends,
+    # and as a permutation (every address exactly once) on the device result
+    rows = cols = 8192
+    L = Layout.from_spec(W.blocked_swizzled_spec(rows, cols))
+    bl = B.Layout(W.blocked_swizzled_spec(rows, cols))
+    n = rows * cols
+    got = B.axe_layout_eval(bl, (rows, cols), n)
+    sample = np.concatenate([np.arange(0, 70000), np.arange(0, n, 9973), np.arange(n - 70000, n)])
+    want = R.evaluate_np(L, sample, ["m"])[:, 0, 0]
+    assert np.array_equal(got.reshape(-1)[torch.from_numpy(sample).cuda()].cpu().numpy(), want)
+    srt = torch.sort(got.reshape(-1)).values
+    assert bool((srt == torch.arange(n, device="cuda")).all())
+    # a layout whose E_D exceeds 2^31 takes the 64-bit digit path
+    big = Layout.make((1 << 20, 1 << 13), (1 << 13, 1))
+    idx = np.array([0, 1, (1 << 33) - 1, (1 << 32) + 12345, 123456789012 % (1 << 33)], dtype=np.int64)
+    g2 = B.axe_layout_eval(B.Layout(spec_of(big)), (1 << 20, 1 << 13), len(idx), torch.from_numpy(idx).cuda()).cpu().numpy()
+    assert np.array_equal(g2, R.evaluate_np(big, idx, ["m"]))
+
+
+# ----------------------------------------------------------------------------- relayout
+def relayout_both(src_L: Layout, dst_L: Layout, shape, src_words: np.ndarray, dst_len: int, fill=0xA5):
+    want = np.zeros(dst_len, dtype=src_words.dtype)
+    want.view(np.uint8)[:] = fill
+    R.relayout_ref(src_L, dst_L, shape, src_words, want)
+    d_dst = torch.full((dst_len * src_words.dtype.itemsize,), fill, dtype=torch.uint8).cuda()
+    d_src = dev(src_words.view(np.uint8))
+    B.axe_relayout(B.Layout(spec_of(src_L), ["m", "gpuid"]), B.Layout(spec_of(dst_L), ["m", "gpuid"]), shape, d_src, d_dst,
+                   elem_bytes=src_words.dtype.itemsize)
+    got = d_dst.cpu().numpy().view(src_words.dtype)
+    return got, want
+
+
+@pytest.mark.parametrize("rows,cols", [(128, 64), (256, 192), (1152, 704)])
+def test_relayout_blocked_swizzled_small(rows, cols):
+    words = W.relayout_words(rows, cols, 31, "index").reshape(-1)
+    src_L = Layout.from_spec(W.row_major_spec(rows, cols))
+    dst_L = Layout.from_spec(W.blocked_swizzled_spec(rows, cols))
+    got, want = relayout_both(src_L, dst_L, (rows, cols), words, rows * cols)
+    assert np.array_equal(got, want)
+    back, want_back = relayout_both(dst_L, src_L, (rows, cols), got, rows * cols)
+    assert np.array_equal(back, want_back) and np.array_equal(back, words)
+
+
+@pytest.mark.parametrize("eb", [1, 2, 4, 8, 16])
+def test_relayout_element_sizes_transposes_and_ragged(eb):
+    rng = np.random.default_rng(eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64, 16: np.dtype((np.void, 16))}[eb]
+    for shape in ((24, 24), (37, 53), (6, 4, 5), (96, 40), (3, 128, 7)):
+        n = prod(shape)
+        src = rng.integers(0, 256, n * eb, dtype=np.uint8).view(dt)
+        A = ax.row_major(shape)
+        strides_f = [prod(shape[:i]) for i in range(len(shape))]
+        Bf = Layout.make(shape, strides_f)                                  # column-major
+        for s_L, d_L in ((A, Bf), (Bf, A), (A, A)):
+            got, want = relayout_both(s_L, d_L, shape, src, n)
+            assert got.tobytes() == want.tobytes(), (shape, eb)
+    # destination with a pitch, an offset and two replicas; untouched words keep the fill pattern
+    shape = (10, 12)
+    src = rng.integers(0, 256, 120 * eb, dtype=np.uint8).view(dt)
+    D = Layout.make(shape, (16, 1), R=((2,), (200,)), O={"m": 5})
+    got, want = relayout_both(ax.row_major(shape), D, shape, src, 400)
+    assert got.tobytes() == want.tobytes()
+    # negative stride (reversed rows) with the offset that keeps addresses non-negative
+    Rv = Layout.make(shape, (-12, 1), O={"m": 108})
+    got, want = relayout_both(ax.row_major(shape), Rv, shape, src, 120)
+    assert got.tobytes() == want.tobytes()
+
+
+def test_relayout_without_common_refinement_uses_generic_path():
+    # source digits (6, 4), destination digits (4, 6) over the same 24 elements: no joint loop nest
+    rng = np.random.default_rng(3)
+    src = rng.integers(0, 2 ** 16, 24, dtype=np.uint16)
+    s_L = Layout.make((6, 4), (1, 6))
+    d_L = Layout.make((4, 6), (1, 4))
+    got, want = relayout_both(s_L, d_L, (24,), src, 24)
+    assert np.array_equal(got, want)
+    s_L = Layout.make((9, 10), (10, 1))
+    d_L = Layout.make((6, 15), (1, 6))
+    src = rng.integers(0, 2 ** 16, 90, dtype=np.uint16)
+    got, want = relayout_both(s_L, d_L, (90,), src, 90)
+    assert np.array_equal(got, want)
+
+
+def test_relayout_composition():
+    rng = np.random.default_rng(4)
+    shape = (64, 48)
+    src = rng.integers(0, 2 ** 32, prod(shape), dtype=np.uint32)
+    A, Bc = ax.row_major(shape), Layout.make(shape, (1, 64))
+    Cb, _ = ax.tile(ax.row_major((4, 3)), (4, 3), ax.row_major((16, 16)), (16, 16))
+    ab, _ = relayout_both(A, Bc, shape, src, prod(shape))
+    bc, _ = relayout_both(Bc, Cb, shape, ab, prod(shape))
+    ac, want = relayout_both(A, Cb, shape, src, prod(shape))
+    assert np.array_equal(bc, ac) and np.array_equal(ac, want)
+
+
+@pytest.mark.parametrize("kind", ["uniform", "index"])
+def test_relayout_config2_full_size(kind):
+    rows = cols = 8192
+    words = W.config2(kind).reshape(-1)
+    src_spec, dst_spec = W.row_major_spec(rows, cols), W.blocked_swizzled_spec(rows, cols)
+    d_src = dev(words)
+    d_dst = torch.zeros(rows * cols, dtype=torch.int16, device="cuda")
+    Ls, Ld = B.Layout(src_spec), B.Layout(dst_spec)
+    B.axe_relayout(Ls, Ld, (rows, cols), d_src, d_dst)
+    got = host_words(d_dst, np.uint16)
+    want = np.zeros(rows * cols, dtype=np.uint16)
+    R.relayout_ref(Layout.from_spec(src_spec), Layout.from_spec(dst_spec), (rows, cols), words, want)
+    assert np.array_equal(got, want)
+    d_back = torch.zeros(rows * cols, dtype=torch.int16, device="cuda")
+    B.axe_relayout(Ld, Ls, (rows, cols), d_dst, d_back)
+    assert np.array_equal(host_words(d_back, np.uint16), words)          # bit-exact round trip
+
+
+# ----------------------------------------------------------------------------- GEMM
+def run_gemm(g: W.GemmInputs, tile=B.AXE_TILE_AUTO, device_axis=False, lda=None, ldb=None, ldc=None):
+    """Launches axe_gemm on the inputs; returns C decoded to fp64 (M, N)."""
+    As, Bs, Cs = W.gemm_specs(g, device_axis=device_axis, shard=3)
+    a, b = g.a_mk, g.b_nk
+    if lda:
+        As = W.spec([(g.M, lda, "m"), (g.K, 1, "m")])
+        a = np.zeros((g.M, lda), dtype=a.dtype); a[:, :g.K] = g.a_mk
+    if ldb:
+        Bs = W.spec([(g.K, 1, "m"), (g.N, ldb, "m")])
+        b = np.zeros((g.N, ldb), dtype=b.dtype); b[:, :g.K] = g.b_nk
+    ldc_ = ldc or g.N
+    if ldc:
+        Cs = W.spec([(g.M, ldc, "m"), (g.N, 1, "m")])
+    axes = ["m", "gpuid"]
+    dA, dB = dev(a.reshape(-1)), dev(b.reshape(-1))
+    out_t = torch.float32 if g.out_dtype == "f32" else torch.int16
+    dC = torch.zeros(g.M * ldc_, dtype=out_t, device="cuda")
+    sa = torch.from_numpy(g.scale_a).cuda() if g.scale_a is not None else None
+    sb = torch.from_numpy(g.scale_b).cuda() if g.scale_b is not None else None
+    desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16 if g.dtype == "bf16" else B.AXE_FP8_E4M3,
+                      B.AXE_F32 if g.out_dtype == "f32" else B.AXE_BF16,
+                      B.Layout(As, axes), B.Layout(Bs, axes), B.Layout(Cs, axes),
+                      a.size, b.size, g.M * ldc_, sa, sb, tile_hint=tile)
+    B.axe_gemm(desc, dA, dB, dC)
+    torch.cuda.synchronize()
+    c = dC.cpu().numpy().reshape(g.M, ldc_)[:, :g.N]
+    return c.astype(np.float64) if g.out_dtype == "f32" else R.bf16_to_f64(c.view(np.uint16))
+
+
+def oracle_gemm(g: W.GemmInputs, rows=None, cols=None):
+    dt = R.AXE_BF16 if g.dtype == "bf16" else R.AXE_FP8_E4M3
+    return R.gemm_ref(g.a_mk, g.b_nk.T, dt, g.scale_a, g.scale_b, rows=rows, cols=cols)
+
+
+def check_gemm(c, ref, tol, tile=128):
+    assert np.isfinite(c).all()
+    err = R.rel_frobenius(c, ref)
+    assert err <= tol, f"global relative Frobenius error {err:.3e} > {tol}"
+    M, N = ref.shape
+    worst = 0.0
+    for i in range(0, M, tile):
+        for j in range(0, N, tile):
+            worst = max(worst, R.rel_frobenius(c[i:i + tile, j:j + tile], ref[i:i + tile, j:j + tile]))
+    assert worst <= tol, f"worst {tile}x{tile} tile error {worst:.3e} > {tol}"
+    return err
+
+
+def test_gemm_config1_bf16_256_fp32_out():
+    g = W.config1()
+    c = run_gemm(g)
+    err = check_gemm(c, oracle_gemm(g), BF16_TOL)
+    assert err < 1e-5            # fp32 output: only accumulation order differs from the fp64 sum
+
+
+@pytest.mark.parametrize("M,N,K", [(64, 64, 32), (200, 136, 96), (65, 63, 8), (1, 1, 8), (300, 70, 520)])
+@pytest.mark.parametrize("out", ["f32", "bf16"])
+def test_gemm_bf16_small_tile_ragged(M, N, K, out):
+    g = W.gemm_bf16(M, N, K, 40 + M, out_dtype=out)
+    c = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+    check_gemm(c, oracle_gemm(g), BF16_TOL, tile=64)
+
+
+def test_gemm_identity_and_pitched_operands():
+    K = N = 128
+    g = W.gemm_bf16(K, N, K, 50, out_dtype="f32")
+    g.a_mk = W.to_bf16_bits(np.eye(K, dtype=np.float32))
+    c = run_gemm(g, lda=K + 24, ldb=K + 8, ldc=N + 4)
+    assert np.array_equal(c, R.bf16_to_f64(g.b_nk).T)       # A = I returns B exactly
+
+
+def test_gemm_device_axis_of_extent_one():
+    g = W.config4(128, 192, 256)
+    g.out_dtype = "f32"
+    c = run_gemm(g, device_axis=True)
+    check_gemm(c, oracle_gemm(g), BF16_TOL, tile=64)
+
+
+@pytest.mark.parametrize("M,N,K,scaled", [(128, 128, 128, False), (128, 256, 384, True), (200, 72, 272, True),
+                                          (64, 64, 16, False)])
+def test_gemm_fp8_small_tile(M, N, K, scaled):
+    g = W.gemm_fp8(M, N, K, 60 + K, scaled=scaled)
+    c = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+    check_gemm(c, oracle_gemm(g), FP8_TOL, tile=64)
+    g.out_dtype = "f32"
+    c = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+    err = check_gemm(c, oracle_gemm(g), FP8_TOL, tile=64)
+    assert err < 1e-5            # e4m3 products are exact in fp32; only the summation order differs

@@ -1,0 +1,158 @@
+"""Host logic without a GPU: the plans axe_layout_eval / axe_relayout build (canonicalisation,
+common refinement, vector width, loop order, unroll digit) are executed by host-memory stand-ins
+of the integer kernels (libaxe_hostcheck.so) that refuse any address outside the declared
+buffers; results must equal the oracle bit for bit.  This is what is checked before a plan is
+ever run on the GPU."""
+import ctypes as C
+import os
+import random
+from math import prod
+
+import numpy as np
+import pytest
+
+from oracle import axe_layout as ax
+from oracle import axe_ref as R
+from oracle.axe_layout import Iter, Layout, Swizzle
+from paper_2601_19092_amd import binding as B
+from paper_2601_19092_amd import workloads as W
+
+HOSTCHECK = os.path.join(os.path.dirname(B.LIB_PATH), "libaxe_hostcheck.so")
+
+
+@pytest.fixture(scope="module")
+def hc():
+    if not os.path.exists(HOSTCHECK):
+        from paper_2601_19092_amd.build import build_hostcheck
+        build_hostcheck()
+    L = C.CDLL(HOSTCHECK)
+    LP = C.POINTER(B.axe_layout_t)
+    L.axe_layout_eval.argtypes = [LP, C.c_int32, C.POINTER(C.c_int64), C.c_int64, C.c_void_p, C.c_void_p, C.c_void_p]
+    L.axe_relayout.argtypes = [LP, LP, C.c_int32, C.POINTER(C.c_int64), C.c_int32, C.c_int32, C.c_void_p, C.c_int64,
+                               C.c_void_p, C.c_int64, C.c_void_p]
+    L.axe_hostcheck_set_buffers.argtypes = [C.c_int64, C.c_int64]
+    L.axe_last_error.restype = C.c_char_p
+    return L
+
+
+def spec_of(L: Layout) -> dict:
+    z = L.swizzle
+    return W.spec([(i.extent, i.stride, i.axis) for i in L.D], [(i.extent, i.stride, i.axis) for i in L.R],
+                  dict(L.O), (z.axis, z.bits, z.base, z.shift) if z else None)
+
+
+def host_relayout(hc, src_L, dst_L, shape, src, dst_len, fill=0xA5, env=None):
+    eb = src.dtype.itemsize
+    dst = np.zeros(dst_len, dtype=src.dtype)
+    dst.view(np.uint8)[:] = fill
+    want = dst.copy()
+    R.relayout_ref(src_L, dst_L, shape, src, want)
+    ls, ld = B.Layout(spec_of(src_L), ["m", "gpuid"]), B.Layout(spec_of(dst_L), ["m", "gpuid"])
+    shp = (C.c_int64 * len(shape))(*shape)
+    hc.axe_hostcheck_set_buffers(src.nbytes, dst.nbytes)
+    old = {}
+    for k, v in (env or {}).items():
+        old[k] = os.environ.get(k)
+        os.environ[k] = str(v)
+    try:
+        rc = hc.axe_relayout(C.byref(ls.c), C.byref(ld.c), len(shape), shp, eb, 0, src.ctypes.data, src.size,
+                             dst.ctypes.data, dst.size, None)
+    finally:
+        for k, v in old.items():
+            if v is None:
+                del os.environ[k]
+            else:
+                os.environ[k] = v
+    assert rc == 0, hc.axe_last_error().decode()
+    assert hc.axe_hostcheck_violations() == 0
+    return dst, want
+
+
+@pytest.mark.parametrize("rows,cols", [(128, 64), (256, 192), (1152, 704)])
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+def test_plan_blocked_swizzled(hc, rows, cols, unroll):
+    words = W.relayout_words(rows, cols, 31, "index").reshape(-1)
+    src_L = Layout.from_spec(W.row_major_spec(rows, cols))
+    dst_L = Layout.from_spec(W.blocked_swizzled_spec(rows, cols))
+    got, want = host_relayout(hc, src_L, dst_L, (rows, cols), words, rows * cols, env={"AXE_RELAYOUT_UNROLL": unroll})
+    assert np.array_equal(got, want)
+    back, wb = host_relayout(hc, dst_L, src_L, (rows, cols), got, rows * cols, env={"AXE_RELAYOUT_UNROLL": unroll})
+    assert np.array_equal(back, wb) and np.array_equal(back, words)
+
+
+@pytest.mark.parametrize("eb", [1, 2, 4, 8, 16])
+def test_plan_element_sizes_transposes_replicas(hc, eb):
+    rng = np.random.default_rng(eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64, 16: np.dtype((np.void, 16))}[eb]
+    for shape in ((24, 24), (37, 53), (6, 4, 5), (96, 40), (3, 128, 7), (1,), (1, 1), (16,)):
+        n = prod(shape)
+        src = rng.integers(0, 256, n * eb, dtype=np.uint8).view(dt)
+        A = ax.row_major(shape)
+        Bf = Layout.make(shape, [prod(shape[:i]) for i in range(len(shape))])
+        for s_L, d_L in ((A, Bf), (Bf, A), (A, A)):
+            got, want = host_relayout(hc, s_L, d_L, shape, src, n)
+            assert got.tobytes() == want.tobytes(), (shape, eb)
+    shape = (10, 12)
+    src = rng.integers(0, 256, 120 * eb, dtype=np.uint8).view(dt)
+    D = Layout.make(shape, (16, 1), R=((2,), (200,)), O={"m": 5})
+    got, want = host_relayout(hc, ax.row_major(shape), D, shape, src, 400)
+    assert got.tobytes() == want.tobytes()
+    D8 = Layout.make(shape, (16, 1), R=((2, 2), (200, 400)), O={"m": 8})
+    got, want = host_relayout(hc, ax.row_major(shape), D8, shape, src, 808)
+    assert got.tobytes() == want.tobytes()
+    Rv = Layout.make(shape, (-12, 1), O={"m": 108})
+    got, want = host_relayout(hc, ax.row_major(shape), Rv, shape, src, 120)
+    assert got.tobytes() == want.tobytes()
+
+
+def test_plan_random_layout_pairs(hc):
+    """Random pairs of injective layouts over the same element count: permuted / split /
+    padded strides on both sides, with and without swizzles; joint and generic paths."""
+    rng = random.Random(77)
+    done = 0
+    while done < 150:
+        # random mixed-radix factorisation for each side, random nesting order of strides
+        E = rng.choice([24, 36, 48, 64, 96, 120, 128, 256, 360, 512])
+        def rand_layout():
+            ext, rest = [], E
+            while rest > 1 and len(ext) < 5:
+                f = rng.choice([d for d in range(2, rest + 1) if rest % d == 0])
+                ext.append(f)
+                rest //= f
+            order = list(range(len(ext)))
+            rng.shuffle(order)
+            strides, acc = [0] * len(ext), 1
+            pad = rng.choice([0, 0, 1, 8])
+            for k in order:
+                strides[k] = acc
+                acc = acc * ext[k] + (pad if rng.random() < 0.3 else 0)
+            size = sum((e - 1) * s for e, s in zip(ext, strides)) + 1
+            L = Layout(tuple(Iter(e, s, "m") for e, s in zip(ext, strides)))
+            if rng.random() < 0.3:
+                bits, base = rng.choice([(1, 0), (2, 1), (3, 3)])
+                shift = base + bits + rng.randint(0, 2)
+                L = L.with_(swizzle=Swizzle("m", bits, base, shift))
+                size = ((size - 1) | ((1 << (bits + base)) - 1)) + 1
+            return L, size
+        (s_L, s_size), (d_L, d_size) = rand_layout(), rand_layout()
+        if not s_L.D or not d_L.D:
+            continue
+        src = np.array([rng.randrange(65536) for _ in range(s_size)], dtype=np.uint16)
+        got, want = host_relayout(hc, s_L, d_L, (E,), src, d_size)
+        assert np.array_equal(got, want), (s_L, d_L)
+        done += 1
+
+
+def test_plan_eval_matches_oracle(hc):
+    rng = random.Random(5)
+    axes = ["m", "lane", "reg", "gpuid"]
+    for _ in range(60):
+        D = tuple(Iter(rng.randint(1, 6), rng.choice([1, 2, 3, 8, -4, 1000003]), rng.choice(axes)) for _ in range(rng.randint(1, 6)))
+        Rr = tuple(Iter(rng.randint(1, 3), rng.choice([1, 7, -2]), rng.choice(axes)) for _ in range(rng.randint(0, 2)))
+        L = Layout(D, Rr, ax._norm_offset({a: rng.randint(-3, 3) for a in axes if rng.random() < 0.5}))
+        bl = B.Layout(spec_of(L), L.axes())
+        n = L.E_D
+        out = np.zeros((n, L.E_R, len(L.axes())), dtype=np.int64)
+        shp = (C.c_int64 * 1)(n)
+        assert hc.axe_layout_eval(C.byref(bl.c), 1, shp, n, None, out.ctypes.data, None) == 0
+        assert np.array_equal(out, R.evaluate_np(L, np.arange(n), L.axes()))
