@@ -1,0 +1,222 @@
+#!/usr/bin/env python3
+"""Benchmark of the Axe-layout hot path on one MI355X.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W]
+
+A step is one pass of the GEMM hot path (host layout analysis, HBM -> LDS -> VGPR -> MFMA -> HBM)
+over one batch of synthetic input: the bf16 GEMM M = N = K = 8192 (configuration 3), inputs
+resident in HBM, rotating over two buffer sets.  The headline value is its whole-job TFLOP/s.
+The same JSON line carries, under "companions", the other configurations measured in the same
+run (relayout GB/s, fp8 GEMM, the tensor-parallel shard, the 256^3 GEMM, layout evaluation),
+the roofline of the dominant kernel and the CPU oracle timed on a bounded sample.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+PEAK = {"bf16": 2516.6, "fp8": 5033.2, "hbm": 8000.0}     # TFLOP/s, TFLOP/s, GB/s (MI355X, dense)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def time_loop(fn, steps, warmup):
+    """Returns (wall ms per step, device ms per step from HIP events on the launch stream)."""
+    import torch
+    for i in range(warmup):
+        fn(i)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record()
+    for i in range(steps):
+        fn(i)
+    ev1.record()
+    torch.cuda.synchronize()
+    wall = (time.perf_counter() - t0) * 1e3 / steps
+    return wall, ev0.elapsed_time(ev1) / steps
+
+
+def dev(a):
+    import torch
+    a = np.ascontiguousarray(a)
+    view = {1: np.uint8, 2: np.int16, 4: np.int32}[a.dtype.itemsize]
+    return torch.from_numpy(a.view(view)).cuda()
+
+
+def gemm_setup(g, n_sets, device_axis=False, tile=0):
+    import torch
+    from paper_2601_19092_amd import binding as B
+    from paper_2601_19092_amd import workloads as W
+    As, Bs, Cs = W.gemm_specs(g, device_axis=device_axis, shard=3)
+    axes = ["m", "gpuid"]
+    out_t = torch.float32 if g.out_dtype == "f32" else torch.int16
+    sets = []
+    for s in range(n_sets):
+        dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_nk.reshape(-1))
+        if s:                       # other sets: same statistics, different bits (rotated rows)
+            dA, dB = torch.roll(dA, 4096 * s), torch.roll(dB, 4096 * s)
+        dC = torch.zeros(g.M * g.N, dtype=out_t, device="cuda")
+        sets.append((dA, dB, dC))
+    sa = torch.from_numpy(g.scale_a).cuda() if g.scale_a is not None else None
+    sb = torch.from_numpy(g.scale_b).cuda() if g.scale_b is not None else None
+    desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16 if g.dtype == "bf16" else B.AXE_FP8_E4M3,
+                      B.AXE_F32 if g.out_dtype == "f32" else B.AXE_BF16,
+                      B.Layout(As, axes), B.Layout(Bs, axes), B.Layout(Cs, axes),
+                      g.M * g.K, g.N * g.K, g.M * g.N, sa, sb, tile_hint=tile)
+    def step(i):
+        dA, dB, dC = sets[i % n_sets]
+        B.axe_gemm(desc, dA, dB, dC)
+    return step, sets, desc
+
+
+def bench_gemm(name, g, steps, warmup, n_sets=2, device_axis=False):
+    step, sets, desc = gemm_setup(g, n_sets, device_axis)
+    wall, devms = time_loop(step, steps, warmup)
+    flops = 2.0 * g.M * g.N * g.K
+    r = {"workload": name, "ms_per_step": wall, "kernel_ms": devms, "tflops": flops / (wall * 1e-3) / 1e12,
+         "kernel_tflops": flops / (devms * 1e-3) / 1e12}
+    r["frac_of_peak"] = r["kernel_tflops"] / PEAK["fp8" if g.dtype == "fp8" else "bf16"]
+    log(f"[bench] {name}: {wall:.4f} ms/step wall, {devms:.4f} ms device, {r['kernel_tflops']:.1f} TFLOP/s "
+        f"({100 * r['frac_of_peak']:.1f}% of peak)")
+    return r, sets
+
+
+def bench_relayout(steps, warmup, n_pairs=4):
+    import torch
+    from paper_2601_19092_amd import binding as B
+    from paper_2601_19092_amd import workloads as W
+    rows = cols = 8192
+    words = W.config2("uniform")
+    Ls, Ld = B.Layout(W.row_major_spec(rows, cols)), B.Layout(W.blocked_swizzled_spec(rows, cols))
+    pairs = []
+    for p in range(n_pairs):
+        src = dev(words.reshape(-1))
+        if p:
+            src = torch.roll(src, 777 * p)
+        pairs.append((src, torch.zeros(rows * cols, dtype=torch.int16, device="cuda")))
+    nbytes = 2.0 * rows * cols * 2          # read + write
+    out = {}
+    for label, np_ in (("rotating", n_pairs), ("single_pair", 1)):
+        def step(i, np_=np_):
+            s, d = pairs[i % np_]
+            B.axe_relayout(Ls, Ld, (rows, cols), s, d)
+        wall, devms = time_loop(step, steps, warmup)
+        out[label] = {"ms_per_step": wall, "kernel_ms": devms, "GBps": nbytes / (devms * 1e-3) / 1e9}
+    def back(i):
+        s, d = pairs[i % n_pairs]
+        B.axe_relayout(Ld, Ls, (rows, cols), d, s)
+    wall, devms = time_loop(back, steps, warmup)
+    out["inverse_rotating"] = {"ms_per_step": wall, "kernel_ms": devms, "GBps": nbytes / (devms * 1e-3) / 1e9}
+    out["frac_of_hbm_peak"] = out["rotating"]["GBps"] / PEAK["hbm"]
+    log(f"[bench] relayout 8192^2 bf16 -> 128x64 swizzled tiles: {out['rotating']['GBps']:.0f} GB/s rotating "
+        f"({100 * out['frac_of_hbm_peak']:.1f}% of HBM peak), {out['single_pair']['GBps']:.0f} GB/s single pair, "
+        f"inverse {out['inverse_rotating']['GBps']:.0f} GB/s")
+    return out
+
+
+def bench_eval(steps, warmup):
+    import torch
+    from paper_2601_19092_amd import binding as B
+    from paper_2601_19092_amd import workloads as W
+    rows = cols = 8192
+    L = B.Layout(W.blocked_swizzled_spec(rows, cols))
+    n = rows * cols
+    out = torch.empty((n, 1, 1), dtype=torch.int64, device="cuda")
+    wall, devms = time_loop(lambda i: B.axe_layout_eval(L, (rows, cols), n, None, out), steps, warmup)
+    r = {"points": n, "kernel_ms": devms, "Gpoints_per_s": n / (devms * 1e-3) / 1e9, "GBps_written": n * 8 / (devms * 1e-3) / 1e9}
+    log(f"[bench] layout eval 2^26 points: {devms:.4f} ms, {r['Gpoints_per_s']:.1f} Gpoint/s")
+    return r
+
+
+def cpu_baseline(g, budget_rows=512):
+    """The CPU oracle as it stands, on the first `budget_rows` rows of the same GEMM."""
+    from oracle import axe_ref as R
+    rows = np.arange(budget_rows)
+    R.gemm_ref(g.a_mk[:2], g.b_nk.T[:, :2], R.AXE_BF16)        # builds / loads the C oracle outside the timing
+    t0 = time.perf_counter()
+    R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_BF16, rows=rows)
+    dt = time.perf_counter() - t0
+    fl = 2.0 * budget_rows * g.N * g.K
+    return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": R.oracle_threads(), "kind": "oracle",
+            "sample": f"rows 0..{budget_rows - 1} of C (all {g.N} columns, K = {g.K}) of the same bf16 GEMM, "
+                      f"plain fp64 triple loop, {dt:.1f} s"}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--only", default="", help="comma list of: gemm,relayout,fp8,shard,small,eval,cpu (default all)")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding across GPUs); use --gpus 1")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    from paper_2601_19092_amd import binding as B
+    from paper_2601_19092_amd import workloads as W
+    B.lib()                                                  # fails loudly if the HIP library is missing
+    only = set(filter(None, args.only.split(",")))
+    want = lambda k: not only or k in only
+
+    log("[bench] generating configuration 3 (bf16 GEMM 8192^3) on the host ...")
+    g3 = W.config3()
+    head, _ = bench_gemm("bf16 GEMM M=N=K=8192, A row-major, B column-major, bf16 out", g3, args.steps, args.warmup)
+    comp = {}
+    if want("relayout"):
+        comp["relayout_cfg2"] = bench_relayout(max(20, args.steps), args.warmup)
+    if want("shard"):
+        comp["gemm_cfg4_tp_shard"], _ = bench_gemm("bf16 GEMM M=4096 K=8192 N=3584 (1 of 8 shards)", W.config4(),
+                                                   args.steps, args.warmup, device_axis=True)
+    if want("fp8"):
+        comp["gemm_cfg5_fp8_block_scaled"], _ = bench_gemm("fp8 e4m3 GEMM 8192^3, fp32 128x128 block scales", W.config5(),
+                                                           max(10, args.steps // 2), args.warmup)
+    if want("small"):
+        comp["gemm_cfg1_256"], _ = bench_gemm("bf16 GEMM 256^3, fp32 out, 64x64x32 tiles", W.config1(),
+                                              max(200, args.steps), max(200, args.warmup), n_sets=1)
+    if want("eval"):
+        comp["layout_eval"] = bench_eval(20, 5)
+    cpu = None
+    if not args.no_cpu and want("cpu"):
+        log("[bench] timing the CPU oracle on a bounded sample ...")
+        cpu = cpu_baseline(g3)
+        log(f"[bench] cpu oracle: {cpu['value'] * 1e3:.2f} GFLOP/s on {cpu['cores']} threads")
+
+    flops = 2.0 * g3.M * g3.N * g3.K
+    line = {
+        "metric": "GEMM TFLOP/s + % MFMA peak; relayout GB/s + % HBM peak (1 GPU)",
+        "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "config 3: bf16 GEMM M=N=K=8192, A row-major, B column-major, N(0, K^-1/2) inputs, "
+                               "fp32 accumulate, bf16 output; 256x256x64 tiles described as Axe layouts"},
+        "roofline": {"bound": "mfma", "achieved": head["kernel_tflops"], "peak": PEAK["bf16"], "unit": "TFLOP/s",
+                     "frac": head["kernel_tflops"] / PEAK["bf16"], "traffic": None,
+                     "kernel": "gemm_256_kernel<bf16>", "flops_per_launch": flops, "kernel_ms": head["kernel_ms"]},
+        "cpu_baseline": cpu,
+        "companions": comp,
+    }
+    tr = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tr):
+        try:
+            line["roofline"]["traffic"] = json.load(open(tr)).get("gemm_256_kernel_bf16_bytes_per_launch")
+        except Exception:
+            pass
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -300,4 +300,95 @@ def test_gemm_fp8_small_tile(M, N, K, scaled):
     g.out_dtype = "f32"
     c = run_gemm(g, tile=B.AXE_TILE_64x64x32)
     err = check_gemm(c, oracle_gemm(g), FP8_TOL, tile=64)
-    assert err < 1e-5            # e4m3 products are exact in fp32; only the summation order differs
+    assert err < 1e-4            # fp32 output: only the accumulation inside the MFMA differs from the fp64 sum
+
+
+# ----------------------------------------------------------------------------- large tile (256 x 256)
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 256, 128), (512, 768, 192), (768, 256, 1024)])
+def test_gemm_bf16_large_tile(M, N, K):
+    g = W.gemm_bf16(M, N, K, 70 + K)
+    c = run_gemm(g, tile=B.AXE_TILE_256x256x64)
+    check_gemm(c, oracle_gemm(g), BF16_TOL)
+    # bf16 output of the large tile equals the small tile's up to the last rounding (different k order)
+    c_small = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+    assert R.rel_frobenius(c, c_small) < 2e-3
+
+
+def test_gemm_bf16_large_tile_identity_pitched_and_device_axis():
+    K = N = 256
+    g = W.gemm_bf16(K, N, K, 71)
+    g.a_mk = W.to_bf16_bits(np.eye(K, dtype=np.float32))
+    c = run_gemm(g, tile=B.AXE_TILE_256x256x64, lda=K + 64, ldb=K + 8, ldc=N + 8, device_axis=False)
+    assert np.array_equal(c, R.bf16_to_f64(g.b_nk).T)       # exact: bf16 values survive fp32 and the final rounding
+    g4 = W.config4(512, 256, 512)
+    c = run_gemm(g4, tile=B.AXE_TILE_256x256x64, device_axis=True)
+    check_gemm(c, oracle_gemm(g4), BF16_TOL)
+
+
+@pytest.mark.parametrize("M,N,K,scaled", [(256, 256, 128, False), (256, 512, 384, True), (512, 256, 256, True)])
+def test_gemm_fp8_large_tile(M, N, K, scaled):
+    g = W.gemm_fp8(M, N, K, 80 + K, scaled=scaled)
+    c = run_gemm(g, tile=B.AXE_TILE_256x256x64)
+    check_gemm(c, oracle_gemm(g), FP8_TOL)
+
+
+# ----------------------------------------------------------------------------- full-size configurations
+def full_size_check(g: W.GemmInputs, tol, device_axis=False, seed=0):
+    """Whole C on the GPU in the launch configuration the benchmark times; the oracle computes
+    sampled 128 x 128 tiles, two full rows, two full columns and scattered single elements one by
+    one; two randomised projections (C v and u^T C, computed in fp64 from the inputs) cover every
+    256-row and 256-column block of the full matrix."""
+    c = run_gemm(g, device_axis=device_axis)
+    assert np.isfinite(c).all()
+    rng = np.random.default_rng(seed)
+    M, N = g.M, g.N
+    tiles = {(0, 0), (M // 128 - 1, N // 128 - 1)}
+    while len(tiles) < 6:
+        tiles.add((int(rng.integers(M // 128)), int(rng.integers(N // 128))))
+    for ti, tj in sorted(tiles):
+        rows, cols = np.arange(ti * 128, ti * 128 + 128), np.arange(tj * 128, tj * 128 + 128)
+        ref = oracle_gemm(g, rows, cols)
+        err = R.rel_frobenius(c[np.ix_(rows, cols)], ref)
+        assert err <= tol, f"tile ({ti},{tj}): {err:.3e}"
+    rows = np.array([1, M - 2])
+    assert R.rel_frobenius(c[rows], oracle_gemm(g, rows, None)) <= tol
+    cols = np.array([0, N - 3])
+    assert R.rel_frobenius(c[:, cols], oracle_gemm(g, None, cols)) <= tol
+    for _ in range(256):
+        i, j = int(rng.integers(M)), int(rng.integers(N))
+        ref = oracle_gemm(g, np.array([i]), np.array([j]))[0, 0]
+        assert abs(c[i, j] - ref) <= 4 * tol * max(abs(ref), np.sqrt(np.mean(c[i] ** 2)))
+    # projections in fp64: C v = A (B v),  u^T C = (u^T A) B, block by block
+    dt = R.AXE_BF16 if g.dtype == "bf16" else R.AXE_FP8_E4M3
+    A, Bm = R.decode(g.a_mk, dt), R.decode(g.b_nk, dt)          # (M,K), (N,K)
+    v, u = rng.choice([-1.0, 1.0], N), rng.choice([-1.0, 1.0], M)
+    if g.scale_a is None:
+        y_ref, z_ref = A @ (Bm.T @ v), (u @ A) @ Bm.T
+    else:
+        y_ref, z_ref = np.zeros(M), np.zeros(N)
+        sa = np.repeat(g.scale_a.astype(np.float64), 128, axis=0)[:M]      # (M, nkb)
+        sb = np.repeat(g.scale_b.astype(np.float64), 128, axis=0)[:N]      # (N, nkb)
+        for kb in range(g.scale_a.shape[1]):
+            ks = slice(kb * 128, (kb + 1) * 128)
+            y_ref += sa[:, kb] * (A[:, ks] @ (Bm[:, ks].T @ (sb[:, kb] * v)))
+            z_ref += sb[:, kb] * (((u * sa[:, kb]) @ A[:, ks]) @ Bm[:, ks].T)
+    y, z = c @ v, u @ c
+    for blk in range(0, M, 256):
+        assert np.linalg.norm(y[blk:blk + 256] - y_ref[blk:blk + 256]) <= tol * np.linalg.norm(c[blk:blk + 256])
+    for blk in range(0, N, 256):
+        assert np.linalg.norm(z[blk:blk + 256] - z_ref[blk:blk + 256]) <= tol * np.linalg.norm(c[:, blk:blk + 256])
+    # (with random signs the rounding errors of a row add in quadrature, so the projection error of a
+    #  correct result is about the element-wise relative error times the block's Frobenius norm)
+    assert np.linalg.norm(y - y_ref) <= tol / 2 * np.linalg.norm(c)
+
+
+def test_gemm_config3_full_size():
+    full_size_check(W.config3(), BF16_TOL, seed=3)
+
+
+def test_gemm_config4_full_size_shard():
+    full_size_check(W.config4(), BF16_TOL, device_axis=True, seed=4)
+
+
+def test_gemm_config5_full_size_fp8_scaled():
+    full_size_check(W.config5(), FP8_TOL, seed=5)
