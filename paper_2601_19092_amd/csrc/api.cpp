@@ -415,7 +415,7 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   P.args.scale_b = g->d_scale_b;
   P.args.nkb = (int32_t)((g->K + 127) / 128);
   P.args.out_bf16 = g->out_dtype == AXE_BF16;
-  const int64_t bk = fp8 ? 128 : 64;
+  const int64_t bk = fp8 ? 128 : 32;
   const bool big_ok = (g->M % 256 == 0) && (g->N % 256 == 0) && (g->K % bk == 0) && (ldc % 8 == 0) &&
                       P.args.out_bf16;
   int tile = g->tile_hint;

@@ -1,0 +1,81 @@
+// Pieces shared by the large-tile GEMM kernels (device code only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "device_types.h"
+
+namespace axe {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+
+constexpr int kTile = 256;                        // workgroup tile edge (M and N)
+constexpr int kEpiPitch = 272;                    // bytes per accumulator row in the epilogue staging
+constexpr int kEpiB = 4 * 128 * kEpiPitch;        // 139264 bytes: 4 waves x 128 rows
+
+// Workgroup barrier without the memory fence of __syncthreads().  That fence waits for every
+// outstanding global load (vmcnt(0)), which would drain the load pipeline at each K step; the
+// kernels wait explicitly, with s_waitcnt, for exactly the loads and LDS reads a barrier publishes.
+__device__ __forceinline__ void wg_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+  bf16x2 v = {(__bf16)lo, (__bf16)hi};            // v_cvt_pk_bf16_f32, round to nearest even
+  return __builtin_bit_cast(uint32_t, v);
+}
+
+// Workgroup id -> (tile row, tile col).  Consecutive workgroup ids go to different XCDs (8 of
+// them, each with its own L2), so ids are first regrouped per XCD, then walked in column-major
+// groups of 8 tile rows so that the tiles resident on one XCD share A and B panels.
+__device__ __forceinline__ void tile_of_block(int bid, int nwg, int grid_m, int grid_n, int& tm, int& tn) {
+  int lin = bid;
+  if ((nwg & 7) == 0) lin = (bid & 7) * (nwg >> 3) + (bid >> 3);
+  const int GM = 8;
+  int per_group = GM * grid_n;
+  int group = lin / per_group;
+  int first_m = group * GM;
+  int gsz = grid_m - first_m < GM ? grid_m - first_m : GM;
+  int in_group = lin - group * per_group;
+  tm = first_m + in_group % gsz;
+  tn = in_group / gsz;
+}
+
+// Epilogue of a 256 x 256 tile held as 4 x 4 MFMA 32x32 accumulator fragments per wave (operands
+// swapped: lane l holds, for fragment (i, j) and a = 0..3, the 4 consecutive columns
+// j*32 + 8a + 4*(l/32) .. +3 of row i*32 + l%32).  Each wave converts to bf16, stages its 128 x 128
+// sub-tile in its own LDS region (row pitch 272 bytes) and writes it out with 16-byte stores, 256
+// contiguous bytes per row.  The caller guarantees that no wave still reads the pipeline stages.
+__device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[4][4], uint8_t* lds, int w, int lane, uint16_t* C,
+                                                int64_t ldc) {
+  const int fr = lane & 31, fh = lane >> 5;
+  uint8_t* ew = lds + w * 128 * kEpiPitch;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j)
+#pragma unroll
+      for (int a = 0; a < 4; ++a) {
+        uint2 v = {pack_bf16(acc[i][j][4 * a + 0], acc[i][j][4 * a + 1]),
+                   pack_bf16(acc[i][j][4 * a + 2], acc[i][j][4 * a + 3])};
+        *(uint2*)(ew + (i * 32 + fr) * kEpiPitch + (j * 32 + 8 * a + 4 * fh) * 2) = v;
+      }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+  const int er = lane >> 4, ec = lane & 15;
+#pragma unroll 4
+  for (int t = 0; t < 32; ++t) {
+    int row = t * 4 + er;
+    uint4 v = *(const uint4*)(ew + row * kEpiPitch + ec * 16);
+    *(uint4*)(C + (int64_t)row * ldc + ec * 8) = v;
+  }
+}
+
+}  // namespace axe

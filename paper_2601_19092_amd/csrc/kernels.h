@@ -12,7 +12,7 @@ hipError_t launch_relayout_generic(const GenericRelayoutPlan& p, int unit_bytes,
                                    hipStream_t s);
 hipError_t launch_gemm_small(const GemmArgs& g, bool fp8, hipStream_t s);
 // Large-tile kernels: 256 x 256 workgroup tile; require M % 256 == 0, N % 256 == 0 and K a
-// multiple of the K step (bf16: 64, fp8: 128).
+// multiple of the K step (bf16: 32, fp8: 128).
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_fp8_256(const GemmArgs& g, hipStream_t s);
 
