@@ -106,6 +106,9 @@ def bench_relayout(steps, warmup, n_pairs=4):
             src = torch.roll(src, 777 * p)
         pairs.append((src, torch.zeros(rows * cols, dtype=torch.int16, device="cuda")))
     nbytes = 2.0 * rows * cols * 2          # read + write
+    # one plain device copy of the same 128 MiB (untimed): the known-size kernel against which the
+    # FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script are calibrated
+    pairs[0][1].copy_(pairs[0][0])
     out = {}
     for label, np_ in (("rotating", n_pairs), ("single_pair", 1)):
         def step(i, np_=np_):

@@ -279,6 +279,9 @@ int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank,
   for (int k = 0; k < p.n_r; ++k) p.rext[k] = (int32_t)md.R[k].e, p.rstr[k] = md.R[k].s;
   p.E_R = md.E_R;
   p.threads = threads;
+  // non-temporal accesses once the data cannot stay in the 256 MiB last-level cache anyway
+  const int nt = env_int("AXE_RELAYOUT_NT", -1);
+  p.streaming = nt >= 0 ? nt : (2 * E * (int64_t)elem_bytes >= (int64_t(128) << 20));
   hipError_t e = launch_relayout_joint(p, unit, d_src, d_dst, st);
   return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_relayout");
 }

@@ -1,6 +1,240 @@
+// axe_gemm_describe: the Axe layouts (Defs. 2.1 - 2.3 of the paper, plus the swizzle stage) of every
+// tile movement of the kernel axe_gemm launches.  The layouts are composed the way Sec. 3.3 composes
+// tiles: register tile (x) lane (x) wave (x) workgroup.  Host only.
+//
+// Axes: 0 "m" (HBM), 1 "lds" (element address inside one LDS stage), 2 "wg" (row-major tile index),
+// 3 "wave", 4 "lane", 5 "reg" (element index inside the lane's fragment / per-thread loop).
+#include <string.h>
+
+#include <vector>
+
 #include "../../include/axe.h"
 #include "host_layout.h"
-extern "C" int axe_gemm_describe(const axe_gemm_desc_t*, int32_t, axe_layout_t*, int64_t*, int32_t*, void*, size_t) {
-  axe::set_error("axe_gemm_describe: not built yet");
-  return AXE_EUNSUPPORTED;
+
+namespace {
+
+enum Axis { M_ = 0, LDS = 1, WG = 2, WAVE = 3, LANE = 4, REG = 5, NAXES = 6 };
+const char* const kNames[NAXES] = {"m", "lds", "wg", "wave", "lane", "reg"};
+
+struct Builder {
+  std::vector<axe_iter_t> d, r;
+  int64_t off[NAXES] = {0};
+  int swz_axis = -1, bits = 0, base = 0, shift = 0;
+  std::vector<int64_t> shape;
+  void D(int64_t e, int64_t s, int axis) { d.push_back(axe_iter_t{e, s, axis}); }
+  void R(int64_t e, int64_t s, int axis) { r.push_back(axe_iter_t{e, s, axis}); }
+  void swz(int axis, int b, int ba, int sh) { swz_axis = axis, bits = b, base = ba, shift = sh; }
+};
+
+int ilog2(int64_t v) {
+  int l = 0;
+  while ((int64_t(1) << l) < v) ++l;
+  return l;
+}
+
+// Kernel geometry: workgroup tile T x T x BK elements, wave grid 2 x 2, MFMA fragment F x F,
+// LDS rows of ROWB bytes made of 16-byte chunks of CE elements.
+struct Geo {
+  bool big, fp8;
+  int T, BK, F, ROWB, CE, EB;
+  int key_shift;   // swizzle key = (row >> key_shift) & (chunks per row - 1)
+};
+
+Geo geometry(bool big, bool fp8) {
+  Geo g;
+  g.big = big;
+  g.fp8 = fp8;
+  g.EB = fp8 ? 1 : 2;
+  g.CE = 16 / g.EB;
+  if (big) {
+    g.T = 256;
+    g.F = 32;
+    g.ROWB = fp8 ? 128 : 64;
+  } else {
+    g.T = 64;
+    g.F = 16;
+    g.ROWB = fp8 ? 128 : 64;
+  }
+  g.BK = g.ROWB / g.EB;
+  g.key_shift = g.ROWB == 64 ? 2 : 1;
+  return g;
+}
+
+// (rows, k) tile of an operand: which thread fetches which element from HBM.
+int g2l_threads(const Geo& g, bool is_b, Builder& b) {
+  const int CH = g.ROWB / 16;                          // chunks per row
+  std::vector<axe_iter_t> rows, ks;
+  if (g.big) {
+    if (g.fp8) {
+      axe::set_error("axe_gemm_describe: the HBM -> LDS thread map of the fp8 256x256 kernel involves the wave id "
+                     "in its swizzle key and is not a single-axis swizzle");
+      return AXE_EUNSUPPORTED;
+    }
+    // one wave instruction = 1 KiB = RPI rows; wave w takes row groups w, w+4, ...: row = (4 i + w) * RPI + lr
+    const int RPI = 1024 / g.ROWB, NI = g.T / (4 * RPI);
+    rows = {{NI, g.CE, REG}, {4, 1, WAVE}, {RPI, CH, LANE}};
+    ks = {{CH, 1, LANE}, {g.CE, 1, REG}};
+    // the LDS side is linear in the lane id, so the chunk swizzle shows up on the lane axis:
+    // lane = CH * lr + (c ^ key(lr)), key(lr) = (lr >> key_shift) & (CH - 1)
+    b.swz(LANE, ilog2(CH), 0, ilog2(CH) + g.key_shift);
+  } else {
+    // thread t fetches chunk t (+ 256 p): row = 32 p' ..., see kernels_gemm_small.hip
+    const int PER = (64 * CH) / 256;                   // chunks per thread
+    const int RPW = 64 / CH;                           // rows per wave and pass
+    if (PER > 1) rows.push_back({PER, g.CE, REG});
+    rows.push_back({4, 1, WAVE});
+    rows.push_back({RPW, CH, LANE});
+    ks = {{CH, 1, LANE}, {g.CE, 1, REG}};
+  }
+  if (!is_b) {
+    for (auto& it : rows) b.d.push_back(it);
+    for (auto& it : ks) b.d.push_back(it);
+    b.shape = {g.T, g.BK};
+  } else {
+    for (auto& it : ks) b.d.push_back(it);
+    for (auto& it : rows) b.d.push_back(it);
+    b.shape = {g.BK, g.T};
+  }
+  return AXE_OK;
+}
+
+// (rows, k) tile -> element address inside one LDS stage (A region first, then B).
+int lds_layout(const Geo& g, bool is_b, Builder& b) {
+  const int CH = g.ROWB / 16;
+  if (!is_b) {
+    b.D(g.T, g.BK, LDS);
+    b.D(g.BK, 1, LDS);
+    b.shape = {g.T, g.BK};
+  } else {
+    b.D(g.BK, 1, LDS);
+    b.D(g.T, g.BK, LDS);
+    b.off[LDS] = (int64_t)g.T * g.BK;
+    b.shape = {g.BK, g.T};
+  }
+  // chunk index ^= (row >> key_shift) & (CH - 1), in element units
+  b.swz(LDS, ilog2(CH), ilog2(g.CE), ilog2(g.BK) + g.key_shift);
+  return AXE_OK;
+}
+
+// (rows, k) tile -> MFMA operand registers.  Waves form a 2 x 2 grid (wave = 2 wm + wn); A rows are
+// split over wm and replicated over wn, B rows the other way round.
+int operand_layout(const Geo& g, bool is_b, Builder& b) {
+  const int WT = g.T / 2, NF = WT / g.F;               // wave tile edge, fragments per wave tile edge
+  const int LG = 64 / g.F;                             // lane groups along k
+  const int KPL = g.fp8 ? 32 : 8;                      // k elements per lane per MFMA
+  const int KS = g.BK / (LG * KPL);                    // MFMA k sub-steps per LDS tile
+  std::vector<axe_iter_t> rows = {{2, is_b ? 1 : 2, WAVE}, {NF, KPL, REG}, {g.F, 1, LANE}};
+  std::vector<axe_iter_t> ks;
+  if (KS > 1) ks.push_back({KS, (int64_t)NF * KPL, REG});
+  ks.push_back({LG, g.F, LANE});
+  ks.push_back({KPL, 1, REG});
+  if (!is_b) {
+    for (auto& it : rows) b.d.push_back(it);
+    for (auto& it : ks) b.d.push_back(it);
+    b.shape = {g.T, g.BK};
+  } else {
+    for (auto& it : ks) b.d.push_back(it);
+    for (auto& it : rows) b.d.push_back(it);
+    b.shape = {g.BK, g.T};
+  }
+  b.R(2, is_b ? 2 : 1, WAVE);
+  return AXE_OK;
+}
+
+// (M, N) of the (tile-padded) problem -> wg, wave, lane, reg: the accumulators.  Operands are
+// swapped in the MFMA, so a lane owns, per fragment, groups of 4 consecutive columns of one row.
+int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Builder& b) {
+  const int WT = g.T / 2, NF = WT / g.F;
+  const int per_frag = g.F * g.F / 64;                 // accumulator registers per fragment
+  const int CG = g.F / (4 * (64 / g.F));               // groups of 4 columns per lane per fragment (32x32: 4, 16x16: 1)
+  if (!tile_only) b.D(grid_m, grid_n, WG);
+  b.D(2, 2, WAVE);
+  b.D(NF, (int64_t)NF * per_frag, REG);
+  b.D(g.F, 1, LANE);
+  if (!tile_only) b.D(grid_n, 1, WG);
+  b.D(2, 1, WAVE);
+  b.D(NF, per_frag, REG);
+  if (CG > 1) b.D(CG, 4, REG);
+  b.D(64 / g.F, g.F, LANE);
+  b.D(4, 1, REG);
+  if (tile_only) b.shape = {g.T, g.T};
+  else b.shape = {grid_m * g.T, grid_n * g.T};
+  return AXE_OK;
+}
+
+// (T, T) tile of C -> wave, lane, reg: who stores which element.  The large tile goes through LDS
+// and is written row by row (16 lanes x 16 bytes per row); the small tile stores accumulators directly.
+int c_store_layout(const Geo& g, Builder& b) {
+  if (!g.big) return acc_layout(g, 1, 1, true, b);
+  b.D(2, 2, WAVE);
+  b.D(32, 8, REG);
+  b.D(4, 16, LANE);
+  b.D(2, 1, WAVE);
+  b.D(16, 1, LANE);
+  b.D(8, 1, REG);
+  b.shape = {g.T, g.T};
+  return AXE_OK;
+}
+
+}  // namespace
+
+extern "C" int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_layout_t* out, int64_t* shape,
+                                 int32_t* rank, void* arena, size_t arena_bytes) {
+  if (!g || !out || !shape || !rank || !arena) {
+    axe::set_error("axe_gemm_describe: NULL argument");
+    return AXE_EINVAL;
+  }
+  int tile = axe_gemm_tile(g);
+  if (tile < 0) return tile;
+  const Geo geo = geometry(tile == AXE_TILE_256x256x64, g->in_dtype == AXE_FP8_E4M3);
+  Builder b;
+  int rc;
+  switch (which) {
+    case AXE_DESC_A_G2L_THREADS: rc = g2l_threads(geo, false, b); break;
+    case AXE_DESC_B_G2L_THREADS: rc = g2l_threads(geo, true, b); break;
+    case AXE_DESC_A_LDS: rc = lds_layout(geo, false, b); break;
+    case AXE_DESC_B_LDS: rc = lds_layout(geo, true, b); break;
+    case AXE_DESC_A_OPERAND: rc = operand_layout(geo, false, b); break;
+    case AXE_DESC_B_OPERAND: rc = operand_layout(geo, true, b); break;
+    case AXE_DESC_ACC:
+      rc = acc_layout(geo, (g->M + geo.T - 1) / geo.T, (g->N + geo.T - 1) / geo.T, false, b);
+      break;
+    case AXE_DESC_C_STORE: rc = c_store_layout(geo, b); break;
+    default:
+      axe::set_error("axe_gemm_describe: unknown selector %d", which);
+      return AXE_EINVAL;
+  }
+  if (rc) return rc;
+  // lay the result out in the caller's arena
+  const size_t need = sizeof(axe_iter_t) * (b.d.size() + b.r.size()) + sizeof(int64_t) * NAXES + sizeof(char*) * NAXES + 16;
+  if (arena_bytes < need || b.shape.size() > AXE_MAX_RANK) {
+    axe::set_error("axe_gemm_describe: arena of %zu bytes is too small (%zu needed)", arena_bytes, need);
+    return AXE_ERANGE;
+  }
+  char* p = (char*)arena;
+  p += (8 - ((uintptr_t)p & 7)) & 7;
+  axe_iter_t* d = (axe_iter_t*)p;
+  p += sizeof(axe_iter_t) * b.d.size();
+  axe_iter_t* r = (axe_iter_t*)p;
+  p += sizeof(axe_iter_t) * b.r.size();
+  int64_t* off = (int64_t*)p;
+  p += sizeof(int64_t) * NAXES;
+  const char** names = (const char**)p;
+  for (size_t i = 0; i < b.d.size(); ++i) d[i] = b.d[i];
+  for (size_t i = 0; i < b.r.size(); ++i) r[i] = b.r[i];
+  for (int a = 0; a < NAXES; ++a) off[a] = b.off[a], names[a] = kNames[a];
+  out->n_axes = NAXES;
+  out->axis_names = names;
+  out->n_d = (int32_t)b.d.size();
+  out->d = d;
+  out->n_r = (int32_t)b.r.size();
+  out->r = b.r.empty() ? nullptr : r;
+  out->offset = off;
+  out->swz_axis = b.swz_axis;
+  out->swz_bits = b.bits;
+  out->swz_base = b.base;
+  out->swz_shift = b.shift;
+  *rank = (int32_t)b.shape.size();
+  for (size_t i = 0; i < b.shape.size(); ++i) shape[i] = b.shape[i];
+  return AXE_OK;
 }

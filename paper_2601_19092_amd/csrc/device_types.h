@@ -44,6 +44,7 @@ struct RelayoutPlan {
   int64_t rstr[kMaxR];
   int64_t E_R;
   uint64_t threads;                // total work items = elements / (vector width * U)
+  int32_t streaming;               // 1: non-temporal loads and stores (data larger than the caches)
 };
 
 // Fallback when the two digit systems have no common refinement: decode each side separately.

@@ -5,7 +5,7 @@
 // Tile movements, each an Axe layout (reported by axe_gemm_describe):
 //   HBM -> LDS  : global_load_lds_dwordx4; one wave instruction fills 8 LDS rows of 128 bytes; the
 //                 XOR swizzle is applied on the global side: lane (r = lane / 8, p = lane % 8)
-//                 fetches chunk p ^ key(r) of row r, key(r) = (r & 7) ^ ((r >> 3) & 1).
+//                 fetches chunk p ^ key(r) of row r, key(r) = (r >> 1) & 7 (64 LDS banks: conflict-free).
 //   LDS layout  : two stages of 64 KiB, A tile then B tile, rows of 128 bytes (128 fp8).
 //   LDS -> VGPR : lane l reads row l % 32 of a fragment and the two adjacent 16-byte chunks
 //                 4 * ks + 2 * (l / 32) + {0, 1}: 32 consecutive k per lane, the operand layout
@@ -45,7 +45,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   // ---- HBM -> LDS: per wave and K step, 8 instructions for A and 8 for B; instruction i of wave w
   //      covers LDS rows (4 i + w) * 8 .. + 7
   const int lr = lane >> 3;                                   // row inside the 8-row group
-  const int lc = (lane & 7) ^ lr ^ (w & 1);                   // global chunk this lane fetches
+  const int lc = (lane & 7) ^ ((4 * (w & 1) + (lr >> 1)) & 7);  // global chunk this lane fetches: p ^ key(row)
   const uint8_t* ga = (const uint8_t*)g.A + ((m0 + w * 8 + lr) * g.lda) * EB + lc * 16;
   const uint8_t* gb = (const uint8_t*)g.B + ((n0 + w * 8 + lr) * g.ldb) * EB + lc * 16;
   const int64_t a_step = 32 * g.lda * EB, b_step = 32 * g.ldb * EB;   // bytes between instructions
@@ -64,7 +64,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_256_kernel(GemmArgs g) {
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 32 + lane % 32
   const int fr = lane & 31, fh = lane >> 5;
-  const int fkey = (fr & 7) ^ ((fr >> 3) & 1);
+  const int fkey = (fr >> 1) & 7;
   const uint8_t* fa_base = lds + (wm * 128 + fr) * kRowB;
   const uint8_t* fb_base = lds + kOperandB + (wn * 128 + fr) * kRowB;
 

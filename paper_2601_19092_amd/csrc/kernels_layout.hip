@@ -83,10 +83,10 @@ template <int BYTES> struct Word;
 template <> struct Word<1> { using T = uint8_t; };
 template <> struct Word<2> { using T = uint16_t; };
 template <> struct Word<4> { using T = uint32_t; };
-template <> struct Word<8> { using T = uint2; };
-template <> struct Word<16> { using T = uint4; };
+template <> struct Word<8> { using T = __attribute__((ext_vector_type(2))) uint32_t; };
+template <> struct Word<16> { using T = __attribute__((ext_vector_type(4))) uint32_t; };
 
-template <int BYTES, int U, bool REPL>
+template <int BYTES, int U, bool REPL, bool NT>
 __global__ __launch_bounds__(256) void relayout_joint_kernel(RelayoutPlan p, const void* __restrict__ src_,
                                                              void* __restrict__ dst_) {
   using T = typename Word<BYTES>::T;
@@ -111,12 +111,17 @@ __global__ __launch_bounds__(256) void relayout_joint_kernel(RelayoutPlan p, con
   }
   T v[U];
 #pragma unroll
-  for (int u = 0; u < U; ++u) v[u] = src[swz_apply(s + u * p.us, p.s_swz)];
+  for (int u = 0; u < U; ++u) {
+    const T* a = &src[swz_apply(s + u * p.us, p.s_swz)];
+    v[u] = NT ? __builtin_nontemporal_load(a) : *a;
+  }
 #pragma unroll
   for (int u = 0; u < U; ++u) {
     int64_t da = d + u * p.ud;
     if (!REPL) {
-      dst[swz_apply(da, p.d_swz)] = v[u];
+      T* a = &dst[swz_apply(da, p.d_swz)];
+      if (NT) __builtin_nontemporal_store(v[u], a);
+      else *a = v[u];
     } else {
       for (int64_t t = 0; t < p.E_R; ++t) {
         int64_t tr = t, ra = da;
@@ -135,9 +140,11 @@ template <int BYTES, int U>
 static hipError_t launch_joint_u(const RelayoutPlan& p, const void* src, void* dst, hipStream_t s) {
   unsigned blocks = (unsigned)((p.threads + 255) / 256);
   if (p.n_r > 0)
-    hipLaunchKernelGGL((relayout_joint_kernel<BYTES, U, true>), dim3(blocks), dim3(256), 0, s, p, src, dst);
+    hipLaunchKernelGGL((relayout_joint_kernel<BYTES, U, true, false>), dim3(blocks), dim3(256), 0, s, p, src, dst);
+  else if (p.streaming)
+    hipLaunchKernelGGL((relayout_joint_kernel<BYTES, U, false, true>), dim3(blocks), dim3(256), 0, s, p, src, dst);
   else
-    hipLaunchKernelGGL((relayout_joint_kernel<BYTES, U, false>), dim3(blocks), dim3(256), 0, s, p, src, dst);
+    hipLaunchKernelGGL((relayout_joint_kernel<BYTES, U, false, false>), dim3(blocks), dim3(256), 0, s, p, src, dst);
   return hipGetLastError();
 }
 

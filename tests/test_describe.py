@@ -1,0 +1,204 @@
+"""The layouts axe_gemm_describe reports for every tile movement, evaluated with the oracle: they
+must be bijections onto the hardware boxes they claim, compose as tile products (Sec. 3.3), keep the
+direct-to-LDS loads linear in the lane id, and give bank-conflict-free operand reads on a 64-bank LDS.
+CPU only (describe is host code)."""
+import itertools
+from math import prod
+
+import numpy as np
+import pytest
+
+from oracle import axe_layout as ax
+from oracle import axe_ref as R
+from oracle.axe_layout import Layout
+from paper_2601_19092_amd import binding as B
+from paper_2601_19092_amd import workloads as W
+
+AXES = ["m", "lds", "wg", "wave", "lane", "reg"]
+
+
+def desc_for(kind):
+    if kind == "small_bf16":
+        M, N, K, dt, out, tile = 256, 256, 256, B.AXE_BF16, B.AXE_F32, B.AXE_TILE_AUTO
+    elif kind == "small_fp8":
+        M, N, K, dt, out, tile = 128, 192, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_64x64x32
+    else:
+        M, N, K, dt, out, tile = 512, 768, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_AUTO
+    d = B.GemmDesc(M, N, K, dt, out, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, N)),
+                   B.Layout(W.row_major_spec(M, N)), M * K, N * K, M * N, tile_hint=tile)
+    return d, (M, N, K)
+
+
+def get(desc, which):
+    spec, shape = B.axe_gemm_describe(desc, which)
+    return Layout.from_spec(spec), shape
+
+
+def table(L, shape):
+    """All points: int array [E_D, E_R, 6] over AXES."""
+    return R.evaluate_np(L, np.arange(prod(shape)), AXES)
+
+
+GEO = {"small_bf16": dict(T=64, BK=32, EB=2, waves=4), "small_fp8": dict(T=64, BK=128, EB=1, waves=4),
+       "big_bf16": dict(T=256, BK=32, EB=2, waves=4)}
+
+
+@pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
+def test_tile_shapes_and_kernel_choice(kind):
+    desc, _ = desc_for(kind)
+    geo = GEO[kind]
+    assert B.axe_gemm_tile(desc) == (B.AXE_TILE_256x256x64 if kind == "big_bf16" else B.AXE_TILE_64x64x32)
+    for which, want in ((B.AXE_DESC_A_G2L_THREADS, (geo["T"], geo["BK"])), (B.AXE_DESC_B_G2L_THREADS, (geo["BK"], geo["T"])),
+                        (B.AXE_DESC_A_LDS, (geo["T"], geo["BK"])), (B.AXE_DESC_B_LDS, (geo["BK"], geo["T"])),
+                        (B.AXE_DESC_A_OPERAND, (geo["T"], geo["BK"])), (B.AXE_DESC_B_OPERAND, (geo["BK"], geo["T"])),
+                        (B.AXE_DESC_C_STORE, (geo["T"], geo["T"]))):
+        L, shape = get(desc, which)
+        assert shape == want and ax.admits(L, shape)
+
+
+@pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
+def test_accumulator_layout_is_a_bijection_and_a_tile_product(kind):
+    desc, (M, N, K) = desc_for(kind)
+    geo = GEO[kind]
+    T = geo["T"]
+    L, shape = get(desc, B.AXE_DESC_ACC)
+    gm, gn = -(-M // T), -(-N // T)
+    assert shape == (gm * T, gn * T)
+    pts = table(L, shape)[:, 0, :]
+    regs = T * T // 256
+    box = np.stack(np.meshgrid(np.arange(gm * gn), np.arange(4), np.arange(64), np.arange(regs), indexing="ij"), -1).reshape(-1, 4)
+    got = pts[:, [2, 3, 4, 5]]
+    assert np.all(pts[:, [0, 1]] == 0)
+    assert len(got) == len(box) and np.array_equal(np.unique(got, axis=0), box)      # every accumulator exactly once
+    # composition: grid (x) 2x2 waves (x) fragments-in-registers (x) MFMA accumulator fragment
+    F = 32 if T == 256 else 16
+    NF = T // 2 // F
+    per = F * F // 64
+    if F == 32:     # 32x32 fragment with swapped operands: row -> lane, column c = 8a + 4b + c' -> reg 4a + c', lane + 32 b
+        frag = Layout.make((32, 4, 2, 4), ("1@lane", "4@reg", "32@lane", "1@reg"))
+    else:           # 16x16: row -> lane, column 4b + c' -> lane + 16 b, reg c'
+        frag = Layout.make((16, 4, 4), ("1@lane", "16@lane", "1@reg"))
+    regs_t = Layout.make((NF, NF), (f"{NF}@reg", "1@reg"))
+    waves = Layout.make((2, 2), ("2@wave", "1@wave"))
+    grid = Layout.make((gm, gn), (f"{gn}@wg", "1@wg"))
+    t1, s1 = ax.tile(regs_t, (NF, NF), frag, (F, F))
+    t2, s2 = ax.tile(waves, (2, 2), t1, (NF * F, NF * F))
+    t3, s3 = ax.tile(grid, (gm, gn), t2, (T // 1, T // 1))
+    assert ax.span(frag)["reg"] == per
+    want = R.evaluate_np(t3, np.arange(prod(shape)), AXES)[:, 0, :]
+    assert np.array_equal(want, pts)
+
+
+@pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
+def test_global_to_lds_thread_map(kind):
+    desc, _ = desc_for(kind)
+    geo = GEO[kind]
+    T, BK, EB = geo["T"], geo["BK"], geo["EB"]
+    CE = 16 // EB
+    for which_t, which_l, shape in ((B.AXE_DESC_A_G2L_THREADS, B.AXE_DESC_A_LDS, (T, BK)),
+                                    (B.AXE_DESC_B_G2L_THREADS, B.AXE_DESC_B_LDS, (BK, T))):
+        Lt, st = get(desc, which_t)
+        Ll, sl = get(desc, which_l)
+        assert st == sl == shape
+        th = table(Lt, shape)[:, 0, :]
+        regs = T * BK // 256
+        key = (th[:, 3] * 64 + th[:, 4]) * regs + th[:, 5]
+        assert np.array_equal(np.sort(key), np.arange(T * BK))           # every thread register exactly once
+        lds = table(Ll, shape)[:, 0, 1]
+        base = 0 if which_l == B.AXE_DESC_A_LDS else T * BK
+        assert np.array_equal(np.sort(lds), np.arange(base, base + T * BK))   # LDS stage filled exactly once
+        # each lane moves whole 16-byte chunks: CE consecutive registers <-> CE consecutive k <-> CE consecutive LDS elements
+        order = np.argsort(key)
+        lds_by_thread = lds[order].reshape(4, 64, regs // CE, CE)
+        assert np.all(np.diff(lds_by_thread, axis=-1) == 1) and np.all(lds_by_thread[..., 0] % CE == 0)
+        if kind == "big_bf16":
+            # direct-to-LDS loads: one wave instruction writes lane * 16 bytes from a 1 KiB aligned base
+            first = lds_by_thread[..., 0] * EB                            # byte address of each lane's chunk
+            for w, i in itertools.product(range(4), range(regs // CE)):
+                b0 = first[w, 0, i]
+                assert b0 % 1024 == 0 and np.array_equal(first[w, :, i], b0 + 16 * np.arange(64))
+
+
+def bank_conflicts(byte_addrs):
+    """64 banks of 4 bytes; a 16-byte read per lane is served 16 lanes at a time: conflict-free iff the
+    16 lanes of a group touch 16 distinct 16-byte bank groups.  Returns the worst multiplicity."""
+    worst = 1
+    for g in range(0, 64, 16):
+        slots = (byte_addrs[g:g + 16] // 16) % 16
+        worst = max(worst, int(np.bincount(slots, minlength=16).max()))
+    return worst
+
+
+@pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
+def test_operand_reads_cover_the_tile_and_are_bank_conflict_free(kind):
+    desc, _ = desc_for(kind)
+    geo = GEO[kind]
+    T, BK, EB = geo["T"], geo["BK"], geo["EB"]
+    CE = 16 // EB
+    for which_o, which_l, shape in ((B.AXE_DESC_A_OPERAND, B.AXE_DESC_A_LDS, (T, BK)),
+                                    (B.AXE_DESC_B_OPERAND, B.AXE_DESC_B_LDS, (BK, T))):
+        Lo, _ = get(desc, which_o)
+        Ll, _ = get(desc, which_l)
+        op = table(Lo, shape)                              # [E, 2 replicas, 6]
+        assert op.shape[1] == 2
+        regs = (T // 2) * BK // 64
+        key = ((op[:, :, 3] * 64 + op[:, :, 4]) * regs + op[:, :, 5]).reshape(-1)
+        assert np.array_equal(np.sort(key), np.arange(4 * 64 * regs))     # each wave holds its half, once
+        for swz, expect_clean in ((True, True), (False, False)):
+            L = Ll if swz else Ll.with_(swizzle=None)
+            lds = np.repeat(table(L, shape)[:, 0, 1], 2)
+            addr = np.empty(4 * 64 * regs, dtype=np.int64)
+            addr[key] = lds * EB
+            addr = addr.reshape(4, 64, regs // CE, CE)[..., 0]             # byte address of each 16-byte read
+            worst = max(bank_conflicts(addr[w, :, i]) for w in range(4) for i in range(addr.shape[2]))
+            assert (worst == 1) == expect_clean, (kind, which_o, swz, worst)
+
+
+@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16"])
+def test_c_store_map(kind):
+    desc, _ = desc_for(kind)
+    T = GEO[kind]["T"]
+    L, shape = get(desc, B.AXE_DESC_C_STORE)
+    pts = table(L, shape)[:, 0, :]
+    regs = T * T // 256
+    key = (pts[:, 3] * 64 + pts[:, 4]) * regs + pts[:, 5]
+    assert np.array_equal(np.sort(key), np.arange(T * T))
+    if kind == "big_bf16":
+        # one store instruction (8 consecutive registers of every lane): 4 rows x 256 contiguous bytes
+        col = np.empty(T * T, dtype=np.int64); row = np.empty(T * T, dtype=np.int64)
+        idx = np.arange(T * T)
+        row[key], col[key] = idx // T, idx % T
+        row, col = row.reshape(4, 64, regs // 8, 8), col.reshape(4, 64, regs // 8, 8)
+        assert np.all(np.diff(col, axis=-1) == 1) and np.all(row[..., 0:1] == row)
+        for w, t in itertools.product(range(4), range(regs // 8)):
+            r, c = row[w, :, t, 0], col[w, :, t, 0]
+            assert len(set(r.tolist())) == 4
+            for rr in set(r.tolist()):
+                cs = np.sort(c[r == rr])
+                assert np.array_equal(cs, cs[0] + 8 * np.arange(16)) and cs[0] % 128 == 0
+
+
+def test_mfma_operand_layout_matches_its_statement():
+    """MFMA 32x32x16 bf16: lane = row + 32 * (k // 8), 8 consecutive k per lane; 16x16x32: lane = row + 16 * (k // 8)."""
+    desc, _ = desc_for("big_bf16")
+    L, shape = get(desc, B.AXE_DESC_A_OPERAND)
+    for r, k in ((0, 0), (5, 7), (37, 8), (130, 17), (255, 31)):
+        pts = ax.evaluate_at(L, shape, (r, k), AXES)
+        wm, f, fr = r // 128, (r % 128) // 32, r % 32
+        ks, fh, e = k // 16, (k % 16) // 8, k % 8
+        assert sorted(p[3] for p in pts) == [2 * wm, 2 * wm + 1]
+        assert {p[4] for p in pts} == {fr + 32 * fh} and {p[5] for p in pts} == {(ks * 4 + f) * 8 + e}
+    desc, _ = desc_for("small_bf16")
+    L, shape = get(desc, B.AXE_DESC_B_OPERAND)
+    for k, n in ((0, 0), (9, 17), (31, 63)):
+        pts = ax.evaluate_at(L, shape, (k, n), AXES)
+        wn, f, fr = n // 32, (n % 32) // 16, n % 16
+        assert sorted(p[3] for p in pts) == [wn, wn + 2]
+        assert {p[4] for p in pts} == {fr + 16 * (k // 8)} and {p[5] for p in pts} == {f * 8 + k % 8}
+
+
+def test_describe_errors():
+    desc, _ = desc_for("small_bf16")
+    with pytest.raises(B.AxeError) as e:
+        B.axe_gemm_describe(desc, 99)
+    assert e.value.code == B.AXE_EINVAL
