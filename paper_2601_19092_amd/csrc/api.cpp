@@ -418,14 +418,16 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   P.args.scale_b = g->d_scale_b;
   P.args.nkb = (int32_t)((g->K + 127) / 128);
   P.args.out_bf16 = g->out_dtype == AXE_BF16;
-  const int64_t bk = fp8 ? 128 : 32;
+  const int64_t bk = fp8 ? 128 : 64;
+  // the large-tile kernels address a tile's 256 rows through 32-bit buffer offsets
+  const bool pitch_ok = 256 * lda * eb < (int64_t(1) << 31) && 256 * ldb * eb < (int64_t(1) << 31);
   const bool big_ok = (g->M % 256 == 0) && (g->N % 256 == 0) && (g->K % bk == 0) && (ldc % 8 == 0) &&
-                      P.args.out_bf16;
+                      P.args.out_bf16 && pitch_ok;
   int tile = g->tile_hint;
   if (tile == AXE_TILE_AUTO) tile = big_ok ? AXE_TILE_256x256x64 : AXE_TILE_64x64x32;
   if (tile == AXE_TILE_256x256x64 && !big_ok) {
-    set_error("axe_gemm: the 256x256 tile needs M, N multiples of 256, K a multiple of %lld and bf16 output",
-              (long long)bk);
+    set_error("axe_gemm: the 256x256 tile needs M, N multiples of 256, K a multiple of %lld, bf16 output and "
+              "row pitches below 2^31 / 256 bytes", (long long)bk);
     return AXE_EUNSUPPORTED;
   }
   if (tile != AXE_TILE_256x256x64 && tile != AXE_TILE_64x64x32) {
