@@ -35,9 +35,24 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
 }
 
 // Workgroup id -> (tile row, tile col).  Consecutive workgroup ids go to different XCDs (8 of
-// them, each with its own L2), so ids are first regrouped per XCD, then walked in column-major
-// groups of 8 tile rows so that the tiles resident on one XCD share A and B panels.
+// them, each with its own L2, 32 CUs each), so the id is split into (XCD, position on that XCD).
+// When the tile grid is made of 16 x 16 blocks, one round of 256 concurrent workgroups covers one
+// block (32 panels, 128 MiB for K = 8192: half the last-level cache), XCD x owning an 8 x 4
+// sub-block of it (12 panels through its L2), and the blocks are visited in snake order so that
+// consecutive rounds share 16 panels.  Other grids: regroup per XCD, then column-major groups of 8
+// tile rows.
 __device__ __forceinline__ void tile_of_block(int bid, int nwg, int grid_m, int grid_n, int& tm, int& tn) {
+  if (((grid_m | grid_n) & 15) == 0) {
+    const int xcd = bid & 7, idx = bid >> 3;
+    const int round = idx >> 5, cu = idx & 31;
+    const int bpr = grid_n >> 4;
+    const int br = round / bpr;
+    int bc = round - br * bpr;
+    if (br & 1) bc = bpr - 1 - bc;
+    tm = br * 16 + (xcd >> 2) * 8 + (cu & 7);
+    tn = bc * 16 + (xcd & 3) * 4 + (cu >> 3);
+    return;
+  }
   int lin = bid;
   if ((nwg & 7) == 0) lin = (bid & 7) * (nwg >> 3) + (bid >> 3);
   const int GM = 8;
