@@ -95,6 +95,34 @@ __device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[4][4], uint8
   }
 }
 
+// Epilogue of a 256 x 256 tile held by 4 waves as 8 x 8 MFMA 16x16 accumulator fragments each
+// (operands swapped: lane l holds, for fragment (i, j), the 4 consecutive columns
+// j*16 + 4*(l/16) .. +3 of row i*16 + l%16 of the wave's 128 x 128 sub-tile).  Each wave converts to
+// bf16, stages its sub-tile in its own LDS region (row pitch 272 bytes: the 8-byte writes of a
+// wave instruction fall on 64 distinct banks) and writes it out with 16-byte stores, 256
+// contiguous bytes per row.  The caller guarantees that no wave still reads the pipeline stages.
+__device__ __forceinline__ void store_tile_bf16_16(const f32x4 (&acc)[8][8], uint8_t* lds, int w, int lane,
+                                                   uint16_t* C, int64_t ldc) {
+  const int fr = lane & 15, fq = lane >> 4;
+  uint8_t* ew = lds + w * 128 * kEpiPitch;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      uint2 v = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
+      *(uint2*)(ew + (i * 16 + fr) * kEpiPitch + (j * 16 + 4 * fq) * 2) = v;
+    }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+  const int er = lane >> 4, ec = lane & 15;
+#pragma unroll 4
+  for (int t = 0; t < 32; ++t) {
+    int row = t * 4 + er;
+    uint4 v = *(const uint4*)(ew + row * kEpiPitch + ec * 16);
+    *(uint4*)(C + (int64_t)row * ldc + ec * 8) = v;
+  }
+}
+
 // Epilogue of a 256 x 256 tile held by 8 waves as 4 x 2 MFMA 32x32 accumulator fragments each
 // (operands swapped: lane l holds, for fragment (i, j) and a = 0..3, the 4 consecutive columns
 // j*32 + 8a + 4*(l/32) .. +3 of row i*32 + l%32 of the wave's 128 x 64 sub-tile).  Each wave converts
