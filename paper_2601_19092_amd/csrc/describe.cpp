@@ -38,6 +38,7 @@ struct Geo {
   bool big, fp8;
   int T, BK, F, ROWB, CE, EB;
   int key_shift;   // swizzle key = (row >> key_shift) & (chunks per row - 1)
+  int64_t b_off;   // element offset of the B block inside one LDS stage
 };
 
 Geo geometry(bool big, bool fp8) {
@@ -46,17 +47,18 @@ Geo geometry(bool big, bool fp8) {
   g.fp8 = fp8;
   g.EB = fp8 ? 1 : 2;
   g.CE = 16 / g.EB;
+  g.ROWB = (fp8 || big) ? 128 : 64;
   if (big) {
     g.T = 256;
-    g.F = 32;
-    g.ROWB = fp8 ? 128 : 64;
+    g.F = fp8 ? 32 : 16;
   } else {
     g.T = 64;
     g.F = 16;
-    g.ROWB = fp8 ? 128 : 64;
   }
   g.BK = g.ROWB / g.EB;
   g.key_shift = g.ROWB == 64 ? 2 : 1;
+  // bf16 256x256: five 32 KiB blocks, A in blocks 0 and 1, the B ring starts at block 2
+  g.b_off = (int64_t)g.T * g.BK * ((big && !fp8) ? 2 : 1);
   return g;
 }
 
@@ -70,13 +72,20 @@ int g2l_threads(const Geo& g, bool is_b, Builder& b) {
                      "in its swizzle key and is not a single-axis swizzle");
       return AXE_EUNSUPPORTED;
     }
-    // one wave instruction = 1 KiB = RPI rows; wave w takes row groups w, w+4, ...: row = (4 i + w) * RPI + lr
-    const int RPI = 1024 / g.ROWB, NI = g.T / (4 * RPI);
-    rows = {{NI, g.CE, REG}, {4, 1, WAVE}, {RPI, CH, LANE}};
+    // one wave instruction = 1 KiB = 8 rows of 128 bytes; wave w takes row groups w, w + 4, ...:
+    // row = (4 i + w) * 8 + lr, chunk c.  A travels through registers (lane = 8 lr + c, piece i in
+    // registers 8 i .. 8 i + 7) and is swizzled by the LDS write.  B is loaded straight into LDS, which
+    // such a load fills linearly in the lane id, so the swizzle shows up in which chunk a lane
+    // fetches: c ^ key(row), key = (4 (w & 1) + (lr >> 1)) & 7.  That key spans the wave id, so the
+    // B map is stated on the thread id t = 64 w + lane, folded into the lane axis: key = (t >> 4) & 7.
+    const int NI = g.T / 32;
+    if (!is_b) {
+      rows = {{NI, g.CE, REG}, {4, 1, WAVE}, {8, CH, LANE}};
+    } else {
+      rows = {{NI, g.CE, REG}, {4, 64, LANE}, {8, CH, LANE}};
+      b.swz(LANE, ilog2(CH), 0, ilog2(CH) + g.key_shift);
+    }
     ks = {{CH, 1, LANE}, {g.CE, 1, REG}};
-    // the LDS side is linear in the lane id, so the chunk swizzle shows up on the lane axis:
-    // lane = CH * lr + (c ^ key(lr)), key(lr) = (lr >> key_shift) & (CH - 1)
-    b.swz(LANE, ilog2(CH), 0, ilog2(CH) + g.key_shift);
   } else {
     // thread t fetches chunk t (+ 256 p): row = 32 p' ..., see kernels_gemm_small.hip
     const int PER = (64 * CH) / 256;                   // chunks per thread
@@ -108,7 +117,7 @@ int lds_layout(const Geo& g, bool is_b, Builder& b) {
   } else {
     b.D(g.BK, 1, LDS);
     b.D(g.T, g.BK, LDS);
-    b.off[LDS] = (int64_t)g.T * g.BK;
+    b.off[LDS] = g.b_off;
     b.shape = {g.BK, g.T};
   }
   // chunk index ^= (row >> key_shift) & (CH - 1), in element units

@@ -40,7 +40,7 @@ def table(L, shape):
 
 
 GEO = {"small_bf16": dict(T=64, BK=32, EB=2, waves=4), "small_fp8": dict(T=64, BK=128, EB=1, waves=4),
-       "big_bf16": dict(T=256, BK=32, EB=2, waves=4)}
+       "big_bf16": dict(T=256, BK=64, EB=2, waves=4)}
 
 
 @pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
@@ -71,7 +71,7 @@ def test_accumulator_layout_is_a_bijection_and_a_tile_product(kind):
     assert np.all(pts[:, [0, 1]] == 0)
     assert len(got) == len(box) and np.array_equal(np.unique(got, axis=0), box)      # every accumulator exactly once
     # composition: grid (x) 2x2 waves (x) fragments-in-registers (x) MFMA accumulator fragment
-    F = 32 if T == 256 else 16
+    F = 16
     NF = T // 2 // F
     per = F * F // 64
     if F == 32:     # 32x32 fragment with swapped operands: row -> lane, column c = 8a + 4b + c' -> reg 4a + c', lane + 32 b
@@ -105,18 +105,28 @@ def test_global_to_lds_thread_map(kind):
         key = (th[:, 3] * 64 + th[:, 4]) * regs + th[:, 5]
         assert np.array_equal(np.sort(key), np.arange(T * BK))           # every thread register exactly once
         lds = table(Ll, shape)[:, 0, 1]
-        base = 0 if which_l == B.AXE_DESC_A_LDS else T * BK
+        # B block: right after A in the small kernels; the 256x256 bf16 kernel keeps two A blocks first
+        base = 0 if which_l == B.AXE_DESC_A_LDS else T * BK * (2 if kind == "big_bf16" else 1)
         assert np.array_equal(np.sort(lds), np.arange(base, base + T * BK))   # LDS stage filled exactly once
         # each lane moves whole 16-byte chunks: CE consecutive registers <-> CE consecutive k <-> CE consecutive LDS elements
         order = np.argsort(key)
         lds_by_thread = lds[order].reshape(4, 64, regs // CE, CE)
         assert np.all(np.diff(lds_by_thread, axis=-1) == 1) and np.all(lds_by_thread[..., 0] % CE == 0)
         if kind == "big_bf16":
-            # direct-to-LDS loads: one wave instruction writes lane * 16 bytes from a 1 KiB aligned base
+            # one wave instruction moves 8 rows x 128 bytes into a 1 KiB aligned piece of LDS
             first = lds_by_thread[..., 0] * EB                            # byte address of each lane's chunk
             for w, i in itertools.product(range(4), range(regs // CE)):
-                b0 = first[w, 0, i]
-                assert b0 % 1024 == 0 and np.array_equal(first[w, :, i], b0 + 16 * np.arange(64))
+                b0 = first[w, :, i].min()
+                assert b0 % 1024 == 0
+                if which_l == B.AXE_DESC_B_LDS:
+                    # direct-to-LDS load: lane l writes byte 16 l of the piece
+                    assert np.array_equal(first[w, :, i], b0 + 16 * np.arange(64))
+                else:
+                    # through registers: the 8 lanes of a row write that row's 8 chunk positions, permuted
+                    rows_ = (first[w, :, i] - b0) // 128
+                    assert np.array_equal(rows_, np.arange(64) // 8)
+                    for r in range(8):
+                        assert sorted(((first[w, 8 * r:8 * r + 8, i] - b0) % 128 // 16).tolist()) == list(range(8))
 
 
 def bank_conflicts(byte_addrs):
@@ -179,15 +189,15 @@ def test_c_store_map(kind):
 
 
 def test_mfma_operand_layout_matches_its_statement():
-    """MFMA 32x32x16 bf16: lane = row + 32 * (k // 8), 8 consecutive k per lane; 16x16x32: lane = row + 16 * (k // 8)."""
+    """MFMA 16x16x32 bf16: lane = row + 16 * (k // 8), 8 consecutive k per lane."""
     desc, _ = desc_for("big_bf16")
     L, shape = get(desc, B.AXE_DESC_A_OPERAND)
-    for r, k in ((0, 0), (5, 7), (37, 8), (130, 17), (255, 31)):
+    for r, k in ((0, 0), (5, 7), (37, 8), (130, 17), (255, 63)):
         pts = ax.evaluate_at(L, shape, (r, k), AXES)
-        wm, f, fr = r // 128, (r % 128) // 32, r % 32
-        ks, fh, e = k // 16, (k % 16) // 8, k % 8
+        wm, f, fr = r // 128, (r % 128) // 16, r % 16
+        ks, fq, e = k // 32, (k % 32) // 8, k % 8
         assert sorted(p[3] for p in pts) == [2 * wm, 2 * wm + 1]
-        assert {p[4] for p in pts} == {fr + 32 * fh} and {p[5] for p in pts} == {(ks * 4 + f) * 8 + e}
+        assert {p[4] for p in pts} == {fr + 16 * fq} and {p[5] for p in pts} == {(ks * 8 + f) * 8 + e}
     desc, _ = desc_for("small_bf16")
     L, shape = get(desc, B.AXE_DESC_B_OPERAND)
     for k, n in ((0, 0), (9, 17), (31, 63)):
