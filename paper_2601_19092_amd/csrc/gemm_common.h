@@ -123,6 +123,31 @@ __device__ __forceinline__ void store_tile_bf16_16(const f32x4 (&acc)[8][8], uin
   }
 }
 
+// Epilogue of a 256 x 256 tile held by 8 waves as 8 x 4 MFMA 16x16 accumulator fragments each (lane l
+// holds, for fragment (i, j), the 4 consecutive columns j*16 + 4*(l/16) .. +3 of row i*16 + l%16 of the
+// wave's 128 x 64 sub-tile).  Staging and stores as in store_tile_bf16_w8.
+__device__ __forceinline__ void store_tile_bf16_w8_16(const f32x4 (&acc)[8][4], uint8_t* lds, int w, int lane,
+                                                      uint16_t* C, int64_t ldc) {
+  const int fr = lane & 15, fq = lane >> 4;
+  uint8_t* ew = lds + w * 128 * kEpiPitch8;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      uint2 v = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
+      *(uint2*)(ew + (i * 16 + fr) * kEpiPitch8 + (j * 16 + 4 * fq) * 2) = v;
+    }
+  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+  __builtin_amdgcn_wave_barrier();
+  const int er = lane >> 3, ec = lane & 7;
+#pragma unroll 4
+  for (int t = 0; t < 16; ++t) {
+    int row = t * 8 + er;
+    uint4 v = *(const uint4*)(ew + row * kEpiPitch8 + ec * 16);
+    *(uint4*)(C + (int64_t)row * ldc + ec * 8) = v;
+  }
+}
+
 // Epilogue of a 256 x 256 tile held by 8 waves as 4 x 2 MFMA 32x32 accumulator fragments each
 // (operands swapped: lane l holds, for fragment (i, j) and a = 0..3, the 4 consecutive columns
 // j*32 + 8a + 4*(l/32) .. +3 of row i*32 + l%32 of the wave's 128 x 64 sub-tile).  Each wave converts

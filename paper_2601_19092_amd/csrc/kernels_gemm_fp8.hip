@@ -1,19 +1,38 @@
-// fp8 (OCP e4m3) GEMM for gfx950 (MI355X) with optional fp32 scales per 128 x 128 block:
-// workgroup tile 256 x 256 x 128, 4 waves (one per SIMD), each a 128 x 128 sub-tile = 4 x 4 MFMA
-// 32x32x64 fragments.  A row-major, B column-major (both K contiguous).
+// fp8 (OCP e4m3) GEMM for gfx950 (MI355X) with optional fp32 scales per 128 x 128 block: workgroup
+// tile 256 x 256 x 128, 8 waves (two per SIMD), each a 128 x 64 sub-tile = 8 x 4 MFMA 16x16x128
+// fragments.  A row-major, B column-major (both K contiguous).
 //
-// Tile movements, each an Axe layout (reported by axe_gemm_describe):
-//   HBM -> LDS  : global_load_lds_dwordx4; one wave instruction fills 8 LDS rows of 128 bytes; the
-//                 XOR swizzle is applied on the global side: lane (r = lane / 8, p = lane % 8)
-//                 fetches chunk p ^ key(r) of row r, key(r) = (r >> 1) & 7 (64 LDS banks: conflict-free).
-//   LDS layout  : two stages of 64 KiB, A tile then B tile, rows of 128 bytes (128 fp8).
-//   LDS -> VGPR : lane l reads row l % 32 of a fragment and the two adjacent 16-byte chunks
-//                 4 * ks + 2 * (l / 32) + {0, 1}: 32 consecutive k per lane, the operand layout
-//                 of MFMA 32x32x64 (A and B are loaded the same way, so the pairing of k is kept).
-//   scales      : one K step is one 128-deep scale block; it is accumulated on its own (MFMA with a
-//                 zero accumulator), then acc += (sA * sB) * block on the vector ALU.
+// One K-tile is one 128-deep scale block and one MFMA per fragment: every MFMA starts from a zero
+// accumulator, and its result P is folded into the running sum on the vector ALU,
+// acc += (sA * sB) * P, two MFMAs later.  The vector ALU cannot address the AGPR half of the
+// register file, so the running sums live in ordinary VGPRs; that is what sets the wave tile: 128
+// accumulator registers, two P buffers, four A and four B fragments of 8 registers each stay below
+// the 256 registers a wave has when two waves share a SIMD.
+//
+// Tile movements, each an Axe layout (the LDS side as in the bf16 kernel, reported by axe_gemm_describe):
+//   HBM -> LDS  : buffer_load ... lds, 16 bytes per lane straight into LDS; one wave instruction
+//                 covers 8 rows x 128 bytes.  The LDS side of such a load is linear in the lane id,
+//                 so the XOR swizzle is applied on the global side: lane (r = lane / 8, p = lane % 8)
+//                 fetches chunk p ^ key(r) of row r.
+//   LDS layout  : five 32 KiB blocks (one operand, one K-tile each): A double-buffered in blocks 0, 1,
+//                 B in a ring of blocks 2, 3, 4.  Rows of 128 bytes (128 fp8); 16-byte chunk c of row r
+//                 sits at chunk position c ^ key(r), key(r) = (r >> 1) & 7 (64 LDS banks: conflict-free).
+//   LDS -> VGPR : lane l reads row l % 16 of a fragment and the two adjacent 16-byte chunks
+//                 2 * (l / 16) + {0, 1}: 32 consecutive k per lane, the operand layout of MFMA
+//                 16x16x128 (A and B are loaded the same way, so the pairing of k is kept).
 //   VGPR -> HBM : accumulators -> bf16 -> LDS -> 16-byte coalesced stores.
+//
+// Schedule.  A K-step is 32 MFMAs per wave, fragment (i, j) with j innermost.  A fragments are read
+// three rows ahead of their use, so every LDS read of A of tile kt has been issued when row 4 ends;
+// the B fragments of a tile are read during the last row of the tile before.  One workgroup barrier
+// per K-step, after row 4: it publishes tile kt+1 and frees the A block of tile kt and the B block of
+// tile kt (read at the end of step kt-1).  Between two barriers a wave issues A of tile kt+2 (into
+// the block just freed: one K-step to land, so it goes first) and then B of tile kt+3 (ring of
+// three blocks: a little more than one K-step).
+// The K rotation and the workgroup -> tile order are those of the bf16 kernel.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "device_types.h"
 #include "gemm_common.h"
@@ -22,130 +41,197 @@
 namespace axe {
 
 namespace {
-constexpr int kRowB = 128;                        // bytes of K per LDS row
-constexpr int kOperandB = kTile * kRowB;          // 32 KiB per operand per stage
-constexpr int kStageB = 2 * kOperandB;            // 64 KiB
-static_assert(2 * kStageB <= kEpiB, "the epilogue staging area covers both stages");
+constexpr int kRow = 128;                         // bytes of K per LDS row (128 fp8)
+constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-tile
+constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
+constexpr int kLds = 5 * kBlk;                    // 160 KiB
+constexpr int kRot = 8;                           // K-rotation window, in K-tiles
+static_assert(kEpiB8 <= kLds, "the epilogue staging area fits");
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef __attribute__((address_space(3))) uint8_t* lds_u8;
+__device__ __forceinline__ i32x8 lds_read32(lds_u8 p0, lds_u8 p1) {
+  const i32x4 lo = *(__attribute__((address_space(3))) const i32x4*)p0;
+  const i32x4 hi = *(__attribute__((address_space(3))) const i32x4*)p1;
+  return i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
 }  // namespace
 
-__global__ __launch_bounds__(256, 1) void gemm_fp8_256_kernel(GemmArgs g) {
-  constexpr int EB = 1;
-  constexpr int BK = kRowB / EB;                  // 128 fp8 per K step
-  __shared__ __attribute__((aligned(1024))) uint8_t lds[kEpiB];
+__global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
+  uint8_t* const lds = lds_mem;                                    // generic view, for the epilogue
+  const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses for the main loop
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);          // wave id, kept scalar
-  const int wm = w >> 1, wn = w & 1;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);          // wave id 0..7, kept scalar
+  const int wm = w >> 2, wn = w & 3;                               // wave grid 2 x 4
   int tm, tn;
   tile_of_block(blockIdx.x, gridDim.x, g.grid_m, g.grid_n, tm, tn);
   const int64_t m0 = (int64_t)tm * kTile, n0 = (int64_t)tn * kTile;
-  const int nk = (int)(g.K / BK);
+  const int nk = (int)(g.K / 128);
+  // K rotation (see the bf16 kernel): position T of the walk -> K-tile
+  const int rot = (tm + tn) & (kRot - 1);
+  const int nk_rot = nk & ~(kRot - 1);
+  auto ktile = [&](int T) -> int { return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T; };
 
-  // ---- HBM -> LDS: per wave and K step, 8 instructions for A and 8 for B; instruction i of wave w
-  //      covers LDS rows (4 i + w) * 8 .. + 7
-  const int lr = lane >> 3;                                   // row inside the 8-row group
-  const int lc = (lane & 7) ^ ((4 * (w & 1) + (lr >> 1)) & 7);  // global chunk this lane fetches: p ^ key(row)
-  const uint8_t* ga = (const uint8_t*)g.A + ((m0 + w * 8 + lr) * g.lda) * EB + lc * 16;
-  const uint8_t* gb = (const uint8_t*)g.B + ((n0 + w * 8 + lr) * g.ldb) * EB + lc * 16;
-  const int64_t a_step = 32 * g.lda * EB, b_step = 32 * g.ldb * EB;   // bytes between instructions
-
-  auto issue_loads = [&](int kt, int stage) {
-    const uint8_t* pa = ga + (int64_t)kt * kRowB;
-    const uint8_t* pb = gb + (int64_t)kt * kRowB;
-    uint8_t* la = lds + stage * kStageB + w * 8 * kRowB;
-    uint8_t* lb = la + kOperandB;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) {
-      __builtin_amdgcn_global_load_lds(pa + i * a_step, (__attribute__((address_space(3))) void*)(la + i * 32 * kRowB), 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(pb + i * b_step, (__attribute__((address_space(3))) void*)(lb + i * 32 * kRowB), 16, 0, 0);
-    }
+  // ---- HBM -> LDS.  Per K-tile and operand 32 wave instructions of 8 rows; wave w issues pieces
+  //      i = 0..3 = row groups w, w + 8, w + 16, w + 24.
+  const int lr = lane >> 3, lp = lane & 7;
+  const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 8 i) * 8 + lr
+  const int a_pitch = (int)g.lda, b_pitch = (int)g.ldb;            // bytes
+  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)((const uint8_t*)g.A + m0 * g.lda), 0, 255 * a_pitch + (int)g.K, 0x00020000);
+  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
+      (void*)((const uint8_t*)g.B + n0 * g.ldb), 0, 255 * b_pitch + (int)g.K, 0x00020000);
+  const int a_voff = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
+  const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
+  const int a_piece = 64 * a_pitch, b_piece = 64 * b_pitch;        // bytes between pieces
+  auto a_load = [&](int T, int i, int stage) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr)(lds3 + stage * kBlk + (w + 8 * i) * 1024), 16, a_voff,
+                                             i * a_piece + ktile(T) * kRow, 0, 0);
+  };
+  // B ring: byte offsets of the blocks that hold tiles kt, kt+1, kt+2 (tile kt+3 reuses the first)
+  int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
+  auto b_load = [&](int T, int i, int slot_off) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr)(lds3 + slot_off + (w + 8 * i) * 1024), 16, b_voff,
+                                             i * b_piece + ktile(T) * kRow, 0, 0);
   };
 
-  // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 32 + lane % 32
-  const int fr = lane & 31, fh = lane >> 5;
+  // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16; the lane's
+  //      32 bytes are the chunks 2 q and 2 q + 1 (q = lane / 16), found at positions (2 q) ^ key, (2 q + 1) ^ key
+  const int fr = lane & 15, fq = lane >> 4;
   const int fkey = (fr >> 1) & 7;
-  const uint8_t* fa_base = lds + (wm * 128 + fr) * kRowB;
-  const uint8_t* fb_base = lds + kOperandB + (wn * 128 + fr) * kRowB;
+  const lds_u8 fa0 = lds3 + (wm * 128 + fr) * kRow + (((2 * fq) ^ fkey) << 4);
+  const lds_u8 fa1 = lds3 + (wm * 128 + fr) * kRow + (((2 * fq + 1) ^ fkey) << 4);
+  const lds_u8 fb0 = lds3 + (wn * 64 + fr) * kRow + (((2 * fq) ^ fkey) << 4);
+  const lds_u8 fb1 = lds3 + (wn * 64 + fr) * kRow + (((2 * fq + 1) ^ fkey) << 4);
 
-  f32x16 acc[4][4];
+  f32x4 acc[8][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
     for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  // fp8: one K step = one 128-deep scale block = two MFMA 32x32x64 (ks = 0, 1); a lane's operand
-  // fragment is 32 bytes = two adjacent 16-byte chunks.  B fragments of the step stay resident,
-  // A fragments are streamed one fragment row ahead of the MFMAs that use them.
-  i32x8 fb[2][4], fa[2][2];
-  auto read_frag = [&](const uint8_t* base, int stage, int ks, int f) -> i32x8 {
-    const int o0 = stage * kStageB + (((4 * ks + 2 * fh) ^ fkey) << 4);
-    const int o1 = stage * kStageB + (((4 * ks + 2 * fh + 1) ^ fkey) << 4);
-    i32x4 lo = *(const i32x4*)(base + o0 + f * 32 * kRowB);
-    i32x4 hi = *(const i32x4*)(base + o1 + f * 32 * kRowB);
-    return i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
-  };
+  // Block scales: one product sA * sB per K-step of this wave.  A register holds those of 64
+  // consecutive K-steps, one per lane (no scalar or vector memory access in the steady loop); it is
+  // refilled every 64 steps.
   const bool scaled = g.scale_a != nullptr;
   const float* sa = scaled ? g.scale_a + (int64_t)((m0 + wm * 128) / 128) * g.nkb : nullptr;
-  const float* sb = scaled ? g.scale_b + (int64_t)((n0 + wn * 128) / 128) * g.nkb : nullptr;
+  const float* sb = scaled ? g.scale_b + (int64_t)((n0 + wn * 64) / 128) * g.nkb : nullptr;
+  auto scales_from = [&](int base) -> float {
+    if (!scaled) return 1.0f;
+    const int T = base + lane;
+    const int t = ktile(T < nk ? T : nk - 1);
+    return sa[t] * sb[t];
+  };
+  auto lane_value = [](float v, int l) -> float {
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
+  };
 
-  issue_loads(0, 0);
+  i32x8 fa[4], fb[4];      // A fragment i sits in slot i % 4 (read three rows ahead of its use); B fragments 0..3 of the tile
+  f32x4 P[2];              // results of the last two MFMAs
+
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+
+  auto read_a = [&](int f, int stage) {
+    fa[f & 3] = lds_read32(fa0 + stage * kBlk + f * 16 * kRow, fa1 + stage * kBlk + f * 16 * kRow);
+  };
+  auto read_b = [&](int f, int slot_off) {
+    fb[f] = lds_read32(fb0 + slot_off + f * 16 * kRow, fb1 + slot_off + f * 16 * kRow);
+  };
+  auto fold = [&](int i, int j, int buf, float s) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[i][j][e] = __builtin_fmaf(s, P[buf][e], acc[i][j][e]);
+  };
+
+  // K-step kt (PAR = kt & 1) in exact program order (sched_barrier(0) forbids any reordering across
+  // it).  Slot q = 4 i + j: MFMA (i, j) from a zero accumulator; then the result of the MFMA before
+  // is folded into the running sum.  Row i also reads A fragment i + 3 (rows 5..7: fragments 0..2 of
+  // the next tile) into the slot row i - 1 has just left; in row 7 B fragment j of the next tile
+  // replaces fragment j right after its last use.  The barrier follows row 4, when the last A read of
+  // the tile has been issued.  Slots 2, 6, 10, 14 load B of tile kt+2; slots 20, 22, 24, 26 load A of
+  // tile kt+2.  Nothing is guarded against the end of K: loads of tiles past the end stay inside the
+  // buffer descriptors, land in blocks that are free by then, and are never multiplied.
+  auto step = [&](auto par_c, int kt, float sc, float sc_prev) {
+    constexpr int PAR = decltype(par_c)::value;
+#pragma unroll
+    for (int q = 0; q < 32; ++q) {
+      const int i = q >> 2, j = q & 3;
+      P[q & 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i & 3], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+      __builtin_amdgcn_sched_barrier(0);
+      if (q > 0) fold((q - 1) >> 2, (q - 1) & 3, (q - 1) & 1, sc);
+      else if (kt > 0) fold(7, 3, 1, sc_prev);
+      if (j == 1) {
+        if (i < 5) read_a(i + 3, PAR);
+        else read_a(i - 5, PAR ^ 1);
+      }
+      if (i == 7) read_b(j, bo1);
+      if (q < 16 && j == 2) b_load(kt + 2, i, bo2);
+      if (q >= 20 && q < 28 && (q & 1) == 0) a_load(kt + 2, (q - 20) >> 1, PAR);
+      if (q == 19) {
+        // Own reads of tile kt are complete and so are own loads of tile kt+1 (the 4 B loads issued
+        // since may still be in flight).  After the barrier tile kt+1 is readable by every wave and
+        // nobody reads the blocks of tile kt any more.
+        asm volatile("s_waitcnt vmcnt(4) lgkmcnt(0)" ::: "memory");
+        wg_barrier();
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    const int t = bo0;
+    bo0 = bo1, bo1 = bo2, bo2 = t;
+  };
+
+  // ---- prologue: tiles 0 and 1 of both operands
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a_load(0, i, 0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b_load(0, i, bo0);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) a_load(1, i, 1);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b_load(1, i, bo1);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   wg_barrier();
-  if (nk > 1) issue_loads(1, 1);
-  for (int kt = 0; kt < nk; ++kt) {
-    const int st = kt & 1;
-    const float sc = scaled ? sa[kt] * sb[kt] : 1.0f;
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+  for (int f = 0; f < 4; ++f) read_b(f, bo0);
 #pragma unroll
-      for (int j = 0; j < 4; ++j) fb[ks][j] = read_frag(fb_base, st, ks, j);
-    fa[0][0] = read_frag(fa_base, st, 0, 0);
-    fa[0][1] = read_frag(fa_base, st, 1, 0);
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      if (i + 1 < 4) {
-        fa[(i + 1) & 1][0] = read_frag(fa_base, st, 0, i + 1);
-        fa[(i + 1) & 1][1] = read_frag(fa_base, st, 1, i + 1);
-      } else {
-        // every LDS read of this step has been issued: once they land, stage st can be refilled
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        wg_barrier();
-        if (kt + 2 < nk) issue_loads(kt + 2, st);
-      }
-      if (scaled) {
-        // the 128-deep block is accumulated on its own, then scaled into the running sum
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          f32x16 part;
-#pragma unroll
-          for (int e = 0; e < 16; ++e) part[e] = 0.f;
-          part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[0][j], fa[i & 1][0], part, 0, 0, 0, 0, 0, 0);
-          part = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[1][j], fa[i & 1][1], part, 0, 0, 0, 0, 0, 0);
-#pragma unroll
-          for (int e = 0; e < 16; ++e) acc[i][j][e] = __builtin_fmaf(sc, part[e], acc[i][j][e]);
-        }
-      } else {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-          acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[0][j], fa[i & 1][0], acc[i][j], 0, 0, 0, 0, 0, 0);
-          acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(fb[1][j], fa[i & 1][1], acc[i][j], 0, 0, 0, 0, 0, 0);
-        }
-      }
+  for (int f = 0; f < 3; ++f) read_a(f, 0);
+
+  int kt = 0;
+  float sc = 1.0f, sc_prev = 1.0f;
+  for (int base = 0; base < nk; base += 64) {
+    const float scv = scales_from(base);
+    const int end = nk < base + 64 ? nk : base + 64;
+    sc = lane_value(scv, 0);
+    for (; kt + 1 < end; kt += 2) {
+      const float sc1 = lane_value(scv, (kt + 1) & 63);
+      step(I0{}, kt, sc, sc_prev);
+      const float sc2 = lane_value(scv, (kt + 2) & 63);
+      step(I1{}, kt + 1, sc1, sc);
+      sc_prev = sc1;
+      sc = sc2;
+    }
+    if (kt < end) {                                                // odd number of K-steps: the very last one
+      step(I0{}, kt, sc, sc_prev);
+      sc_prev = sc;
+      ++kt;
     }
   }
+  fold(7, 3, 1, sc_prev);
 
-  // ---- epilogue: one more barrier so that no wave overwrites fragments another wave is still to read
+  // ---- epilogue: all loads must have landed (they would overwrite the staging area) and no wave
+  //      may still read fragments
   asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
   wg_barrier();
-  store_tile_bf16(acc, lds, w, lane, (uint16_t*)g.C + (m0 + wm * 128) * g.ldc + n0 + wn * 128, g.ldc);
+  store_tile_bf16_w8_16(acc, lds, w, lane, (uint16_t*)g.C + (m0 + wm * 128) * g.ldc + n0 + wn * 64, g.ldc);
 }
 
 hipError_t launch_gemm_fp8_256(const GemmArgs& g, hipStream_t s) {
   unsigned nwg = (unsigned)(g.grid_m * g.grid_n);
-  hipLaunchKernelGGL(gemm_fp8_256_kernel, dim3(nwg), dim3(256), 0, s, g);
+  hipLaunchKernelGGL(gemm_fp8_256_kernel, dim3(nwg), dim3(512), 0, s, g);
   return hipGetLastError();
 }
 
