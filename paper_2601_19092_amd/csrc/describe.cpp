@@ -37,6 +37,7 @@ int ilog2(int64_t v) {
 struct Geo {
   bool big, fp8;
   int T, BK, F, ROWB, CE, EB;
+  int WM, WN;      // wave grid: wave = WN * wm + wn; A rows are split over wm, B rows over wn
   int key_shift;   // swizzle key = (row >> key_shift) & (chunks per row - 1)
   int64_t b_off;   // element offset of the B block inside one LDS stage
 };
@@ -48,17 +49,19 @@ Geo geometry(bool big, bool fp8) {
   g.EB = fp8 ? 1 : 2;
   g.CE = 16 / g.EB;
   g.ROWB = (fp8 || big) ? 128 : 64;
+  g.WM = 2;
+  g.WN = (big && fp8) ? 4 : 2;
+  g.F = 16;
   if (big) {
     g.T = 256;
-    g.F = fp8 ? 32 : 16;
   } else {
     g.T = 64;
     g.F = 16;
   }
   g.BK = g.ROWB / g.EB;
   g.key_shift = g.ROWB == 64 ? 2 : 1;
-  // bf16 256x256: five 32 KiB blocks, A in blocks 0 and 1, the B ring starts at block 2
-  g.b_off = (int64_t)g.T * g.BK * ((big && !fp8) ? 2 : 1);
+  // 256x256 kernels: five 32 KiB blocks, A in blocks 0 and 1, the B ring starts at block 2
+  g.b_off = (int64_t)g.T * g.BK * (big ? 2 : 1);
   return g;
 }
 
@@ -67,22 +70,18 @@ int g2l_threads(const Geo& g, bool is_b, Builder& b) {
   const int CH = g.ROWB / 16;                          // chunks per row
   std::vector<axe_iter_t> rows, ks;
   if (g.big) {
-    if (g.fp8) {
-      axe::set_error("axe_gemm_describe: the HBM -> LDS thread map of the fp8 256x256 kernel involves the wave id "
-                     "in its swizzle key and is not a single-axis swizzle");
-      return AXE_EUNSUPPORTED;
-    }
-    // one wave instruction = 1 KiB = 8 rows of 128 bytes; wave w takes row groups w, w + 4, ...:
-    // row = (4 i + w) * 8 + lr, chunk c.  A travels through registers (lane = 8 lr + c, piece i in
-    // registers 8 i .. 8 i + 7) and is swizzled by the LDS write.  B is loaded straight into LDS, which
-    // such a load fills linearly in the lane id, so the swizzle shows up in which chunk a lane
-    // fetches: c ^ key(row), key = (4 (w & 1) + (lr >> 1)) & 7.  That key spans the wave id, so the
-    // B map is stated on the thread id t = 64 w + lane, folded into the lane axis: key = (t >> 4) & 7.
-    const int NI = g.T / 32;
-    if (!is_b) {
-      rows = {{NI, g.CE, REG}, {4, 1, WAVE}, {8, CH, LANE}};
+    // one wave instruction = 1 KiB = 8 rows of 128 bytes; wave w of NW takes row groups w, w + NW, ...:
+    // row = (NW i + w) * 8 + lr, chunk c.  A operand that travels through registers (A of the bf16
+    // kernel: lane = 8 lr + c, piece i in registers CE i .. CE i + CE - 1) is swizzled by the LDS write.
+    // The others are loaded straight into LDS, which such a load fills linearly in the lane id, so
+    // the swizzle shows up in which chunk a lane fetches: c ^ key(row), key = (4 (w & 1) + (lr >> 1)) & 7.
+    // That key spans the wave id, so those maps are stated on the thread id t = 64 w + lane, folded
+    // into the lane axis: key = (t >> 4) & 7.
+    const int NW = g.WM * g.WN, NI = g.T / (8 * NW);
+    if (!is_b && !g.fp8) {
+      rows = {{NI, g.CE, REG}, {NW, 1, WAVE}, {8, CH, LANE}};
     } else {
-      rows = {{NI, g.CE, REG}, {4, 64, LANE}, {8, CH, LANE}};
+      rows = {{NI, g.CE, REG}, {NW, 64, LANE}, {8, CH, LANE}};
       b.swz(LANE, ilog2(CH), 0, ilog2(CH) + g.key_shift);
     }
     ks = {{CH, 1, LANE}, {g.CE, 1, REG}};
@@ -125,14 +124,17 @@ int lds_layout(const Geo& g, bool is_b, Builder& b) {
   return AXE_OK;
 }
 
-// (rows, k) tile -> MFMA operand registers.  Waves form a 2 x 2 grid (wave = 2 wm + wn); A rows are
-// split over wm and replicated over wn, B rows the other way round.
+// (rows, k) tile -> MFMA operand registers.  Waves form a WM x WN grid (wave = WN wm + wn); A rows are
+// split over wm and replicated over wn, B rows the other way round.  Register index = (k sub-step,
+// fragment, element): kernels that keep only a few fragments in registers at a time reuse the
+// physical registers, the index names the fragment.
 int operand_layout(const Geo& g, bool is_b, Builder& b) {
-  const int WT = g.T / 2, NF = WT / g.F;               // wave tile edge, fragments per wave tile edge
+  const int WT = is_b ? g.T / g.WN : g.T / g.WM;       // rows of this operand per wave
+  const int NF = WT / g.F;                             // fragments per wave
   const int LG = 64 / g.F;                             // lane groups along k
   const int KPL = g.fp8 ? 32 : 8;                      // k elements per lane per MFMA
   const int KS = g.BK / (LG * KPL);                    // MFMA k sub-steps per LDS tile
-  std::vector<axe_iter_t> rows = {{2, is_b ? 1 : 2, WAVE}, {NF, KPL, REG}, {g.F, 1, LANE}};
+  std::vector<axe_iter_t> rows = {{is_b ? g.WN : g.WM, is_b ? 1 : g.WN, WAVE}, {NF, KPL, REG}, {g.F, 1, LANE}};
   std::vector<axe_iter_t> ks;
   if (KS > 1) ks.push_back({KS, (int64_t)NF * KPL, REG});
   ks.push_back({LG, g.F, LANE});
@@ -146,24 +148,22 @@ int operand_layout(const Geo& g, bool is_b, Builder& b) {
     for (auto& it : rows) b.d.push_back(it);
     b.shape = {g.BK, g.T};
   }
-  b.R(2, is_b ? 2 : 1, WAVE);
+  b.R(is_b ? g.WM : g.WN, is_b ? g.WN : 1, WAVE);
   return AXE_OK;
 }
 
 // (M, N) of the (tile-padded) problem -> wg, wave, lane, reg: the accumulators.  Operands are
-// swapped in the MFMA, so a lane owns, per fragment, groups of 4 consecutive columns of one row.
+// swapped in the MFMA, so a lane owns, per 16 x 16 fragment, 4 consecutive columns of one row.
 int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Builder& b) {
-  const int WT = g.T / 2, NF = WT / g.F;
+  const int NFM = g.T / g.WM / g.F, NFN = g.T / g.WN / g.F;
   const int per_frag = g.F * g.F / 64;                 // accumulator registers per fragment
-  const int CG = g.F / (4 * (64 / g.F));               // groups of 4 columns per lane per fragment (32x32: 4, 16x16: 1)
   if (!tile_only) b.D(grid_m, grid_n, WG);
-  b.D(2, 2, WAVE);
-  b.D(NF, (int64_t)NF * per_frag, REG);
+  b.D(g.WM, g.WN, WAVE);
+  b.D(NFM, (int64_t)NFN * per_frag, REG);
   b.D(g.F, 1, LANE);
   if (!tile_only) b.D(grid_n, 1, WG);
-  b.D(2, 1, WAVE);
-  b.D(NF, per_frag, REG);
-  if (CG > 1) b.D(CG, 4, REG);
+  b.D(g.WN, 1, WAVE);
+  b.D(NFN, per_frag, REG);
   b.D(64 / g.F, g.F, LANE);
   b.D(4, 1, REG);
   if (tile_only) b.shape = {g.T, g.T};
@@ -172,14 +172,18 @@ int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Bui
 }
 
 // (T, T) tile of C -> wave, lane, reg: who stores which element.  The large tile goes through LDS
-// and is written row by row (16 lanes x 16 bytes per row); the small tile stores accumulators directly.
+// and is written row by row (16 bytes per lane); the small tile stores accumulators directly.
 int c_store_layout(const Geo& g, Builder& b) {
   if (!g.big) return acc_layout(g, 1, 1, true, b);
-  b.D(2, 2, WAVE);
-  b.D(32, 8, REG);
-  b.D(4, 16, LANE);
-  b.D(2, 1, WAVE);
-  b.D(16, 1, LANE);
+  // per wave: sub-tile of T / WM rows x T / WN columns; one store instruction writes 1 KiB = RPI rows of
+  // the sub-tile, LPR lanes x 8 elements per row
+  const int rows_w = g.T / g.WM, cols_w = g.T / g.WN;
+  const int LPR = cols_w / 8, RPI = 64 / LPR;
+  b.D(g.WM, g.WN, WAVE);
+  b.D(rows_w / RPI, 8, REG);
+  b.D(RPI, LPR, LANE);
+  b.D(g.WN, 1, WAVE);
+  b.D(LPR, 1, LANE);
   b.D(8, 1, REG);
   b.shape = {g.T, g.T};
   return AXE_OK;

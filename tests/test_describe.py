@@ -22,6 +22,8 @@ def desc_for(kind):
         M, N, K, dt, out, tile = 256, 256, 256, B.AXE_BF16, B.AXE_F32, B.AXE_TILE_AUTO
     elif kind == "small_fp8":
         M, N, K, dt, out, tile = 128, 192, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_64x64x32
+    elif kind == "big_fp8":
+        M, N, K, dt, out, tile = 512, 768, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_AUTO
     else:
         M, N, K, dt, out, tile = 512, 768, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_AUTO
     d = B.GemmDesc(M, N, K, dt, out, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, N)),
@@ -39,15 +41,17 @@ def table(L, shape):
     return R.evaluate_np(L, np.arange(prod(shape)), AXES)
 
 
-GEO = {"small_bf16": dict(T=64, BK=32, EB=2, waves=4), "small_fp8": dict(T=64, BK=128, EB=1, waves=4),
-       "big_bf16": dict(T=256, BK=64, EB=2, waves=4)}
+GEO = {"small_bf16": dict(T=64, BK=32, EB=2, waves=4, wn=2), "small_fp8": dict(T=64, BK=128, EB=1, waves=4, wn=2),
+       "big_bf16": dict(T=256, BK=64, EB=2, waves=4, wn=2), "big_fp8": dict(T=256, BK=128, EB=1, waves=8, wn=4)}
+KINDS = ["small_bf16", "small_fp8", "big_bf16", "big_fp8"]
+BIG = ("big_bf16", "big_fp8")
 
 
-@pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
+@pytest.mark.parametrize("kind", KINDS)
 def test_tile_shapes_and_kernel_choice(kind):
     desc, _ = desc_for(kind)
     geo = GEO[kind]
-    assert B.axe_gemm_tile(desc) == (B.AXE_TILE_256x256x64 if kind == "big_bf16" else B.AXE_TILE_64x64x32)
+    assert B.axe_gemm_tile(desc) == (B.AXE_TILE_256x256x64 if kind in BIG else B.AXE_TILE_64x64x32)
     for which, want in ((B.AXE_DESC_A_G2L_THREADS, (geo["T"], geo["BK"])), (B.AXE_DESC_B_G2L_THREADS, (geo["BK"], geo["T"])),
                         (B.AXE_DESC_A_LDS, (geo["T"], geo["BK"])), (B.AXE_DESC_B_LDS, (geo["BK"], geo["T"])),
                         (B.AXE_DESC_A_OPERAND, (geo["T"], geo["BK"])), (B.AXE_DESC_B_OPERAND, (geo["BK"], geo["T"])),
@@ -56,7 +60,7 @@ def test_tile_shapes_and_kernel_choice(kind):
         assert shape == want and ax.admits(L, shape)
 
 
-@pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
+@pytest.mark.parametrize("kind", KINDS)
 def test_accumulator_layout_is_a_bijection_and_a_tile_product(kind):
     desc, (M, N, K) = desc_for(kind)
     geo = GEO[kind]
@@ -65,31 +69,31 @@ def test_accumulator_layout_is_a_bijection_and_a_tile_product(kind):
     gm, gn = -(-M // T), -(-N // T)
     assert shape == (gm * T, gn * T)
     pts = table(L, shape)[:, 0, :]
-    regs = T * T // 256
-    box = np.stack(np.meshgrid(np.arange(gm * gn), np.arange(4), np.arange(64), np.arange(regs), indexing="ij"), -1).reshape(-1, 4)
+    NW, WN = geo["waves"], geo["wn"]
+    WM = NW // WN
+    regs = T * T // (64 * NW)
+    box = np.stack(np.meshgrid(np.arange(gm * gn), np.arange(NW), np.arange(64), np.arange(regs), indexing="ij"), -1).reshape(-1, 4)
     got = pts[:, [2, 3, 4, 5]]
     assert np.all(pts[:, [0, 1]] == 0)
     assert len(got) == len(box) and np.array_equal(np.unique(got, axis=0), box)      # every accumulator exactly once
-    # composition: grid (x) 2x2 waves (x) fragments-in-registers (x) MFMA accumulator fragment
+    # composition: grid (x) WM x WN waves (x) fragments-in-registers (x) MFMA accumulator fragment
     F = 16
-    NF = T // 2 // F
+    NFM, NFN = T // WM // F, T // WN // F
     per = F * F // 64
-    if F == 32:     # 32x32 fragment with swapped operands: row -> lane, column c = 8a + 4b + c' -> reg 4a + c', lane + 32 b
-        frag = Layout.make((32, 4, 2, 4), ("1@lane", "4@reg", "32@lane", "1@reg"))
-    else:           # 16x16: row -> lane, column 4b + c' -> lane + 16 b, reg c'
-        frag = Layout.make((16, 4, 4), ("1@lane", "16@lane", "1@reg"))
-    regs_t = Layout.make((NF, NF), (f"{NF}@reg", "1@reg"))
-    waves = Layout.make((2, 2), ("2@wave", "1@wave"))
+    # 16x16 fragment with swapped operands: row -> lane, column 4b + c' -> lane + 16 b, reg c'
+    frag = Layout.make((16, 4, 4), ("1@lane", "16@lane", "1@reg"))
+    regs_t = Layout.make((NFM, NFN), (f"{NFN}@reg", "1@reg"))
+    waves = Layout.make((WM, WN), (f"{WN}@wave", "1@wave"))
     grid = Layout.make((gm, gn), (f"{gn}@wg", "1@wg"))
-    t1, s1 = ax.tile(regs_t, (NF, NF), frag, (F, F))
-    t2, s2 = ax.tile(waves, (2, 2), t1, (NF * F, NF * F))
-    t3, s3 = ax.tile(grid, (gm, gn), t2, (T // 1, T // 1))
+    t1, s1 = ax.tile(regs_t, (NFM, NFN), frag, (F, F))
+    t2, s2 = ax.tile(waves, (WM, WN), t1, (NFM * F, NFN * F))
+    t3, s3 = ax.tile(grid, (gm, gn), t2, (T, T))
     assert ax.span(frag)["reg"] == per
     want = R.evaluate_np(t3, np.arange(prod(shape)), AXES)[:, 0, :]
     assert np.array_equal(want, pts)
 
 
-@pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
+@pytest.mark.parametrize("kind", KINDS)
 def test_global_to_lds_thread_map(kind):
     desc, _ = desc_for(kind)
     geo = GEO[kind]
@@ -101,24 +105,25 @@ def test_global_to_lds_thread_map(kind):
         Ll, sl = get(desc, which_l)
         assert st == sl == shape
         th = table(Lt, shape)[:, 0, :]
-        regs = T * BK // 256
+        NW = geo["waves"]
+        regs = T * BK // (64 * NW)
         key = (th[:, 3] * 64 + th[:, 4]) * regs + th[:, 5]
         assert np.array_equal(np.sort(key), np.arange(T * BK))           # every thread register exactly once
         lds = table(Ll, shape)[:, 0, 1]
         # B block: right after A in the small kernels; the 256x256 bf16 kernel keeps two A blocks first
-        base = 0 if which_l == B.AXE_DESC_A_LDS else T * BK * (2 if kind == "big_bf16" else 1)
+        base = 0 if which_l == B.AXE_DESC_A_LDS else T * BK * (2 if kind in BIG else 1)
         assert np.array_equal(np.sort(lds), np.arange(base, base + T * BK))   # LDS stage filled exactly once
         # each lane moves whole 16-byte chunks: CE consecutive registers <-> CE consecutive k <-> CE consecutive LDS elements
         order = np.argsort(key)
-        lds_by_thread = lds[order].reshape(4, 64, regs // CE, CE)
+        lds_by_thread = lds[order].reshape(NW, 64, regs // CE, CE)
         assert np.all(np.diff(lds_by_thread, axis=-1) == 1) and np.all(lds_by_thread[..., 0] % CE == 0)
-        if kind == "big_bf16":
+        if kind in BIG:
             # one wave instruction moves 8 rows x 128 bytes into a 1 KiB aligned piece of LDS
             first = lds_by_thread[..., 0] * EB                            # byte address of each lane's chunk
-            for w, i in itertools.product(range(4), range(regs // CE)):
+            for w, i in itertools.product(range(NW), range(regs // CE)):
                 b0 = first[w, :, i].min()
                 assert b0 % 1024 == 0
-                if which_l == B.AXE_DESC_B_LDS:
+                if which_l == B.AXE_DESC_B_LDS or kind == "big_fp8":
                     # direct-to-LDS load: lane l writes byte 16 l of the piece
                     assert np.array_equal(first[w, :, i], b0 + 16 * np.arange(64))
                 else:
@@ -139,7 +144,7 @@ def bank_conflicts(byte_addrs):
     return worst
 
 
-@pytest.mark.parametrize("kind", ["small_bf16", "small_fp8", "big_bf16"])
+@pytest.mark.parametrize("kind", KINDS)
 def test_operand_reads_cover_the_tile_and_are_bank_conflict_free(kind):
     desc, _ = desc_for(kind)
     geo = GEO[kind]
@@ -149,43 +154,49 @@ def test_operand_reads_cover_the_tile_and_are_bank_conflict_free(kind):
                                     (B.AXE_DESC_B_OPERAND, B.AXE_DESC_B_LDS, (BK, T))):
         Lo, _ = get(desc, which_o)
         Ll, _ = get(desc, which_l)
-        op = table(Lo, shape)                              # [E, 2 replicas, 6]
-        assert op.shape[1] == 2
-        regs = (T // 2) * BK // 64
+        NW, WN = geo["waves"], geo["wn"]
+        WM = NW // WN
+        is_b = which_o == B.AXE_DESC_B_OPERAND
+        repl = WM if is_b else WN                              # waves that hold the same operand rows
+        op = table(Lo, shape)                                  # [E, replicas, 6]
+        assert op.shape[1] == repl
+        regs = (T // (WN if is_b else WM)) * BK // 64
         key = ((op[:, :, 3] * 64 + op[:, :, 4]) * regs + op[:, :, 5]).reshape(-1)
-        assert np.array_equal(np.sort(key), np.arange(4 * 64 * regs))     # each wave holds its half, once
+        assert np.array_equal(np.sort(key), np.arange(NW * 64 * regs))     # each wave holds its share, once
         for swz, expect_clean in ((True, True), (False, False)):
             L = Ll if swz else Ll.with_(swizzle=None)
-            lds = np.repeat(table(L, shape)[:, 0, 1], 2)
-            addr = np.empty(4 * 64 * regs, dtype=np.int64)
+            lds = np.repeat(table(L, shape)[:, 0, 1], repl)
+            addr = np.empty(NW * 64 * regs, dtype=np.int64)
             addr[key] = lds * EB
-            addr = addr.reshape(4, 64, regs // CE, CE)[..., 0]             # byte address of each 16-byte read
-            worst = max(bank_conflicts(addr[w, :, i]) for w in range(4) for i in range(addr.shape[2]))
+            addr = addr.reshape(NW, 64, regs // CE, CE)[..., 0]            # byte address of each 16-byte read
+            worst = max(bank_conflicts(addr[w, :, i]) for w in range(NW) for i in range(addr.shape[2]))
             assert (worst == 1) == expect_clean, (kind, which_o, swz, worst)
 
 
-@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16"])
+@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16", "big_fp8"])
 def test_c_store_map(kind):
     desc, _ = desc_for(kind)
-    T = GEO[kind]["T"]
+    T, NW, WN = GEO[kind]["T"], GEO[kind]["waves"], GEO[kind]["wn"]
     L, shape = get(desc, B.AXE_DESC_C_STORE)
     pts = table(L, shape)[:, 0, :]
-    regs = T * T // 256
+    regs = T * T // (64 * NW)
     key = (pts[:, 3] * 64 + pts[:, 4]) * regs + pts[:, 5]
     assert np.array_equal(np.sort(key), np.arange(T * T))
-    if kind == "big_bf16":
-        # one store instruction (8 consecutive registers of every lane): 4 rows x 256 contiguous bytes
+    if kind in BIG:
+        # one store instruction (8 consecutive registers of every lane): whole rows of the wave's sub-tile,
+        # T / WN * 2 contiguous bytes each
         col = np.empty(T * T, dtype=np.int64); row = np.empty(T * T, dtype=np.int64)
         idx = np.arange(T * T)
         row[key], col[key] = idx // T, idx % T
-        row, col = row.reshape(4, 64, regs // 8, 8), col.reshape(4, 64, regs // 8, 8)
+        row, col = row.reshape(NW, 64, regs // 8, 8), col.reshape(NW, 64, regs // 8, 8)
         assert np.all(np.diff(col, axis=-1) == 1) and np.all(row[..., 0:1] == row)
-        for w, t in itertools.product(range(4), range(regs // 8)):
+        lpr = T // WN // 8                                   # lanes per row
+        for w, t in itertools.product(range(NW), range(regs // 8)):
             r, c = row[w, :, t, 0], col[w, :, t, 0]
-            assert len(set(r.tolist())) == 4
+            assert len(set(r.tolist())) == 64 // lpr
             for rr in set(r.tolist()):
                 cs = np.sort(c[r == rr])
-                assert np.array_equal(cs, cs[0] + 8 * np.arange(16)) and cs[0] % 128 == 0
+                assert np.array_equal(cs, cs[0] + 8 * np.arange(lpr)) and cs[0] % (8 * lpr) == 0
 
 
 def test_mfma_operand_layout_matches_its_statement():
