@@ -208,14 +208,14 @@ def main():
                                "fp32 accumulate, bf16 output; 256x256x64 tiles described as Axe layouts"},
         "roofline": {"bound": "mfma", "achieved": head["kernel_tflops"], "peak": PEAK["bf16"], "unit": "TFLOP/s",
                      "frac": head["kernel_tflops"] / PEAK["bf16"], "traffic": None,
-                     "kernel": "gemm_256_kernel<bf16>", "flops_per_launch": flops, "kernel_ms": head["kernel_ms"]},
+                     "kernel": "gemm_bf16_256_kernel", "flops_per_launch": flops, "kernel_ms": head["kernel_ms"]},
         "cpu_baseline": cpu,
         "companions": comp,
     }
     tr = os.path.join(ROOT, "profiles", "traffic.json")
     if os.path.exists(tr):
         try:
-            line["roofline"]["traffic"] = json.load(open(tr)).get("gemm_256_kernel_bf16_bytes_per_launch")
+            line["roofline"]["traffic"] = json.load(open(tr)).get("gemm_bf16_256_kernel_bytes_per_launch")
         except Exception:
             pass
     print(json.dumps(line), flush=True)

@@ -162,7 +162,11 @@ int axe_gemm_tile(const axe_gemm_desc_t* g);
  *   shape, rank : receive the logical shape the layout admits (up to AXE_MAX_RANK entries).
  *   arena, arena_bytes : caller-provided HOST scratch (2 KiB is enough).
  * Axis names used: "m" (HBM element address), "lds" (LDS element address), "wg", "wave", "lane",
- * "reg" (index of the element inside the lane's fragment / accumulator / per-thread loop). */
+ * "reg" (index of the element inside the lane's fragment / accumulator / per-thread loop).
+ * In the thread maps of operands that are loaded straight into LDS by the 256 x 256 kernels the
+ * swizzle key spans the wave id; those maps are stated on the thread id, folded into the "lane"
+ * axis as lane + 64 * wave (extent 64 * waves), with "wave" unused.
+ * AXE_EUNSUPPORTED is never returned for a descriptor axe_gemm accepts. */
 enum {
   AXE_DESC_A_G2L_THREADS = 0, /* (BM, BK) tile of A  -> wave, lane, reg : who fetches which element  */
   AXE_DESC_B_G2L_THREADS = 1,
