@@ -304,7 +304,10 @@ def test_gemm_fp8_small_tile(M, N, K, scaled):
 
 
 # ----------------------------------------------------------------------------- large tile (256 x 256)
-@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 256, 128), (512, 768, 192), (768, 256, 1024)])
+# K = 64 nk: nk = 1, 2, 3 (shorter than the pipeline), 16 (two rotation windows), 11 and 9 (a window plus an
+# unrotated tail, odd number of K-steps); several tiles so that the workgroups rotate differently
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 256, 128), (512, 768, 192), (768, 256, 1024),
+                                   (512, 768, 704), (768, 512, 576)])
 def test_gemm_bf16_large_tile(M, N, K):
     g = W.gemm_bf16(M, N, K, 70 + K)
     c = run_gemm(g, tile=B.AXE_TILE_256x256x64)
@@ -325,7 +328,8 @@ def test_gemm_bf16_large_tile_identity_pitched_and_device_axis():
     check_gemm(c, oracle_gemm(g4), BF16_TOL)
 
 
-@pytest.mark.parametrize("M,N,K,scaled", [(256, 256, 128, False), (256, 512, 384, True), (512, 256, 256, True)])
+@pytest.mark.parametrize("M,N,K,scaled", [(256, 256, 128, False), (256, 512, 384, True), (512, 256, 256, True),
+                                          (512, 768, 1408, True), (768, 512, 2048, False), (256, 256, 8960, True)])
 def test_gemm_fp8_large_tile(M, N, K, scaled):
     g = W.gemm_fp8(M, N, K, 80 + K, scaled=scaled)
     c = run_gemm(g, tile=B.AXE_TILE_256x256x64)
