@@ -171,10 +171,12 @@ int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Bui
   return AXE_OK;
 }
 
-// (T, T) tile of C -> wave, lane, reg: who stores which element.  The large tile goes through LDS
-// and is written row by row (16 bytes per lane); the small tile stores accumulators directly.
+// (T, T) tile of C -> wave, lane, reg: who stores which element.  The fp8 256 x 256 kernel stages
+// the tile in LDS and writes it row by row (16 bytes per lane).
 int c_store_layout(const Geo& g, Builder& b) {
-  if (!g.big) return acc_layout(g, 1, 1, true, b);
+  // the 64 x 64 kernels and the bf16 256 x 256 kernel store accumulator fragments directly: the
+  // store map is the accumulator layout of one tile (8 bytes of bf16 per lane and fragment)
+  if (!g.big || !g.fp8) return acc_layout(g, 1, 1, true, b);
   // per wave: sub-tile of T / WM rows x T / WN columns; one store instruction writes 1 KiB = RPI rows of
   // the sub-tile, LPR lanes x 8 elements per row
   const int rows_w = g.T / g.WM, cols_w = g.T / g.WN;

@@ -27,11 +27,12 @@
 //                 16x16x32 operand layout (8 consecutive k per lane).
 //   MFMA        : operands swapped (B fragment first) so that a lane's accumulator fragment holds 4
 //                 consecutive columns of one C row.
-//   VGPR -> HBM : accumulators -> bf16 -> LDS -> 16-byte coalesced stores.
+//   VGPR -> HBM : accumulators -> bf16, 8 bytes per lane and fragment, stored directly (the eight
+//                 fragments of a fragment row complete 256 contiguous bytes per row; L2 merges them).
 //
 // Schedule.  A K-step is two sub-steps of 64 MFMAs; a sub-step also reads the 16 fragments of the
 // next sub-step and moves 4 pieces of each operand.  One workgroup barrier per K-step, after sub-step
-// 0: by then every LDS read of tile kt has completed, and the barrier publishes tile kt+1.  With one
+// 0: by then every LDS read of step kt has completed, and the barrier publishes step kt+1.  With one
 // wave per SIMD nothing hides a late load, and a memory system that busy answers late (a wave's
 // loads of one K-tile complete 1500 - 2300 cycles after issue), so every load gets at least a full
 // K-step (2048 MFMA cycles), most of them one and a half to two.  160 KiB of LDS hold five 32 KiB
@@ -40,6 +41,11 @@
 //   B: buffer_load ... lds (direct to LDS) into the ring of three blocks, 1 to 1.5 K-steps ahead;
 //   A: buffer_load into 16 x 4 staging registers per lane two K-steps ahead, ds_write_b128 into the
 //      double-buffered block half a K-step to one K-step ahead of use.
+//
+// Tiles.  When there are more tiles than CUs (and the number of K-steps is even and at least 4) one
+// workgroup per CU walks its tiles back to back: the load side simply runs on into the next tile's
+// first K-steps, so only the first tile of a workgroup has a prologue, and a tile's stores overlap
+// the arrival of the next tile's operands.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -71,26 +77,59 @@ __device__ __forceinline__ void mfma_16x16x32(f32x4& acc, bf16x8 a, bf16x8 b) {
 }
 }  // namespace
 
+// Output descriptor words for a buffer store issued as an asm statement (see store_fragment).
+__device__ __forceinline__ i32x4 raw_rsrc(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  // the words are wave-uniform by construction; readfirstlane tells the compiler so (they must sit in SGPRs)
+  return i32x4{__builtin_amdgcn_readfirstlane((int)(uint32_t)a), __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu)),
+               __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
+}
+
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
-  uint8_t* const lds = lds_mem;                                    // generic view, for the epilogue
-  const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses for the main loop
+  const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);          // wave id 0..3, kept scalar
   const int wm = w >> 1, wn = w & 1;                               // wave grid 2 x 2
-  int tm, tn;
-  tile_of_block(blockIdx.x, gridDim.x, g.grid_m, g.grid_n, tm, tn);
-  const int64_t m0 = (int64_t)tm * kTile, n0 = (int64_t)tn * kTile;
   const int nk = (int)(g.K / 64);
-  // K rotation: each workgroup walks every aligned window of kRot K-tiles in its own rotated order
-  // (the sum over k does not care), so that the workgroups sharing a panel fetch the kRot adjacent
-  // lines of a row at once -- one 1 KiB burst per row -- and find the other lines in L2 during the
-  // rest of the window (measured on the bare load stream: 16 -> 21.5 TB/s).
-  const int rot = (tm + tn) & (kRot - 1);
-  const int nk_rot = nk & ~(kRot - 1);                             // tiles beyond the last full window keep their order
-  auto kcol = [&](int T) -> int {                                  // K-tile visited at position T -> byte column
+  const int ntiles = g.grid_m * g.grid_n;
+  const int nk_rot = nk & ~(kRot - 1);                             // K-tiles beyond the last full rotation window keep their order
+
+  // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ...  The load side of the
+  //      pipeline runs two to four K-steps ahead of the MFMAs and crosses into the next tile before
+  //      the current one is finished, so two tiles are described at any time: cur and nxt.
+  const int a_pitch = (int)(g.lda * 2), b_pitch = (int)(g.ldb * 2);
+  struct Tile {
+    __amdgpu_buffer_rsrc_t ra, rb;
+    int rot;
+  };
+  auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
+    Tile t;
+    if (v < ntiles) {
+      int tm, tn;
+      tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
+      t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda * 2), 0,
+                                               255 * a_pitch + (int)g.K * 2, 0x00020000);
+      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * kTile * g.ldb * 2), 0,
+                                               255 * b_pitch + (int)g.K * 2, 0x00020000);
+      // K rotation: each workgroup walks every aligned window of kRot K-tiles in its own rotated order
+      // (the sum over k does not care), so that the workgroups sharing a panel fetch the kRot adjacent
+      // lines of a row at once -- one 1 KiB burst per row -- and find the other lines in L2 during the
+      // rest of the window (measured on the bare load stream: 16 -> 21.5 TB/s).
+      t.rot = (tm + tn) & (kRot - 1);
+    } else {                                                       // no such tile: every load returns zero
+      t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
+      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
+      t.rot = 0;
+    }
+    return t;
+  };
+  int v = blockIdx.x;
+  Tile cur = describe(v), nxt = describe(v + (int)gridDim.x);
+  // K-step T of the current tile (T >= nk: step T - nk of the next one) -> byte column
+  auto kcol = [&](int T, int rot) -> int {
     const int t = T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T;
     return t * kRow;
   };
@@ -101,11 +140,6 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
   //      piece go into the scalar offset.
   const int lr = lane >> 3, lp = lane & 7;
   const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 4 i) * 8 + lr
-  const int a_pitch = (int)(g.lda * 2), b_pitch = (int)(g.ldb * 2);
-  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)((const uint8_t*)g.A + m0 * g.lda * 2), 0, 255 * a_pitch + (int)g.K * 2, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)((const uint8_t*)g.B + n0 * g.ldb * 2), 0, 255 * b_pitch + (int)g.K * 2, 0x00020000);
   const int a_voff = (w * 8 + lr) * a_pitch + lp * 16;
   const int a_voff_x = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
   const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
@@ -113,21 +147,25 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
   const lds_u8 a_wr = lds3 + (w * 8 + lr) * kRow + ((lp ^ lkey) << 4);    // + stage * kBlk + i * 4096
 
   u32x4 stg[16];                                                   // A staging: slot (T & 1) * 8 + i
-  auto a_load = [&](int T, int i) -> u32x4 {
-    return __builtin_amdgcn_raw_buffer_load_b128(ra, a_voff, i * a_piece + kcol(T), 0);
+  // cross = false: the caller knows T < nk (steady part of the K loop), nothing of the next tile is looked at
+  auto a_load = [&](int T, int i, bool cross) __attribute__((always_inline)) -> u32x4 {
+    const bool nx = cross && T >= nk;
+    return __builtin_amdgcn_raw_buffer_load_b128(nx ? nxt.ra : cur.ra, a_voff,
+                                                 i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)), 0);
   };
-  auto a_write = [&](int stage, int i, u32x4 v) {
+  auto a_write = [&](int stage, int i, u32x4 v) __attribute__((always_inline)) {
     *(__attribute__((address_space(3))) u32x4*)(a_wr + stage * kBlk + i * 4096) = v;
   };
   auto a_direct = [&](int T, int i, int stage) {                   // prologue only
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr)(lds3 + stage * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                             i * a_piece + kcol(T), 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(cur.ra, (lds_ptr)(lds3 + stage * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
+                                             i * a_piece + kcol(T, cur.rot), 0, 0);
   };
-  // B ring: byte offsets of the blocks that hold tiles kt, kt+1, kt+2 (tile kt+3 reuses the first)
+  // B ring: byte offsets of the blocks that hold K-steps kt, kt+1, kt+2 (step kt+3 reuses the first)
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
-  auto b_load = [&](int T, int i, int slot_off) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16, b_voff,
-                                             i * b_piece + kcol(T), 0, 0);
+  auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
+    const bool nx = cross && T >= nk;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16,
+                                             b_voff, i * b_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)), 0, 0);
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16
@@ -150,26 +188,53 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
 
   bf16x8 fa[8], fb[2][8];    // A fragment i serves one row of 8 MFMAs and is re-read right after it; B is double-buffered
 
+  // ---- VGPR -> HBM.  Operands are swapped in the MFMA, so lane l holds, for fragment (i, j), the 4
+  //      consecutive columns j*16 + 4*(l/16) .. +3 of row i*16 + l%16 of the wave's 128 x 128 sub-tile:
+  //      8 bytes of bf16.  The eight stores of a fragment row fill 256 contiguous bytes of 16 rows one after
+  //      the other; L2 merges them into whole lines.  The store is an asm statement so that the
+  //      compiler's wait-count bookkeeping, which would otherwise turn every counted wait for a load
+  //      into a wait for everything while a store is pending, does not see it: stores and loads share
+  //      the hardware counter, but a counted wait for a load stays valid with stores in between,
+  //      because loads complete in order among themselves.
+  i32x4 rc;                                                        // descriptor of this wave's part of the C tile
+  int c_rowblk;                                                    // bytes between fragment rows
+  const int c_voff = (int)((fr * g.ldc + 4 * fq) * 2);
+  auto set_output = [&](int vv) __attribute__((always_inline)) {
+    int tm, tn;
+    tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
+    rc = raw_rsrc((uint16_t*)g.C + ((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * kTile + wn * 128,
+                  (uint32_t)((127 * g.ldc + 128) * 2));
+    c_rowblk = (int)(16 * g.ldc * 2);
+  };
+  auto store_fragment = [&](int i, int j) __attribute__((always_inline)) {
+    typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+    const u32x2 d = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
+    const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
+    asm volatile("buffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile
+  };
+
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
 
   // Sub-step S of K-step kt (PAR = kt & 1), in exact program order (sched_barrier(0) forbids any
   // reordering across it): 64 MFMAs, (i, j) with j innermost; in the first half the 8 B fragments of
   // the next sub-step are read into the other buffer, and after each row i the A fragment i of the
-  // next sub-step replaces the one just used; after MFMAs 2, 18, 34, 50 one B load, after MFMAs 10, 26, 42, 58 one
-  // staged A piece goes to LDS and its slot is reloaded.  Nothing is guarded against the end of K:
-  // loads of tiles past the end stay inside the buffer descriptors, land in slots and blocks that
-  // are free by then, and are never multiplied.
-  auto substep = [&](auto par_c, auto s_c, int kt) {
+  // next sub-step replaces the one just used; after MFMAs 2, 18, 34, 50 one B load, after MFMAs 10,
+  // 26, 42, 58 one staged A piece goes to LDS and its slot is reloaded.  Steps past the end of the
+  // tile are steps of the workgroup's next tile (or of none: then their loads return zero).
+  auto substep = [&](auto par_c, auto s_c, auto cross_c, int kt) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value, S = decltype(s_c)::value;
+    constexpr bool CROSS = decltype(cross_c)::value != 0;          // the loads of this step may belong to the next tile
     constexpr int CUR = S, NXT = S ^ 1;
-    // fragments read now: sub-step 1 of this tile, or sub-step 0 of the next one
-    constexpr int RST = S == 0 ? PAR : PAR ^ 1;                    // A stage of that tile
+    // fragments read now: sub-step 1 of this step, or sub-step 0 of the next one
+    constexpr int RST = S == 0 ? PAR : PAR ^ 1;                    // A stage of that step
     const lds_u8 pa = fax[NXT] + RST * kBlk;
     const lds_u8 pb = fbx[NXT] + (S == 0 ? bo0 : bo1);
-    // A pieces written now: 4..7 of tile kt+1 (sub-step 0) or 0..3 of tile kt+2 (sub-step 1); the slot
-    // is reloaded with the same piece two tiles later.  B pieces loaded now: 4..7 of tile kt+2 into
-    // its ring block (sub-step 0) or 0..3 of tile kt+3 into the block tile kt has just left (sub-step 1).
+    // A pieces written now: 4..7 of step kt+1 (sub-step 0) or 0..3 of step kt+2 (sub-step 1); the slot
+    // is reloaded with the same piece two steps later.  B pieces loaded now: 4..7 of step kt+2 into
+    // its ring block (sub-step 0) or 0..3 of step kt+3 into the block step kt has just left (sub-step 1).
     constexpr int WST = S == 0 ? PAR ^ 1 : PAR;
     const int wT = S == 0 ? kt + 1 : kt + 2;
     const int bT = S == 0 ? kt + 2 : kt + 3;
@@ -181,50 +246,57 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
       __builtin_amdgcn_sched_barrier(0);
       if ((q & 3) == 1 && q < 32) fb[NXT][q >> 2] = lds_read(pb + (q >> 2) * 16 * kRow);
       if ((q & 7) == 7) fa[i] = lds_read(pa + i * 16 * kRow);
-      if ((q & 15) == 2) b_load(bT, (S == 0 ? 4 : 0) + (q >> 4), bslot);
+      if ((q & 15) == 2) b_load(bT, (S == 0 ? 4 : 0) + (q >> 4), bslot, CROSS);
       if ((q & 15) == 10) {
         const int p = (S == 0 ? 4 : 0) + (q >> 4);
         // the load that filled this slot was issued 4 sub-steps ago; 31 loads have been issued since
         asm volatile("s_waitcnt vmcnt(31)" ::: "memory");
         a_write(WST, p, stg[WST * 8 + p]);
-        stg[WST * 8 + p] = a_load(wT + 2, p);
+        stg[WST * 8 + p] = a_load(wT + 2, p, CROSS);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
     if (S == 0) {
-      // Own reads of tile kt and own writes of tile kt+1 are complete, and so are own B loads of tile
-      // kt+1 (the 17 younger loads may still be in flight).  After the barrier tile kt+1 is readable
-      // by every wave and nobody reads tile kt any more.
+      // Own reads of step kt and own writes of step kt+1 are complete, and so are own B loads of step
+      // kt+1 (the 17 younger loads may still be in flight).  After the barrier step kt+1 is readable
+      // by every wave and nobody reads step kt any more.
       asm volatile("s_waitcnt vmcnt(17) lgkmcnt(0)" ::: "memory");
       wg_barrier();
     }
   };
-  auto step = [&](auto par_c, int kt) {
-    substep(par_c, I0{}, kt);
-    substep(par_c, I1{}, kt);
+  auto step = [&](auto par_c, auto cross_c, int kt) __attribute__((always_inline)) {
+    substep(par_c, I0{}, cross_c, kt);
+    substep(par_c, I1{}, cross_c, kt);
     const int t = bo0;
     bo0 = bo1, bo1 = bo2, bo2 = t;
   };
 
-  // ---- prologue: what the sub-steps before (0, 0) would have done.  Tile 0 and pieces 0..3 of tile 1
-  //      of A go straight to LDS; the staging slots are filled oldest first in the order the loop
-  //      consumes them, so that the counted waits of the first steps hold as well.
+  // ---- prologue (first tile only): what the sub-steps before (0, 0) would have done.  Step 0 and
+  //      pieces 0..3 of step 1 of A go straight to LDS; the staging slots are filled oldest first in
+  //      the order the loop consumes them, so that the counted waits of the first steps hold as well.
 #pragma unroll
   for (int i = 0; i < 8; ++i) a_direct(0, i, 0);
+  if (nk > 1) {
 #pragma unroll
-  for (int i = 0; i < 4; ++i) a_direct(1, i, 1);
+    for (int i = 0; i < 4; ++i) a_direct(1, i, 1);
+  } else {                                                         // a single K-step per tile: step 1 belongs to the next tile
 #pragma unroll
-  for (int i = 4; i < 8; ++i) stg[8 + i] = a_load(1, i);
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(nxt.ra, (lds_ptr)(lds3 + kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
+                                               i * a_piece + kcol(0, nxt.rot), 0, 0);
+  }
 #pragma unroll
-  for (int i = 0; i < 8; ++i) stg[i] = a_load(2, i);
+  for (int i = 4; i < 8; ++i) stg[8 + i] = a_load(1, i, true);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) stg[8 + i] = a_load(3, i);
+  for (int i = 0; i < 8; ++i) stg[i] = a_load(2, i, true);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) b_load(0, i, bo0);
+  for (int i = 0; i < 4; ++i) stg[8 + i] = a_load(3, i, true);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) b_load(1, i, bo1);
+  for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) b_load(2, i, bo2);
+  for (int i = 0; i < 8; ++i) b_load(1, i, bo1, true);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b_load(2, i, bo2, true);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   wg_barrier();
 #pragma unroll
@@ -232,22 +304,49 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
 #pragma unroll
   for (int f = 0; f < 8; ++f) fa[f] = lds_read(fax[0] + f * 16 * kRow);
 
-  int kt = 0;
-  for (; kt + 1 < nk; kt += 2) {
-    step(I0{}, kt);
-    step(I1{}, kt + 1);
+  // ---- all K-steps of all tiles of this workgroup, one uninterrupted pipeline.  The host launches
+  //      more than one tile per workgroup only when nk is even (the A stage and staging slots of a
+  //      step are chosen by its parity, which must continue across the tile boundary) and at least 4
+  //      (the load side looks at most one tile ahead).
+  for (;;) {
+    set_output(v);
+    int kt = 0;
+    for (; kt + 5 < nk; kt += 2) {                                 // every load of these steps is of this tile (at most step kt + 5)
+      step(I0{}, I0{}, kt);
+      step(I1{}, I0{}, kt + 1);
+    }
+    for (; kt + 1 < nk; kt += 2) {                                 // the last steps load the next tile's first K-steps
+      step(I0{}, I1{}, kt);
+      step(I1{}, I1{}, kt + 1);
+    }
+    if (kt < nk) step(I0{}, I1{}, kt);                             // odd nk: only with one tile per workgroup
+    // the tile is complete: store it while the loads of the next tile's first K-steps, issued by the
+    // steps above, are on their way; the MFMAs have to retire before their results are read
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) store_fragment(i, j);
+    v += (int)gridDim.x;
+    if (v >= ntiles) break;
+    cur = nxt;
+    nxt = describe(v + (int)gridDim.x);
   }
-  if (kt < nk) step(I0{}, kt);
-
-  // ---- epilogue: all loads must have landed (they would overwrite the staging area) and no wave
-  //      may still read fragments
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-  wg_barrier();
-  store_tile_bf16_16(acc, lds, w, lane, (uint16_t*)g.C + (m0 + wm * 128) * g.ldc + n0 + wn * 128, g.ldc);
 }
 
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
-  unsigned nwg = (unsigned)(g.grid_m * g.grid_n);
+  const int ntiles = g.grid_m * g.grid_n;
+  const int nk = (int)(g.K / 64);
+  static int cus = 0;
+  if (!cus) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cus = n;
+  }
+  // one resident workgroup per CU walks several tiles when the pipeline can continue across tiles
+  const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
+  unsigned nwg = (unsigned)(chain ? cus : ntiles);
   hipLaunchKernelGGL(gemm_bf16_256_kernel, dim3(nwg), dim3(256), 0, s, g);
   return hipGetLastError();
 }
