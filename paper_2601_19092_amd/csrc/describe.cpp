@@ -174,21 +174,9 @@ int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Bui
 // (T, T) tile of C -> wave, lane, reg: who stores which element.  The fp8 256 x 256 kernel stages
 // the tile in LDS and writes it row by row (16 bytes per lane).
 int c_store_layout(const Geo& g, Builder& b) {
-  // the 64 x 64 kernels and the bf16 256 x 256 kernel store accumulator fragments directly: the
-  // store map is the accumulator layout of one tile (8 bytes of bf16 per lane and fragment)
-  if (!g.big || !g.fp8) return acc_layout(g, 1, 1, true, b);
-  // per wave: sub-tile of T / WM rows x T / WN columns; one store instruction writes 1 KiB = RPI rows of
-  // the sub-tile, LPR lanes x 8 elements per row
-  const int rows_w = g.T / g.WM, cols_w = g.T / g.WN;
-  const int LPR = cols_w / 8, RPI = 64 / LPR;
-  b.D(g.WM, g.WN, WAVE);
-  b.D(rows_w / RPI, 8, REG);
-  b.D(RPI, LPR, LANE);
-  b.D(g.WN, 1, WAVE);
-  b.D(LPR, 1, LANE);
-  b.D(8, 1, REG);
-  b.shape = {g.T, g.T};
-  return AXE_OK;
+  // every kernel stores its accumulator fragments directly: the store map is the accumulator layout
+  // of one tile (8 bytes of bf16 per lane and fragment)
+  return acc_layout(g, 1, 1, true, b);
 }
 
 }  // namespace

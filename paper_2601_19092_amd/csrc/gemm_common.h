@@ -14,10 +14,6 @@ typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 
 constexpr int kTile = 256;                        // workgroup tile edge (M and N)
-constexpr int kEpiPitch = 272;                    // bytes per accumulator row in the epilogue staging
-constexpr int kEpiB = 4 * 128 * kEpiPitch;        // 139264 bytes: 4 waves x 128 rows
-constexpr int kEpiPitch8 = 144;                   // same for the 8-wave kernels (128 x 64 per wave)
-constexpr int kEpiB8 = 8 * 128 * kEpiPitch8;      // 147456 bytes: 8 waves x 128 rows
 
 // Workgroup barrier without the memory fence of __syncthreads().  That fence waits for every
 // outstanding global load (vmcnt(0)), which would drain the load pipeline at each K step; the
@@ -65,118 +61,25 @@ __device__ __forceinline__ void tile_of_block(int bid, int nwg, int grid_m, int 
   tn = in_group / gsz;
 }
 
-// Epilogue of a 256 x 256 tile held as 4 x 4 MFMA 32x32 accumulator fragments per wave (operands
-// swapped: lane l holds, for fragment (i, j) and a = 0..3, the 4 consecutive columns
-// j*32 + 8a + 4*(l/32) .. +3 of row i*32 + l%32).  Each wave converts to bf16, stages its 128 x 128
-// sub-tile in its own LDS region (row pitch 272 bytes) and writes it out with 16-byte stores, 256
-// contiguous bytes per row.  The caller guarantees that no wave still reads the pipeline stages.
-__device__ __forceinline__ void store_tile_bf16(const f32x16 (&acc)[4][4], uint8_t* lds, int w, int lane, uint16_t* C,
-                                                int64_t ldc) {
-  const int fr = lane & 31, fh = lane >> 5;
-  uint8_t* ew = lds + w * 128 * kEpiPitch;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j)
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        uint2 v = {pack_bf16(acc[i][j][4 * a + 0], acc[i][j][4 * a + 1]),
-                   pack_bf16(acc[i][j][4 * a + 2], acc[i][j][4 * a + 3])};
-        *(uint2*)(ew + (i * 32 + fr) * kEpiPitch + (j * 32 + 8 * a + 4 * fh) * 2) = v;
-      }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_wave_barrier();
-  const int er = lane >> 4, ec = lane & 15;
-#pragma unroll 4
-  for (int t = 0; t < 32; ++t) {
-    int row = t * 4 + er;
-    uint4 v = *(const uint4*)(ew + row * kEpiPitch + ec * 16);
-    *(uint4*)(C + (int64_t)row * ldc + ec * 8) = v;
-  }
+// Descriptor words for a buffer store issued as an asm statement: base address, byte range, raw
+// 32-bit data format.  The words are wave-uniform by construction; readfirstlane tells the compiler so
+// (they must sit in SGPRs).
+__device__ __forceinline__ i32x4 raw_rsrc(const void* p, uint32_t bytes) {
+  const uint64_t a = (uint64_t)p;
+  return i32x4{__builtin_amdgcn_readfirstlane((int)(uint32_t)a), __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu)),
+               __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
 }
 
-// Epilogue of a 256 x 256 tile held by 4 waves as 8 x 8 MFMA 16x16 accumulator fragments each
-// (operands swapped: lane l holds, for fragment (i, j), the 4 consecutive columns
-// j*16 + 4*(l/16) .. +3 of row i*16 + l%16 of the wave's 128 x 128 sub-tile).  Each wave converts to
-// bf16, stages its sub-tile in its own LDS region (row pitch 272 bytes: the 8-byte writes of a
-// wave instruction fall on 64 distinct banks) and writes it out with 16-byte stores, 256
-// contiguous bytes per row.  The caller guarantees that no wave still reads the pipeline stages.
-__device__ __forceinline__ void store_tile_bf16_16(const f32x4 (&acc)[8][8], uint8_t* lds, int w, int lane,
-                                                   uint16_t* C, int64_t ldc) {
-  const int fr = lane & 15, fq = lane >> 4;
-  uint8_t* ew = lds + w * 128 * kEpiPitch;
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      uint2 v = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
-      *(uint2*)(ew + (i * 16 + fr) * kEpiPitch + (j * 16 + 4 * fq) * 2) = v;
-    }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_wave_barrier();
-  const int er = lane >> 4, ec = lane & 15;
-#pragma unroll 4
-  for (int t = 0; t < 32; ++t) {
-    int row = t * 4 + er;
-    uint4 v = *(const uint4*)(ew + row * kEpiPitch + ec * 16);
-    *(uint4*)(C + (int64_t)row * ldc + ec * 8) = v;
+// Compute units of the current device (host side; asked once per process).
+inline int cu_count() {
+  static int cus = 0;
+  if (!cus) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
+      n = 256;
+    cus = n;
   }
-}
-
-// Epilogue of a 256 x 256 tile held by 8 waves as 8 x 4 MFMA 16x16 accumulator fragments each (lane l
-// holds, for fragment (i, j), the 4 consecutive columns j*16 + 4*(l/16) .. +3 of row i*16 + l%16 of the
-// wave's 128 x 64 sub-tile).  Staging and stores as in store_tile_bf16_w8.
-__device__ __forceinline__ void store_tile_bf16_w8_16(const f32x4 (&acc)[8][4], uint8_t* lds, int w, int lane,
-                                                      uint16_t* C, int64_t ldc) {
-  const int fr = lane & 15, fq = lane >> 4;
-  uint8_t* ew = lds + w * 128 * kEpiPitch8;
-#pragma unroll
-  for (int i = 0; i < 8; ++i)
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      uint2 v = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
-      *(uint2*)(ew + (i * 16 + fr) * kEpiPitch8 + (j * 16 + 4 * fq) * 2) = v;
-    }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_wave_barrier();
-  const int er = lane >> 3, ec = lane & 7;
-#pragma unroll 4
-  for (int t = 0; t < 16; ++t) {
-    int row = t * 8 + er;
-    uint4 v = *(const uint4*)(ew + row * kEpiPitch8 + ec * 16);
-    *(uint4*)(C + (int64_t)row * ldc + ec * 8) = v;
-  }
-}
-
-// Epilogue of a 256 x 256 tile held by 8 waves as 4 x 2 MFMA 32x32 accumulator fragments each
-// (operands swapped: lane l holds, for fragment (i, j) and a = 0..3, the 4 consecutive columns
-// j*32 + 8a + 4*(l/32) .. +3 of row i*32 + l%32 of the wave's 128 x 64 sub-tile).  Each wave converts
-// to bf16, stages its sub-tile in its own LDS region (row pitch 144 bytes) and writes it out with
-// 16-byte stores, 128 contiguous bytes per row.  The caller guarantees that no wave still reads
-// the pipeline stages.
-__device__ __forceinline__ void store_tile_bf16_w8(const f32x16 (&acc)[4][2], uint8_t* lds, int w, int lane,
-                                                   uint16_t* C, int64_t ldc) {
-  const int fr = lane & 31, fh = lane >> 5;
-  uint8_t* ew = lds + w * 128 * kEpiPitch8;
-#pragma unroll
-  for (int i = 0; i < 4; ++i)
-#pragma unroll
-    for (int j = 0; j < 2; ++j)
-#pragma unroll
-      for (int a = 0; a < 4; ++a) {
-        uint2 v = {pack_bf16(acc[i][j][4 * a + 0], acc[i][j][4 * a + 1]),
-                   pack_bf16(acc[i][j][4 * a + 2], acc[i][j][4 * a + 3])};
-        *(uint2*)(ew + (i * 32 + fr) * kEpiPitch8 + (j * 32 + 8 * a + 4 * fh) * 2) = v;
-      }
-  asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-  __builtin_amdgcn_wave_barrier();
-  const int er = lane >> 3, ec = lane & 7;
-#pragma unroll 4
-  for (int t = 0; t < 16; ++t) {
-    int row = t * 8 + er;
-    uint4 v = *(const uint4*)(ew + row * kEpiPitch8 + ec * 16);
-    *(uint4*)(C + (int64_t)row * ldc + ec * 8) = v;
-  }
+  return cus;
 }
 
 }  // namespace axe

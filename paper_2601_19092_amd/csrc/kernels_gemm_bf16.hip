@@ -62,7 +62,6 @@ constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
 constexpr int kRot = 8;                           // K-rotation window, in K-tiles
-static_assert(kEpiB <= kLds, "the epilogue staging area fits");
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(3))) uint8_t* lds_u8;
@@ -76,14 +75,6 @@ __device__ __forceinline__ void mfma_16x16x32(f32x4& acc, bf16x8 a, bf16x8 b) {
   asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
 }
 }  // namespace
-
-// Output descriptor words for a buffer store issued as an asm statement (see store_fragment).
-__device__ __forceinline__ i32x4 raw_rsrc(const void* p, uint32_t bytes) {
-  const uint64_t a = (uint64_t)p;
-  // the words are wave-uniform by construction; readfirstlane tells the compiler so (they must sit in SGPRs)
-  return i32x4{__builtin_amdgcn_readfirstlane((int)(uint32_t)a), __builtin_amdgcn_readfirstlane((int)((a >> 32) & 0xffffu)),
-               __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
-}
 
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
@@ -337,13 +328,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
   const int nk = (int)(g.K / 64);
-  static int cus = 0;
-  if (!cus) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    cus = n;
-  }
+  const int cus = cu_count();
   // one resident workgroup per CU walks several tiles when the pipeline can continue across tiles
   const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
   unsigned nwg = (unsigned)(chain ? cus : ntiles);

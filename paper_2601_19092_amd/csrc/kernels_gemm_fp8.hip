@@ -20,7 +20,8 @@
 //   LDS -> VGPR : lane l reads row l % 16 of a fragment and the two adjacent 16-byte chunks
 //                 2 * (l / 16) + {0, 1}: 32 consecutive k per lane, the operand layout of MFMA
 //                 16x16x128 (A and B are loaded the same way, so the pairing of k is kept).
-//   VGPR -> HBM : accumulators -> bf16 -> LDS -> 16-byte coalesced stores.
+//   VGPR -> HBM : accumulators -> bf16, 8 bytes per lane and fragment, stored directly (the four
+//                 fragments of a fragment row complete 128 contiguous bytes per row; L2 merges them).
 //
 // Schedule.  A K-step is 32 MFMAs per wave, fragment (i, j) with j innermost.  A fragments are read
 // three rows ahead of their use, so every LDS read of A of tile kt has been issued when row 4 ends;
@@ -29,7 +30,10 @@
 // tile kt (read at the end of step kt-1).  Between two barriers a wave issues A of tile kt+2 (into
 // the block just freed: one K-step to land, so it goes first) and then B of tile kt+3 (ring of
 // three blocks: a little more than one K-step).
-// The K rotation and the workgroup -> tile order are those of the bf16 kernel.
+// The K rotation, the workgroup -> tile order and the chaining of a workgroup's tiles into one
+// pipeline are those of the bf16 kernel.  (Measured: chaining gains nothing here -- this kernel is
+// held back by the L2 -> CU path, which carries twice the bytes per flop of the bf16 kernel, not by
+// the fill and drain of its pipeline -- but it lets both kernels share one epilogue and launch shape.)
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -46,7 +50,6 @@ constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
 constexpr int kRot = 8;                           // K-rotation window, in K-tiles
-static_assert(kEpiB8 <= kLds, "the epilogue staging area fits");
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(3))) uint8_t* lds_u8;
 __device__ __forceinline__ i32x8 lds_read32(lds_u8 p0, lds_u8 p1) {
@@ -58,43 +61,70 @@ __device__ __forceinline__ i32x8 lds_read32(lds_u8 p0, lds_u8 p1) {
 
 __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
-  uint8_t* const lds = lds_mem;                                    // generic view, for the epilogue
-  const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses for the main loop
+  const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int w = __builtin_amdgcn_readfirstlane(tid >> 6);          // wave id 0..7, kept scalar
   const int wm = w >> 2, wn = w & 3;                               // wave grid 2 x 4
-  int tm, tn;
-  tile_of_block(blockIdx.x, gridDim.x, g.grid_m, g.grid_n, tm, tn);
-  const int64_t m0 = (int64_t)tm * kTile, n0 = (int64_t)tn * kTile;
   const int nk = (int)(g.K / 128);
-  // K rotation (see the bf16 kernel): position T of the walk -> K-tile
-  const int rot = (tm + tn) & (kRot - 1);
-  const int nk_rot = nk & ~(kRot - 1);
-  auto ktile = [&](int T) -> int { return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T; };
+  const int ntiles = g.grid_m * g.grid_n;
+  const int nk_rot = nk & ~(kRot - 1);                             // K-tiles beyond the last full rotation window keep their order
+  const bool scaled = g.scale_a != nullptr;
+
+  // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ...  The loads run two
+  //      K-steps ahead of the MFMAs and cross into the next tile before the current one is finished,
+  //      so two tiles are described at any time: cur and nxt.
+  const int a_pitch = (int)g.lda, b_pitch = (int)g.ldb;            // bytes
+  struct Tile {
+    __amdgpu_buffer_rsrc_t ra, rb;
+    const float *sa, *sb;                                          // block scales of this wave's rows (A) and columns (B)
+    int rot;
+  };
+  auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
+    Tile t;
+    if (v < ntiles) {
+      int tm, tn;
+      tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
+      t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda), 0,
+                                               255 * a_pitch + (int)g.K, 0x00020000);
+      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * kTile * g.ldb), 0,
+                                               255 * b_pitch + (int)g.K, 0x00020000);
+      t.sa = scaled ? g.scale_a + (int64_t)(2 * tm + wm) * g.nkb : nullptr;
+      t.sb = scaled ? g.scale_b + (int64_t)(2 * tn + (wn >> 1)) * g.nkb : nullptr;
+      t.rot = (tm + tn) & (kRot - 1);                              // K rotation (see the bf16 kernel)
+    } else {                                                       // no such tile: every load returns zero
+      t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
+      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
+      t.sa = t.sb = nullptr;
+      t.rot = 0;
+    }
+    return t;
+  };
+  int v = blockIdx.x;
+  Tile cur = describe(v), nxt = describe(v + (int)gridDim.x);
+  // position T of a tile's walk -> K-tile
+  auto ktile = [&](int T, int rot) -> int { return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T; };
 
   // ---- HBM -> LDS.  Per K-tile and operand 32 wave instructions of 8 rows; wave w issues pieces
-  //      i = 0..3 = row groups w, w + 8, w + 16, w + 24.
+  //      i = 0..3 = row groups w, w + 8, w + 16, w + 24.  Step T >= nk of the current tile is step
+  //      T - nk of the next one (cross = false: the caller knows T < nk).
   const int lr = lane >> 3, lp = lane & 7;
   const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 8 i) * 8 + lr
-  const int a_pitch = (int)g.lda, b_pitch = (int)g.ldb;            // bytes
-  const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)((const uint8_t*)g.A + m0 * g.lda), 0, 255 * a_pitch + (int)g.K, 0x00020000);
-  const __amdgpu_buffer_rsrc_t rb = __builtin_amdgcn_make_buffer_rsrc(
-      (void*)((const uint8_t*)g.B + n0 * g.ldb), 0, 255 * b_pitch + (int)g.K, 0x00020000);
   const int a_voff = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
   const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
   const int a_piece = 64 * a_pitch, b_piece = 64 * b_pitch;        // bytes between pieces
-  auto a_load = [&](int T, int i, int stage) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(ra, (lds_ptr)(lds3 + stage * kBlk + (w + 8 * i) * 1024), 16, a_voff,
-                                             i * a_piece + ktile(T) * kRow, 0, 0);
+  auto a_load = [&](int T, int i, int stage, bool cross) __attribute__((always_inline)) {
+    const bool nx = cross && T >= nk;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + stage * kBlk + (w + 8 * i) * 1024), 16,
+                                             a_voff, i * a_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
   };
   // B ring: byte offsets of the blocks that hold tiles kt, kt+1, kt+2 (tile kt+3 reuses the first)
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
-  auto b_load = [&](int T, int i, int slot_off) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(rb, (lds_ptr)(lds3 + slot_off + (w + 8 * i) * 1024), 16, b_voff,
-                                             i * b_piece + ktile(T) * kRow, 0, 0);
+  auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
+    const bool nx = cross && T >= nk;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 8 * i) * 1024), 16,
+                                             b_voff, i * b_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16; the lane's
@@ -117,14 +147,11 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   // Block scales: one product sA * sB per K-step of this wave.  A register holds those of 64
   // consecutive K-steps, one per lane (no scalar or vector memory access in the steady loop); it is
   // refilled every 64 steps.
-  const bool scaled = g.scale_a != nullptr;
-  const float* sa = scaled ? g.scale_a + (int64_t)((m0 + wm * 128) / 128) * g.nkb : nullptr;
-  const float* sb = scaled ? g.scale_b + (int64_t)((n0 + wn * 64) / 128) * g.nkb : nullptr;
   auto scales_from = [&](int base) -> float {
     if (!scaled) return 1.0f;
     const int T = base + lane;
-    const int t = ktile(T < nk ? T : nk - 1);
-    return sa[t] * sb[t];
+    const int t = ktile(T < nk ? T : nk - 1, cur.rot);
+    return cur.sa[t] * cur.sb[t];
   };
   auto lane_value = [](float v, int l) -> float {
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
@@ -155,8 +182,9 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   // the tile has been issued.  Slots 2, 6, 10, 14 load B of tile kt+2; slots 20, 22, 24, 26 load A of
   // tile kt+2.  Nothing is guarded against the end of K: loads of tiles past the end stay inside the
   // buffer descriptors, land in blocks that are free by then, and are never multiplied.
-  auto step = [&](auto par_c, int kt, float sc, float sc_prev) {
+  auto step = [&](auto par_c, auto cross_c, int kt, float sc, float sc_prev) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value;
+    constexpr bool CROSS = decltype(cross_c)::value != 0;          // the loads of this step may belong to the next tile
 #pragma unroll
     for (int q = 0; q < 32; ++q) {
       const int i = q >> 2, j = q & 3;
@@ -169,8 +197,8 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
         else read_a(i - 5, PAR ^ 1);
       }
       if (i == 7) read_b(j, bo1);
-      if (q < 16 && j == 2) b_load(kt + 2, i, bo2);
-      if (q >= 20 && q < 28 && (q & 1) == 0) a_load(kt + 2, (q - 20) >> 1, PAR);
+      if (q < 16 && j == 2) b_load(kt + 2, i, bo2, CROSS);
+      if (q >= 20 && q < 28 && (q & 1) == 0) a_load(kt + 2, (q - 20) >> 1, PAR, CROSS);
       if (q == 19) {
         // Own reads of tile kt are complete and so are own loads of tile kt+1 (the 4 B loads issued
         // since may still be in flight).  After the barrier tile kt+1 is readable by every wave and
@@ -184,15 +212,38 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
     bo0 = bo1, bo1 = bo2, bo2 = t;
   };
 
-  // ---- prologue: tiles 0 and 1 of both operands
+  // ---- VGPR -> HBM.  Operands are swapped in the MFMA, so lane l holds, for fragment (i, j), the 4
+  //      consecutive columns j*16 + 4*(l/16) .. +3 of row i*16 + l%16 of the wave's 128 x 64 sub-tile:
+  //      8 bytes of bf16, stored directly (the four fragments of a fragment row complete 128
+  //      contiguous bytes per row; L2 merges them).  An asm statement, for the reason given in the
+  //      bf16 kernel: the compiler's wait-count bookkeeping must not see the store.
+  i32x4 rc;                                                        // descriptor of this wave's part of the C tile
+  const int c_rowblk = (int)(16 * g.ldc * 2);                      // bytes between fragment rows
+  const int c_voff = (int)((fr * g.ldc + 4 * fq) * 2);
+  auto set_output = [&](int vv) __attribute__((always_inline)) {
+    int tm, tn;
+    tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
+    rc = raw_rsrc((uint16_t*)g.C + ((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * kTile + wn * 64,
+                  (uint32_t)((127 * g.ldc + 64) * 2));
+  };
+  auto store_fragment = [&](int i, int j) __attribute__((always_inline)) {
+    typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+    const u32x2 d = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
+    const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
+    asm volatile("buffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
 #pragma unroll
-  for (int i = 0; i < 4; ++i) a_load(0, i, 0);
+    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile
+  };
+
+  // ---- prologue (first tile only): tiles 0 and 1 of both operands
 #pragma unroll
-  for (int i = 0; i < 4; ++i) b_load(0, i, bo0);
+  for (int i = 0; i < 4; ++i) a_load(0, i, 0, true);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) a_load(1, i, 1);
+  for (int i = 0; i < 4; ++i) b_load(0, i, bo0, true);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) b_load(1, i, bo1);
+  for (int i = 0; i < 4; ++i) a_load(1, i, 1, true);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b_load(1, i, bo1, true);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   wg_barrier();
 #pragma unroll
@@ -200,37 +251,76 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
 #pragma unroll
   for (int f = 0; f < 3; ++f) read_a(f, 0);
 
-  int kt = 0;
-  float sc = 1.0f, sc_prev = 1.0f;
-  for (int base = 0; base < nk; base += 64) {
-    const float scv = scales_from(base);
-    const int end = nk < base + 64 ? nk : base + 64;
-    sc = lane_value(scv, 0);
-    for (; kt + 1 < end; kt += 2) {
-      const float sc1 = lane_value(scv, (kt + 1) & 63);
-      step(I0{}, kt, sc, sc_prev);
-      const float sc2 = lane_value(scv, (kt + 2) & 63);
-      step(I1{}, kt + 1, sc1, sc);
-      sc_prev = sc1;
-      sc = sc2;
+  // ---- all K-steps of all tiles of this workgroup, one uninterrupted pipeline.  The host launches
+  //      more than one tile per workgroup only when nk is even (the A block of a step is chosen by its
+  //      parity, which must continue across the tile boundary) and at least 4.
+  float scv0 = scales_from(0);                                     // first tile: waited for here, with the prologue
+  float nsa = 1.0f, nsb = 1.0f;                                    // next tile's scales of steps 0..63, one per lane, on their way
+  for (;;) {
+    set_output(v);
+    const bool more = v + (int)gridDim.x < ntiles;
+    int kt = 0;
+    float sc = 1.0f, sc_prev = 1.0f;
+    for (int base = 0; base < nk; base += 64) {
+      const float scv = base == 0 ? scv0 : scales_from(base);
+      const int end = nk < base + 64 ? nk : base + 64;
+      const int steady = end < nk - 2 ? end : nk - 2;              // steps below load only this tile (at most step kt + 2)
+      sc = lane_value(scv, 0);
+      for (; kt + 1 < steady; kt += 2) {
+        const float sc1 = lane_value(scv, (kt + 1) & 63);
+        step(I0{}, I0{}, kt, sc, sc_prev);
+        const float sc2 = lane_value(scv, (kt + 2) & 63);
+        step(I1{}, I0{}, kt + 1, sc1, sc);
+        sc_prev = sc1;
+        sc = sc2;
+      }
+      if (end == nk && more && scaled) {
+        // The next tile's first register of scales is fetched now and waited for after this tile's
+        // stores (asm statements: a load the compiler sees would be waited for with vmcnt(0), which
+        // drains the operand pipeline).
+        const int T = lane < nk ? lane : nk - 1;
+        const int t = ktile(T, nxt.rot);
+        asm volatile("global_load_dword %0, %1, off" : "=v"(nsa) : "v"(nxt.sa + t) : "memory");
+        asm volatile("global_load_dword %0, %1, off" : "=v"(nsb) : "v"(nxt.sb + t) : "memory");
+      }
+      for (; kt + 1 < end; kt += 2) {                              // the last steps load the next tile's first K-steps
+        const float sc1 = lane_value(scv, (kt + 1) & 63);
+        step(I0{}, I1{}, kt, sc, sc_prev);
+        const float sc2 = lane_value(scv, (kt + 2) & 63);
+        step(I1{}, I1{}, kt + 1, sc1, sc);
+        sc_prev = sc1;
+        sc = sc2;
+      }
+      if (kt < end) {                                              // odd nk (one tile per workgroup): the very last step
+        step(I0{}, I1{}, kt, sc, sc_prev);
+        sc_prev = sc;
+        ++kt;
+      }
     }
-    if (kt < end) {                                                // odd number of K-steps: the very last one
-      step(I0{}, kt, sc, sc_prev);
-      sc_prev = sc;
-      ++kt;
-    }
+    fold(7, 3, 1, sc_prev);
+    // the tile is complete: store it while the loads of the next tile's first K-steps are on their way
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) store_fragment(i, j);
+    v += (int)gridDim.x;
+    if (v >= ntiles) break;
+    // 16 operand loads and 32 stores were issued after the two scale loads; memory operations of a
+    // wave complete in order, so at most 48 outstanding means the scales have arrived
+    asm volatile("s_waitcnt vmcnt(48)" : "+v"(nsa), "+v"(nsb)::"memory");
+    scv0 = scaled ? nsa * nsb : 1.0f;
+    cur = nxt;
+    nxt = describe(v + (int)gridDim.x);
   }
-  fold(7, 3, 1, sc_prev);
-
-  // ---- epilogue: all loads must have landed (they would overwrite the staging area) and no wave
-  //      may still read fragments
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-  wg_barrier();
-  store_tile_bf16_w8_16(acc, lds, w, lane, (uint16_t*)g.C + (m0 + wm * 128) * g.ldc + n0 + wn * 64, g.ldc);
 }
 
 hipError_t launch_gemm_fp8_256(const GemmArgs& g, hipStream_t s) {
-  unsigned nwg = (unsigned)(g.grid_m * g.grid_n);
+  const int ntiles = g.grid_m * g.grid_n;
+  const int nk = (int)(g.K / 128);
+  const int cus = cu_count();
+  // one resident workgroup per CU walks several tiles when the pipeline can continue across tiles
+  const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
+  unsigned nwg = (unsigned)(chain ? cus : ntiles);
   hipLaunchKernelGGL(gemm_fp8_256_kernel, dim3(nwg), dim3(512), 0, s, g);
   return hipGetLastError();
 }

@@ -182,10 +182,11 @@ def test_c_store_map(kind):
     regs = T * T // (64 * NW)
     key = (pts[:, 3] * 64 + pts[:, 4]) * regs + pts[:, 5]
     assert np.array_equal(np.sort(key), np.arange(T * T))
-    if kind == "big_bf16":
+    if kind in BIG:
         # accumulator fragments are stored directly: one store instruction (4 consecutive registers of
         # every lane) covers 16 rows x 16 columns, 4 lanes x 4 elements = 32 contiguous bytes per row;
-        # the eight fragments of a fragment row follow one another and complete 256 bytes per row
+        # the fragments of a fragment row follow one another and complete T / WN * 2 bytes per row
+        nj = T // WN // 16                                            # fragments per fragment row
         col = np.empty(T * T, dtype=np.int64); row = np.empty(T * T, dtype=np.int64)
         idx = np.arange(T * T)
         row[key], col[key] = idx // T, idx % T
@@ -197,24 +198,9 @@ def test_c_store_map(kind):
             for rr in set(r.tolist()):
                 cs = np.sort(c[r == rr])
                 assert np.array_equal(cs, cs[0] + 4 * np.arange(4)) and cs[0] % 16 == 0
-        for w, i in itertools.product(range(NW), range(8)):           # fragment row i: fragments 8 i .. 8 i + 7
-            c0 = np.sort(np.unique(col[w, :, 8 * i:8 * i + 8, :]))
-            assert np.array_equal(c0, c0[0] + np.arange(128))
-    if kind == "big_fp8":
-        # one store instruction (8 consecutive registers of every lane): whole rows of the wave's sub-tile,
-        # T / WN * 2 contiguous bytes each
-        col = np.empty(T * T, dtype=np.int64); row = np.empty(T * T, dtype=np.int64)
-        idx = np.arange(T * T)
-        row[key], col[key] = idx // T, idx % T
-        row, col = row.reshape(NW, 64, regs // 8, 8), col.reshape(NW, 64, regs // 8, 8)
-        assert np.all(np.diff(col, axis=-1) == 1) and np.all(row[..., 0:1] == row)
-        lpr = T // WN // 8                                   # lanes per row
-        for w, t in itertools.product(range(NW), range(regs // 8)):
-            r, c = row[w, :, t, 0], col[w, :, t, 0]
-            assert len(set(r.tolist())) == 64 // lpr
-            for rr in set(r.tolist()):
-                cs = np.sort(c[r == rr])
-                assert np.array_equal(cs, cs[0] + 8 * np.arange(lpr)) and cs[0] % (8 * lpr) == 0
+        for w, i in itertools.product(range(NW), range(8)):           # fragment row i: fragments nj i .. nj i + nj - 1
+            c0 = np.sort(np.unique(col[w, :, nj * i:nj * i + nj, :]))
+            assert np.array_equal(c0, c0[0] + np.arange(16 * nj))
 
 
 def test_mfma_operand_layout_matches_its_statement():

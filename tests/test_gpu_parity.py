@@ -396,3 +396,12 @@ def test_gemm_config4_full_size_shard():
 
 def test_gemm_config5_full_size_fp8_scaled():
     full_size_check(W.config5(), FP8_TOL, seed=5)
+
+
+def test_gemm_chained_tiles_on_a_grid_of_17_by_16():
+    """More tiles than compute units, so every workgroup walks two tiles as one pipeline, on a tile
+    grid that is not made of 16 x 16 blocks (the other workgroup -> tile order); the last 16 workgroups
+    get a second tile, the others do not."""
+    full_size_check(W.gemm_bf16(4352, 4096, 512, 91), BF16_TOL, seed=6)
+    # fp8: 66 K-steps, so the register of block scales is refilled inside each chained tile
+    full_size_check(W.gemm_fp8(4352, 4096, 8448, 92, scaled=True), FP8_TOL, seed=7)
