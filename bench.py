@@ -7,8 +7,9 @@ A step is one pass of the GEMM hot path (host layout analysis, HBM -> LDS -> VGP
 over one batch of synthetic input: the bf16 GEMM M = N = K = 8192 (configuration 3), inputs
 resident in HBM, rotating over two buffer sets.  The headline value is its whole-job TFLOP/s.
 The same JSON line carries, under "companions", the other configurations measured in the same
-run (relayout GB/s, fp8 GEMM, the tensor-parallel shard, the 256^3 GEMM, layout evaluation),
-the roofline of the dominant kernel and the CPU oracle timed on a bounded sample.
+run (relayout GB/s, fp8 GEMM, the tensor-parallel shard, the 256^3 GEMM, layout evaluation, and
+for context the measured ceilings: register-only MFMA loops and a plain device copy), the roofline
+of the dominant kernel and the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
@@ -142,7 +143,46 @@ def bench_eval(steps, warmup):
     return r
 
 
-def cpu_baseline(g, budget_rows=512):
+def bench_ceilings(g3, g5, steps=20, warmup=5):
+    """Measured ceilings for context: register-only MFMA loops (the instruction, wave count and
+    accumulator walk of the two 256 x 256 kernels) on a sample of the real operands, and a plain
+    device-to-device copy of the relayout's size."""
+    import ctypes as C
+    import torch
+    from paper_2601_19092_amd import binding as B
+    path = os.path.join(os.path.dirname(B.LIB_PATH), "libaxe_probe.so")
+    if not os.path.exists(path):
+        sys.exit(f"bench.py: {path} is missing (run __graft_entry__.build())")
+    P = C.CDLL(path)
+    P.axe_probe_mfma.restype = C.c_int
+    P.axe_probe_mfma.argtypes = [C.c_int32, C.c_void_p, C.c_size_t, C.c_int32, C.c_void_p, C.c_size_t,
+                                 C.POINTER(C.c_double), C.c_void_p]
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    sink = torch.zeros(cus * 512, dtype=torch.float32, device="cuda")
+    out = {}
+    for key, g, fp8, nbytes, iters in (("mfma_bf16", g3, 0, 16 * 256 * 16, 8000), ("mfma_fp8", g5, 1, 12 * 256 * 32, 4000)):
+        # rows from the middle of A: 64 or 96 KiB of consecutive operand codes
+        sample = dev(g.a_mk.reshape(-1).view(np.uint8)[g.a_mk.nbytes // 2:][:nbytes].copy())
+        flops = C.c_double(0.0)
+        def launch(i):
+            rc = P.axe_probe_mfma(fp8, sample.data_ptr(), nbytes, iters, sink.data_ptr(), sink.numel(), C.byref(flops),
+                                  torch.cuda.current_stream().cuda_stream)
+            if rc:
+                sys.exit(f"bench.py: axe_probe_mfma failed ({rc})")
+        _, devms = time_loop(launch, steps, warmup)
+        out[key + "_register_only_tflops"] = flops.value / (devms * 1e-3) / 1e12
+    n = 8192 * 8192
+    pairs = [(torch.randint(-30000, 30000, (n,), dtype=torch.int16, device="cuda"),
+              torch.empty(n, dtype=torch.int16, device="cuda")) for _ in range(4)]
+    _, devms = time_loop(lambda i: pairs[i % 4][1].copy_(pairs[i % 4][0]), 40, 10)
+    out["device_copy_GBps"] = 2.0 * n * 2 / (devms * 1e-3) / 1e9
+    log(f"[bench] measured ceilings: register-only MFMA loop bf16 {out['mfma_bf16_register_only_tflops']:.0f} TFLOP/s, "
+        f"fp8 {out['mfma_fp8_register_only_tflops']:.0f} TFLOP/s on samples of the inputs; "
+        f"plain device copy of 128 MiB {out['device_copy_GBps']:.0f} GB/s")
+    return out
+
+
+def cpu_baseline(g, budget_rows=1536):
     """The CPU oracle as it stands, on the first `budget_rows` rows of the same GEMM."""
     from oracle import axe_ref as R
     rows = np.arange(budget_rows)
@@ -161,7 +201,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--only", default="", help="comma list of: gemm,relayout,fp8,shard,small,eval,cpu (default all)")
+    ap.add_argument("--only", default="", help="comma list of: gemm,relayout,fp8,shard,small,eval,ceilings,cpu (default all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -184,14 +224,23 @@ def main():
     if want("shard"):
         comp["gemm_cfg4_tp_shard"], _ = bench_gemm("bf16 GEMM M=4096 K=8192 N=3584 (1 of 8 shards)", W.config4(),
                                                    args.steps, args.warmup, device_axis=True)
+    g5 = W.config5() if (want("fp8") or want("ceilings")) else None
     if want("fp8"):
-        comp["gemm_cfg5_fp8_block_scaled"], _ = bench_gemm("fp8 e4m3 GEMM 8192^3, fp32 128x128 block scales", W.config5(),
+        comp["gemm_cfg5_fp8_block_scaled"], _ = bench_gemm("fp8 e4m3 GEMM 8192^3, fp32 128x128 block scales", g5,
                                                            max(10, args.steps // 2), args.warmup)
     if want("small"):
         comp["gemm_cfg1_256"], _ = bench_gemm("bf16 GEMM 256^3, fp32 out, 64x64x32 tiles", W.config1(),
                                               max(200, args.steps), max(200, args.warmup), n_sets=1)
     if want("eval"):
         comp["layout_eval"] = bench_eval(20, 5)
+    if want("ceilings"):
+        c = bench_ceilings(g3, g5)
+        c["gemm_cfg3_frac_of_measured"] = head["kernel_tflops"] / c["mfma_bf16_register_only_tflops"]
+        if "gemm_cfg5_fp8_block_scaled" in comp:
+            c["gemm_cfg5_frac_of_measured"] = comp["gemm_cfg5_fp8_block_scaled"]["kernel_tflops"] / c["mfma_fp8_register_only_tflops"]
+        if "relayout_cfg2" in comp:
+            c["relayout_cfg2_frac_of_measured"] = comp["relayout_cfg2"]["rotating"]["GBps"] / c["device_copy_GBps"]
+        comp["measured_ceilings"] = c
     cpu = None
     if not args.no_cpu and want("cpu"):
         log("[bench] timing the CPU oracle on a bounded sample ...")

@@ -1,0 +1,39 @@
+/* Measurement aids of the Axe-layout GEMM path: ceilings of the matrix pipe.
+ *
+ * Not part of the hot path and not part of libaxe_hip.so: these live in libaxe_probe.so, which only
+ * the benchmark's --ceilings mode loads.  They answer the question the roofline fraction alone
+ * cannot: what does the matrix pipe sustain on this data when nothing but MFMAs is issued?
+ */
+#ifndef AXE_PROBE_H
+#define AXE_PROBE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define AXE_PROBE_SAMPLE_BF16 (16 * 256 * 16) /* bytes of operand sample the bf16 loop reads */
+#define AXE_PROBE_SAMPLE_FP8 (12 * 256 * 32)  /* bytes of operand sample the fp8 loop reads  */
+
+/* Launches, on `stream` (a hipStream_t, NULL = default stream), a register-only loop of the MFMA
+ * instruction, wave count and accumulator order of the 256 x 256 GEMM kernel of that input type
+ * (fp8 = 0: bf16, v_mfma_f32_16x16x32_bf16, one wave per SIMD, 8 x 8 fragments; fp8 = 1: e4m3,
+ * v_mfma_f32_16x16x128_f8f6f4, two waves per SIMD, 8 x 4 fragments), one workgroup per compute unit,
+ * `iters` passes over the wave's fragments.
+ *   sample       device pointer, 32-byte aligned, at least AXE_PROBE_SAMPLE_* bytes of operand codes
+ *                (a piece of the real input, so that the loop toggles the datapath as the GEMM does);
+ *                read only
+ *   sink         device pointer to sink_floats floats, at least one per launched thread
+ *                (512 x compute units covers both); written, content meaningless
+ *   flops        host pointer; receives the flops the launch performs
+ * The call is asynchronous; the caller times it with events on `stream`.  Returns 0, 1 for a bad
+ * argument, 2 if the launch failed.  Nothing is allocated. */
+int axe_probe_mfma(int32_t fp8, const void* sample, size_t sample_bytes, int32_t iters, float* sink, size_t sink_floats,
+                   double* flops, void* stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif

@@ -57,6 +57,15 @@ def build_hostcheck() -> str:
     return out
 
 
+def build_probe() -> str:
+    """Measurement aids (csrc/probes.hip): register-only MFMA loops, loaded by bench.py --ceilings only."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    out = os.path.join(HERE, "libaxe_probe.so")
+    subprocess.check_call([hipcc, *FLAGS, "-shared", os.path.join(CSRC, "probes.hip"), "-o", out], stderr=subprocess.DEVNULL)
+    return out
+
+
 if __name__ == "__main__":
     print(build_library(verbose="-v" in sys.argv))
     print(build_hostcheck())
+    print(build_probe())

@@ -1,0 +1,89 @@
+// Measured ceilings of the matrix pipe (measurement aids, not part of the hot path; a library of
+// their own, libaxe_probe.so, loaded only by bench.py --ceilings).
+//
+// A register-only loop of the very MFMA instruction, wave shape and accumulator walk of the GEMM
+// kernel it stands for: operands are loaded once from a caller-supplied sample of the real input,
+// then the loop issues nothing but MFMAs.  What it sustains on that data is what the kernel could
+// reach if LDS, L2 and HBM cost neither time nor power; on random data this is well below the
+// nominal peak because the chip runs into its power limit.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/axe_probe.h"
+#include "gemm_common.h"
+
+namespace {
+using axe::bf16x8;
+using axe::f32x4;
+using axe::i32x8;
+
+// bf16: one wave per SIMD (4 per workgroup), 8 x 8 fragments of v_mfma_f32_16x16x32_bf16, j innermost.
+__global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __restrict__ in, float* out, int iters) {
+  bf16x8 a[8], b[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = in[i * 256 + threadIdx.x];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) b[j] = in[(8 + j) * 256 + threadIdx.x];
+  f32x4 acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j) s += acc[i][j][0] + acc[i][j][1] + acc[i][j][2] + acc[i][j][3];
+  out[blockIdx.x * 256 + threadIdx.x] = s;
+}
+
+// fp8: two waves per SIMD (8 per workgroup), 8 x 4 fragments of v_mfma_f32_16x16x128_f8f6f4, j innermost.
+__global__ __launch_bounds__(512, 1) void probe_fp8_kernel(const i32x8* __restrict__ in, float* out, int iters) {
+  const int t = threadIdx.x & 255;
+  i32x8 a[8], b[4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = in[i * 256 + t];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) b[j] = in[(8 + j) * 256 + t];
+  f32x4 acc[8][4];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(b[j], a[i], acc[i][j], 0, 0, 0, 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 4; ++j) s += acc[i][j][0] + acc[i][j][1] + acc[i][j][2] + acc[i][j][3];
+  out[blockIdx.x * 512 + threadIdx.x] = s;
+}
+}  // namespace
+
+extern "C" int axe_probe_mfma(int32_t fp8, const void* sample, size_t sample_bytes, int32_t iters, float* sink,
+                              size_t sink_floats, double* flops, void* stream) {
+  const int cus = axe::cu_count();
+  const size_t need = fp8 ? AXE_PROBE_SAMPLE_FP8 : AXE_PROBE_SAMPLE_BF16;
+  const size_t threads = (size_t)cus * (fp8 ? 512 : 256);
+  if (!sample || !sink || !flops || iters <= 0 || sample_bytes < need || sink_floats < threads || ((uintptr_t)sample & 31)) return 1;
+  if (fp8) {
+    hipLaunchKernelGGL(probe_fp8_kernel, dim3(cus), dim3(512), 0, (hipStream_t)stream, (const i32x8*)sample, sink, iters);
+    *flops = 2.0 * 16 * 16 * 128 * 32 * (double)iters * 8 * cus;
+  } else {
+    hipLaunchKernelGGL(probe_bf16_kernel, dim3(cus), dim3(256), 0, (hipStream_t)stream, (const bf16x8*)sample, sink, iters);
+    *flops = 2.0 * 16 * 16 * 32 * 64 * (double)iters * 4 * cus;
+  }
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}

@@ -28,6 +28,17 @@ def test_library_exports_every_declared_symbol():
     assert b"shape" in L.axe_strerror(B.AXE_ESHAPE)
 
 
+def test_probe_library_exports_what_its_header_declares():
+    """libaxe_probe.so (measurement aids, loaded by the benchmark only) against include/axe_probe.h."""
+    text = open(os.path.join(ROOT, "include", "axe_probe.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = sorted(set(re.findall(r"\b(axe_[a-z_0-9]+)\s*\(", text)))
+    assert names == ["axe_probe_mfma"]
+    P = C.CDLL(os.path.join(os.path.dirname(B.LIB_PATH), "libaxe_probe.so"))
+    for n in names:
+        assert getattr(P, n) is not None
+
+
 def _eval_rc(spec, shape, n=None, axes=None):
     L = B.Layout(spec, axes)
     shp = (C.c_int64 * len(shape))(*shape)
