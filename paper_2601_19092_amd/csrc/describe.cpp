@@ -59,7 +59,7 @@ Geo geometry(bool big, bool fp8) {
     g.F = 16;
   }
   g.BK = g.ROWB / g.EB;
-  g.key_shift = g.ROWB == 64 ? 2 : 1;
+  g.key_shift = 1;
   // 256x256 kernels: five 32 KiB blocks, A in blocks 0 and 1, the B ring starts at block 2
   g.b_off = (int64_t)g.T * g.BK * (big ? 2 : 1);
   return g;
@@ -137,8 +137,15 @@ int operand_layout(const Geo& g, bool is_b, Builder& b) {
   std::vector<axe_iter_t> rows = {{is_b ? g.WN : g.WM, is_b ? 1 : g.WN, WAVE}, {NF, KPL, REG}, {g.F, 1, LANE}};
   std::vector<axe_iter_t> ks;
   if (KS > 1) ks.push_back({KS, (int64_t)NF * KPL, REG});
-  ks.push_back({LG, g.F, LANE});
-  ks.push_back({KPL, 1, REG});
+  if (g.fp8) {
+    // the 32 k of a lane are two runs of 16: k = 64 h + 16 (lane / 16) + e sits in register 16 h + e
+    ks.push_back({2, 16, REG});
+    ks.push_back({LG, g.F, LANE});
+    ks.push_back({16, 1, REG});
+  } else {
+    ks.push_back({LG, g.F, LANE});
+    ks.push_back({KPL, 1, REG});
+  }
   if (!is_b) {
     for (auto& it : rows) b.d.push_back(it);
     for (auto& it : ks) b.d.push_back(it);
@@ -171,8 +178,7 @@ int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Bui
   return AXE_OK;
 }
 
-// (T, T) tile of C -> wave, lane, reg: who stores which element.  The fp8 256 x 256 kernel stages
-// the tile in LDS and writes it row by row (16 bytes per lane).
+// (T, T) tile of C -> wave, lane, reg: who stores which element.
 int c_store_layout(const Geo& g, Builder& b) {
   // every kernel stores its accumulator fragments directly: the store map is the accumulator layout
   // of one tile (8 bytes of bf16 per lane and fragment)

@@ -17,9 +17,14 @@
 //   LDS layout  : five 32 KiB blocks (one operand, one K-tile each): A double-buffered in blocks 0, 1,
 //                 B in a ring of blocks 2, 3, 4.  Rows of 128 bytes (128 fp8); 16-byte chunk c of row r
 //                 sits at chunk position c ^ key(r), key(r) = (r >> 1) & 7 (64 LDS banks: conflict-free).
-//   LDS -> VGPR : lane l reads row l % 16 of a fragment and the two adjacent 16-byte chunks
-//                 2 * (l / 16) + {0, 1}: 32 consecutive k per lane, the operand layout of MFMA
-//                 16x16x128 (A and B are loaded the same way, so the pairing of k is kept).
+//   LDS -> VGPR : lane l reads row l % 16 of a fragment and the 16-byte chunks l / 16 and l / 16 + 4.
+//                 MFMA 16x16x128 multiplies the 32 bytes of a lane of A with the 32 bytes of the
+//                 same lane group of B; which k they are is free as long as A and B agree, and
+//                 this choice keeps the reads free of bank conflicts: an LDS unit serves a
+//                 16-byte-per-lane read 16 lanes at a time, lanes 0-3, 12-15, 20-23, 24-27 together
+//                 and then 4-7, 8-11, 16-19, 28-31 (measured: with adjacent chunks 2 q, 2 q + 1
+//                 every read took 8 LDS cycles instead of 4), so neighbouring lane groups must
+//                 differ in chunk bit 0 for the key below to separate them.
 //   VGPR -> HBM : accumulators -> bf16, 8 bytes per lane and fragment, stored directly (the four
 //                 fragments of a fragment row complete 128 contiguous bytes per row; L2 merges them).
 //
@@ -128,13 +133,13 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16; the lane's
-  //      32 bytes are the chunks 2 q and 2 q + 1 (q = lane / 16), found at positions (2 q) ^ key, (2 q + 1) ^ key
+  //      32 bytes are the chunks q and q + 4 (q = lane / 16), found at positions q ^ key, (q + 4) ^ key
   const int fr = lane & 15, fq = lane >> 4;
   const int fkey = (fr >> 1) & 7;
-  const lds_u8 fa0 = lds3 + (wm * 128 + fr) * kRow + (((2 * fq) ^ fkey) << 4);
-  const lds_u8 fa1 = lds3 + (wm * 128 + fr) * kRow + (((2 * fq + 1) ^ fkey) << 4);
-  const lds_u8 fb0 = lds3 + (wn * 64 + fr) * kRow + (((2 * fq) ^ fkey) << 4);
-  const lds_u8 fb1 = lds3 + (wn * 64 + fr) * kRow + (((2 * fq + 1) ^ fkey) << 4);
+  const lds_u8 fa0 = lds3 + (wm * 128 + fr) * kRow + ((fq ^ fkey) << 4);
+  const lds_u8 fa1 = lds3 + (wm * 128 + fr) * kRow + (((fq + 4) ^ fkey) << 4);
+  const lds_u8 fb0 = lds3 + (wn * 64 + fr) * kRow + ((fq ^ fkey) << 4);
+  const lds_u8 fb1 = lds3 + (wn * 64 + fr) * kRow + (((fq + 4) ^ fkey) << 4);
 
   f32x4 acc[8][4];
 #pragma unroll
