@@ -4,9 +4,9 @@
 //
 // One K-tile is one 128-deep scale block and one MFMA per fragment: every MFMA starts from a zero
 // accumulator, and its result P is folded into the running sum on the vector ALU,
-// acc += (sA * sB) * P, two MFMAs later.  The vector ALU cannot address the AGPR half of the
+// acc += (sA * sB) * P, three MFMAs later.  The vector ALU cannot address the AGPR half of the
 // register file, so the running sums live in ordinary VGPRs; that is what sets the wave tile: 128
-// accumulator registers, two P buffers, four A and four B fragments of 8 registers each stay below
+// accumulator registers, four P buffers, four A and four B fragments of 8 registers each stay below
 // the 256 registers a wave has when two waves share a SIMD.
 //
 // Tile movements, each an Axe layout (the LDS side as in the bf16 kernel, reported by axe_gemm_describe):
@@ -36,9 +36,12 @@
 // the block just freed: one K-step to land, so it goes first) and then B of tile kt+3 (ring of
 // three blocks: a little more than one K-step).
 // The K rotation, the workgroup -> tile order and the chaining of a workgroup's tiles into one
-// pipeline are those of the bf16 kernel.  (Measured: chaining gains nothing here -- this kernel is
-// held back by the L2 -> CU path, which carries twice the bytes per flop of the bf16 kernel, not by
-// the fill and drain of its pipeline -- but it lets both kernels share one epilogue and launch shape.)
+// pipeline are those of the bf16 kernel.  (Measured: chaining gains nothing here.  With the MFMAs
+// taken out, the loads, LDS reads and barriers of this kernel alone run at the equivalent of 4.9
+// PFLOP/s -- 19 TB/s from the L2s, about what they deliver -- and a register-only loop of the MFMAs
+// and folds alone runs at 4.9 PFLOP/s as well: two streams that each nearly fill the time overlap
+// imperfectly.  The L2 -> CU path carries twice the bytes per flop of the bf16 kernel; a larger
+// tile would need more accumulator registers than two waves per SIMD have.)
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -55,6 +58,8 @@ constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
 constexpr int kRot = 8;                           // K-rotation window, in K-tiles
+constexpr int kFD = 3;                            // an MFMA's result is folded into the running sum kFD MFMAs later
+constexpr int kNP = 4;                            // product buffers (a power of two above kFD)
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(3))) uint8_t* lds_u8;
 __device__ __forceinline__ i32x8 lds_read32(lds_u8 p0, lds_u8 p1) {
@@ -163,7 +168,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   };
 
   i32x8 fa[4], fb[4];      // A fragment i sits in slot i % 4 (read three rows ahead of its use); B fragments 0..3 of the tile
-  f32x4 P[2];              // results of the last two MFMAs
+  f32x4 P[kNP];            // results of the last kNP MFMAs
 
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
@@ -180,8 +185,8 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   };
 
   // K-step kt (PAR = kt & 1) in exact program order (sched_barrier(0) forbids any reordering across
-  // it).  Slot q = 4 i + j: MFMA (i, j) from a zero accumulator; then the result of the MFMA before
-  // is folded into the running sum.  Row i also reads A fragment i + 3 (rows 5..7: fragments 0..2 of
+  // it).  Slot q = 4 i + j: MFMA (i, j) from a zero accumulator; then the result of MFMA q - 3 (long
+  // complete, so the fold never waits) is folded into the running sum.  Row i also reads A fragment i + 3 (rows 5..7: fragments 0..2 of
   // the next tile) into the slot row i - 1 has just left; in row 7 B fragment j of the next tile
   // replaces fragment j right after its last use.  The barrier follows row 4, when the last A read of
   // the tile has been issued.  Slots 2, 6, 10, 14 load B of tile kt+2; slots 20, 22, 24, 26 load A of
@@ -193,10 +198,10 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
 #pragma unroll
     for (int q = 0; q < 32; ++q) {
       const int i = q >> 2, j = q & 3;
-      P[q & 1] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i & 3], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+      P[q % kNP] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i & 3], f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
       __builtin_amdgcn_sched_barrier(0);
-      if (q > 0) fold((q - 1) >> 2, (q - 1) & 3, (q - 1) & 1, sc);
-      else if (kt > 0) fold(7, 3, 1, sc_prev);
+      if (q >= kFD) fold((q - kFD) >> 2, (q - kFD) & 3, (q - kFD) % kNP, sc);
+      else if (kt > 0) fold(7, 4 + q - kFD, (32 + q - kFD) % kNP, sc_prev);
       if (j == 1) {
         if (i < 5) read_a(i + 3, PAR);
         else read_a(i - 5, PAR ^ 1);
@@ -302,7 +307,8 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
         ++kt;
       }
     }
-    fold(7, 3, 1, sc_prev);
+#pragma unroll
+    for (int t = 0; t < kFD; ++t) fold(7, 4 - kFD + t, (32 - kFD + t) % kNP, sc_prev);
     // the tile is complete: store it while the loads of the next tile's first K-steps are on their way
 #pragma unroll
     for (int i = 0; i < 8; ++i)
