@@ -144,12 +144,14 @@ typedef struct {
                                the shape does not fit it)                                         */
 } axe_gemm_desc_t;
 
-enum { AXE_TILE_AUTO = 0, AXE_TILE_64x64x32 = 1, AXE_TILE_256x256x64 = 2 };
+enum { AXE_TILE_AUTO = 0, AXE_TILE_64x64x32 = 1, AXE_TILE_256x256x64 = 2, AXE_TILE_256x224x64 = 3 };
 
 int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d_C, void* stream);
 
 /* The kernel axe_gemm would launch for `g` (host only, device pointers not needed):
- * returns AXE_TILE_64x64x32 or AXE_TILE_256x256x64, or the error axe_gemm would return. */
+ * returns AXE_TILE_64x64x32, AXE_TILE_256x256x64 or AXE_TILE_256x224x64 (bf16 only: 224 columns of C
+ * per workgroup, chosen when N is a multiple of 224 and the tile count then fills the compute units
+ * better, e.g. N = 3584 with M = 4096), or the error axe_gemm would return. */
 int axe_gemm_tile(const axe_gemm_desc_t* g);
 
 /* ---------------------------------------------------------------------------------------------

@@ -421,23 +421,41 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   const int64_t bk = fp8 ? 128 : 64;
   // the large-tile kernels address a tile's 256 rows through 32-bit buffer offsets
   const bool pitch_ok = 256 * lda * eb < (int64_t(1) << 31) && 256 * ldb * eb < (int64_t(1) << 31);
-  const bool big_ok = (g->M % 256 == 0) && (g->N % 256 == 0) && (g->K % bk == 0) && (ldc % 8 == 0) &&
-                      P.args.out_bf16 && pitch_ok;
+  const bool big_common = (g->M % 256 == 0) && (g->K % bk == 0) && (ldc % 8 == 0) && P.args.out_bf16 && pitch_ok;
+  const bool big_ok = big_common && (g->N % 256 == 0);
+  // bf16 only: 224 columns per tile (7 fragments per wave instead of 8)
+  const bool n224_ok = big_common && !fp8 && (g->N % 224 == 0);
   int tile = g->tile_hint;
-  if (tile == AXE_TILE_AUTO) tile = big_ok ? AXE_TILE_256x256x64 : AXE_TILE_64x64x32;
+  if (tile == AXE_TILE_AUTO) {
+    tile = big_ok ? AXE_TILE_256x256x64 : (n224_ok ? AXE_TILE_256x224x64 : AXE_TILE_64x64x32);
+    if (big_ok && n224_ok) {
+      // both fit: the launch runs ceil(tiles / compute units) rounds of tiles one after the other,
+      // each as long as the tile is wide; take the narrower tile when that is shorter in total
+      const int64_t cus = axe::cu_count(), gm = g->M / 256;
+      const int64_t t256 = (gm * (g->N / 256) + cus - 1) / cus * 256, t224 = (gm * (g->N / 224) + cus - 1) / cus * 224;
+      if (t224 < t256) tile = AXE_TILE_256x224x64;
+    }
+  }
   if (tile == AXE_TILE_256x256x64 && !big_ok) {
     set_error("axe_gemm: the 256x256 tile needs M, N multiples of 256, K a multiple of %lld, bf16 output and "
               "row pitches below 2^31 / 256 bytes", (long long)bk);
     return AXE_EUNSUPPORTED;
   }
-  if (tile != AXE_TILE_256x256x64 && tile != AXE_TILE_64x64x32) {
+  if (tile == AXE_TILE_256x224x64 && !n224_ok) {
+    set_error("axe_gemm: the 256x224 tile needs bf16 inputs, M a multiple of 256, N of 224, K of 64, bf16 output and "
+              "row pitches below 2^31 / 256 bytes");
+    return AXE_EUNSUPPORTED;
+  }
+  if (tile != AXE_TILE_256x256x64 && tile != AXE_TILE_256x224x64 && tile != AXE_TILE_64x64x32) {
     set_error("axe_gemm: unknown tile_hint %d", tile);
     return AXE_EINVAL;
   }
   P.tile = tile;
-  const int64_t bt = tile == AXE_TILE_256x256x64 ? 256 : 64;
-  P.args.grid_m = (int32_t)((g->M + bt - 1) / bt);
-  P.args.grid_n = (int32_t)((g->N + bt - 1) / bt);
+  const int64_t bm = tile == AXE_TILE_64x64x32 ? 64 : 256;
+  const int64_t bn = tile == AXE_TILE_64x64x32 ? 64 : (tile == AXE_TILE_256x224x64 ? 224 : 256);
+  P.args.grid_m = (int32_t)((g->M + bm - 1) / bm);
+  P.args.grid_n = (int32_t)((g->N + bn - 1) / bn);
+  P.args.tile_n = (int32_t)bn;
   if (P.args.grid_m > 65535) {
     set_error("axe_gemm: M too large for one launch");
     return AXE_EUNSUPPORTED;
@@ -451,7 +469,7 @@ int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d
   GemmPlan P;
   if (int rc = plan_gemm(g, d_A, d_B, d_C, P, true)) return rc;
   hipError_t e;
-  if (P.tile == AXE_TILE_256x256x64)
+  if (P.tile == AXE_TILE_256x256x64 || P.tile == AXE_TILE_256x224x64)
     e = P.fp8 ? launch_gemm_fp8_256(P.args, (hipStream_t)stream) : launch_gemm_bf16_256(P.args, (hipStream_t)stream);
   else
     e = launch_gemm_small(P.args, P.fp8, (hipStream_t)stream);

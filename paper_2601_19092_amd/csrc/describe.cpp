@@ -32,17 +32,17 @@ int ilog2(int64_t v) {
   return l;
 }
 
-// Kernel geometry: workgroup tile T x T x BK elements, wave grid 2 x 2, MFMA fragment F x F,
-// LDS rows of ROWB bytes made of 16-byte chunks of CE elements.
+// Kernel geometry: workgroup tile T x TN x BK elements (T rows of A, TN rows of B), wave grid WM x WN,
+// MFMA fragment F x F, LDS rows of ROWB bytes made of 16-byte chunks of CE elements.
 struct Geo {
   bool big, fp8;
-  int T, BK, F, ROWB, CE, EB;
+  int T, TN, BK, F, ROWB, CE, EB;
   int WM, WN;      // wave grid: wave = WN * wm + wn; A rows are split over wm, B rows over wn
   int key_shift;   // swizzle key = (row >> key_shift) & (chunks per row - 1)
   int64_t b_off;   // element offset of the B block inside one LDS stage
 };
 
-Geo geometry(bool big, bool fp8) {
+Geo geometry(bool big, bool fp8, int tile_n) {
   Geo g;
   g.big = big;
   g.fp8 = fp8;
@@ -58,6 +58,7 @@ Geo geometry(bool big, bool fp8) {
     g.T = 64;
     g.F = 16;
   }
+  g.TN = tile_n;
   g.BK = g.ROWB / g.EB;
   g.key_shift = 1;
   // 256x256 kernels: five 32 KiB blocks, A in blocks 0 and 1, the B ring starts at block 2
@@ -77,7 +78,7 @@ int g2l_threads(const Geo& g, bool is_b, Builder& b) {
     // the swizzle shows up in which chunk a lane fetches: c ^ key(row), key = (4 (w & 1) + (lr >> 1)) & 7.
     // That key spans the wave id, so those maps are stated on the thread id t = 64 w + lane, folded
     // into the lane axis: key = (t >> 4) & 7.
-    const int NW = g.WM * g.WN, NI = g.T / (8 * NW);
+    const int NW = g.WM * g.WN, NI = (is_b ? g.TN : g.T) / (8 * NW);
     if (!is_b && !g.fp8) {
       rows = {{NI, g.CE, REG}, {NW, 1, WAVE}, {8, CH, LANE}};
     } else {
@@ -101,7 +102,7 @@ int g2l_threads(const Geo& g, bool is_b, Builder& b) {
   } else {
     for (auto& it : ks) b.d.push_back(it);
     for (auto& it : rows) b.d.push_back(it);
-    b.shape = {g.BK, g.T};
+    b.shape = {g.BK, g.TN};
   }
   return AXE_OK;
 }
@@ -115,9 +116,9 @@ int lds_layout(const Geo& g, bool is_b, Builder& b) {
     b.shape = {g.T, g.BK};
   } else {
     b.D(g.BK, 1, LDS);
-    b.D(g.T, g.BK, LDS);
+    b.D(g.TN, g.BK, LDS);
     b.off[LDS] = g.b_off;
-    b.shape = {g.BK, g.T};
+    b.shape = {g.BK, g.TN};
   }
   // chunk index ^= (row >> key_shift) & (CH - 1), in element units
   b.swz(LDS, ilog2(CH), ilog2(g.CE), ilog2(g.BK) + g.key_shift);
@@ -129,7 +130,7 @@ int lds_layout(const Geo& g, bool is_b, Builder& b) {
 // fragment, element): kernels that keep only a few fragments in registers at a time reuse the
 // physical registers, the index names the fragment.
 int operand_layout(const Geo& g, bool is_b, Builder& b) {
-  const int WT = is_b ? g.T / g.WN : g.T / g.WM;       // rows of this operand per wave
+  const int WT = is_b ? g.TN / g.WN : g.T / g.WM;      // rows of this operand per wave
   const int NF = WT / g.F;                             // fragments per wave
   const int LG = 64 / g.F;                             // lane groups along k
   const int KPL = g.fp8 ? 32 : 8;                      // k elements per lane per MFMA
@@ -153,7 +154,7 @@ int operand_layout(const Geo& g, bool is_b, Builder& b) {
   } else {
     for (auto& it : ks) b.d.push_back(it);
     for (auto& it : rows) b.d.push_back(it);
-    b.shape = {g.BK, g.T};
+    b.shape = {g.BK, g.TN};
   }
   b.R(is_b ? g.WM : g.WN, is_b ? g.WN : 1, WAVE);
   return AXE_OK;
@@ -162,7 +163,7 @@ int operand_layout(const Geo& g, bool is_b, Builder& b) {
 // (M, N) of the (tile-padded) problem -> wg, wave, lane, reg: the accumulators.  Operands are
 // swapped in the MFMA, so a lane owns, per 16 x 16 fragment, 4 consecutive columns of one row.
 int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Builder& b) {
-  const int NFM = g.T / g.WM / g.F, NFN = g.T / g.WN / g.F;
+  const int NFM = g.T / g.WM / g.F, NFN = g.TN / g.WN / g.F;
   const int per_frag = g.F * g.F / 64;                 // accumulator registers per fragment
   if (!tile_only) b.D(grid_m, grid_n, WG);
   b.D(g.WM, g.WN, WAVE);
@@ -173,8 +174,8 @@ int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Bui
   b.D(NFN, per_frag, REG);
   b.D(64 / g.F, g.F, LANE);
   b.D(4, 1, REG);
-  if (tile_only) b.shape = {g.T, g.T};
-  else b.shape = {grid_m * g.T, grid_n * g.T};
+  if (tile_only) b.shape = {g.T, g.TN};
+  else b.shape = {grid_m * g.T, grid_n * g.TN};
   return AXE_OK;
 }
 
@@ -195,7 +196,8 @@ extern "C" int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_la
   }
   int tile = axe_gemm_tile(g);
   if (tile < 0) return tile;
-  const Geo geo = geometry(tile == AXE_TILE_256x256x64, g->in_dtype == AXE_FP8_E4M3);
+  const bool big = tile != AXE_TILE_64x64x32;
+  const Geo geo = geometry(big, g->in_dtype == AXE_FP8_E4M3, tile == AXE_TILE_256x224x64 ? 224 : (big ? 256 : 64));
   Builder b;
   int rc;
   switch (which) {
@@ -206,7 +208,7 @@ extern "C" int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_la
     case AXE_DESC_A_OPERAND: rc = operand_layout(geo, false, b); break;
     case AXE_DESC_B_OPERAND: rc = operand_layout(geo, true, b); break;
     case AXE_DESC_ACC:
-      rc = acc_layout(geo, (g->M + geo.T - 1) / geo.T, (g->N + geo.T - 1) / geo.T, false, b);
+      rc = acc_layout(geo, (g->M + geo.T - 1) / geo.T, (g->N + geo.TN - 1) / geo.TN, false, b);
       break;
     case AXE_DESC_C_STORE: rc = c_store_layout(geo, b); break;
     default:

@@ -73,6 +73,7 @@ struct GemmArgs {
   int32_t nkb;
   int32_t out_bf16;                // 0: fp32 output, 1: bf16 output
   int32_t grid_m, grid_n;          // workgroup tiles along M and N
+  int32_t tile_n;                  // columns of C per workgroup tile (64, 224 or 256)
 };
 
 }  // namespace axe

@@ -70,16 +70,4 @@ __device__ __forceinline__ i32x4 raw_rsrc(const void* p, uint32_t bytes) {
                __builtin_amdgcn_readfirstlane((int)bytes), 0x00020000};
 }
 
-// Compute units of the current device (host side; asked once per process).
-inline int cu_count() {
-  static int cus = 0;
-  if (!cus) {
-    int dev = 0, n = 0;
-    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n <= 0)
-      n = 256;
-    cus = n;
-  }
-  return cus;
-}
-
 }  // namespace axe

@@ -1,4 +1,4 @@
-// bf16 GEMM for gfx950 (MI355X), workgroup tile 256 x 256 x 64, one workgroup of 4 waves per CU (one
+// bf16 GEMM for gfx950 (MI355X), workgroup tile 256 x 256 x 64 (or 256 x 224 x 64), one workgroup of 4 waves per CU (one
 // wave per SIMD); each wave owns a 128 x 128 sub-tile = 8 x 8 MFMA 16x16x32 fragments in 256
 // accumulator registers.  A is row-major (K contiguous), B column-major (K contiguous).
 //
@@ -42,6 +42,11 @@
 //   A: buffer_load into 16 x 4 staging registers per lane two K-steps ahead, ds_write_b128 into the
 //      double-buffered block half a K-step to one K-step ahead of use.
 //
+// Tile width.  The same kernel body exists with 224 instead of 256 columns of C per tile (7 instead
+// of 8 fragments per wave along N): M = 4096, N = 3584 makes 16 x 16 such tiles, one per CU, where
+// 256-wide tiles would leave 32 CUs idle (measured: 5 - 8 % faster; less than the 14 % of the tile
+// count because the chip is power-limited and 224 busy CUs clock higher than 256).
+//
 // Tiles.  When there are more tiles than CUs (and the number of K-steps is even and at least 4) one
 // workgroup per CU walks its tiles back to back: the load side simply runs on into the next tile's
 // first K-steps, so only the first tile of a workgroup has a prologue, and a tile's stores overlap
@@ -76,7 +81,12 @@ __device__ __forceinline__ void mfma_16x16x32(f32x4& acc, bf16x8 a, bf16x8 b) {
 }
 }  // namespace
 
-__global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
+// NB = columns of C per tile (B rows per tile): 256, or 224 = 2 waves x 7 fragments for problems whose
+// tile count then fills the compute units better (B pieces past row 223 are outside the tile's buffer
+// descriptor: they cost no traffic and fill LDS rows nobody reads).
+template <int NB>
+__device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
+  constexpr int NJ = NB / 32;                                      // fragments per wave along N
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
   const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
 
@@ -94,6 +104,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
   const int a_pitch = (int)(g.lda * 2), b_pitch = (int)(g.ldb * 2);
   struct Tile {
     __amdgpu_buffer_rsrc_t ra, rb;
+    i32x4 ra_words;                                                // ra once more, as the four SGPR words an asm statement takes
     int rot;
   };
   auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
@@ -103,16 +114,18 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
       tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda * 2), 0,
                                                255 * a_pitch + (int)g.K * 2, 0x00020000);
-      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * kTile * g.ldb * 2), 0,
-                                               255 * b_pitch + (int)g.K * 2, 0x00020000);
+      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * NB * g.ldb * 2), 0,
+                                               (NB - 1) * b_pitch + (int)g.K * 2, 0x00020000);
       // K rotation: each workgroup walks every aligned window of kRot K-tiles in its own rotated order
       // (the sum over k does not care), so that the workgroups sharing a panel fetch the kRot adjacent
       // lines of a row at once -- one 1 KiB burst per row -- and find the other lines in L2 during the
       // rest of the window (measured on the bare load stream: 16 -> 21.5 TB/s).
       t.rot = (tm + tn) & (kRot - 1);
+      t.ra_words = raw_rsrc((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda * 2, (uint32_t)(255 * a_pitch + (int)g.K * 2));
     } else {                                                       // no such tile: every load returns zero
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
+      t.ra_words = raw_rsrc(g.A, 0);
       t.rot = 0;
     }
     return t;
@@ -139,10 +152,16 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
 
   u32x4 stg[16];                                                   // A staging: slot (T & 1) * 8 + i
   // cross = false: the caller knows T < nk (steady part of the K loop), nothing of the next tile is looked at
+  // The staging loads are asm statements: the compiler then keeps no wait-count bookkeeping for them
+  // (what it keeps is merged conservatively over all paths into a loop and comes out as waits for
+  // loads issued one K-step ago); the counted waits in the sub-steps are the only ones.
   auto a_load = [&](int T, int i, bool cross) __attribute__((always_inline)) -> u32x4 {
     const bool nx = cross && T >= nk;
-    return __builtin_amdgcn_raw_buffer_load_b128(nx ? nxt.ra : cur.ra, a_voff,
-                                                 i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)), 0);
+    const i32x4 r = nx ? nxt.ra_words : cur.ra_words;
+    const int soff = __builtin_amdgcn_readfirstlane(i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)));
+    u32x4 v;
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
+    return v;
   };
   auto a_write = [&](int stage, int i, u32x4 v) __attribute__((always_inline)) {
     *(__attribute__((address_space(3))) u32x4*)(a_wr + stage * kBlk + i * 4096) = v;
@@ -166,18 +185,18 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
     fax[s] = lds3 + (wm * 128 + fr) * kRow + (((4 * s + fq) ^ fkey) << 4);
-    fbx[s] = lds3 + (wn * 128 + fr) * kRow + (((4 * s + fq) ^ fkey) << 4);
+    fbx[s] = lds3 + (wn * (NB / 2) + fr) * kRow + (((4 * s + fq) ^ fkey) << 4);
   }
 
-  f32x4 acc[8][8];
+  f32x4 acc[8][NJ];
 #pragma unroll
   for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  bf16x8 fa[8], fb[2][8];    // A fragment i serves one row of 8 MFMAs and is re-read right after it; B is double-buffered
+  bf16x8 fa[8], fb[2][NJ];    // A fragment i serves one row of 8 MFMAs and is re-read right after it; B is double-buffered
 
   // ---- VGPR -> HBM.  Operands are swapped in the MFMA, so lane l holds, for fragment (i, j), the 4
   //      consecutive columns j*16 + 4*(l/16) .. +3 of row i*16 + l%16 of the wave's 128 x 128 sub-tile:
@@ -193,8 +212,8 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
   auto set_output = [&](int vv) __attribute__((always_inline)) {
     int tm, tn;
     tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
-    rc = raw_rsrc((uint16_t*)g.C + ((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * kTile + wn * 128,
-                  (uint32_t)((127 * g.ldc + 128) * 2));
+    rc = raw_rsrc((uint16_t*)g.C + ((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * NB + wn * (NB / 2),
+                  (uint32_t)((127 * g.ldc + NB / 2) * 2));
     c_rowblk = (int)(16 * g.ldc * 2);
   };
   auto store_fragment = [&](int i, int j) __attribute__((always_inline)) {
@@ -210,10 +229,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
   using I1 = std::integral_constant<int, 1>;
 
   // Sub-step S of K-step kt (PAR = kt & 1), in exact program order (sched_barrier(0) forbids any
-  // reordering across it): 64 MFMAs, (i, j) with j innermost; in the first half the 8 B fragments of
-  // the next sub-step are read into the other buffer, and after each row i the A fragment i of the
-  // next sub-step replaces the one just used; after MFMAs 2, 18, 34, 50 one B load, after MFMAs 10,
-  // 26, 42, 58 one staged A piece goes to LDS and its slot is reloaded.  Steps past the end of the
+  // reordering across it): 8 x NJ MFMAs, (i, j) with j innermost; in rows 0..3 the B fragments of the
+  // next sub-step are read into the other buffer (after MFMAs j = 1 and j = 5), and after each row i
+  // the A fragment i of the next sub-step replaces the one just used; after MFMA j = 2 of the even
+  // rows one B load, of the odd rows one staged A piece goes to LDS and its slot is reloaded.  Steps past the end of the
   // tile are steps of the workgroup's next tile (or of none: then their loads return zero).
   auto substep = [&](auto par_c, auto s_c, auto cross_c, int kt) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value, S = decltype(s_c)::value;
@@ -231,21 +250,24 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
     const int bT = S == 0 ? kt + 2 : kt + 3;
     const int bslot = S == 0 ? bo2 : bo0;
 #pragma unroll
-    for (int q = 0; q < 64; ++q) {
-      const int i = q >> 3, j = q & 7;
-      mfma_16x16x32(acc[i][j], fb[CUR][j], fa[i]);
-      __builtin_amdgcn_sched_barrier(0);
-      if ((q & 3) == 1 && q < 32) fb[NXT][q >> 2] = lds_read(pb + (q >> 2) * 16 * kRow);
-      if ((q & 7) == 7) fa[i] = lds_read(pa + i * 16 * kRow);
-      if ((q & 15) == 2) b_load(bT, (S == 0 ? 4 : 0) + (q >> 4), bslot, CROSS);
-      if ((q & 15) == 10) {
-        const int p = (S == 0 ? 4 : 0) + (q >> 4);
-        // the load that filled this slot was issued 4 sub-steps ago; 31 loads have been issued since
-        asm volatile("s_waitcnt vmcnt(31)" ::: "memory");
-        a_write(WST, p, stg[WST * 8 + p]);
-        stg[WST * 8 + p] = a_load(wT + 2, p, CROSS);
+    for (int i = 0; i < 8; ++i) {
+#pragma unroll
+      for (int j = 0; j < NJ; ++j) {
+        mfma_16x16x32(acc[i][j], fb[CUR][j], fa[i]);
+        __builtin_amdgcn_sched_barrier(0);
+        if (i < 4 && (j == 1 || j == 5) && 2 * i + (j == 5) < NJ)
+          fb[NXT][2 * i + (j == 5)] = lds_read(pb + (2 * i + (j == 5)) * 16 * kRow);
+        if (j == NJ - 1) fa[i] = lds_read(pa + i * 16 * kRow);
+        if ((i & 1) == 0 && j == 2) b_load(bT, (S == 0 ? 4 : 0) + (i >> 1), bslot, CROSS);
+        if ((i & 1) == 1 && j == 2) {
+          const int p = (S == 0 ? 4 : 0) + (i >> 1);
+          // the load that filled this slot was issued 4 sub-steps ago; 31 loads have been issued since
+          asm volatile("s_waitcnt vmcnt(31)" ::: "memory");
+          a_write(WST, p, stg[WST * 8 + p]);
+          stg[WST * 8 + p] = a_load(wT + 2, p, CROSS);
+        }
+        __builtin_amdgcn_sched_barrier(0);
       }
-      __builtin_amdgcn_sched_barrier(0);
     }
     if (S == 0) {
       // Own reads of step kt and own writes of step kt+1 are complete, and so are own B loads of step
@@ -291,7 +313,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   wg_barrier();
 #pragma unroll
-  for (int f = 0; f < 8; ++f) fb[0][f] = lds_read(fbx[0] + bo0 + f * 16 * kRow);
+  for (int f = 0; f < NJ; ++f) fb[0][f] = lds_read(fbx[0] + bo0 + f * 16 * kRow);
 #pragma unroll
   for (int f = 0; f < 8; ++f) fa[f] = lds_read(fax[0] + f * 16 * kRow);
 
@@ -317,13 +339,18 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) {
 #pragma unroll
     for (int i = 0; i < 8; ++i)
 #pragma unroll
-      for (int j = 0; j < 8; ++j) store_fragment(i, j);
+      for (int j = 0; j < NJ; ++j) store_fragment(i, j);
     v += (int)gridDim.x;
     if (v >= ntiles) break;
     cur = nxt;
     nxt = describe(v + (int)gridDim.x);
   }
 }
+
+// (plain kernels around the template: a __global__ template would be instantiated by the host pass
+//  too, which cannot parse the register constraints of the asm statements)
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) { gemm_bf16_256_body<256>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256x224_kernel(GemmArgs g) { gemm_bf16_256_body<224>(g); }
 
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -332,7 +359,10 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   // one resident workgroup per CU walks several tiles when the pipeline can continue across tiles
   const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
   unsigned nwg = (unsigned)(chain ? cus : ntiles);
-  hipLaunchKernelGGL(gemm_bf16_256_kernel, dim3(nwg), dim3(256), 0, s, g);
+  if (g.tile_n == 224)
+    hipLaunchKernelGGL(gemm_bf16_256x224_kernel, dim3(nwg), dim3(256), 0, s, g);
+  else
+    hipLaunchKernelGGL(gemm_bf16_256_kernel, dim3(nwg), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 

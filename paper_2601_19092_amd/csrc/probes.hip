@@ -11,6 +11,7 @@
 
 #include "../../include/axe_probe.h"
 #include "gemm_common.h"
+#include "kernels.h"
 
 namespace {
 using axe::bf16x8;

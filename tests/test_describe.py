@@ -24,6 +24,8 @@ def desc_for(kind):
         M, N, K, dt, out, tile = 128, 192, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_64x64x32
     elif kind == "big_fp8":
         M, N, K, dt, out, tile = 512, 768, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_AUTO
+    elif kind == "big_bf16_n224":
+        M, N, K, dt, out, tile = 512, 672, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_AUTO
     else:
         M, N, K, dt, out, tile = 512, 768, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_AUTO
     d = B.GemmDesc(M, N, K, dt, out, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, N)),
@@ -41,21 +43,25 @@ def table(L, shape):
     return R.evaluate_np(L, np.arange(prod(shape)), AXES)
 
 
-GEO = {"small_bf16": dict(T=64, BK=32, EB=2, waves=4, wn=2), "small_fp8": dict(T=64, BK=128, EB=1, waves=4, wn=2),
-       "big_bf16": dict(T=256, BK=64, EB=2, waves=4, wn=2), "big_fp8": dict(T=256, BK=128, EB=1, waves=8, wn=4)}
-KINDS = ["small_bf16", "small_fp8", "big_bf16", "big_fp8"]
-BIG = ("big_bf16", "big_fp8")
+# T x TN x BK: rows of A, rows of B (columns of C) and K elements per workgroup tile
+GEO = {"small_bf16": dict(T=64, TN=64, BK=32, EB=2, waves=4, wn=2), "small_fp8": dict(T=64, TN=64, BK=128, EB=1, waves=4, wn=2),
+       "big_bf16": dict(T=256, TN=256, BK=64, EB=2, waves=4, wn=2), "big_fp8": dict(T=256, TN=256, BK=128, EB=1, waves=8, wn=4),
+       "big_bf16_n224": dict(T=256, TN=224, BK=64, EB=2, waves=4, wn=2)}
+KINDS = ["small_bf16", "small_fp8", "big_bf16", "big_fp8", "big_bf16_n224"]
+BIG = ("big_bf16", "big_fp8", "big_bf16_n224")
+TILE = {"small_bf16": B.AXE_TILE_64x64x32, "small_fp8": B.AXE_TILE_64x64x32, "big_bf16": B.AXE_TILE_256x256x64,
+        "big_fp8": B.AXE_TILE_256x256x64, "big_bf16_n224": B.AXE_TILE_256x224x64}
 
 
 @pytest.mark.parametrize("kind", KINDS)
 def test_tile_shapes_and_kernel_choice(kind):
     desc, _ = desc_for(kind)
     geo = GEO[kind]
-    assert B.axe_gemm_tile(desc) == (B.AXE_TILE_256x256x64 if kind in BIG else B.AXE_TILE_64x64x32)
-    for which, want in ((B.AXE_DESC_A_G2L_THREADS, (geo["T"], geo["BK"])), (B.AXE_DESC_B_G2L_THREADS, (geo["BK"], geo["T"])),
-                        (B.AXE_DESC_A_LDS, (geo["T"], geo["BK"])), (B.AXE_DESC_B_LDS, (geo["BK"], geo["T"])),
-                        (B.AXE_DESC_A_OPERAND, (geo["T"], geo["BK"])), (B.AXE_DESC_B_OPERAND, (geo["BK"], geo["T"])),
-                        (B.AXE_DESC_C_STORE, (geo["T"], geo["T"]))):
+    assert B.axe_gemm_tile(desc) == TILE[kind]
+    for which, want in ((B.AXE_DESC_A_G2L_THREADS, (geo["T"], geo["BK"])), (B.AXE_DESC_B_G2L_THREADS, (geo["BK"], geo["TN"])),
+                        (B.AXE_DESC_A_LDS, (geo["T"], geo["BK"])), (B.AXE_DESC_B_LDS, (geo["BK"], geo["TN"])),
+                        (B.AXE_DESC_A_OPERAND, (geo["T"], geo["BK"])), (B.AXE_DESC_B_OPERAND, (geo["BK"], geo["TN"])),
+                        (B.AXE_DESC_C_STORE, (geo["T"], geo["TN"]))):
         L, shape = get(desc, which)
         assert shape == want and ax.admits(L, shape)
 
@@ -64,21 +70,21 @@ def test_tile_shapes_and_kernel_choice(kind):
 def test_accumulator_layout_is_a_bijection_and_a_tile_product(kind):
     desc, (M, N, K) = desc_for(kind)
     geo = GEO[kind]
-    T = geo["T"]
+    T, TN = geo["T"], geo["TN"]
     L, shape = get(desc, B.AXE_DESC_ACC)
-    gm, gn = -(-M // T), -(-N // T)
-    assert shape == (gm * T, gn * T)
+    gm, gn = -(-M // T), -(-N // TN)
+    assert shape == (gm * T, gn * TN)
     pts = table(L, shape)[:, 0, :]
     NW, WN = geo["waves"], geo["wn"]
     WM = NW // WN
-    regs = T * T // (64 * NW)
+    regs = T * TN // (64 * NW)
     box = np.stack(np.meshgrid(np.arange(gm * gn), np.arange(NW), np.arange(64), np.arange(regs), indexing="ij"), -1).reshape(-1, 4)
     got = pts[:, [2, 3, 4, 5]]
     assert np.all(pts[:, [0, 1]] == 0)
     assert len(got) == len(box) and np.array_equal(np.unique(got, axis=0), box)      # every accumulator exactly once
     # composition: grid (x) WM x WN waves (x) fragments-in-registers (x) MFMA accumulator fragment
     F = 16
-    NFM, NFN = T // WM // F, T // WN // F
+    NFM, NFN = T // WM // F, TN // WN // F
     per = F * F // 64
     # 16x16 fragment with swapped operands: row -> lane, column 4b + c' -> lane + 16 b, reg c'
     frag = Layout.make((16, 4, 4), ("1@lane", "16@lane", "1@reg"))
@@ -87,7 +93,7 @@ def test_accumulator_layout_is_a_bijection_and_a_tile_product(kind):
     grid = Layout.make((gm, gn), (f"{gn}@wg", "1@wg"))
     t1, s1 = ax.tile(regs_t, (NFM, NFN), frag, (F, F))
     t2, s2 = ax.tile(waves, (WM, WN), t1, (NFM * F, NFN * F))
-    t3, s3 = ax.tile(grid, (gm, gn), t2, (T, T))
+    t3, s3 = ax.tile(grid, (gm, gn), t2, (T, TN))
     assert ax.span(frag)["reg"] == per
     want = R.evaluate_np(t3, np.arange(prod(shape)), AXES)[:, 0, :]
     assert np.array_equal(want, pts)
@@ -97,22 +103,23 @@ def test_accumulator_layout_is_a_bijection_and_a_tile_product(kind):
 def test_global_to_lds_thread_map(kind):
     desc, _ = desc_for(kind)
     geo = GEO[kind]
-    T, BK, EB = geo["T"], geo["BK"], geo["EB"]
+    T, TN, BK, EB = geo["T"], geo["TN"], geo["BK"], geo["EB"]
     CE = 16 // EB
     for which_t, which_l, shape in ((B.AXE_DESC_A_G2L_THREADS, B.AXE_DESC_A_LDS, (T, BK)),
-                                    (B.AXE_DESC_B_G2L_THREADS, B.AXE_DESC_B_LDS, (BK, T))):
+                                    (B.AXE_DESC_B_G2L_THREADS, B.AXE_DESC_B_LDS, (BK, TN))):
+        R_ = shape[0] if which_l == B.AXE_DESC_A_LDS else shape[1]      # rows of this operand in the tile
         Lt, st = get(desc, which_t)
         Ll, sl = get(desc, which_l)
         assert st == sl == shape
         th = table(Lt, shape)[:, 0, :]
         NW = geo["waves"]
-        regs = T * BK // (64 * NW)
+        regs = R_ * BK // (64 * NW)
         key = (th[:, 3] * 64 + th[:, 4]) * regs + th[:, 5]
-        assert np.array_equal(np.sort(key), np.arange(T * BK))           # every thread register exactly once
+        assert np.array_equal(np.sort(key), np.arange(R_ * BK))          # every thread register exactly once
         lds = table(Ll, shape)[:, 0, 1]
         # B block: right after A in the small kernels; the 256x256 bf16 kernel keeps two A blocks first
         base = 0 if which_l == B.AXE_DESC_A_LDS else T * BK * (2 if kind in BIG else 1)
-        assert np.array_equal(np.sort(lds), np.arange(base, base + T * BK))   # LDS stage filled exactly once
+        assert np.array_equal(np.sort(lds), np.arange(base, base + R_ * BK))  # LDS stage filled exactly once
         # each lane moves whole 16-byte chunks: CE consecutive registers <-> CE consecutive k <-> CE consecutive LDS elements
         order = np.argsort(key)
         lds_by_thread = lds[order].reshape(NW, 64, regs // CE, CE)
@@ -155,10 +162,10 @@ def bank_conflicts(byte_addrs):
 def test_operand_reads_cover_the_tile_and_are_bank_conflict_free(kind):
     desc, _ = desc_for(kind)
     geo = GEO[kind]
-    T, BK, EB = geo["T"], geo["BK"], geo["EB"]
+    T, TN, BK, EB = geo["T"], geo["TN"], geo["BK"], geo["EB"]
     CE = 16 // EB
     for which_o, which_l, shape in ((B.AXE_DESC_A_OPERAND, B.AXE_DESC_A_LDS, (T, BK)),
-                                    (B.AXE_DESC_B_OPERAND, B.AXE_DESC_B_LDS, (BK, T))):
+                                    (B.AXE_DESC_B_OPERAND, B.AXE_DESC_B_LDS, (BK, TN))):
         Lo, _ = get(desc, which_o)
         Ll, _ = get(desc, which_l)
         NW, WN = geo["waves"], geo["wn"]
@@ -167,7 +174,7 @@ def test_operand_reads_cover_the_tile_and_are_bank_conflict_free(kind):
         repl = WM if is_b else WN                              # waves that hold the same operand rows
         op = table(Lo, shape)                                  # [E, replicas, 6]
         assert op.shape[1] == repl
-        regs = (T // (WN if is_b else WM)) * BK // 64
+        regs = ((TN // WN) if is_b else (T // WM)) * BK // 64
         key = ((op[:, :, 3] * 64 + op[:, :, 4]) * regs + op[:, :, 5]).reshape(-1)
         assert np.array_equal(np.sort(key), np.arange(NW * 64 * regs))     # each wave holds its share, once
         for swz, expect_clean in ((True, True), (False, False)):
@@ -180,23 +187,23 @@ def test_operand_reads_cover_the_tile_and_are_bank_conflict_free(kind):
             assert (worst == 1) == expect_clean, (kind, which_o, swz, worst)
 
 
-@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16", "big_fp8"])
+@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16", "big_fp8", "big_bf16_n224"])
 def test_c_store_map(kind):
     desc, _ = desc_for(kind)
-    T, NW, WN = GEO[kind]["T"], GEO[kind]["waves"], GEO[kind]["wn"]
+    T, TN, NW, WN = GEO[kind]["T"], GEO[kind]["TN"], GEO[kind]["waves"], GEO[kind]["wn"]
     L, shape = get(desc, B.AXE_DESC_C_STORE)
     pts = table(L, shape)[:, 0, :]
-    regs = T * T // (64 * NW)
+    regs = T * TN // (64 * NW)
     key = (pts[:, 3] * 64 + pts[:, 4]) * regs + pts[:, 5]
-    assert np.array_equal(np.sort(key), np.arange(T * T))
+    assert np.array_equal(np.sort(key), np.arange(T * TN))
     if kind in BIG:
         # accumulator fragments are stored directly: one store instruction (4 consecutive registers of
         # every lane) covers 16 rows x 16 columns, 4 lanes x 4 elements = 32 contiguous bytes per row;
         # the fragments of a fragment row follow one another and complete T / WN * 2 bytes per row
-        nj = T // WN // 16                                            # fragments per fragment row
-        col = np.empty(T * T, dtype=np.int64); row = np.empty(T * T, dtype=np.int64)
-        idx = np.arange(T * T)
-        row[key], col[key] = idx // T, idx % T
+        nj = TN // WN // 16                                           # fragments per fragment row
+        col = np.empty(T * TN, dtype=np.int64); row = np.empty(T * TN, dtype=np.int64)
+        idx = np.arange(T * TN)
+        row[key], col[key] = idx // TN, idx % TN
         row, col = row.reshape(NW, 64, regs // 4, 4), col.reshape(NW, 64, regs // 4, 4)
         assert np.all(np.diff(col, axis=-1) == 1) and np.all(row[..., 0:1] == row)
         for w, t in itertools.product(range(NW), range(regs // 4)):

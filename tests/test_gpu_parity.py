@@ -243,6 +243,14 @@ def run_gemm(g: W.GemmInputs, tile=B.AXE_TILE_AUTO, device_axis=False, lda=None,
     return c.astype(np.float64) if g.out_dtype == "f32" else R.bf16_to_f64(c.view(np.uint16))
 
 
+def gemm_desc_only(g: W.GemmInputs, tile=B.AXE_TILE_AUTO):
+    """Descriptor of the plain problem (no device buffers): for questions to the host side."""
+    As, Bs, Cs = W.gemm_specs(g)
+    return B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16 if g.dtype == "bf16" else B.AXE_FP8_E4M3,
+                      B.AXE_F32 if g.out_dtype == "f32" else B.AXE_BF16,
+                      B.Layout(As), B.Layout(Bs), B.Layout(Cs), g.M * g.K, g.N * g.K, g.M * g.N, tile_hint=tile)
+
+
 def oracle_gemm(g: W.GemmInputs, rows=None, cols=None):
     dt = R.AXE_BF16 if g.dtype == "bf16" else R.AXE_FP8_E4M3
     return R.gemm_ref(g.a_mk, g.b_nk.T, dt, g.scale_a, g.scale_b, rows=rows, cols=cols)
@@ -317,6 +325,16 @@ def test_gemm_bf16_large_tile(M, N, K):
     assert R.rel_frobenius(c, c_small) < 2e-3
 
 
+# 224 columns per tile (7 fragments per wave along N): same K cases, N a multiple of 224
+@pytest.mark.parametrize("M,N,K", [(256, 224, 64), (256, 448, 128), (512, 672, 192), (768, 224, 1024), (512, 448, 704)])
+def test_gemm_bf16_large_tile_224_columns(M, N, K):
+    g = W.gemm_bf16(M, N, K, 170 + K)
+    c = run_gemm(g, tile=B.AXE_TILE_256x224x64)
+    check_gemm(c, oracle_gemm(g), BF16_TOL, tile=32)
+    c_small = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+    assert R.rel_frobenius(c, c_small) < 2e-3
+
+
 def test_gemm_bf16_large_tile_identity_pitched_and_device_axis():
     K = N = 256
     g = W.gemm_bf16(K, N, K, 71)
@@ -337,12 +355,12 @@ def test_gemm_fp8_large_tile(M, N, K, scaled):
 
 
 # ----------------------------------------------------------------------------- full-size configurations
-def full_size_check(g: W.GemmInputs, tol, device_axis=False, seed=0):
+def full_size_check(g: W.GemmInputs, tol, device_axis=False, seed=0, tile=B.AXE_TILE_AUTO):
     """Whole C on the GPU in the launch configuration the benchmark times; the oracle computes
     sampled 128 x 128 tiles, two full rows, two full columns and scattered single elements one by
     one; two randomised projections (C v and u^T C, computed in fp64 from the inputs) cover every
     256-row and 256-column block of the full matrix."""
-    c = run_gemm(g, device_axis=device_axis)
+    c = run_gemm(g, device_axis=device_axis, tile=tile)
     assert np.isfinite(c).all()
     rng = np.random.default_rng(seed)
     M, N = g.M, g.N
@@ -391,7 +409,10 @@ def test_gemm_config3_full_size():
 
 
 def test_gemm_config4_full_size_shard():
-    full_size_check(W.config4(), BF16_TOL, device_axis=True, seed=4)
+    g = W.config4()
+    # 16 x 16 tiles of 256 x 224 fill the 256 compute units; 16 x 14 tiles of 256 x 256 would leave 32 idle
+    assert B.axe_gemm_tile(gemm_desc_only(g)) == B.AXE_TILE_256x224x64
+    full_size_check(g, BF16_TOL, device_axis=True, seed=4)
 
 
 def test_gemm_config5_full_size_fp8_scaled():
@@ -403,5 +424,10 @@ def test_gemm_chained_tiles_on_a_grid_of_17_by_16():
     grid that is not made of 16 x 16 blocks (the other workgroup -> tile order); the last 16 workgroups
     get a second tile, the others do not."""
     full_size_check(W.gemm_bf16(4352, 4096, 512, 91), BF16_TOL, seed=6)
+    # 224-column tiles, 17 x 16 of them
+    # (left to itself the library takes 17 x 14 tiles of 256 x 256 here: one round instead of two)
+    g = W.gemm_bf16(4352, 3584, 512, 93)
+    assert B.axe_gemm_tile(gemm_desc_only(g)) == B.AXE_TILE_256x256x64
+    full_size_check(g, BF16_TOL, seed=8, tile=B.AXE_TILE_256x224x64)
     # fp8: 66 K-steps, so the register of block scales is refilled inside each chained tile
     full_size_check(W.gemm_fp8(4352, 4096, 8448, 92, scaled=True), FP8_TOL, seed=7)
