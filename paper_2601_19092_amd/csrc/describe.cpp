@@ -181,8 +181,25 @@ int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Bui
 
 // (T, T) tile of C -> wave, lane, reg: who stores which element.
 int c_store_layout(const Geo& g, Builder& b) {
-  // every kernel stores its accumulator fragments directly: the store map is the accumulator layout
-  // of one tile (8 bytes of bf16 per lane and fragment)
+  // The bf16 256 x 256 kernel pairs neighbouring fragments: after an exchange between lane groups a
+  // lane stores 8 consecutive columns (16 bytes).  Column = 128 wn + 32 p + 16 b + 8 h + 4 t + e is
+  // stored by lane group 2 h + b from register 8 p + 4 t + e of the fragment row.
+  if (g.big && !g.fp8 && g.TN == 256) {
+    const int NFM = g.T / g.WM / g.F;
+    b.D(g.WM, g.WN, WAVE);
+    b.D(NFM, 32, REG);
+    b.D(g.F, 1, LANE);
+    b.D(g.WN, 1, WAVE);
+    b.D(4, 8, REG);
+    b.D(2, 16, LANE);
+    b.D(2, 32, LANE);
+    b.D(2, 4, REG);
+    b.D(4, 1, REG);
+    b.shape = {g.T, g.TN};
+    return AXE_OK;
+  }
+  // the other kernels store their accumulator fragments as they are: the store map is the accumulator
+  // layout of one tile (8 bytes of bf16 per lane and fragment)
   return acc_layout(g, 1, 1, true, b);
 }
 

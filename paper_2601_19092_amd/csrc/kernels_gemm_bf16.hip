@@ -27,8 +27,10 @@
 //                 16x16x32 operand layout (8 consecutive k per lane).
 //   MFMA        : operands swapped (B fragment first) so that a lane's accumulator fragment holds 4
 //                 consecutive columns of one C row.
-//   VGPR -> HBM : accumulators -> bf16, 8 bytes per lane and fragment, stored directly (the eight
-//                 fragments of a fragment row complete 256 contiguous bytes per row; L2 merges them).
+//   VGPR -> HBM : accumulators -> bf16, stored directly: two neighbouring fragments exchange halves between
+//                 lane groups (v_permlane16_swap) so that a lane stores 16 contiguous bytes, an instruction
+//                 64 contiguous bytes of 16 rows (the four pairs of a fragment row complete 256 bytes per
+//                 row; L2 merges them).  The 224-wide tile stores fragment by fragment, 8 bytes per lane.
 //
 // Schedule.  A K-step is two sub-steps of 64 MFMAs; a sub-step also reads the 16 fragments of the
 // next sub-step and moves 4 pieces of each operand.  One workgroup barrier per K-step, after sub-step
@@ -224,6 +226,23 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile
   };
+  // Two neighbouring fragments (i, j), (i, j + 1) in one 16-byte store per lane: lane groups q = l / 16
+  // hold columns 4 q .. 4 q + 3 of each fragment; v_permlane16_swap exchanges the odd lane groups of
+  // the first with the even lane groups of the second, after which an even group q owns columns
+  // 4 q .. 4 q + 7 of fragment j and an odd group q columns 4 (q - 1) .. 4 q + 3 of fragment j + 1.
+  // Half as many store instructions and write requests; 64 contiguous bytes per row and instruction.
+  const int c_voff2 = (int)((fr * g.ldc + ((fq & 1) ? 16 + 4 * (fq - 1) : 4 * fq)) * 2);
+  auto store_fragment_pair = [&](int i, int j) __attribute__((always_inline)) {
+    const auto lo = __builtin_amdgcn_permlane16_swap(pack_bf16(acc[i][j][0], acc[i][j][1]),
+                                                     pack_bf16(acc[i][j + 1][0], acc[i][j + 1][1]), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16(acc[i][j][2], acc[i][j][3]),
+                                                     pack_bf16(acc[i][j + 1][2], acc[i][j + 1][3]), false, false);
+    const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
+    const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
+    asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
+  };
 
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
@@ -336,10 +355,18 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     // the tile is complete: store it while the loads of the next tile's first K-steps, issued by the
     // steps above, are on their way; the MFMAs have to retire before their results are read
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);                             // no accumulator read may move above the padding
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i) {
 #pragma unroll
-      for (int j = 0; j < NJ; ++j) store_fragment(i, j);
+      for (int j = 0; j < NJ; j += 2) {
+        if (NJ % 2 == 0) store_fragment_pair(i, j);                // (7 fragments per row do not pair up: stored one by one)
+        else {
+          store_fragment(i, j);
+          if (j + 1 < NJ) store_fragment(i, j + 1);
+        }
+      }
+    }
     v += (int)gridDim.x;
     if (v >= ntiles) break;
     cur = nxt;

@@ -197,24 +197,38 @@ def test_c_store_map(kind):
     key = (pts[:, 3] * 64 + pts[:, 4]) * regs + pts[:, 5]
     assert np.array_equal(np.sort(key), np.arange(T * TN))
     if kind in BIG:
-        # accumulator fragments are stored directly: one store instruction (4 consecutive registers of
-        # every lane) covers 16 rows x 16 columns, 4 lanes x 4 elements = 32 contiguous bytes per row;
-        # the fragments of a fragment row follow one another and complete T / WN * 2 bytes per row
-        nj = TN // WN // 16                                           # fragments per fragment row
+        # per = registers of one store instruction.  The fp8 and the 224-wide bf16 kernels store a fragment
+        # at a time (4 registers = 4 columns per lane: 16 rows x 32 contiguous bytes); the 256-wide bf16
+        # kernel stores fragment pairs (8 registers = 8 columns per lane: 16 rows x 64 contiguous bytes).
+        # Either way the stores of a fragment row follow one another and complete TN / WN * 2 bytes per row.
+        per = 8 if kind == "big_bf16" else 4
+        lanes_per_row = 64 // 16
+        per_row = TN // WN // (per * lanes_per_row)                   # store instructions per fragment row
         col = np.empty(T * TN, dtype=np.int64); row = np.empty(T * TN, dtype=np.int64)
         idx = np.arange(T * TN)
         row[key], col[key] = idx // TN, idx % TN
-        row, col = row.reshape(NW, 64, regs // 4, 4), col.reshape(NW, 64, regs // 4, 4)
+        row, col = row.reshape(NW, 64, regs // per, per), col.reshape(NW, 64, regs // per, per)
         assert np.all(np.diff(col, axis=-1) == 1) and np.all(row[..., 0:1] == row)
-        for w, t in itertools.product(range(NW), range(regs // 4)):
+        assert np.all(col[..., 0] % per == 0)                         # aligned 8- or 16-byte stores
+        for w, t in itertools.product(range(NW), range(regs // per)):
             r, c = row[w, :, t, 0], col[w, :, t, 0]
             assert len(set(r.tolist())) == 16
             for rr in set(r.tolist()):
                 cs = np.sort(c[r == rr])
-                assert np.array_equal(cs, cs[0] + 4 * np.arange(4)) and cs[0] % 16 == 0
-        for w, i in itertools.product(range(NW), range(8)):           # fragment row i: fragments nj i .. nj i + nj - 1
-            c0 = np.sort(np.unique(col[w, :, nj * i:nj * i + nj, :]))
-            assert np.array_equal(c0, c0[0] + np.arange(16 * nj))
+                assert np.array_equal(cs, cs[0] + per * np.arange(4)) and cs[0] % (4 * per) == 0
+        for w, i in itertools.product(range(NW), range(8)):           # fragment row i
+            c0 = np.sort(np.unique(col[w, :, per_row * i:per_row * i + per_row, :]))
+            assert np.array_equal(c0, c0[0] + np.arange(TN // WN))
+    if kind == "big_bf16":
+        # the exchange: lane group q = lane // 16 of the accumulator layout holds columns 4 q .. 4 q + 3 of
+        # each fragment; the storing lane group of column c (inside its 32-column fragment pair) is
+        # 2 * ((c % 16) // 8) + (c // 16): even groups store the first fragment, odd groups the second
+        acc, _ = get(desc, B.AXE_DESC_ACC)
+        for r, c in ((0, 0), (3, 5), (17, 12), (100, 16), (130, 27), (255, 255), (77, 200)):
+            (p,) = ax.evaluate_at(L, shape, (r, c), AXES)
+            cc = c % 32
+            assert p[4] == r % 16 + 16 * (2 * ((cc % 16) // 8) + cc // 16)
+            assert p[5] % 8 == 4 * ((cc % 8) // 4) + c % 4 and p[3] == 2 * (r // 128) + c // 128
 
 
 def test_mfma_operand_layout_matches_its_statement():
