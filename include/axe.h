@@ -49,7 +49,10 @@ enum {
                              share an address), or a non-memory axis has extent > 1 on one GPU        */
   AXE_ERANGE       = -4,  /* an address falls outside the declared buffer, or arithmetic overflows    */
   AXE_EUNSUPPORTED = -5,  /* valid layouts outside the kernel families of this library               */
-  AXE_EHIP         = -6   /* HIP runtime failure (launch error)                                       */
+  AXE_EHIP         = -6,  /* HIP runtime failure (launch error)                                       */
+  AXE_ENOFORM      = -7   /* a layout operator's sufficient conditions do not hold (the paper's FAILURE
+                             outcome of grouping, tile-of and slice): valid inputs, no answer of the
+                             required form                                                             */
 };
 
 /* Def. 2.1: f_I(x) = (x * stride) @ axis;  extent > 0, stride != 0, 0 <= axis < n_axes. */
@@ -181,6 +184,52 @@ enum {
 };
 int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_layout_t* out,
                       int64_t* shape, int32_t* rank, void* arena, size_t arena_bytes);
+
+/* ---------------------------------------------------------------------------------------------
+ * Layout operators (Sec. 3.3; Apps. A - F).  Host only: pure integer bookkeeping on (D, R, O),
+ * nothing is launched.  Results are written through `out`, whose d / r / offset pointers point
+ * into the caller's HOST `arena` (1 KiB is always enough); out->axis_names is the first operand's.
+ * Operands of one call must share one axis list (equal n_axes).  A result with more than
+ * AXE_MAX_D / AXE_MAX_R iters is AXE_ERANGE.
+ *
+ *   axe_layout_span          span[a] = 1 + sum |stride| (extent - 1) over the D and R iters on axis a
+ *                            (Sec. 2.3; O does not enter); span has n_axes entries.
+ *   axe_layout_canonicalize  App. A: D0 (drop unit iters), D1 (fuse a chain (e1, e2 s2)(e2, s2) on one
+ *                            axis) on D; C0 (drop unit iters), C1 (strides positive, the reach goes
+ *                            into O), C2 (absorb (e2, q s) into (e1, s) when 1 <= q <= e1) on (R, O).
+ *                            R comes out sorted by (axis, stride, extent).  A swizzle stage is kept.
+ *   axe_layout_gap_condition 1 if the sign-normalised replicas satisfy the gap condition (per axis,
+ *                            strides increasing, each above extent x stride of the one before), under
+ *                            which the canonical form is unique; 0 if not; negative on error.
+ *   axe_layout_equal         1 if the canonical forms (and swizzle stages) coincide, else 0; a 0 is
+ *                            conclusive when both operands satisfy the gap condition.
+ *   axe_layout_group         Alg. 1: the same map with D cut into `rank` consecutive blocks whose
+ *                            extent products are shape[i] (iters split by gcd where they straddle a
+ *                            boundary); block_end[i] = number of iters in blocks 0..i.
+ *   axe_layout_tile          Alg. 2: T = A (x) B, f_T(x || y) = f_A(x) * span(B) + f_B(y); A and B
+ *                            grouped by SA and SB (same rank); shape_out = (SA[0], SB[0], SA[1], ...),
+ *                            2 * rank entries.  B may carry a swizzle stage if everything A adds on the
+ *                            swizzled axis is a multiple of 2^(shift + bits) (else AXE_EUNSUPPORTED).
+ *   axe_layout_direct_sum    App. F: as tile, without the span scaling: f(x || y) = f_A(x) + f_B(y).
+ *   axe_layout_tile_of       Alg. 3: decides A = C (x) B and recovers C; shape_out = SA / SB (rank entries).
+ *   axe_layout_slice         Alg. 4: a layout admitting `size` with f(u) = f_{L<shape>}(begin + u); per
+ *                            block the greedy peel, then the no-wrap or the symmetric one-wrap form.
+ *                            A swizzle stage is kept (it acts on the sum D + R + O).
+ */
+int axe_layout_span(const axe_layout_t* L, int64_t* span);
+int axe_layout_canonicalize(const axe_layout_t* L, axe_layout_t* out, void* arena, size_t arena_bytes);
+int axe_layout_gap_condition(const axe_layout_t* L);
+int axe_layout_equal(const axe_layout_t* A, const axe_layout_t* B);
+int axe_layout_group(const axe_layout_t* L, int32_t rank, const int64_t* shape, axe_layout_t* out,
+                     int32_t* block_end, void* arena, size_t arena_bytes);
+int axe_layout_tile(const axe_layout_t* A, int32_t rank, const int64_t* SA, const axe_layout_t* B, const int64_t* SB,
+                    axe_layout_t* out, int64_t* shape_out, void* arena, size_t arena_bytes);
+int axe_layout_direct_sum(const axe_layout_t* A, int32_t rank, const int64_t* SA, const axe_layout_t* B,
+                          const int64_t* SB, axe_layout_t* out, int64_t* shape_out, void* arena, size_t arena_bytes);
+int axe_layout_tile_of(const axe_layout_t* A, int32_t rank, const int64_t* SA, const axe_layout_t* B, const int64_t* SB,
+                       axe_layout_t* out, int64_t* shape_out, void* arena, size_t arena_bytes);
+int axe_layout_slice(const axe_layout_t* L, int32_t rank, const int64_t* shape, const int64_t* begin,
+                     const int64_t* size, axe_layout_t* out, void* arena, size_t arena_bytes);
 
 const char* axe_strerror(int code);
 const char* axe_last_error(void);

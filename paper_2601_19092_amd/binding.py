@@ -14,7 +14,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libaxe_hip.so")
 
-AXE_OK, AXE_EINVAL, AXE_ESHAPE, AXE_EALIAS, AXE_ERANGE, AXE_EUNSUPPORTED, AXE_EHIP = 0, -1, -2, -3, -4, -5, -6
+AXE_OK, AXE_EINVAL, AXE_ESHAPE, AXE_EALIAS, AXE_ERANGE, AXE_EUNSUPPORTED, AXE_EHIP, AXE_ENOFORM = 0, -1, -2, -3, -4, -5, -6, -7
 AXE_BF16, AXE_FP8_E4M3, AXE_F32 = 1, 2, 3
 AXE_TILE_AUTO, AXE_TILE_64x64x32, AXE_TILE_256x256x64, AXE_TILE_256x224x64 = 0, 1, 2, 3
 (AXE_DESC_A_G2L_THREADS, AXE_DESC_B_G2L_THREADS, AXE_DESC_A_LDS, AXE_DESC_B_LDS, AXE_DESC_A_OPERAND,
@@ -22,7 +22,9 @@ AXE_TILE_AUTO, AXE_TILE_64x64x32, AXE_TILE_256x256x64, AXE_TILE_256x224x64 = 0, 
 AXE_MAX_RANK = 8
 
 EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
-           "axe_last_error", "axe_version"]
+           "axe_last_error", "axe_version", "axe_layout_span", "axe_layout_canonicalize", "axe_layout_gap_condition",
+           "axe_layout_equal", "axe_layout_group", "axe_layout_tile", "axe_layout_direct_sum", "axe_layout_tile_of",
+           "axe_layout_slice"]
 
 
 class axe_iter_t(C.Structure):
@@ -78,6 +80,16 @@ def lib() -> C.CDLL:
         L.axe_gemm_describe.restype = C.c_int
         L.axe_gemm_describe.argtypes = [C.POINTER(axe_gemm_desc_t), i32, LP, C.POINTER(i64), C.POINTER(i32), vp,
                                         C.c_size_t]
+        P64, P32, sz = C.POINTER(i64), C.POINTER(i32), C.c_size_t
+        for name, args in (("axe_layout_span", [LP, P64]), ("axe_layout_canonicalize", [LP, LP, vp, sz]),
+                           ("axe_layout_gap_condition", [LP]), ("axe_layout_equal", [LP, LP]),
+                           ("axe_layout_group", [LP, i32, P64, LP, P32, vp, sz]),
+                           ("axe_layout_tile", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
+                           ("axe_layout_direct_sum", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
+                           ("axe_layout_tile_of", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
+                           ("axe_layout_slice", [LP, i32, P64, P64, P64, LP, vp, sz])):
+            getattr(L, name).restype = C.c_int
+            getattr(L, name).argtypes = args
         L.axe_strerror.restype = C.c_char_p
         L.axe_strerror.argtypes = [C.c_int]
         L.axe_last_error.restype = C.c_char_p
@@ -194,6 +206,16 @@ def axe_gemm_tile(desc: GemmDesc) -> int:
     return rc
 
 
+def _spec_of(out: axe_layout_t, names: Optional[Sequence[str]] = None) -> dict:
+    """An axe_layout_t the library filled in, as plain data (the same form Layout() takes)."""
+    if names is None:
+        names = [out.axis_names[i].decode() for i in range(out.n_axes)]
+    return {"D": [(out.d[i].extent, out.d[i].stride, names[out.d[i].axis]) for i in range(out.n_d)],
+            "R": [(out.r[i].extent, out.r[i].stride, names[out.r[i].axis]) for i in range(out.n_r)],
+            "O": {names[a]: out.offset[a] for a in range(out.n_axes) if out.offset and out.offset[a] != 0},
+            "swizzle": (names[out.swz_axis], out.swz_bits, out.swz_base, out.swz_shift) if out.swz_axis >= 0 else None}
+
+
 def axe_gemm_describe(desc: GemmDesc, which: int) -> Tuple[dict, Tuple[int, ...]]:
     """Returns (spec, shape): the layout of one tile movement as plain data."""
     out = axe_layout_t()
@@ -201,12 +223,77 @@ def axe_gemm_describe(desc: GemmDesc, which: int) -> Tuple[dict, Tuple[int, ...]
     rank = C.c_int32(0)
     arena = C.create_string_buffer(4096)
     _check(lib().axe_gemm_describe(C.byref(desc.c), which, C.byref(out), shape, C.byref(rank), arena, len(arena)))
-    names = [out.axis_names[i].decode() for i in range(out.n_axes)]
-    spec = {"D": [(out.d[i].extent, out.d[i].stride, names[out.d[i].axis]) for i in range(out.n_d)],
-            "R": [(out.r[i].extent, out.r[i].stride, names[out.r[i].axis]) for i in range(out.n_r)],
-            "O": {names[a]: out.offset[a] for a in range(out.n_axes) if out.offset and out.offset[a] != 0},
-            "swizzle": (names[out.swz_axis], out.swz_bits, out.swz_base, out.swz_shift) if out.swz_axis >= 0 else None}
-    return spec, tuple(shape[i] for i in range(rank.value))
+    return _spec_of(out), tuple(shape[i] for i in range(rank.value))
+
+
+# ---- layout operators (host only; the library does the work, this only marshals)
+def _same_axes(*Ls: Layout) -> None:
+    for L in Ls[1:]:
+        if L.axes != Ls[0].axes:
+            raise ValueError("the operands must be built on one axis list (pass axes= to Layout)")
+
+
+def layout_span(L: Layout) -> Dict[str, int]:
+    sp = (C.c_int64 * len(L.axes))()
+    _check(lib().axe_layout_span(C.byref(L.c), sp))
+    return {a: sp[i] for i, a in enumerate(L.axes)}
+
+
+def layout_canonicalize(L: Layout) -> dict:
+    out, arena = axe_layout_t(), C.create_string_buffer(1024)
+    _check(lib().axe_layout_canonicalize(C.byref(L.c), C.byref(out), arena, len(arena)))
+    return _spec_of(out, L.axes)
+
+
+def _flag(rc: int) -> bool:
+    if rc < 0:
+        _check(rc)
+    return bool(rc)
+
+
+def layout_gap_condition(L: Layout) -> bool:
+    return _flag(lib().axe_layout_gap_condition(C.byref(L.c)))
+
+
+def layout_equal(A: Layout, B: Layout) -> bool:
+    _same_axes(A, B)
+    return _flag(lib().axe_layout_equal(C.byref(A.c), C.byref(B.c)))
+
+
+def layout_group(L: Layout, shape: Sequence[int]) -> Tuple[dict, List[int]]:
+    out, arena = axe_layout_t(), C.create_string_buffer(1024)
+    ends = (C.c_int32 * len(shape))()
+    _check(lib().axe_layout_group(C.byref(L.c), len(shape), _shape_arr(shape), C.byref(out), ends, arena, len(arena)))
+    return _spec_of(out, L.axes), list(ends)
+
+
+def _binary(fn, A: Layout, SA: Sequence[int], B: Layout, SB: Sequence[int], n_out: int):
+    _same_axes(A, B)
+    if len(SA) != len(SB):
+        raise ValueError("the two shapes must have the same rank")
+    out, arena = axe_layout_t(), C.create_string_buffer(1024)
+    shape = (C.c_int64 * n_out)()
+    _check(fn(C.byref(A.c), len(SA), _shape_arr(SA), C.byref(B.c), _shape_arr(SB), C.byref(out), shape, arena, len(arena)))
+    return _spec_of(out, A.axes), tuple(shape)
+
+
+def layout_tile(A: Layout, SA: Sequence[int], B: Layout, SB: Sequence[int]) -> Tuple[dict, Tuple[int, ...]]:
+    return _binary(lib().axe_layout_tile, A, SA, B, SB, 2 * len(SA))
+
+
+def layout_direct_sum(A: Layout, SA: Sequence[int], B: Layout, SB: Sequence[int]) -> Tuple[dict, Tuple[int, ...]]:
+    return _binary(lib().axe_layout_direct_sum, A, SA, B, SB, 2 * len(SA))
+
+
+def layout_tile_of(A: Layout, SA: Sequence[int], B: Layout, SB: Sequence[int]) -> Tuple[dict, Tuple[int, ...]]:
+    return _binary(lib().axe_layout_tile_of, A, SA, B, SB, len(SA))
+
+
+def layout_slice(L: Layout, shape: Sequence[int], begin: Sequence[int], size: Sequence[int]) -> dict:
+    out, arena = axe_layout_t(), C.create_string_buffer(1024)
+    _check(lib().axe_layout_slice(C.byref(L.c), len(shape), _shape_arr(shape), _shape_arr(begin), _shape_arr(size),
+                                  C.byref(out), arena, len(arena)))
+    return _spec_of(out, L.axes)
 
 
 def version() -> int:

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaxe_hip.so")
-SOURCES = ["api.cpp", "host_layout.cpp", "describe.cpp", "kernels_layout.hip", "kernels_gemm_small.hip",
+SOURCES = ["api.cpp", "host_layout.cpp", "layout_algebra.cpp", "describe.cpp", "kernels_layout.hip", "kernels_gemm_small.hip",
            "kernels_gemm_bf16.hip", "kernels_gemm_fp8.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
@@ -50,7 +50,7 @@ def build_hostcheck() -> str:
     kernels (csrc/cpu_emulation.cpp) so that planning can be checked without a GPU."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     out = os.path.join(HERE, "libaxe_hostcheck.so")
-    srcs = [os.path.join(CSRC, f) for f in ("api.cpp", "host_layout.cpp", "describe.cpp", "cpu_emulation.cpp")]
+    srcs = [os.path.join(CSRC, f) for f in ("api.cpp", "host_layout.cpp", "layout_algebra.cpp", "describe.cpp", "cpu_emulation.cpp")]
     cmd = [hipcc, "-O1", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared", "-x", "hip",
            "-Wno-unused-command-line-argument", *srcs, "-o", out]
     subprocess.check_call(cmd)

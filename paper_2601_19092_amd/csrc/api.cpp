@@ -45,6 +45,7 @@ const char* axe_strerror(int code) {
     case AXE_ERANGE: return "address outside the declared buffer, or integer overflow";
     case AXE_EUNSUPPORTED: return "layouts outside the supported kernel families";
     case AXE_EHIP: return "HIP runtime failure";
+    case AXE_ENOFORM: return "the layout operator's sufficient conditions do not hold";
     default: return "unknown error code";
   }
 }

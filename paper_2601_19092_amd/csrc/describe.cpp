@@ -162,20 +162,41 @@ int operand_layout(const Geo& g, bool is_b, Builder& b) {
 
 // (M, N) of the (tile-padded) problem -> wg, wave, lane, reg: the accumulators.  Operands are
 // swapped in the MFMA, so a lane owns, per 16 x 16 fragment, 4 consecutive columns of one row.
+// Not written down but composed with the tile operator (Sec. 3.3, Alg. 2), innermost first:
+//   fragment (16, 16)  (x)  register tile (NFM, NFN)  (x)  wave grid (WM, WN)  (x)  workgroup grid.
 int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Builder& b) {
-  const int NFM = g.T / g.WM / g.F, NFN = g.TN / g.WN / g.F;
-  const int per_frag = g.F * g.F / 64;                 // accumulator registers per fragment
-  if (!tile_only) b.D(grid_m, grid_n, WG);
-  b.D(g.WM, g.WN, WAVE);
-  b.D(NFM, (int64_t)NFN * per_frag, REG);
-  b.D(g.F, 1, LANE);
-  if (!tile_only) b.D(grid_n, 1, WG);
-  b.D(g.WN, 1, WAVE);
-  b.D(NFN, per_frag, REG);
-  b.D(64 / g.F, g.F, LANE);
-  b.D(4, 1, REG);
-  if (tile_only) b.shape = {g.T, g.TN};
-  else b.shape = {grid_m * g.T, grid_n * g.TN};
+  const int64_t NFM = g.T / g.WM / g.F, NFN = g.TN / g.WN / g.F;
+  struct Level {
+    axe_iter_t d[3];
+    int n;
+    int64_t shape[2];
+  };
+  // row -> lane; column 4 q + c -> lane group q (16 lanes apart), register c
+  const Level frag = {{{g.F, 1, LANE}, {64 / g.F, g.F, LANE}, {4, 1, REG}}, 3, {g.F, g.F}};
+  const Level outer[3] = {{{{NFM, NFN, REG}, {NFN, 1, REG}}, 2, {NFM, NFN}},
+                          {{{g.WM, g.WN, WAVE}, {g.WN, 1, WAVE}}, 2, {g.WM, g.WN}},
+                          {{{grid_m, grid_n, WG}, {grid_n, 1, WG}}, 2, {grid_m, grid_n}}};
+  auto as_layout = [](const axe_iter_t* d, int n) {
+    axe_layout_t L;
+    memset(&L, 0, sizeof L);
+    L.n_axes = NAXES, L.n_d = n, L.d = d, L.swz_axis = -1;
+    return L;
+  };
+  char arena[2][1024];
+  axe_layout_t cur = as_layout(frag.d, frag.n);
+  int64_t shape[2] = {frag.shape[0], frag.shape[1]};
+  for (int level = 0; level < (tile_only ? 2 : 3); ++level) {
+    const axe_layout_t out_l = as_layout(outer[level].d, outer[level].n);
+    axe_layout_t next;
+    int64_t interleaved[4];
+    if (int rc = axe_layout_tile(&out_l, 2, outer[level].shape, &cur, shape, &next, interleaved, arena[level & 1], 1024)) return rc;
+    cur = next;                                        // admits (rows, cols) = products of the interleaved pairs as well
+    shape[0] = interleaved[0] * interleaved[1];
+    shape[1] = interleaved[2] * interleaved[3];
+  }
+  for (int i = 0; i < cur.n_d; ++i)
+    if (cur.d[i].extent > 1 || cur.n_d == 1) b.D(cur.d[i].extent, cur.d[i].stride, cur.d[i].axis);
+  b.shape = {shape[0], shape[1]};
   return AXE_OK;
 }
 
