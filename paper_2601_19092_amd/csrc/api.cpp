@@ -172,6 +172,67 @@ int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank,
     return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_relayout");
   }
 
+  // --- transposing case: no digit is contiguous on both sides, but one is contiguous in the source
+  //     and another in the destination, and every 16-byte chunk along either is aligned: tiles of
+  //     those two digits go through LDS (16-byte accesses on both sides)
+  {
+    int kS = -1, kD = -1, both = -1;
+    for (size_t k = 0; k < J.size(); ++k) {
+      if (J[k].e == 1) continue;
+      if (J[k].ss == 1 && J[k].ds == 1) both = (int)k;
+      else if (J[k].ss == 1) kS = (int)k;
+      else if (J[k].ds == 1) kD = (int)k;
+    }
+    const int64_t ce = elem_bytes <= 8 ? 16 / elem_bytes : 0;
+    bool ok = both < 0 && kS >= 0 && kD >= 0 && ce > 0 && md.R.empty() && !ms.swz.mask && !md.swz.mask &&
+              env_int("AXE_RELAYOUT_TRANSPOSE", 1) != 0;
+    if (ok) {
+      // a tile row is worth fetching only if it is at least 64 bytes long on both sides
+      ok = J[kS].e % ce == 0 && J[kD].e % ce == 0 && J[kS].e * elem_bytes >= 64 && J[kD].e * elem_bytes >= 64 &&
+           ms.off % ce == 0 && md.off % ce == 0 && (((uintptr_t)d_src | (uintptr_t)d_dst) & 15) == 0;
+      for (size_t k = 0; k < J.size() && ok; ++k) {
+        if ((int)k != kS && J[k].e > 1 && J[k].ss % ce) ok = false;
+        if ((int)k != kD && J[k].e > 1 && J[k].ds % ce) ok = false;
+      }
+    }
+    if (ok) {
+      TransposePlan p;
+      memset(&p, 0, sizeof p);
+      const int64_t T = transpose_tile_edge(elem_bytes);
+      p.eS = J[kS].e, p.dS = J[kS].ds;
+      p.eD = J[kD].e, p.sD = J[kD].ss;
+      p.s_off = ms.off, p.d_off = md.off;
+      const uint64_t tiles_s = (uint64_t)((p.eS + T - 1) / T), tiles_d = (uint64_t)((p.eD + T - 1) / T);
+      uint64_t blocks = tiles_s * tiles_d;
+      // outer digits, smallest strides first so that neighbouring workgroups stay close in memory
+      std::vector<JointIter> outer;
+      for (size_t k = 0; k < J.size(); ++k)
+        if ((int)k != kS && (int)k != kD && J[k].e > 1) outer.push_back(J[k]);
+      auto mag = [](int64_t x) { return x < 0 ? -x : x; };
+      std::stable_sort(outer.begin(), outer.end(), [&](const JointIter& a, const JointIter& b) {
+        return std::min(mag(a.ss), mag(a.ds)) < std::min(mag(b.ss), mag(b.ds));
+      });
+      bool fits = tiles_s < (uint64_t(1) << 31) && tiles_d < (uint64_t(1) << 31) && outer.size() <= (size_t)kMaxJoint;
+      for (size_t k = 0; k < outer.size() && fits; ++k) {
+        fits = outer[k].e < (int64_t(1) << 31) && blocks < (uint64_t(1) << 31);
+        p.ext[k] = (uint32_t)outer[k].e;
+        p.ss[k] = outer[k].ss;
+        p.ds[k] = outer[k].ds;
+        blocks *= (uint64_t)outer[k].e;
+      }
+      if (fits && blocks < (uint64_t(1) << 31)) {
+        p.n = (int)outer.size();
+        p.tiles_s = (uint32_t)tiles_s;
+        p.tiles_d = (uint32_t)tiles_d;
+        p.blocks = blocks;
+        const int nt = env_int("AXE_RELAYOUT_NT", -1);
+        p.streaming = nt >= 0 ? nt : (2 * E * (int64_t)elem_bytes >= (int64_t(128) << 20));
+        hipError_t e = launch_relayout_transpose(p, elem_bytes, d_src, d_dst, st);
+        return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_relayout");
+      }
+    }
+  }
+
   // --- vector width: a joint digit with unit stride on both sides
   int unit = elem_bytes;
   int64_t v = 1;

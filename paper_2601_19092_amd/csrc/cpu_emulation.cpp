@@ -5,6 +5,8 @@
 #include <hip/hip_runtime.h>
 #include <string.h>
 
+#include <vector>
+
 #include "device_types.h"
 #include "kernels.h"
 
@@ -12,6 +14,7 @@ namespace axe {
 
 static int64_t g_src_bytes = 0, g_dst_bytes = 0;
 static int g_violations = 0;
+static int g_transposes = 0;      // launches of the transposing relayout since the buffers were declared
 
 static int64_t swz_apply(int64_t x, Swz z) { return x ^ (((x >> z.shift) & (int64_t)z.mask) << z.base); }
 
@@ -87,6 +90,55 @@ hipError_t launch_relayout_joint(const RelayoutPlan& p, int unit, const void* sr
   return hipSuccess;
 }
 
+// Same tiles, same chunk guards and the same addresses as the kernel; a chunk is checked as the 16
+// bytes the kernel would touch, on both sides.
+hipError_t launch_relayout_transpose(const TransposePlan& p, int eb, const void* src_, void* dst_, hipStream_t) {
+  const char* src = (const char*)src_;
+  char* dst = (char*)dst_;
+  const int64_t T = transpose_tile_edge(eb), CE = 16 / eb, CPR = T / CE;
+  ++g_transposes;
+  for (uint64_t blk = 0; blk < p.blocks; ++blk) {
+    uint64_t b = blk;
+    const int64_t ts = (int64_t)(b % p.tiles_s);
+    b /= p.tiles_s;
+    const int64_t td = (int64_t)(b % p.tiles_d);
+    b /= p.tiles_d;
+    int64_t sb = p.s_off, db = p.d_off;
+    for (int k = 0; k < p.n; ++k) {
+      sb += (int64_t)(b % p.ext[k]) * p.ss[k];
+      db += (int64_t)(b % p.ext[k]) * p.ds[k];
+      b /= p.ext[k];
+    }
+    std::vector<char> tile((size_t)(T * T * eb), 0);
+    std::vector<char> have((size_t)(T * T), 0);
+    for (int64_t c = 0; c < T * CPR; ++c) {                       // HBM -> LDS
+      const int64_t r = c / CPR, cc = c % CPR, iD = td * T + r, iS = ts * T + cc * CE;
+      if (iD >= p.eD || iS >= p.eS) continue;
+      const int64_t a = (sb + iD * p.sD + iS) * eb;
+      if (a < 0 || a + 16 > g_src_bytes || (a & 15)) {
+        ++g_violations;
+        continue;
+      }
+      memcpy(&tile[(size_t)((r * T + cc * CE) * eb)], src + a, 16);
+      for (int64_t k = 0; k < CE; ++k) have[(size_t)(r * T + cc * CE + k)] = 1;
+    }
+    for (int64_t c = 0; c < T * CPR; ++c) {                       // LDS -> HBM
+      const int64_t r = c / CPR, cc = c % CPR, iS = ts * T + r, iD = td * T + cc * CE;
+      if (iS >= p.eS || iD >= p.eD) continue;
+      const int64_t a = (db + iS * p.dS + iD) * eb;
+      if (a < 0 || a + 16 > g_dst_bytes || (a & 15)) {
+        ++g_violations;
+        continue;
+      }
+      for (int64_t k = 0; k < CE; ++k) {
+        if (!have[(size_t)((cc * CE + k) * T + r)]) ++g_violations;   // would store what was never loaded
+        memcpy(dst + a + k * eb, &tile[(size_t)(((cc * CE + k) * T + r) * eb)], (size_t)eb);
+      }
+    }
+  }
+  return hipSuccess;
+}
+
 hipError_t launch_relayout_generic(const GenericRelayoutPlan& p, int unit, const void* src_, void* dst_, hipStream_t) {
   const char* src = (const char*)src_;
   char* dst = (char*)dst_;
@@ -125,5 +177,7 @@ extern "C" void axe_hostcheck_set_buffers(int64_t src_bytes, int64_t dst_bytes) 
   axe::g_src_bytes = src_bytes;
   axe::g_dst_bytes = dst_bytes;
   axe::g_violations = 0;
+  axe::g_transposes = 0;
 }
 extern "C" int axe_hostcheck_violations(void) { return axe::g_violations; }
+extern "C" int axe_hostcheck_transposes(void) { return axe::g_transposes; }

@@ -47,6 +47,21 @@ struct RelayoutPlan {
   int32_t streaming;               // 1: non-temporal loads and stores (data larger than the caches)
 };
 
+// Transposing relayout: the joint loop nest has one digit that is contiguous in the source (extent
+// eS, destination stride dS) and another that is contiguous in the destination (extent eD, source
+// stride sD).  A workgroup moves one T x T tile of those two digits through LDS; the other digits
+// (fastest first) are decoded from the workgroup index.  Addresses in elements.
+struct TransposePlan {
+  int32_t n;
+  uint32_t ext[kMaxJoint];
+  int64_t ss[kMaxJoint], ds[kMaxJoint];
+  int64_t eS, eD, sD, dS;
+  int64_t s_off, d_off;
+  uint32_t tiles_s, tiles_d;       // tiles along the source-fast and the destination-fast digit
+  uint64_t blocks;                 // tiles_s * tiles_d * product of ext[]
+  int32_t streaming;               // 1: non-temporal loads and stores
+};
+
 // Fallback when the two digit systems have no common refinement: decode each side separately.
 struct GenericRelayoutPlan {
   int32_t ns, nd;

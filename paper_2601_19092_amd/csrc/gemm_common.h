@@ -61,6 +61,14 @@ __device__ __forceinline__ void tile_of_block(int bid, int nwg, int grid_m, int 
   tn = in_group / gsz;
 }
 
+// A buffer instruction written as an asm statement is opaque to the compiler's hazard recogniser.
+// One hazard of this chip can then go unpadded: a vector-memory instruction that reads an SGPR
+// (descriptor word or scalar offset) needs 5 wait states after a vector-ALU instruction wrote that
+// SGPR -- and the register allocator does write SGPRs that way (v_readfirstlane / v_readlane from a
+// uniform value it parked in a VGPR).  Unpadded, the instruction now and then used the stale offset:
+// a fragment stored over its neighbour.  Every such asm statement therefore starts with s_nop 4; the
+// MFMAs issued before keep the matrix pipe busy meanwhile.
+//
 // Descriptor words for a buffer store issued as an asm statement: base address, byte range, raw
 // 32-bit data format.  The words are wave-uniform by construction; readfirstlane tells the compiler so
 // (they must sit in SGPRs).

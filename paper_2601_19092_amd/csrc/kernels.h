@@ -8,6 +8,12 @@ namespace axe {
 
 hipError_t launch_layout_eval(const EvalDesc& d, int64_t n, const int64_t* idx, int64_t* out, hipStream_t s);
 hipError_t launch_relayout_joint(const RelayoutPlan& p, int unit_bytes, const void* src, void* dst, hipStream_t s);
+// elem_bytes 1, 2, 4 or 8; every 16-byte chunk of a tile row must be aligned on both sides
+hipError_t launch_relayout_transpose(const TransposePlan& p, int elem_bytes, const void* src, void* dst, hipStream_t s);
+// tile edge (elements) the transposing kernel uses for an element size
+// (measured on 8192 x 8192: rows of 256 - 512 bytes per tile beat 128-byte rows by 10 - 17 %, except for
+//  single bytes, where the gather of 16 LDS bytes per store makes a 256 x 256 tile slower)
+inline int transpose_tile_edge(int elem_bytes) { return elem_bytes == 8 ? 64 : 128; }
 hipError_t launch_relayout_generic(const GenericRelayoutPlan& p, int unit_bytes, const void* src, void* dst,
                                    hipStream_t s);
 hipError_t launch_gemm_small(const GemmArgs& g, bool fp8, hipStream_t s);

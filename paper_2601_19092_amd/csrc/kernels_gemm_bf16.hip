@@ -162,7 +162,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const i32x4 r = nx ? nxt.ra_words : cur.ra_words;
     const int soff = __builtin_amdgcn_readfirstlane(i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)));
     u32x4 v;
-    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
     return v;
   };
   auto a_write = [&](int stage, int i, u32x4 v) __attribute__((always_inline)) {
@@ -222,7 +222,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
     const u32x2 d = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
-    asm volatile("buffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile
   };
@@ -239,7 +239,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
                                                      pack_bf16(acc[i][j + 1][2], acc[i][j + 1][3]), false, false);
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
-    asm volatile("buffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
   };

@@ -172,6 +172,115 @@ hipError_t launch_relayout_joint(const RelayoutPlan& p, int unit_bytes, const vo
 }
 
 // ------------------------------------------------------------------------------------------
+// Relayout, transposing: source and destination are contiguous along different digits of the joint
+// loop nest (row-major <-> column-major and their batched, strided relatives).  Moving single
+// elements would leave one side with 2-byte accesses scattered over rows; instead a workgroup
+// takes a T x T tile of the two digits, reads it with 16-byte loads along the source-fast digit
+// (T * EB = 128 to 512 contiguous bytes per tile row), parks it in LDS, and writes it with 16-byte
+// stores along the destination-fast digit, each store gathering its 16 / EB elements from as many
+// LDS rows.  LDS rows are padded by one word so that the gather walks over distinct banks.
+// ------------------------------------------------------------------------------------------
+template <int EB, bool NT>
+__global__ __launch_bounds__(256) void relayout_transpose_kernel(TransposePlan p, const uint8_t* __restrict__ src,
+                                                                 uint8_t* __restrict__ dst) {
+  constexpr int T = EB == 8 ? 64 : 128;                           // tile edge, elements (transpose_tile_edge)
+  constexpr int CE = 16 / EB;                                    // elements per 16-byte chunk
+  constexpr int CPR = T / CE;                                    // chunks per tile row
+  constexpr int PW = T * EB / 4 + 1;                             // LDS row pitch, words
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  __shared__ uint32_t tile[T * PW];
+
+  // workgroup -> (tile along S, tile along D, outer digits)
+  uint64_t b = blockIdx.x;
+  const uint32_t ts = (uint32_t)(b % p.tiles_s);
+  b /= p.tiles_s;
+  const uint32_t td = (uint32_t)(b % p.tiles_d);
+  b /= p.tiles_d;
+  int64_t sb = p.s_off, db = p.d_off;
+  for (int k = 0; k < p.n; ++k) {
+    const uint64_t q = b / p.ext[k];
+    const int64_t dig = (int64_t)(b - q * p.ext[k]);
+    sb += dig * p.ss[k];
+    db += dig * p.ds[k];
+    b = q;
+  }
+  const int64_t s0 = (int64_t)ts * T, d0 = (int64_t)td * T;      // tile origin in the two digits
+
+  // HBM -> LDS: row r of the tile is destination-fast index d0 + r, its chunks run along the source
+  for (int c = threadIdx.x; c < T * CPR; c += 256) {
+    const int r = c / CPR, cc = c % CPR;
+    const int64_t iD = d0 + r, iS = s0 + (int64_t)cc * CE;
+    if (iD < p.eD && iS < p.eS) {                                // extents are multiples of CE: a chunk is in or out as a whole
+      const u32x4* a = (const u32x4*)(src + (sb + iD * p.sD + iS) * EB);
+      const u32x4 v = NT ? __builtin_nontemporal_load(a) : *a;
+#pragma unroll
+      for (int j = 0; j < 4; ++j) tile[r * PW + cc * 4 + j] = v[j];
+    }
+  }
+  __syncthreads();
+  // LDS -> HBM: output row r is source-fast index s0 + r, its chunks run along the destination
+  const uint8_t* tb = (const uint8_t*)tile;
+  for (int c = threadIdx.x; c < T * CPR; c += 256) {
+    const int r = c / CPR, cc = c % CPR;
+    const int64_t iS = s0 + r, iD = d0 + (int64_t)cc * CE;
+    if (iS < p.eS && iD < p.eD) {
+      u32x4 v;
+      if (EB == 1) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          uint32_t w = 0;
+#pragma unroll
+          for (int k = 0; k < 4; ++k) w |= (uint32_t)tb[(cc * CE + 4 * j + k) * (PW * 4) + r] << (8 * k);
+          v[j] = w;
+        }
+      } else if (EB == 2) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const uint32_t lo = *(const uint16_t*)(tb + (cc * CE + 2 * j) * (PW * 4) + r * 2);
+          const uint32_t hi = *(const uint16_t*)(tb + (cc * CE + 2 * j + 1) * (PW * 4) + r * 2);
+          v[j] = lo | (hi << 16);
+        }
+      } else if (EB == 4) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) v[j] = tile[(cc * CE + j) * PW + r];
+      } else {
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+          v[2 * j] = tile[(cc * CE + j) * PW + 2 * r];
+          v[2 * j + 1] = tile[(cc * CE + j) * PW + 2 * r + 1];
+        }
+      }
+      u32x4* a = (u32x4*)(dst + (db + iS * p.dS + iD) * EB);
+      if (NT) __builtin_nontemporal_store(v, a);
+      else *a = v;
+    }
+  }
+}
+
+template <int EB>
+static hipError_t launch_transpose_e(const TransposePlan& p, const void* src, void* dst, hipStream_t s) {
+  if (p.streaming)
+    hipLaunchKernelGGL((relayout_transpose_kernel<EB, true>), dim3((unsigned)p.blocks), dim3(256), 0, s, p, (const uint8_t*)src,
+                       (uint8_t*)dst);
+  else
+    hipLaunchKernelGGL((relayout_transpose_kernel<EB, false>), dim3((unsigned)p.blocks), dim3(256), 0, s, p, (const uint8_t*)src,
+                       (uint8_t*)dst);
+  return hipGetLastError();
+}
+
+hipError_t launch_relayout_transpose(const TransposePlan& p, int elem_bytes, const void* src, void* dst, hipStream_t s) {
+  if (p.blocks == 0) return hipSuccess;
+  if (p.blocks > 0x7fffffffull) return hipErrorInvalidValue;
+  switch (elem_bytes) {
+    case 1: return launch_transpose_e<1>(p, src, dst, s);
+    case 2: return launch_transpose_e<2>(p, src, dst, s);
+    case 4: return launch_transpose_e<4>(p, src, dst, s);
+    case 8: return launch_transpose_e<8>(p, src, dst, s);
+    default: return hipErrorInvalidValue;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
 // Relayout, generic: one element per thread, source and destination decoded separately from
 // the logical index.  Correct for any pair of layouts; used when no joint loop nest exists.
 // ------------------------------------------------------------------------------------------

@@ -168,6 +168,52 @@ def test_relayout_element_sizes_transposes_and_ragged(eb):
     assert got.tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_relayout_transposing_path(eb):
+    """Source and destination contiguous along different digits: tiles through LDS.  Whole and clipped
+    tiles, a batch digit, pitched rows and offsets on both sides, both directions."""
+    rng = np.random.default_rng(100 + eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    ce = 16 // eb
+    T = {1: 128, 2: 128, 4: 128, 8: 64}[eb]
+    cases = [((T, T), None), ((2 * T + ce, 3 * T - ce), None), ((ce * 5, 4 * T), None),
+             ((3, T + 2 * ce, 2 * T), "batch"), ((T + ce, T - ce), "pitched"), ((5 * T, 7 * T + 3 * ce), None)]
+    for shape, kind in cases:
+        rows, cols = shape[-2], shape[-1]
+        if kind == "batch":
+            s_L, d_L = ax.row_major(shape), Layout.make(shape, (rows * cols, 1, rows))
+            n_src = n_dst = prod(shape)
+        elif kind == "pitched":
+            ps, pd = cols + 3 * ce, rows + 2 * ce
+            s_L, d_L = Layout.make(shape, (ps, 1), O={"m": ce}), Layout.make(shape, (1, pd), O={"m": 2 * ce})
+            n_src, n_dst = ce + rows * ps, 2 * ce + cols * pd
+        else:
+            s_L, d_L = ax.row_major(shape), Layout.make(shape, (1, rows))
+            n_src = n_dst = prod(shape)
+        src = rng.integers(0, 256, n_src * eb, dtype=np.uint8).view(dt)
+        got, want = relayout_both(s_L, d_L, shape, src, n_dst)
+        assert got.tobytes() == want.tobytes(), (shape, kind)
+        back, wb = relayout_both(d_L, s_L, shape, got, n_src)
+        assert back.tobytes() == wb.tobytes(), (shape, kind)
+
+
+@pytest.mark.parametrize("rows,cols,dtype", [(8192, 8192, np.uint16), (4096, 12288, np.uint16), (8192, 8192, np.uint32)])
+def test_relayout_transpose_full_size(rows, cols, dtype):
+    """Row-major -> column-major of a matrix of the workload's size against the definition written with
+    NumPy (a transposed view made contiguous), bit for bit; and back."""
+    rng = np.random.default_rng(rows + cols)
+    src = rng.integers(0, np.iinfo(dtype).max, rows * cols, dtype=dtype)
+    d_src = dev(src.view(np.uint8))
+    d_dst = torch.zeros(rows * cols * src.itemsize, dtype=torch.uint8, device="cuda")
+    Ls, Ld = B.Layout(W.row_major_spec(rows, cols)), B.Layout(W.col_major_spec(rows, cols))
+    B.axe_relayout(Ls, Ld, (rows, cols), d_src, d_dst, elem_bytes=src.itemsize)
+    got = d_dst.cpu().numpy().view(dtype)
+    assert np.array_equal(got, np.ascontiguousarray(src.reshape(rows, cols).T).reshape(-1))
+    d_back = torch.zeros_like(d_dst)
+    B.axe_relayout(Ld, Ls, (rows, cols), d_dst, d_back, elem_bytes=src.itemsize)
+    assert np.array_equal(d_back.cpu().numpy().view(dtype), src)
+
+
 def test_relayout_without_common_refinement_uses_generic_path():
     # source digits (6, 4), destination digits (4, 6) over the same 24 elements: no joint loop nest
     rng = np.random.default_rng(3)
@@ -431,3 +477,32 @@ def test_gemm_chained_tiles_on_a_grid_of_17_by_16():
     full_size_check(g, BF16_TOL, seed=8, tile=B.AXE_TILE_256x224x64)
     # fp8: 66 K-steps, so the register of block scales is refilled inside each chained tile
     full_size_check(W.gemm_fp8(4352, 4096, 8448, 92, scaled=True), FP8_TOL, seed=7)
+
+
+@pytest.mark.parametrize("which", ["config4", "chained_256", "fp8"])
+def test_gemm_is_bitwise_repeatable(which):
+    """The kernels are deterministic: many launches on the same buffers give the same bits every time
+    (each launch into a cleared C).  Guards the padding of the asm-issued buffer instructions: without it
+    a store now and then used a stale scalar offset and landed on a neighbouring fragment."""
+    if which == "config4":
+        g, kw = W.config4(), dict(device_axis=True)
+    elif which == "chained_256":
+        g, kw = W.gemm_bf16(4352, 4096, 512, 91), {}
+    else:
+        g, kw = W.gemm_fp8(4352, 4096, 1024, 95, scaled=True), {}
+    As, Bs, Cs = W.gemm_specs(g, shard=3, **kw)
+    axes = ["m", "gpuid"]
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_nk.reshape(-1))
+    dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
+    sa = torch.from_numpy(g.scale_a).cuda() if g.scale_a is not None else None
+    sb = torch.from_numpy(g.scale_b).cuda() if g.scale_b is not None else None
+    desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16 if g.dtype == "bf16" else B.AXE_FP8_E4M3, B.AXE_BF16,
+                      B.Layout(As, axes), B.Layout(Bs, axes), B.Layout(Cs, axes), g.M * g.K, g.N * g.K, g.M * g.N, sa, sb)
+    first = None
+    for it in range(40):
+        dC.zero_()
+        B.axe_gemm(desc, dA, dB, dC)
+        if first is None:
+            first = dC.clone()
+        else:
+            assert torch.equal(first, dC), f"launch {it} differs from launch 0 in {(first != dC).sum().item()} elements"

@@ -105,6 +105,51 @@ def test_plan_element_sizes_transposes_replicas(hc, eb):
     assert got.tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_plan_transposing_path(hc, eb):
+    """Source and destination contiguous along different digits: the tiled path through LDS.  Whole
+    and clipped tiles, a batch digit, pitched rows on both sides, an offset; the stand-in kernel checks
+    every 16-byte access against the buffers and that nothing is stored that was not loaded."""
+    rng = np.random.default_rng(100 + eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    ce = 16 // eb
+    T = {1: 128, 2: 128, 4: 128, 8: 64}[eb]
+    cases = [((T, T), None), ((2 * T + ce, 3 * T - ce), None), ((ce * 5, 4 * T), None),
+             ((3, T + 2 * ce, 2 * T), "batch"), ((T + ce, T - ce), "pitched")]
+    for shape, kind in cases:
+        rows, cols = shape[-2], shape[-1]
+        if kind == "batch":
+            # (b, r, c): source row-major, destination transposes the last two dimensions inside each batch
+            s_L = ax.row_major(shape)
+            d_L = Layout.make(shape, (rows * cols, 1, rows))
+            n_src = n_dst = prod(shape)
+        elif kind == "pitched":
+            ps, pd = cols + 3 * ce, rows + 2 * ce                          # row pitches, multiples of a chunk
+            s_L = Layout.make(shape, (ps, 1), O={"m": ce})
+            d_L = Layout.make(shape, (1, pd), O={"m": 2 * ce})
+            n_src, n_dst = ce + rows * ps, 2 * ce + cols * pd
+        else:
+            s_L = ax.row_major(shape)
+            d_L = Layout.make(shape, (1, rows))
+            n_src = n_dst = prod(shape)
+        src = rng.integers(0, 256, n_src * eb, dtype=np.uint8).view(dt)
+        got, want = host_relayout(hc, s_L, d_L, shape, src, n_dst)
+        assert hc.axe_hostcheck_transposes() == 1, (shape, kind)
+        assert got.tobytes() == want.tobytes(), (shape, kind)
+        back, wb = host_relayout(hc, d_L, s_L, shape, got, n_src)           # and the other way round
+        assert hc.axe_hostcheck_transposes() == 1 and back.tobytes() == wb.tobytes()
+    # rows that do not end on a 16-byte boundary, a swizzled side or a replicated destination stay on the other paths
+    shape = (T, T + 1)
+    src = rng.integers(0, 256, prod(shape) * eb, dtype=np.uint8).view(dt)
+    got, want = host_relayout(hc, ax.row_major(shape), Layout.make(shape, (1, T)), shape, src, prod(shape))
+    assert hc.axe_hostcheck_transposes() == 0 and got.tobytes() == want.tobytes()
+    shape = (T, T)
+    src = rng.integers(0, 256, prod(shape) * eb, dtype=np.uint8).view(dt)
+    D2 = Layout.make(shape, (1, T), R=((2,), (T * T,)))
+    got, want = host_relayout(hc, ax.row_major(shape), D2, shape, src, 2 * T * T)
+    assert hc.axe_hostcheck_transposes() == 0 and got.tobytes() == want.tobytes()
+
+
 def test_plan_random_layout_pairs(hc):
     """Random pairs of injective layouts over the same element count: permuted / split /
     padded strides on both sides, with and without swizzles; joint and generic paths."""
