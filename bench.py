@@ -129,6 +129,25 @@ def bench_relayout(steps, warmup, n_pairs=4):
     return out
 
 
+def bench_transpose(steps, warmup, n_pairs=4):
+    """Row-major -> column-major of the same 8192 x 8192 bf16 matrix: source and destination are
+    contiguous along different digits, the relayout goes through LDS tiles."""
+    import torch
+    from paper_2601_19092_amd import binding as B
+    from paper_2601_19092_amd import workloads as W
+    rows = cols = 8192
+    Ls, Ld = B.Layout(W.row_major_spec(rows, cols)), B.Layout(W.col_major_spec(rows, cols))
+    pairs = [(torch.randint(-30000, 30000, (rows * cols,), dtype=torch.int16, device="cuda"),
+              torch.zeros(rows * cols, dtype=torch.int16, device="cuda")) for _ in range(n_pairs)]
+    wall, devms = time_loop(lambda i: B.axe_relayout(Ls, Ld, (rows, cols), *pairs[i % n_pairs]), steps, warmup)
+    assert torch.equal(pairs[0][1].view(cols, rows), pairs[0][0].view(rows, cols).t())
+    r = {"ms_per_step": wall, "kernel_ms": devms, "GBps": 2.0 * rows * cols * 2 / (devms * 1e-3) / 1e9}
+    r["frac_of_hbm_peak"] = r["GBps"] / PEAK["hbm"]
+    log(f"[bench] relayout 8192^2 bf16 row-major -> column-major (transposing tiles): {r['GBps']:.0f} GB/s rotating "
+        f"({100 * r['frac_of_hbm_peak']:.1f}% of HBM peak)")
+    return r
+
+
 def bench_eval(steps, warmup):
     import torch
     from paper_2601_19092_amd import binding as B
@@ -221,6 +240,7 @@ def main():
     comp = {}
     if want("relayout"):
         comp["relayout_cfg2"] = bench_relayout(max(20, args.steps), args.warmup)
+        comp["relayout_transpose_8192"] = bench_transpose(max(20, args.steps), args.warmup)
     if want("shard"):
         comp["gemm_cfg4_tp_shard"], _ = bench_gemm("bf16 GEMM M=4096 K=8192 N=3584 (1 of 8 shards)", W.config4(),
                                                    args.steps, args.warmup, device_axis=True)
