@@ -74,7 +74,8 @@ def gemm_setup(g, n_sets, device_axis=False, tile=0):
     desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16 if g.dtype == "bf16" else B.AXE_FP8_E4M3,
                       B.AXE_F32 if g.out_dtype == "f32" else B.AXE_BF16,
                       B.Layout(As, axes), B.Layout(Bs, axes), B.Layout(Cs, axes),
-                      g.M * g.K, g.N * g.K, g.M * g.N, sa, sb, tile_hint=tile)
+                      g.M * g.K, g.N * g.K, g.M * g.N, sa, sb, tile_hint=tile,
+                      scale_dtype=B.AXE_SCALE_E8M0 if g.scale_dtype == "e8m0" else B.AXE_SCALE_F32)
     def step(i):
         dA, dB, dC = sets[i % n_sets]
         B.axe_gemm(desc, dA, dB, dC)
@@ -248,6 +249,10 @@ def main():
     if want("fp8"):
         comp["gemm_cfg5_fp8_block_scaled"], _ = bench_gemm("fp8 e4m3 GEMM 8192^3, fp32 128x128 block scales", g5,
                                                            max(10, args.steps // 2), args.warmup)
+    if want("fp8"):
+        comp["gemm_fp8_e8m0_block_scaled"], _ = bench_gemm(
+            "fp8 e4m3 GEMM 8192^3, E8M0 (power-of-two) 128x128 block scales on the MFMA scale path",
+            W.gemm_fp8(8192, 8192, 8192, W.SEED_BASE + 5, scaled="e8m0"), max(10, args.steps // 2), args.warmup)
     if want("small"):
         comp["gemm_cfg1_256"], _ = bench_gemm("bf16 GEMM 256^3, fp32 out, 64x64x32 tiles", W.config1(),
                                               max(200, args.steps), max(200, args.warmup), n_sets=1)

@@ -123,10 +123,13 @@ int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank,
  *       layout on the memory axis `mem_axis`, addresses in elements of the tensor's dtype.
  *   in_dtype  : AXE_BF16 (2 bytes) or AXE_FP8_E4M3 (1 byte, OCP e4m3: max 448, no inf).
  *   out_dtype : AXE_F32 or AXE_BF16 (round to nearest even from the fp32 accumulator).
- *   d_scale_a, d_scale_b : both NULL, or DEVICE fp32 arrays, row-major (ceil(M/sb), ceil(K/sb))
+ *   d_scale_a, d_scale_b : both NULL, or DEVICE arrays of scale_dtype, row-major (ceil(M/sb), ceil(K/sb))
  *       and (ceil(N/sb), ceil(K/sb)) with sb = scale_block (must be 128):
  *       C[i][j] = sum_kb sA[i/sb][kb] * sB[j/sb][kb] * sum_{k in block kb} A[i][k] B[k][j]
  *       (block-wise scaled GEMM, Sec. 4.1).  Only with AXE_FP8_E4M3.
+ *   scale_dtype : AXE_SCALE_F32 (0; fp32 scales, folded on the vector ALU) or AXE_SCALE_E8M0 (one byte
+ *       per block, value 2^(code - 127), codes 1..254; the "FP8 (e8m0) block-wise scaling" of Sec. 4.1,
+ *       applied by the matrix cores' own scale path).  E8M0 arrays must be 4-byte aligned.
  *   a_elems, b_elems, c_elems : sizes of the device buffers in elements (range check).
  * Supported family (else AXE_EUNSUPPORTED): after canonicalisation A and B have unit stride
  * along k and C has unit stride along j (A row-major, B column-major, C row-major, any leading
@@ -140,12 +143,15 @@ typedef struct {
   axe_layout_t A, B, C;
   int32_t      mem_axis;
   int64_t      a_elems, b_elems, c_elems;
-  const float* d_scale_a;
-  const float* d_scale_b;
+  const void*  d_scale_a;   /* fp32 or E8M0 (uint8) arrays, see scale_dtype */
+  const void*  d_scale_b;
   int32_t      scale_block;
   int32_t      tile_hint;   /* 0 = library default; AXE_TILE_* forces a kernel (AXE_EUNSUPPORTED if
                                the shape does not fit it)                                         */
+  int32_t      scale_dtype; /* AXE_SCALE_F32 or AXE_SCALE_E8M0                                    */
 } axe_gemm_desc_t;
+
+enum { AXE_SCALE_F32 = 0, AXE_SCALE_E8M0 = 1 };
 
 enum { AXE_TILE_AUTO = 0, AXE_TILE_64x64x32 = 1, AXE_TILE_256x256x64 = 2, AXE_TILE_256x224x64 = 3 };
 

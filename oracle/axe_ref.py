@@ -155,6 +155,15 @@ def decode(bits: np.ndarray, dtype: int) -> np.ndarray:
     raise ValueError("unknown input dtype")
 
 
+def e8m0_decode(codes: np.ndarray) -> np.ndarray:
+    """E8M0 scale codes (OCP microscaling formats: 8 exponent bits, no sign, no mantissa) -> fp64:
+    2^(code - 127) for codes 0..254, NaN for 255.  Every value is a power of two, so the fp32 the
+    GEMM oracle takes holds it exactly for codes 1..254."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    out = np.ldexp(1.0, c - 127)
+    return np.where(c == 255, np.nan, out)
+
+
 def gemm_ref_numpy(a_bits: np.ndarray, b_bits: np.ndarray, dtype: int,
                    scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None,
                    block: int = 128) -> np.ndarray:

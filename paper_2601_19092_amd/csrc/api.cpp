@@ -429,6 +429,14 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
     set_error("axe_gemm: scales must be given for both operands or neither");
     return AXE_EINVAL;
   }
+  if (g->scale_dtype != AXE_SCALE_F32 && g->scale_dtype != AXE_SCALE_E8M0) {
+    set_error("axe_gemm: unknown scale_dtype %d", g->scale_dtype);
+    return AXE_EINVAL;
+  }
+  if (g->d_scale_a && g->scale_dtype == AXE_SCALE_E8M0 && (((uintptr_t)g->d_scale_a | (uintptr_t)g->d_scale_b) & 3)) {
+    set_error("axe_gemm: E8M0 scale arrays must be 4-byte aligned");
+    return AXE_EINVAL;
+  }
   if (g->d_scale_a && (!fp8 || g->scale_block != 128)) {
     set_error("axe_gemm: block scales need in_dtype fp8 and scale_block 128");
     return AXE_EUNSUPPORTED;
@@ -476,8 +484,9 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   P.args.lda = lda;
   P.args.ldb = ldb;
   P.args.ldc = ldc;
-  P.args.scale_a = g->d_scale_a;
-  P.args.scale_b = g->d_scale_b;
+  P.args.scale_a = (const float*)g->d_scale_a;
+  P.args.scale_b = (const float*)g->d_scale_b;
+  P.args.scale_e8m0 = g->d_scale_a && g->scale_dtype == AXE_SCALE_E8M0;
   P.args.nkb = (int32_t)((g->K + 127) / 128);
   P.args.out_bf16 = g->out_dtype == AXE_BF16;
   const int64_t bk = fp8 ? 128 : 64;
@@ -532,7 +541,10 @@ int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d
   if (int rc = plan_gemm(g, d_A, d_B, d_C, P, true)) return rc;
   hipError_t e;
   if (P.tile == AXE_TILE_256x256x64 || P.tile == AXE_TILE_256x224x64)
-    e = P.fp8 ? launch_gemm_fp8_256(P.args, (hipStream_t)stream) : launch_gemm_bf16_256(P.args, (hipStream_t)stream);
+    e = !P.fp8 ? launch_gemm_bf16_256(P.args, (hipStream_t)stream)
+        // power-of-two scales (or none) ride on the matrix cores' scale operands; arbitrary fp32 scales are folded on the vector ALU
+        : (P.args.scale_e8m0 || !P.args.scale_a ? launch_gemm_fp8_e8m0_256(P.args, (hipStream_t)stream)
+                                                : launch_gemm_fp8_256(P.args, (hipStream_t)stream));
   else
     e = launch_gemm_small(P.args, P.fp8, (hipStream_t)stream);
   return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm");

@@ -36,21 +36,23 @@ int ilog2(int64_t v) {
 // MFMA fragment F x F, LDS rows of ROWB bytes made of 16-byte chunks of CE elements.
 struct Geo {
   bool big, fp8;
+  bool mx;         // fp8 on the matrix cores' scale path (E8M0 scales or none): the 4-wave structure of the bf16 kernel
   int T, TN, BK, F, ROWB, CE, EB;
   int WM, WN;      // wave grid: wave = WN * wm + wn; A rows are split over wm, B rows over wn
   int key_shift;   // swizzle key = (row >> key_shift) & (chunks per row - 1)
   int64_t b_off;   // element offset of the B block inside one LDS stage
 };
 
-Geo geometry(bool big, bool fp8, int tile_n) {
+Geo geometry(bool big, bool fp8, bool mx, int tile_n) {
   Geo g;
   g.big = big;
   g.fp8 = fp8;
+  g.mx = big && fp8 && mx;
   g.EB = fp8 ? 1 : 2;
   g.CE = 16 / g.EB;
   g.ROWB = (fp8 || big) ? 128 : 64;
   g.WM = 2;
-  g.WN = (big && fp8) ? 4 : 2;
+  g.WN = (big && fp8 && !g.mx) ? 4 : 2;
   g.F = 16;
   if (big) {
     g.T = 256;
@@ -79,7 +81,7 @@ int g2l_threads(const Geo& g, bool is_b, Builder& b) {
     // That key spans the wave id, so those maps are stated on the thread id t = 64 w + lane, folded
     // into the lane axis: key = (t >> 4) & 7.
     const int NW = g.WM * g.WN, NI = (is_b ? g.TN : g.T) / (8 * NW);
-    if (!is_b && !g.fp8) {
+    if (!is_b && (!g.fp8 || g.mx)) {
       rows = {{NI, g.CE, REG}, {NW, 1, WAVE}, {8, CH, LANE}};
     } else {
       rows = {{NI, g.CE, REG}, {NW, 64, LANE}, {8, CH, LANE}};
@@ -202,10 +204,10 @@ int acc_layout(const Geo& g, int64_t grid_m, int64_t grid_n, bool tile_only, Bui
 
 // (T, T) tile of C -> wave, lane, reg: who stores which element.
 int c_store_layout(const Geo& g, Builder& b) {
-  // The bf16 256 x 256 kernel pairs neighbouring fragments: after an exchange between lane groups a
+  // The 4-wave 256 x 256 kernels (bf16, and fp8 on the scale path) pair neighbouring fragments: after an exchange between lane groups a
   // lane stores 8 consecutive columns (16 bytes).  Column = 128 wn + 32 p + 16 b + 8 h + 4 t + e is
   // stored by lane group 2 h + b from register 8 p + 4 t + e of the fragment row.
-  if (g.big && !g.fp8 && g.TN == 256) {
+  if (g.big && (!g.fp8 || g.mx) && g.TN == 256) {
     const int NFM = g.T / g.WM / g.F;
     b.D(g.WM, g.WN, WAVE);
     b.D(NFM, 32, REG);
@@ -235,7 +237,8 @@ extern "C" int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_la
   int tile = axe_gemm_tile(g);
   if (tile < 0) return tile;
   const bool big = tile != AXE_TILE_64x64x32;
-  const Geo geo = geometry(big, g->in_dtype == AXE_FP8_E4M3, tile == AXE_TILE_256x224x64 ? 224 : (big ? 256 : 64));
+  const bool mx = g->in_dtype == AXE_FP8_E4M3 && (!g->d_scale_a || g->scale_dtype == AXE_SCALE_E8M0);
+  const Geo geo = geometry(big, g->in_dtype == AXE_FP8_E4M3, mx, tile == AXE_TILE_256x224x64 ? 224 : (big ? 256 : 64));
   Builder b;
   int rc;
   switch (which) {

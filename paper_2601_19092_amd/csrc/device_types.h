@@ -83,8 +83,9 @@ struct GemmArgs {
   void* C;
   int64_t M, N, K;
   int64_t lda, ldb, ldc;           // row pitch of A (per i), of B's memory image (per j), of C (per i)
-  const float* scale_a;            // (ceil(M/128), nkb) or null
+  const float* scale_a;            // (ceil(M/128), nkb) or null; bytes (E8M0 codes) when scale_e8m0
   const float* scale_b;            // (ceil(N/128), nkb) or null
+  int32_t scale_e8m0;              // 1: the scale arrays hold one E8M0 byte per block (2^(code - 127))
   int32_t nkb;
   int32_t out_bf16;                // 0: fp32 output, 1: bf16 output
   int32_t grid_m, grid_n;          // workgroup tiles along M and N

@@ -1,0 +1,350 @@
+// fp8 (OCP e4m3) GEMM for gfx950 (MI355X) with power-of-two block scales (E8M0, one byte per
+// 128 x 128 block: value 2^(e - 127)) or none, on the matrix cores' own scale path:
+// v_mfma_scale_f32_16x16x128_f8f6f4 multiplies each operand by the scale its lane supplies and
+// accumulates in place, so the running sums stay in AGPRs and no vector-ALU fold is needed (the
+// kernel for arbitrary fp32 scales has to fold every product on the vector ALU).
+//
+// Structure and measured reasons are those of the bf16 kernel (kernels_gemm_bf16.hip): workgroup tile
+// 256 x 256, one workgroup of 4 waves per CU, wave tile 128 x 128 = 8 x 8 fragments in 256 AGPRs, five
+// 32 KiB LDS blocks (A double-buffered and staged through registers two K-steps ahead, B direct to
+// LDS through a ring of three), K rotation, tiles of a workgroup chained, direct paired stores.
+// What differs:
+//   K-step      : 128 elements = one LDS row = ONE MFMA per fragment (32 cycles); a K-step is 64 MFMAs,
+//                 split in two halves by fragment rows (rows 0..3, rows 4..7), with the barrier
+//                 between them.
+//   Fragments   : 32 bytes per lane (two ds_read_b128: K chunks q and q + 4, q = lane / 16 -- exactly the
+//                 order in which the instruction pairs the bytes of its operands: lane group q holds
+//                 k = 16 q .. 16 q + 15 and k = 64 + 16 q .. 64 + 16 q + 15, and the scale of lane
+//                 r + 16 b applies to the 32-wide block b of row r; found by experiment).  All 16
+//                 fragments of step kt+1 are read in the second half of step kt; rows are processed
+//                 in pairs so that a B fragment is re-read right after its last use (row 7) and is
+//                 not needed again before 14 MFMAs later.
+//   Scales      : two bytes per K-step and wave (its 128 rows and 128 columns lie in one scale block),
+//                 fetched with scalar loads one K-step ahead and broadcast to the lanes.
+#include <hip/hip_runtime.h>
+
+#include <type_traits>
+
+#include "device_types.h"
+#include "gemm_common.h"
+#include "kernels.h"
+
+namespace axe {
+
+namespace {
+constexpr int kRow = 128;                         // bytes of K per LDS row (128 fp8)
+constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-tile
+constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
+constexpr int kLds = 5 * kBlk;                    // 160 KiB
+constexpr int kRot = 8;                           // K-rotation window, in K-tiles
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((address_space(3))) void* lds_ptr;
+typedef __attribute__((address_space(3))) uint8_t* lds_u8;
+__device__ __forceinline__ i32x8 lds_read32(lds_u8 p0, lds_u8 p1) {
+  const i32x4 lo = *(__attribute__((address_space(3))) const i32x4*)p0;
+  const i32x4 hi = *(__attribute__((address_space(3))) const i32x4*)p1;
+  return i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
+// acc += (first * 2^(s_first - 127)) (16 x 128) * (second * 2^(s_second - 127)) (128 x 16), accumulator pinned to
+// AGPRs (see the bf16 kernel).  The scale operands are VGPRs whose byte 0 is the E8M0 code.
+__device__ __forceinline__ void mfma_scaled(f32x4& acc, i32x8 first, i32x8 second, uint32_t s_first, uint32_t s_second) {
+  asm volatile("v_mfma_scale_f32_16x16x128_f8f6f4 %0, %1, %2, %0, %3, %4 op_sel_hi:[0,0,0]"
+               : "+a"(acc)
+               : "v"(first), "v"(second), "v"(s_first), "v"(s_second));
+}
+}  // namespace
+
+__global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
+  __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
+  const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int w = __builtin_amdgcn_readfirstlane(tid >> 6);          // wave id 0..3, kept scalar
+  const int wm = w >> 1, wn = w & 1;                               // wave grid 2 x 2
+  const int nk = (int)(g.K / 128);
+  const int ntiles = g.grid_m * g.grid_n;
+  const int nk_rot = nk & ~(kRot - 1);                             // K-tiles beyond the last full rotation window keep their order
+  const bool scaled = g.scale_a != nullptr;
+
+  // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ... (cur and nxt, see the bf16 kernel)
+  const int a_pitch = (int)g.lda, b_pitch = (int)g.ldb;            // bytes
+  struct Tile {
+    __amdgpu_buffer_rsrc_t rb;
+    i32x4 ra_words;                                                // A's descriptor as the four SGPR words an asm statement takes
+    const uint8_t *sa, *sb;                                        // E8M0 codes of this wave's row block and column block, one per K-tile
+    int rot;
+  };
+  auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
+    Tile t;
+    if (v < ntiles) {
+      int tm, tn;
+      tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
+      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * kTile * g.ldb), 0,
+                                               255 * b_pitch + (int)g.K, 0x00020000);
+      t.rot = (tm + tn) & (kRot - 1);                              // K rotation
+      t.ra_words = raw_rsrc((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda, (uint32_t)(255 * a_pitch + (int)g.K));
+      t.sa = (const uint8_t*)g.scale_a + (int64_t)(2 * tm + wm) * g.nkb;
+      t.sb = (const uint8_t*)g.scale_b + (int64_t)(2 * tn + wn) * g.nkb;
+    } else {                                                       // no such tile: every load returns zero
+      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
+      t.ra_words = raw_rsrc(g.A, 0);
+      t.sa = (const uint8_t*)g.scale_a, t.sb = (const uint8_t*)g.scale_b;   // valid addresses; the codes are never used
+      t.rot = 0;
+    }
+    return t;
+  };
+  int v = blockIdx.x;
+  Tile cur = describe(v), nxt = describe(v + (int)gridDim.x);
+  // K-step T of the current tile (T >= nk: step T - nk of the next one) -> K-tile index
+  auto ktile = [&](int T, int rot) -> int { return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T; };
+
+  // ---- block scales.  The wave's 128 rows and 128 columns lie in one scale block each, so a K-step
+  //      needs two codes.  A register per operand holds the codes of 64 consecutive K-steps of the
+  //      walk, one per lane; v_readlane hands out one per step.  The registers for the NEXT 64 steps
+  //      (of this tile, or the first of the next tile) are fetched when a block of 64 steps begins and
+  //      taken over when it ends.  These are ordinary loads: the compiler waits for them (for everything
+  //      outstanding, in fact) before the first use, once per 64 K-steps or per tile -- a register that
+  //      an asm-issued load is still filling must not live through a region where the register
+  //      allocator may decide to spill it.
+  uint32_t cva = 127u, cvb = 127u, nva = 127u, nvb = 127u;        // this block's and the next block's codes, lane = step % 64
+  auto fetch_codes = [&](const Tile& t, int base, uint32_t& oa, uint32_t& ob) __attribute__((always_inline)) {
+    if (!scaled) return;
+    const int T = base + lane;
+    const int kt_ = ktile(T < nk ? T : nk - 1, t.rot);
+    oa = t.sa[kt_];
+    ob = t.sb[kt_];
+  };
+  auto lane_value = [](uint32_t val, int l) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)val, l); };
+
+  // ---- HBM -> LDS / VGPR (as in the bf16 kernel; pitches and columns in bytes = elements)
+  const int lr = lane >> 3, lp = lane & 7;
+  const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 4 i) * 8 + lr
+  const int a_voff = (w * 8 + lr) * a_pitch + lp * 16;
+  const int a_voff_x = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
+  const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
+  const int a_piece = 32 * a_pitch, b_piece = 32 * b_pitch;        // bytes between pieces
+  const lds_u8 a_wr = lds3 + (w * 8 + lr) * kRow + ((lp ^ lkey) << 4);    // + stage * kBlk + i * 4096
+
+  u32x4 stg[16];                                                   // A staging: slot (T & 1) * 8 + i
+  auto a_load = [&](int T, int i, bool cross) __attribute__((always_inline)) -> u32x4 {
+    const bool nx = cross && T >= nk;
+    const i32x4 r = nx ? nxt.ra_words : cur.ra_words;
+    const int soff = __builtin_amdgcn_readfirstlane(i * a_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow);
+    u32x4 val;
+    asm volatile("s_nop 4\n\tbuffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(val) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
+    return val;
+  };
+  auto a_write = [&](int stage, int i, u32x4 val) __attribute__((always_inline)) {
+    *(__attribute__((address_space(3))) u32x4*)(a_wr + stage * kBlk + i * 4096) = val;
+  };
+  // prologue only: A straight into LDS, through descriptors that live only there
+  auto a_rsrc = [&](int vv) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
+    if (vv >= ntiles) return __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
+    int tm, tn;
+    tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
+    return __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda), 0, 255 * a_pitch + (int)g.K,
+                                             0x00020000);
+  };
+  const __amdgpu_buffer_rsrc_t ra_first = a_rsrc(v);
+  auto a_direct = [&](int T, int i, int stage) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(ra_first, (lds_ptr)(lds3 + stage * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
+                                             i * a_piece + ktile(T, cur.rot) * kRow, 0, 0);
+  };
+  int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;     // B ring: blocks of K-steps kt, kt+1, kt+2
+  auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
+    const bool nx = cross && T >= nk;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16, b_voff,
+                                             i * b_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+  };
+
+  // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16, chunks q and q + 4
+  const int fr = lane & 15, fq = lane >> 4;
+  const int fkey = (fr >> 1) & 7;
+  const lds_u8 fax0 = lds3 + (wm * 128 + fr) * kRow + ((fq ^ fkey) << 4);
+  const lds_u8 fax1 = lds3 + (wm * 128 + fr) * kRow + (((fq + 4) ^ fkey) << 4);
+  const lds_u8 fbx0 = lds3 + (wn * 128 + fr) * kRow + ((fq ^ fkey) << 4);
+  const lds_u8 fbx1 = lds3 + (wn * 128 + fr) * kRow + (((fq + 4) ^ fkey) << 4);
+  auto read_a = [&](int f, int off) __attribute__((always_inline)) -> i32x8 {
+    return lds_read32(fax0 + off + f * 16 * kRow, fax1 + off + f * 16 * kRow);
+  };
+  auto read_b = [&](int f, int off) __attribute__((always_inline)) -> i32x8 {
+    return lds_read32(fbx0 + off + f * 16 * kRow, fbx1 + off + f * 16 * kRow);
+  };
+
+  f32x4 acc[8][8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i)
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+
+  i32x8 fa[8], fb[8];      // all fragments of the current K-step; each is re-read for the next step right after its last use
+
+  // ---- VGPR -> HBM (as in the bf16 kernel: fragment pairs exchange halves, 16 bytes per lane)
+  i32x4 rc;
+  int c_rowblk;
+  const int c_voff2 = (int)((fr * g.ldc + ((fq & 1) ? 16 + 4 * (fq - 1) : 4 * fq)) * 2);
+  auto set_output = [&](int vv) __attribute__((always_inline)) {
+    int tm, tn;
+    tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
+    rc = raw_rsrc((uint16_t*)g.C + ((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * kTile + wn * 128,
+                  (uint32_t)((127 * g.ldc + 128) * 2));
+    c_rowblk = (int)(16 * g.ldc * 2);
+  };
+  auto store_fragment_pair = [&](int i, int j) __attribute__((always_inline)) {
+    const auto lo = __builtin_amdgcn_permlane16_swap(pack_bf16(acc[i][j][0], acc[i][j][1]),
+                                                     pack_bf16(acc[i][j + 1][0], acc[i][j + 1][1]), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16(acc[i][j][2], acc[i][j][3]),
+                                                     pack_bf16(acc[i][j + 1][2], acc[i][j + 1][3]), false, false);
+    const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
+    const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
+  };
+
+  using I0 = std::integral_constant<int, 0>;
+  using I1 = std::integral_constant<int, 1>;
+
+  // Half H of K-step kt (PAR = kt & 1), in exact program order: fragment rows 4 H .. 4 H + 3, two rows at a
+  // time with j innermost: MFMAs (r, j), (r + 1, j).  After MFMAs 2, 10, 18, 26 one B load, after MFMAs
+  // 6, 14, 22, 30 one staged A piece goes to LDS and its slot is reloaded (pieces, steps and blocks as in
+  // the bf16 kernel).  The second half also reads the 16 fragments of step kt+1, each right after the
+  // last MFMA that uses the register it goes to: A fragments 0..3 during rows 4, 5; A fragments 4, 5
+  // and, after MFMA (7, j), B fragment j during rows 6, 7; A fragments 6, 7 at the end.
+  auto half = [&](auto par_c, auto h_c, auto cross_c, int kt, uint32_t va, uint32_t vb) __attribute__((always_inline)) {
+    constexpr int PAR = decltype(par_c)::value, H = decltype(h_c)::value;
+    constexpr bool CROSS = decltype(cross_c)::value != 0;
+    constexpr int WST = H == 0 ? PAR ^ 1 : PAR;
+    const int wT = H == 0 ? kt + 1 : kt + 2;
+    const int bT = H == 0 ? kt + 2 : kt + 3;
+    const int bslot = H == 0 ? bo2 : bo0;
+    constexpr int pa = (PAR ^ 1) * kBlk;                           // step kt+1: A stage, B ring block
+    const int pb = bo1;
+#pragma unroll
+    for (int q = 0; q < 32; ++q) {
+      const int i = 4 * H + 2 * (q >> 4) + (q & 1), j = (q >> 1) & 7;
+      mfma_scaled(acc[i][j], fb[j], fa[i], vb, va);
+      __builtin_amdgcn_sched_barrier(0);
+      if (H == 1) {
+        if (q < 16 && (q & 3) == 1) fa[q >> 2] = read_a(q >> 2, pa);
+        if (q == 16) fa[4] = read_a(4, pa);
+        if (q == 18) fa[5] = read_a(5, pa);
+        if (q >= 16 && (q & 1) == 1) fb[j] = read_b(j, pb);
+        if (q == 31) {
+          fa[6] = read_a(6, pa);
+          fa[7] = read_a(7, pa);
+        }
+      }
+      if ((q & 7) == 2) b_load(bT, (H == 0 ? 4 : 0) + (q >> 3), bslot, CROSS);
+      if ((q & 7) == 6) {
+        const int p = (H == 0 ? 4 : 0) + (q >> 3);
+        // the load that filled this slot was issued 4 halves ago; 31 loads have been issued since
+        asm volatile("s_waitcnt vmcnt(31)" ::: "memory");
+        a_write(WST, p, stg[WST * 8 + p]);
+        stg[WST * 8 + p] = a_load(wT + 2, p, CROSS);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    if (H == 0) {
+      // Own writes of step kt+1 are complete, and so are own B loads of step kt+1 (the 17 younger loads may
+      // still be in flight); nobody has read LDS since the last barrier's second half.  After the barrier
+      // step kt+1 is readable by every wave and the blocks of step kt are free.
+      asm volatile("s_waitcnt vmcnt(17) lgkmcnt(0)" ::: "memory");
+      wg_barrier();
+    }
+  };
+  auto step = [&](auto par_c, auto cross_c, int kt) __attribute__((always_inline)) {
+    uint32_t va = lane_value(cva, kt & 63), vb = lane_value(cvb, kt & 63);
+    // the codes are now in VGPRs, written by the vector ALU; the MFMA is an asm statement, so the compiler's
+    // hazard recogniser cannot pad between that write and the matrix core's read of its scale operands
+    asm volatile("s_nop 3" : "+v"(va), "+v"(vb));
+    half(par_c, I0{}, cross_c, kt, va, vb);
+    half(par_c, I1{}, cross_c, kt, va, vb);
+    const int t = bo0;
+    bo0 = bo1, bo1 = bo2, bo2 = t;
+  };
+
+  // ---- prologue (first tile only), as in the bf16 kernel
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a_direct(0, i, 0);
+  if (nk > 1) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) a_direct(1, i, 1);
+  } else {                                                         // a single K-step per tile: step 1 belongs to the next tile
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc(v + (int)gridDim.x), (lds_ptr)(lds3 + kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
+                                               i * a_piece + ktile(0, nxt.rot) * kRow, 0, 0);
+  }
+#pragma unroll
+  for (int i = 4; i < 8; ++i) stg[8 + i] = a_load(1, i, true);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) stg[i] = a_load(2, i, true);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) stg[8 + i] = a_load(3, i, true);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) b_load(1, i, bo1, true);
+#pragma unroll
+  for (int i = 0; i < 4; ++i) b_load(2, i, bo2, true);
+  fetch_codes(cur, 0, cva, cvb);
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  wg_barrier();
+#pragma unroll
+  for (int f = 0; f < 8; ++f) fb[f] = read_b(f, bo0);
+#pragma unroll
+  for (int f = 0; f < 8; ++f) fa[f] = read_a(f, 0);
+
+  // ---- all K-steps of all tiles of this workgroup, one uninterrupted pipeline (nk even and >= 4 when chained)
+  for (;;) {
+    set_output(v);
+    const bool more = v + (int)gridDim.x < ntiles;
+    int kt = 0;
+    for (int base = 0; base < nk; base += 64) {
+      const int end = nk < base + 64 ? nk : base + 64;
+      // the next 64 steps of the walk: of this tile, or the first of the next tile
+      if (end < nk) fetch_codes(cur, end, nva, nvb);
+      else if (more) fetch_codes(nxt, 0, nva, nvb);
+      for (; kt + 1 < end && kt + 5 < nk; kt += 2) {               // every load of these steps is of this tile (at most step kt + 5)
+        step(I0{}, I0{}, kt);
+        step(I1{}, I0{}, kt + 1);
+      }
+      for (; kt + 1 < end; kt += 2) {                              // the last steps load the next tile's first K-steps
+        step(I0{}, I1{}, kt);
+        step(I1{}, I1{}, kt + 1);
+      }
+      if (kt < end) {                                              // odd nk: only with one tile per workgroup
+        step(I0{}, I1{}, kt);
+        ++kt;
+      }
+      if (end < nk) cva = nva, cvb = nvb;
+    }
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");             // the last MFMAs retire before their results are read
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int i = 0; i < 8; ++i)
+#pragma unroll
+      for (int j = 0; j < 8; j += 2) store_fragment_pair(i, j);
+    v += (int)gridDim.x;
+    if (v >= ntiles) break;
+    cva = nva, cvb = nvb;
+    cur = nxt;
+    nxt = describe(v + (int)gridDim.x);
+  }
+}
+
+hipError_t launch_gemm_fp8_e8m0_256(const GemmArgs& g, hipStream_t s) {
+  const int ntiles = g.grid_m * g.grid_n;
+  const int nk = (int)(g.K / 128);
+  const int cus = cu_count();
+  const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
+  unsigned nwg = (unsigned)(chain ? cus : ntiles);
+  hipLaunchKernelGGL(gemm_fp8_e8m0_256_kernel, dim3(nwg), dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+}  // namespace axe

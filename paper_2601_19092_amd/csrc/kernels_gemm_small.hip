@@ -121,7 +121,13 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
       }
       if (g.scale_a) {
         // one K step is one 128-deep scale block: accumulate it alone, then scale and add
-        const float sc = g.scale_a[(int64_t)sa_row * g.nkb + kt] * g.scale_b[(int64_t)sb_row * g.nkb + kt];
+        float sc;
+        if (g.scale_e8m0) {          // 2^(ca - 127) * 2^(cb - 127), built as the bits of two floats (codes 1..254 are normal numbers)
+          const uint32_t ca = ((const uint8_t*)g.scale_a)[(int64_t)sa_row * g.nkb + kt], cb = ((const uint8_t*)g.scale_b)[(int64_t)sb_row * g.nkb + kt];
+          sc = __builtin_bit_cast(float, ca << 23) * __builtin_bit_cast(float, cb << 23);
+        } else {
+          sc = g.scale_a[(int64_t)sa_row * g.nkb + kt] * g.scale_b[(int64_t)sb_row * g.nkb + kt];
+        }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
 #pragma unroll

@@ -53,9 +53,10 @@ class GemmInputs:
     dtype: str                      # "bf16" | "fp8"
     a_mk: np.ndarray                # raw words, shape (M, K)
     b_nk: np.ndarray                # raw words, shape (N, K)
-    scale_a: Optional[np.ndarray] = None   # fp32 (ceil(M/128), ceil(K/128))
-    scale_b: Optional[np.ndarray] = None   # fp32 (ceil(N/128), ceil(K/128))
+    scale_a: Optional[np.ndarray] = None   # fp32, or uint8 E8M0 codes, (ceil(M/128), ceil(K/128))
+    scale_b: Optional[np.ndarray] = None   # same, (ceil(N/128), ceil(K/128))
     out_dtype: str = "bf16"         # "f32" | "bf16"
+    scale_dtype: str = "f32"        # "f32" | "e8m0" (one byte per block, the power of two 2^(code - 127))
 
 
 def gemm_bf16(M: int, N: int, K: int, seed: int, std_a: float = 1.0, std_b: float = 1.0,
@@ -65,12 +66,17 @@ def gemm_bf16(M: int, N: int, K: int, seed: int, std_a: float = 1.0, std_b: floa
     return GemmInputs(M, N, K, "bf16", a, b, out_dtype=out_dtype)
 
 
-def gemm_fp8(M: int, N: int, K: int, seed: int, block: int = 128, scaled: bool = True) -> GemmInputs:
+def gemm_fp8(M: int, N: int, K: int, seed: int, block: int = 128, scaled=True) -> GemmInputs:
+    """scaled: False, True (fp32 scales uniform in [0.5, 2]) or "e8m0" (codes 124..130: powers of two 1/8 .. 8)."""
     a = to_e4m3_bits(normal(seed, (M, K)))
     b = to_e4m3_bits(normal(seed + 1000, (N, K)))
     sa = sb = None
+    kb = -(-K // block)
+    if scaled == "e8m0":
+        sa = (124 + np.floor(uniform(seed + 2000, (-(-M // block), kb), 0.0, 7.0))).astype(np.uint8)
+        sb = (124 + np.floor(uniform(seed + 3000, (-(-N // block), kb), 0.0, 7.0))).astype(np.uint8)
+        return GemmInputs(M, N, K, "fp8", a, b, sa, sb, out_dtype="bf16", scale_dtype="e8m0")
     if scaled:
-        kb = -(-K // block)
         sa = uniform(seed + 2000, (-(-M // block), kb), 0.5, 2.0)
         sb = uniform(seed + 3000, (-(-N // block), kb), 0.5, 2.0)
     return GemmInputs(M, N, K, "fp8", a, b, sa, sb, out_dtype="bf16")

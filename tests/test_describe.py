@@ -22,14 +22,22 @@ def desc_for(kind):
         M, N, K, dt, out, tile = 256, 256, 256, B.AXE_BF16, B.AXE_F32, B.AXE_TILE_AUTO
     elif kind == "small_fp8":
         M, N, K, dt, out, tile = 128, 192, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_64x64x32
-    elif kind == "big_fp8":
+    elif kind in ("big_fp8", "big_fp8_mx"):
         M, N, K, dt, out, tile = 512, 768, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_AUTO
     elif kind == "big_bf16_n224":
         M, N, K, dt, out, tile = 512, 672, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_AUTO
     else:
         M, N, K, dt, out, tile = 512, 768, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_AUTO
+    scales = {}
+    if kind == "big_fp8":
+        # fp32 block scales: the 8-wave kernel that folds on the vector ALU.  describe never touches the
+        # arrays; a non-NULL address stands for them.
+        class _Fake:
+            def data_ptr(self):
+                return 0x1000
+        scales = dict(scale_a=_Fake(), scale_b=_Fake())
     d = B.GemmDesc(M, N, K, dt, out, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, N)),
-                   B.Layout(W.row_major_spec(M, N)), M * K, N * K, M * N, tile_hint=tile)
+                   B.Layout(W.row_major_spec(M, N)), M * K, N * K, M * N, tile_hint=tile, **scales)
     return d, (M, N, K)
 
 
@@ -46,11 +54,14 @@ def table(L, shape):
 # T x TN x BK: rows of A, rows of B (columns of C) and K elements per workgroup tile
 GEO = {"small_bf16": dict(T=64, TN=64, BK=32, EB=2, waves=4, wn=2), "small_fp8": dict(T=64, TN=64, BK=128, EB=1, waves=4, wn=2),
        "big_bf16": dict(T=256, TN=256, BK=64, EB=2, waves=4, wn=2), "big_fp8": dict(T=256, TN=256, BK=128, EB=1, waves=8, wn=4),
-       "big_bf16_n224": dict(T=256, TN=224, BK=64, EB=2, waves=4, wn=2)}
-KINDS = ["small_bf16", "small_fp8", "big_bf16", "big_fp8", "big_bf16_n224"]
-BIG = ("big_bf16", "big_fp8", "big_bf16_n224")
+       "big_bf16_n224": dict(T=256, TN=224, BK=64, EB=2, waves=4, wn=2),
+       "big_fp8_mx": dict(T=256, TN=256, BK=128, EB=1, waves=4, wn=2)}
+KINDS = ["small_bf16", "small_fp8", "big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx"]
+BIG = ("big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx")
+A_VIA_REGISTERS = ("big_bf16", "big_bf16_n224", "big_fp8_mx")        # A staged through VGPRs and written with ds_write
+PAIRED_STORES = ("big_bf16", "big_fp8_mx")
 TILE = {"small_bf16": B.AXE_TILE_64x64x32, "small_fp8": B.AXE_TILE_64x64x32, "big_bf16": B.AXE_TILE_256x256x64,
-        "big_fp8": B.AXE_TILE_256x256x64, "big_bf16_n224": B.AXE_TILE_256x224x64}
+        "big_fp8": B.AXE_TILE_256x256x64, "big_bf16_n224": B.AXE_TILE_256x224x64, "big_fp8_mx": B.AXE_TILE_256x256x64}
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -130,7 +141,7 @@ def test_global_to_lds_thread_map(kind):
             for w, i in itertools.product(range(NW), range(regs // CE)):
                 b0 = first[w, :, i].min()
                 assert b0 % 1024 == 0
-                if which_l == B.AXE_DESC_B_LDS or kind == "big_fp8":
+                if which_l == B.AXE_DESC_B_LDS or kind not in A_VIA_REGISTERS:
                     # direct-to-LDS load: lane l writes byte 16 l of the piece
                     assert np.array_equal(first[w, :, i], b0 + 16 * np.arange(64))
                 else:
@@ -187,7 +198,7 @@ def test_operand_reads_cover_the_tile_and_are_bank_conflict_free(kind):
             assert (worst == 1) == expect_clean, (kind, which_o, swz, worst)
 
 
-@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16", "big_fp8", "big_bf16_n224"])
+@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx"])
 def test_c_store_map(kind):
     desc, _ = desc_for(kind)
     T, TN, NW, WN = GEO[kind]["T"], GEO[kind]["TN"], GEO[kind]["waves"], GEO[kind]["wn"]
@@ -201,7 +212,7 @@ def test_c_store_map(kind):
         # at a time (4 registers = 4 columns per lane: 16 rows x 32 contiguous bytes); the 256-wide bf16
         # kernel stores fragment pairs (8 registers = 8 columns per lane: 16 rows x 64 contiguous bytes).
         # Either way the stores of a fragment row follow one another and complete TN / WN * 2 bytes per row.
-        per = 8 if kind == "big_bf16" else 4
+        per = 8 if kind in PAIRED_STORES else 4
         lanes_per_row = 64 // 16
         per_row = TN // WN // (per * lanes_per_row)                   # store instructions per fragment row
         col = np.empty(T * TN, dtype=np.int64); row = np.empty(T * TN, dtype=np.int64)
@@ -219,7 +230,7 @@ def test_c_store_map(kind):
         for w, i in itertools.product(range(NW), range(8)):           # fragment row i
             c0 = np.sort(np.unique(col[w, :, per_row * i:per_row * i + per_row, :]))
             assert np.array_equal(c0, c0[0] + np.arange(TN // WN))
-    if kind == "big_bf16":
+    if kind in PAIRED_STORES:
         # the exchange: lane group q = lane // 16 of the accumulator layout holds columns 4 q .. 4 q + 3 of
         # each fragment; the storing lane group of column c (inside its 32-column fragment pair) is
         # 2 * ((c % 16) // 8) + (c // 16): even groups store the first fragment, odd groups the second
@@ -261,7 +272,7 @@ def test_fp8_mfma_operand_layout_matches_its_statement():
     """MFMA 16x16x128 fp8 as the kernels feed it: lane = row + 16 * ((k % 64) // 16); the lane's 32 bytes
     are k = 16 q .. 16 q + 15 (registers 0..15) and k = 64 + 16 q .. (registers 16..31): the same two runs
     for A and for B, so every product pairs equal k."""
-    for kind in ("small_fp8", "big_fp8"):
+    for kind in ("small_fp8", "big_fp8", "big_fp8_mx"):
         desc, _ = desc_for(kind)
         T = GEO[kind]["T"]
         for which, shape_of in ((B.AXE_DESC_A_OPERAND, lambda r, k: (r, k)), (B.AXE_DESC_B_OPERAND, lambda r, k: (k, r))):

@@ -282,7 +282,8 @@ def run_gemm(g: W.GemmInputs, tile=B.AXE_TILE_AUTO, device_axis=False, lda=None,
     desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16 if g.dtype == "bf16" else B.AXE_FP8_E4M3,
                       B.AXE_F32 if g.out_dtype == "f32" else B.AXE_BF16,
                       B.Layout(As, axes), B.Layout(Bs, axes), B.Layout(Cs, axes),
-                      a.size, b.size, g.M * ldc_, sa, sb, tile_hint=tile)
+                      a.size, b.size, g.M * ldc_, sa, sb, tile_hint=tile,
+                      scale_dtype=B.AXE_SCALE_E8M0 if g.scale_dtype == "e8m0" else B.AXE_SCALE_F32)
     B.axe_gemm(desc, dA, dB, dC)
     torch.cuda.synchronize()
     c = dC.cpu().numpy().reshape(g.M, ldc_)[:, :g.N]
@@ -297,9 +298,17 @@ def gemm_desc_only(g: W.GemmInputs, tile=B.AXE_TILE_AUTO):
                       B.Layout(As), B.Layout(Bs), B.Layout(Cs), g.M * g.K, g.N * g.K, g.M * g.N, tile_hint=tile)
 
 
+def oracle_scales(g: W.GemmInputs):
+    """The scale arrays as the oracle takes them (fp32); E8M0 codes are decoded by the oracle's own rule."""
+    if g.scale_a is None or g.scale_dtype != "e8m0":
+        return g.scale_a, g.scale_b
+    return R.e8m0_decode(g.scale_a).astype(np.float32), R.e8m0_decode(g.scale_b).astype(np.float32)
+
+
 def oracle_gemm(g: W.GemmInputs, rows=None, cols=None):
     dt = R.AXE_BF16 if g.dtype == "bf16" else R.AXE_FP8_E4M3
-    return R.gemm_ref(g.a_mk, g.b_nk.T, dt, g.scale_a, g.scale_b, rows=rows, cols=cols)
+    sa, sb = oracle_scales(g)
+    return R.gemm_ref(g.a_mk, g.b_nk.T, dt, sa, sb, rows=rows, cols=cols)
 
 
 def check_gemm(c, ref, tol, tile=128):
@@ -343,6 +352,13 @@ def test_gemm_device_axis_of_extent_one():
     g.out_dtype = "f32"
     c = run_gemm(g, device_axis=True)
     check_gemm(c, oracle_gemm(g), BF16_TOL, tile=64)
+
+
+def test_gemm_fp8_small_tile_e8m0():
+    for M, N, K in ((128, 256, 384), (200, 72, 272), (64, 64, 128)):
+        g = W.gemm_fp8(M, N, K, 60 + K, scaled="e8m0")
+        c = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+        check_gemm(c, oracle_gemm(g), FP8_TOL, tile=64)
 
 
 @pytest.mark.parametrize("M,N,K,scaled", [(128, 128, 128, False), (128, 256, 384, True), (200, 72, 272, True),
@@ -393,7 +409,9 @@ def test_gemm_bf16_large_tile_identity_pitched_and_device_axis():
 
 
 @pytest.mark.parametrize("M,N,K,scaled", [(256, 256, 128, False), (256, 512, 384, True), (512, 256, 256, True),
-                                          (512, 768, 1408, True), (768, 512, 2048, False), (256, 256, 8960, True)])
+                                          (512, 768, 1408, True), (768, 512, 2048, False), (256, 256, 8960, True),
+                                          (256, 256, 128, "e8m0"), (256, 512, 384, "e8m0"), (512, 768, 1408, "e8m0"),
+                                          (768, 512, 2048, "e8m0"), (256, 256, 8960, "e8m0"), (512, 256, 17152, "e8m0")])
 def test_gemm_fp8_large_tile(M, N, K, scaled):
     g = W.gemm_fp8(M, N, K, 80 + K, scaled=scaled)
     c = run_gemm(g, tile=B.AXE_TILE_256x256x64)
@@ -434,8 +452,9 @@ def full_size_check(g: W.GemmInputs, tol, device_axis=False, seed=0, tile=B.AXE_
         y_ref, z_ref = A @ (Bm.T @ v), (u @ A) @ Bm.T
     else:
         y_ref, z_ref = np.zeros(M), np.zeros(N)
-        sa = np.repeat(g.scale_a.astype(np.float64), 128, axis=0)[:M]      # (M, nkb)
-        sb = np.repeat(g.scale_b.astype(np.float64), 128, axis=0)[:N]      # (N, nkb)
+        fa, fb = oracle_scales(g)
+        sa = np.repeat(fa.astype(np.float64), 128, axis=0)[:M]             # (M, nkb)
+        sb = np.repeat(fb.astype(np.float64), 128, axis=0)[:N]             # (N, nkb)
         for kb in range(g.scale_a.shape[1]):
             ks = slice(kb * 128, (kb + 1) * 128)
             y_ref += sa[:, kb] * (A[:, ks] @ (Bm[:, ks].T @ (sb[:, kb] * v)))
@@ -463,6 +482,14 @@ def test_gemm_config4_full_size_shard():
 
 def test_gemm_config5_full_size_fp8_scaled():
     full_size_check(W.config5(), FP8_TOL, seed=5)
+
+
+def test_gemm_config5_shape_with_e8m0_scales_and_unscaled():
+    """Configuration 5's shape with power-of-two (E8M0) block scales, and without scales: both run on the
+    matrix cores' scale path (chained tiles, 64 K-steps)."""
+    full_size_check(W.gemm_fp8(8192, 8192, 8192, 19097, scaled="e8m0"), FP8_TOL, seed=9)
+    full_size_check(W.gemm_fp8(4352, 4096, 8448, 96, scaled="e8m0"), FP8_TOL, seed=10)   # 17 x 16 tiles, 66 K-steps: code registers refilled
+    full_size_check(W.gemm_fp8(4096, 4096, 4096, 97, scaled=False), FP8_TOL, seed=11)
 
 
 def test_gemm_chained_tiles_on_a_grid_of_17_by_16():

@@ -136,6 +136,32 @@ def test_e4m3_decode_matches_torch_and_format_facts():
     assert not np.isinf(got).any()
 
 
+def test_e8m0_decode_format_facts():
+    """E8M0 (OCP microscaling): value 2^(code - 127), bias 127, 255 is NaN, no zero, no sign; torch's
+    float8_e8m0fnu view, where this build of torch has it, must agree on every code."""
+    v = R.e8m0_decode(np.arange(256, dtype=np.uint8))
+    assert v[127] == 1.0 and v[128] == 2.0 and v[126] == 0.5 and v[0] == 2.0 ** -127 and v[254] == 2.0 ** 127
+    assert np.isnan(v[255]) and np.all(v[:255] > 0)
+    assert np.all(v[1:255] == 2.0 * v[0:254])                       # each code doubles the one before
+    assert np.array_equal(v[1:255].astype(np.float32).astype(np.float64), v[1:255])     # exact in fp32 (normal numbers)
+    import torch
+    if hasattr(torch, "float8_e8m0fnu"):
+        t = torch.arange(256, dtype=torch.uint8).view(torch.float8_e8m0fnu).to(torch.float64).numpy()
+        assert np.array_equal(np.isnan(t), np.isnan(v)) and np.array_equal(t[:255], v[:255])
+    # a GEMM with E8M0 scales is the fp32-scaled GEMM on the decoded scales
+    g = W.gemm_fp8(128, 256, 384, 5, scaled="e8m0")
+    assert g.scale_a.dtype == np.uint8 and g.scale_a.min() >= 124 and g.scale_a.max() <= 130
+    sa, sb = R.e8m0_decode(g.scale_a).astype(np.float32), R.e8m0_decode(g.scale_b).astype(np.float32)
+    c = R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, sa, sb)
+    want = R.gemm_ref_numpy(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, sa, sb)
+    assert np.allclose(c, want, rtol=1e-12, atol=1e-12)
+    # power-of-two scales commute with rounding: scaling the block sums equals scaling the decoded inputs
+    A, Bm = R.decode(g.a_mk, R.AXE_FP8_E4M3), R.decode(g.b_nk, R.AXE_FP8_E4M3)
+    As = A * np.repeat(np.repeat(sa.astype(np.float64), 128, 0), 128, 1)[:128, :384]
+    Bs = Bm * np.repeat(np.repeat(sb.astype(np.float64), 128, 0), 128, 1)[:256, :384]
+    assert np.allclose(As @ Bs.T, c, rtol=1e-12, atol=1e-12)
+
+
 def test_input_quantisation_is_round_to_nearest_even():
     x = W.normal(3, (4096,), 1.0)
     # bf16: decoded value is the nearest representable; spacing is 2^-7 relative at most
