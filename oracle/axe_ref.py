@@ -258,6 +258,33 @@ def gemm_ref(a_bits: np.ndarray, b_bits: np.ndarray, dtype: int,
     return out
 
 
+def gemm_grouped_ref(a_bits: np.ndarray, b_bits: np.ndarray, group_rows: Sequence[int], dtype: int,
+                     rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None) -> np.ndarray:
+    """Grouped GEMM, the building block of the fused MoE layer of Sec. 4.1 (its two "group GEMMs"):
+    the rows of A are sorted by group (expert), group g owns rows group_rows[g] .. group_rows[g+1]-1
+    and has its own right-hand side:  C[r, :] = A[r, :] @ B[g]  for r in that range.
+
+    a_bits logical (M, K); b_bits logical (G, K, N) (any strides); group_rows G+1 non-decreasing
+    integers, 0 <= group_rows[0], group_rows[G] <= M.  fp64 result [len(rows), len(cols)]; a row that
+    belongs to no group is NaN (the operation does not define, and must not write, it).
+    Each group is one call of the plain triple loop (gemm_ref): nothing is blocked or fused."""
+    M, K = a_bits.shape
+    G, K2, N = b_bits.shape
+    off = [int(x) for x in group_rows]
+    if len(off) != G + 1 or K2 != K:
+        raise ValueError("group_rows needs G + 1 entries; inner dimensions must agree")
+    if off[0] < 0 or off[-1] > M or any(off[g] > off[g + 1] for g in range(G)):
+        raise ValueError("group_rows must be non-decreasing within [0, M]")
+    rows = np.arange(M, dtype=np.int64) if rows is None else np.asarray(rows, dtype=np.int64)
+    cols = np.arange(N, dtype=np.int64) if cols is None else np.asarray(cols, dtype=np.int64)
+    out = np.full((rows.size, cols.size), np.nan, dtype=np.float64)
+    for g in range(G):
+        sel = np.nonzero((rows >= off[g]) & (rows < off[g + 1]))[0]
+        if sel.size:
+            out[sel, :] = gemm_ref(a_bits, b_bits[g], dtype, rows=rows[sel], cols=cols)
+    return out
+
+
 def rel_frobenius(c: np.ndarray, ref: np.ndarray) -> float:
     """|| c - ref ||_F / || ref ||_F in fp64."""
     c = np.asarray(c, dtype=np.float64)

@@ -82,6 +82,58 @@ def gemm_fp8(M: int, N: int, K: int, seed: int, block: int = 128, scaled=True) -
     return GemmInputs(M, N, K, "fp8", a, b, sa, sb, out_dtype="bf16")
 
 
+@dataclass
+class GroupedGemmInputs:
+    """Grouped GEMM over experts: A (M, K) row-major, rows sorted by group; B logical (G, K, N) whose memory
+    image `b_gnk` is (G, N, K) (each group's matrix column-major, as in GemmInputs); group_rows = G + 1 row
+    offsets (int32, non-decreasing, group_rows[G] <= M)."""
+    M: int
+    N: int
+    K: int
+    G: int
+    a_mk: np.ndarray
+    b_gnk: np.ndarray
+    group_rows: np.ndarray
+
+
+def moe_group_rows(tokens: int, experts: int, topk: int, seed: int, skew: float = 0.5) -> np.ndarray:
+    """Rows per expert of a synthetic top-k routing: every token picks `topk` distinct experts by
+    Gumbel-top-k on expert popularities drawn from N(0, skew^2) (mildly unbalanced, like a trained
+    router; skew 0 = uniform).  Returns the experts + 1 offsets of the rows sorted by expert."""
+    rng = _rng(seed)
+    pop = rng.standard_normal(experts) * skew
+    keys = pop[None, :] + rng.gumbel(size=(tokens, experts))
+    pick = np.argpartition(-keys, topk - 1, axis=1)[:, :topk]
+    counts = np.bincount(pick.ravel(), minlength=experts)
+    return np.concatenate([[0], np.cumsum(counts)]).astype(np.int32)
+
+
+def gemm_grouped_bf16(group_rows, N: int, K: int, seed: int, M: Optional[int] = None, std_a: float = 1.0,
+                      std_b: Optional[float] = None) -> GroupedGemmInputs:
+    group_rows = np.ascontiguousarray(group_rows, dtype=np.int32)
+    G = group_rows.size - 1
+    M = int(group_rows[-1]) if M is None else M
+    std_b = K ** -0.5 if std_b is None else std_b
+    return GroupedGemmInputs(M, N, K, G, to_bf16_bits(normal(seed, (M, K), std_a)),
+                             to_bf16_bits(normal(seed + 7919, (G, N, K), std_b)), group_rows)
+
+
+# the MoE layer of Qwen3-30B-A3B (the configuration the paper's fused-MoE figure is measured on):
+# hidden size, expert intermediate size, experts, experts per token
+MOE_HIDDEN, MOE_INTER, MOE_EXPERTS, MOE_TOPK = 2048, 768, 128, 8
+
+
+def moe_gemm1(tokens: int, seed: int = SEED_BASE + 11) -> GroupedGemmInputs:
+    """First grouped GEMM of the layer: routed tokens (tokens * topk rows of the hidden size) against each
+    expert's gate and up projections side by side (N = 2 * intermediate)."""
+    return gemm_grouped_bf16(moe_group_rows(tokens, MOE_EXPERTS, MOE_TOPK, seed), 2 * MOE_INTER, MOE_HIDDEN, seed + 1)
+
+
+def moe_gemm2(tokens: int, seed: int = SEED_BASE + 11) -> GroupedGemmInputs:
+    """Second grouped GEMM: the activations (intermediate size) against each expert's down projection."""
+    return gemm_grouped_bf16(moe_group_rows(tokens, MOE_EXPERTS, MOE_TOPK, seed), MOE_HIDDEN, MOE_INTER, seed + 2)
+
+
 def relayout_words(rows: int, cols: int, seed: int, kind: str = "uniform") -> np.ndarray:
     """Raw bf16 words of a (rows, cols) tensor.  kind="uniform": i.i.d. uniform[-1, 1] cast to
     bf16; kind="index": word = (flat index * 40503) mod 65536, so that a misplaced chunk cannot

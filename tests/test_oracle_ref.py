@@ -262,3 +262,72 @@ def test_workload_seeds_and_statistics():
     assert np.abs(R.bf16_to_f64(w)).max() <= 1.0
     idx = W.config2("index", 128, 64)
     assert idx[0, 1] == 40503 and idx[1, 0] == (64 * 40503) % 65536
+
+
+# ----------------------------------------------------------------------------- grouped GEMM (MoE)
+def _grouped_case(seed, off, N, K, M=None):
+    g = W.gemm_grouped_bf16(off, N, K, seed, M=M)
+    return g, g.a_mk, g.b_gnk.transpose(0, 2, 1)          # logical (G, K, N) view of the (G, N, K) image
+
+
+def test_grouped_gemm_equals_block_diagonal_dense_product():
+    """Independent construction: place group g's rows of A in column block g of a (M, G K) matrix and
+    stack the B[g] vertically; one dense fp64 product (BLAS) then is the grouped GEMM."""
+    off = [0, 5, 5, 19, 40]                              # an empty group, ragged sizes
+    g, a, b = _grouped_case(3, off, N=24, K=32)
+    A = R.decode(a, R.AXE_BF16)
+    B = R.decode(np.ascontiguousarray(b), R.AXE_BF16)
+    G, K, N = B.shape
+    wide = np.zeros((g.M, G * K))
+    for e in range(G):
+        wide[off[e]:off[e + 1], e * K:(e + 1) * K] = A[off[e]:off[e + 1]]
+    want = wide @ B.reshape(G * K, N)
+    got = R.gemm_grouped_ref(a, b, off, R.AXE_BF16)
+    assert not np.isnan(got).any()
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-12)
+
+
+def test_grouped_gemm_brute_force_and_undefined_rows():
+    off = [2, 3, 7]                                      # rows 0, 1 and 7.. belong to no group
+    g, a, b = _grouped_case(4, off, N=5, K=16, M=9)
+    A = R.decode(a, R.AXE_BF16)
+    B = R.decode(np.ascontiguousarray(b), R.AXE_BF16)
+    got = R.gemm_grouped_ref(a, b, off, R.AXE_BF16)
+    for r in range(9):
+        owner = [e for e in range(2) if off[e] <= r < off[e + 1]]
+        for j in range(5):
+            if not owner:
+                assert np.isnan(got[r, j])
+            else:
+                want = sum(A[r, k] * B[owner[0], k, j] for k in range(16))
+                assert abs(got[r, j] - want) <= 1e-12 * max(1.0, abs(want))
+
+
+def test_grouped_gemm_special_cases():
+    # one group = the plain GEMM; sampled rows / columns = the same entries of the full result
+    g, a, b = _grouped_case(5, [0, 33], N=17, K=48)
+    full = R.gemm_grouped_ref(a, b, [0, 33], R.AXE_BF16)
+    np.testing.assert_array_equal(full, R.gemm_ref(a, b[0], R.AXE_BF16))
+    rows, cols = np.array([32, 0, 7]), np.array([16, 3])
+    np.testing.assert_array_equal(R.gemm_grouped_ref(a, b, [0, 33], R.AXE_BF16, rows=rows, cols=cols), full[np.ix_(rows, cols)])
+    # swapping two groups (rows and right-hand sides together) swaps their output rows
+    off = [0, 4, 10]
+    g, a, b = _grouped_case(6, off, N=8, K=16)
+    c = R.gemm_grouped_ref(a, b, off, R.AXE_BF16)
+    a2 = np.concatenate([a[4:10], a[0:4]])
+    c2 = R.gemm_grouped_ref(a2, b[::-1], [0, 6, 10], R.AXE_BF16)
+    np.testing.assert_array_equal(c2, np.concatenate([c[4:10], c[0:4]]))
+    with pytest.raises(ValueError):
+        R.gemm_grouped_ref(a, b, [0, 11, 10], R.AXE_BF16)
+
+
+def test_moe_routing_recipe():
+    """tokens x topk rows in all, every token in topk distinct experts, fixed by the seed."""
+    off = W.moe_group_rows(512, 128, 8, W.SEED_BASE)
+    assert off.dtype == np.int32 and off.size == 129 and off[0] == 0 and off[-1] == 512 * 8
+    assert (np.diff(off) >= 0).all() and np.diff(off).max() <= 512          # an expert sees a token at most once
+    np.testing.assert_array_equal(off, W.moe_group_rows(512, 128, 8, W.SEED_BASE))
+    assert (W.moe_group_rows(512, 128, 8, W.SEED_BASE + 1) != off).any()
+    g1, g2 = W.moe_gemm1(64), W.moe_gemm2(64)
+    assert (g1.M, g1.N, g1.K, g1.G) == (512, 1536, 2048, 128) and (g2.N, g2.K) == (2048, 768)
+    np.testing.assert_array_equal(g1.group_rows, g2.group_rows)
