@@ -164,6 +164,42 @@ int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d
 int axe_gemm_tile(const axe_gemm_desc_t* g);
 
 /* ---------------------------------------------------------------------------------------------
+ * axe_gemm_grouped -- the grouped GEMM of a mixture-of-experts layer (Sec. 4.1, "fused MoE layer": its
+ * two group GEMMs): the rows of A and C are sorted by group (expert), group e owns the rows
+ * group_rows[e] .. group_rows[e+1]-1 and has its own right-hand side,
+ *       C[r, j] = sum_k A[r, k] * B[e, k, j]      for group_rows[e] <= r < group_rows[e+1].
+ * Rows that belong to no group (below group_rows[0], from group_rows[G] on) are not written.
+ *
+ *   M, N, K : logical sizes; M = rows of A and C, all groups together (any positive value).
+ *   G       : number of groups, 1..4096.
+ *   A : (M, K), B : (G, K, N), C : (M, N)  Axe layouts on `mem_axis`, in elements.
+ *   d_A, d_B, d_C  : DEVICE buffers of a_elems / b_elems / c_elems elements, 16-byte aligned;
+ *                    d_C must not overlap d_A or d_B.
+ *   d_group_rows   : DEVICE, G + 1 int32, non-decreasing, within [0, M].  The host never reads them
+ *                    (a router writes them on the device): the kernel clamps each entry to [0, M], so
+ *                    no access leaves the buffers whatever they hold; entries that decrease give
+ *                    unspecified values in C.
+ * Supported family (else AXE_EUNSUPPORTED): bf16 inputs, bf16 output; A and C row-major, each B[e]
+ * column-major (unit stride along k) with one pitch for all e and a constant stride between groups
+ * (the grouped form of B by (G, K, N) has one iter per block); leading dimensions, offsets and the group
+ * stride multiples of 16 bytes; N a multiple of 256, K a multiple of 64.
+ * One launch: tiles are (group, 256 rows of it, 256 columns), found on the device from d_group_rows;
+ * nothing is allocated and no scratch memory is used. */
+typedef struct {
+  int64_t      M, N, K;
+  int32_t      G;
+  int32_t      in_dtype, out_dtype;      /* AXE_BF16, AXE_BF16 */
+  axe_layout_t A, B, C;
+  int32_t      mem_axis;
+  int64_t      a_elems, b_elems, c_elems;
+} axe_gemm_grouped_desc_t;
+
+int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const void* d_B, void* d_C,
+                     const int32_t* d_group_rows, void* stream);
+/* The checks of axe_gemm_grouped without a launch (host only): AXE_OK or the error it would return. */
+int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g);
+
+/* ---------------------------------------------------------------------------------------------
  * axe_gemm_describe -- the Axe layouts of every tile movement of the kernel axe_gemm would
  * launch for `g` (Sec. 3.1 / Fig. 3: tensors in shared memory and registers carry layouts; tile
  * composes register tile (x) lane (x) wave (x) workgroup, Sec. 3.3).  Host only, no device work.

@@ -22,7 +22,7 @@ AXE_TILE_AUTO, AXE_TILE_64x64x32, AXE_TILE_256x256x64, AXE_TILE_256x224x64 = 0, 
 AXE_MAX_RANK = 8
 AXE_SCALE_F32, AXE_SCALE_E8M0 = 0, 1
 
-EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
+EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
            "axe_last_error", "axe_version", "axe_layout_span", "axe_layout_canonicalize", "axe_layout_gap_condition",
            "axe_layout_equal", "axe_layout_group", "axe_layout_tile", "axe_layout_direct_sum", "axe_layout_tile_of",
            "axe_layout_slice"]
@@ -48,6 +48,14 @@ class axe_gemm_desc_t(C.Structure):
                 ("a_elems", C.c_int64), ("b_elems", C.c_int64), ("c_elems", C.c_int64),
                 ("d_scale_a", C.c_void_p), ("d_scale_b", C.c_void_p),
                 ("scale_block", C.c_int32), ("tile_hint", C.c_int32), ("scale_dtype", C.c_int32)]
+
+
+class axe_gemm_grouped_desc_t(C.Structure):
+    _fields_ = [("M", C.c_int64), ("N", C.c_int64), ("K", C.c_int64), ("G", C.c_int32),
+                ("in_dtype", C.c_int32), ("out_dtype", C.c_int32),
+                ("A", axe_layout_t), ("B", axe_layout_t), ("C", axe_layout_t),
+                ("mem_axis", C.c_int32),
+                ("a_elems", C.c_int64), ("b_elems", C.c_int64), ("c_elems", C.c_int64)]
 
 
 class AxeError(RuntimeError):
@@ -76,6 +84,10 @@ def lib() -> C.CDLL:
         L.axe_relayout.argtypes = [LP, LP, i32, C.POINTER(i64), i32, i32, vp, i64, vp, i64, vp]
         L.axe_gemm.restype = C.c_int
         L.axe_gemm.argtypes = [C.POINTER(axe_gemm_desc_t), vp, vp, vp, vp]
+        L.axe_gemm_grouped.restype = C.c_int
+        L.axe_gemm_grouped.argtypes = [C.POINTER(axe_gemm_grouped_desc_t), vp, vp, vp, vp, vp]
+        L.axe_gemm_grouped_check.restype = C.c_int
+        L.axe_gemm_grouped_check.argtypes = [C.POINTER(axe_gemm_grouped_desc_t)]
         L.axe_gemm_tile.restype = C.c_int
         L.axe_gemm_tile.argtypes = [C.POINTER(axe_gemm_desc_t)]
         L.axe_gemm_describe.restype = C.c_int
@@ -198,6 +210,30 @@ def axe_gemm(desc: GemmDesc, A_buf, B_buf, C_buf, stream=None):
     assert A_buf.is_cuda and B_buf.is_cuda and C_buf.is_cuda
     _check(lib().axe_gemm(C.byref(desc.c), A_buf.data_ptr(), B_buf.data_ptr(), C_buf.data_ptr(), _stream_ptr(stream)))
     return C_buf
+
+
+class GroupedGemmDesc:
+    """Holder of an axe_gemm_grouped_desc_t (keeps the three layouts alive).  A: (M, K), B: (G, K, N), Cl: (M, N)."""
+
+    def __init__(self, M: int, N: int, K: int, G: int, A: Layout, B: Layout, Cl: Layout, a_elems: int, b_elems: int,
+                 c_elems: int, in_dtype: int = AXE_BF16, out_dtype: int = AXE_BF16, mem_axis: str = "m"):
+        ma = A.axis(mem_axis)
+        assert B.axis(mem_axis) == ma and Cl.axis(mem_axis) == ma, "memory axis must have the same index in A, B, C"
+        self.layouts = (A, B, Cl)
+        self.c = axe_gemm_grouped_desc_t(M, N, K, G, in_dtype, out_dtype, A.c, B.c, Cl.c, ma, a_elems, b_elems, c_elems)
+
+
+def axe_gemm_grouped(desc: GroupedGemmDesc, A_buf, B_buf, C_buf, group_rows, stream=None):
+    """group_rows: int32 device tensor of G + 1 row offsets."""
+    assert A_buf.is_cuda and B_buf.is_cuda and C_buf.is_cuda and group_rows.is_cuda
+    assert str(group_rows.dtype) == "torch.int32" and group_rows.numel() == desc.c.G + 1 and group_rows.is_contiguous()
+    _check(lib().axe_gemm_grouped(C.byref(desc.c), A_buf.data_ptr(), B_buf.data_ptr(), C_buf.data_ptr(),
+                                  group_rows.data_ptr(), _stream_ptr(stream)))
+    return C_buf
+
+
+def axe_gemm_grouped_check(desc: GroupedGemmDesc) -> None:
+    _check(lib().axe_gemm_grouped_check(C.byref(desc.c)))
 
 
 def axe_gemm_tile(desc: GemmDesc) -> int:

@@ -534,7 +534,135 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   return AXE_OK;
 }
 
+
+// B of a grouped GEMM, logical (G, K, N): grouped by that shape (Alg. 1) every block must reduce to at
+// most one iter on the memory axis -- stride 1 along k, one pitch along n, one stride between groups.
+int grouped_b(const axe_layout_t* L, int mem_axis, int64_t G, int64_t K, int64_t N, int64_t elems, int64_t* ldg,
+              int64_t* ldb, int64_t* offset) {
+  const char* what = "axe_gemm_grouped(B)";
+  HLayout h;
+  if (int rc = load_layout(L, h, what)) return rc;
+  const int64_t shape[3] = {G, K, N};
+  if (int rc = check_shape(h, 3, shape, what)) return rc;
+  MemLayout m;
+  if (int rc = reduce_to_memory(h, mem_axis, m, what)) return rc;
+  if (!m.R.empty() || m.swz.mask) {
+    set_error("%s: replicated or swizzled operands are not supported", what);
+    return AXE_EUNSUPPORTED;
+  }
+  if (int rc = check_range(m, elems, what)) return rc;
+  axe_layout_t grouped;
+  int32_t block_end[3];
+  alignas(16) char arena[2048];
+  if (int rc = axe_layout_group(L, 3, shape, &grouped, block_end, arena, sizeof arena)) return rc;
+  int64_t stride[3] = {0, 0, 0};
+  for (int b = 0, first = 0; b < 3; first = block_end[b++]) {
+    std::vector<HIter> blk;
+    for (int i = first; i < block_end[b]; ++i)
+      if (grouped.d[i].axis == mem_axis) blk.push_back(HIter{grouped.d[i].extent, grouped.d[i].stride, mem_axis});
+    canon_D(blk);                                                  // D0, D1 inside the block
+    if (blk.size() > 1 || (blk.size() == 1 && blk[0].s <= 0)) {
+      set_error("%s: dimension %d is not a single positive stride in memory", what, b);
+      return AXE_EUNSUPPORTED;
+    }
+    stride[b] = blk.empty() ? 0 : blk[0].s;
+  }
+  if (K > 1 && stride[1] != 1) {
+    set_error("%s: each group's matrix must have unit stride along k (column-major)", what);
+    return AXE_EUNSUPPORTED;
+  }
+  *ldb = N > 1 ? stride[2] : K;
+  *ldg = G > 1 ? stride[0] : 0;
+  *offset = m.off;
+  if (*ldb < K) {
+    set_error("%s: pitch %lld below K", what, (long long)*ldb);
+    return AXE_EUNSUPPORTED;
+  }
+  return AXE_OK;
+}
+
+int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const void* dB, void* dC, const int32_t* rows,
+                      GemmArgs& a, bool need_ptrs) {
+  const char* fn = "axe_gemm_grouped";
+  if (!g) {
+    set_error("%s: descriptor is NULL", fn);
+    return AXE_EINVAL;
+  }
+  if (g->M <= 0 || g->N <= 0 || g->K <= 0 || g->G <= 0) {
+    set_error("%s: M, N, K, G must be positive", fn);
+    return AXE_EINVAL;
+  }
+  if (g->in_dtype != AXE_BF16 || g->out_dtype != AXE_BF16) {
+    set_error("%s: bf16 inputs and bf16 output only", fn);
+    return g->in_dtype == AXE_FP8_E4M3 || g->out_dtype == AXE_F32 ? AXE_EUNSUPPORTED : AXE_EINVAL;
+  }
+  int64_t lda, ldb, ldc, ldg, oa, ob, oc;
+  if (int rc = strided_2d(&g->A, g->mem_axis, g->M, g->K, true, g->a_elems, "axe_gemm_grouped(A)", &lda, &oa)) return rc;
+  if (int rc = grouped_b(&g->B, g->mem_axis, g->G, g->K, g->N, g->b_elems, &ldg, &ldb, &ob)) return rc;
+  if (int rc = strided_2d(&g->C, g->mem_axis, g->M, g->N, true, g->c_elems, "axe_gemm_grouped(C)", &ldc, &oc)) return rc;
+  if ((g->K % 8) || (lda % 8) || (ldb % 8) || (ldg % 8) || (oa % 8) || (ob % 8) || (oc % 8) || (ldc % 8)) {
+    set_error("%s: K, leading dimensions, the group stride and offsets must be multiples of 8 elements (16 bytes)", fn);
+    return AXE_EUNSUPPORTED;
+  }
+  if (g->G > 4096 || g->N % 256 || g->N / 256 > 2048 || g->K % 64 || g->M >= (int64_t(1) << 31) ||
+      256 * lda * 2 >= (int64_t(1) << 31) || 256 * ldb * 2 >= (int64_t(1) << 31) || 128 * ldc * 2 >= (int64_t(1) << 31)) {
+    set_error("%s: needs G <= 4096, N a multiple of 256 (at most 2048 tile columns), K a multiple of 64, M < 2^31 and "
+              "row pitches below 2^31 / 256 bytes", fn);
+    return AXE_EUNSUPPORTED;
+  }
+  if ((g->M / 256 + g->G) * (g->N / 256) > (int64_t(1) << 24)) {
+    set_error("%s: too many tiles for one launch", fn);
+    return AXE_EUNSUPPORTED;
+  }
+  if (need_ptrs) {
+    if (!dA || !dB || !dC || !rows) {
+      set_error("%s: NULL device pointer", fn);
+      return AXE_EINVAL;
+    }
+    if ((((uintptr_t)dA | (uintptr_t)dB | (uintptr_t)dC) & 15) || ((uintptr_t)rows & 3)) {
+      set_error("%s: device buffers must be 16-byte aligned (group_rows: 4-byte)", fn);
+      return AXE_EINVAL;
+    }
+    const char* c0 = (const char*)dC;
+    const char* c1 = c0 + g->c_elems * 2;
+    const char* a0 = (const char*)dA;
+    const char* b0 = (const char*)dB;
+    const char* r0 = (const char*)rows;
+    if ((a0 < c1 && c0 < a0 + g->a_elems * 2) || (b0 < c1 && c0 < b0 + g->b_elems * 2) ||
+        (r0 < c1 && c0 < r0 + (g->G + 1) * 4)) {
+      set_error("%s: C overlaps an input buffer", fn);
+      return AXE_EINVAL;
+    }
+  }
+  memset(&a, 0, sizeof a);
+  a.A = (const char*)dA + oa * 2;
+  a.B = (const char*)dB + ob * 2;
+  a.C = (char*)dC + oc * 2;
+  a.M = g->M, a.N = g->N, a.K = g->K;
+  a.lda = lda, a.ldb = ldb, a.ldc = ldc, a.ldg = ldg;
+  a.out_bf16 = 1;
+  a.grid_m = 0;
+  a.grid_n = (int32_t)(g->N / 256);
+  a.tile_n = 256;
+  a.group_rows = rows;
+  a.groups = g->G;
+  return AXE_OK;
+}
+
 }  // namespace
+
+int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const void* d_B, void* d_C,
+                     const int32_t* d_group_rows, void* stream) {
+  GemmArgs a;
+  if (int rc = plan_gemm_grouped(g, d_A, d_B, d_C, d_group_rows, a, true)) return rc;
+  hipError_t e = launch_gemm_bf16_256_grouped(a, (hipStream_t)stream);
+  return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm_grouped");
+}
+
+int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g) {
+  GemmArgs a;
+  return plan_gemm_grouped(g, nullptr, nullptr, nullptr, nullptr, a, false);
+}
 
 int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d_C, void* stream) {
   GemmPlan P;

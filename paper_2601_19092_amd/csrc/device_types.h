@@ -90,6 +90,10 @@ struct GemmArgs {
   int32_t out_bf16;                // 0: fp32 output, 1: bf16 output
   int32_t grid_m, grid_n;          // workgroup tiles along M and N
   int32_t tile_n;                  // columns of C per workgroup tile (64, 224 or 256)
+  // grouped GEMM only: group e owns rows group_rows[e] .. group_rows[e + 1] - 1 of A and C and the matrix B + e * ldg
+  const int32_t* group_rows;       // device, groups + 1 entries
+  int32_t groups;
+  int64_t ldg;
 };
 
 }  // namespace axe

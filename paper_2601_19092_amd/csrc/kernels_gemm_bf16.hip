@@ -55,6 +55,7 @@
 // the arrival of the next tile's operands.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "device_types.h"
@@ -83,10 +84,78 @@ __device__ __forceinline__ void mfma_16x16x32(f32x4& acc, bf16x8 a, bf16x8 b) {
 }
 }  // namespace
 
+// Tiles of a grouped problem, counted group after group: group e has ceil(rows_e / 256) x grid_n of them
+// (columns fastest).  Lane t of the calling wave receives the workgroup's t-th tile: its first row, its
+// number of rows (0: no such tile), its tile column and its group.  Workgroup ids are dealt round-robin
+// to the 8 XCDs, so XCD x takes the x-th eighth of the tile sequence and its 32 workgroups walk it side
+// by side: neighbours in the sequence share A rows (same group and row block) or a B panel in that
+// XCD's L2.  The offsets are clamped to [0, M], so that whatever they hold no access leaves the buffers.
+// t_desc packs rows (bits 0..8), tile column (9..19) and group (20..31): the host admits at most 4096
+// groups and 2048 tile columns.
+__device__ __forceinline__ int desc_rows(int d) { return d & 511; }
+__device__ __forceinline__ int desc_tn(int d) { return (d >> 9) & 2047; }
+__device__ __forceinline__ int desc_group(int d) { return (int)((unsigned)d >> 20); }
+__device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_row0, int& t_desc) {
+  const int G = g.groups, M = (int)g.M, gn = g.grid_n;
+  const int* __restrict__ off = g.group_rows;
+  int r0 = 0, rows = 0, tg = 0, incl = 0;
+  auto chunk = [&](int g0) __attribute__((always_inline)) {         // groups g0 .. g0 + 63, one per lane
+    const int gi = g0 + lane;
+    int a = 0, b = 0;
+    if (gi < G) a = off[gi], b = off[gi + 1];
+    a = a < 0 ? 0 : (a > M ? M : a);
+    b = b < 0 ? 0 : (b > M ? M : b);
+    r0 = a;
+    rows = b > a ? b - a : 0;
+    tg = ((rows + kTile - 1) / kTile) * gn;
+    incl = tg;                                                     // inclusive prefix sum over the lanes
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+      const int o = __shfl_up(incl, d, 64);
+      if (lane >= d) incl += o;
+    }
+  };
+  int total = 0;
+  for (int g0 = 0; g0 < G; g0 += 64) {
+    chunk(g0);
+    total += __builtin_amdgcn_readlane(incl, 63);
+  }
+  const int per = (total + 7) >> 3;                                // tiles per XCD
+  const int s = (int)(blockIdx.x >> 3) + lane * (int)(gridDim.x >> 3);
+  const int u = (int)(blockIdx.x & 7) * per + s;                   // position of this lane's tile in the sequence
+  const bool valid = s < per && u < total;
+  int f_local = 0, f_rows = 0, f_r0 = 0, f_group = 0, base = 0;
+  for (int g0 = 0; g0 < G; g0 += 64) {
+    chunk(g0);
+    const int excl = incl - tg;
+    const int lim = G - g0 < 64 ? G - g0 : 64;
+#pragma unroll 1
+    for (int l = 0; l < lim; ++l) {
+      const int n = __builtin_amdgcn_readlane(tg, l);
+      if (n == 0) continue;
+      const int local = u - base - __builtin_amdgcn_readlane(excl, l);
+      const int lr0 = __builtin_amdgcn_readlane(r0, l), lrows = __builtin_amdgcn_readlane(rows, l);
+      if (valid && local >= 0 && local < n) f_local = local, f_rows = lrows, f_r0 = lr0, f_group = g0 + l;
+    }
+    base += __builtin_amdgcn_readlane(incl, 63);
+  }
+  const int tm = f_local / gn;
+  t_row0 = f_r0 + tm * kTile;
+  const int left = f_rows - tm * kTile;                            // 0 when the lane found no tile
+  t_desc = (left < kTile ? left : kTile) | ((f_local - tm * gn) << 9) | (f_group << 20);
+}
+
 // NB = columns of C per tile (B rows per tile): 256, or 224 = 2 waves x 7 fragments for problems whose
 // tile count then fills the compute units better (B pieces past row 223 are outside the tile's buffer
 // descriptor: they cost no traffic and fill LDS rows nobody reads).
-template <int NB>
+//
+// GROUPED: the grouped GEMM of an MoE layer.  The rows of A and C are sorted by group, group e owns rows
+// group_rows[e] .. group_rows[e + 1] - 1 (device memory: the host does not know them) and multiplies them with
+// its own B.  A tile is (group, 256 rows of that group, 256 columns); the rows a group does not fill are
+// outside the tile's buffer descriptors: they load as zero and their stores are dropped.  Each wave first
+// works out which tiles its workgroup owns (group_tiles below) and keeps them one per lane; the pipeline
+// then runs over them exactly as over the tiles of a dense problem.
+template <int NB, bool GROUPED>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   constexpr int NJ = NB / 32;                                      // fragments per wave along N
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
@@ -109,9 +178,27 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     i32x4 ra_words;                                                // ra once more, as the four SGPR words an asm statement takes
     int rot;
   };
+  int tb_row0 = 0, tb_desc = 0;                                    // grouped: lane t = the workgroup's t-th tile
+  if constexpr (GROUPED) group_tiles(g, lane, tb_row0, tb_desc);
+  auto table_rows = [&](int t) __attribute__((always_inline)) -> int { return t < 64 ? desc_rows(__builtin_amdgcn_readlane(tb_desc, t)) : 0; };
+  // dense: v = tile id; grouped: v = index into the workgroup's table
   auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
     Tile t;
-    if (v < ntiles) {
+    if constexpr (GROUPED) {
+      const int rows = table_rows(v);
+      if (rows > 0) {
+        const int row0 = __builtin_amdgcn_readlane(tb_row0, v), dsc = __builtin_amdgcn_readlane(tb_desc, v);
+        const int grp = desc_group(dsc), tn = desc_tn(dsc);
+        const uint8_t* pa = (const uint8_t*)g.A + (int64_t)row0 * g.lda * 2;
+        t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)pa, 0, (rows - 1) * a_pitch + (int)g.K * 2, 0x00020000);
+        t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + ((int64_t)grp * g.ldg + (int64_t)tn * NB * g.ldb) * 2), 0,
+                                                 (NB - 1) * b_pitch + (int)g.K * 2, 0x00020000);
+        t.rot = ((row0 >> 8) + tn) & (kRot - 1);
+        t.ra_words = raw_rsrc(pa, (uint32_t)((rows - 1) * a_pitch + (int)g.K * 2));
+        return t;
+      }
+    }
+    if (!GROUPED && v < ntiles) {
       int tm, tn;
       tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda * 2), 0,
@@ -132,8 +219,10 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     }
     return t;
   };
-  int v = blockIdx.x;
-  Tile cur = describe(v), nxt = describe(v + (int)gridDim.x);
+  int v = GROUPED ? 0 : (int)blockIdx.x;
+  const int vstep = GROUPED ? 1 : (int)gridDim.x;
+  if (GROUPED && table_rows(0) <= 0) return;                       // more workgroups than tiles (the host sizes the launch for the worst case)
+  Tile cur = describe(v), nxt = describe(v + vstep);
   // K-step T of the current tile (T >= nk: step T - nk of the next one) -> byte column
   auto kcol = [&](int T, int rot) -> int {
     const int t = T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T;
@@ -212,6 +301,16 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   int c_rowblk;                                                    // bytes between fragment rows
   const int c_voff = (int)((fr * g.ldc + 4 * fq) * 2);
   auto set_output = [&](int vv) __attribute__((always_inline)) {
+    if constexpr (GROUPED) {
+      const int row0 = __builtin_amdgcn_readlane(tb_row0, vv), dsc = __builtin_amdgcn_readlane(tb_desc, vv);
+      const int tn = desc_tn(dsc);
+      int rows = desc_rows(dsc) - wm * 128;                          // rows of the tile that fall to this wave
+      rows = rows < 0 ? 0 : (rows > 128 ? 128 : rows);
+      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * 128) * g.ldc + (int64_t)tn * NB + wn * (NB / 2),
+                    rows ? (uint32_t)(((rows - 1) * g.ldc + NB / 2) * 2) : 0u);
+      c_rowblk = (int)(16 * g.ldc * 2);
+      return;
+    }
     int tm, tn;
     tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
     rc = raw_rsrc((uint16_t*)g.C + ((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * NB + wn * (NB / 2),
@@ -367,17 +466,18 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
         }
       }
     }
-    v += (int)gridDim.x;
-    if (v >= ntiles) break;
+    v += vstep;
+    if (GROUPED ? table_rows(v) <= 0 : v >= ntiles) break;
     cur = nxt;
-    nxt = describe(v + (int)gridDim.x);
+    nxt = describe(v + vstep);
   }
 }
 
 // (plain kernels around the template: a __global__ template would be instantiated by the host pass
 //  too, which cannot parse the register constraints of the asm statements)
-__global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) { gemm_bf16_256_body<256>(g); }
-__global__ __launch_bounds__(256, 1) void gemm_bf16_256x224_kernel(GemmArgs g) { gemm_bf16_256_body<224>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) { gemm_bf16_256_body<256, false>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256x224_kernel(GemmArgs g) { gemm_bf16_256_body<224, false>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true>(g); }
 
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -390,6 +490,22 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
     hipLaunchKernelGGL(gemm_bf16_256x224_kernel, dim3(nwg), dim3(256), 0, s, g);
   else
     hipLaunchKernelGGL(gemm_bf16_256_kernel, dim3(nwg), dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+// Grouped: the host does not know the group sizes, only that sum_e ceil(rows_e / 256) <= M / 256 + groups.
+// One workgroup per CU walks its tiles when the pipeline can continue across tiles (a wave keeps at
+// most 64 tiles, one per lane: beyond 64 x CUs tiles in the worst case more workgroups are launched);
+// otherwise one workgroup per possible tile, those without a tile leave at once.
+hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
+  const int64_t worst = (g.M / kTile + g.groups) * (int64_t)g.grid_n;
+  const int nk = (int)(g.K / 64);
+  const int cus = cu_count();
+  const bool chain = (nk % 2 == 0) && nk >= 4;
+  int64_t nwg = chain ? std::max<int64_t>(cus, (worst + 63) / 64) : worst;
+  nwg = (nwg + 7) / 8 * 8;                                         // the tile sequence is cut into 8 parts, one per XCD
+  if (nwg > 0x7fffffff) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(gemm_bf16_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 

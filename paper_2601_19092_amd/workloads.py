@@ -214,3 +214,16 @@ def gemm_specs(g: "GemmInputs", device_axis: bool = False, shard: int = 0) -> Tu
     else:
         B = col_major_spec(g.K, g.N)
     return A, B, C
+
+
+def grouped_gemm_specs(g: "GroupedGemmInputs", lda: Optional[int] = None, ldb: Optional[int] = None,
+                       ldg: Optional[int] = None, ldc: Optional[int] = None) -> Tuple[dict, dict, dict]:
+    """Layout specs of a grouped GEMM's operands: A (M, K) and C (M, N) row-major, B (G, K, N) with each
+    group's matrix column-major; optional pitches in elements."""
+    lda = g.K if lda is None else lda
+    ldb = g.K if ldb is None else ldb
+    ldg = g.N * ldb if ldg is None else ldg
+    ldc = g.N if ldc is None else ldc
+    return (spec([(g.M, lda, "m"), (g.K, 1, "m")]),
+            spec([(g.G, ldg, "m"), (g.K, 1, "m"), (g.N, ldb, "m")]),
+            spec([(g.M, ldc, "m"), (g.N, 1, "m")]))

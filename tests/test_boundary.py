@@ -146,6 +146,41 @@ def test_gemm_family_matching_and_errors():
     assert B.lib().axe_gemm(C.byref(d.c), None, None, None, None) == B.AXE_EINVAL
 
 
+def _grouped_desc(M=1000, N=512, K=256, G=4, A=None, Bs=None, Cs=None, in_dtype=B.AXE_BF16, out_dtype=B.AXE_BF16,
+                  b_elems=None):
+    A = A or W.row_major_spec(M, K)
+    Bs = Bs or W.spec([(G, N * K, "m"), (K, 1, "m"), (N, K, "m")])
+    Cs = Cs or W.row_major_spec(M, N)
+    return B.GroupedGemmDesc(M, N, K, G, B.Layout(A), B.Layout(Bs), B.Layout(Cs), M * K + 64,
+                             b_elems if b_elems is not None else 2 * G * N * K, M * N + 64, in_dtype, out_dtype)
+
+
+def test_grouped_gemm_family_matching_and_errors():
+    chk = lambda d: B.lib().axe_gemm_grouped_check(C.byref(d.c))
+    assert chk(_grouped_desc()) == B.AXE_OK
+    assert chk(_grouped_desc(M=7)) == B.AXE_OK                                          # M is free: ragged groups are the point
+    # contiguous groups fuse with the column digit under rule D1; the grouped form (Alg. 1) still has one iter per block
+    assert chk(_grouped_desc(G=1)) == B.AXE_OK
+    # pitched B: rows of K + 8, groups 64 elements apart from dense packing
+    assert chk(_grouped_desc(Bs=W.spec([(4, 512 * 264 + 64, "m"), (256, 1, "m"), (512, 264, "m")]))) == B.AXE_OK
+    # groups stored in two banks: no single stride between groups
+    two = W.spec([(2, 10 ** 6, "m"), (2, 512 * 256, "m"), (256, 1, "m"), (512, 256, "m")])
+    assert chk(_grouped_desc(Bs=two, b_elems=4 * 10 ** 6)) == B.AXE_EUNSUPPORTED
+    # each B[e] row-major (unit stride along n) is outside the family
+    assert chk(_grouped_desc(Bs=W.spec([(4, 512 * 256, "m"), (256, 512, "m"), (512, 1, "m")]))) == B.AXE_EUNSUPPORTED
+    assert chk(_grouped_desc(N=500, Bs=W.spec([(4, 500 * 256, "m"), (256, 1, "m"), (500, 256, "m")]))) == B.AXE_EUNSUPPORTED
+    assert chk(_grouped_desc(K=96, A=W.row_major_spec(1000, 96), Bs=W.spec([(4, 512 * 96, "m"), (96, 1, "m"), (512, 96, "m")]))) \
+        == B.AXE_EUNSUPPORTED
+    assert chk(_grouped_desc(in_dtype=B.AXE_FP8_E4M3)) == B.AXE_EUNSUPPORTED
+    assert chk(_grouped_desc(out_dtype=B.AXE_F32)) == B.AXE_EUNSUPPORTED
+    assert chk(_grouped_desc(in_dtype=9)) == B.AXE_EINVAL
+    assert chk(_grouped_desc(G=0, Bs=W.spec([(1, 1, "m"), (256, 1, "m"), (512, 256, "m")]))) == B.AXE_EINVAL
+    assert chk(_grouped_desc(A=W.row_major_spec(1000, 128))) == B.AXE_ESHAPE
+    assert chk(_grouped_desc(b_elems=1000)) == B.AXE_ERANGE
+    d = _grouped_desc()
+    assert B.lib().axe_gemm_grouped(C.byref(d.c), None, None, None, None, None) == B.AXE_EINVAL
+
+
 def test_python_binding_raises_axe_error():
     with pytest.raises(B.AxeError) as e:
         B._check(B.AXE_EALIAS)

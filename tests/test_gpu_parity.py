@@ -533,3 +533,126 @@ def test_gemm_is_bitwise_repeatable(which):
             first = dC.clone()
         else:
             assert torch.equal(first, dC), f"launch {it} differs from launch 0 in {(first != dC).sum().item()} elements"
+
+
+# ----------------------------------------------------------------------------- grouped GEMM (MoE)
+SENTINEL = 0x7FC1          # a bf16 NaN pattern: rows of C that belong to no group must keep it
+
+
+def run_grouped(g: W.GroupedGemmInputs, lda=None, ldb=None, ldg=None, ldc=None, rows_on_device=None):
+    """Launches axe_gemm_grouped; returns (C decoded to fp64, raw C words), both (M, N)."""
+    lda_, ldb_, ldc_ = lda or g.K, ldb or g.K, ldc or g.N
+    ldg_ = ldg or g.N * ldb_
+    As, Bs, Cs = W.grouped_gemm_specs(g, lda_, ldb_, ldg_, ldc_)
+    a = np.zeros((g.M, lda_), dtype=np.uint16); a[:, :g.K] = g.a_mk
+    b = np.zeros((g.G, ldg_), dtype=np.uint16)
+    bv = np.zeros((g.G, g.N, ldb_), dtype=np.uint16); bv[:, :, :g.K] = g.b_gnk
+    b[:, :g.N * ldb_] = bv.reshape(g.G, -1)
+    dA, dB = dev(a.reshape(-1)), dev(b.reshape(-1))
+    dC = torch.full((g.M * ldc_,), SENTINEL, dtype=torch.int16, device="cuda")
+    dR = torch.from_numpy(np.ascontiguousarray(g.group_rows if rows_on_device is None else rows_on_device, dtype=np.int32)).cuda()
+    desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(Bs), B.Layout(Cs), a.size, b.size, g.M * ldc_)
+    B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+    torch.cuda.synchronize()
+    raw = dC.cpu().numpy().view(np.uint16).reshape(g.M, ldc_)
+    if ldc_ > g.N:
+        assert (raw[:, g.N:] == SENTINEL).all(), "the padding of C was written"
+    raw = raw[:, :g.N]
+    return R.bf16_to_f64(raw), raw
+
+
+def check_grouped(g: W.GroupedGemmInputs, c, raw, ref):
+    """ref: the oracle's (M, N) with NaN rows where no group owns the row."""
+    owned = ~np.isnan(ref[:, 0])
+    assert (raw[~owned] == SENTINEL).all(), "a row outside every group was written"
+    assert np.isfinite(c[owned]).all()
+    if not owned.any():
+        return
+    assert R.rel_frobenius(c[owned], ref[owned]) <= BF16_TOL
+    off = g.group_rows
+    for e in range(g.G):                                   # every group, every 128-column block: no tile can hide
+        if off[e + 1] > off[e]:
+            for j in range(0, g.N, 128):
+                blk = (slice(off[e], off[e + 1]), slice(j, j + 128))
+                err = R.rel_frobenius(c[blk], ref[blk])
+                assert err <= BF16_TOL, f"group {e} columns {j}: {err:.3e}"
+
+
+GROUPED_CASES = [
+    # (group_rows, N, K, M)   M None = group_rows[-1]
+    ([0, 256], 256, 64, None),                             # one full tile, one K-step
+    ([0, 1], 256, 128, None),                              # a single row
+    ([0, 100, 100, 357, 400], 512, 192, None),             # an empty group, ragged sizes, odd number of K-steps
+    ([3, 130, 700, 701], 256, 256, 720),                   # rows below the first and above the last group stay untouched
+    ([0, 0, 0], 256, 64, 8),                               # nothing to do at all
+    ([0, 300, 520, 1300, 1301, 2000], 768, 512, None),     # chained launch (8 K-steps), several tiles per group
+]
+
+
+@pytest.mark.parametrize("off,N,K,M", GROUPED_CASES)
+def test_gemm_grouped_small_cases(off, N, K, M):
+    g = W.gemm_grouped_bf16(off, N, K, 77, M=M)
+    c, raw = run_grouped(g)
+    ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16)
+    check_grouped(g, c, raw, ref)
+
+
+def test_gemm_grouped_pitched_operands_and_many_groups():
+    rng = np.random.default_rng(5)
+    sizes = rng.integers(0, 90, 150)                       # 150 groups: three 64-group chunks in the kernel's tile search
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    g = W.gemm_grouped_bf16(off, 256, 128, 78)
+    c, raw = run_grouped(g, lda=136, ldb=144, ldg=256 * 144 + 64, ldc=264)
+    ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16)
+    check_grouped(g, c, raw, ref)
+
+
+def test_gemm_grouped_offsets_out_of_range_are_clamped():
+    """Whatever the device-side offsets hold, nothing outside the buffers is touched: entries are clamped to
+    [0, M].  With clamped values that still increase, the result is that of the clamped offsets."""
+    off_dev = [-5, 100, 300, 10 ** 6]
+    off_eff = [0, 100, 300, 400]
+    g = W.gemm_grouped_bf16(off_eff, 256, 128, 79)
+    c, raw = run_grouped(g, rows_on_device=off_dev)
+    ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off_eff, R.AXE_BF16)
+    check_grouped(g, c, raw, ref)
+
+
+@pytest.mark.parametrize("which", ["gemm1", "gemm2"])
+def test_gemm_grouped_moe_layer_shapes_full_size(which):
+    """The two grouped GEMMs of the MoE layer at 4096 tokens (32768 routed rows, 128 experts), in the launch
+    configuration the benchmark times; the oracle computes sampled groups' 128-column blocks, rows at group
+    borders, and randomised projections over every group."""
+    g = (W.moe_gemm1 if which == "gemm1" else W.moe_gemm2)(4096)
+    c, raw = run_grouped(g)
+    assert np.isfinite(c).all()
+    off = g.group_rows
+    bl = g.b_gnk.transpose(0, 2, 1)
+    rng = np.random.default_rng(11)
+    sizes = np.diff(off)
+    picks = {int(np.argmax(sizes)), int(np.argmin(sizes)), 0, g.G - 1} | {int(x) for x in rng.integers(0, g.G, 4)}
+    for e in sorted(picks):
+        if sizes[e] == 0:
+            continue
+        rows = np.arange(off[e], off[e + 1])
+        j = int(rng.integers(g.N // 128)) * 128
+        cols = np.arange(j, j + 128)
+        ref = R.gemm_ref(g.a_mk, bl[e], R.AXE_BF16, rows=rows, cols=cols)
+        err = R.rel_frobenius(c[np.ix_(rows, cols)], ref)
+        assert err <= BF16_TOL, f"group {e} columns {j}: {err:.3e}"
+    # the first and last row of every group, all columns
+    edge = np.unique(np.concatenate([off[:-1][sizes > 0], off[1:][sizes > 0] - 1]))
+    ref = R.gemm_grouped_ref(g.a_mk, bl, off, R.AXE_BF16, rows=edge)
+    assert R.rel_frobenius(c[edge], ref) <= BF16_TOL
+    # projections: per group C_e v = A_e (B_e v) in fp64, every group and every 256-row block of it
+    A = R.decode(g.a_mk, R.AXE_BF16)
+    v = rng.choice([-1.0, 1.0], g.N)
+    y = c @ v
+    for e in range(g.G):
+        if sizes[e] == 0:
+            continue
+        Be = R.decode(np.ascontiguousarray(g.b_gnk[e]), R.AXE_BF16)        # (N, K)
+        y_ref = A[off[e]:off[e + 1]] @ (Be.T @ v)
+        for r0 in range(off[e], off[e + 1], 256):
+            r1 = min(r0 + 256, off[e + 1])
+            assert np.linalg.norm(y[r0:r1] - y_ref[r0 - off[e]:r1 - off[e]]) <= BF16_TOL * np.linalg.norm(c[r0:r1]), (e, r0)
