@@ -406,6 +406,66 @@ int strided_2d(const axe_layout_t* L, int mem_axis, int64_t d0, int64_t d1, bool
   return AXE_OK;
 }
 
+
+// An input operand that is not a plain pitched matrix may still be a blocked one (Sec. 3.3: a tile product
+// of a grid of blocks and a block): grouped by its logical shape (Alg. 1), the k block is
+// [(K / 64, kt_stride), (64, 1)] (64-wide K-tiles stored kt_stride elements apart) and / or the row block is
+// [(R / rb, rb_stride), (rb, pitch)].  kt_stride = 0 / rb = 0 in the result mean "not split".
+struct Operand2D {
+  int64_t pitch, off, kt_stride, rb, rb_stride;
+};
+
+int blocked_2d(const axe_layout_t* L, int mem_axis, int64_t d0, int64_t d1, bool k_is_dim1, int64_t elems, const char* what,
+               Operand2D* out) {
+  HLayout h;
+  if (int rc = load_layout(L, h, what)) return rc;
+  const int64_t shape[2] = {d0, d1};
+  if (int rc = check_shape(h, 2, shape, what)) return rc;
+  MemLayout m;
+  if (int rc = reduce_to_memory(h, mem_axis, m, what)) return rc;
+  if (!m.R.empty() || m.swz.mask) {
+    set_error("%s: replicated or swizzled GEMM operands are not supported", what);
+    return AXE_EUNSUPPORTED;
+  }
+  if (int rc = check_range(m, elems, what)) return rc;
+  axe_layout_t grouped;
+  int32_t block_end[2];
+  alignas(16) char arena[2048];
+  if (int rc = axe_layout_group(L, 2, shape, &grouped, block_end, arena, sizeof arena)) return rc;
+  std::vector<HIter> blk[2];
+  for (int b = 0, first = 0; b < 2; first = block_end[b++]) {
+    for (int i = first; i < block_end[b]; ++i)
+      if (grouped.d[i].axis == mem_axis) blk[b].push_back(HIter{grouped.d[i].extent, grouped.d[i].stride, mem_axis});
+    canon_D(blk[b]);
+    for (const HIter& it : blk[b])
+      if (it.s <= 0) {
+        set_error("%s: negative strides are not supported", what);
+        return AXE_EUNSUPPORTED;
+      }
+  }
+  const std::vector<HIter>& kb = blk[k_is_dim1 ? 1 : 0];
+  const std::vector<HIter>& rb = blk[k_is_dim1 ? 0 : 1];
+  const int64_t K = k_is_dim1 ? d1 : d0, Rn = k_is_dim1 ? d0 : d1;
+  Operand2D o = {0, m.off, 0, 0, 0};
+  bool ok = true;
+  if (kb.empty()) ok = K == 1;
+  else if (kb.size() == 1) ok = kb[0].s == 1 && kb[0].e == K;
+  else if (kb.size() == 2) ok = kb[1].s == 1 && kb[1].e == 64 && kb[0].e * 64 == K, o.kt_stride = kb[0].s;
+  else ok = false;
+  if (rb.empty()) o.pitch = K;
+  else if (rb.size() == 1) o.pitch = rb[0].s;
+  else if (rb.size() == 2) o.pitch = rb[1].s, o.rb = rb[1].e, o.rb_stride = rb[0].s;
+  else ok = false;
+  if (ok && rb.size() == 1 && rb[0].e != Rn) ok = false;
+  if (!ok || o.pitch < (o.kt_stride ? 64 : K)) {
+    set_error("%s: layout is neither a pitched matrix with unit stride along k nor a blocked one "
+              "((K/64, s)(64, 1) along k, (R/rb, S)(rb, pitch) along the other dimension)", what);
+    return AXE_EUNSUPPORTED;
+  }
+  *out = o;
+  return AXE_OK;
+}
+
 int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC, GemmPlan& P, bool need_ptrs) {
   if (!g) {
     set_error("axe_gemm: descriptor is NULL");
@@ -442,9 +502,18 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
     return AXE_EUNSUPPORTED;
   }
   int64_t lda, ldb, ldc, oa, ob_, oc;
-  if (int rc = strided_2d(&g->A, g->mem_axis, g->M, g->K, true, g->a_elems, "axe_gemm(A)", &lda, &oa)) return rc;
-  if (int rc = strided_2d(&g->B, g->mem_axis, g->K, g->N, false, g->b_elems, "axe_gemm(B)", &ldb, &ob_)) return rc;
+  Operand2D opa, opb;
+  if (int rc = blocked_2d(&g->A, g->mem_axis, g->M, g->K, true, g->a_elems, "axe_gemm(A)", &opa)) return rc;
+  if (int rc = blocked_2d(&g->B, g->mem_axis, g->K, g->N, false, g->b_elems, "axe_gemm(B)", &opb)) return rc;
   if (int rc = strided_2d(&g->C, g->mem_axis, g->M, g->N, true, g->c_elems, "axe_gemm(C)", &ldc, &oc)) return rc;
+  lda = opa.pitch, ldb = opb.pitch, oa = opa.off, ob_ = opb.off;
+  // blocked operands: the 256-tile bf16 kernel only, row blocks a power-of-two number of tiles high
+  const bool blocked = opa.kt_stride || opa.rb || opb.kt_stride || opb.rb;
+  auto block_ok = [&](const Operand2D& o) {
+    if (o.rb && (o.rb % 256 || !is_pow2(o.rb / 256) || o.rb_stride % 8)) return false;
+    if (o.kt_stride && (o.kt_stride % 8 || (g->K / 64) * o.kt_stride * 2 >= (int64_t(1) << 30))) return false;
+    return true;
+  };
   const int64_t vec = 16 / eb;
   if ((g->K % vec) || (lda % vec) || (ldb % vec) || (oa % vec) || (ob_ % vec)) {
     set_error("axe_gemm: K, leading dimensions and offsets of A and B must be multiples of %lld elements (16 bytes)",
@@ -497,6 +566,14 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   // bf16 only: 224 columns per tile (7 fragments per wave instead of 8)
   const bool n224_ok = big_common && !fp8 && (g->N % 224 == 0);
   int tile = g->tile_hint;
+  if (blocked) {
+    if (fp8 || !big_ok || !block_ok(opa) || !block_ok(opb) || (tile != AXE_TILE_AUTO && tile != AXE_TILE_256x256x64)) {
+      set_error("axe_gemm: blocked operands need the bf16 256x256 tile (M, N multiples of 256, K of 64, bf16 output), "
+                "row blocks of 256 x 2^n rows and strides that are multiples of 16 bytes");
+      return AXE_EUNSUPPORTED;
+    }
+    tile = AXE_TILE_256x256x64;
+  }
   if (tile == AXE_TILE_AUTO) {
     tile = big_ok ? AXE_TILE_256x256x64 : (n224_ok ? AXE_TILE_256x224x64 : AXE_TILE_64x64x32);
     if (big_ok && n224_ok) {
@@ -527,6 +604,12 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   P.args.grid_m = (int32_t)((g->M + bm - 1) / bm);
   P.args.grid_n = (int32_t)((g->N + bn - 1) / bn);
   P.args.tile_n = (int32_t)bn;
+  P.args.a_kstep = (int32_t)(opa.kt_stride ? opa.kt_stride * eb : 64 * eb);
+  P.args.b_kstep = (int32_t)(opb.kt_stride ? opb.kt_stride * eb : 64 * eb);
+  P.args.a_tpb_shift = opa.rb ? ilog2(opa.rb / 256) : 0;
+  P.args.b_tpb_shift = opb.rb ? ilog2(opb.rb / 256) : 0;
+  P.args.a_blk_stride = opa.rb ? opa.rb_stride : bm * lda;
+  P.args.b_blk_stride = opb.rb ? opb.rb_stride : bn * ldb;
   if (P.args.grid_m > 65535) {
     set_error("axe_gemm: M too large for one launch");
     return AXE_EUNSUPPORTED;
@@ -535,10 +618,11 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
 }
 
 
-// B of a grouped GEMM, logical (G, K, N): grouped by that shape (Alg. 1) every block must reduce to at
-// most one iter on the memory axis -- stride 1 along k, one pitch along n, one stride between groups.
+// B of a grouped GEMM, logical (G, K, N): grouped by that shape (Alg. 1) the group block must be one iter
+// on the memory axis (one stride between groups); the k and n blocks are those of a pitched or blocked
+// matrix (blocked_2d above).
 int grouped_b(const axe_layout_t* L, int mem_axis, int64_t G, int64_t K, int64_t N, int64_t elems, int64_t* ldg,
-              int64_t* ldb, int64_t* offset) {
+              Operand2D* out) {
   const char* what = "axe_gemm_grouped(B)";
   HLayout h;
   if (int rc = load_layout(L, h, what)) return rc;
@@ -555,29 +639,39 @@ int grouped_b(const axe_layout_t* L, int mem_axis, int64_t G, int64_t K, int64_t
   int32_t block_end[3];
   alignas(16) char arena[2048];
   if (int rc = axe_layout_group(L, 3, shape, &grouped, block_end, arena, sizeof arena)) return rc;
-  int64_t stride[3] = {0, 0, 0};
+  std::vector<HIter> blk[3];
   for (int b = 0, first = 0; b < 3; first = block_end[b++]) {
-    std::vector<HIter> blk;
     for (int i = first; i < block_end[b]; ++i)
-      if (grouped.d[i].axis == mem_axis) blk.push_back(HIter{grouped.d[i].extent, grouped.d[i].stride, mem_axis});
-    canon_D(blk);                                                  // D0, D1 inside the block
-    if (blk.size() > 1 || (blk.size() == 1 && blk[0].s <= 0)) {
-      set_error("%s: dimension %d is not a single positive stride in memory", what, b);
-      return AXE_EUNSUPPORTED;
-    }
-    stride[b] = blk.empty() ? 0 : blk[0].s;
+      if (grouped.d[i].axis == mem_axis) blk[b].push_back(HIter{grouped.d[i].extent, grouped.d[i].stride, mem_axis});
+    canon_D(blk[b]);                                               // D0, D1 inside the block
+    for (const HIter& it : blk[b])
+      if (it.s <= 0) {
+        set_error("%s: negative strides are not supported", what);
+        return AXE_EUNSUPPORTED;
+      }
   }
-  if (K > 1 && stride[1] != 1) {
-    set_error("%s: each group's matrix must have unit stride along k (column-major)", what);
+  if (blk[0].size() > 1) {
+    set_error("%s: the groups are not a single stride apart", what);
     return AXE_EUNSUPPORTED;
   }
-  *ldb = N > 1 ? stride[2] : K;
-  *ldg = G > 1 ? stride[0] : 0;
-  *offset = m.off;
-  if (*ldb < K) {
-    set_error("%s: pitch %lld below K", what, (long long)*ldb);
+  *ldg = blk[0].empty() ? 0 : blk[0][0].s;
+  Operand2D o = {0, m.off, 0, 0, 0};
+  const std::vector<HIter>&kb = blk[1], &nb = blk[2];
+  bool ok = true;
+  if (kb.empty()) ok = K == 1;
+  else if (kb.size() == 1) ok = kb[0].s == 1;
+  else if (kb.size() == 2) ok = kb[1].s == 1 && kb[1].e == 64, o.kt_stride = kb[0].s;
+  else ok = false;
+  if (nb.empty()) o.pitch = K;
+  else if (nb.size() == 1) o.pitch = nb[0].s;
+  else if (nb.size() == 2) o.pitch = nb[1].s, o.rb = nb[1].e, o.rb_stride = nb[0].s;
+  else ok = false;
+  if (!ok || o.pitch < (o.kt_stride ? 64 : K)) {
+    set_error("%s: each group's matrix must be column-major (unit stride along k) or blocked "
+              "((K/64, s)(64, 1) along k, (N/rb, S)(rb, pitch) along n)", what);
     return AXE_EUNSUPPORTED;
   }
+  *out = o;
   return AXE_OK;
 }
 
@@ -597,8 +691,15 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     return g->in_dtype == AXE_FP8_E4M3 || g->out_dtype == AXE_F32 ? AXE_EUNSUPPORTED : AXE_EINVAL;
   }
   int64_t lda, ldb, ldc, ldg, oa, ob, oc;
+  Operand2D opb;
   if (int rc = strided_2d(&g->A, g->mem_axis, g->M, g->K, true, g->a_elems, "axe_gemm_grouped(A)", &lda, &oa)) return rc;
-  if (int rc = grouped_b(&g->B, g->mem_axis, g->G, g->K, g->N, g->b_elems, &ldg, &ldb, &ob)) return rc;
+  if (int rc = grouped_b(&g->B, g->mem_axis, g->G, g->K, g->N, g->b_elems, &ldg, &opb)) return rc;
+  ldb = opb.pitch, ob = opb.off;
+  if ((opb.rb && (opb.rb % 256 || !is_pow2(opb.rb / 256) || opb.rb_stride % 8)) ||
+      (opb.kt_stride && (opb.kt_stride % 8 || (g->K / 64) * opb.kt_stride * 2 >= (int64_t(1) << 30)))) {
+    set_error("%s: a blocked B needs row blocks of 256 x 2^n columns of C and strides that are multiples of 16 bytes", fn);
+    return AXE_EUNSUPPORTED;
+  }
   if (int rc = strided_2d(&g->C, g->mem_axis, g->M, g->N, true, g->c_elems, "axe_gemm_grouped(C)", &ldc, &oc)) return rc;
   if ((g->K % 8) || (lda % 8) || (ldb % 8) || (ldg % 8) || (oa % 8) || (ob % 8) || (oc % 8) || (ldc % 8)) {
     set_error("%s: K, leading dimensions, the group stride and offsets must be multiples of 8 elements (16 bytes)", fn);
@@ -644,6 +745,11 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
   a.grid_m = 0;
   a.grid_n = (int32_t)(g->N / 256);
   a.tile_n = 256;
+  a.a_kstep = 128;
+  a.b_kstep = (int32_t)(opb.kt_stride ? opb.kt_stride * 2 : 128);
+  a.b_tpb_shift = opb.rb ? ilog2(opb.rb / 256) : 0;
+  a.a_blk_stride = 256 * lda;
+  a.b_blk_stride = opb.rb ? opb.rb_stride : 256 * ldb;
   a.group_rows = rows;
   a.groups = g->G;
   return AXE_OK;

@@ -90,6 +90,11 @@ struct GemmArgs {
   int32_t out_bf16;                // 0: fp32 output, 1: bf16 output
   int32_t grid_m, grid_n;          // workgroup tiles along M and N
   int32_t tile_n;                  // columns of C per workgroup tile (64, 224 or 256)
+  // 256-tile bf16 kernel: operands pre-tiled along K / blocked along rows (plain matrix: kstep 128, shift 0,
+  // blk_stride = tile rows x pitch)
+  int32_t a_kstep, b_kstep;        // bytes between consecutive 64-wide K-tiles of one row
+  int32_t a_tpb_shift, b_tpb_shift;  // log2(tiles per row block)
+  int64_t a_blk_stride, b_blk_stride;  // elements between row blocks
   // grouped GEMM only: group e owns rows group_rows[e] .. group_rows[e + 1] - 1 of A and C and the matrix B + e * ldg
   const int32_t* group_rows;       // device, groups + 1 entries
   int32_t groups;

@@ -155,7 +155,10 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 // outside the tile's buffer descriptors: they load as zero and their stores are dropped.  Each wave first
 // works out which tiles its workgroup owns (group_tiles below) and keeps them one per lane; the pipeline
 // then runs over them exactly as over the tiles of a dense problem.
-template <int NB, bool GROUPED>
+//
+// BLOCKED: the operands may be stored in blocks (see a_kstep below); without it the scalar offsets are
+// the constants of a plain pitched matrix.
+template <int NB, bool GROUPED, bool BLOCKED>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   constexpr int NJ = NB / 32;                                      // fragments per wave along N
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
@@ -173,6 +176,21 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   //      pipeline runs two to four K-steps ahead of the MFMAs and crosses into the next tile before
   //      the current one is finished, so two tiles are described at any time: cur and nxt.
   const int a_pitch = (int)(g.lda * 2), b_pitch = (int)(g.ldb * 2);
+  // Operands may be stored pre-tiled along K and blocked along their rows (Sec. 3.3: a blocked layout is a
+  // tile product): element (row, k) sits at  (row / rb) * blk_stride + (row % rb) * pitch + (k / 64) * kstep
+  // + k % 64  with rb a power-of-two multiple of the tile height.  The plain pitched matrix is kstep = 64,
+  // blk_stride = rb * pitch.  All that changes here are scalar offsets: of a tile's first row, and between
+  // K-tiles; with 256 x 64 blocks stored contiguously every K-step of a tile reads 32 contiguous KiB.
+  const int a_kstep = BLOCKED ? g.a_kstep : kRow, b_kstep = BLOCKED ? g.b_kstep : kRow;   // bytes between K-tiles
+  const int a_span = (nk - 1) * a_kstep + kRow, b_span = (nk - 1) * b_kstep + kRow;   // bytes a row of a tile reaches over
+  auto a_tile_off = [&](int tm) -> int64_t {                       // elements
+    if (!BLOCKED) return (int64_t)tm * kTile * g.lda;
+    return (int64_t)(tm >> g.a_tpb_shift) * g.a_blk_stride + (int64_t)(tm & ((1 << g.a_tpb_shift) - 1)) * kTile * g.lda;
+  };
+  auto b_tile_off = [&](int tn) -> int64_t {
+    if (!BLOCKED) return (int64_t)tn * NB * g.ldb;
+    return (int64_t)(tn >> g.b_tpb_shift) * g.b_blk_stride + (int64_t)(tn & ((1 << g.b_tpb_shift) - 1)) * NB * g.ldb;
+  };
   struct Tile {
     __amdgpu_buffer_rsrc_t ra, rb;
     i32x4 ra_words;                                                // ra once more, as the four SGPR words an asm statement takes
@@ -190,27 +208,25 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
         const int row0 = __builtin_amdgcn_readlane(tb_row0, v), dsc = __builtin_amdgcn_readlane(tb_desc, v);
         const int grp = desc_group(dsc), tn = desc_tn(dsc);
         const uint8_t* pa = (const uint8_t*)g.A + (int64_t)row0 * g.lda * 2;
-        t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)pa, 0, (rows - 1) * a_pitch + (int)g.K * 2, 0x00020000);
-        t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + ((int64_t)grp * g.ldg + (int64_t)tn * NB * g.ldb) * 2), 0,
-                                                 (NB - 1) * b_pitch + (int)g.K * 2, 0x00020000);
+        t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)pa, 0, (rows - 1) * a_pitch + a_span, 0x00020000);
+        t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + ((int64_t)grp * g.ldg + b_tile_off(tn)) * 2), 0,
+                                                 (NB - 1) * b_pitch + b_span, 0x00020000);
         t.rot = ((row0 >> 8) + tn) & (kRot - 1);
-        t.ra_words = raw_rsrc(pa, (uint32_t)((rows - 1) * a_pitch + (int)g.K * 2));
+        t.ra_words = raw_rsrc(pa, (uint32_t)((rows - 1) * a_pitch + a_span));
         return t;
       }
     }
     if (!GROUPED && v < ntiles) {
       int tm, tn;
       tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
-      t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda * 2), 0,
-                                               255 * a_pitch + (int)g.K * 2, 0x00020000);
-      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * NB * g.ldb * 2), 0,
-                                               (NB - 1) * b_pitch + (int)g.K * 2, 0x00020000);
+      t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + a_tile_off(tm) * 2), 0, 255 * a_pitch + a_span, 0x00020000);
+      t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + b_tile_off(tn) * 2), 0, (NB - 1) * b_pitch + b_span, 0x00020000);
       // K rotation: each workgroup walks every aligned window of kRot K-tiles in its own rotated order
       // (the sum over k does not care), so that the workgroups sharing a panel fetch the kRot adjacent
       // lines of a row at once -- one 1 KiB burst per row -- and find the other lines in L2 during the
       // rest of the window (measured on the bare load stream: 16 -> 21.5 TB/s).
       t.rot = (tm + tn) & (kRot - 1);
-      t.ra_words = raw_rsrc((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda * 2, (uint32_t)(255 * a_pitch + (int)g.K * 2));
+      t.ra_words = raw_rsrc((const uint8_t*)g.A + a_tile_off(tm) * 2, (uint32_t)(255 * a_pitch + a_span));
     } else {                                                       // no such tile: every load returns zero
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
@@ -223,10 +239,9 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   const int vstep = GROUPED ? 1 : (int)gridDim.x;
   if (GROUPED && table_rows(0) <= 0) return;                       // more workgroups than tiles (the host sizes the launch for the worst case)
   Tile cur = describe(v), nxt = describe(v + vstep);
-  // K-step T of the current tile (T >= nk: step T - nk of the next one) -> byte column
+  // K-step T of the current tile (T >= nk: step T - nk of the next one) -> K-tile
   auto kcol = [&](int T, int rot) -> int {
-    const int t = T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T;
-    return t * kRow;
+    return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T;
   };
 
   // ---- HBM -> LDS.  Per K-tile and operand 32 wave instructions of 8 rows; wave w issues pieces
@@ -249,7 +264,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   auto a_load = [&](int T, int i, bool cross) __attribute__((always_inline)) -> u32x4 {
     const bool nx = cross && T >= nk;
     const i32x4 r = nx ? nxt.ra_words : cur.ra_words;
-    const int soff = __builtin_amdgcn_readfirstlane(i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)));
+    const int soff = __builtin_amdgcn_readfirstlane(i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep);
     u32x4 v;
     asm volatile("s_nop 4\n\tbuffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
     return v;
@@ -259,14 +274,14 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   };
   auto a_direct = [&](int T, int i, int stage) {                   // prologue only
     __builtin_amdgcn_raw_ptr_buffer_load_lds(cur.ra, (lds_ptr)(lds3 + stage * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                             i * a_piece + kcol(T, cur.rot), 0, 0);
+                                             i * a_piece + kcol(T, cur.rot) * a_kstep, 0, 0);
   };
   // B ring: byte offsets of the blocks that hold K-steps kt, kt+1, kt+2 (step kt+3 reuses the first)
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16,
-                                             b_voff, i * b_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)), 0, 0);
+                                             b_voff, i * b_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * b_kstep, 0, 0);
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16
@@ -414,7 +429,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
 #pragma unroll
     for (int i = 0; i < 4; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(nxt.ra, (lds_ptr)(lds3 + kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                               i * a_piece + kcol(0, nxt.rot), 0, 0);
+                                               i * a_piece + kcol(0, nxt.rot) * a_kstep, 0, 0);
   }
 #pragma unroll
   for (int i = 4; i < 8; ++i) stg[8 + i] = a_load(1, i, true);
@@ -475,9 +490,10 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
 
 // (plain kernels around the template: a __global__ template would be instantiated by the host pass
 //  too, which cannot parse the register constraints of the asm statements)
-__global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) { gemm_bf16_256_body<256, false>(g); }
-__global__ __launch_bounds__(256, 1) void gemm_bf16_256x224_kernel(GemmArgs g) { gemm_bf16_256_body<224, false>(g); }
-__global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, false>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256x224_kernel(GemmArgs g) { gemm_bf16_256_body<224, false, false>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_blocked_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true>(g); }
 
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -486,8 +502,11 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   // one resident workgroup per CU walks several tiles when the pipeline can continue across tiles
   const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
   unsigned nwg = (unsigned)(chain ? cus : ntiles);
+  const bool blocked = g.a_kstep != kRow || g.b_kstep != kRow || g.a_blk_stride != kTile * g.lda || g.b_blk_stride != g.tile_n * g.ldb;
   if (g.tile_n == 224)
     hipLaunchKernelGGL(gemm_bf16_256x224_kernel, dim3(nwg), dim3(256), 0, s, g);
+  else if (blocked)
+    hipLaunchKernelGGL(gemm_bf16_256_blocked_kernel, dim3(nwg), dim3(256), 0, s, g);
   else
     hipLaunchKernelGGL(gemm_bf16_256_kernel, dim3(nwg), dim3(256), 0, s, g);
   return hipGetLastError();

@@ -227,3 +227,30 @@ def grouped_gemm_specs(g: "GroupedGemmInputs", lda: Optional[int] = None, ldb: O
     return (spec([(g.M, lda, "m"), (g.K, 1, "m")]),
             spec([(g.G, ldg, "m"), (g.K, 1, "m"), (g.N, ldb, "m")]),
             spec([(g.M, ldc, "m"), (g.N, 1, "m")]))
+
+
+# ---- operands stored in 256 x 64 blocks (rows x k), each block contiguous, blocks of one row block side by side
+def pack_blocked(rows_k: np.ndarray, rb: int = 256, kb: int = 64) -> np.ndarray:
+    """Memory image of a (R, K) matrix (unit stride along k in the plain form) stored as contiguous rb x kb
+    blocks: block (r / rb, k / kb) at ((r / rb) * (K / kb) + k / kb) * rb * kb, row-major inside the block.
+    Leading dimensions are kept: (..., R, K) -> (..., R * K)."""
+    *lead, Rn, K = rows_k.shape
+    v = rows_k.reshape(*lead, Rn // rb, rb, K // kb, kb)
+    n = len(lead)
+    return np.ascontiguousarray(v.transpose(*range(n), n, n + 2, n + 1, n + 3)).reshape(*lead, Rn * K)
+
+
+def blocked_iters(Rn: int, K: int, rb: int = 256, kb: int = 64):
+    """(row iters, k iters) of that image as Axe iters on "m"."""
+    return [(Rn // rb, rb * K, "m"), (rb, kb, "m")], [(K // kb, rb * kb, "m"), (kb, 1, "m")]
+
+
+def blocked_a_spec(M: int, K: int) -> dict:
+    r, k = blocked_iters(M, K)
+    return spec(r + k)
+
+
+def blocked_b_spec(K: int, N: int, G: Optional[int] = None) -> dict:
+    """B logical (K, N), or (G, K, N) with the groups' images one after the other."""
+    r, k = blocked_iters(N, K)
+    return spec(([(G, N * K, "m")] if G is not None else []) + k + r)

@@ -146,6 +146,33 @@ def test_gemm_family_matching_and_errors():
     assert B.lib().axe_gemm(C.byref(d.c), None, None, None, None) == B.AXE_EINVAL
 
 
+def test_gemm_accepts_blocked_operands():
+    """Operands stored as contiguous 256 x 64 blocks (a tile product, Sec. 3.3) are in the family of the
+    bf16 256 x 256 kernel; the same layouts are refused where no kernel reads them."""
+    M = N = 512
+    K = 256
+    blkA, blkB = W.blocked_a_spec(M, K), W.blocked_b_spec(K, N)
+    kw = dict(M=M, N=N, K=K)
+    plainA, plainB = W.row_major_spec(M, K), W.col_major_spec(K, N)
+    assert _tile_rc(_gemm_desc(A=blkA, Bs=blkB, **kw)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(A=plainA, Bs=blkB, **kw)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(A=blkA, Bs=plainB, **kw)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(A=blkA, Bs=blkB, tile=B.AXE_TILE_64x64x32, **kw)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(_gemm_desc(A=blkA, Bs=blkB, out_dtype=B.AXE_F32, **kw)) == B.AXE_EUNSUPPORTED
+    # row blocks of 128 rows are not a multiple of the tile
+    r, k = W.blocked_iters(M, K, rb=128)
+    assert _tile_rc(_gemm_desc(A=W.spec(r + k), Bs=plainB, **kw)) == B.AXE_EUNSUPPORTED
+    # K-tiles of 32 are not the kernel's K step
+    r, k = W.blocked_iters(M, K, kb=32)
+    assert _tile_rc(_gemm_desc(A=W.spec(r + k), Bs=plainB, **kw)) == B.AXE_EUNSUPPORTED
+    # blocked along k only (rows pitched): a legal mixture
+    mixed = W.spec([(M, 64, "m"), (K // 64, M * 64, "m"), (64, 1, "m")])
+    assert _tile_rc(_gemm_desc(A=mixed, Bs=plainB, **kw)) == B.AXE_TILE_256x256x64
+    # grouped: blocked right-hand sides
+    chk = lambda d: B.lib().axe_gemm_grouped_check(C.byref(d.c))
+    assert chk(_grouped_desc(Bs=W.blocked_b_spec(256, 512, G=4))) == B.AXE_OK
+
+
 def _grouped_desc(M=1000, N=512, K=256, G=4, A=None, Bs=None, Cs=None, in_dtype=B.AXE_BF16, out_dtype=B.AXE_BF16,
                   b_elems=None):
     A = A or W.row_major_spec(M, K)

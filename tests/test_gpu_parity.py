@@ -656,3 +656,66 @@ def test_gemm_grouped_moe_layer_shapes_full_size(which):
         for r0 in range(off[e], off[e + 1], 256):
             r1 = min(r0 + 256, off[e + 1])
             assert np.linalg.norm(y[r0:r1] - y_ref[r0 - off[e]:r1 - off[e]]) <= BF16_TOL * np.linalg.norm(c[r0:r1]), (e, r0)
+
+
+# ----------------------------------------------------------------------------- blocked (pre-tiled) operands
+def run_gemm_blocked(g: W.GemmInputs, a_blocked: bool, b_blocked: bool):
+    """bf16 GEMM whose operands are stored as contiguous 256 x 64 blocks (images built with NumPy
+    reshape / transpose, layouts stated as tile products); returns C decoded to fp64."""
+    As = W.blocked_a_spec(g.M, g.K) if a_blocked else W.row_major_spec(g.M, g.K)
+    Bs = W.blocked_b_spec(g.K, g.N) if b_blocked else W.col_major_spec(g.K, g.N)
+    a = W.pack_blocked(g.a_mk) if a_blocked else g.a_mk.reshape(-1)
+    b = W.pack_blocked(g.b_nk) if b_blocked else g.b_nk.reshape(-1)
+    dA, dB = dev(a), dev(b)
+    dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
+    desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, g.N)),
+                      a.size, b.size, g.M * g.N)
+    assert B.axe_gemm_tile(desc) == B.AXE_TILE_256x256x64
+    B.axe_gemm(desc, dA, dB, dC)
+    torch.cuda.synchronize()
+    return R.bf16_to_f64(dC.cpu().numpy().view(np.uint16).reshape(g.M, g.N))
+
+
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 768, 192), (768, 256, 1024), (4352, 4096, 512)])
+@pytest.mark.parametrize("a_blocked,b_blocked", [(True, True), (True, False), (False, True)])
+def test_gemm_bf16_blocked_operands(M, N, K, a_blocked, b_blocked):
+    g = W.gemm_bf16(M, N, K, 91, std_b=K ** -0.5)
+    c = run_gemm_blocked(g, a_blocked, b_blocked)
+    if M * N * K <= 1 << 28:
+        check_gemm(c, oracle_gemm(g), BF16_TOL)
+    else:                                                   # the chained launch (17 x 16 tiles): bit-identical to the plain layout
+        ref = run_gemm(g)
+        assert np.array_equal(c, ref)
+        rows = np.array([0, 255, 256, M - 1])
+        assert R.rel_frobenius(c[rows], oracle_gemm(g, rows, None)) <= BF16_TOL
+
+
+def test_gemm_grouped_blocked_right_hand_sides():
+    off = [0, 300, 520, 1300, 1301, 2000]
+    g = W.gemm_grouped_bf16(off, 768, 512, 92)
+    As, _, Cs = W.grouped_gemm_specs(g)
+    b = W.pack_blocked(g.b_gnk)                              # (G, N * K): each group's image, one after the other
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(b.reshape(-1))
+    dC = torch.full((g.M * g.N,), SENTINEL, dtype=torch.int16, device="cuda")
+    dR = torch.from_numpy(g.group_rows).cuda()
+    desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(W.blocked_b_spec(g.K, g.N, G=g.G)), B.Layout(Cs),
+                             g.a_mk.size, b.size, g.M * g.N)
+    B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+    torch.cuda.synchronize()
+    raw = dC.cpu().numpy().view(np.uint16).reshape(g.M, g.N)
+    ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16)
+    check_grouped(g, R.bf16_to_f64(raw), raw, ref)
+    # and bit-identical to the launch on the plain layout (same kernel, same order of operations)
+    _, raw_plain = run_grouped(g)
+    assert np.array_equal(raw, raw_plain)
+
+
+def test_relayout_produces_the_blocked_operand_layout():
+    """The blocked image the GEMM reads is what axe_relayout writes from the plain one (weight pre-packing)."""
+    K, N = 512, 768
+    b_nk = W.to_bf16_bits(W.normal(93, (N, K)))
+    Ls, Ld = B.Layout(W.col_major_spec(K, N)), B.Layout(W.blocked_b_spec(K, N))
+    src, dst = dev(b_nk.reshape(-1)), torch.zeros(N * K, dtype=torch.int16, device="cuda")
+    B.axe_relayout(Ls, Ld, (K, N), src, dst)
+    torch.cuda.synchronize()
+    assert np.array_equal(dst.cpu().numpy().view(np.uint16), W.pack_blocked(b_nk))
