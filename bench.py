@@ -149,6 +149,39 @@ def bench_transpose(steps, warmup, n_pairs=4):
     return r
 
 
+def bench_grouped(steps, warmup, tokens=4096):
+    """The two grouped GEMMs of an MoE layer (hidden 2048, expert intermediate 768, 128 experts, 8 per token) at
+    `tokens` tokens: routed rows sorted by expert, offsets on the device.  Weights as plain column-major
+    matrices and pre-packed into contiguous 256 x 64 blocks by axe_relayout (untimed, as a server would do once)."""
+    import torch
+    from paper_2601_19092_amd import binding as B
+    from paper_2601_19092_amd import workloads as W
+    out = {"tokens": tokens, "experts": W.MOE_EXPERTS, "experts_per_token": W.MOE_TOPK}
+    for name, g in (("gemm1_gate_up", W.moe_gemm1(tokens)), ("gemm2_down", W.moe_gemm2(tokens))):
+        As, Bs, Cs = W.grouped_gemm_specs(g)
+        Bblk = W.blocked_b_spec(g.K, g.N, G=g.G)
+        dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_gnk.reshape(-1))
+        dBblk = torch.empty_like(dB)
+        B.axe_relayout(B.Layout(Bs), B.Layout(Bblk), (g.G, g.K, g.N), dB, dBblk)
+        assert np.array_equal(dBblk[:g.N * g.K].cpu().numpy().view(np.uint16), W.pack_blocked(g.b_gnk[0]))
+        dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
+        dR = torch.from_numpy(g.group_rows).cuda()
+        flops = 2.0 * g.M * g.N * g.K
+        sizes = np.diff(g.group_rows)
+        nbytes = 2.0 * (int((sizes > 0).sum()) * g.N * g.K + g.M * g.K + g.M * g.N)
+        r = {"M": g.M, "N": g.N, "K": g.K, "tiles": int(np.ceil(sizes / 256).sum()) * (g.N // 256), "algorithmic_bytes": nbytes}
+        for label, spec_b, buf in (("plain", Bs, dB), ("blocked", Bblk, dBblk)):
+            desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(spec_b), B.Layout(Cs), g.M * g.K, g.b_gnk.size, g.M * g.N)
+            wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, buf, dC, dR), steps, warmup)
+            r[label] = {"kernel_ms": devms, "tflops": flops / (devms * 1e-3) / 1e12, "GBps": nbytes / (devms * 1e-3) / 1e9}
+        out[name] = r
+        log(f"[bench] grouped GEMM {name} {tokens} tokens (M={g.M} N={g.N} K={g.K}, {g.G} experts, {r['tiles']} tiles): "
+            f"plain weights {r['plain']['kernel_ms']*1e3:.0f} us = {r['plain']['tflops']:.0f} TFLOP/s, {r['plain']['GBps']:.0f} GB/s; "
+            f"blocked weights {r['blocked']['kernel_ms']*1e3:.0f} us = {r['blocked']['tflops']:.0f} TFLOP/s, {r['blocked']['GBps']:.0f} GB/s")
+        del dA, dB, dBblk, dC
+    return out
+
+
 def bench_eval(steps, warmup):
     import torch
     from paper_2601_19092_amd import binding as B
@@ -221,7 +254,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--only", default="", help="comma list of: gemm,relayout,fp8,shard,small,eval,ceilings,cpu (default all)")
+    ap.add_argument("--only", default="", help="comma list of: gemm,relayout,fp8,shard,grouped,small,eval,ceilings,cpu (default all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -253,6 +286,8 @@ def main():
         comp["gemm_fp8_e8m0_block_scaled"], _ = bench_gemm(
             "fp8 e4m3 GEMM 8192^3, E8M0 (power-of-two) 128x128 block scales on the MFMA scale path",
             W.gemm_fp8(8192, 8192, 8192, W.SEED_BASE + 5, scaled="e8m0"), max(10, args.steps // 2), args.warmup)
+    if want("grouped"):
+        comp["moe_grouped_gemm"] = bench_grouped(max(10, args.steps // 3), args.warmup)
     if want("small"):
         comp["gemm_cfg1_256"], _ = bench_gemm("bf16 GEMM 256^3, fp32 out, 64x64x32 tiles", W.config1(),
                                               max(200, args.steps), max(200, args.warmup), n_sets=1)

@@ -85,7 +85,7 @@ __device__ __forceinline__ void mfma_16x16x32(f32x4& acc, bf16x8 a, bf16x8 b) {
 }  // namespace
 
 // Tiles of a grouped problem, counted group after group: group e has ceil(rows_e / 256) x grid_n of them
-// (columns fastest).  Lane t of the calling wave receives the workgroup's t-th tile: its first row, its
+// (row blocks fastest).  Lane t of the calling wave receives the workgroup's t-th tile: its first row, its
 // number of rows (0: no such tile), its tile column and its group.  Workgroup ids are dealt round-robin
 // to the 8 XCDs, so XCD x takes the x-th eighth of the tile sequence and its 32 workgroups walk it side
 // by side: neighbours in the sequence share A rows (same group and row block) or a B panel in that
@@ -139,10 +139,15 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
     }
     base += __builtin_amdgcn_readlane(incl, 63);
   }
-  const int tm = f_local / gn;
+  // inside a group the row blocks run fastest: the tiles that read one B panel are neighbours in the
+  // sequence (they run side by side on one XCD and the second reads the panel from that L2), and the
+  // tiles that read one block of A rows are only a group's few row blocks apart
+  const int gm = (f_rows + kTile - 1) / kTile;                     // row blocks of the group (0: the lane found no tile)
+  const int tn = gm ? f_local / gm : 0;
+  const int tm = f_local - tn * gm;
   t_row0 = f_r0 + tm * kTile;
-  const int left = f_rows - tm * kTile;                            // 0 when the lane found no tile
-  t_desc = (left < kTile ? left : kTile) | ((f_local - tm * gn) << 9) | (f_group << 20);
+  const int left = f_rows - tm * kTile;
+  t_desc = (left < kTile ? left : kTile) | (tn << 9) | (f_group << 20);
 }
 
 // NB = columns of C per tile (B rows per tile): 256, or 224 = 2 waves x 7 fragments for problems whose
