@@ -285,6 +285,19 @@ def gemm_grouped_ref(a_bits: np.ndarray, b_bits: np.ndarray, group_rows: Sequenc
     return out
 
 
+def swiglu_ref(p: np.ndarray) -> np.ndarray:
+    """The gated activation between the two group GEMMs of the MoE layer (Sec. 4.1 names the layer of
+    Qwen3-30B-A3B, whose experts are gated SiLU units): for P = [gate | up] of shape (M, 2 I),
+        H[r, c] = silu(P[r, c]) * P[r, c + I],      silu(x) = x / (1 + exp(-x)),
+    in fp64.  NaN rows (rows no group owns) stay NaN."""
+    if p.shape[1] % 2:
+        raise ValueError("the gate and up halves must have equal widths")
+    half = p.shape[1] // 2
+    gate, up = p[:, :half], p[:, half:]
+    with np.errstate(over="ignore"):
+        return gate / (1.0 + np.exp(-gate)) * up
+
+
 def rel_frobenius(c: np.ndarray, ref: np.ndarray) -> float:
     """|| c - ref ||_F / || ref ||_F in fp64."""
     c = np.asarray(c, dtype=np.float64)

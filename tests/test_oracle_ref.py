@@ -331,3 +331,24 @@ def test_moe_routing_recipe():
     g1, g2 = W.moe_gemm1(64), W.moe_gemm2(64)
     assert (g1.M, g1.N, g1.K, g1.G) == (512, 1536, 2048, 128) and (g2.N, g2.K) == (2048, 768)
     np.testing.assert_array_equal(g1.group_rows, g2.group_rows)
+
+
+def test_swiglu_closed_forms_and_library_routine():
+    x = np.array([[0.0, 1.0, -1.0, 30.0, -30.0, -800.0, 2.0, 3.0, 5.0, -7.0, 0.5, 1.0]])     # gate | up, I = 6
+    h = R.swiglu_ref(x)
+    e = np.e
+    assert h[0, 0] == 0.0                                               # silu(0) = 0
+    assert abs(h[0, 1] - (1 / (1 + 1 / e)) * 3.0) < 1e-15               # silu(1) = e / (1 + e)
+    assert abs(h[0, 2] - (-1 / (1 + e)) * 5.0) < 1e-15                  # silu(-1) = -1 / (1 + e)
+    assert abs(h[0, 3] - 30.0 * -7.0) < 1e-9                            # silu(x) -> x
+    assert abs(h[0, 4]) < 1e-11 and h[0, 5] == 0.0                      # silu(-x) -> 0, also where exp overflows
+    # silu(x) - silu(-x) = x  (from sigma(x) + sigma(-x) = 1)
+    g = np.linspace(-9, 9, 181)[None, :]
+    both = R.swiglu_ref(np.concatenate([g, np.ones_like(g)], axis=1)) - R.swiglu_ref(np.concatenate([-g, np.ones_like(g)], axis=1))
+    np.testing.assert_allclose(both, g, atol=1e-14)
+    # against the library's SiLU in fp64, and the gate / up halves are not swapped (silu is not symmetric)
+    p = np.random.default_rng(1).standard_normal((7, 10)) * 3
+    want = torch.nn.functional.silu(torch.from_numpy(p[:, :5])).numpy() * p[:, 5:]
+    np.testing.assert_allclose(R.swiglu_ref(p), want, rtol=1e-14, atol=1e-300)
+    assert not np.allclose(R.swiglu_ref(p), R.swiglu_ref(np.concatenate([p[:, 5:], p[:, :5]], axis=1)))
+    assert np.isnan(R.swiglu_ref(np.full((1, 4), np.nan))).all()
