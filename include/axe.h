@@ -192,7 +192,17 @@ typedef struct {
   axe_layout_t A, B, C;
   int32_t      mem_axis;
   int64_t      a_elems, b_elems, c_elems;
+  int32_t      epilogue;                 /* AXE_EPI_NONE or AXE_EPI_SWIGLU */
 } axe_gemm_grouped_desc_t;
+
+/* AXE_EPI_SWIGLU: the gated activation between the two group GEMMs, fused into the first.  The logical
+ * columns [0, N/2) of every B[e] are the gate projection, [N/2, N) the up projection, C is (M, N/2):
+ *       C[r, c] = silu(P[r, c]) * P[r, c + N/2],   P = A B[e] in fp32,   silu(x) = x / (1 + exp(-x)).
+ * Supported family: as above, and gate and up columns interleaved in memory in runs of 16 rows of the
+ * group's image (logical column h N/2 + 16 f + i in row 32 f + 16 h + i): along n the grouped form of B is
+ * (2, 16 p)(N/32, 32 p)(16, p), or (2, 16 p)(N/256, S)(8, 32 p)(16, p) for 256-row blocks; axe_relayout
+ * produces either from the plain matrix. */
+enum { AXE_EPI_NONE = 0, AXE_EPI_SWIGLU = 1 };
 
 int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const void* d_B, void* d_C,
                      const int32_t* d_group_rows, void* stream);

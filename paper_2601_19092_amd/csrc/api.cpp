@@ -621,7 +621,10 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
 // B of a grouped GEMM, logical (G, K, N): grouped by that shape (Alg. 1) the group block must be one iter
 // on the memory axis (one stride between groups); the k and n blocks are those of a pitched or blocked
 // matrix (blocked_2d above).
-int grouped_b(const axe_layout_t* L, int mem_axis, int64_t G, int64_t K, int64_t N, int64_t elems, int64_t* ldg,
+// gated: logical column n = h * (N / 2) + 16 f + i (h = 0: gate, 1: up) must sit in memory row 32 f + 16 h + i of
+// the group's image -- n block [(2, 16 p), (N / 32, 32 p), (16, p)], or with 256-row blocks
+// [(2, 16 p), (N / 256, S), (8, 32 p), (16, p)] -- which the result then describes as that image's rows.
+int grouped_b(const axe_layout_t* L, int mem_axis, int64_t G, int64_t K, int64_t N, int64_t elems, bool gated, int64_t* ldg,
               Operand2D* out) {
   const char* what = "axe_gemm_grouped(B)";
   HLayout h;
@@ -662,7 +665,18 @@ int grouped_b(const axe_layout_t* L, int mem_axis, int64_t G, int64_t K, int64_t
   else if (kb.size() == 1) ok = kb[0].s == 1;
   else if (kb.size() == 2) ok = kb[1].s == 1 && kb[1].e == 64, o.kt_stride = kb[0].s;
   else ok = false;
-  if (nb.empty()) o.pitch = K;
+  if (gated) {
+    const size_t n = nb.size();
+    const int64_t p = n ? nb[n - 1].s : 0;
+    if ((n != 3 && n != 4) || nb[0].e != 2 || nb[0].s != 16 * p || nb[n - 1].e != 16 || nb[n - 2].s != 32 * p ||
+        (n == 4 && nb[2].e != 8)) {
+      set_error("%s: the gated epilogue needs gate and up columns interleaved in runs of 16 rows: n block "
+                "(2, 16 p)(N/32, 32 p)(16, p) or, in 256-row blocks, (2, 16 p)(N/256, S)(8, 32 p)(16, p)", what);
+      return AXE_EUNSUPPORTED;
+    }
+    o.pitch = p;
+    if (n == 4) o.rb = 256, o.rb_stride = nb[1].s;
+  } else if (nb.empty()) o.pitch = K;
   else if (nb.size() == 1) o.pitch = nb[0].s;
   else if (nb.size() == 2) o.pitch = nb[1].s, o.rb = nb[1].e, o.rb_stride = nb[0].s;
   else ok = false;
@@ -693,14 +707,20 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
   int64_t lda, ldb, ldc, ldg, oa, ob, oc;
   Operand2D opb;
   if (int rc = strided_2d(&g->A, g->mem_axis, g->M, g->K, true, g->a_elems, "axe_gemm_grouped(A)", &lda, &oa)) return rc;
-  if (int rc = grouped_b(&g->B, g->mem_axis, g->G, g->K, g->N, g->b_elems, &ldg, &opb)) return rc;
+  if (g->epilogue != AXE_EPI_NONE && g->epilogue != AXE_EPI_SWIGLU) {
+    set_error("%s: unknown epilogue %d", fn, g->epilogue);
+    return AXE_EINVAL;
+  }
+  const bool gated = g->epilogue == AXE_EPI_SWIGLU;
+  const int64_t NC = gated ? g->N / 2 : g->N;                      // columns of C
+  if (int rc = grouped_b(&g->B, g->mem_axis, g->G, g->K, g->N, g->b_elems, gated, &ldg, &opb)) return rc;
   ldb = opb.pitch, ob = opb.off;
   if ((opb.rb && (opb.rb % 256 || !is_pow2(opb.rb / 256) || opb.rb_stride % 8)) ||
       (opb.kt_stride && (opb.kt_stride % 8 || (g->K / 64) * opb.kt_stride * 2 >= (int64_t(1) << 30)))) {
     set_error("%s: a blocked B needs row blocks of 256 x 2^n columns of C and strides that are multiples of 16 bytes", fn);
     return AXE_EUNSUPPORTED;
   }
-  if (int rc = strided_2d(&g->C, g->mem_axis, g->M, g->N, true, g->c_elems, "axe_gemm_grouped(C)", &ldc, &oc)) return rc;
+  if (int rc = strided_2d(&g->C, g->mem_axis, g->M, NC, true, g->c_elems, "axe_gemm_grouped(C)", &ldc, &oc)) return rc;
   if ((g->K % 8) || (lda % 8) || (ldb % 8) || (ldg % 8) || (oa % 8) || (ob % 8) || (oc % 8) || (ldc % 8)) {
     set_error("%s: K, leading dimensions, the group stride and offsets must be multiples of 8 elements (16 bytes)", fn);
     return AXE_EUNSUPPORTED;
@@ -752,6 +772,7 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
   a.b_blk_stride = opb.rb ? opb.rb_stride : 256 * ldb;
   a.group_rows = rows;
   a.groups = g->G;
+  a.gated = gated;
   return AXE_OK;
 }
 

@@ -163,8 +163,14 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 //
 // BLOCKED: the operands may be stored in blocks (see a_kstep below); without it the scalar offsets are
 // the constants of a plain pitched matrix.
-template <int NB, bool GROUPED, bool BLOCKED>
+//
+// GATED: the epilogue of the first group GEMM of an MoE layer.  B holds each expert's gate and up
+// projections interleaved in runs of 16 rows (the host accepts only that layout), so that fragment pair
+// (j, j + 1) of a wave is (gate, up) of the same 16 output columns in the same lanes; the tile stores
+// silu(gate) * up, half as wide as the product.
+template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
+  static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
   constexpr int NJ = NB / 32;                                      // fragments per wave along N
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
   const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
@@ -326,8 +332,9 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
       const int tn = desc_tn(dsc);
       int rows = desc_rows(dsc) - wm * 128;                          // rows of the tile that fall to this wave
       rows = rows < 0 ? 0 : (rows > 128 ? 128 : rows);
-      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * 128) * g.ldc + (int64_t)tn * NB + wn * (NB / 2),
-                    rows ? (uint32_t)(((rows - 1) * g.ldc + NB / 2) * 2) : 0u);
+      constexpr int CW = GATED ? NB / 4 : NB / 2;                    // columns of C this wave writes
+      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * 128) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
+                    rows ? (uint32_t)(((rows - 1) * g.ldc + CW) * 2) : 0u);
       c_rowblk = (int)(16 * g.ldc * 2);
       return;
     }
@@ -361,6 +368,29 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
+  };
+
+  // Gated epilogue: h = silu(gate) * up for the fragment pairs (j, j + 1) and (j + 2, j + 3), stored like a
+  // fragment pair (32 output columns, 64 contiguous bytes per row).  fp32 throughout; the exponential and
+  // the reciprocal are the hardware's approximations (1 ulp), far inside the bf16 rounding of the result.
+  auto store_gated_quad = [&](int i, int j) __attribute__((always_inline)) {
+    float h[2][4];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float gate = acc[i][j + 2 * q][e], up = acc[i][j + 2 * q + 1][e];
+        h[q][e] = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
+      }
+    const auto lo = __builtin_amdgcn_permlane16_swap(pack_bf16(h[0][0], h[0][1]), pack_bf16(h[1][0], h[1][1]), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16(h[0][2], h[0][3]), pack_bf16(h[1][2], h[1][3]), false, false);
+    const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
+    const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 16);
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[i][j + q][e] = 0.f;
   };
 
   using I0 = std::integral_constant<int, 0>;
@@ -477,12 +507,17 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     __builtin_amdgcn_sched_barrier(0);                             // no accumulator read may move above the padding
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
+      if constexpr (GATED) {
 #pragma unroll
-      for (int j = 0; j < NJ; j += 2) {
-        if (NJ % 2 == 0) store_fragment_pair(i, j);                // (7 fragments per row do not pair up: stored one by one)
-        else {
-          store_fragment(i, j);
-          if (j + 1 < NJ) store_fragment(i, j + 1);
+        for (int j = 0; j < NJ; j += 4) store_gated_quad(i, j);
+      } else {
+#pragma unroll
+        for (int j = 0; j < NJ; j += 2) {
+          if (NJ % 2 == 0) store_fragment_pair(i, j);              // (7 fragments per row do not pair up: stored one by one)
+          else {
+            store_fragment(i, j);
+            if (j + 1 < NJ) store_fragment(i, j + 1);
+          }
         }
       }
     }
@@ -499,6 +534,7 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_kernel(GemmArgs g) { gem
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256x224_kernel(GemmArgs g) { gemm_bf16_256_body<224, false, false>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_blocked_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true>(g); }
 
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -529,7 +565,10 @@ hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
   int64_t nwg = chain ? std::max<int64_t>(cus, (worst + 63) / 64) : worst;
   nwg = (nwg + 7) / 8 * 8;                                         // the tile sequence is cut into 8 parts, one per XCD
   if (nwg > 0x7fffffff) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(gemm_bf16_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  if (g.gated)
+    hipLaunchKernelGGL(gemm_bf16_256_grouped_gated_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  else
+    hipLaunchKernelGGL(gemm_bf16_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 

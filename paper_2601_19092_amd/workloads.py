@@ -254,3 +254,18 @@ def blocked_b_spec(K: int, N: int, G: Optional[int] = None) -> dict:
     """B logical (K, N), or (G, K, N) with the groups' images one after the other."""
     r, k = blocked_iters(N, K)
     return spec(([(G, N * K, "m")] if G is not None else []) + k + r)
+
+
+# ---- gate and up projections of an expert interleaved in runs of 16 rows (what the gated epilogue reads)
+def pack_gate_up(b_gnk: np.ndarray) -> np.ndarray:
+    """(G, N, K) with rows [gate 0 .. I-1 | up 0 .. I-1] -> rows 32 f + 16 h + i = (h ? up : gate)[16 f + i]."""
+    G, N, K = b_gnk.shape
+    return np.ascontiguousarray(b_gnk.reshape(G, 2, N // 32, 16, K).transpose(0, 2, 1, 3, 4)).reshape(G, N, K)
+
+
+def gated_b_spec(K: int, N: int, G: int, blocked: bool = False) -> dict:
+    """Layout of the logical (G, K, N) right-hand sides whose memory image is pack_gate_up (then pack_blocked)."""
+    if not blocked:
+        return spec([(G, N * K, "m"), (K, 1, "m"), (2, 16 * K, "m"), (N // 32, 32 * K, "m"), (16, K, "m")])
+    return spec([(G, N * K, "m"), (K // 64, 256 * 64, "m"), (64, 1, "m"),
+                 (2, 16 * 64, "m"), (N // 256, 256 * K, "m"), (8, 32 * 64, "m"), (16, 64, "m")])

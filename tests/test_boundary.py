@@ -208,6 +208,25 @@ def test_grouped_gemm_family_matching_and_errors():
     assert B.lib().axe_gemm_grouped(C.byref(d.c), None, None, None, None, None) == B.AXE_EINVAL
 
 
+def test_grouped_gemm_gated_epilogue_needs_interleaved_gate_and_up():
+    M, N, K, G = 1000, 512, 256, 4
+    chk = lambda d: B.lib().axe_gemm_grouped_check(C.byref(d.c))
+    def desc(Bs, Cn=N // 2, epi=B.AXE_EPI_SWIGLU):
+        return B.GroupedGemmDesc(M, N, K, G, B.Layout(W.row_major_spec(M, K)), B.Layout(Bs), B.Layout(W.row_major_spec(M, Cn)),
+                                 M * K, G * N * K, M * Cn, epilogue=epi)
+    assert chk(desc(W.gated_b_spec(K, N, G))) == B.AXE_OK
+    assert chk(desc(W.gated_b_spec(K, N, G, blocked=True))) == B.AXE_OK
+    # gate and up side by side (the plain matrix) cannot feed the fused epilogue
+    assert chk(desc(W.spec([(G, N * K, "m"), (K, 1, "m"), (N, K, "m")]))) == B.AXE_EUNSUPPORTED
+    # runs of 32 instead of 16
+    assert chk(desc(W.spec([(G, N * K, "m"), (K, 1, "m"), (2, 32 * K, "m"), (N // 64, 64 * K, "m"), (32, K, "m")]))) == B.AXE_EUNSUPPORTED
+    # C must be N / 2 wide
+    assert chk(desc(W.gated_b_spec(K, N, G), Cn=N)) == B.AXE_ESHAPE
+    assert chk(desc(W.gated_b_spec(K, N, G), epi=7)) == B.AXE_EINVAL
+    # without the epilogue the interleaved layout is just a permutation of columns nobody asked for
+    assert chk(desc(W.gated_b_spec(K, N, G), Cn=N, epi=B.AXE_EPI_NONE)) == B.AXE_EUNSUPPORTED
+
+
 def test_python_binding_raises_axe_error():
     with pytest.raises(B.AxeError) as e:
         B._check(B.AXE_EALIAS)
