@@ -174,11 +174,26 @@ def bench_grouped(steps, warmup, tokens=4096):
             desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(spec_b), B.Layout(Cs), g.M * g.K, g.b_gnk.size, g.M * g.N)
             wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, buf, dC, dR), steps, warmup)
             r[label] = {"kernel_ms": devms, "tflops": flops / (devms * 1e-3) / 1e12, "GBps": nbytes / (devms * 1e-3) / 1e9}
+        if name == "gemm1_gate_up":
+            # the same GEMM with the gated activation fused (C half as wide); gate / up interleaved and blocked by axe_relayout
+            Bg = W.gated_b_spec(g.K, g.N, g.G, blocked=True)
+            B.axe_relayout(B.Layout(Bs), B.Layout(Bg), (g.G, g.K, g.N), dB, dBblk)
+            assert np.array_equal(dBblk[:g.N * g.K].cpu().numpy().view(np.uint16), W.pack_blocked(W.pack_gate_up(g.b_gnk[:1]))[0])
+            dH = torch.zeros(g.M * (g.N // 2), dtype=torch.int16, device="cuda")
+            desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(Bg), B.Layout(W.row_major_spec(g.M, g.N // 2)),
+                                     g.M * g.K, g.b_gnk.size, g.M * (g.N // 2), epilogue=B.AXE_EPI_SWIGLU)
+            wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dBblk, dH, dR), steps, warmup)
+            r["blocked_gated"] = {"kernel_ms": devms, "tflops": flops / (devms * 1e-3) / 1e12,
+                                  "GBps": (nbytes - g.M * g.N) / (devms * 1e-3) / 1e9}
+            log(f"[bench]   with the gated activation fused (C = silu(gate) * up, {g.N // 2} wide): {devms*1e3:.0f} us")
+            del dH
         out[name] = r
         log(f"[bench] grouped GEMM {name} {tokens} tokens (M={g.M} N={g.N} K={g.K}, {g.G} experts, {r['tiles']} tiles): "
             f"plain weights {r['plain']['kernel_ms']*1e3:.0f} us = {r['plain']['tflops']:.0f} TFLOP/s, {r['plain']['GBps']:.0f} GB/s; "
             f"blocked weights {r['blocked']['kernel_ms']*1e3:.0f} us = {r['blocked']['tflops']:.0f} TFLOP/s, {r['blocked']['GBps']:.0f} GB/s")
         del dA, dB, dBblk, dC
+    out["layer_kernel_ms"] = out["gemm1_gate_up"]["blocked_gated"]["kernel_ms"] + out["gemm2_down"]["blocked"]["kernel_ms"]
+    log(f"[bench] MoE layer expert compute (gemm1 + activation, gemm2) at {tokens} tokens: {out['layer_kernel_ms']*1e3:.0f} us")
     return out
 
 
