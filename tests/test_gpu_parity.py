@@ -778,3 +778,76 @@ def test_gemm_grouped_gated_moe_layer_full_size():
             rows = np.arange(off[e], off[e + 1])
             ref = R.swiglu_ref(R.gemm_ref(g.a_mk, bl[e], R.AXE_BF16, rows=rows, cols=np.array([cols1[0], I + cols1[0]])))
             assert R.rel_frobenius(c[np.ix_(rows, cols1)], ref) <= 2 * BF16_TOL, e
+
+
+# ----------------------------------------------------------------------------- HIP graph capture
+def test_entry_points_can_be_captured_in_a_hip_graph():
+    """A serving loop records its launches once and replays them.  The library allocates nothing, clears
+    nothing with memset and never synchronises, so a chain relayout -> grouped GEMM (gated) -> grouped GEMM ->
+    dense GEMM can be captured; every replay must reproduce the eager result bit for bit, with the program's own
+    eager work and synchronisations in between and with the inputs (group sizes included) changed between replays."""
+    tokens_rows = [[0, 300, 520, 1300, 1301, 2000], [0, 0, 700, 701, 1500, 1800]]
+    N1, K1, N2 = 512, 256, 256                                  # expert: K1 -> N1 / 2 (gated) -> N2
+    G, M = 5, 2000
+    g1 = W.gemm_grouped_bf16(tokens_rows[0], N1, K1, 95)
+    w2 = W.to_bf16_bits(W.normal(96, (G, N2, N1 // 2), (N1 // 2) ** -0.5))
+    dense_b = W.to_bf16_bits(W.normal(97, (256, N2), N2 ** -0.5))            # (N, K) image of a 256-column dense GEMM
+    dA = dev(g1.a_mk.reshape(-1))
+    dW1 = dev(g1.b_gnk.reshape(-1))
+    dW1p = torch.zeros_like(dW1)
+    dW2 = dev(w2.reshape(-1))
+    dBd = dev(dense_b.reshape(-1))
+    dR = torch.from_numpy(g1.group_rows).cuda()
+    dH = torch.zeros(M * (N1 // 2), dtype=torch.int16, device="cuda")
+    dY = torch.zeros(M * N2, dtype=torch.int16, device="cuda")
+    Mp = 2048                                                   # the dense GEMM reads Y padded to a multiple of 256 rows
+    dYp = torch.zeros(Mp * N2, dtype=torch.int16, device="cuda")
+    dZ = torch.zeros(Mp * 256, dtype=torch.int16, device="cuda")
+    plain1 = B.Layout(W.spec([(G, N1 * K1, "m"), (K1, 1, "m"), (N1, K1, "m")]))
+    gated1 = B.Layout(W.gated_b_spec(K1, N1, G, blocked=True))
+    d1 = B.GroupedGemmDesc(M, N1, K1, G, B.Layout(W.row_major_spec(M, K1)), gated1, B.Layout(W.row_major_spec(M, N1 // 2)),
+                           M * K1, dW1.numel(), M * (N1 // 2), epilogue=B.AXE_EPI_SWIGLU)
+    g2 = W.GroupedGemmInputs(M, N2, N1 // 2, G, None, w2, g1.group_rows)
+    As2, Bs2, Cs2 = W.grouped_gemm_specs(g2)
+    d2 = B.GroupedGemmDesc(M, N2, N1 // 2, G, B.Layout(As2), B.Layout(Bs2), B.Layout(Cs2), M * (N1 // 2), dW2.numel(), M * N2)
+    d3 = B.GemmDesc(Mp, 256, N2, B.AXE_BF16, B.AXE_BF16, B.Layout(W.row_major_spec(Mp, N2)), B.Layout(W.col_major_spec(N2, 256)),
+                    B.Layout(W.row_major_spec(Mp, 256)), Mp * N2, dBd.numel(), Mp * 256)
+
+    def chain():
+        B.axe_relayout(plain1, gated1, (G, K1, N1), dW1, dW1p)
+        B.axe_gemm_grouped(d1, dA, dW1p, dH, dR)
+        B.axe_gemm_grouped(d2, dH, dW2, dY, dR)
+        dYp[:M * N2].copy_(dY)
+        B.axe_gemm(d3, dYp, dBd, dZ)
+
+    def eager(rows, a_words):
+        dR.copy_(torch.from_numpy(np.asarray(rows, dtype=np.int32)))
+        dA.copy_(dev(a_words.reshape(-1)))
+        for t in (dH, dY, dYp, dZ, dW1p):
+            t.zero_()
+        chain()
+        torch.cuda.synchronize()
+        return dH.clone(), dY.clone(), dZ.clone()
+
+    inputs = [(tokens_rows[0], g1.a_mk), (tokens_rows[1], np.roll(g1.a_mk, 17, axis=0)), (tokens_rows[0], np.roll(g1.a_mk, 5, axis=1))]
+    want = [eager(r, a) for r, a in inputs]
+    assert not torch.equal(want[0][1], want[1][1])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                               # warm-up on the capture stream, as torch asks for
+        chain()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        chain()
+    for rep in range(2):
+        for (rows, a_words), (h, y, z) in zip(inputs, want):
+            dR.copy_(torch.from_numpy(np.asarray(rows, dtype=np.int32)))
+            dA.copy_(dev(a_words.reshape(-1)))
+            for t in (dH, dY, dYp, dZ, dW1p):
+                t.zero_()
+            scratch = torch.randn(1 << 20, device="cuda").sum().item()       # eager work and a synchronisation between replays
+            graph.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(dH, h) and torch.equal(dY, y) and torch.equal(dZ, z), (rep, rows)
