@@ -118,6 +118,16 @@ def bf16_to_f64(bits: np.ndarray) -> np.ndarray:
     return b.view(np.float32).astype(np.float64)
 
 
+def f16_to_f64(bits: np.ndarray) -> np.ndarray:
+    """IEEE binary16 from its definition: 1 sign bit, 5 exponent bits (bias 15), 10 fraction bits;
+    exponent 0 holds the subnormals m / 1024 * 2^-14, exponent 31 infinities (m = 0) and NaNs."""
+    b = np.asarray(bits, dtype=np.uint16).astype(np.int64)
+    s, e, m = b >> 15, (b >> 10) & 31, (b & 1023).astype(np.float64)
+    v = np.where(e == 0, m / 1024.0 * 2.0 ** -14, (1.0 + m / 1024.0) * np.exp2((e - 15).astype(np.float64)))
+    v = np.where(e == 31, np.where(m == 0, np.inf, np.nan), v)
+    return np.where(s == 1, -v, v)
+
+
 def e4m3_table() -> np.ndarray:
     """All 256 values of OCP FP8 E4M3 (the 'fn' flavour: bias 7, no infinities, the two
     codes S.1111.111 are NaN, largest finite 448)."""
@@ -145,6 +155,7 @@ def e4m3_to_f64(bits: np.ndarray) -> np.ndarray:
 # --------------------------------------------------------------------------------------
 AXE_BF16 = 1
 AXE_FP8_E4M3 = 2
+AXE_F16 = 4
 
 
 def decode(bits: np.ndarray, dtype: int) -> np.ndarray:
@@ -152,6 +163,8 @@ def decode(bits: np.ndarray, dtype: int) -> np.ndarray:
         return bf16_to_f64(bits)
     if dtype == AXE_FP8_E4M3:
         return e4m3_to_f64(bits)
+    if dtype == AXE_F16:
+        return f16_to_f64(bits)
     raise ValueError("unknown input dtype")
 
 
@@ -229,7 +242,7 @@ def gemm_ref(a_bits: np.ndarray, b_bits: np.ndarray, dtype: int,
     if K != K2:
         raise ValueError("inner dimensions differ")
     isz = a_bits.dtype.itemsize
-    want = 2 if dtype == AXE_BF16 else 1
+    want = 1 if dtype == AXE_FP8_E4M3 else 2
     if isz != want or b_bits.dtype.itemsize != want:
         raise ValueError("bit arrays have the wrong word size")
     rows = np.arange(M, dtype=np.int64) if rows is None else np.ascontiguousarray(rows, dtype=np.int64)

@@ -11,7 +11,8 @@
  * Only the loop over output elements is spread over threads; every output is an independent
  * serial sum.  The number formats are decoded from their definitions:
  *   bf16  = upper 16 bits of IEEE binary32;
- *   e4m3  = OCP FP8 E4M3 (bias 7, subnormals, no infinities, S.1111.111 = NaN, max 448).
+ *   e4m3  = OCP FP8 E4M3 (bias 7, subnormals, no infinities, S.1111.111 = NaN, max 448);
+ *   f16   = IEEE binary16 (the fused MoE layer of Sec. 4.1 is an FP16 layer).
  * This file shares nothing with the GPU library.
  */
 #include <math.h>
@@ -21,13 +22,23 @@
 #include <omp.h>
 #endif
 
-enum { ORACLE_BF16 = 1, ORACLE_FP8_E4M3 = 2 };
+enum { ORACLE_BF16 = 1, ORACLE_FP8_E4M3 = 2, ORACLE_F16 = 4 };
 
 static double dec_bf16(uint16_t h) {
     uint32_t w = (uint32_t)h << 16;
     float f;
     memcpy(&f, &w, sizeof f);
     return (double)f;
+}
+
+/* IEEE binary16: 1 sign, 5 exponent (bias 15), 10 fraction bits; exponent 0 = subnormals, 31 = inf / NaN */
+static double dec_f16(uint16_t h) {
+    int s = h >> 15, e = (h >> 10) & 31, m = h & 1023;
+    double v;
+    if (e == 31) v = m ? NAN : INFINITY;
+    else if (e == 0) v = ldexp((double)m / 1024.0, -14);
+    else v = ldexp(1.0 + (double)m / 1024.0, e - 15);
+    return s ? -v : v;
 }
 
 static double dec_e4m3(uint8_t c) {
@@ -41,6 +52,7 @@ static double dec_e4m3(uint8_t c) {
 
 static double load(const void* p, int64_t idx, int dtype) {
     if (dtype == ORACLE_BF16) return dec_bf16(((const uint16_t*)p)[idx]);
+    if (dtype == ORACLE_F16) return dec_f16(((const uint16_t*)p)[idx]);
     return dec_e4m3(((const uint8_t*)p)[idx]);
 }
 
@@ -62,7 +74,7 @@ int axe_oracle_gemm(int dtype, int64_t M, int64_t N, int64_t K,
                     const float* sA, const float* sB, int64_t bs,
                     const int64_t* rows, int64_t nrows, const int64_t* cols, int64_t ncols,
                     double* out) {
-    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP8_E4M3) return -1;
+    if (dtype != ORACLE_BF16 && dtype != ORACLE_FP8_E4M3 && dtype != ORACLE_F16) return -1;
     if ((sA == 0) != (sB == 0)) return -2;
     if (sA && bs <= 0) return -3;
     (void)M; (void)N;

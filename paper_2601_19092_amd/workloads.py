@@ -29,6 +29,12 @@ def to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return t.view(torch.int16).numpy().view(np.uint16).copy()
 
 
+def to_f16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> IEEE binary16 (round to nearest even) -> raw uint16 words."""
+    t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).to(torch.float16)
+    return t.view(torch.int16).numpy().view(np.uint16).copy()
+
+
 def to_e4m3_bits(x: np.ndarray) -> np.ndarray:
     """fp32 -> clip to the finite range [-448, 448] -> OCP e4m3 (round to nearest even) -> raw bytes."""
     t = torch.from_numpy(np.ascontiguousarray(x, dtype=np.float32)).clamp_(-448.0, 448.0)
@@ -50,7 +56,7 @@ class GemmInputs:
     M: int
     N: int
     K: int
-    dtype: str                      # "bf16" | "fp8"
+    dtype: str                      # "bf16" | "f16" | "fp8"
     a_mk: np.ndarray                # raw words, shape (M, K)
     b_nk: np.ndarray                # raw words, shape (N, K)
     scale_a: Optional[np.ndarray] = None   # fp32, or uint8 E8M0 codes, (ceil(M/128), ceil(K/128))
@@ -64,6 +70,14 @@ def gemm_bf16(M: int, N: int, K: int, seed: int, std_a: float = 1.0, std_b: floa
     a = to_bf16_bits(normal(seed, (M, K), std_a))
     b = to_bf16_bits(normal(seed + 1000, (N, K), std_b))
     return GemmInputs(M, N, K, "bf16", a, b, out_dtype=out_dtype)
+
+
+def gemm_f16(M: int, N: int, K: int, seed: int, std_a: float = 1.0, std_b: float = 1.0,
+             out_dtype: str = "f16") -> GemmInputs:
+    """The same draws as gemm_bf16, cast to IEEE binary16 (the fused MoE layer of the paper is an FP16 layer)."""
+    a = to_f16_bits(normal(seed, (M, K), std_a))
+    b = to_f16_bits(normal(seed + 1000, (N, K), std_b))
+    return GemmInputs(M, N, K, "f16", a, b, out_dtype=out_dtype)
 
 
 def gemm_fp8(M: int, N: int, K: int, seed: int, block: int = 128, scaled=True) -> GemmInputs:
@@ -94,6 +108,7 @@ class GroupedGemmInputs:
     a_mk: np.ndarray
     b_gnk: np.ndarray
     group_rows: np.ndarray
+    dtype: str = "bf16"             # "bf16" | "f16" (inputs and output)
 
 
 def moe_group_rows(tokens: int, experts: int, topk: int, seed: int, skew: float = 0.5) -> np.ndarray:
@@ -109,13 +124,14 @@ def moe_group_rows(tokens: int, experts: int, topk: int, seed: int, skew: float 
 
 
 def gemm_grouped_bf16(group_rows, N: int, K: int, seed: int, M: Optional[int] = None, std_a: float = 1.0,
-                      std_b: Optional[float] = None) -> GroupedGemmInputs:
+                      std_b: Optional[float] = None, dtype: str = "bf16") -> GroupedGemmInputs:
     group_rows = np.ascontiguousarray(group_rows, dtype=np.int32)
     G = group_rows.size - 1
     M = int(group_rows[-1]) if M is None else M
     std_b = K ** -0.5 if std_b is None else std_b
-    return GroupedGemmInputs(M, N, K, G, to_bf16_bits(normal(seed, (M, K), std_a)),
-                             to_bf16_bits(normal(seed + 7919, (G, N, K), std_b)), group_rows)
+    cast = to_f16_bits if dtype == "f16" else to_bf16_bits
+    return GroupedGemmInputs(M, N, K, G, cast(normal(seed, (M, K), std_a)), cast(normal(seed + 7919, (G, N, K), std_b)),
+                             group_rows, dtype)
 
 
 # the MoE layer of Qwen3-30B-A3B (the configuration the paper's fused-MoE figure is measured on):

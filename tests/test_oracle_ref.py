@@ -124,6 +124,29 @@ def test_bf16_decode_matches_torch_for_all_codes():
     assert got[0x3F80] == 1.0 and got[0xC000] == -2.0 and got[0x3DCD] == pytest.approx(0.1, rel=4e-3)
 
 
+def test_f16_decode_matches_numpy_for_all_codes_in_python_and_c():
+    codes = np.arange(65536, dtype=np.uint16)
+    want = codes.view(np.float16).astype(np.float64)
+    got = R.f16_to_f64(codes)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    ok = ~np.isnan(want)
+    assert np.array_equal(got[ok], want[ok]) and np.array_equal(np.signbit(got[ok]), np.signbit(want[ok]))
+    # format facts: largest finite value, smallest subnormal, one
+    assert R.f16_to_f64(np.array([0x7BFF, 0x0001, 0x3C00], dtype=np.uint16)).tolist() == [65504.0, 2.0 ** -24, 1.0]
+    # the C decoder: a 1 x K by K x 1 product with b = 1 sums the decoded values of a
+    fin = codes[np.isfinite(want)]
+    for chunk in np.array_split(fin, 64):
+        a = chunk.reshape(1, -1)
+        ones = np.full((a.shape[1], 1), 0x3C00, dtype=np.uint16)
+        assert R.gemm_ref(a, ones, R.AXE_F16)[0, 0] == np.sum(want[chunk.astype(np.int64)], dtype=np.float64)
+    # single codes, so that no two decoding mistakes can cancel in a sum
+    for c in (0x0001, 0x03FF, 0x0400, 0x3555, 0x7BFF, 0x8001, 0xC000, 0xFBFF):
+        one = np.array([[c]], dtype=np.uint16)
+        assert R.gemm_ref(one, np.array([[0x3C00]], dtype=np.uint16), R.AXE_F16)[0, 0] == want[c]
+    # RNE cast of the generator: ties go to the even code
+    assert W.to_f16_bits(np.array([1.0 + 2.0 ** -11, 1.0 + 3 * 2.0 ** -11], dtype=np.float32)).tolist() == [0x3C00, 0x3C02]
+
+
 def test_e4m3_decode_matches_torch_and_format_facts():
     codes = np.arange(256, dtype=np.uint8)
     want = torch.from_numpy(codes.copy()).view(torch.float8_e4m3fn).to(torch.float64).numpy()
