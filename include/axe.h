@@ -121,8 +121,10 @@ int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank,
  *
  *   A : logical shape (M, K);  B : logical shape (K, N);  C : logical shape (M, N); each with its
  *       layout on the memory axis `mem_axis`, addresses in elements of the tensor's dtype.
- *   in_dtype  : AXE_BF16 (2 bytes) or AXE_FP8_E4M3 (1 byte, OCP e4m3: max 448, no inf).
- *   out_dtype : AXE_F32 or AXE_BF16 (round to nearest even from the fp32 accumulator).
+ *   in_dtype  : AXE_BF16 (2 bytes), AXE_F16 (IEEE binary16; the fused MoE layer of Sec. 4.1 is an FP16
+ *               layer) or AXE_FP8_E4M3 (1 byte, OCP e4m3: max 448, no inf).
+ *   out_dtype : AXE_F32, or the 16-bit type that goes with the inputs -- AXE_BF16 for bf16 and fp8 inputs,
+ *               AXE_F16 for fp16 inputs (round to nearest even from the fp32 accumulator).
  *   d_scale_a, d_scale_b : both NULL, or DEVICE arrays of scale_dtype, row-major (ceil(M/sb), ceil(K/sb))
  *       and (ceil(N/sb), ceil(K/sb)) with sb = scale_block (must be 128):
  *       C[i][j] = sum_kb sA[i/sb][kb] * sB[j/sb][kb] * sum_{k in block kb} A[i][k] B[k][j]
@@ -134,8 +136,10 @@ int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank,
  * Supported family (else AXE_EUNSUPPORTED): after canonicalisation A and B have unit stride
  * along k and C has unit stride along j (A row-major, B column-major, C row-major, any leading
  * dimensions that are multiples of 16 bytes, any offsets that keep 16-byte alignment); K a
- * multiple of 16 bytes' worth of elements.  d_C must not overlap d_A or d_B. */
-enum { AXE_BF16 = 1, AXE_FP8_E4M3 = 2, AXE_F32 = 3 };
+ * multiple of 16 bytes' worth of elements.  For the 256 x 256 tile with 16-bit inputs, A and B may also be
+ * stored in blocks (Sec. 3.3, a tile product): along k the grouped form (K/64, s)(64, 1), along the other
+ * dimension (R/rb, S)(rb, pitch) with rb = 256 x 2^n.  d_C must not overlap d_A or d_B. */
+enum { AXE_BF16 = 1, AXE_FP8_E4M3 = 2, AXE_F32 = 3, AXE_F16 = 4 };
 
 typedef struct {
   int64_t      M, N, K;
@@ -179,7 +183,7 @@ int axe_gemm_tile(const axe_gemm_desc_t* g);
  *                    (a router writes them on the device): the kernel clamps each entry to [0, M], so
  *                    no access leaves the buffers whatever they hold; entries that decrease give
  *                    unspecified values in C.
- * Supported family (else AXE_EUNSUPPORTED): bf16 inputs, bf16 output; A and C row-major, each B[e]
+ * Supported family (else AXE_EUNSUPPORTED): bf16 inputs and output, or fp16 inputs and output; A and C row-major, each B[e]
  * column-major (unit stride along k) with one pitch for all e and a constant stride between groups
  * (the grouped form of B by (G, K, N) has one iter per block); leading dimensions, offsets and the group
  * stride multiples of 16 bytes; N a multiple of 256, K a multiple of 64.
@@ -188,7 +192,7 @@ int axe_gemm_tile(const axe_gemm_desc_t* g);
 typedef struct {
   int64_t      M, N, K;
   int32_t      G;
-  int32_t      in_dtype, out_dtype;      /* AXE_BF16, AXE_BF16 */
+  int32_t      in_dtype, out_dtype;      /* both AXE_BF16, or both AXE_F16 */
   axe_layout_t A, B, C;
   int32_t      mem_axis;
   int64_t      a_elems, b_elems, c_elems;

@@ -15,7 +15,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libaxe_hip.so")
 
 AXE_OK, AXE_EINVAL, AXE_ESHAPE, AXE_EALIAS, AXE_ERANGE, AXE_EUNSUPPORTED, AXE_EHIP, AXE_ENOFORM = 0, -1, -2, -3, -4, -5, -6, -7
-AXE_BF16, AXE_FP8_E4M3, AXE_F32 = 1, 2, 3
+AXE_BF16, AXE_FP8_E4M3, AXE_F32, AXE_F16 = 1, 2, 3, 4
 AXE_TILE_AUTO, AXE_TILE_64x64x32, AXE_TILE_256x256x64, AXE_TILE_256x224x64 = 0, 1, 2, 3
 (AXE_DESC_A_G2L_THREADS, AXE_DESC_B_G2L_THREADS, AXE_DESC_A_LDS, AXE_DESC_B_LDS, AXE_DESC_A_OPERAND,
  AXE_DESC_B_OPERAND, AXE_DESC_ACC, AXE_DESC_C_STORE) = range(8)

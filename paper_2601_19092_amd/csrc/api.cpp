@@ -475,13 +475,18 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
     set_error("axe_gemm: M, N, K must be positive");
     return AXE_EINVAL;
   }
-  if (g->in_dtype != AXE_BF16 && g->in_dtype != AXE_FP8_E4M3) {
+  if (g->in_dtype != AXE_BF16 && g->in_dtype != AXE_FP8_E4M3 && g->in_dtype != AXE_F16) {
     set_error("axe_gemm: in_dtype %d unknown", g->in_dtype);
     return AXE_EINVAL;
   }
-  if (g->out_dtype != AXE_F32 && g->out_dtype != AXE_BF16) {
+  if (g->out_dtype != AXE_F32 && g->out_dtype != AXE_BF16 && g->out_dtype != AXE_F16) {
     set_error("axe_gemm: out_dtype %d unknown", g->out_dtype);
     return AXE_EINVAL;
+  }
+  const bool f16 = g->in_dtype == AXE_F16;
+  if (g->out_dtype != AXE_F32 && (g->out_dtype == AXE_F16) != f16) {
+    set_error("axe_gemm: a 16-bit output has the type that goes with the inputs (fp16 for fp16, bf16 for bf16 and fp8)");
+    return AXE_EUNSUPPORTED;
   }
   const bool fp8 = g->in_dtype == AXE_FP8_E4M3;
   const int eb = fp8 ? 1 : 2, ob = g->out_dtype == AXE_F32 ? 4 : 2;
@@ -557,14 +562,15 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   P.args.scale_b = (const float*)g->d_scale_b;
   P.args.scale_e8m0 = g->d_scale_a && g->scale_dtype == AXE_SCALE_E8M0;
   P.args.nkb = (int32_t)((g->K + 127) / 128);
-  P.args.out_bf16 = g->out_dtype == AXE_BF16;
+  P.args.out_bf16 = g->out_dtype != AXE_F32;
+  P.args.f16 = f16;
   const int64_t bk = fp8 ? 128 : 64;
   // the large-tile kernels address a tile's 256 rows through 32-bit buffer offsets
   const bool pitch_ok = 256 * lda * eb < (int64_t(1) << 31) && 256 * ldb * eb < (int64_t(1) << 31);
   const bool big_common = (g->M % 256 == 0) && (g->K % bk == 0) && (ldc % 8 == 0) && P.args.out_bf16 && pitch_ok;
   const bool big_ok = big_common && (g->N % 256 == 0);
   // bf16 only: 224 columns per tile (7 fragments per wave instead of 8)
-  const bool n224_ok = big_common && !fp8 && (g->N % 224 == 0);
+  const bool n224_ok = big_common && !fp8 && !f16 && (g->N % 224 == 0);
   int tile = g->tile_hint;
   if (blocked) {
     if (fp8 || !big_ok || !block_ok(opa) || !block_ok(opb) || (tile != AXE_TILE_AUTO && tile != AXE_TILE_256x256x64)) {
@@ -700,9 +706,11 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     set_error("%s: M, N, K, G must be positive", fn);
     return AXE_EINVAL;
   }
-  if (g->in_dtype != AXE_BF16 || g->out_dtype != AXE_BF16) {
-    set_error("%s: bf16 inputs and bf16 output only", fn);
-    return g->in_dtype == AXE_FP8_E4M3 || g->out_dtype == AXE_F32 ? AXE_EUNSUPPORTED : AXE_EINVAL;
+  if (!((g->in_dtype == AXE_BF16 && g->out_dtype == AXE_BF16) || (g->in_dtype == AXE_F16 && g->out_dtype == AXE_F16))) {
+    set_error("%s: bf16 inputs with bf16 output, or fp16 inputs with fp16 output", fn);
+    const bool known = (g->in_dtype >= AXE_BF16 && g->in_dtype <= AXE_F16 && g->in_dtype != AXE_F32) &&
+                       (g->out_dtype == AXE_BF16 || g->out_dtype == AXE_F32 || g->out_dtype == AXE_F16);
+    return known ? AXE_EUNSUPPORTED : AXE_EINVAL;
   }
   int64_t lda, ldb, ldc, ldg, oa, ob, oc;
   Operand2D opb;
@@ -762,6 +770,7 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
   a.M = g->M, a.N = g->N, a.K = g->K;
   a.lda = lda, a.ldb = ldb, a.ldc = ldc, a.ldg = ldg;
   a.out_bf16 = 1;
+  a.f16 = g->in_dtype == AXE_F16;
   a.grid_m = 0;
   a.grid_n = (int32_t)(g->N / 256);
   a.tile_n = 256;

@@ -79,8 +79,23 @@ __device__ __forceinline__ bf16x8 lds_read(lds_u8 p) { return *(__attribute__((a
 // registers over both halves and moves fragments between them around every MFMA.  No two MFMAs on
 // the same accumulator are closer than 64 instructions, so the hardware's dependent-issue rules
 // need no software padding here; the epilogue pads before it reads the accumulators.
+// F16: the operands are IEEE binary16 instead of bf16 (same fragment layout, same rate); fragments are
+// handled as 16 raw bytes either way.
+template <bool F16>
 __device__ __forceinline__ void mfma_16x16x32(f32x4& acc, bf16x8 a, bf16x8 b) {
-  asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  if constexpr (F16) asm volatile("v_mfma_f32_16x16x32_f16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+  else asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc) : "v"(a), "v"(b));
+}
+// two fp32 -> two 16-bit values of the output type, round to nearest even
+template <bool F16>
+__device__ __forceinline__ uint32_t pack16(float lo, float hi) {
+  if constexpr (F16) {
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    const f16x2 v = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+  } else {
+    return pack_bf16(lo, hi);
+  }
 }
 }  // namespace
 
@@ -168,7 +183,7 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 // projections interleaved in runs of 16 rows (the host accepts only that layout), so that fragment pair
 // (j, j + 1) of a wave is (gate, up) of the same 16 output columns in the same lanes; the tile stores
 // silu(gate) * up, half as wide as the product.
-template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false>
+template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
   constexpr int NJ = NB / 32;                                      // fragments per wave along N
@@ -346,7 +361,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   };
   auto store_fragment = [&](int i, int j) __attribute__((always_inline)) {
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
-    const u32x2 d = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
+    const u32x2 d = {pack16<F16>(acc[i][j][0], acc[i][j][1]), pack16<F16>(acc[i][j][2], acc[i][j][3])};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
 #pragma unroll
@@ -359,10 +374,10 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   // Half as many store instructions and write requests; 64 contiguous bytes per row and instruction.
   const int c_voff2 = (int)((fr * g.ldc + ((fq & 1) ? 16 + 4 * (fq - 1) : 4 * fq)) * 2);
   auto store_fragment_pair = [&](int i, int j) __attribute__((always_inline)) {
-    const auto lo = __builtin_amdgcn_permlane16_swap(pack_bf16(acc[i][j][0], acc[i][j][1]),
-                                                     pack_bf16(acc[i][j + 1][0], acc[i][j + 1][1]), false, false);
-    const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16(acc[i][j][2], acc[i][j][3]),
-                                                     pack_bf16(acc[i][j + 1][2], acc[i][j + 1][3]), false, false);
+    const auto lo = __builtin_amdgcn_permlane16_swap(pack16<F16>(acc[i][j][0], acc[i][j][1]),
+                                                     pack16<F16>(acc[i][j + 1][0], acc[i][j + 1][1]), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(pack16<F16>(acc[i][j][2], acc[i][j][3]),
+                                                     pack16<F16>(acc[i][j + 1][2], acc[i][j + 1][3]), false, false);
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
@@ -382,8 +397,8 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
         const float gate = acc[i][j + 2 * q][e], up = acc[i][j + 2 * q + 1][e];
         h[q][e] = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
       }
-    const auto lo = __builtin_amdgcn_permlane16_swap(pack_bf16(h[0][0], h[0][1]), pack_bf16(h[1][0], h[1][1]), false, false);
-    const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16(h[0][2], h[0][3]), pack_bf16(h[1][2], h[1][3]), false, false);
+    const auto lo = __builtin_amdgcn_permlane16_swap(pack16<F16>(h[0][0], h[0][1]), pack16<F16>(h[1][0], h[1][1]), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(pack16<F16>(h[0][2], h[0][3]), pack16<F16>(h[1][2], h[1][3]), false, false);
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 16);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
@@ -421,7 +436,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     for (int i = 0; i < 8; ++i) {
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
-        mfma_16x16x32(acc[i][j], fb[CUR][j], fa[i]);
+        mfma_16x16x32<F16>(acc[i][j], fb[CUR][j], fa[i]);
         __builtin_amdgcn_sched_barrier(0);
         if (i < 4 && (j == 1 || j == 5) && 2 * i + (j == 5) < NJ)
           fb[NXT][2 * i + (j == 5)] = lds_read(pb + (2 * i + (j == 5)) * 16 * kRow);
@@ -535,6 +550,10 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256x224_kernel(GemmArgs g) {
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_blocked_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true>(g); }
+// IEEE binary16 inputs and output: the dense kernel (plain or blocked operands) and the grouped ones
+__global__ __launch_bounds__(256, 1) void gemm_f16_256_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true, false, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, true>(g); }
 
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -544,7 +563,9 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
   unsigned nwg = (unsigned)(chain ? cus : ntiles);
   const bool blocked = g.a_kstep != kRow || g.b_kstep != kRow || g.a_blk_stride != kTile * g.lda || g.b_blk_stride != g.tile_n * g.ldb;
-  if (g.tile_n == 224)
+  if (g.f16)
+    hipLaunchKernelGGL(gemm_f16_256_kernel, dim3(nwg), dim3(256), 0, s, g);
+  else if (g.tile_n == 224)
     hipLaunchKernelGGL(gemm_bf16_256x224_kernel, dim3(nwg), dim3(256), 0, s, g);
   else if (blocked)
     hipLaunchKernelGGL(gemm_bf16_256_blocked_kernel, dim3(nwg), dim3(256), 0, s, g);
@@ -565,8 +586,12 @@ hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
   int64_t nwg = chain ? std::max<int64_t>(cus, (worst + 63) / 64) : worst;
   nwg = (nwg + 7) / 8 * 8;                                         // the tile sequence is cut into 8 parts, one per XCD
   if (nwg > 0x7fffffff) return hipErrorInvalidValue;
-  if (g.gated)
+  if (g.gated && g.f16)
+    hipLaunchKernelGGL(gemm_f16_256_grouped_gated_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  else if (g.gated)
     hipLaunchKernelGGL(gemm_bf16_256_grouped_gated_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  else if (g.f16)
+    hipLaunchKernelGGL(gemm_f16_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
   else
     hipLaunchKernelGGL(gemm_bf16_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
   return hipGetLastError();

@@ -33,7 +33,13 @@ __device__ __forceinline__ uint16_t f32_to_bf16_rne(float f) {
   return __builtin_bit_cast(uint16_t, h);
 }
 
-template <bool FP8>
+__device__ __forceinline__ uint16_t f32_to_f16_rne(float f) {
+  _Float16 h = (_Float16)f;
+  return __builtin_bit_cast(uint16_t, h);
+}
+
+// F16 (with FP8 = false): 16-bit inputs and a 16-bit output are IEEE binary16 instead of bf16
+template <bool FP8, bool F16 = false>
 __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
   constexpr int EB = FP8 ? 1 : 2;             // element bytes
   constexpr int ROWB = FP8 ? 128 : 64;        // bytes of K per LDS row
@@ -103,7 +109,13 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
       for (int i = 0; i < 2; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j)
-          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          if constexpr (F16) {
+            typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, fb[j]), __builtin_bit_cast(f16x8, fa[i]),
+                                                               acc[i][j], 0, 0, 0);
+          } else {
+            acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb[j], fa[i], acc[i][j], 0, 0, 0);
+          }
     } else {
       i32x8 fa[2], fb[2];
 #pragma unroll
@@ -162,7 +174,7 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
         uint16_t* C = (uint16_t*)g.C + m * g.ldc + n;
         uint16_t h[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) h[e] = f32_to_bf16_rne(acc[i][j][e]);
+        for (int e = 0; e < 4; ++e) h[e] = F16 ? f32_to_f16_rne(acc[i][j][e]) : f32_to_bf16_rne(acc[i][j][e]);
         if (n + 3 < g.N && ((g.ldc & 3) == 0)) {
           *(uint2*)C = uint2{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16)};
         } else {
@@ -187,6 +199,8 @@ hipError_t launch_gemm_small(const GemmArgs& g, bool fp8, hipStream_t s) {
   dim3 grid((unsigned)((g.N + 63) / 64), (unsigned)((g.M + 63) / 64));
   if (fp8)
     hipLaunchKernelGGL(gemm_small_kernel<true>, grid, dim3(256), 0, s, g);
+  else if (g.f16)
+    hipLaunchKernelGGL((gemm_small_kernel<false, true>), grid, dim3(256), 0, s, g);
   else
     hipLaunchKernelGGL(gemm_small_kernel<false>, grid, dim3(256), 0, s, g);
   return hipGetLastError();

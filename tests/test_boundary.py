@@ -137,6 +137,11 @@ def test_gemm_family_matching_and_errors():
     assert _tile_rc(_gemm_desc(K=250, A=W.row_major_spec(256, 250), Bs=W.col_major_spec(250, 256))) == B.AXE_EUNSUPPORTED
     assert _tile_rc(_gemm_desc(a_elems=100)) == B.AXE_ERANGE
     assert _tile_rc(_gemm_desc(in_dtype=7)) == B.AXE_EINVAL
+    # fp16 inputs go with an fp16 (or fp32) output, bf16 inputs with bf16 (or fp32)
+    assert _tile_rc(_gemm_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_F16)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_BF16)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(_gemm_desc(in_dtype=B.AXE_BF16, out_dtype=B.AXE_F16)) == B.AXE_EUNSUPPORTED
     assert _tile_rc(_gemm_desc(M=0)) == B.AXE_EINVAL
     # pitched operands (leading dimension larger than the row) are in the family
     pitched = W.spec([(256, 264, "m"), (256, 1, "m")])
@@ -198,6 +203,8 @@ def test_grouped_gemm_family_matching_and_errors():
     assert chk(_grouped_desc(N=500, Bs=W.spec([(4, 500 * 256, "m"), (256, 1, "m"), (500, 256, "m")]))) == B.AXE_EUNSUPPORTED
     assert chk(_grouped_desc(K=96, A=W.row_major_spec(1000, 96), Bs=W.spec([(4, 512 * 96, "m"), (96, 1, "m"), (512, 96, "m")]))) \
         == B.AXE_EUNSUPPORTED
+    assert chk(_grouped_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_F16)) == B.AXE_OK
+    assert chk(_grouped_desc(in_dtype=B.AXE_F16)) == B.AXE_EUNSUPPORTED                 # fp16 in, bf16 out
     assert chk(_grouped_desc(in_dtype=B.AXE_FP8_E4M3)) == B.AXE_EUNSUPPORTED
     assert chk(_grouped_desc(out_dtype=B.AXE_F32)) == B.AXE_EUNSUPPORTED
     assert chk(_grouped_desc(in_dtype=9)) == B.AXE_EINVAL

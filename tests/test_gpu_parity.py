@@ -260,6 +260,15 @@ def test_relayout_config2_full_size(kind):
 
 
 # ----------------------------------------------------------------------------- GEMM
+IN_DT = {"bf16": B.AXE_BF16, "f16": B.AXE_F16, "fp8": B.AXE_FP8_E4M3}
+OUT_DT = {"f32": B.AXE_F32, "bf16": B.AXE_BF16, "f16": B.AXE_F16}
+ORACLE_DT = {"bf16": R.AXE_BF16, "f16": R.AXE_F16, "fp8": R.AXE_FP8_E4M3}
+
+
+def decode16(words: np.ndarray, dtype: str) -> np.ndarray:
+    return R.f16_to_f64(words) if dtype == "f16" else R.bf16_to_f64(words)
+
+
 def run_gemm(g: W.GemmInputs, tile=B.AXE_TILE_AUTO, device_axis=False, lda=None, ldb=None, ldc=None):
     """Launches axe_gemm on the inputs; returns C decoded to fp64 (M, N)."""
     As, Bs, Cs = W.gemm_specs(g, device_axis=device_axis, shard=3)
@@ -279,15 +288,14 @@ def run_gemm(g: W.GemmInputs, tile=B.AXE_TILE_AUTO, device_axis=False, lda=None,
     dC = torch.zeros(g.M * ldc_, dtype=out_t, device="cuda")
     sa = torch.from_numpy(g.scale_a).cuda() if g.scale_a is not None else None
     sb = torch.from_numpy(g.scale_b).cuda() if g.scale_b is not None else None
-    desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16 if g.dtype == "bf16" else B.AXE_FP8_E4M3,
-                      B.AXE_F32 if g.out_dtype == "f32" else B.AXE_BF16,
+    desc = B.GemmDesc(g.M, g.N, g.K, IN_DT[g.dtype], OUT_DT[g.out_dtype],
                       B.Layout(As, axes), B.Layout(Bs, axes), B.Layout(Cs, axes),
                       a.size, b.size, g.M * ldc_, sa, sb, tile_hint=tile,
                       scale_dtype=B.AXE_SCALE_E8M0 if g.scale_dtype == "e8m0" else B.AXE_SCALE_F32)
     B.axe_gemm(desc, dA, dB, dC)
     torch.cuda.synchronize()
     c = dC.cpu().numpy().reshape(g.M, ldc_)[:, :g.N]
-    return c.astype(np.float64) if g.out_dtype == "f32" else R.bf16_to_f64(c.view(np.uint16))
+    return c.astype(np.float64) if g.out_dtype == "f32" else decode16(c.view(np.uint16), g.out_dtype)
 
 
 def gemm_desc_only(g: W.GemmInputs, tile=B.AXE_TILE_AUTO):
@@ -306,9 +314,8 @@ def oracle_scales(g: W.GemmInputs):
 
 
 def oracle_gemm(g: W.GemmInputs, rows=None, cols=None):
-    dt = R.AXE_BF16 if g.dtype == "bf16" else R.AXE_FP8_E4M3
     sa, sb = oracle_scales(g)
-    return R.gemm_ref(g.a_mk, g.b_nk.T, dt, sa, sb, rows=rows, cols=cols)
+    return R.gemm_ref(g.a_mk, g.b_nk.T, ORACLE_DT[g.dtype], sa, sb, rows=rows, cols=cols)
 
 
 def check_gemm(c, ref, tol, tile=128):
@@ -536,7 +543,7 @@ def test_gemm_is_bitwise_repeatable(which):
 
 
 # ----------------------------------------------------------------------------- grouped GEMM (MoE)
-SENTINEL = 0x7FC1          # a bf16 NaN pattern: rows of C that belong to no group must keep it
+SENTINEL = 0x7FC1          # a NaN pattern in bf16 and in binary16: rows of C that belong to no group must keep it
 
 
 def run_grouped(g: W.GroupedGemmInputs, lda=None, ldb=None, ldg=None, ldc=None, rows_on_device=None):
@@ -551,14 +558,15 @@ def run_grouped(g: W.GroupedGemmInputs, lda=None, ldb=None, ldg=None, ldc=None, 
     dA, dB = dev(a.reshape(-1)), dev(b.reshape(-1))
     dC = torch.full((g.M * ldc_,), SENTINEL, dtype=torch.int16, device="cuda")
     dR = torch.from_numpy(np.ascontiguousarray(g.group_rows if rows_on_device is None else rows_on_device, dtype=np.int32)).cuda()
-    desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(Bs), B.Layout(Cs), a.size, b.size, g.M * ldc_)
+    desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(Bs), B.Layout(Cs), a.size, b.size, g.M * ldc_,
+                             in_dtype=IN_DT[g.dtype], out_dtype=OUT_DT[g.dtype])
     B.axe_gemm_grouped(desc, dA, dB, dC, dR)
     torch.cuda.synchronize()
     raw = dC.cpu().numpy().view(np.uint16).reshape(g.M, ldc_)
     if ldc_ > g.N:
         assert (raw[:, g.N:] == SENTINEL).all(), "the padding of C was written"
     raw = raw[:, :g.N]
-    return R.bf16_to_f64(raw), raw
+    return decode16(raw, g.dtype), raw
 
 
 def check_grouped(g: W.GroupedGemmInputs, c, raw, ref):
@@ -851,3 +859,56 @@ def test_entry_points_can_be_captured_in_a_hip_graph():
             graph.replay()
             torch.cuda.synchronize()
             assert torch.equal(dH, h) and torch.equal(dY, y) and torch.equal(dZ, z), (rep, rows)
+
+
+# ----------------------------------------------------------------------------- IEEE binary16 (the paper's MoE layer is an FP16 layer)
+F16_TOL = 2e-3            # output rounding 2^-12 / sqrt(3) dominates (bf16: 2^-9 / sqrt(3)); a correct kernel lands near 2e-4
+
+
+@pytest.mark.parametrize("M,N,K,out", [(64, 64, 32, "f16"), (200, 136, 96, "f32"), (65, 63, 8, "f16"), (256, 256, 64, "f16"),
+                                       (512, 768, 192, "f16"), (768, 256, 1024, "f16")])
+def test_gemm_f16(M, N, K, out):
+    g = W.gemm_f16(M, N, K, 98, std_b=K ** -0.5, out_dtype=out)
+    c = run_gemm(g)
+    check_gemm(c, oracle_gemm(g), F16_TOL)
+
+
+def test_gemm_f16_chained_and_blocked():
+    g = W.gemm_f16(4352, 4096, 512, 99, std_b=512 ** -0.5)
+    c = run_gemm(g)
+    rows = np.array([0, 255, 256, 4351])
+    assert R.rel_frobenius(c[rows], oracle_gemm(g, rows, None)) <= F16_TOL
+    cols = np.array([0, 4095])
+    assert R.rel_frobenius(c[:, cols], oracle_gemm(g, None, cols)) <= F16_TOL
+    # blocked operands: same kernel, same order of operations, same bits
+    dA, dB = dev(W.pack_blocked(g.a_mk)), dev(W.pack_blocked(g.b_nk))
+    dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
+    desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_F16, B.AXE_F16, B.Layout(W.blocked_a_spec(g.M, g.K)), B.Layout(W.blocked_b_spec(g.K, g.N)),
+                      B.Layout(W.row_major_spec(g.M, g.N)), g.M * g.K, g.N * g.K, g.M * g.N)
+    B.axe_gemm(desc, dA, dB, dC)
+    torch.cuda.synchronize()
+    assert np.array_equal(R.f16_to_f64(dC.cpu().numpy().view(np.uint16).reshape(g.M, g.N)), c)
+
+
+def test_gemm_grouped_f16_plain_and_gated():
+    off = [0, 300, 520, 1300, 1301, 2000]
+    N, K = 768, 512
+    g = W.gemm_grouped_bf16(off, N, K, 100, std_b=2.0 * K ** -0.5, dtype="f16")
+    bl = g.b_gnk.transpose(0, 2, 1)
+    P = R.gemm_grouped_ref(g.a_mk, bl, off, R.AXE_F16)
+    c, raw = run_grouped(g)
+    owned = ~np.isnan(P[:, 0])
+    assert R.rel_frobenius(c[owned], P[owned]) <= F16_TOL
+    check_grouped(g, c, raw, P)
+    # gated
+    img = W.pack_blocked(W.pack_gate_up(g.b_gnk))
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
+    dC = torch.full((g.M * (N // 2),), SENTINEL, dtype=torch.int16, device="cuda")
+    dR = torch.from_numpy(g.group_rows).cuda()
+    desc = B.GroupedGemmDesc(g.M, N, K, g.G, B.Layout(W.row_major_spec(g.M, K)), B.Layout(W.gated_b_spec(K, N, g.G, True)),
+                             B.Layout(W.row_major_spec(g.M, N // 2)), g.M * K, img.size, g.M * (N // 2),
+                             in_dtype=B.AXE_F16, out_dtype=B.AXE_F16, epilogue=B.AXE_EPI_SWIGLU)
+    B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+    torch.cuda.synchronize()
+    h = R.f16_to_f64(dC.cpu().numpy().view(np.uint16).reshape(g.M, N // 2))
+    assert R.rel_frobenius(h[owned], R.swiglu_ref(P)[owned]) <= F16_TOL
