@@ -149,15 +149,16 @@ def bench_transpose(steps, warmup, n_pairs=4):
     return r
 
 
-def bench_grouped(steps, warmup, tokens=4096):
+def bench_grouped(steps, warmup, tokens=4096, dtype="f16"):
     """The two grouped GEMMs of an MoE layer (hidden 2048, expert intermediate 768, 128 experts, 8 per token) at
-    `tokens` tokens: routed rows sorted by expert, offsets on the device.  Weights as plain column-major
+    `tokens` tokens, in fp16 like the paper's layer: routed rows sorted by expert, offsets on the device.  Weights as plain column-major
     matrices and pre-packed into contiguous 256 x 64 blocks by axe_relayout (untimed, as a server would do once)."""
     import torch
     from paper_2601_19092_amd import binding as B
     from paper_2601_19092_amd import workloads as W
-    out = {"tokens": tokens, "experts": W.MOE_EXPERTS, "experts_per_token": W.MOE_TOPK}
-    for name, g in (("gemm1_gate_up", W.moe_gemm1(tokens)), ("gemm2_down", W.moe_gemm2(tokens))):
+    out = {"tokens": tokens, "experts": W.MOE_EXPERTS, "experts_per_token": W.MOE_TOPK, "dtype": dtype}
+    dt = B.AXE_F16 if dtype == "f16" else B.AXE_BF16
+    for name, g in (("gemm1_gate_up", W.moe_gemm1(tokens, dtype=dtype)), ("gemm2_down", W.moe_gemm2(tokens, dtype=dtype))):
         As, Bs, Cs = W.grouped_gemm_specs(g)
         Bblk = W.blocked_b_spec(g.K, g.N, G=g.G)
         dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_gnk.reshape(-1))
@@ -171,7 +172,8 @@ def bench_grouped(steps, warmup, tokens=4096):
         nbytes = 2.0 * (int((sizes > 0).sum()) * g.N * g.K + g.M * g.K + g.M * g.N)
         r = {"M": g.M, "N": g.N, "K": g.K, "tiles": int(np.ceil(sizes / 256).sum()) * (g.N // 256), "algorithmic_bytes": nbytes}
         for label, spec_b, buf in (("plain", Bs, dB), ("blocked", Bblk, dBblk)):
-            desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(spec_b), B.Layout(Cs), g.M * g.K, g.b_gnk.size, g.M * g.N)
+            desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(spec_b), B.Layout(Cs), g.M * g.K, g.b_gnk.size, g.M * g.N,
+                                     in_dtype=dt, out_dtype=dt)
             wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, buf, dC, dR), steps, warmup)
             r[label] = {"kernel_ms": devms, "tflops": flops / (devms * 1e-3) / 1e12, "GBps": nbytes / (devms * 1e-3) / 1e9}
         if name == "gemm1_gate_up":
@@ -181,14 +183,14 @@ def bench_grouped(steps, warmup, tokens=4096):
             assert np.array_equal(dBblk[:g.N * g.K].cpu().numpy().view(np.uint16), W.pack_blocked(W.pack_gate_up(g.b_gnk[:1]))[0])
             dH = torch.zeros(g.M * (g.N // 2), dtype=torch.int16, device="cuda")
             desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(Bg), B.Layout(W.row_major_spec(g.M, g.N // 2)),
-                                     g.M * g.K, g.b_gnk.size, g.M * (g.N // 2), epilogue=B.AXE_EPI_SWIGLU)
+                                     g.M * g.K, g.b_gnk.size, g.M * (g.N // 2), in_dtype=dt, out_dtype=dt, epilogue=B.AXE_EPI_SWIGLU)
             wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dBblk, dH, dR), steps, warmup)
             r["blocked_gated"] = {"kernel_ms": devms, "tflops": flops / (devms * 1e-3) / 1e12,
                                   "GBps": (nbytes - g.M * g.N) / (devms * 1e-3) / 1e9}
             log(f"[bench]   with the gated activation fused (C = silu(gate) * up, {g.N // 2} wide): {devms*1e3:.0f} us")
             del dH
         out[name] = r
-        log(f"[bench] grouped GEMM {name} {tokens} tokens (M={g.M} N={g.N} K={g.K}, {g.G} experts, {r['tiles']} tiles): "
+        log(f"[bench] grouped {dtype} GEMM {name} {tokens} tokens (M={g.M} N={g.N} K={g.K}, {g.G} experts, {r['tiles']} tiles): "
             f"plain weights {r['plain']['kernel_ms']*1e3:.0f} us = {r['plain']['tflops']:.0f} TFLOP/s, {r['plain']['GBps']:.0f} GB/s; "
             f"blocked weights {r['blocked']['kernel_ms']*1e3:.0f} us = {r['blocked']['tflops']:.0f} TFLOP/s, {r['blocked']['GBps']:.0f} GB/s")
         del dA, dB, dBblk, dC

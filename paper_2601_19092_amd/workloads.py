@@ -139,15 +139,15 @@ def gemm_grouped_bf16(group_rows, N: int, K: int, seed: int, M: Optional[int] = 
 MOE_HIDDEN, MOE_INTER, MOE_EXPERTS, MOE_TOPK = 2048, 768, 128, 8
 
 
-def moe_gemm1(tokens: int, seed: int = SEED_BASE + 11) -> GroupedGemmInputs:
+def moe_gemm1(tokens: int, seed: int = SEED_BASE + 11, dtype: str = "bf16") -> GroupedGemmInputs:
     """First grouped GEMM of the layer: routed tokens (tokens * topk rows of the hidden size) against each
     expert's gate and up projections side by side (N = 2 * intermediate)."""
-    return gemm_grouped_bf16(moe_group_rows(tokens, MOE_EXPERTS, MOE_TOPK, seed), 2 * MOE_INTER, MOE_HIDDEN, seed + 1)
+    return gemm_grouped_bf16(moe_group_rows(tokens, MOE_EXPERTS, MOE_TOPK, seed), 2 * MOE_INTER, MOE_HIDDEN, seed + 1, dtype=dtype)
 
 
-def moe_gemm2(tokens: int, seed: int = SEED_BASE + 11) -> GroupedGemmInputs:
+def moe_gemm2(tokens: int, seed: int = SEED_BASE + 11, dtype: str = "bf16") -> GroupedGemmInputs:
     """Second grouped GEMM: the activations (intermediate size) against each expert's down projection."""
-    return gemm_grouped_bf16(moe_group_rows(tokens, MOE_EXPERTS, MOE_TOPK, seed), MOE_HIDDEN, MOE_INTER, seed + 2)
+    return gemm_grouped_bf16(moe_group_rows(tokens, MOE_EXPERTS, MOE_TOPK, seed), MOE_HIDDEN, MOE_INTER, seed + 2, dtype=dtype)
 
 
 def relayout_words(rows: int, cols: int, seed: int, kind: str = "uniform") -> np.ndarray:
