@@ -187,8 +187,8 @@ int axe_gemm_tile(const axe_gemm_desc_t* g);
  * column-major (unit stride along k) with one pitch for all e and a constant stride between groups
  * (the grouped form of B by (G, K, N) has one iter per block); leading dimensions, offsets and the group
  * stride multiples of 16 bytes; N a multiple of 256, K a multiple of 64.
- * One launch: tiles are (group, 256 rows of it, 256 columns), found on the device from d_group_rows;
- * nothing is allocated and no scratch memory is used. */
+ * One launch, work found on the device from d_group_rows; nothing is allocated and no scratch memory
+ * is used. */
 typedef struct {
   int64_t      M, N, K;
   int32_t      G;
@@ -197,7 +197,15 @@ typedef struct {
   int32_t      mem_axis;
   int64_t      a_elems, b_elems, c_elems;
   int32_t      epilogue;                 /* AXE_EPI_NONE or AXE_EPI_SWIGLU */
+  int32_t      kernel_hint;              /* AXE_GROUPED_AUTO, or one of the two kernels below */
 } axe_gemm_grouped_desc_t;
+
+/* Two kernels serve the same family.  AXE_GROUPED_TILES: 256 x 256 tiles of the chained GEMM pipeline, for
+ * groups of hundreds of rows.  AXE_GROUPED_STREAM: one workgroup per (group, 128 rows of B), the group's
+ * rows (64 at a time) held in registers while its weights stream by once -- for the few rows per group of
+ * an MoE layer at decode batch sizes, where the time is that of reading the weights.  AUTO takes the
+ * streaming kernel when M <= 32 G (the host knows M, not the group sizes). */
+enum { AXE_GROUPED_AUTO = 0, AXE_GROUPED_TILES = 1, AXE_GROUPED_STREAM = 2 };
 
 /* AXE_EPI_SWIGLU: the gated activation between the two group GEMMs, fused into the first.  The logical
  * columns [0, N/2) of every B[e] are the gate projection, [N/2, N) the up projection, C is (M, N/2):

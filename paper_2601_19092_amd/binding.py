@@ -22,6 +22,7 @@ AXE_TILE_AUTO, AXE_TILE_64x64x32, AXE_TILE_256x256x64, AXE_TILE_256x224x64 = 0, 
 AXE_MAX_RANK = 8
 AXE_SCALE_F32, AXE_SCALE_E8M0 = 0, 1
 AXE_EPI_NONE, AXE_EPI_SWIGLU = 0, 1
+AXE_GROUPED_AUTO, AXE_GROUPED_TILES, AXE_GROUPED_STREAM = 0, 1, 2
 
 EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
            "axe_last_error", "axe_version", "axe_layout_span", "axe_layout_canonicalize", "axe_layout_gap_condition",
@@ -56,7 +57,8 @@ class axe_gemm_grouped_desc_t(C.Structure):
                 ("in_dtype", C.c_int32), ("out_dtype", C.c_int32),
                 ("A", axe_layout_t), ("B", axe_layout_t), ("C", axe_layout_t),
                 ("mem_axis", C.c_int32),
-                ("a_elems", C.c_int64), ("b_elems", C.c_int64), ("c_elems", C.c_int64), ("epilogue", C.c_int32)]
+                ("a_elems", C.c_int64), ("b_elems", C.c_int64), ("c_elems", C.c_int64), ("epilogue", C.c_int32),
+                ("kernel_hint", C.c_int32)]
 
 
 class AxeError(RuntimeError):
@@ -218,11 +220,12 @@ class GroupedGemmDesc:
 
     def __init__(self, M: int, N: int, K: int, G: int, A: Layout, B: Layout, Cl: Layout, a_elems: int, b_elems: int,
                  c_elems: int, in_dtype: int = AXE_BF16, out_dtype: int = AXE_BF16, mem_axis: str = "m",
-                 epilogue: int = 0):
+                 epilogue: int = 0, kernel_hint: int = 0):
         ma = A.axis(mem_axis)
         assert B.axis(mem_axis) == ma and Cl.axis(mem_axis) == ma, "memory axis must have the same index in A, B, C"
         self.layouts = (A, B, Cl)
-        self.c = axe_gemm_grouped_desc_t(M, N, K, G, in_dtype, out_dtype, A.c, B.c, Cl.c, ma, a_elems, b_elems, c_elems, epilogue)
+        self.c = axe_gemm_grouped_desc_t(M, N, K, G, in_dtype, out_dtype, A.c, B.c, Cl.c, ma, a_elems, b_elems, c_elems, epilogue,
+                                         kernel_hint)
 
 
 def axe_gemm_grouped(desc: GroupedGemmDesc, A_buf, B_buf, C_buf, group_rows, stream=None):

@@ -12,7 +12,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libaxe_hip.so")
 SOURCES = ["api.cpp", "host_layout.cpp", "layout_algebra.cpp", "describe.cpp", "kernels_layout.hip", "kernels_gemm_small.hip",
-           "kernels_gemm_bf16.hip", "kernels_gemm_fp8.hip", "kernels_gemm_fp8_e8m0.hip"]
+           "kernels_gemm_bf16.hip", "kernels_gemm_grouped_stream.hip", "kernels_gemm_fp8.hip", "kernels_gemm_fp8_e8m0.hip"]
 FLAGS = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-x", "hip",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 

@@ -719,6 +719,10 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     set_error("%s: unknown epilogue %d", fn, g->epilogue);
     return AXE_EINVAL;
   }
+  if (g->kernel_hint != AXE_GROUPED_AUTO && g->kernel_hint != AXE_GROUPED_TILES && g->kernel_hint != AXE_GROUPED_STREAM) {
+    set_error("%s: unknown kernel_hint %d", fn, g->kernel_hint);
+    return AXE_EINVAL;
+  }
   const bool gated = g->epilogue == AXE_EPI_SWIGLU;
   const int64_t NC = gated ? g->N / 2 : g->N;                      // columns of C
   if (int rc = grouped_b(&g->B, g->mem_axis, g->G, g->K, g->N, g->b_elems, gated, &ldg, &opb)) return rc;
@@ -791,7 +795,8 @@ int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const vo
                      const int32_t* d_group_rows, void* stream) {
   GemmArgs a;
   if (int rc = plan_gemm_grouped(g, d_A, d_B, d_C, d_group_rows, a, true)) return rc;
-  hipError_t e = launch_gemm_bf16_256_grouped(a, (hipStream_t)stream);
+  const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 32 * (int64_t)g->G);
+  hipError_t e = stream_kernel ? launch_gemm_grouped_stream(a, (hipStream_t)stream) : launch_gemm_bf16_256_grouped(a, (hipStream_t)stream);
   return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm_grouped");
 }
 

@@ -1,0 +1,168 @@
+// Grouped GEMM for few rows per group (an MoE layer at decode batch sizes): bound by streaming the
+// experts' weights from HBM once, not by the matrix cores.
+//
+// The 256 x 256 kernel spends a whole tile (and a whole compute unit) on a group with a handful of
+// rows, and a launch has too few such tiles to keep every HBM channel busy.  Here a workgroup owns one
+// group and 128 rows of its B image (128 columns of C, or 64 with the gated epilogue); each of its four
+// waves owns 32 of them -- two MFMA 16x16x32 operand fragments -- for the whole of K and keeps up to 64
+// rows of the group as four accumulator fragments per B fragment.  Nothing is shared between waves, so
+// there is no LDS and no barrier: the weights go from HBM straight into the MFMA operand registers,
+// each element read once per workgroup, many small workgroups in flight per compute unit.
+//
+// Tile movements as layouts:
+//   HBM -> VGPR (B): lane l of a wave reads, for one 64-wide K-tile, the 16-byte chunks l / 16 and l / 16 + 4
+//                    of row l % 16 of a fragment: with weights stored in 256 x 64 blocks a fragment's
+//                    16 rows x 128 bytes are 2 contiguous KiB (and a workgroup's 128 rows 16 KiB).
+//   HBM -> VGPR (A): the same map on the group's rows (they come from L2: every workgroup of a group
+//                    reads the same few rows); rows the group does not have load as zero (buffer bounds).
+//   MFMA           : operands swapped (B fragment first), so a lane's accumulator fragment holds 4
+//                    consecutive columns of one C row; the k order inside a K-tile (chunks q, q + 4) is
+//                    the same for A and B, which is all the sum needs.
+//   VGPR -> HBM    : 8 bytes per lane and row fragment; rows past the group's end are not stored.
+// Groups with more than 64 rows are handled in passes of 64 (the weights are then read again: the
+// host chooses this kernel only when the average group is small).
+#include <hip/hip_runtime.h>
+
+#include "device_types.h"
+#include "gemm_common.h"
+#include "kernels.h"
+
+namespace axe {
+
+namespace {
+typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
+typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
+
+template <bool F16>
+__device__ __forceinline__ f32x4 mfma16(u32x4 a, u32x4 b, f32x4 c) {
+  if constexpr (F16) {
+    typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+  } else {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+  }
+}
+template <bool F16>
+__device__ __forceinline__ uint32_t pack16s(float lo, float hi) {
+  if constexpr (F16) {
+    typedef __attribute__((ext_vector_type(2))) _Float16 f16x2;
+    const f16x2 v = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(uint32_t, v);
+  } else {
+    return pack_bf16(lo, hi);
+  }
+}
+}  // namespace
+
+template <bool F16, bool GATED>
+__global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
+  const int lane = threadIdx.x & 63;
+  const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
+  const int e = blockIdx.y;                                        // group
+  const int M = (int)g.M;
+  int r0 = g.group_rows[e], r1 = g.group_rows[e + 1];
+  r0 = r0 < 0 ? 0 : (r0 > M ? M : r0);                             // whatever the offsets hold, no access leaves the buffers
+  r1 = r1 < 0 ? 0 : (r1 > M ? M : r1);
+  if (r1 <= r0) return;
+  const int nk = (int)(g.K / 64);
+  const int fr = lane & 15, fq = lane >> 4;
+
+  // this wave's 32 rows of the group's B image: rows brow .. brow + 31 (two fragments)
+  const int brow = (int)blockIdx.x * 128 + w * 32;
+  const int tn = brow >> 8;                                        // 256-row block of the image
+  const int64_t b_off = (int64_t)e * g.ldg + (int64_t)(tn >> g.b_tpb_shift) * g.b_blk_stride +
+                        ((int64_t)(tn & ((1 << g.b_tpb_shift) - 1)) * 256 + (brow & 255)) * g.ldb;
+  const int b_pitch = (int)(g.ldb * 2), b_kstep = g.b_kstep;
+  const __amdgpu_buffer_rsrc_t rb =
+      __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + b_off * 2), 0, 31 * b_pitch + (nk - 1) * b_kstep + 128, 0x00020000);
+  const int b_voff = fr * b_pitch + fq * 16;
+  const int a_pitch = (int)(g.lda * 2);
+  const int a_voff = fr * a_pitch + fq * 16;
+
+  for (int p0 = r0; p0 < r1; p0 += 64) {                           // passes of 64 rows of the group
+    const int rows = r1 - p0 < 64 ? r1 - p0 : 64;
+    const int nfrag = (rows + 15) >> 4;                            // row fragments that hold any row (wave-uniform)
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)p0 * g.lda * 2), 0,
+                                                                        (rows - 1) * a_pitch + (int)g.K * 2, 0x00020000);
+    f32x4 acc[2][4];
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi) acc[f][mi] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // one K-tile (64 elements): per fragment the chunks q (k = 8 q ..) and q + 4 (k = 32 + 8 q ..)
+    u32x4 b[2][2][2], a[2][4][2];                                  // [buffer][fragment][half]
+    auto load = [&](int buf, int kt) __attribute__((always_inline)) {
+#pragma unroll
+      for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+          b[buf][f][h] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, b_voff + f * 16 * b_pitch + h * 64, kt * b_kstep, 0));
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+        if (mi < nfrag) {
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+            a[buf][mi][h] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(ra, a_voff + mi * 16 * a_pitch + h * 64, kt * 128, 0));
+        }
+    };
+    auto multiply = [&](int buf) __attribute__((always_inline)) {
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+        if (mi < nfrag) {
+#pragma unroll
+          for (int h = 0; h < 2; ++h)
+#pragma unroll
+            for (int f = 0; f < 2; ++f) acc[f][mi] = mfma16<F16>(b[buf][f][h], a[buf][mi][h], acc[f][mi]);
+        }
+    };
+    load(0, 0);
+    int kt = 0;
+    for (; kt + 2 <= nk; kt += 2) {                                // two K-tiles per trip, the next one always on its way
+      load(1, kt + 1);
+      multiply(0);
+      if (kt + 2 < nk) load(0, kt + 2);
+      multiply(1);
+    }
+    if (kt < nk) multiply(0);                                      // odd number of K-tiles: the last one was loaded into buffer 0
+
+    // ---- store: lane holds columns 4 q .. 4 q + 3 of row 16 mi + fr for each of its two fragments
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+      const int row = mi * 16 + fr;
+      if (mi < nfrag && row < rows) {
+        if constexpr (GATED) {                                     // fragment 0 = gate, fragment 1 = up of the same 16 outputs
+          float h[4];
+#pragma unroll
+          for (int x = 0; x < 4; ++x) {
+            const float gate = acc[0][mi][x], up = acc[1][mi][x];
+            h[x] = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
+          }
+          uint16_t* c = (uint16_t*)g.C + (int64_t)(p0 + row) * g.ldc + (brow >> 1) + 4 * fq;
+          *(u32x2*)c = u32x2{pack16s<F16>(h[0], h[1]), pack16s<F16>(h[2], h[3])};
+        } else {
+#pragma unroll
+          for (int f = 0; f < 2; ++f) {
+            uint16_t* c = (uint16_t*)g.C + (int64_t)(p0 + row) * g.ldc + brow + f * 16 + 4 * fq;
+            *(u32x2*)c = u32x2{pack16s<F16>(acc[f][mi][0], acc[f][mi][1]), pack16s<F16>(acc[f][mi][2], acc[f][mi][3])};
+          }
+        }
+      }
+    }
+  }
+}
+
+hipError_t launch_gemm_grouped_stream(const GemmArgs& g, hipStream_t s) {
+  const dim3 grid((unsigned)(g.N / 128), (unsigned)g.groups);
+  if (g.f16 && g.gated)
+    hipLaunchKernelGGL((gemm_grouped_stream_kernel<true, true>), grid, dim3(256), 0, s, g);
+  else if (g.f16)
+    hipLaunchKernelGGL((gemm_grouped_stream_kernel<true, false>), grid, dim3(256), 0, s, g);
+  else if (g.gated)
+    hipLaunchKernelGGL((gemm_grouped_stream_kernel<false, true>), grid, dim3(256), 0, s, g);
+  else
+    hipLaunchKernelGGL((gemm_grouped_stream_kernel<false, false>), grid, dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+}  // namespace axe

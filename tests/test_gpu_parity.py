@@ -546,7 +546,7 @@ def test_gemm_is_bitwise_repeatable(which):
 SENTINEL = 0x7FC1          # a NaN pattern in bf16 and in binary16: rows of C that belong to no group must keep it
 
 
-def run_grouped(g: W.GroupedGemmInputs, lda=None, ldb=None, ldg=None, ldc=None, rows_on_device=None):
+def run_grouped(g: W.GroupedGemmInputs, lda=None, ldb=None, ldg=None, ldc=None, rows_on_device=None, kernel=B.AXE_GROUPED_TILES):
     """Launches axe_gemm_grouped; returns (C decoded to fp64, raw C words), both (M, N)."""
     lda_, ldb_, ldc_ = lda or g.K, ldb or g.K, ldc or g.N
     ldg_ = ldg or g.N * ldb_
@@ -559,7 +559,7 @@ def run_grouped(g: W.GroupedGemmInputs, lda=None, ldb=None, ldg=None, ldc=None, 
     dC = torch.full((g.M * ldc_,), SENTINEL, dtype=torch.int16, device="cuda")
     dR = torch.from_numpy(np.ascontiguousarray(g.group_rows if rows_on_device is None else rows_on_device, dtype=np.int32)).cuda()
     desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(Bs), B.Layout(Cs), a.size, b.size, g.M * ldc_,
-                             in_dtype=IN_DT[g.dtype], out_dtype=OUT_DT[g.dtype])
+                             in_dtype=IN_DT[g.dtype], out_dtype=OUT_DT[g.dtype], kernel_hint=kernel)
     B.axe_gemm_grouped(desc, dA, dB, dC, dR)
     torch.cuda.synchronize()
     raw = dC.cpu().numpy().view(np.uint16).reshape(g.M, ldc_)
@@ -597,20 +597,25 @@ GROUPED_CASES = [
 ]
 
 
+KERNELS = [B.AXE_GROUPED_TILES, B.AXE_GROUPED_STREAM]
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
 @pytest.mark.parametrize("off,N,K,M", GROUPED_CASES)
-def test_gemm_grouped_small_cases(off, N, K, M):
+def test_gemm_grouped_small_cases(off, N, K, M, kernel):
     g = W.gemm_grouped_bf16(off, N, K, 77, M=M)
-    c, raw = run_grouped(g)
+    c, raw = run_grouped(g, kernel=kernel)
     ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16)
     check_grouped(g, c, raw, ref)
 
 
-def test_gemm_grouped_pitched_operands_and_many_groups():
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_gemm_grouped_pitched_operands_and_many_groups(kernel):
     rng = np.random.default_rng(5)
     sizes = rng.integers(0, 90, 150)                       # 150 groups: three 64-group chunks in the kernel's tile search
     off = np.concatenate([[0], np.cumsum(sizes)])
     g = W.gemm_grouped_bf16(off, 256, 128, 78)
-    c, raw = run_grouped(g, lda=136, ldb=144, ldg=256 * 144 + 64, ldc=264)
+    c, raw = run_grouped(g, lda=136, ldb=144, ldg=256 * 144 + 64, ldc=264, kernel=kernel)
     ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16)
     check_grouped(g, c, raw, ref)
 
@@ -621,6 +626,9 @@ def test_gemm_grouped_offsets_out_of_range_are_clamped():
     off_dev = [-5, 100, 300, 10 ** 6]
     off_eff = [0, 100, 300, 400]
     g = W.gemm_grouped_bf16(off_eff, 256, 128, 79)
+    for kernel in KERNELS:
+        c, raw = run_grouped(g, rows_on_device=off_dev, kernel=kernel)
+        check_grouped(g, c, raw, R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off_eff, R.AXE_BF16))
     c, raw = run_grouped(g, rows_on_device=off_dev)
     ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off_eff, R.AXE_BF16)
     check_grouped(g, c, raw, ref)
@@ -912,3 +920,73 @@ def test_gemm_grouped_f16_plain_and_gated():
     torch.cuda.synchronize()
     h = R.f16_to_f64(dC.cpu().numpy().view(np.uint16).reshape(g.M, N // 2))
     assert R.rel_frobenius(h[owned], R.swiglu_ref(P)[owned]) <= F16_TOL
+
+
+# ----------------------------------------------------------------------------- grouped GEMM, few rows per group (decode)
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+@pytest.mark.parametrize("gated,blocked", [(False, False), (False, True), (True, False), (True, True)])
+def test_gemm_grouped_stream_kernel_variants(dtype, gated, blocked):
+    """The streaming kernel on ragged small groups (1 .. 70 rows: up to two passes of 64 rows, every number of row
+    fragments), plain and gated, plain and blocked weights, bf16 and fp16."""
+    sizes = [1, 0, 16, 17, 33, 64, 65, 70, 3, 48]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    N, K = 512, 320
+    g = W.gemm_grouped_bf16(off, N, K, 101, M=int(off[-1]) + 2, std_b=2.0 * K ** -0.5, dtype=dtype)
+    odt, tol = ORACLE_DT[dtype], (F16_TOL if dtype == "f16" else BF16_TOL)
+    ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, odt)
+    img = W.pack_gate_up(g.b_gnk) if gated else g.b_gnk
+    Kp = 384                                                 # K = 320 is no multiple of the K-tile: pad with zeros
+    a_words = np.zeros((g.M, Kp), dtype=np.uint16); a_words[:, :K] = g.a_mk
+    b_p = np.zeros((g.G, N, Kp), dtype=np.uint16); b_p[:, :, :K] = img
+    img = W.pack_blocked(b_p) if blocked else b_p
+    if gated:
+        Bs = W.gated_b_spec(Kp, N, g.G, blocked)
+    else:
+        Bs = W.blocked_b_spec(Kp, N, G=g.G) if blocked else W.spec([(g.G, N * Kp, "m"), (Kp, 1, "m"), (N, Kp, "m")])
+    NC = N // 2 if gated else N
+    dA, dB = dev(a_words.reshape(-1)), dev(img.reshape(-1))
+    dC = torch.full((g.M * NC,), SENTINEL, dtype=torch.int16, device="cuda")
+    dR = torch.from_numpy(g.group_rows).cuda()
+    desc = B.GroupedGemmDesc(g.M, N, Kp, g.G, B.Layout(W.row_major_spec(g.M, Kp)), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, NC)),
+                             a_words.size, img.size, g.M * NC, in_dtype=IN_DT[dtype], out_dtype=OUT_DT[dtype],
+                             epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=B.AXE_GROUPED_STREAM)
+    B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+    torch.cuda.synchronize()
+    raw = dC.cpu().numpy().view(np.uint16).reshape(g.M, NC)
+    want = R.swiglu_ref(ref) if gated else ref
+    owned = ~np.isnan(want[:, 0])
+    assert (raw[~owned] == SENTINEL).all()
+    c = decode16(raw, dtype)
+    assert np.isfinite(c[owned]).all()
+    assert R.rel_frobenius(c[owned], want[owned]) <= tol
+    for e in range(g.G):
+        if sizes[e]:
+            for j in range(0, NC, 64):
+                blk = (slice(off[e], off[e + 1]), slice(j, j + 64))
+                assert R.rel_frobenius(c[blk], want[blk]) <= tol, (e, j)
+
+
+@pytest.mark.parametrize("tokens", [1, 8, 64])
+def test_gemm_grouped_moe_layer_at_decode_sizes(tokens):
+    """Both grouped GEMMs of the layer at decode batch sizes through the kernel the library picks itself (streaming),
+    blocked weights, gated first GEMM: the whole result against the oracle."""
+    g1, g2 = W.moe_gemm1(tokens), W.moe_gemm2(tokens)
+    I = g1.N // 2
+    for g, gated in ((g1, True), (g2, False)):
+        img = W.pack_blocked(W.pack_gate_up(g.b_gnk) if gated else g.b_gnk)
+        NC = I if gated else g.N
+        Bs = W.gated_b_spec(g.K, g.N, g.G, True) if gated else W.blocked_b_spec(g.K, g.N, G=g.G)
+        dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
+        dC = torch.full((g.M * NC,), SENTINEL, dtype=torch.int16, device="cuda")
+        dR = torch.from_numpy(g.group_rows).cuda()
+        desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(W.row_major_spec(g.M, g.K)), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, NC)),
+                                 g.M * g.K, img.size, g.M * NC, epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE)
+        B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+        torch.cuda.synchronize()
+        c = R.bf16_to_f64(dC.cpu().numpy().view(np.uint16).reshape(g.M, NC))
+        ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), g.group_rows, R.AXE_BF16)
+        ref = R.swiglu_ref(ref) if gated else ref
+        assert np.isfinite(c).all() and not np.isnan(ref).any()
+        assert R.rel_frobenius(c, ref) <= BF16_TOL
+        for r in range(0, g.M, 16):
+            assert R.rel_frobenius(c[r:r + 16], ref[r:r + 16]) <= BF16_TOL, r
