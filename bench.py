@@ -194,8 +194,43 @@ def bench_grouped(steps, warmup, tokens=4096, dtype="f16"):
             f"plain weights {r['plain']['kernel_ms']*1e3:.0f} us = {r['plain']['tflops']:.0f} TFLOP/s, {r['plain']['GBps']:.0f} GB/s; "
             f"blocked weights {r['blocked']['kernel_ms']*1e3:.0f} us = {r['blocked']['tflops']:.0f} TFLOP/s, {r['blocked']['GBps']:.0f} GB/s")
         del dA, dB, dBblk, dC
+    out["decode"] = bench_grouped_decode(steps, warmup, dtype)
     out["layer_kernel_ms"] = out["gemm1_gate_up"]["blocked_gated"]["kernel_ms"] + out["gemm2_down"]["blocked"]["kernel_ms"]
     log(f"[bench] MoE layer expert compute (gemm1 + activation, gemm2) at {tokens} tokens: {out['layer_kernel_ms']*1e3:.0f} us")
+    return out
+
+
+def bench_grouped_decode(steps, warmup, dtype, tokens=64):
+    """The same layer at a decode batch size (few rows per expert): the library picks its weight-streaming kernel;
+    gemm1 with the gated activation, blocked weights.  Bound: HBM (the active experts' weights are read once)."""
+    import torch
+    from paper_2601_19092_amd import binding as B
+    from paper_2601_19092_amd import workloads as W
+    dt = B.AXE_F16 if dtype == "f16" else B.AXE_BF16
+    out = {"tokens": tokens}
+    total = 0.0
+    for name, g, gated in (("gemm1_gate_up_gated", W.moe_gemm1(tokens, dtype=dtype), True), ("gemm2_down", W.moe_gemm2(tokens, dtype=dtype), False)):
+        NC = g.N // 2 if gated else g.N
+        plain = B.Layout(W.grouped_gemm_specs(g)[1])
+        Bs = B.Layout(W.gated_b_spec(g.K, g.N, g.G, True) if gated else W.blocked_b_spec(g.K, g.N, G=g.G))
+        dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_gnk.reshape(-1))
+        dBp = torch.empty_like(dB)
+        B.axe_relayout(plain, Bs, (g.G, g.K, g.N), dB, dBp)
+        dC = torch.zeros(g.M * NC, dtype=torch.int16, device="cuda")
+        dR = torch.from_numpy(g.group_rows).cuda()
+        desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(W.row_major_spec(g.M, g.K)), Bs, B.Layout(W.row_major_spec(g.M, NC)),
+                                 g.M * g.K, g.b_gnk.size, g.M * NC, in_dtype=dt, out_dtype=dt,
+                                 epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE)
+        wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dBp, dC, dR), steps, warmup)
+        active = int((np.diff(g.group_rows) > 0).sum())
+        nbytes = 2.0 * (active * g.N * g.K + g.M * g.K + g.M * NC)
+        out[name] = {"M": g.M, "active_experts": active, "kernel_ms": devms, "algorithmic_bytes": nbytes,
+                     "GBps": nbytes / (devms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (devms * 1e-3) / 1e9 / PEAK["hbm"]}
+        total += devms
+        log(f"[bench] grouped {dtype} GEMM {name} at {tokens} tokens (M={g.M}, {active} active experts), streaming kernel: "
+            f"{devms*1e3:.0f} us, {out[name]['GBps']:.0f} GB/s ({100*out[name]['frac_of_hbm_peak']:.1f}% of HBM peak)")
+        del dA, dB, dBp, dC
+    out["layer_kernel_ms"] = total
     return out
 
 

@@ -204,7 +204,8 @@ typedef struct {
  * groups of hundreds of rows.  AXE_GROUPED_STREAM: one workgroup per (group, 128 rows of B), the group's
  * rows (64 at a time) held in registers while its weights stream by once -- for the few rows per group of
  * an MoE layer at decode batch sizes, where the time is that of reading the weights.  AUTO takes the
- * streaming kernel when M <= 32 G (the host knows M, not the group sizes). */
+ * streaming kernel when M <= 16 G (the host knows M, not the group sizes; measured crossover on the
+ * MoE layer of the benchmark: 16 - 32 rows per group on average). */
 enum { AXE_GROUPED_AUTO = 0, AXE_GROUPED_TILES = 1, AXE_GROUPED_STREAM = 2 };
 
 /* AXE_EPI_SWIGLU: the gated activation between the two group GEMMs, fused into the first.  The logical
