@@ -20,8 +20,10 @@
 //                    the same for A and B, which is all the sum needs.
 //   VGPR -> HBM    : 8 bytes per lane and row fragment; rows past the group's end are not stored.
 // Groups with more than 64 rows are handled in passes of 64 (the weights are then read again: the
-// host chooses this kernel only when the average group is small).
+// host chooses this kernel only when the average group is small).  For a handful of rows per group a
+// second variant splits K over the four waves of a workgroup (see the template below).
 #include <hip/hip_runtime.h>
+#include <stdlib.h>
 
 #include "device_types.h"
 #include "gemm_common.h"
@@ -54,8 +56,15 @@ __device__ __forceinline__ uint32_t pack16s(float lo, float hi) {
 }
 }  // namespace
 
-template <bool F16, bool GATED>
+// SPLITK = false: a wave owns 32 rows of B for the whole of K, passes of 64 rows of the group (4 row fragments).
+// SPLITK = true, for groups of a handful of rows, where a launch has few workgroups: the workgroup owns
+// only 32 rows of B, its four waves take a quarter of K each (4 x as many waves and loads in flight for
+// the same weights), passes of 16 rows; the four partial sums meet in LDS and wave 0 adds them in a
+// fixed order and stores.
+template <bool F16, bool GATED, bool SPLITK>
 __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
+  constexpr int MI = SPLITK ? 1 : 4;                               // row fragments per pass
+  __shared__ float partial[SPLITK ? 3 * 64 * 8 : 1];               // SPLITK: the sums of waves 1..3
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int e = blockIdx.y;                                        // group
@@ -63,12 +72,13 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   int r0 = g.group_rows[e], r1 = g.group_rows[e + 1];
   r0 = r0 < 0 ? 0 : (r0 > M ? M : r0);                             // whatever the offsets hold, no access leaves the buffers
   r1 = r1 < 0 ? 0 : (r1 > M ? M : r1);
-  if (r1 <= r0) return;
+  if (r1 <= r0) return;                                            // (the whole workgroup: no barrier is left waiting)
   const int nk = (int)(g.K / 64);
+  const int k_lo = SPLITK ? (nk * w) >> 2 : 0, k_hi = SPLITK ? (nk * (w + 1)) >> 2 : nk;   // this wave's K-tiles
   const int fr = lane & 15, fq = lane >> 4;
 
   // this wave's 32 rows of the group's B image: rows brow .. brow + 31 (two fragments)
-  const int brow = (int)blockIdx.x * 128 + w * 32;
+  const int brow = SPLITK ? (int)blockIdx.x * 32 : (int)blockIdx.x * 128 + w * 32;
   const int tn = brow >> 8;                                        // 256-row block of the image
   const int64_t b_off = (int64_t)e * g.ldg + (int64_t)(tn >> g.b_tpb_shift) * g.b_blk_stride +
                         ((int64_t)(tn & ((1 << g.b_tpb_shift) - 1)) * 256 + (brow & 255)) * g.ldb;
@@ -79,19 +89,19 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   const int a_pitch = (int)(g.lda * 2);
   const int a_voff = fr * a_pitch + fq * 16;
 
-  for (int p0 = r0; p0 < r1; p0 += 64) {                           // passes of 64 rows of the group
-    const int rows = r1 - p0 < 64 ? r1 - p0 : 64;
+  for (int p0 = r0; p0 < r1; p0 += 16 * MI) {                      // passes over the rows of the group
+    const int rows = r1 - p0 < 16 * MI ? r1 - p0 : 16 * MI;
     const int nfrag = (rows + 15) >> 4;                            // row fragments that hold any row (wave-uniform)
     const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)p0 * g.lda * 2), 0,
                                                                         (rows - 1) * a_pitch + (int)g.K * 2, 0x00020000);
-    f32x4 acc[2][4];
+    f32x4 acc[2][MI];
 #pragma unroll
     for (int f = 0; f < 2; ++f)
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi) acc[f][mi] = f32x4{0.f, 0.f, 0.f, 0.f};
+      for (int mi = 0; mi < MI; ++mi) acc[f][mi] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // one K-tile (64 elements): per fragment the chunks q (k = 8 q ..) and q + 4 (k = 32 + 8 q ..)
-    u32x4 b[2][2][2], a[2][4][2];                                  // [buffer][fragment][half]
+    // one K-tile (64 elements) of a fragment is two 16-byte chunks per lane: q (k = 8 q ..) and q + 4 (k = 32 + 8 q ..)
+    u32x4 b[2][2][2], a[2][MI][2];                                 // [buffer][fragment][chunk]
     auto load = [&](int buf, int kt) __attribute__((always_inline)) {
 #pragma unroll
       for (int f = 0; f < 2; ++f)
@@ -99,7 +109,7 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
         for (int h = 0; h < 2; ++h)
           b[buf][f][h] = __builtin_bit_cast(u32x4, __builtin_amdgcn_raw_buffer_load_b128(rb, b_voff + f * 16 * b_pitch + h * 64, kt * b_kstep, 0));
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
+      for (int mi = 0; mi < MI; ++mi)
         if (mi < nfrag) {
 #pragma unroll
           for (int h = 0; h < 2; ++h)
@@ -108,7 +118,7 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
     };
     auto multiply = [&](int buf) __attribute__((always_inline)) {
 #pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
+      for (int mi = 0; mi < MI; ++mi)
         if (mi < nfrag) {
 #pragma unroll
           for (int h = 0; h < 2; ++h)
@@ -116,19 +126,39 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
             for (int f = 0; f < 2; ++f) acc[f][mi] = mfma16<F16>(b[buf][f][h], a[buf][mi][h], acc[f][mi]);
         }
     };
-    load(0, 0);
-    int kt = 0;
-    for (; kt + 2 <= nk; kt += 2) {                                // two K-tiles per trip, the next one always on its way
+    int kt = k_lo;
+    if (kt < k_hi) load(0, kt);
+    for (; kt + 2 <= k_hi; kt += 2) {                              // two K-tiles per trip, the next one always on its way
       load(1, kt + 1);
       multiply(0);
-      if (kt + 2 < nk) load(0, kt + 2);
+      if (kt + 2 < k_hi) load(0, kt + 2);
       multiply(1);
     }
-    if (kt < nk) multiply(0);                                      // odd number of K-tiles: the last one was loaded into buffer 0
+    if (kt < k_hi) multiply(0);                                    // odd number of K-tiles: the last one was loaded into buffer 0
+
+    if constexpr (SPLITK) {
+      if (w) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f)
+#pragma unroll
+          for (int x = 0; x < 4; ++x) partial[((w - 1) * 8 + f * 4 + x) * 64 + lane] = acc[f][0][x];
+      }
+      __syncthreads();
+      if (w == 0) {
+#pragma unroll
+        for (int v = 0; v < 3; ++v)
+#pragma unroll
+          for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int x = 0; x < 4; ++x) acc[f][0][x] += partial[(v * 8 + f * 4 + x) * 64 + lane];
+      }
+      __syncthreads();                                             // the next pass writes the array again
+      if (w) continue;                                             // wave 0 stores
+    }
 
     // ---- store: lane holds columns 4 q .. 4 q + 3 of row 16 mi + fr for each of its two fragments
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int mi = 0; mi < MI; ++mi) {
       const int row = mi * 16 + fr;
       if (mi < nfrag && row < rows) {
         if constexpr (GATED) {                                     // fragment 0 = gate, fragment 1 = up of the same 16 outputs
@@ -152,16 +182,28 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   }
 }
 
-hipError_t launch_gemm_grouped_stream(const GemmArgs& g, hipStream_t s) {
-  const dim3 grid((unsigned)(g.N / 128), (unsigned)g.groups);
+namespace {
+template <bool SPLITK>
+void launch_stream(const GemmArgs& g, dim3 grid, hipStream_t s) {
   if (g.f16 && g.gated)
-    hipLaunchKernelGGL((gemm_grouped_stream_kernel<true, true>), grid, dim3(256), 0, s, g);
+    hipLaunchKernelGGL((gemm_grouped_stream_kernel<true, true, SPLITK>), grid, dim3(256), 0, s, g);
   else if (g.f16)
-    hipLaunchKernelGGL((gemm_grouped_stream_kernel<true, false>), grid, dim3(256), 0, s, g);
+    hipLaunchKernelGGL((gemm_grouped_stream_kernel<true, false, SPLITK>), grid, dim3(256), 0, s, g);
   else if (g.gated)
-    hipLaunchKernelGGL((gemm_grouped_stream_kernel<false, true>), grid, dim3(256), 0, s, g);
+    hipLaunchKernelGGL((gemm_grouped_stream_kernel<false, true, SPLITK>), grid, dim3(256), 0, s, g);
   else
-    hipLaunchKernelGGL((gemm_grouped_stream_kernel<false, false>), grid, dim3(256), 0, s, g);
+    hipLaunchKernelGGL((gemm_grouped_stream_kernel<false, false, SPLITK>), grid, dim3(256), 0, s, g);
+}
+}  // namespace
+
+// The host knows the number of rows of all groups together, not the group sizes: up to 8 rows per group on
+// average (an MoE layer of 128 experts, 8 per token, up to 128 tokens: at most 22 rows in any group in the
+// benchmark's routing) it takes the variant that splits K over the waves and handles 16 rows per pass
+// (measured crossover between 8 and 16; AXE_GROUPED_SPLITK_ROWS overrides it for experiments).
+hipError_t launch_gemm_grouped_stream(const GemmArgs& g, hipStream_t s) {
+  static const int avg = [] { const char* v = getenv("AXE_GROUPED_SPLITK_ROWS"); return v ? atoi(v) : 8; }();
+  if (g.M <= avg * (int64_t)g.groups) launch_stream<true>(g, dim3((unsigned)(g.N / 32), (unsigned)g.groups), s);
+  else launch_stream<false>(g, dim3((unsigned)(g.N / 128), (unsigned)g.groups), s);
   return hipGetLastError();
 }
 

@@ -990,3 +990,15 @@ def test_gemm_grouped_moe_layer_at_decode_sizes(tokens):
         assert R.rel_frobenius(c, ref) <= BF16_TOL
         for r in range(0, g.M, 16):
             assert R.rel_frobenius(c[r:r + 16], ref[r:r + 16]) <= BF16_TOL, r
+
+
+def test_gemm_grouped_stream_kernel_many_empty_groups_and_passes_of_16_rows():
+    """Few rows in all (M <= 4 G): the variant that takes a group 16 rows at a time; groups of 40 and 17 rows need
+    several passes, most groups are empty."""
+    sizes = np.zeros(40, dtype=np.int64)
+    sizes[[0, 7, 8, 31, 39]] = [40, 17, 1, 16, 3]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    g = W.gemm_grouped_bf16(off, 512, 448, 102)
+    assert g.M <= 4 * g.G
+    c, raw = run_grouped(g, kernel=B.AXE_GROUPED_STREAM)
+    check_grouped(g, c, raw, R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16))
