@@ -179,9 +179,9 @@ def e8m0_decode(codes: np.ndarray) -> np.ndarray:
 
 def gemm_ref_numpy(a_bits: np.ndarray, b_bits: np.ndarray, dtype: int,
                    scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None,
-                   block: int = 128) -> np.ndarray:
+                   block: int = 128, block_m_a: Optional[int] = None) -> np.ndarray:
     """a_bits: logical (M, K); b_bits: logical (K, N) (any strides).  fp64 result (M, N).
-    With scales: C = sum_kb sA[i//block, kb] sB[j//block, kb] (A_kb @ B_kb)."""
+    With scales: C = sum_kb sA[i//block_m_a, kb] sB[j//block, kb] (A_kb @ B_kb); block_m_a defaults to block."""
     A = decode(a_bits, dtype)
     B = decode(b_bits, dtype)
     M, K = A.shape
@@ -189,7 +189,7 @@ def gemm_ref_numpy(a_bits: np.ndarray, b_bits: np.ndarray, dtype: int,
     if scale_a is None and scale_b is None:
         return A @ B
     C = np.zeros((M, N), dtype=np.float64)
-    ri = np.arange(M) // block
+    ri = np.arange(M) // (block if block_m_a is None else block_m_a)
     cj = np.arange(N) // block
     for kb in range((K + block - 1) // block):
         ks = slice(kb * block, min(K, (kb + 1) * block))
@@ -220,7 +220,7 @@ def _c():
         lib.axe_oracle_gemm.restype = ctypes.c_int
         lib.axe_oracle_gemm.argtypes = [ctypes.c_int, i64, i64, i64,
                                         vp, i64, i64, vp, i64, i64,
-                                        vp, vp, i64,
+                                        vp, vp, i64, i64,
                                         vp, i64, vp, i64, vp]
         lib.axe_oracle_threads.restype = ctypes.c_int
         _clib = lib
@@ -234,7 +234,7 @@ def oracle_threads() -> int:
 def gemm_ref(a_bits: np.ndarray, b_bits: np.ndarray, dtype: int,
              scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None,
              block: int = 128, rows: Optional[np.ndarray] = None,
-             cols: Optional[np.ndarray] = None) -> np.ndarray:
+             cols: Optional[np.ndarray] = None, block_m_a: Optional[int] = None) -> np.ndarray:
     """The plain C triple loop.  a_bits logical (M, K), b_bits logical (K, N), any (element)
     strides; result fp64 [len(rows), len(cols)] (all rows / cols when None)."""
     M, K = a_bits.shape
@@ -257,14 +257,15 @@ def gemm_ref(a_bits: np.ndarray, b_bits: np.ndarray, dtype: int,
         nkb = (K + block - 1) // block
         sa = np.ascontiguousarray(scale_a, dtype=np.float32)
         sb = np.ascontiguousarray(scale_b, dtype=np.float32)
-        if sa.shape != ((M + block - 1) // block, nkb) or sb.shape != ((N + block - 1) // block, nkb):
+        bma = block if block_m_a is None else block_m_a          # rows of A that share a scale (1: one scale per row and k block)
+        if sa.shape != ((M + bma - 1) // bma, nkb) or sb.shape != ((N + block - 1) // block, nkb):
             raise ValueError("scale arrays have the wrong shape")
     rc = _c().axe_oracle_gemm(
         dtype, M, N, K,
         a_bits.ctypes.data, a_bits.strides[0] // isz, a_bits.strides[1] // isz,
         b_bits.ctypes.data, b_bits.strides[0] // isz, b_bits.strides[1] // isz,
         sa.ctypes.data if sa is not None else None,
-        sb.ctypes.data if sb is not None else None, block,
+        sb.ctypes.data if sb is not None else None, block, (block if block_m_a is None else block_m_a),
         rows.ctypes.data, rows.size, cols.ctypes.data, cols.size, out.ctypes.data)
     if rc != 0:
         raise RuntimeError(f"axe_oracle_gemm failed ({rc})")

@@ -6,7 +6,8 @@
  * natural k order (the dense GEMM workloads of the paper's Sec. 4.1), and, when scales are
  * given, the block-scaled form
  *     C[i][j] = sum_{kb} sA[i/bs][kb] * sB[j/bs][kb] * ( sum_{k in block kb} a[i][k] * b[k][j] )
- * (the block-wise scaled FP8 GEMM of Sec. 4.1; scales here are fp32 as this build's workload fixes).
+ * (the block-wise scaled FP8 GEMM of Sec. 4.1; scales here are fp32 as this build's workload fixes;
+ * A's scales may also be one per row and k block).
  *
  * Only the loop over output elements is spread over threads; every output is an independent
  * serial sum.  The number formats are decoded from their definitions:
@@ -65,18 +66,20 @@ int axe_oracle_threads(void) {
 }
 
 /* A: logical (M,K), element (i,k) at A[i*a_sm + k*a_sk]; B: logical (K,N), element (k,j) at
- * B[k*b_sk + j*b_sn] (strides in elements).  sA: row-major (ceil(M/bs), ceil(K/bs)) floats or
- * NULL; sB: row-major (ceil(N/bs), ceil(K/bs)) floats or NULL (both or neither).
+ * B[k*b_sk + j*b_sn] (strides in elements).  sA: row-major (ceil(M/bs_am), ceil(K/bs)) floats or
+ * NULL (bs_am = rows of A that share a scale: bs for square blocks, 1 for one scale per row and
+ * k block, the usual choice for activations); sB: row-major (ceil(N/bs), ceil(K/bs)) floats or NULL
+ * (both or neither).
  * out: row-major (nrows, ncols) doubles holding C[rows[r]][cols[c]]. */
 int axe_oracle_gemm(int dtype, int64_t M, int64_t N, int64_t K,
                     const void* A, int64_t a_sm, int64_t a_sk,
                     const void* B, int64_t b_sk, int64_t b_sn,
-                    const float* sA, const float* sB, int64_t bs,
+                    const float* sA, const float* sB, int64_t bs, int64_t bs_am,
                     const int64_t* rows, int64_t nrows, const int64_t* cols, int64_t ncols,
                     double* out) {
     if (dtype != ORACLE_BF16 && dtype != ORACLE_FP8_E4M3 && dtype != ORACLE_F16) return -1;
     if ((sA == 0) != (sB == 0)) return -2;
-    if (sA && bs <= 0) return -3;
+    if (sA && (bs <= 0 || bs_am <= 0)) return -3;
     (void)M; (void)N;
     int64_t nkb = sA ? (K + bs - 1) / bs : 0;
 #pragma omp parallel for collapse(2) schedule(static)
@@ -93,7 +96,7 @@ int axe_oracle_gemm(int dtype, int64_t M, int64_t N, int64_t K,
                     int64_t k1 = (kb + 1) * bs < K ? (kb + 1) * bs : K;
                     for (int64_t k = kb * bs; k < k1; ++k)
                         part += load(A, i * a_sm + k * a_sk, dtype) * load(B, k * b_sk + j * b_sn, dtype);
-                    acc += (double)sA[(i / bs) * nkb + kb] * (double)sB[(j / bs) * nkb + kb] * part;
+                    acc += (double)sA[(i / bs_am) * nkb + kb] * (double)sB[(j / bs) * nkb + kb] * part;
                 }
             }
             out[r * ncols + c] = acc;

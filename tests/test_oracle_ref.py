@@ -257,6 +257,34 @@ def test_gemm_fp8_scaled_form():
     assert g.scale_a.shape != g.scale_b.shape
 
 
+def test_gemm_fp8_row_scaled_activations():
+    """One scale per row of A and 128-wide k block (weights keep 128 x 128 blocks): brute force from the
+    definition; repeating a block's scale over its 128 rows gives back the block-scaled form."""
+    M, N, K = 130, 256, 384
+    g = W.gemm_fp8(M, N, K, 14)
+    rng = np.random.default_rng(2)
+    sa_rows = rng.uniform(0.5, 2.0, (M, K // 128)).astype(np.float32)
+    A, Bm = R.e4m3_to_f64(g.a_mk), R.e4m3_to_f64(g.b_nk).T
+    want = np.zeros((M, N))
+    for i in range(M):
+        for kb in range(K // 128):
+            ks = slice(kb * 128, (kb + 1) * 128)
+            want[i] += float(sa_rows[i, kb]) * (A[i, ks] @ Bm[ks]) * np.repeat(g.scale_b[:, kb].astype(np.float64), 128)[:N]
+    c = R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, sa_rows, g.scale_b, block_m_a=1)
+    assert R.rel_frobenius(c, want) <= 1e-12
+    assert R.rel_frobenius(R.gemm_ref_numpy(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, sa_rows, g.scale_b, block_m_a=1), want) <= 1e-12
+    rep = np.repeat(g.scale_a, 128, axis=0)[:M]
+    np.testing.assert_array_equal(R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, rep, g.scale_b, block_m_a=1),
+                                  R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, g.scale_a, g.scale_b))
+    # one row's scale changed: that row changes, no other
+    bad = sa_rows.copy()
+    bad[77, 1] *= 2
+    cb = R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, bad, g.scale_b, block_m_a=1)
+    assert np.array_equal(np.delete(cb, 77, axis=0), np.delete(c, 77, axis=0)) and R.rel_frobenius(cb[77], c[77]) > 1e-2
+    with pytest.raises(ValueError):
+        R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, g.scale_a, g.scale_b, block_m_a=1)      # wrong shape for per-row scales
+
+
 def test_gemm_operand_orientation_is_checked_by_shape():
     # K-contiguous B handed over as (K, N) view: a transposed operand changes the result
     g = W.gemm_bf16(8, 8, 8, 14)
