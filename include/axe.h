@@ -128,7 +128,8 @@ int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank,
  *   d_scale_a, d_scale_b : both NULL, or DEVICE arrays of scale_dtype, row-major (ceil(M/sb), ceil(K/sb))
  *       and (ceil(N/sb), ceil(K/sb)) with sb = scale_block (must be 128):
  *       C[i][j] = sum_kb sA[i/sb][kb] * sB[j/sb][kb] * sum_{k in block kb} A[i][k] B[k][j]
- *       (block-wise scaled GEMM, Sec. 4.1).  Only with AXE_FP8_E4M3.
+ *       (block-wise scaled GEMM, Sec. 4.1).  Only with AXE_FP8_E4M3.  With scale_a_rows = 1 the scales
+ *       of A are one per row and k block, d_scale_a row-major (M, ceil(K/sb)), sA[i][kb] in the formula.
  *   scale_dtype : AXE_SCALE_F32 (0; fp32 scales, folded on the vector ALU) or AXE_SCALE_E8M0 (one byte
  *       per block, value 2^(code - 127), codes 1..254; the "FP8 (e8m0) block-wise scaling" of Sec. 4.1,
  *       applied by the matrix cores' own scale path).  E8M0 arrays must be 4-byte aligned.
@@ -153,6 +154,9 @@ typedef struct {
   int32_t      tile_hint;   /* 0 = library default; AXE_TILE_* forces a kernel (AXE_EUNSUPPORTED if
                                the shape does not fit it)                                         */
   int32_t      scale_dtype; /* AXE_SCALE_F32 or AXE_SCALE_E8M0                                    */
+  int32_t      scale_a_rows; /* rows of A that share a scale: 0 or 128 = square blocks; 1 = one scale per
+                                row and 128-wide k block (activations; d_scale_a is then (M, ceil(K/128)));
+                                B keeps 128 x 128 blocks.  Served by the 64 x 64 kernel only.          */
 } axe_gemm_desc_t;
 
 enum { AXE_SCALE_F32 = 0, AXE_SCALE_E8M0 = 1 };

@@ -49,7 +49,8 @@ class axe_gemm_desc_t(C.Structure):
                 ("mem_axis", C.c_int32),
                 ("a_elems", C.c_int64), ("b_elems", C.c_int64), ("c_elems", C.c_int64),
                 ("d_scale_a", C.c_void_p), ("d_scale_b", C.c_void_p),
-                ("scale_block", C.c_int32), ("tile_hint", C.c_int32), ("scale_dtype", C.c_int32)]
+                ("scale_block", C.c_int32), ("tile_hint", C.c_int32), ("scale_dtype", C.c_int32),
+                ("scale_a_rows", C.c_int32)]
 
 
 class axe_gemm_grouped_desc_t(C.Structure):
@@ -199,14 +200,16 @@ class GemmDesc:
 
     def __init__(self, M: int, N: int, K: int, in_dtype: int, out_dtype: int, A: Layout, B: Layout, Cl: Layout,
                  a_elems: int, b_elems: int, c_elems: int, scale_a=None, scale_b=None, scale_block: int = 128,
-                 tile_hint: int = AXE_TILE_AUTO, mem_axis: str = "m", scale_dtype: int = AXE_SCALE_F32):
+                 tile_hint: int = AXE_TILE_AUTO, mem_axis: str = "m", scale_dtype: int = AXE_SCALE_F32,
+                 scale_a_rows: int = 0):
         ma = A.axis(mem_axis)
         assert B.axis(mem_axis) == ma and Cl.axis(mem_axis) == ma, "memory axis must have the same index in A, B, C"
         self.layouts = (A, B, Cl)
         self.scales = (scale_a, scale_b)
         self.c = axe_gemm_desc_t(M, N, K, in_dtype, out_dtype, A.c, B.c, Cl.c, ma, a_elems, b_elems, c_elems,
                                  scale_a.data_ptr() if scale_a is not None else None,
-                                 scale_b.data_ptr() if scale_b is not None else None, scale_block, tile_hint, scale_dtype)
+                                 scale_b.data_ptr() if scale_b is not None else None, scale_block, tile_hint, scale_dtype,
+                                 scale_a_rows)
 
 
 def axe_gemm(desc: GemmDesc, A_buf, B_buf, C_buf, stream=None):

@@ -502,6 +502,11 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
     set_error("axe_gemm: E8M0 scale arrays must be 4-byte aligned");
     return AXE_EINVAL;
   }
+  if (g->scale_a_rows != 0 && g->scale_a_rows != 1 && g->scale_a_rows != 128) {
+    set_error("axe_gemm: scale_a_rows must be 0, 1 or 128");
+    return AXE_EINVAL;
+  }
+  const bool row_scaled = g->d_scale_a && g->scale_a_rows == 1;
   if (g->d_scale_a && (!fp8 || g->scale_block != 128)) {
     set_error("axe_gemm: block scales need in_dtype fp8 and scale_block 128");
     return AXE_EUNSUPPORTED;
@@ -561,6 +566,7 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   P.args.scale_a = (const float*)g->d_scale_a;
   P.args.scale_b = (const float*)g->d_scale_b;
   P.args.scale_e8m0 = g->d_scale_a && g->scale_dtype == AXE_SCALE_E8M0;
+  P.args.scale_a_rows = row_scaled ? 1 : 128;
   P.args.nkb = (int32_t)((g->K + 127) / 128);
   P.args.out_bf16 = g->out_dtype != AXE_F32;
   P.args.f16 = f16;
@@ -572,6 +578,13 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   // bf16 only: 224 columns per tile (7 fragments per wave instead of 8)
   const bool n224_ok = big_common && !fp8 && !f16 && (g->N % 224 == 0);
   int tile = g->tile_hint;
+  if (row_scaled) {                                                // only the 64 x 64 kernel folds a scale per row
+    if (tile != AXE_TILE_AUTO && tile != AXE_TILE_64x64x32) {
+      set_error("axe_gemm: one scale per row of A is served by the 64x64 kernel only");
+      return AXE_EUNSUPPORTED;
+    }
+    tile = AXE_TILE_64x64x32;
+  }
   if (blocked) {
     if (fp8 || !big_ok || !block_ok(opa) || !block_ok(opb) || (tile != AXE_TILE_AUTO && tile != AXE_TILE_256x256x64)) {
       set_error("axe_gemm: blocked operands need the bf16 256x256 tile (M, N multiples of 256, K of 64, bf16 output), "

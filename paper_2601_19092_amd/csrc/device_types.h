@@ -86,6 +86,7 @@ struct GemmArgs {
   const float* scale_a;            // (ceil(M/128), nkb) or null; bytes (E8M0 codes) when scale_e8m0
   const float* scale_b;            // (ceil(N/128), nkb) or null
   int32_t scale_e8m0;              // 1: the scale arrays hold one E8M0 byte per block (2^(code - 127))
+  int32_t scale_a_rows;            // rows of A that share a scale: 128, or 1 (scale_a is then (M, nkb))
   int32_t nkb;
   int32_t out_bf16;                // 0: fp32 output, 1: 16-bit output (bf16, or binary16 when f16 is set)
   int32_t f16;                     // 1: 16-bit inputs (and a 16-bit output) are IEEE binary16 instead of bf16

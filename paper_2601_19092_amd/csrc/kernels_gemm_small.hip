@@ -132,13 +132,22 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
         fb[f] = i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       }
       if (g.scale_a) {
-        // one K step is one 128-deep scale block: accumulate it alone, then scale and add
-        float sc;
-        if (g.scale_e8m0) {          // 2^(ca - 127) * 2^(cb - 127), built as the bits of two floats (codes 1..254 are normal numbers)
-          const uint32_t ca = ((const uint8_t*)g.scale_a)[(int64_t)sa_row * g.nkb + kt], cb = ((const uint8_t*)g.scale_b)[(int64_t)sb_row * g.nkb + kt];
-          sc = __builtin_bit_cast(float, ca << 23) * __builtin_bit_cast(float, cb << 23);
-        } else {
-          sc = g.scale_a[(int64_t)sa_row * g.nkb + kt] * g.scale_b[(int64_t)sb_row * g.nkb + kt];
+        // one K step is one 128-deep scale block: accumulate it alone, then scale and add.  A's scale is
+        // that of the tile's 128-row block, or (scale_a_rows == 1) of the lane's own row of each fragment.
+        float sc[2];
+#pragma unroll
+        for (int i = 0; i < 2; ++i) {
+          int64_t ar = sa_row;
+          if (g.scale_a_rows == 1) {
+            ar = m0 + wm * 32 + i * 16 + frow;
+            ar = ar < g.M ? ar : g.M - 1;        // rows past the end are never stored
+          }
+          if (g.scale_e8m0) {        // 2^(ca - 127) * 2^(cb - 127), built as the bits of two floats (codes 1..254 are normal numbers)
+            const uint32_t ca = ((const uint8_t*)g.scale_a)[ar * g.nkb + kt], cb = ((const uint8_t*)g.scale_b)[(int64_t)sb_row * g.nkb + kt];
+            sc[i] = __builtin_bit_cast(float, ca << 23) * __builtin_bit_cast(float, cb << 23);
+          } else {
+            sc[i] = g.scale_a[ar * g.nkb + kt] * g.scale_b[(int64_t)sb_row * g.nkb + kt];
+          }
         }
 #pragma unroll
         for (int i = 0; i < 2; ++i)
@@ -147,7 +156,7 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
             f32x4 part = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb[j], fa[i], f32x4{0.f, 0.f, 0.f, 0.f},
                                                                         0, 0, 0, 0, 0, 0);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) acc[i][j][e] = __builtin_fmaf(sc, part[e], acc[i][j][e]);
+            for (int e = 0; e < 4; ++e) acc[i][j][e] = __builtin_fmaf(sc[i], part[e], acc[i][j][e]);
           }
       } else {
 #pragma unroll

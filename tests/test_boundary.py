@@ -151,6 +151,22 @@ def test_gemm_family_matching_and_errors():
     assert B.lib().axe_gemm(C.byref(d.c), None, None, None, None) == B.AXE_EINVAL
 
 
+def test_gemm_row_scaled_activations_go_to_the_small_kernel():
+    import numpy as np
+    g = W.gemm_fp8(256, 256, 256, 3)
+    As, Bs, Cs = W.gemm_specs(g)
+    class FakeTensor:                                     # plan only: nothing is launched, any non-NULL pointer will do
+        def data_ptr(self):
+            return 4096
+    def desc(rows, tile=B.AXE_TILE_AUTO, dt=B.AXE_FP8_E4M3):
+        return B.GemmDesc(256, 256, 256, dt, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(Cs), 256 * 256, 256 * 256, 256 * 256,
+                          FakeTensor(), FakeTensor(), tile_hint=tile, scale_a_rows=rows)
+    assert _tile_rc(desc(0)) == B.AXE_TILE_256x256x64 and _tile_rc(desc(128)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(desc(1)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(desc(1, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(desc(64)) == B.AXE_EINVAL
+
+
 def test_gemm_accepts_blocked_operands():
     """Operands stored as contiguous 256 x 64 blocks (a tile product, Sec. 3.3) are in the family of the
     bf16 256 x 256 kernel; the same layouts are refused where no kernel reads them."""

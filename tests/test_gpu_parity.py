@@ -1002,3 +1002,32 @@ def test_gemm_grouped_stream_kernel_many_empty_groups_and_passes_of_16_rows():
     assert g.M <= 4 * g.G
     c, raw = run_grouped(g, kernel=B.AXE_GROUPED_STREAM)
     check_grouped(g, c, raw, R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16))
+
+
+@pytest.mark.parametrize("scale_dtype", ["f32", "e8m0"])
+@pytest.mark.parametrize("M,N,K", [(130, 256, 384), (256, 128, 1024), (70, 72, 272)])
+def test_gemm_fp8_row_scaled_activations(M, N, K, scale_dtype):
+    """One scale per row of A and 128-wide k block (the usual choice for activations), 128 x 128 blocks for B."""
+    g = W.gemm_fp8(M, N, K, 103, scaled="e8m0" if scale_dtype == "e8m0" else True)
+    rng = np.random.default_rng(3)
+    nkb = (K + 127) // 128
+    if scale_dtype == "e8m0":
+        sa_rows = rng.integers(124, 131, (M, nkb)).astype(np.uint8)
+        sa_oracle, sb_oracle = R.e8m0_decode(sa_rows).astype(np.float32), R.e8m0_decode(g.scale_b).astype(np.float32)
+    else:
+        sa_rows = rng.uniform(0.5, 2.0, (M, nkb)).astype(np.float32)
+        sa_oracle, sb_oracle = sa_rows, g.scale_b
+    As, Bs, Cs = W.gemm_specs(g)
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_nk.reshape(-1))
+    dC = torch.zeros(M * N, dtype=torch.int16, device="cuda")
+    sa, sb = torch.from_numpy(sa_rows).cuda(), torch.from_numpy(g.scale_b).cuda()
+    desc = B.GemmDesc(M, N, K, B.AXE_FP8_E4M3, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(Cs), M * K, N * K, M * N, sa, sb,
+                      scale_dtype=B.AXE_SCALE_E8M0 if scale_dtype == "e8m0" else B.AXE_SCALE_F32, scale_a_rows=1)
+    assert B.axe_gemm_tile(desc) == B.AXE_TILE_64x64x32
+    B.axe_gemm(desc, dA, dB, dC)
+    torch.cuda.synchronize()
+    c = R.bf16_to_f64(dC.cpu().numpy().view(np.uint16).reshape(M, N))
+    ref = R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, sa_oracle, sb_oracle, block_m_a=1)
+    assert R.rel_frobenius(c, ref) <= FP8_TOL
+    for i in range(0, M, 16):                                # per 16 rows: a scale applied to the wrong row cannot hide
+        assert R.rel_frobenius(c[i:i + 16], ref[i:i + 16]) <= FP8_TOL, i
