@@ -22,7 +22,7 @@ AXE_TILE_AUTO, AXE_TILE_64x64x32, AXE_TILE_256x256x64, AXE_TILE_256x224x64 = 0, 
 AXE_MAX_RANK = 8
 AXE_SCALE_F32, AXE_SCALE_E8M0 = 0, 1
 AXE_EPI_NONE, AXE_EPI_SWIGLU = 0, 1
-AXE_GROUPED_AUTO, AXE_GROUPED_TILES, AXE_GROUPED_STREAM = 0, 1, 2
+AXE_GROUPED_AUTO, AXE_GROUPED_TILES, AXE_GROUPED_STREAM, AXE_GROUPED_TILES_256, AXE_GROUPED_TILES_128 = 0, 1, 2, 3, 4
 
 EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
            "axe_last_error", "axe_version", "axe_layout_span", "axe_layout_canonicalize", "axe_layout_gap_condition",

@@ -732,7 +732,7 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     set_error("%s: unknown epilogue %d", fn, g->epilogue);
     return AXE_EINVAL;
   }
-  if (g->kernel_hint != AXE_GROUPED_AUTO && g->kernel_hint != AXE_GROUPED_TILES && g->kernel_hint != AXE_GROUPED_STREAM) {
+  if (g->kernel_hint < AXE_GROUPED_AUTO || g->kernel_hint > AXE_GROUPED_TILES_128) {
     set_error("%s: unknown kernel_hint %d", fn, g->kernel_hint);
     return AXE_EINVAL;
   }
@@ -799,6 +799,7 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
   a.group_rows = rows;
   a.groups = g->G;
   a.gated = gated;
+  a.tile_m = g->kernel_hint == AXE_GROUPED_TILES_256 ? 256 : (g->kernel_hint == AXE_GROUPED_TILES_128 ? 128 : 0);
   return AXE_OK;
 }
 

@@ -55,6 +55,8 @@
 // the arrival of the next tile's operands.
 #include <hip/hip_runtime.h>
 
+#include <stdlib.h>
+
 #include <algorithm>
 #include <type_traits>
 
@@ -110,6 +112,7 @@ __device__ __forceinline__ uint32_t pack16(float lo, float hi) {
 __device__ __forceinline__ int desc_rows(int d) { return d & 511; }
 __device__ __forceinline__ int desc_tn(int d) { return (d >> 9) & 2047; }
 __device__ __forceinline__ int desc_group(int d) { return (int)((unsigned)d >> 20); }
+template <int TM>                                                 // rows of a tile
 __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_row0, int& t_desc) {
   const int G = g.groups, M = (int)g.M, gn = g.grid_n;
   const int* __restrict__ off = g.group_rows;
@@ -122,7 +125,7 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
     b = b < 0 ? 0 : (b > M ? M : b);
     r0 = a;
     rows = b > a ? b - a : 0;
-    tg = ((rows + kTile - 1) / kTile) * gn;
+    tg = ((rows + TM - 1) / TM) * gn;
     incl = tg;                                                     // inclusive prefix sum over the lanes
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
@@ -157,12 +160,12 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
   // inside a group the row blocks run fastest: the tiles that read one B panel are neighbours in the
   // sequence (they run side by side on one XCD and the second reads the panel from that L2), and the
   // tiles that read one block of A rows are only a group's few row blocks apart
-  const int gm = (f_rows + kTile - 1) / kTile;                     // row blocks of the group (0: the lane found no tile)
+  const int gm = (f_rows + TM - 1) / TM;                           // row blocks of the group (0: the lane found no tile)
   const int tn = gm ? f_local / gm : 0;
   const int tm = f_local - tn * gm;
-  t_row0 = f_r0 + tm * kTile;
-  const int left = f_rows - tm * kTile;
-  t_desc = (left < kTile ? left : kTile) | (tn << 9) | (f_group << 20);
+  t_row0 = f_r0 + tm * TM;
+  const int left = f_rows - tm * TM;
+  t_desc = (left < TM ? left : TM) | (tn << 9) | (f_group << 20);
 }
 
 // NB = columns of C per tile (B rows per tile): 256, or 224 = 2 waves x 7 fragments for problems whose
@@ -183,9 +186,21 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 // projections interleaved in runs of 16 rows (the host accepts only that layout), so that fragment pair
 // (j, j + 1) of a wave is (gate, up) of the same 16 output columns in the same lanes; the tile stores
 // silu(gate) * up, half as wide as the product.
-template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false>
+//
+// MR = fragment rows per wave: 8 (tile of 256 rows), or 4 for the grouped kernel when groups are small: a
+// tile is then 128 rows x 256 columns, a wave owns 64 x 128 of it, a K-step is 2 x 32 MFMAs per wave instead of
+// 2 x 64 and moves half as much of A (4 pieces per wave and K-step), so that the weights stream past twice as
+// fast -- with few rows per group the time is that of reading B from HBM.  The A blocks in LDS keep their
+// places (half of each is used); loads per K-step 12 instead of 16, hence other wait counts.
+template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
+  static_assert(MR == 8 || (MR == 4 && GROUPED), "128-row tiles exist for the grouped kernel");
+  constexpr int TM = 32 * MR;                                      // rows of a tile
+  constexpr int NA = MR;                                           // A pieces (8 rows x 128 bytes) per wave and K-step
+  constexpr int HA = NA / 2;                                       // ... per sub-step
+  constexpr int kWaitSlot = MR == 8 ? 31 : 23;                     // loads issued after the one that filled a staging slot, two K-steps later
+  constexpr int kWaitStep = MR == 8 ? 17 : 13;                     // loads issued after the last B load of the next K-step, at the barrier
   constexpr int NJ = NB / 32;                                      // fragments per wave along N
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
   const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
@@ -223,7 +238,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     int rot;
   };
   int tb_row0 = 0, tb_desc = 0;                                    // grouped: lane t = the workgroup's t-th tile
-  if constexpr (GROUPED) group_tiles(g, lane, tb_row0, tb_desc);
+  if constexpr (GROUPED) group_tiles<TM>(g, lane, tb_row0, tb_desc);
   auto table_rows = [&](int t) __attribute__((always_inline)) -> int { return t < 64 ? desc_rows(__builtin_amdgcn_readlane(tb_desc, t)) : 0; };
   // dense: v = tile id; grouped: v = index into the workgroup's table
   auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
@@ -282,7 +297,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   const int a_piece = 32 * a_pitch, b_piece = 32 * b_pitch;        // bytes between pieces
   const lds_u8 a_wr = lds3 + (w * 8 + lr) * kRow + ((lp ^ lkey) << 4);    // + stage * kBlk + i * 4096
 
-  u32x4 stg[16];                                                   // A staging: slot (T & 1) * 8 + i
+  u32x4 stg[2 * NA];                                               // A staging: slot (T & 1) * NA + i
   // cross = false: the caller knows T < nk (steady part of the K loop), nothing of the next tile is looked at
   // The staging loads are asm statements: the compiler then keeps no wait-count bookkeeping for them
   // (what it keeps is merged conservatively over all paths into a loop and comes out as waits for
@@ -316,19 +331,19 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   lds_u8 fax[2], fbx[2];                                           // row base + swizzled chunk, per sub-step
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
-    fax[s] = lds3 + (wm * 128 + fr) * kRow + (((4 * s + fq) ^ fkey) << 4);
+    fax[s] = lds3 + (wm * (16 * MR) + fr) * kRow + (((4 * s + fq) ^ fkey) << 4);
     fbx[s] = lds3 + (wn * (NB / 2) + fr) * kRow + (((4 * s + fq) ^ fkey) << 4);
   }
 
-  f32x4 acc[8][NJ];
+  f32x4 acc[MR][NJ];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < MR; ++i)
 #pragma unroll
     for (int j = 0; j < NJ; ++j)
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  bf16x8 fa[8], fb[2][NJ];    // A fragment i serves one row of 8 MFMAs and is re-read right after it; B is double-buffered
+  bf16x8 fa[MR], fb[2][NJ];    // A fragment i serves one row of 8 MFMAs and is re-read right after it; B is double-buffered
 
   // ---- VGPR -> HBM.  Operands are swapped in the MFMA, so lane l holds, for fragment (i, j), the 4
   //      consecutive columns j*16 + 4*(l/16) .. +3 of row i*16 + l%16 of the wave's 128 x 128 sub-tile:
@@ -345,10 +360,10 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     if constexpr (GROUPED) {
       const int row0 = __builtin_amdgcn_readlane(tb_row0, vv), dsc = __builtin_amdgcn_readlane(tb_desc, vv);
       const int tn = desc_tn(dsc);
-      int rows = desc_rows(dsc) - wm * 128;                          // rows of the tile that fall to this wave
-      rows = rows < 0 ? 0 : (rows > 128 ? 128 : rows);
+      int rows = desc_rows(dsc) - wm * (16 * MR);                    // rows of the tile that fall to this wave
+      rows = rows < 0 ? 0 : (rows > 16 * MR ? 16 * MR : rows);
       constexpr int CW = GATED ? NB / 4 : NB / 2;                    // columns of C this wave writes
-      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * 128) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
+      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * (16 * MR)) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
                     rows ? (uint32_t)(((rows - 1) * g.ldc + CW) * 2) : 0u);
       c_rowblk = (int)(16 * g.ldc * 2);
       return;
@@ -433,21 +448,25 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const int bT = S == 0 ? kt + 2 : kt + 3;
     const int bslot = S == 0 ? bo2 : bo0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < MR; ++i) {
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         mfma_16x16x32<F16>(acc[i][j], fb[CUR][j], fa[i]);
         __builtin_amdgcn_sched_barrier(0);
-        if (i < 4 && (j == 1 || j == 5) && 2 * i + (j == 5) < NJ)
-          fb[NXT][2 * i + (j == 5)] = lds_read(pb + (2 * i + (j == 5)) * 16 * kRow);
+        // (with 4 rows the reads sit earlier in the row: the last fragment is needed 9 MFMAs after row 3 ends)
+        constexpr int jb0 = MR == 8 ? 1 : 0, jb1 = MR == 8 ? 5 : 3;
+        if (i < 4 && (j == jb0 || j == jb1) && 2 * i + (j == jb1) < NJ)
+          fb[NXT][2 * i + (j == jb1)] = lds_read(pb + (2 * i + (j == jb1)) * 16 * kRow);
         if (j == NJ - 1) fa[i] = lds_read(pa + i * 16 * kRow);
-        if ((i & 1) == 0 && j == 2) b_load(bT, (S == 0 ? 4 : 0) + (i >> 1), bslot, CROSS);
-        if ((i & 1) == 1 && j == 2) {
-          const int p = (S == 0 ? 4 : 0) + (i >> 1);
-          // the load that filled this slot was issued 4 sub-steps ago; 31 loads have been issued since
-          asm volatile("s_waitcnt vmcnt(31)" ::: "memory");
-          a_write(WST, p, stg[WST * 8 + p]);
-          stg[WST * 8 + p] = a_load(wT + 2, p, CROSS);
+        // four B loads per sub-step: after MFMA j = 2 of the even rows (8 rows), or of every row (4 rows)
+        if (MR == 8 ? ((i & 1) == 0 && j == 2) : j == 2) b_load(bT, (S == 0 ? 4 : 0) + (MR == 8 ? i >> 1 : i), bslot, CROSS);
+        // HA staged A pieces per sub-step: after MFMA j = 2 (8 rows) or j = 6 (4 rows) of the odd rows
+        if ((i & 1) == 1 && j == (MR == 8 ? 2 : 6)) {
+          const int p = (S == 0 ? HA : 0) + (i >> 1);
+          // the load that filled this slot was issued 4 sub-steps ago; kWaitSlot loads have been issued since
+          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWaitSlot) : "memory");
+          a_write(WST, p, stg[WST * NA + p]);
+          stg[WST * NA + p] = a_load(wT + 2, p, CROSS);
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -456,7 +475,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
       // Own reads of step kt and own writes of step kt+1 are complete, and so are own B loads of step
       // kt+1 (the 17 younger loads may still be in flight).  After the barrier step kt+1 is readable
       // by every wave and nobody reads step kt any more.
-      asm volatile("s_waitcnt vmcnt(17) lgkmcnt(0)" ::: "memory");
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kWaitStep) : "memory");
       wg_barrier();
     }
   };
@@ -471,22 +490,22 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   //      pieces 0..3 of step 1 of A go straight to LDS; the staging slots are filled oldest first in
   //      the order the loop consumes them, so that the counted waits of the first steps hold as well.
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a_direct(0, i, 0);
+  for (int i = 0; i < NA; ++i) a_direct(0, i, 0);
   if (nk > 1) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a_direct(1, i, 1);
+    for (int i = 0; i < HA; ++i) a_direct(1, i, 1);
   } else {                                                         // a single K-step per tile: step 1 belongs to the next tile
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
+    for (int i = 0; i < HA; ++i)
       __builtin_amdgcn_raw_ptr_buffer_load_lds(nxt.ra, (lds_ptr)(lds3 + kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
                                                i * a_piece + kcol(0, nxt.rot) * a_kstep, 0, 0);
   }
 #pragma unroll
-  for (int i = 4; i < 8; ++i) stg[8 + i] = a_load(1, i, true);
+  for (int i = HA; i < NA; ++i) stg[NA + i] = a_load(1, i, true);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) stg[i] = a_load(2, i, true);
+  for (int i = 0; i < NA; ++i) stg[i] = a_load(2, i, true);
 #pragma unroll
-  for (int i = 0; i < 4; ++i) stg[8 + i] = a_load(3, i, true);
+  for (int i = 0; i < HA; ++i) stg[NA + i] = a_load(3, i, true);
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
 #pragma unroll
@@ -498,7 +517,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
 #pragma unroll
   for (int f = 0; f < NJ; ++f) fb[0][f] = lds_read(fbx[0] + bo0 + f * 16 * kRow);
 #pragma unroll
-  for (int f = 0; f < 8; ++f) fa[f] = lds_read(fax[0] + f * 16 * kRow);
+  for (int f = 0; f < MR; ++f) fa[f] = lds_read(fax[0] + f * 16 * kRow);
 
   // ---- all K-steps of all tiles of this workgroup, one uninterrupted pipeline.  The host launches
   //      more than one tile per workgroup only when nk is even (the A stage and staging slots of a
@@ -521,7 +540,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
     __builtin_amdgcn_sched_barrier(0);                             // no accumulator read may move above the padding
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < MR; ++i) {
       if constexpr (GATED) {
 #pragma unroll
         for (int j = 0; j < NJ; j += 4) store_gated_quad(i, j);
@@ -554,6 +573,11 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_gated_kernel(Gem
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true, false, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, true>(g); }
+// grouped, tiles of 128 rows (small groups)
+__global__ __launch_bounds__(256, 1) void gemm_bf16_128_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, false, 4>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_128_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, false, 4>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_128_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true, 4>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_128_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, true, 4>(g); }
 
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -579,21 +603,29 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
 // most 64 tiles, one per lane: beyond 64 x CUs tiles in the worst case more workgroups are launched);
 // otherwise one workgroup per possible tile, those without a tile leave at once.
 hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
-  const int64_t worst = (g.M / kTile + g.groups) * (int64_t)g.grid_n;
+  // tiles of 128 rows while the groups are small on average (the host knows M, not the group sizes)
+  static const int small_avg = [] { const char* v = getenv("AXE_GROUPED_TILE128_ROWS"); return v ? atoi(v) : 128; }();
+  const bool t128 = g.tile_m ? g.tile_m == 128 : g.M <= (int64_t)small_avg * g.groups;
+  const int tm = t128 ? 128 : kTile;
+  const int64_t worst = (g.M / tm + g.groups) * (int64_t)g.grid_n;
   const int nk = (int)(g.K / 64);
   const int cus = cu_count();
   const bool chain = (nk % 2 == 0) && nk >= 4;
   int64_t nwg = chain ? std::max<int64_t>(cus, (worst + 63) / 64) : worst;
   nwg = (nwg + 7) / 8 * 8;                                         // the tile sequence is cut into 8 parts, one per XCD
   if (nwg > 0x7fffffff) return hipErrorInvalidValue;
-  if (g.gated && g.f16)
-    hipLaunchKernelGGL(gemm_f16_256_grouped_gated_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
-  else if (g.gated)
-    hipLaunchKernelGGL(gemm_bf16_256_grouped_gated_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
-  else if (g.f16)
-    hipLaunchKernelGGL(gemm_f16_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
-  else
-    hipLaunchKernelGGL(gemm_bf16_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  const dim3 grid((unsigned)nwg), block(256);
+  const int which = (t128 ? 4 : 0) + (g.f16 ? 2 : 0) + (g.gated ? 1 : 0);
+  switch (which) {
+    case 0: hipLaunchKernelGGL(gemm_bf16_256_grouped_kernel, grid, block, 0, s, g); break;
+    case 1: hipLaunchKernelGGL(gemm_bf16_256_grouped_gated_kernel, grid, block, 0, s, g); break;
+    case 2: hipLaunchKernelGGL(gemm_f16_256_grouped_kernel, grid, block, 0, s, g); break;
+    case 3: hipLaunchKernelGGL(gemm_f16_256_grouped_gated_kernel, grid, block, 0, s, g); break;
+    case 4: hipLaunchKernelGGL(gemm_bf16_128_grouped_kernel, grid, block, 0, s, g); break;
+    case 5: hipLaunchKernelGGL(gemm_bf16_128_grouped_gated_kernel, grid, block, 0, s, g); break;
+    case 6: hipLaunchKernelGGL(gemm_f16_128_grouped_kernel, grid, block, 0, s, g); break;
+    default: hipLaunchKernelGGL(gemm_f16_128_grouped_gated_kernel, grid, block, 0, s, g); break;
+  }
   return hipGetLastError();
 }
 

@@ -546,7 +546,7 @@ def test_gemm_is_bitwise_repeatable(which):
 SENTINEL = 0x7FC1          # a NaN pattern in bf16 and in binary16: rows of C that belong to no group must keep it
 
 
-def run_grouped(g: W.GroupedGemmInputs, lda=None, ldb=None, ldg=None, ldc=None, rows_on_device=None, kernel=B.AXE_GROUPED_TILES):
+def run_grouped(g: W.GroupedGemmInputs, lda=None, ldb=None, ldg=None, ldc=None, rows_on_device=None, kernel=B.AXE_GROUPED_TILES_256):
     """Launches axe_gemm_grouped; returns (C decoded to fp64, raw C words), both (M, N)."""
     lda_, ldb_, ldc_ = lda or g.K, ldb or g.K, ldc or g.N
     ldg_ = ldg or g.N * ldb_
@@ -597,7 +597,7 @@ GROUPED_CASES = [
 ]
 
 
-KERNELS = [B.AXE_GROUPED_TILES, B.AXE_GROUPED_STREAM]
+KERNELS = [B.AXE_GROUPED_TILES_256, B.AXE_GROUPED_TILES_128, B.AXE_GROUPED_STREAM]
 
 
 @pytest.mark.parametrize("kernel", KERNELS)
@@ -634,13 +634,14 @@ def test_gemm_grouped_offsets_out_of_range_are_clamped():
     check_grouped(g, c, raw, ref)
 
 
+@pytest.mark.parametrize("kernel", [B.AXE_GROUPED_TILES_256, B.AXE_GROUPED_TILES_128])
 @pytest.mark.parametrize("which", ["gemm1", "gemm2"])
-def test_gemm_grouped_moe_layer_shapes_full_size(which):
+def test_gemm_grouped_moe_layer_shapes_full_size(which, kernel):
     """The two grouped GEMMs of the MoE layer at 4096 tokens (32768 routed rows, 128 experts), in the launch
     configuration the benchmark times; the oracle computes sampled groups' 128-column blocks, rows at group
     borders, and randomised projections over every group."""
     g = (W.moe_gemm1 if which == "gemm1" else W.moe_gemm2)(4096)
-    c, raw = run_grouped(g)
+    c, raw = run_grouped(g, kernel=kernel)
     assert np.isfinite(c).all()
     off = g.group_rows
     bl = g.b_gnk.transpose(0, 2, 1)
@@ -737,9 +738,10 @@ def test_relayout_produces_the_blocked_operand_layout():
     assert np.array_equal(dst.cpu().numpy().view(np.uint16), W.pack_blocked(b_nk))
 
 
+@pytest.mark.parametrize("kernel", [B.AXE_GROUPED_TILES_256, B.AXE_GROUPED_TILES_128])
 @pytest.mark.parametrize("blocked", [False, True])
 @pytest.mark.parametrize("off,N,K", [([0, 300, 520, 1300, 1301, 2000], 768, 512), ([5, 6, 6, 270], 256, 192)])
-def test_gemm_grouped_gated_epilogue(off, N, K, blocked):
+def test_gemm_grouped_gated_epilogue(off, N, K, blocked, kernel):
     """First group GEMM of the MoE layer with the gated activation fused: C = silu(A Wg) * (A Wu), (M, N / 2)."""
     M = off[-1] + 3
     g = W.gemm_grouped_bf16(off, N, K, 94, M=M, std_b=2.0 * K ** -0.5)      # products of a few units: silu is well off its linear part
@@ -749,7 +751,8 @@ def test_gemm_grouped_gated_epilogue(off, N, K, blocked):
     dC = torch.full((M * (N // 2),), SENTINEL, dtype=torch.int16, device="cuda")
     dR = torch.from_numpy(g.group_rows).cuda()
     desc = B.GroupedGemmDesc(M, N, K, g.G, B.Layout(W.row_major_spec(M, K)), B.Layout(W.gated_b_spec(K, N, g.G, blocked)),
-                             B.Layout(W.row_major_spec(M, N // 2)), M * K, img.size, M * (N // 2), epilogue=B.AXE_EPI_SWIGLU)
+                             B.Layout(W.row_major_spec(M, N // 2)), M * K, img.size, M * (N // 2), epilogue=B.AXE_EPI_SWIGLU,
+                             kernel_hint=kernel)
     B.axe_gemm_grouped(desc, dA, dB, dC, dR)
     torch.cuda.synchronize()
     raw = dC.cpu().numpy().view(np.uint16).reshape(M, N // 2)
@@ -904,10 +907,11 @@ def test_gemm_grouped_f16_plain_and_gated():
     g = W.gemm_grouped_bf16(off, N, K, 100, std_b=2.0 * K ** -0.5, dtype="f16")
     bl = g.b_gnk.transpose(0, 2, 1)
     P = R.gemm_grouped_ref(g.a_mk, bl, off, R.AXE_F16)
-    c, raw = run_grouped(g)
     owned = ~np.isnan(P[:, 0])
-    assert R.rel_frobenius(c[owned], P[owned]) <= F16_TOL
-    check_grouped(g, c, raw, P)
+    for kernel in KERNELS:
+        c, raw = run_grouped(g, kernel=kernel)
+        assert R.rel_frobenius(c[owned], P[owned]) <= F16_TOL, kernel
+        check_grouped(g, c, raw, P)
     # gated
     img = W.pack_blocked(W.pack_gate_up(g.b_gnk))
     dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
