@@ -170,7 +170,7 @@ def bench_grouped(steps, warmup, tokens=4096, dtype="f16"):
         flops = 2.0 * g.M * g.N * g.K
         sizes = np.diff(g.group_rows)
         nbytes = 2.0 * (int((sizes > 0).sum()) * g.N * g.K + g.M * g.K + g.M * g.N)
-        r = {"M": g.M, "N": g.N, "K": g.K, "tiles": int(np.ceil(sizes / 256).sum()) * (g.N // 256), "algorithmic_bytes": nbytes}
+        r = {"M": g.M, "N": g.N, "K": g.K, "tiles": int(np.ceil(sizes / 128).sum()) * (g.N // 256), "algorithmic_bytes": nbytes}
         for label, spec_b, buf in (("plain", Bs, dB), ("blocked", Bblk, dBblk)):
             desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(spec_b), B.Layout(Cs), g.M * g.K, g.b_gnk.size, g.M * g.N,
                                      in_dtype=dt, out_dtype=dt)
@@ -190,7 +190,7 @@ def bench_grouped(steps, warmup, tokens=4096, dtype="f16"):
             log(f"[bench]   with the gated activation fused (C = silu(gate) * up, {g.N // 2} wide): {devms*1e3:.0f} us")
             del dH
         out[name] = r
-        log(f"[bench] grouped {dtype} GEMM {name} {tokens} tokens (M={g.M} N={g.N} K={g.K}, {g.G} experts, {r['tiles']} tiles): "
+        log(f"[bench] grouped {dtype} GEMM {name} {tokens} tokens (M={g.M} N={g.N} K={g.K}, {g.G} experts, {r['tiles']} tiles of 128 x 256): "
             f"plain weights {r['plain']['kernel_ms']*1e3:.0f} us = {r['plain']['tflops']:.0f} TFLOP/s, {r['plain']['GBps']:.0f} GB/s; "
             f"blocked weights {r['blocked']['kernel_ms']*1e3:.0f} us = {r['blocked']['tflops']:.0f} TFLOP/s, {r['blocked']['GBps']:.0f} GB/s")
         del dA, dB, dBblk, dC

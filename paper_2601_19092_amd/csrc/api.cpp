@@ -809,7 +809,7 @@ int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const vo
                      const int32_t* d_group_rows, void* stream) {
   GemmArgs a;
   if (int rc = plan_gemm_grouped(g, d_A, d_B, d_C, d_group_rows, a, true)) return rc;
-  const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 16 * (int64_t)g->G);
+  const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G);
   hipError_t e = stream_kernel ? launch_gemm_grouped_stream(a, (hipStream_t)stream) : launch_gemm_bf16_256_grouped(a, (hipStream_t)stream);
   return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm_grouped");
 }

@@ -603,8 +603,10 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
 // most 64 tiles, one per lane: beyond 64 x CUs tiles in the worst case more workgroups are launched);
 // otherwise one workgroup per possible tile, those without a tile leave at once.
 hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
-  // tiles of 128 rows while the groups are small on average (the host knows M, not the group sizes)
-  static const int small_avg = [] { const char* v = getenv("AXE_GROUPED_TILE128_ROWS"); return v ? atoi(v) : 128; }();
+  // tiles of 128 rows unless the groups are large on average (the host knows M, not the group sizes): measured
+  // on an MoE layer (128 groups, N = 1536, K = 2048) 128-row tiles win by 12 - 25 % up to 512 rows per group, by 5 %
+  // at 1024, and lose 3 % at 2048 (AXE_GROUPED_TILE128_ROWS overrides the threshold for experiments)
+  static const int small_avg = [] { const char* v = getenv("AXE_GROUPED_TILE128_ROWS"); return v ? atoi(v) : 1536; }();
   const bool t128 = g.tile_m ? g.tile_m == 128 : g.M <= (int64_t)small_avg * g.groups;
   const int tm = t128 ? 128 : kTile;
   const int64_t worst = (g.M / tm + g.groups) * (int64_t)g.grid_n;
