@@ -1035,3 +1035,25 @@ def test_gemm_fp8_row_scaled_activations(M, N, K, scale_dtype):
     assert R.rel_frobenius(c, ref) <= FP8_TOL
     for i in range(0, M, 16):                                # per 16 rows: a scale applied to the wrong row cannot hide
         assert R.rel_frobenius(c[i:i + 16], ref[i:i + 16]) <= FP8_TOL, i
+
+
+@pytest.mark.parametrize("kernel", KERNELS)
+def test_gemm_grouped_largest_group_count(kernel):
+    """4096 groups (the limit of the tile table's packing), most of them empty, a few large ones."""
+    G = 4096
+    rng = np.random.default_rng(6)
+    sizes = np.zeros(G, dtype=np.int64)
+    hot = rng.choice(G, 300, replace=False)
+    sizes[hot] = rng.integers(1, 40, 300)
+    sizes[[0, G - 1, 2047]] = [130, 257, 64]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    M, N, K = int(off[-1]), 256, 64
+    a = W.to_bf16_bits(W.normal(104, (M, K)))
+    base = W.to_bf16_bits(W.normal(105, (64, N, K), K ** -0.5))
+    b = base[np.arange(G) % 64] ^ (np.arange(G, dtype=np.uint16) % 2 * 0x8000)[:, None, None]     # 64 distinct matrices, sign flipped per parity
+    g = W.GroupedGemmInputs(M, N, K, G, a, np.ascontiguousarray(b), off.astype(np.int32))
+    c, raw = run_grouped(g, kernel=kernel)
+    ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16)
+    assert np.isfinite(c).all() and R.rel_frobenius(c, ref) <= BF16_TOL
+    for e in np.nonzero(sizes)[0]:
+        assert R.rel_frobenius(c[off[e]:off[e + 1]], ref[off[e]:off[e + 1]]) <= BF16_TOL, e
