@@ -34,7 +34,7 @@ int env_int(const char* name, int dflt) {
 
 extern "C" {
 
-int32_t axe_version(void) { return 100; }
+int32_t axe_version(void) { return 10300; }   // 1.3.0: grouped GEMM, fp16, blocked operands, per-row scales (descriptor fields added)
 
 const char* axe_strerror(int code) {
   switch (code) {

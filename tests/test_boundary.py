@@ -24,7 +24,7 @@ def test_library_exports_every_declared_symbol():
     assert set(names) == set(B.EXPORTS)
     for n in names:
         assert getattr(L, n) is not None
-    assert B.version() >= 100
+    assert B.version() >= 10300
     assert b"shape" in L.axe_strerror(B.AXE_ESHAPE)
 
 
