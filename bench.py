@@ -256,10 +256,12 @@ def bench_eval(steps, warmup):
     rows = cols = 8192
     L = B.Layout(W.blocked_swizzled_spec(rows, cols))
     n = rows * cols
-    out = torch.empty((n, 1, 1), dtype=torch.int64, device="cuda")
-    wall, devms = time_loop(lambda i: B.axe_layout_eval(L, (rows, cols), n, None, out), steps, warmup)
+    outs = [torch.empty((n, 1, 1), dtype=torch.int64, device="cuda") for _ in range(2)]      # 512 MiB each: nothing stays in a cache
+    wall, devms = time_loop(lambda i: B.axe_layout_eval(L, (rows, cols), n, None, outs[i % 2]), steps, warmup)
     r = {"points": n, "kernel_ms": devms, "Gpoints_per_s": n / (devms * 1e-3) / 1e9, "GBps_written": n * 8 / (devms * 1e-3) / 1e9}
-    log(f"[bench] layout eval 2^26 points: {devms:.4f} ms, {r['Gpoints_per_s']:.1f} Gpoint/s")
+    r["frac_of_hbm_peak"] = r["GBps_written"] / PEAK["hbm"]
+    log(f"[bench] layout eval 2^26 points: {devms:.4f} ms, {r['Gpoints_per_s']:.1f} Gpoint/s, {r['GBps_written']:.0f} GB/s written "
+        f"({100 * r['frac_of_hbm_peak']:.1f}% of HBM peak)")
     return r
 
 

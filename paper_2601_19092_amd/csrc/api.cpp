@@ -87,6 +87,7 @@ int axe_layout_eval(const axe_layout_t* L, int32_t rank, const int64_t* shape, i
     d.ext[k] = h.D[k].e;
     d.str[k] = h.D[k].s;
     d.axis[k] = h.D[k].axis;
+    d.shift[k] = is_pow2(h.D[k].e) ? ilog2(h.D[k].e) : -1;
   }
   for (int k = 0; k < d.n_r; ++k) {
     d.rext[k] = h.R[k].e;

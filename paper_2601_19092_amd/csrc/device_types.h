@@ -18,6 +18,7 @@ struct Swz {
 struct EvalDesc {
   int32_t n_d, n_r, n_axes;
   int32_t use32;               // E_D < 2^31: digit arithmetic in 32 bits
+  int32_t shift[kMaxD];        // log2(ext) when ext is a power of two, else -1
   int64_t ext[kMaxD], str[kMaxD];
   int32_t axis[kMaxD];
   int64_t rext[kMaxR], rstr[kMaxR];

@@ -64,8 +64,107 @@ __global__ __launch_bounds__(256) void layout_eval_kernel(EvalDesc d, int64_t n,
   }
 }
 
+// The common case -- no replicas, fewer than 2^31 points, at most 4 axes -- without the generic loop's
+// 64-bit divisions and 8-way axis selects: digits in 32 bits (a shift and a mask where the extent is a
+// power of two), one 64-bit multiply-add per digit, the axis loop unrolled to NAX.  A thread evaluates
+// PTS consecutive indices (4 when there is a single axis: two 16-byte stores), so that an iter's
+// parameters are fetched once for all of them.  Bound: the 8 NAX bytes written per index.
+template <int NAX, int PTS>
+__global__ __launch_bounds__(256) void layout_eval_fast_kernel(EvalDesc d, int64_t n, const int64_t* __restrict__ idx,
+                                                               int64_t* __restrict__ out) {
+  // index of the thread's p-th point: a wave owns 64 PTS consecutive indices; with one axis a lane takes pairs
+  // (2 lane, 2 lane + 1) 128 apart, so that every store instruction of the wave writes 1 contiguous KiB;
+  // otherwise lane-interleaved single indices (each store instruction 64 NAX x 8 contiguous bytes).
+  const int64_t t = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = (int)(t & 63);
+  const int64_t wbase = (t >> 6) * (64 * PTS);
+  auto index_of = [&](int p) -> int64_t {
+    return (NAX == 1 && PTS % 2 == 0) ? wbase + (p >> 1) * 128 + lane * 2 + (p & 1) : wbase + p * 64 + lane;
+  };
+  if (wbase >= n) return;
+  int64_t x[PTS], c[PTS][NAX];
+  uint32_t rem[PTS];
+#pragma unroll
+  for (int p = 0; p < PTS; ++p) {
+    const int64_t ip = index_of(p);
+    const int64_t i = ip < n ? ip : n - 1;                         // (a ragged tail repeats the last index; not stored)
+    x[p] = idx ? idx[i] : i;
+    rem[p] = (uint32_t)x[p];
+#pragma unroll
+    for (int a = 0; a < NAX; ++a) c[p][a] = d.off[a];
+  }
+  // digits outermost: an iter's parameters are fetched once for the thread's PTS indices
+  for (int k = d.n_d - 1; k >= 0; --k) {
+    const int sh = d.shift[k];
+    const uint32_t e = (uint32_t)d.ext[k];
+    const int64_t st = d.str[k];
+    const int ax = d.axis[k];
+#pragma unroll
+    for (int p = 0; p < PTS; ++p) {
+      uint32_t dig;
+      if (sh >= 0) {
+        dig = rem[p] & (e - 1u);
+        rem[p] >>= sh;
+      } else {
+        const uint32_t q = rem[p] / e;
+        dig = rem[p] - q * e;
+        rem[p] = q;
+      }
+      const int64_t v = (int64_t)dig * st;
+      if (NAX == 1) {
+        c[p][0] += v;
+      } else {
+#pragma unroll
+        for (int a = 0; a < NAX; ++a) c[p][a] += (a == ax) ? v : 0;
+      }
+    }
+  }
+#pragma unroll
+  for (int p = 0; p < PTS; ++p) {
+    const bool bad = x[p] < 0 || x[p] >= d.E_D;
+#pragma unroll
+    for (int a = 0; a < NAX; ++a) {
+      int64_t v = c[p][a];
+      if (a == d.swz_axis) v = swz_apply(v, d.swz);
+      c[p][a] = bad ? INT64_MIN : v;
+    }
+  }
+  typedef __attribute__((ext_vector_type(2))) int64_t i64x2;
+  if (NAX == 1 && PTS % 2 == 0) {                                  // out is 16-byte aligned (the host checks), the pair's first index is even
+#pragma unroll
+    for (int p = 0; p < PTS; p += 2) {
+      const int64_t ip = index_of(p);
+      if (ip + 1 < n) __builtin_nontemporal_store(i64x2{c[p][0], c[p + 1][0]}, (i64x2*)(out + ip));
+      else if (ip < n) out[ip] = c[p][0];
+    }
+  } else {
+#pragma unroll
+    for (int p = 0; p < PTS; ++p) {
+      const int64_t ip = index_of(p);
+      if (ip < n) {
+#pragma unroll
+        for (int a = 0; a < NAX; ++a) __builtin_nontemporal_store(c[p][a], &out[ip * NAX + a]);
+      }
+    }
+  }
+}
+
 hipError_t launch_layout_eval(const EvalDesc& d, int64_t n, const int64_t* idx, int64_t* out, hipStream_t s) {
   if (n <= 0) return hipSuccess;
+  if (d.use32 && d.E_R == 1 && d.n_r == 0 && d.n_axes <= 4 && n < (int64_t(1) << 40)) {
+    const bool vec = d.n_axes == 1 && ((uintptr_t)out & 15) == 0;  // 4 indices per thread, two 16-byte stores
+    const int pts = d.n_axes == 1 ? (vec ? 4 : 1) : 2;
+    const int64_t threads = (n + pts - 1) / pts;
+    const dim3 grid((unsigned)((threads + 255) / 256)), block(256);
+    switch (d.n_axes * 2 + (vec ? 1 : 0)) {
+      case 3: hipLaunchKernelGGL((layout_eval_fast_kernel<1, 4>), grid, block, 0, s, d, n, idx, out); break;
+      case 2: hipLaunchKernelGGL((layout_eval_fast_kernel<1, 1>), grid, block, 0, s, d, n, idx, out); break;
+      case 4: hipLaunchKernelGGL((layout_eval_fast_kernel<2, 2>), grid, block, 0, s, d, n, idx, out); break;
+      case 6: hipLaunchKernelGGL((layout_eval_fast_kernel<3, 2>), grid, block, 0, s, d, n, idx, out); break;
+      default: hipLaunchKernelGGL((layout_eval_fast_kernel<4, 2>), grid, block, 0, s, d, n, idx, out); break;
+    }
+    return hipGetLastError();
+  }
   int64_t blocks = (n + 255) / 256;
   if (blocks > 65536 * 4) blocks = 65536 * 4;
   if (d.use32)

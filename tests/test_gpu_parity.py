@@ -99,6 +99,27 @@ def test_eval_random_layouts_and_explicit_indices():
     assert list(got) == [3, np.iinfo(np.int64).min, np.iinfo(np.int64).min, 15]
 
 
+@pytest.mark.parametrize("axes", [["m"], ["m", "lane"], ["m", "lane", "reg"], ["m", "lane", "reg", "gpuid"], ["m", "a", "b", "c", "d"]])
+def test_eval_without_replicas_every_axis_count(axes):
+    """Layouts without replicas take a specialised kernel per number of axes (five axes: the general one); odd
+    point counts, extents that are no powers of two, negative strides, explicit indices with some out of range."""
+    rng = random.Random(len(axes))
+    for trial in range(6):
+        ext = [rng.choice([2, 3, 4, 5, 7, 8, 16]) for _ in range(rng.randint(1, 5))]
+        D = [Iter(e, rng.choice([1, 2, 3, 17, 64, -5]) * rng.choice([1, 9]), rng.choice(axes)) for e in ext]
+        L = Layout(tuple(D), (), ax._norm_offset({a: rng.randint(0, 9) for a in axes}))
+        E = L.E_D
+        bl = B.Layout(spec_of(L), axes)
+        got = B.axe_layout_eval(bl, (E,), E).cpu().numpy()                       # implicit indices, E odd or even
+        want = R.evaluate_np(L, np.arange(E), axes)
+        assert np.array_equal(got, want), repr(L)
+        idx = np.array([E - 1, 0, -1, E, E // 2, 2 ** 40, 1 % E], dtype=np.int64)  # 7 indices: an odd count
+        got = B.axe_layout_eval(bl, (E,), len(idx), torch.from_numpy(idx).cuda()).cpu().numpy()
+        ok = (idx >= 0) & (idx < E)
+        assert np.array_equal(got[ok], R.evaluate_np(L, idx[ok], axes)), repr(L)
+        assert (got[~ok] == np.iinfo(np.int64).min).all()
+
+
 def test_eval_large_blocked_swizzled_layout():
     # the config-2 destination at full size: 2^26 points, compared on a strided sample plus both ends,
     # and as a permutation (every address exactly once) on the device result
