@@ -1,6 +1,9 @@
-// bf16 GEMM for gfx950 (MI355X), workgroup tile 256 x 256 x 64 (or 256 x 224 x 64), one workgroup of 4 waves per CU (one
+// bf16 (and fp16) GEMM for gfx950 (MI355X), workgroup tile 256 x 256 x 64 (or 256 x 224 x 64), one workgroup of 4 waves per CU (one
 // wave per SIMD); each wave owns a 128 x 128 sub-tile = 8 x 8 MFMA 16x16x32 fragments in 256
 // accumulator registers.  A is row-major (K contiguous), B column-major (K contiguous).
+// One body, instantiated as: the dense kernel (256 or 224 columns per tile), the dense kernel for operands
+// stored in blocks, the fp16 twins, and the grouped kernels of an MoE layer (tiles of 256 or 128 rows, plain or
+// gated epilogue) -- see the template parameters of gemm_bf16_256_body.
 //
 // Three measured facts shape the kernel:
 //  * On real (random) data the chip runs into its power limit long before the matrix pipe is full,
@@ -101,7 +104,7 @@ __device__ __forceinline__ uint32_t pack16(float lo, float hi) {
 }
 }  // namespace
 
-// Tiles of a grouped problem, counted group after group: group e has ceil(rows_e / 256) x grid_n of them
+// Tiles of a grouped problem, counted group after group: group e has ceil(rows_e / TM) x grid_n of them
 // (row blocks fastest).  Lane t of the calling wave receives the workgroup's t-th tile: its first row, its
 // number of rows (0: no such tile), its tile column and its group.  Workgroup ids are dealt round-robin
 // to the 8 XCDs, so XCD x takes the x-th eighth of the tile sequence and its 32 workgroups walk it side
@@ -174,7 +177,7 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 //
 // GROUPED: the grouped GEMM of an MoE layer.  The rows of A and C are sorted by group, group e owns rows
 // group_rows[e] .. group_rows[e + 1] - 1 (device memory: the host does not know them) and multiplies them with
-// its own B.  A tile is (group, 256 rows of that group, 256 columns); the rows a group does not fill are
+// its own B.  A tile is (group, 256 or 128 rows of that group, 256 columns); the rows a group does not fill are
 // outside the tile's buffer descriptors: they load as zero and their stores are dropped.  Each wave first
 // works out which tiles its workgroup owns (group_tiles below) and keeps them one per lane; the pipeline
 // then runs over them exactly as over the tiles of a dense problem.
