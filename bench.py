@@ -164,88 +164,73 @@ def bench_transpose(steps, warmup, n_pairs=4):
     return r
 
 
-def bench_grouped(steps, warmup, tokens=4096, dtype="f16"):
-    """The two grouped GEMMs of an MoE layer (hidden 2048, expert intermediate 768, 128 experts, 8 per token) at
-    `tokens` tokens, in fp16 like the paper's layer: routed rows sorted by expert, offsets on the device.  Weights as plain column-major
-    matrices and pre-packed into contiguous 256 x 64 blocks by axe_relayout (untimed, as a server would do once)."""
-    import torch
-    from paper_2601_19092_amd import binding as B
-    from paper_2601_19092_amd import workloads as W
-    out = {"tokens": tokens, "experts": W.MOE_EXPERTS, "experts_per_token": W.MOE_TOPK, "dtype": dtype}
-    dt = B.AXE_F16 if dtype == "f16" else B.AXE_BF16
-    for name, g in (("gemm1_gate_up", W.moe_gemm1(tokens, dtype=dtype)), ("gemm2_down", W.moe_gemm2(tokens, dtype=dtype))):
-        As, Bs, Cs = W.grouped_gemm_specs(g)
-        Bblk = W.blocked_b_spec(g.K, g.N, G=g.G)
-        dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_gnk.reshape(-1))
-        dBblk = torch.empty_like(dB)
-        B.axe_relayout(B.Layout(Bs), B.Layout(Bblk), (g.G, g.K, g.N), dB, dBblk)
-        assert np.array_equal(dBblk[:g.N * g.K].cpu().numpy().view(np.uint16), W.pack_blocked(g.b_gnk[0]))
-        dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
-        dR = torch.from_numpy(g.group_rows).cuda()
-        flops = 2.0 * g.M * g.N * g.K
-        sizes = np.diff(g.group_rows)
-        nbytes = 2.0 * (int((sizes > 0).sum()) * g.N * g.K + g.M * g.K + g.M * g.N)
-        r = {"M": g.M, "N": g.N, "K": g.K, "tiles": int(np.ceil(sizes / 128).sum()) * (g.N // 256), "algorithmic_bytes": nbytes}
-        for label, spec_b, buf in (("plain", Bs, dB), ("blocked", Bblk, dBblk)):
-            desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(spec_b), B.Layout(Cs), g.M * g.K, g.b_gnk.size, g.M * g.N,
-                                     in_dtype=dt, out_dtype=dt)
-            wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, buf, dC, dR), steps, warmup)
-            r[label] = {"kernel_ms": devms, "tflops": flops / (devms * 1e-3) / 1e12, "GBps": nbytes / (devms * 1e-3) / 1e9}
-        if name == "gemm1_gate_up":
-            # the same GEMM with the gated activation fused (C half as wide); gate / up interleaved and blocked by axe_relayout
-            Bg = W.gated_b_spec(g.K, g.N, g.G, blocked=True)
-            B.axe_relayout(B.Layout(Bs), B.Layout(Bg), (g.G, g.K, g.N), dB, dBblk)
-            assert np.array_equal(dBblk[:g.N * g.K].cpu().numpy().view(np.uint16), W.pack_blocked(W.pack_gate_up(g.b_gnk[:1]))[0])
-            dH = torch.zeros(g.M * (g.N // 2), dtype=torch.int16, device="cuda")
-            desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(As), B.Layout(Bg), B.Layout(W.row_major_spec(g.M, g.N // 2)),
-                                     g.M * g.K, g.b_gnk.size, g.M * (g.N // 2), in_dtype=dt, out_dtype=dt, epilogue=B.AXE_EPI_SWIGLU)
-            wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dBblk, dH, dR), steps, warmup)
-            r["blocked_gated"] = {"kernel_ms": devms, "tflops": flops / (devms * 1e-3) / 1e12,
-                                  "GBps": (nbytes - g.M * g.N) / (devms * 1e-3) / 1e9}
-            log(f"[bench]   with the gated activation fused (C = silu(gate) * up, {g.N // 2} wide): {devms*1e3:.0f} us")
-            del dH
-        out[name] = r
-        log(f"[bench] grouped {dtype} GEMM {name} {tokens} tokens (M={g.M} N={g.N} K={g.K}, {g.G} experts, {r['tiles']} tiles of 128 x 256): "
-            f"plain weights {r['plain']['kernel_ms']*1e3:.0f} us = {r['plain']['tflops']:.0f} TFLOP/s, {r['plain']['GBps']:.0f} GB/s; "
-            f"blocked weights {r['blocked']['kernel_ms']*1e3:.0f} us = {r['blocked']['tflops']:.0f} TFLOP/s, {r['blocked']['GBps']:.0f} GB/s")
-        del dA, dB, dBblk, dC
-    out["decode"] = bench_grouped_decode(steps, warmup, dtype)
-    out["layer_kernel_ms"] = out["gemm1_gate_up"]["blocked_gated"]["kernel_ms"] + out["gemm2_down"]["blocked"]["kernel_ms"]
-    log(f"[bench] MoE layer expert compute (gemm1 + activation, gemm2) at {tokens} tokens: {out['layer_kernel_ms']*1e3:.0f} us")
-    return out
-
-
-def bench_grouped_decode(steps, warmup, dtype, tokens=64):
-    """The same layer at a decode batch size (few rows per expert): the library picks its weight-streaming kernel;
-    gemm1 with the gated activation, blocked weights.  Bound: HBM (the active experts' weights are read once)."""
+def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
+    """The expert computation of an MoE layer (hidden 2048, expert intermediate 768, 128 experts, 8 per token), in fp16
+    like the paper's layer: gemm1 (gate and up projections, gated activation fused) and gemm2 (down projection) as
+    grouped GEMMs over the routed rows sorted by expert, offsets on the device, over a sweep of token counts as in the
+    paper's figure.  Weights are packed once by axe_relayout (untimed, as a server would do at load time) into
+    contiguous 256 x 64 blocks, gate and up rows interleaved for gemm1.  At the largest count gemm1 and gemm2 are also
+    timed without the epilogue on plain and on blocked weights."""
     import torch
     from paper_2601_19092_amd import binding as B
     from paper_2601_19092_amd import workloads as W
     dt = B.AXE_F16 if dtype == "f16" else B.AXE_BF16
-    out = {"tokens": tokens}
-    total = 0.0
-    for name, g, gated in (("gemm1_gate_up_gated", W.moe_gemm1(tokens, dtype=dtype), True), ("gemm2_down", W.moe_gemm2(tokens, dtype=dtype), False)):
-        NC = g.N // 2 if gated else g.N
-        plain = B.Layout(W.grouped_gemm_specs(g)[1])
-        Bs = B.Layout(W.gated_b_spec(g.K, g.N, g.G, True) if gated else W.blocked_b_spec(g.K, g.N, G=g.G))
-        dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_gnk.reshape(-1))
-        dBp = torch.empty_like(dB)
-        B.axe_relayout(plain, Bs, (g.G, g.K, g.N), dB, dBp)
-        dC = torch.zeros(g.M * NC, dtype=torch.int16, device="cuda")
-        dR = torch.from_numpy(g.group_rows).cuda()
-        desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(W.row_major_spec(g.M, g.K)), Bs, B.Layout(W.row_major_spec(g.M, NC)),
-                                 g.M * g.K, g.b_gnk.size, g.M * NC, in_dtype=dt, out_dtype=dt,
-                                 epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE)
-        wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dBp, dC, dR), steps, warmup)
-        active = int((np.diff(g.group_rows) > 0).sum())
-        nbytes = 2.0 * (active * g.N * g.K + g.M * g.K + g.M * NC)
-        out[name] = {"M": g.M, "active_experts": active, "kernel_ms": devms, "algorithmic_bytes": nbytes,
-                     "GBps": nbytes / (devms * 1e-3) / 1e9, "frac_of_hbm_peak": nbytes / (devms * 1e-3) / 1e9 / PEAK["hbm"]}
-        total += devms
-        log(f"[bench] grouped {dtype} GEMM {name} at {tokens} tokens (M={g.M}, {active} active experts), streaming kernel: "
-            f"{devms*1e3:.0f} us, {out[name]['GBps']:.0f} GB/s ({100*out[name]['frac_of_hbm_peak']:.1f}% of HBM peak)")
-        del dA, dB, dBp, dC
-    out["layer_kernel_ms"] = total
+    top = max(sweep)
+    full = {"gemm1": W.moe_gemm1(top, dtype=dtype), "gemm2": W.moe_gemm2(top, dtype=dtype)}
+    out = {"experts": W.MOE_EXPERTS, "experts_per_token": W.MOE_TOPK, "dtype": dtype, "sweep": {}}
+    layer = {t: 0.0 for t in sweep}
+    for name, f in full.items():
+        gated = name == "gemm1"
+        NC = f.N // 2 if gated else f.N
+        plainL = B.Layout(W.grouped_gemm_specs(f)[1])
+        blkL = B.Layout(W.blocked_b_spec(f.K, f.N, G=f.G))
+        useL = B.Layout(W.gated_b_spec(f.K, f.N, f.G, True)) if gated else blkL
+        dB = dev(f.b_gnk.reshape(-1))
+        dBblk, dBuse = torch.empty_like(dB), None
+        B.axe_relayout(plainL, blkL, (f.G, f.K, f.N), dB, dBblk)
+        assert np.array_equal(dBblk[:f.N * f.K].cpu().numpy().view(np.uint16), W.pack_blocked(f.b_gnk[0]))
+        if gated:
+            dBuse = torch.empty_like(dB)
+            B.axe_relayout(plainL, useL, (f.G, f.K, f.N), dB, dBuse)
+            assert np.array_equal(dBuse[:f.N * f.K].cpu().numpy().view(np.uint16), W.pack_blocked(W.pack_gate_up(f.b_gnk[:1]))[0])
+        else:
+            dBuse = dBblk
+        for tokens in sweep:
+            rows = W.moe_group_rows(tokens, W.MOE_EXPERTS, W.MOE_TOPK, W.SEED_BASE + 11)
+            M = int(rows[-1])
+            dA = dev(f.a_mk[:M].reshape(-1))
+            dC = torch.zeros(M * NC, dtype=torch.int16, device="cuda")
+            dR = torch.from_numpy(rows).cuda()
+            desc = B.GroupedGemmDesc(M, f.N, f.K, f.G, B.Layout(W.row_major_spec(M, f.K)), useL, B.Layout(W.row_major_spec(M, NC)),
+                                     M * f.K, f.b_gnk.size, M * NC, in_dtype=dt, out_dtype=dt,
+                                     epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE)
+            wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dBuse, dC, dR), steps, warmup)
+            active = int((np.diff(rows) > 0).sum())
+            nbytes = 2.0 * (active * f.N * f.K + M * f.K + M * NC)
+            kernel = "streaming (split K)" if M <= 8 * f.G else "tiles of 128 x 256"
+            r = {"M": M, "active_experts": active, "kernel": kernel, "kernel_ms": devms, "algorithmic_bytes": nbytes,
+                 "GBps": nbytes / (devms * 1e-3) / 1e9, "tflops": 2.0 * M * f.N * f.K / (devms * 1e-3) / 1e12}
+            r["frac_of_hbm_peak"] = r["GBps"] / PEAK["hbm"]
+            out["sweep"].setdefault(str(tokens), {})[name] = r
+            layer[tokens] += devms
+            log(f"[bench] MoE {name}{' + gated activation' if gated else ''} {dtype}, {tokens} tokens (M={M}, {active} experts with rows, {kernel}): "
+                f"{devms*1e3:.1f} us, {r['GBps']:.0f} GB/s ({100*r['frac_of_hbm_peak']:.0f}% of HBM peak), {r['tflops']:.0f} TFLOP/s")
+            if tokens == top:                            # without the epilogue, plain against blocked weights
+                dCw = torch.zeros(M * f.N, dtype=torch.int16, device="cuda")
+                for label, lay, buf in (("plain", plainL, dB), ("blocked", blkL, dBblk)):
+                    d2 = B.GroupedGemmDesc(M, f.N, f.K, f.G, B.Layout(W.row_major_spec(M, f.K)), lay, B.Layout(W.row_major_spec(M, f.N)),
+                                           M * f.K, f.b_gnk.size, M * f.N, in_dtype=dt, out_dtype=dt)
+                    wall, d_ms = time_loop(lambda i: B.axe_gemm_grouped(d2, dA, buf, dCw, dR), steps, warmup)
+                    r[label + "_weights_no_epilogue_ms"] = d_ms
+                log(f"[bench]   {name} at {tokens} tokens without epilogue: plain weights {r['plain_weights_no_epilogue_ms']*1e3:.0f} us, "
+                    f"blocked weights {r['blocked_weights_no_epilogue_ms']*1e3:.0f} us")
+                del dCw
+            del dA, dC
+        del dB, dBblk, dBuse
+    for tokens in sweep:
+        out["sweep"][str(tokens)]["layer_kernel_ms"] = layer[tokens]
+    log("[bench] MoE layer expert compute (gemm1 + activation, gemm2), us by tokens: " +
+        ", ".join(f"{t}: {layer[t]*1e3:.0f}" for t in sweep))
     return out
 
 
