@@ -102,6 +102,7 @@ struct GemmArgs {
   const int32_t* group_rows;       // device, groups + 1 entries
   int32_t groups;
   int32_t tile_m;                  // rows of a tile of the grouped tile kernel: 128, 256, or 0 = chosen from M / groups
+  int32_t compact_groups;          // streaming kernel: blockIdx.y counts non-empty groups (set by its launcher when M < groups)
   int32_t gated;                   // 1: store silu(gate) * up (B's rows interleave gate and up in runs of 16), C is N / 2 wide
   int64_t ldg;
 };

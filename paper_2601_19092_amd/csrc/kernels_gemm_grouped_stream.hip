@@ -67,8 +67,36 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   __shared__ float partial[SPLITK ? 3 * 64 * 8 : 1];               // SPLITK: the sums of waves 1..3
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
-  const int e = blockIdx.y;                                        // group
   const int M = (int)g.M;
+  int e = blockIdx.y;                                              // group
+  if (g.compact_groups) {
+    // fewer rows than groups (the first tokens of a decode batch): at most M groups have rows, and the launch
+    // has one workgroup row per possible non-empty group instead of one per group -- an empty workgroup
+    // costs nothing but its dispatch, yet thousands of them cost microseconds.  blockIdx.y = a means the
+    // a-th non-empty group: the wave finds it by counting, 64 groups per step.
+    const int a = e;
+    int seen = 0;
+    e = -1;
+    for (int g0 = 0; g0 < g.groups && e < 0; g0 += 64) {
+      const int gi = g0 + lane;
+      bool has = false;
+      if (gi < g.groups) {
+        int x0 = g.group_rows[gi], x1 = g.group_rows[gi + 1];
+        x0 = x0 < 0 ? 0 : (x0 > M ? M : x0);
+        x1 = x1 < 0 ? 0 : (x1 > M ? M : x1);
+        has = x1 > x0;
+      }
+      uint64_t m = __ballot(has);
+      const int cnt = __popcll(m);
+      if (a < seen + cnt) {
+        for (int k = a - seen; k > 0; --k) m &= m - 1;             // drop the lower set bits
+        e = g0 + (int)__builtin_ctzll(m);
+      }
+      seen += cnt;
+    }
+    e = __builtin_amdgcn_readfirstlane(e);
+    if (e < 0) return;                                             // fewer non-empty groups than workgroup rows
+  }
   int r0 = g.group_rows[e], r1 = g.group_rows[e + 1];
   r0 = r0 < 0 ? 0 : (r0 > M ? M : r0);                             // whatever the offsets hold, no access leaves the buffers
   r1 = r1 < 0 ? 0 : (r1 > M ? M : r1);
@@ -200,10 +228,13 @@ void launch_stream(const GemmArgs& g, dim3 grid, hipStream_t s) {
 // average (an MoE layer of 128 experts, 8 per token, up to 128 tokens: at most 22 rows in any group in the
 // benchmark's routing) it takes the variant that splits K over the waves and handles 16 rows per pass
 // (measured crossover between 8 and 16; AXE_GROUPED_SPLITK_ROWS overrides it for experiments).
-hipError_t launch_gemm_grouped_stream(const GemmArgs& g, hipStream_t s) {
+hipError_t launch_gemm_grouped_stream(const GemmArgs& g0, hipStream_t s) {
+  GemmArgs g = g0;
+  g.compact_groups = g.M < g.groups;                               // at most M groups can have rows
+  const unsigned ny = (unsigned)(g.compact_groups ? g.M : g.groups);
   static const int avg = [] { const char* v = getenv("AXE_GROUPED_SPLITK_ROWS"); return v ? atoi(v) : 8; }();
-  if (g.M <= avg * (int64_t)g.groups) launch_stream<true>(g, dim3((unsigned)(g.N / 32), (unsigned)g.groups), s);
-  else launch_stream<false>(g, dim3((unsigned)(g.N / 128), (unsigned)g.groups), s);
+  if (g.M <= avg * (int64_t)g.groups) launch_stream<true>(g, dim3((unsigned)(g.N / 32), ny), s);
+  else launch_stream<false>(g, dim3((unsigned)(g.N / 128), ny), s);
   return hipGetLastError();
 }
 

@@ -1078,3 +1078,16 @@ def test_gemm_grouped_largest_group_count(kernel):
     assert np.isfinite(c).all() and R.rel_frobenius(c, ref) <= BF16_TOL
     for e in np.nonzero(sizes)[0]:
         assert R.rel_frobenius(c[off[e]:off[e + 1]], ref[off[e]:off[e + 1]]) <= BF16_TOL, e
+
+
+def test_gemm_grouped_fewer_rows_than_groups():
+    """Fewer rows than groups: the streaming kernel's launch has one workgroup row per possible non-empty group and
+    finds the group by counting; groups at both ends, in different 64-group blocks, and a run of empty ones."""
+    sizes = np.zeros(200, dtype=np.int64)
+    sizes[[0, 63, 64, 77, 199]] = [1, 2, 1, 3, 1]
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    g = W.gemm_grouped_bf16(off, 256, 192, 106)
+    assert g.M < g.G
+    for kernel in KERNELS:
+        c, raw = run_grouped(g, kernel=kernel)
+        check_grouped(g, c, raw, R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16))
