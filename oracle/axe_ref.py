@@ -273,7 +273,8 @@ def gemm_ref(a_bits: np.ndarray, b_bits: np.ndarray, dtype: int,
 
 
 def gemm_grouped_ref(a_bits: np.ndarray, b_bits: np.ndarray, group_rows: Sequence[int], dtype: int,
-                     rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None) -> np.ndarray:
+                     rows: Optional[np.ndarray] = None, cols: Optional[np.ndarray] = None,
+                     scale_a: Optional[np.ndarray] = None, scale_b: Optional[np.ndarray] = None, block: int = 128) -> np.ndarray:
     """Grouped GEMM, the building block of the fused MoE layer of Sec. 4.1 (its two "group GEMMs"):
     the rows of A are sorted by group (expert), group g owns rows group_rows[g] .. group_rows[g+1]-1
     and has its own right-hand side:  C[r, :] = A[r, :] @ B[g]  for r in that range.
@@ -281,7 +282,10 @@ def gemm_grouped_ref(a_bits: np.ndarray, b_bits: np.ndarray, group_rows: Sequenc
     a_bits logical (M, K); b_bits logical (G, K, N) (any strides); group_rows G+1 non-decreasing
     integers, 0 <= group_rows[0], group_rows[G] <= M.  fp64 result [len(rows), len(cols)]; a row that
     belongs to no group is NaN (the operation does not define, and must not write, it).
-    Each group is one call of the plain triple loop (gemm_ref): nothing is blocked or fused."""
+    Each group is one call of the plain triple loop (gemm_ref): nothing is blocked or fused.
+    Block-scaled form (both scale arrays or neither): scale_a fp32 (M, ceil(K/block)), one scale per row of A and
+    k block (activations); scale_b fp32 (G, ceil(N/block), ceil(K/block)), one per block x block tile of each B[g]:
+        C[r, j] = sum_kb scale_a[r, kb] * scale_b[g, j // block, kb] * sum_{k in block kb} A[r, k] B[g, k, j]."""
     M, K = a_bits.shape
     G, K2, N = b_bits.shape
     off = [int(x) for x in group_rows]
@@ -295,7 +299,10 @@ def gemm_grouped_ref(a_bits: np.ndarray, b_bits: np.ndarray, group_rows: Sequenc
     for g in range(G):
         sel = np.nonzero((rows >= off[g]) & (rows < off[g + 1]))[0]
         if sel.size:
-            out[sel, :] = gemm_ref(a_bits, b_bits[g], dtype, rows=rows[sel], cols=cols)
+            if scale_a is None and scale_b is None:
+                out[sel, :] = gemm_ref(a_bits, b_bits[g], dtype, rows=rows[sel], cols=cols)
+            else:
+                out[sel, :] = gemm_ref(a_bits, b_bits[g], dtype, scale_a, scale_b[g], block, rows=rows[sel], cols=cols, block_m_a=1)
     return out
 
 

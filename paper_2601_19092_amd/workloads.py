@@ -108,7 +108,10 @@ class GroupedGemmInputs:
     a_mk: np.ndarray
     b_gnk: np.ndarray
     group_rows: np.ndarray
-    dtype: str = "bf16"             # "bf16" | "f16" (inputs and output)
+    dtype: str = "bf16"             # "bf16" | "f16" (inputs and output) | "fp8" (e4m3 inputs, bf16 output)
+    scale_a: Optional[np.ndarray] = None   # fp8: (M, ceil(K/128)), one per row and k block; fp32 or uint8 E8M0 codes
+    scale_b: Optional[np.ndarray] = None   # fp8: (G, N/128, ceil(K/128)), one per 128 x 128 block of each group's matrix
+    scale_dtype: str = "f32"
 
 
 def moe_group_rows(tokens: int, experts: int, topk: int, seed: int, skew: float = 0.5) -> np.ndarray:
@@ -132,6 +135,25 @@ def gemm_grouped_bf16(group_rows, N: int, K: int, seed: int, M: Optional[int] = 
     cast = to_f16_bits if dtype == "f16" else to_bf16_bits
     return GroupedGemmInputs(M, N, K, G, cast(normal(seed, (M, K), std_a)), cast(normal(seed + 7919, (G, N, K), std_b)),
                              group_rows, dtype)
+
+
+def gemm_grouped_fp8(group_rows, N: int, K: int, seed: int, M: Optional[int] = None, scale_dtype: str = "f32") -> GroupedGemmInputs:
+    """e4m3 operands with the usual block scaling of an fp8 MoE layer: activations one scale per row and 128-wide
+    k block, weights one per 128 x 128 block; fp32 scales U[0.5, 2] or E8M0 codes 124..130."""
+    group_rows = np.ascontiguousarray(group_rows, dtype=np.int32)
+    G = group_rows.size - 1
+    M = int(group_rows[-1]) if M is None else M
+    nkb = (K + 127) // 128
+    a = to_e4m3_bits(normal(seed, (M, K)))
+    b = to_e4m3_bits(normal(seed + 7919, (G, N, K)))
+    rng = _rng(seed + 31)
+    if scale_dtype == "e8m0":
+        sa = rng.integers(124, 131, (M, nkb)).astype(np.uint8)
+        sb = rng.integers(124, 131, (G, N // 128, nkb)).astype(np.uint8)
+    else:
+        sa = rng.uniform(0.5, 2.0, (M, nkb)).astype(np.float32)
+        sb = rng.uniform(0.5, 2.0, (G, N // 128, nkb)).astype(np.float32)
+    return GroupedGemmInputs(M, N, K, G, a, b, group_rows, "fp8", sa, sb, scale_dtype)
 
 
 # the MoE layer of Qwen3-30B-A3B (the configuration the paper's fused-MoE figure is measured on):

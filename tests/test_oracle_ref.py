@@ -403,3 +403,30 @@ def test_swiglu_closed_forms_and_library_routine():
     np.testing.assert_allclose(R.swiglu_ref(p), want, rtol=1e-14, atol=1e-300)
     assert not np.allclose(R.swiglu_ref(p), R.swiglu_ref(np.concatenate([p[:, 5:], p[:, :5]], axis=1)))
     assert np.isnan(R.swiglu_ref(np.full((1, 4), np.nan))).all()
+
+
+def test_grouped_gemm_block_scaled_fp8():
+    """Row scales for A, 128 x 128 block scales per group for B: brute force from the definition; all scales one gives
+    the unscaled grouped GEMM."""
+    off = [0, 3, 3, 140, 150]
+    g = W.gemm_grouped_fp8(off, 256, 384, 15)
+    A, Bm = R.e4m3_to_f64(g.a_mk), R.e4m3_to_f64(g.b_gnk)                   # (M, K), (G, N, K)
+    want = np.full((g.M, g.N), np.nan)
+    for e in range(g.G):
+        for r in range(off[e], off[e + 1]):
+            acc = np.zeros(g.N)
+            for kb in range(3):
+                ks = slice(kb * 128, (kb + 1) * 128)
+                acc += float(g.scale_a[r, kb]) * (Bm[e][:, ks] @ A[r, ks]) * np.repeat(g.scale_b[e, :, kb].astype(np.float64), 128)
+            want[r] = acc
+    got = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_FP8_E4M3, scale_a=g.scale_a, scale_b=g.scale_b)
+    assert not np.isnan(got).any() and R.rel_frobenius(got, want) <= 1e-12
+    ones = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_FP8_E4M3,
+                              scale_a=np.ones_like(g.scale_a), scale_b=np.ones_like(g.scale_b))
+    np.testing.assert_allclose(ones, R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_FP8_E4M3), rtol=1e-13)
+    # a scale of group 2 does not touch group 0
+    bad = g.scale_b.copy()
+    bad[2, 1, 0] *= 2
+    other = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_FP8_E4M3, scale_a=g.scale_a, scale_b=bad)
+    assert np.array_equal(other[:3], got[:3]) and np.array_equal(other[3:140, :128], got[3:140, :128])
+    assert R.rel_frobenius(other[3:140, 128:], got[3:140, 128:]) > 1e-2
