@@ -187,7 +187,8 @@ int axe_gemm_tile(const axe_gemm_desc_t* g);
  *                    (a router writes them on the device): the kernel clamps each entry to [0, M], so
  *                    no access leaves the buffers whatever they hold; entries that decrease give
  *                    unspecified values in C.
- * Supported family (else AXE_EUNSUPPORTED): bf16 inputs and output, or fp16 inputs and output; A and C row-major, each B[e]
+ * Supported family (else AXE_EUNSUPPORTED): bf16 inputs and output, fp16 inputs and output, or fp8 inputs with bf16
+ * output (see the scale fields below); A and C row-major, each B[e]
  * column-major (unit stride along k) with one pitch for all e and a constant stride between groups
  * (the grouped form of B by (G, K, N) has one iter per block); leading dimensions, offsets and the group
  * stride multiples of 16 bytes; N a multiple of 256, K a multiple of 64.
@@ -196,13 +197,24 @@ int axe_gemm_tile(const axe_gemm_desc_t* g);
 typedef struct {
   int64_t      M, N, K;
   int32_t      G;
-  int32_t      in_dtype, out_dtype;      /* both AXE_BF16, or both AXE_F16 */
+  int32_t      in_dtype, out_dtype;      /* both AXE_BF16, both AXE_F16, or AXE_FP8_E4M3 with AXE_BF16 */
   axe_layout_t A, B, C;
   int32_t      mem_axis;
   int64_t      a_elems, b_elems, c_elems;
   int32_t      epilogue;                 /* AXE_EPI_NONE or AXE_EPI_SWIGLU */
   int32_t      kernel_hint;              /* AXE_GROUPED_AUTO, or one of the two kernels below */
+  const void*  d_scale_a;                /* fp8 only: both NULL, or DEVICE block scales (see below) */
+  const void*  d_scale_b;
+  int32_t      scale_dtype;              /* AXE_SCALE_F32 or AXE_SCALE_E8M0 */
 } axe_gemm_grouped_desc_t;
+
+/* fp8 (in_dtype AXE_FP8_E4M3, out_dtype AXE_BF16): the block-scaled grouped GEMM of an fp8 MoE layer,
+ *       C[r, j] = sum_kb sA[r][kb] * sB[e][j / 128][kb] * sum_{k in block kb} A[r, k] B[e, k, j],   blocks of 128 along k,
+ * d_scale_a row-major (M, ceil(K/128)): one scale per row of A and k block (activations), d_scale_b row-major
+ * (G, N/128, ceil(K/128)): one per 128 x 128 block of each B[e]; fp32, or E8M0 codes (one byte, 2^(code - 127)).
+ * Both NULL: unscaled.  K a multiple of 128; B[e] column-major (plain, or gate/up interleaved for the gated
+ * epilogue).  Served by the streaming kernel only: M <= 8 G, or kernel_hint AXE_GROUPED_STREAM (any M; groups of
+ * more than 64 rows then take several passes over their weights). */
 
 /* Two kernels serve the same family.  AXE_GROUPED_TILES: 256 x 256 tiles of the chained GEMM pipeline, for
  * groups of hundreds of rows (of 128 x 256 unless groups average more than 1536 rows: a K-step then takes half

@@ -59,7 +59,7 @@ class axe_gemm_grouped_desc_t(C.Structure):
                 ("A", axe_layout_t), ("B", axe_layout_t), ("C", axe_layout_t),
                 ("mem_axis", C.c_int32),
                 ("a_elems", C.c_int64), ("b_elems", C.c_int64), ("c_elems", C.c_int64), ("epilogue", C.c_int32),
-                ("kernel_hint", C.c_int32)]
+                ("kernel_hint", C.c_int32), ("d_scale_a", C.c_void_p), ("d_scale_b", C.c_void_p), ("scale_dtype", C.c_int32)]
 
 
 class AxeError(RuntimeError):
@@ -223,12 +223,14 @@ class GroupedGemmDesc:
 
     def __init__(self, M: int, N: int, K: int, G: int, A: Layout, B: Layout, Cl: Layout, a_elems: int, b_elems: int,
                  c_elems: int, in_dtype: int = AXE_BF16, out_dtype: int = AXE_BF16, mem_axis: str = "m",
-                 epilogue: int = 0, kernel_hint: int = 0):
+                 epilogue: int = 0, kernel_hint: int = 0, scale_a=None, scale_b=None, scale_dtype: int = AXE_SCALE_F32):
         ma = A.axis(mem_axis)
         assert B.axis(mem_axis) == ma and Cl.axis(mem_axis) == ma, "memory axis must have the same index in A, B, C"
         self.layouts = (A, B, Cl)
         self.c = axe_gemm_grouped_desc_t(M, N, K, G, in_dtype, out_dtype, A.c, B.c, Cl.c, ma, a_elems, b_elems, c_elems, epilogue,
-                                         kernel_hint)
+                                         kernel_hint, scale_a.data_ptr() if scale_a is not None else None,
+                                         scale_b.data_ptr() if scale_b is not None else None, scale_dtype)
+        self.scales = (scale_a, scale_b)
 
 
 def axe_gemm_grouped(desc: GroupedGemmDesc, A_buf, B_buf, C_buf, group_rows, stream=None):

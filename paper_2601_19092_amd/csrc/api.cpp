@@ -720,8 +720,9 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     set_error("%s: M, N, K, G must be positive", fn);
     return AXE_EINVAL;
   }
-  if (!((g->in_dtype == AXE_BF16 && g->out_dtype == AXE_BF16) || (g->in_dtype == AXE_F16 && g->out_dtype == AXE_F16))) {
-    set_error("%s: bf16 inputs with bf16 output, or fp16 inputs with fp16 output", fn);
+  const bool fp8 = g->in_dtype == AXE_FP8_E4M3 && g->out_dtype == AXE_BF16;
+  if (!((g->in_dtype == AXE_BF16 && g->out_dtype == AXE_BF16) || (g->in_dtype == AXE_F16 && g->out_dtype == AXE_F16) || fp8)) {
+    set_error("%s: bf16 inputs with bf16 output, fp16 inputs with fp16 output, or fp8 inputs with bf16 output", fn);
     const bool known = (g->in_dtype >= AXE_BF16 && g->in_dtype <= AXE_F16 && g->in_dtype != AXE_F32) &&
                        (g->out_dtype == AXE_BF16 || g->out_dtype == AXE_F32 || g->out_dtype == AXE_F16);
     return known ? AXE_EUNSUPPORTED : AXE_EINVAL;
@@ -747,12 +748,25 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     return AXE_EUNSUPPORTED;
   }
   if (int rc = strided_2d(&g->C, g->mem_axis, g->M, NC, true, g->c_elems, "axe_gemm_grouped(C)", &ldc, &oc)) return rc;
-  if ((g->K % 8) || (lda % 8) || (ldb % 8) || (ldg % 8) || (oa % 8) || (ob % 8) || (oc % 8) || (ldc % 8)) {
-    set_error("%s: K, leading dimensions, the group stride and offsets must be multiples of 8 elements (16 bytes)", fn);
+  const int eb = fp8 ? 1 : 2;
+  const int64_t vec = 16 / eb;
+  if ((g->K % vec) || (lda % vec) || (ldb % vec) || (ldg % vec) || (oa % vec) || (ob % vec) || (oc % 8) || (ldc % 8)) {
+    set_error("%s: K, leading dimensions, the group stride and offsets must be multiples of 16 bytes", fn);
+    return AXE_EUNSUPPORTED;
+  }
+  if ((g->d_scale_a == nullptr) != (g->d_scale_b == nullptr) || (g->d_scale_a && !fp8) ||
+      (g->scale_dtype != AXE_SCALE_F32 && g->scale_dtype != AXE_SCALE_E8M0)) {
+    set_error("%s: block scales come in pairs, with fp8 inputs only, as fp32 or E8M0", fn);
+    return AXE_EINVAL;
+  }
+  const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G);
+  if (fp8 && (!stream_kernel || g->K % 128 || opb.kt_stride || opb.rb)) {
+    set_error("%s: fp8 inputs are served by the streaming kernel only (M <= 8 G or kernel_hint AXE_GROUPED_STREAM), with K a "
+              "multiple of 128 and each B[e] column-major", fn);
     return AXE_EUNSUPPORTED;
   }
   if (g->G > 4096 || g->N % 256 || g->N / 256 > 2048 || g->K % 64 || g->M >= (int64_t(1) << 31) ||
-      256 * lda * 2 >= (int64_t(1) << 31) || 256 * ldb * 2 >= (int64_t(1) << 31) || 128 * ldc * 2 >= (int64_t(1) << 31)) {
+      256 * lda * eb >= (int64_t(1) << 31) || 256 * ldb * eb >= (int64_t(1) << 31) || 128 * ldc * 2 >= (int64_t(1) << 31)) {
     set_error("%s: needs G <= 4096, N a multiple of 256 (at most 2048 tile columns), K a multiple of 64, M < 2^31 and "
               "row pitches below 2^31 / 256 bytes", fn);
     return AXE_EUNSUPPORTED;
@@ -775,20 +789,25 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     const char* a0 = (const char*)dA;
     const char* b0 = (const char*)dB;
     const char* r0 = (const char*)rows;
-    if ((a0 < c1 && c0 < a0 + g->a_elems * 2) || (b0 < c1 && c0 < b0 + g->b_elems * 2) ||
+    if ((a0 < c1 && c0 < a0 + g->a_elems * eb) || (b0 < c1 && c0 < b0 + g->b_elems * eb) ||
         (r0 < c1 && c0 < r0 + (g->G + 1) * 4)) {
       set_error("%s: C overlaps an input buffer", fn);
       return AXE_EINVAL;
     }
   }
   memset(&a, 0, sizeof a);
-  a.A = (const char*)dA + oa * 2;
-  a.B = (const char*)dB + ob * 2;
+  a.A = (const char*)dA + oa * eb;
+  a.B = (const char*)dB + ob * eb;
   a.C = (char*)dC + oc * 2;
   a.M = g->M, a.N = g->N, a.K = g->K;
   a.lda = lda, a.ldb = ldb, a.ldc = ldc, a.ldg = ldg;
   a.out_bf16 = 1;
   a.f16 = g->in_dtype == AXE_F16;
+  a.fp8 = fp8;
+  a.scale_a = (const float*)g->d_scale_a;
+  a.scale_b = (const float*)g->d_scale_b;
+  a.scale_e8m0 = g->d_scale_a && g->scale_dtype == AXE_SCALE_E8M0;
+  a.nkb = (int32_t)((g->K + 127) / 128);
   a.grid_m = 0;
   a.grid_n = (int32_t)(g->N / 256);
   a.tile_n = 256;

@@ -91,6 +91,7 @@ struct GemmArgs {
   int32_t nkb;
   int32_t out_bf16;                // 0: fp32 output, 1: 16-bit output (bf16, or binary16 when f16 is set)
   int32_t f16;                     // 1: 16-bit inputs (and a 16-bit output) are IEEE binary16 instead of bf16
+  int32_t fp8;                     // grouped streaming kernel: 1 = e4m3 inputs (K-tiles of 128 elements), bf16 output
   int32_t grid_m, grid_n;          // workgroup tiles along M and N
   int32_t tile_n;                  // columns of C per workgroup tile (64, 224 or 256)
   // 256-tile bf16 kernel: operands pre-tiled along K / blocked along rows (plain matrix: kstep 128, shift 0,

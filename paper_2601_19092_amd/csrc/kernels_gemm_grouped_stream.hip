@@ -61,8 +61,16 @@ __device__ __forceinline__ uint32_t pack16s(float lo, float hi) {
 // only 32 rows of B, its four waves take a quarter of K each (4 x as many waves and loads in flight for
 // the same weights), passes of 16 rows; the four partial sums meet in LDS and wave 0 adds them in a
 // fixed order and stores.
-template <bool F16, bool GATED, bool SPLITK>
+//
+// DT = 0 bf16, 1 fp16 (a K-tile is 64 elements, two MFMA 16x16x32 per fragment pair), 2 fp8 e4m3 (a K-tile is 128
+// elements = one 128-deep scale block and one MFMA 16x16x128; output bf16).  fp8 with scales: one per row of A
+// and K-tile (activations), one per 128 x 128 block of each group's B; a K-tile's product is formed alone and
+// folded into the sum with the lane's row scale times the fragment's block scale (fp32, or E8M0 codes decoded
+// as 2^(code - 127)).  Here the fold costs nothing: the kernel waits for HBM.
+template <int DT, bool GATED, bool SPLITK>
 __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
+  constexpr bool F16 = DT == 1, FP8 = DT == 2;
+  constexpr int EB = FP8 ? 1 : 2;                                  // bytes per element
   constexpr int MI = SPLITK ? 1 : 4;                               // row fragments per pass
   __shared__ float partial[SPLITK ? 3 * 64 * 8 : 1];               // SPLITK: the sums of waves 1..3
   const int lane = threadIdx.x & 63;
@@ -101,7 +109,7 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   r0 = r0 < 0 ? 0 : (r0 > M ? M : r0);                             // whatever the offsets hold, no access leaves the buffers
   r1 = r1 < 0 ? 0 : (r1 > M ? M : r1);
   if (r1 <= r0) return;                                            // (the whole workgroup: no barrier is left waiting)
-  const int nk = (int)(g.K / 64);
+  const int nk = (int)(g.K * EB / 128);                            // K-tiles of 128 bytes per row
   const int k_lo = SPLITK ? (nk * w) >> 2 : 0, k_hi = SPLITK ? (nk * (w + 1)) >> 2 : nk;   // this wave's K-tiles
   const int fr = lane & 15, fq = lane >> 4;
 
@@ -110,18 +118,34 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   const int tn = brow >> 8;                                        // 256-row block of the image
   const int64_t b_off = (int64_t)e * g.ldg + (int64_t)(tn >> g.b_tpb_shift) * g.b_blk_stride +
                         ((int64_t)(tn & ((1 << g.b_tpb_shift) - 1)) * 256 + (brow & 255)) * g.ldb;
-  const int b_pitch = (int)(g.ldb * 2), b_kstep = g.b_kstep;
+  const int b_pitch = (int)(g.ldb * EB), b_kstep = g.b_kstep;
   const __amdgpu_buffer_rsrc_t rb =
-      __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + b_off * 2), 0, 31 * b_pitch + (nk - 1) * b_kstep + 128, 0x00020000);
+      __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + b_off * EB), 0, 31 * b_pitch + (nk - 1) * b_kstep + 128, 0x00020000);
   const int b_voff = fr * b_pitch + fq * 16;
-  const int a_pitch = (int)(g.lda * 2);
+  const int a_pitch = (int)(g.lda * EB);
+  // fp8 block scales: this wave's two fragments lie in one 128-column block of the logical B each (with the gated
+  // epilogue fragment 0 is a run of gate columns, fragment 1 the same run of up columns, N / 2 further on)
+  const bool scaled = FP8 && g.scale_a != nullptr;
+  int sb_idx[2] = {0, 0};
+  if (scaled) {
+    const int nbn = (int)(g.N / 128);
+#pragma unroll
+    for (int f = 0; f < 2; ++f) {
+      const int col = GATED ? f * (int)(g.N / 2) + (brow >> 1) : brow + 16 * f;
+      sb_idx[f] = (e * nbn + col / 128) * g.nkb;
+    }
+  }
+  auto scale_at = [&](const float* base, int64_t i) -> float {
+    if (g.scale_e8m0) return __builtin_bit_cast(float, (uint32_t)((const uint8_t*)base)[i] << 23);
+    return base[i];
+  };
   const int a_voff = fr * a_pitch + fq * 16;
 
   for (int p0 = r0; p0 < r1; p0 += 16 * MI) {                      // passes over the rows of the group
     const int rows = r1 - p0 < 16 * MI ? r1 - p0 : 16 * MI;
     const int nfrag = (rows + 15) >> 4;                            // row fragments that hold any row (wave-uniform)
-    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)p0 * g.lda * 2), 0,
-                                                                        (rows - 1) * a_pitch + (int)g.K * 2, 0x00020000);
+    const __amdgpu_buffer_rsrc_t ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)p0 * g.lda * EB), 0,
+                                                                        (rows - 1) * a_pitch + (int)g.K * EB, 0x00020000);
     f32x4 acc[2][MI];
 #pragma unroll
     for (int f = 0; f < 2; ++f)
@@ -130,7 +154,18 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
 
     // one K-tile (64 elements) of a fragment is two 16-byte chunks per lane: q (k = 8 q ..) and q + 4 (k = 32 + 8 q ..)
     u32x4 b[2][2][2], a[2][MI][2];                                 // [buffer][fragment][chunk]
+    float sa_v[2][MI], sb_v[2][2];                                 // fp8: the K-tile's scales, fetched with its data
     auto load = [&](int buf, int kt) __attribute__((always_inline)) {
+      if (scaled) {
+#pragma unroll
+        for (int f = 0; f < 2; ++f) sb_v[buf][f] = scale_at(g.scale_b, sb_idx[f] + kt);
+#pragma unroll
+        for (int mi = 0; mi < MI; ++mi)
+          if (mi < nfrag) {
+            const int row = mi * 16 + fr < rows ? mi * 16 + fr : rows - 1;      // rows past the end are never stored
+            sa_v[buf][mi] = scale_at(g.scale_a, (int64_t)(p0 + row) * g.nkb + kt);
+          }
+      }
 #pragma unroll
       for (int f = 0; f < 2; ++f)
 #pragma unroll
@@ -148,10 +183,28 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
 #pragma unroll
       for (int mi = 0; mi < MI; ++mi)
         if (mi < nfrag) {
+          if constexpr (FP8) {
+            const i32x8 av = {(int)a[buf][mi][0][0], (int)a[buf][mi][0][1], (int)a[buf][mi][0][2], (int)a[buf][mi][0][3],
+                              (int)a[buf][mi][1][0], (int)a[buf][mi][1][1], (int)a[buf][mi][1][2], (int)a[buf][mi][1][3]};
 #pragma unroll
-          for (int h = 0; h < 2; ++h)
+            for (int f = 0; f < 2; ++f) {
+              const i32x8 bv = {(int)b[buf][f][0][0], (int)b[buf][f][0][1], (int)b[buf][f][0][2], (int)b[buf][f][0][3],
+                                (int)b[buf][f][1][0], (int)b[buf][f][1][1], (int)b[buf][f][1][2], (int)b[buf][f][1][3]};
+              if (scaled) {
+                const f32x4 part = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bv, av, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
+                const float sc = sa_v[buf][mi] * sb_v[buf][f];
 #pragma unroll
-            for (int f = 0; f < 2; ++f) acc[f][mi] = mfma16<F16>(b[buf][f][h], a[buf][mi][h], acc[f][mi]);
+                for (int x = 0; x < 4; ++x) acc[f][mi][x] = __builtin_fmaf(sc, part[x], acc[f][mi][x]);
+              } else {
+                acc[f][mi] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bv, av, acc[f][mi], 0, 0, 0, 0, 0, 0);
+              }
+            }
+          } else {
+#pragma unroll
+            for (int h = 0; h < 2; ++h)
+#pragma unroll
+              for (int f = 0; f < 2; ++f) acc[f][mi] = mfma16<F16>(b[buf][f][h], a[buf][mi][h], acc[f][mi]);
+          }
         }
     };
     int kt = k_lo;
@@ -213,14 +266,15 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
 namespace {
 template <bool SPLITK>
 void launch_stream(const GemmArgs& g, dim3 grid, hipStream_t s) {
-  if (g.f16 && g.gated)
-    hipLaunchKernelGGL((gemm_grouped_stream_kernel<true, true, SPLITK>), grid, dim3(256), 0, s, g);
-  else if (g.f16)
-    hipLaunchKernelGGL((gemm_grouped_stream_kernel<true, false, SPLITK>), grid, dim3(256), 0, s, g);
-  else if (g.gated)
-    hipLaunchKernelGGL((gemm_grouped_stream_kernel<false, true, SPLITK>), grid, dim3(256), 0, s, g);
-  else
-    hipLaunchKernelGGL((gemm_grouped_stream_kernel<false, false, SPLITK>), grid, dim3(256), 0, s, g);
+  const dim3 block(256);
+  switch ((g.fp8 ? 4 : (g.f16 ? 2 : 0)) + (g.gated ? 1 : 0)) {
+    case 0: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, false, SPLITK>), grid, block, 0, s, g); break;
+    case 1: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, true, SPLITK>), grid, block, 0, s, g); break;
+    case 2: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, false, SPLITK>), grid, block, 0, s, g); break;
+    case 3: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, true, SPLITK>), grid, block, 0, s, g); break;
+    case 4: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, false, SPLITK>), grid, block, 0, s, g); break;
+    default: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, true, SPLITK>), grid, block, 0, s, g); break;
+  }
 }
 }  // namespace
 

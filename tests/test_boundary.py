@@ -250,6 +250,31 @@ def test_grouped_gemm_gated_epilogue_needs_interleaved_gate_and_up():
     assert chk(desc(W.gated_b_spec(K, N, G), Cn=N, epi=B.AXE_EPI_NONE)) == B.AXE_EUNSUPPORTED
 
 
+def test_grouped_gemm_fp8_goes_to_the_streaming_kernel_only():
+    class Fake:
+        def data_ptr(self):
+            return 4096
+    chk = lambda d: B.lib().axe_gemm_grouped_check(C.byref(d.c))
+    def desc(M=100, N=512, K=256, G=64, hint=B.AXE_GROUPED_AUTO, scales=True, out=B.AXE_BF16, Bs=None, sd=B.AXE_SCALE_F32):
+        Bs = Bs or W.spec([(G, N * K, "m"), (K, 1, "m"), (N, K, "m")])
+        return B.GroupedGemmDesc(M, N, K, G, B.Layout(W.row_major_spec(M, K)), B.Layout(Bs), B.Layout(W.row_major_spec(M, N)),
+                                 M * K, G * N * K, M * N, in_dtype=B.AXE_FP8_E4M3, out_dtype=out, kernel_hint=hint,
+                                 scale_a=Fake() if scales else None, scale_b=Fake() if scales else None, scale_dtype=sd)
+    assert chk(desc()) == B.AXE_OK and chk(desc(scales=False)) == B.AXE_OK and chk(desc(sd=B.AXE_SCALE_E8M0)) == B.AXE_OK
+    assert chk(desc(M=4000)) == B.AXE_EUNSUPPORTED                                        # large groups: the tile kernel has no fp8 variant
+    assert chk(desc(M=4000, hint=B.AXE_GROUPED_STREAM)) == B.AXE_OK                       # ... unless the caller insists on streaming
+    assert chk(desc(hint=B.AXE_GROUPED_TILES)) == B.AXE_EUNSUPPORTED
+    assert chk(desc(K=192, Bs=W.spec([(64, 512 * 192, "m"), (192, 1, "m"), (512, 192, "m")]))) == B.AXE_EUNSUPPORTED   # K no multiple of 128
+    assert chk(desc(out=B.AXE_F16)) == B.AXE_EUNSUPPORTED
+    assert chk(desc(sd=5)) == B.AXE_EINVAL
+    d = desc()
+    d.c.d_scale_b = None
+    assert chk(d) == B.AXE_EINVAL                                                          # scales come in pairs
+    bf = B.GroupedGemmDesc(100, 512, 256, 64, B.Layout(W.row_major_spec(100, 256)), B.Layout(W.spec([(64, 512 * 256, "m"), (256, 1, "m"), (512, 256, "m")])),
+                           B.Layout(W.row_major_spec(100, 512)), 100 * 256, 64 * 512 * 256, 100 * 512, scale_a=Fake(), scale_b=Fake())
+    assert chk(bf) == B.AXE_EINVAL                                                         # scales with bf16 inputs
+
+
 def test_python_binding_raises_axe_error():
     with pytest.raises(B.AxeError) as e:
         B._check(B.AXE_EALIAS)

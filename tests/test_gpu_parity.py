@@ -1091,3 +1091,50 @@ def test_gemm_grouped_fewer_rows_than_groups():
     for kernel in KERNELS:
         c, raw = run_grouped(g, kernel=kernel)
         check_grouped(g, c, raw, R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16))
+
+
+# ----------------------------------------------------------------------------- fp8 grouped GEMM (decode sizes)
+@pytest.mark.parametrize("scale_dtype", ["f32", "e8m0", None])
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("sizes,hint", [([1, 0, 3, 16, 2, 0, 7, 1] * 4, B.AXE_GROUPED_AUTO),           # M <= 8 G: the split-K variant
+                                        ([70, 0, 33, 64, 17], B.AXE_GROUPED_STREAM)])                    # passes of 64 rows
+def test_gemm_grouped_fp8_block_scaled(sizes, hint, gated, scale_dtype):
+    """e4m3 operands, one scale per row of A and k block, one per 128 x 128 block of each group's B (fp32 or E8M0), or none;
+    plain and gated epilogue; both variants of the streaming kernel."""
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    N, K = 512, 384
+    g = W.gemm_grouped_fp8(off, N, K, 107, M=int(off[-1]) + 1, scale_dtype=scale_dtype or "f32")
+    if scale_dtype is None:
+        sa_o = sb_o = None
+    elif scale_dtype == "e8m0":
+        sa_o, sb_o = R.e8m0_decode(g.scale_a).astype(np.float32), R.e8m0_decode(g.scale_b).astype(np.float32)
+    else:
+        sa_o, sb_o = g.scale_a, g.scale_b
+    ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_FP8_E4M3, scale_a=sa_o, scale_b=sb_o)
+    if gated:
+        ref = R.swiglu_ref(ref)
+    img = W.pack_gate_up(g.b_gnk) if gated else g.b_gnk
+    Bs = W.gated_b_spec(K, N, g.G) if gated else W.spec([(g.G, N * K, "m"), (K, 1, "m"), (N, K, "m")])
+    NC = N // 2 if gated else N
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
+    dC = torch.full((g.M * NC,), SENTINEL, dtype=torch.int16, device="cuda")
+    dR = torch.from_numpy(g.group_rows).cuda()
+    sa = torch.from_numpy(g.scale_a).cuda() if scale_dtype else None
+    sb = torch.from_numpy(g.scale_b).cuda() if scale_dtype else None
+    desc = B.GroupedGemmDesc(g.M, N, K, g.G, B.Layout(W.row_major_spec(g.M, K)), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, NC)),
+                             g.a_mk.size, img.size, g.M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
+                             epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=hint, scale_a=sa, scale_b=sb,
+                             scale_dtype=B.AXE_SCALE_E8M0 if scale_dtype == "e8m0" else B.AXE_SCALE_F32)
+    B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+    torch.cuda.synchronize()
+    raw = dC.cpu().numpy().view(np.uint16).reshape(g.M, NC)
+    owned = ~np.isnan(ref[:, 0])
+    assert (raw[~owned] == SENTINEL).all()
+    c = R.bf16_to_f64(raw)
+    assert np.isfinite(c[owned]).all()
+    assert R.rel_frobenius(c[owned], ref[owned]) <= FP8_TOL
+    for e in range(g.G):
+        if sizes[e]:
+            for j in range(0, NC, 64):
+                blk = (slice(off[e], off[e + 1]), slice(j, j + 64))
+                assert R.rel_frobenius(c[blk], ref[blk]) <= FP8_TOL, (e, j)
