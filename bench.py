@@ -234,6 +234,52 @@ def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
     return out
 
 
+def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64)):
+    """The same layer with e4m3 weights and activations at decode sizes: E8M0 block scales (one per row and 128-wide k block
+    for the activations, one per 128 x 128 block for the weights), bf16 output; gemm1 with the gated activation.  The
+    weights are half the bytes of the fp16 layer; bound: HBM."""
+    import torch
+    from paper_2601_19092_amd import binding as B
+    from paper_2601_19092_amd import workloads as W
+    top = max(sweep)
+    out = {"dtype": "fp8 e4m3, E8M0 scales", "sweep": {}}
+    layer = {t: 0.0 for t in sweep}
+    rows_top = W.moe_group_rows(top, W.MOE_EXPERTS, W.MOE_TOPK, W.SEED_BASE + 11)
+    for name, N, K in (("gemm1", 2 * W.MOE_INTER, W.MOE_HIDDEN), ("gemm2", W.MOE_HIDDEN, W.MOE_INTER)):
+        gated = name == "gemm1"
+        NC = N // 2 if gated else N
+        f = W.gemm_grouped_fp8(rows_top, N, K, W.SEED_BASE + 21 + gated, scale_dtype="e8m0")
+        img = W.pack_gate_up(f.b_gnk) if gated else f.b_gnk
+        useL = B.Layout(W.gated_b_spec(K, N, f.G) if gated else W.grouped_gemm_specs(f)[1])
+        dB = dev(img.reshape(-1))
+        sb = torch.from_numpy(f.scale_b).cuda()
+        for tokens in sweep:
+            rows = W.moe_group_rows(tokens, W.MOE_EXPERTS, W.MOE_TOPK, W.SEED_BASE + 11)
+            M = int(rows[-1])
+            dA, sa = dev(f.a_mk[:M].reshape(-1)), torch.from_numpy(f.scale_a[:M]).cuda()
+            dC = torch.zeros(M * NC, dtype=torch.int16, device="cuda")
+            dR = torch.from_numpy(rows).cuda()
+            desc = B.GroupedGemmDesc(M, N, K, f.G, B.Layout(W.row_major_spec(M, K)), useL, B.Layout(W.row_major_spec(M, NC)),
+                                     M * K, img.size, M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
+                                     epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, scale_a=sa, scale_b=sb,
+                                     scale_dtype=B.AXE_SCALE_E8M0)
+            wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dB, dC, dR), steps, warmup)
+            active = int((np.diff(rows) > 0).sum())
+            nbytes = active * N * K + M * K + 2.0 * M * NC
+            r = {"M": M, "active_experts": active, "kernel_ms": devms, "algorithmic_bytes": nbytes, "GBps": nbytes / (devms * 1e-3) / 1e9}
+            r["frac_of_hbm_peak"] = r["GBps"] / PEAK["hbm"]
+            out["sweep"].setdefault(str(tokens), {})[name] = r
+            layer[tokens] += devms
+            log(f"[bench] MoE {name}{' + gated activation' if gated else ''} fp8, {tokens} tokens (M={M}, {active} experts with rows, streaming): "
+                f"{devms*1e3:.1f} us, {r['GBps']:.0f} GB/s ({100*r['frac_of_hbm_peak']:.0f}% of HBM peak)")
+            del dA, dC
+        del dB
+    for tokens in sweep:
+        out["sweep"][str(tokens)]["layer_kernel_ms"] = layer[tokens]
+    log("[bench] MoE layer expert compute in fp8, us by tokens: " + ", ".join(f"{t}: {layer[t]*1e3:.0f}" for t in sweep))
+    return out
+
+
 def bench_eval(steps, warmup):
     import torch
     from paper_2601_19092_amd import binding as B
@@ -343,6 +389,7 @@ def main():
             W.gemm_fp8(8192, 8192, 8192, W.SEED_BASE + 5, scaled="e8m0"), max(10, args.steps // 2), args.warmup)
     if want("grouped"):
         comp["moe_grouped_gemm"] = bench_grouped(max(10, args.steps // 3), args.warmup)
+        comp["moe_grouped_gemm_fp8"] = bench_grouped_fp8(max(10, args.steps // 3), args.warmup)
     if want("small"):
         comp["gemm_cfg1_256"], _ = bench_gemm("bf16 GEMM 256^3, fp32 out, 64x64x32 tiles", W.config1(),
                                               max(200, args.steps), max(200, args.warmup), n_sets=1)
