@@ -211,7 +211,8 @@ typedef struct {
 /* fp8 (in_dtype AXE_FP8_E4M3, out_dtype AXE_BF16): the block-scaled grouped GEMM of an fp8 MoE layer,
  *       C[r, j] = sum_kb sA[r][kb] * sB[e][j / 128][kb] * sum_{k in block kb} A[r, k] B[e, k, j],   blocks of 128 along k,
  * d_scale_a row-major (M, ceil(K/128)): one scale per row of A and k block (activations), d_scale_b row-major
- * (G, N/128, ceil(K/128)): one per 128 x 128 block of each B[e]; fp32, or E8M0 codes (one byte, 2^(code - 127)).
+ * (G, N/128, ceil(K/128)): one per 128 x 128 block of each B[e]; fp32, or E8M0 codes (one byte, 2^(code - 127);
+ * such arrays are read in aligned 4-byte words: 4-byte aligned, allocation padded to a multiple of 4 bytes).
  * Both NULL: unscaled.  K a multiple of 128; B[e] column-major (plain, or gate/up interleaved for the gated
  * epilogue).  Served by the streaming kernel only: M <= 8 G, or kernel_hint AXE_GROUPED_STREAM (any M; groups of
  * more than 64 rows then take several passes over their weights). */

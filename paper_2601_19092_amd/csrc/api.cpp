@@ -759,6 +759,10 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     set_error("%s: block scales come in pairs, with fp8 inputs only, as fp32 or E8M0", fn);
     return AXE_EINVAL;
   }
+  if (g->d_scale_a && g->scale_dtype == AXE_SCALE_E8M0 && (((uintptr_t)g->d_scale_a | (uintptr_t)g->d_scale_b) & 3)) {
+    set_error("%s: E8M0 scale arrays must be 4-byte aligned", fn);
+    return AXE_EINVAL;
+  }
   const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G);
   if (fp8 && (!stream_kernel || g->K % 128 || opb.kt_stride || opb.rb)) {
     set_error("%s: fp8 inputs are served by the streaming kernel only (M <= 8 G or kernel_hint AXE_GROUPED_STREAM), with K a "

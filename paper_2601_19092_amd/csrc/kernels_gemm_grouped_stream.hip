@@ -67,12 +67,17 @@ __device__ __forceinline__ uint32_t pack16s(float lo, float hi) {
 // and K-tile (activations), one per 128 x 128 block of each group's B; a K-tile's product is formed alone and
 // folded into the sum with the lane's row scale times the fragment's block scale (fp32, or E8M0 codes decoded
 // as 2^(code - 127)).  Here the fold costs nothing: the kernel waits for HBM.
-template <int DT, bool GATED, bool SPLITK>
+// KS = the number of waves that share one set of 32 B rows and split K among them: 0 = SPLITK off (every wave its
+// own rows, all of K), 4 (16-bit inputs) or 2 (fp8, whose K-tiles are twice as deep: with 4 a wave's share of K
+// would be too few K-tiles for its pipeline); a workgroup then owns 4 / KS sets of 32 rows.
+template <int DT, bool GATED, int KS>
 __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
+  constexpr bool SPLITK = KS != 0;
+  constexpr int KW = SPLITK ? KS : 1, SETS = SPLITK ? 4 / KS : 4;   // waves per row set, row sets per workgroup
   constexpr bool F16 = DT == 1, FP8 = DT == 2;
   constexpr int EB = FP8 ? 1 : 2;                                  // bytes per element
   constexpr int MI = SPLITK ? 1 : 4;                               // row fragments per pass
-  __shared__ float partial[SPLITK ? 3 * 64 * 8 : 1];               // SPLITK: the sums of waves 1..3
+  __shared__ float partial[SPLITK ? (4 - SETS) * 64 * 8 : 1];      // SPLITK: the sums of the waves that do not store
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int M = (int)g.M;
@@ -110,11 +115,12 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   r1 = r1 < 0 ? 0 : (r1 > M ? M : r1);
   if (r1 <= r0) return;                                            // (the whole workgroup: no barrier is left waiting)
   const int nk = (int)(g.K * EB / 128);                            // K-tiles of 128 bytes per row
-  const int k_lo = SPLITK ? (nk * w) >> 2 : 0, k_hi = SPLITK ? (nk * (w + 1)) >> 2 : nk;   // this wave's K-tiles
+  const int kpart = SPLITK ? w % KW : 0, wset = SPLITK ? w / KW : w;
+  const int k_lo = (nk * kpart) / KW, k_hi = (nk * (kpart + 1)) / KW;   // this wave's K-tiles
   const int fr = lane & 15, fq = lane >> 4;
 
   // this wave's 32 rows of the group's B image: rows brow .. brow + 31 (two fragments)
-  const int brow = SPLITK ? (int)blockIdx.x * 32 : (int)blockIdx.x * 128 + w * 32;
+  const int brow = (int)blockIdx.x * (32 * SETS) + wset * 32;
   const int tn = brow >> 8;                                        // 256-row block of the image
   const int64_t b_off = (int64_t)e * g.ldg + (int64_t)(tn >> g.b_tpb_shift) * g.b_blk_stride +
                         ((int64_t)(tn & ((1 << g.b_tpb_shift) - 1)) * 256 + (brow & 255)) * g.ldb;
@@ -135,9 +141,15 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
       sb_idx[f] = (e * nbn + col / 128) * g.nkb;
     }
   }
-  auto scale_at = [&](const float* base, int64_t i) -> float {
-    if (g.scale_e8m0) return __builtin_bit_cast(float, (uint32_t)((const uint8_t*)base)[i] << 23);
-    return base[i];
+  // A scale is fetched with its K-tile and decoded only when the K-tile is multiplied: touching the loaded
+  // word right away would make the wave wait for it -- and for every load issued before it, the next K-tile's
+  // data included (measured: 92 instead of 69 us on the layer's first GEMM at 64 tokens).  E8M0 codes come as the
+  // aligned 4-byte word that holds them (the host requires such arrays 4-byte aligned and padded to whole words).
+  auto scale_word = [&](const float* base, int64_t i) -> uint32_t {
+    return g.scale_e8m0 ? ((const uint32_t*)base)[i >> 2] : ((const uint32_t*)base)[i];
+  };
+  auto scale_value = [&](uint32_t word, int64_t i) -> float {
+    return __builtin_bit_cast(float, g.scale_e8m0 ? ((word >> (8 * (int)(i & 3))) & 0xffu) << 23 : word);
   };
   const int a_voff = fr * a_pitch + fq * 16;
 
@@ -154,17 +166,20 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
 
     // one K-tile (64 elements) of a fragment is two 16-byte chunks per lane: q (k = 8 q ..) and q + 4 (k = 32 + 8 q ..)
     u32x4 b[2][2][2], a[2][MI][2];                                 // [buffer][fragment][chunk]
-    float sa_v[2][MI], sb_v[2][2];                                 // fp8: the K-tile's scales, fetched with its data
+    uint32_t sa_w[2][MI], sb_w[2][2];                              // fp8: the K-tile's scales as loaded, fetched with its data
+    int kt_of[2] = {0, 0};
+    auto sa_index = [&](int mi, int kt) -> int64_t {
+      const int row = mi * 16 + fr < rows ? mi * 16 + fr : rows - 1;            // rows past the end are never stored
+      return (int64_t)(p0 + row) * g.nkb + kt;
+    };
     auto load = [&](int buf, int kt) __attribute__((always_inline)) {
       if (scaled) {
+        kt_of[buf] = kt;
 #pragma unroll
-        for (int f = 0; f < 2; ++f) sb_v[buf][f] = scale_at(g.scale_b, sb_idx[f] + kt);
+        for (int f = 0; f < 2; ++f) sb_w[buf][f] = scale_word(g.scale_b, sb_idx[f] + kt);
 #pragma unroll
         for (int mi = 0; mi < MI; ++mi)
-          if (mi < nfrag) {
-            const int row = mi * 16 + fr < rows ? mi * 16 + fr : rows - 1;      // rows past the end are never stored
-            sa_v[buf][mi] = scale_at(g.scale_a, (int64_t)(p0 + row) * g.nkb + kt);
-          }
+          if (mi < nfrag) sa_w[buf][mi] = scale_word(g.scale_a, sa_index(mi, kt));
       }
 #pragma unroll
       for (int f = 0; f < 2; ++f)
@@ -192,7 +207,7 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
                                 (int)b[buf][f][1][0], (int)b[buf][f][1][1], (int)b[buf][f][1][2], (int)b[buf][f][1][3]};
               if (scaled) {
                 const f32x4 part = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(bv, av, f32x4{0.f, 0.f, 0.f, 0.f}, 0, 0, 0, 0, 0, 0);
-                const float sc = sa_v[buf][mi] * sb_v[buf][f];
+                const float sc = scale_value(sa_w[buf][mi], sa_index(mi, kt_of[buf])) * scale_value(sb_w[buf][f], sb_idx[f] + kt_of[buf]);
 #pragma unroll
                 for (int x = 0; x < 4; ++x) acc[f][mi][x] = __builtin_fmaf(sc, part[x], acc[f][mi][x]);
               } else {
@@ -218,23 +233,25 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
     if (kt < k_hi) multiply(0);                                    // odd number of K-tiles: the last one was loaded into buffer 0
 
     if constexpr (SPLITK) {
-      if (w) {
+      // the waves with kpart > 0 hand their sums to the wave with kpart = 0 of their row set, which adds them
+      // in the order of kpart and stores
+      if (kpart) {
 #pragma unroll
         for (int f = 0; f < 2; ++f)
 #pragma unroll
-          for (int x = 0; x < 4; ++x) partial[((w - 1) * 8 + f * 4 + x) * 64 + lane] = acc[f][0][x];
+          for (int x = 0; x < 4; ++x) partial[((wset * (KW - 1) + kpart - 1) * 8 + f * 4 + x) * 64 + lane] = acc[f][0][x];
       }
       __syncthreads();
-      if (w == 0) {
+      if (kpart == 0) {
 #pragma unroll
-        for (int v = 0; v < 3; ++v)
+        for (int v = 0; v < KW - 1; ++v)
 #pragma unroll
           for (int f = 0; f < 2; ++f)
 #pragma unroll
-            for (int x = 0; x < 4; ++x) acc[f][0][x] += partial[(v * 8 + f * 4 + x) * 64 + lane];
+            for (int x = 0; x < 4; ++x) acc[f][0][x] += partial[((wset * (KW - 1) + v) * 8 + f * 4 + x) * 64 + lane];
       }
       __syncthreads();                                             // the next pass writes the array again
-      if (w) continue;                                             // wave 0 stores
+      if (kpart) continue;
     }
 
     // ---- store: lane holds columns 4 q .. 4 q + 3 of row 16 mi + fr for each of its two fragments
@@ -265,15 +282,17 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
 
 namespace {
 template <bool SPLITK>
-void launch_stream(const GemmArgs& g, dim3 grid, hipStream_t s) {
+void launch_stream(const GemmArgs& g, unsigned ny, hipStream_t s) {
   const dim3 block(256);
+  constexpr int K16 = SPLITK ? 4 : 0, K8 = SPLITK ? 2 : 0;          // waves per row set: 16-bit inputs, fp8
+  const dim3 grid16((unsigned)(g.N / (SPLITK ? 32 : 128)), ny), grid8((unsigned)(g.N / (SPLITK ? 64 : 128)), ny);
   switch ((g.fp8 ? 4 : (g.f16 ? 2 : 0)) + (g.gated ? 1 : 0)) {
-    case 0: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, false, SPLITK>), grid, block, 0, s, g); break;
-    case 1: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, true, SPLITK>), grid, block, 0, s, g); break;
-    case 2: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, false, SPLITK>), grid, block, 0, s, g); break;
-    case 3: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, true, SPLITK>), grid, block, 0, s, g); break;
-    case 4: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, false, SPLITK>), grid, block, 0, s, g); break;
-    default: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, true, SPLITK>), grid, block, 0, s, g); break;
+    case 0: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, false, K16>), grid16, block, 0, s, g); break;
+    case 1: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, true, K16>), grid16, block, 0, s, g); break;
+    case 2: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, false, K16>), grid16, block, 0, s, g); break;
+    case 3: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, true, K16>), grid16, block, 0, s, g); break;
+    case 4: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, false, K8>), grid8, block, 0, s, g); break;
+    default: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, true, K8>), grid8, block, 0, s, g); break;
   }
 }
 }  // namespace
@@ -287,8 +306,8 @@ hipError_t launch_gemm_grouped_stream(const GemmArgs& g0, hipStream_t s) {
   g.compact_groups = g.M < g.groups;                               // at most M groups can have rows
   const unsigned ny = (unsigned)(g.compact_groups ? g.M : g.groups);
   static const int avg = [] { const char* v = getenv("AXE_GROUPED_SPLITK_ROWS"); return v ? atoi(v) : 8; }();
-  if (g.M <= avg * (int64_t)g.groups) launch_stream<true>(g, dim3((unsigned)(g.N / 32), ny), s);
-  else launch_stream<false>(g, dim3((unsigned)(g.N / 128), ny), s);
+  if (g.M <= avg * (int64_t)g.groups) launch_stream<true>(g, ny, s);
+  else launch_stream<false>(g, ny, s);
   return hipGetLastError();
 }
 
