@@ -214,8 +214,8 @@ typedef struct {
  * (G, N/128, ceil(K/128)): one per 128 x 128 block of each B[e]; fp32, or E8M0 codes (one byte, 2^(code - 127);
  * such arrays are read in aligned 4-byte words: 4-byte aligned, allocation padded to a multiple of 4 bytes).
  * Both NULL: unscaled.  K a multiple of 128; B[e] column-major (plain, or gate/up interleaved for the gated
- * epilogue).  Served by the streaming kernel only: M <= 8 G, or kernel_hint AXE_GROUPED_STREAM (any M; groups of
- * more than 64 rows then take several passes over their weights). */
+ * epilogue).  Served by the streaming kernel only, whatever M (groups of more than 64 rows then take several
+ * passes over their weights); a kernel_hint that asks for tiles is AXE_EUNSUPPORTED. */
 
 /* Two kernels serve the same family.  AXE_GROUPED_TILES: 256 x 256 tiles of the chained GEMM pipeline, for
  * groups of hundreds of rows (of 128 x 256 unless groups average more than 1536 rows: a K-step then takes half

@@ -763,10 +763,9 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     set_error("%s: E8M0 scale arrays must be 4-byte aligned", fn);
     return AXE_EINVAL;
   }
-  const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G);
-  if (fp8 && (!stream_kernel || g->K % 128 || opb.kt_stride || opb.rb)) {
-    set_error("%s: fp8 inputs are served by the streaming kernel only (M <= 8 G or kernel_hint AXE_GROUPED_STREAM), with K a "
-              "multiple of 128 and each B[e] column-major", fn);
+  const bool tiles_forced = g->kernel_hint == AXE_GROUPED_TILES || g->kernel_hint == AXE_GROUPED_TILES_256 || g->kernel_hint == AXE_GROUPED_TILES_128;
+  if (fp8 && (tiles_forced || g->K % 128 || opb.kt_stride || opb.rb)) {
+    set_error("%s: fp8 inputs are served by the streaming kernel only, with K a multiple of 128 and each B[e] column-major", fn);
     return AXE_EUNSUPPORTED;
   }
   if (g->G > 4096 || g->N % 256 || g->N / 256 > 2048 || g->K % 64 || g->M >= (int64_t(1) << 31) ||
@@ -833,7 +832,7 @@ int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const vo
                      const int32_t* d_group_rows, void* stream) {
   GemmArgs a;
   if (int rc = plan_gemm_grouped(g, d_A, d_B, d_C, d_group_rows, a, true)) return rc;
-  const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G);
+  const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || a.fp8 || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G);
   hipError_t e = stream_kernel ? launch_gemm_grouped_stream(a, (hipStream_t)stream) : launch_gemm_bf16_256_grouped(a, (hipStream_t)stream);
   return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm_grouped");
 }

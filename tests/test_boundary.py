@@ -261,8 +261,8 @@ def test_grouped_gemm_fp8_goes_to_the_streaming_kernel_only():
                                  M * K, G * N * K, M * N, in_dtype=B.AXE_FP8_E4M3, out_dtype=out, kernel_hint=hint,
                                  scale_a=Fake() if scales else None, scale_b=Fake() if scales else None, scale_dtype=sd)
     assert chk(desc()) == B.AXE_OK and chk(desc(scales=False)) == B.AXE_OK and chk(desc(sd=B.AXE_SCALE_E8M0)) == B.AXE_OK
-    assert chk(desc(M=4000)) == B.AXE_EUNSUPPORTED                                        # large groups: the tile kernel has no fp8 variant
-    assert chk(desc(M=4000, hint=B.AXE_GROUPED_STREAM)) == B.AXE_OK                       # ... unless the caller insists on streaming
+    assert chk(desc(M=4000)) == B.AXE_OK                                                  # large groups stream too (in passes of 64 rows)
+    assert chk(desc(M=4000, hint=B.AXE_GROUPED_STREAM)) == B.AXE_OK
     assert chk(desc(hint=B.AXE_GROUPED_TILES)) == B.AXE_EUNSUPPORTED
     assert chk(desc(K=192, Bs=W.spec([(64, 512 * 192, "m"), (192, 1, "m"), (512, 192, "m")]))) == B.AXE_EUNSUPPORTED   # K no multiple of 128
     assert chk(desc(out=B.AXE_F16)) == B.AXE_EUNSUPPORTED
