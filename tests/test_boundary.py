@@ -221,7 +221,8 @@ def test_grouped_gemm_family_matching_and_errors():
         == B.AXE_EUNSUPPORTED
     assert chk(_grouped_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_F16)) == B.AXE_OK
     assert chk(_grouped_desc(in_dtype=B.AXE_F16)) == B.AXE_EUNSUPPORTED                 # fp16 in, bf16 out
-    assert chk(_grouped_desc(in_dtype=B.AXE_FP8_E4M3)) == B.AXE_EUNSUPPORTED
+    assert chk(_grouped_desc(in_dtype=B.AXE_FP8_E4M3)) == B.AXE_OK                      # fp8 in, bf16 out: the streaming kernel
+    assert chk(_grouped_desc(in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_F32)) == B.AXE_EUNSUPPORTED
     assert chk(_grouped_desc(out_dtype=B.AXE_F32)) == B.AXE_EUNSUPPORTED
     assert chk(_grouped_desc(in_dtype=9)) == B.AXE_EINVAL
     assert chk(_grouped_desc(G=0, Bs=W.spec([(1, 1, "m"), (256, 1, "m"), (512, 256, "m")]))) == B.AXE_EINVAL
