@@ -1138,3 +1138,34 @@ def test_gemm_grouped_fp8_block_scaled(sizes, hint, gated, scale_dtype):
             for j in range(0, NC, 64):
                 blk = (slice(off[e], off[e + 1]), slice(j, j + 64))
                 assert R.rel_frobenius(c[blk], ref[blk]) <= FP8_TOL, (e, j)
+
+
+@pytest.mark.parametrize("kernel,gated", [(B.AXE_GROUPED_TILES_256, False), (B.AXE_GROUPED_TILES_128, False), (B.AXE_GROUPED_TILES_128, True),
+                                          (B.AXE_GROUPED_STREAM, False)])
+def test_gemm_grouped_is_bitwise_repeatable(kernel, gated):
+    """As for the dense kernels: 40 launches of the layer's first GEMM at 512 tokens give the same bits (the 128-row
+    tile has its own schedule of asm-issued loads and counted waits; the streaming kernel adds partial sums in a fixed order)."""
+    g = W.moe_gemm1(512)
+    NC = g.N // 2 if gated else g.N
+    img = W.pack_gate_up(g.b_gnk) if gated else g.b_gnk
+    Bs = W.gated_b_spec(g.K, g.N, g.G) if gated else W.grouped_gemm_specs(g)[1]
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
+    dC = torch.zeros(g.M * NC, dtype=torch.int16, device="cuda")
+    dR = torch.from_numpy(g.group_rows).cuda()
+    desc = B.GroupedGemmDesc(g.M, g.N, g.K, g.G, B.Layout(W.row_major_spec(g.M, g.K)), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, NC)),
+                             g.M * g.K, img.size, g.M * NC, epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=kernel)
+    first = None
+    for it in range(40):
+        dC.zero_()
+        B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+        if first is None:
+            first = dC.clone()
+        else:
+            assert torch.equal(first, dC), f"launch {it} differs from launch 0 in {(first != dC).sum().item()} elements"
+    # and the result is the right one (one group, against the oracle)
+    e = int(np.argmax(np.diff(g.group_rows)))
+    rows = np.arange(g.group_rows[e], g.group_rows[e + 1])
+    ref = R.gemm_ref(g.a_mk, g.b_gnk[e].T, R.AXE_BF16, rows=rows)
+    ref = R.swiglu_ref(ref) if gated else ref
+    c = R.bf16_to_f64(first.cpu().numpy().view(np.uint16).reshape(g.M, NC))[rows]
+    assert R.rel_frobenius(c, ref) <= BF16_TOL
