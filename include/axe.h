@@ -193,7 +193,9 @@ int axe_gemm_tile(const axe_gemm_desc_t* g);
  * (the grouped form of B by (G, K, N) has one iter per block); leading dimensions, offsets and the group
  * stride multiples of 16 bytes; N a multiple of 256, K a multiple of 64.
  * One launch, work found on the device from d_group_rows; nothing is allocated and no scratch memory
- * is used. */
+ * is used.  G = 1 with d_group_rows = {0, M} is a dense GEMM; with few rows (M <= 64) that is the way to
+ * the weight-streaming kernel (8192 x 8192 bf16 weights, M = 16: 33 us, against 125 us of axe_gemm's
+ * 64 x 64 kernel). */
 typedef struct {
   int64_t      M, N, K;
   int32_t      G;

@@ -70,14 +70,16 @@ __device__ __forceinline__ uint32_t pack16s(float lo, float hi) {
 // KS = the number of waves that share one set of 32 B rows and split K among them: 0 = SPLITK off (every wave its
 // own rows, all of K), 4 (16-bit inputs) or 2 (fp8, whose K-tiles are twice as deep: with 4 a wave's share of K
 // would be too few K-tiles for its pipeline); a workgroup then owns 4 / KS sets of 32 rows.
-template <int DT, bool GATED, int KS>
+// MI = row fragments per pass (16 MI rows of the group at a time): 1 goes with split K for groups of a handful of
+// rows, 4 with whole-K waves for the general case, and 4 with split K for launches with few groups (a dense
+// GEMM with few rows is the case of one group), where only the K split yields enough workgroups.
+template <int DT, bool GATED, int KS, int MI>
 __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   constexpr bool SPLITK = KS != 0;
   constexpr int KW = SPLITK ? KS : 1, SETS = SPLITK ? 4 / KS : 4;   // waves per row set, row sets per workgroup
   constexpr bool F16 = DT == 1, FP8 = DT == 2;
   constexpr int EB = FP8 ? 1 : 2;                                  // bytes per element
-  constexpr int MI = SPLITK ? 1 : 4;                               // row fragments per pass
-  __shared__ float partial[SPLITK ? (4 - SETS) * 64 * 8 : 1];      // SPLITK: the sums of the waves that do not store
+  __shared__ float partial[SPLITK ? (4 - SETS) * 64 * 8 * MI : 1]; // SPLITK: the sums of the waves that do not store
   const int lane = threadIdx.x & 63;
   const int w = __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6));
   const int M = (int)g.M;
@@ -237,18 +239,23 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
       // in the order of kpart and stores
       if (kpart) {
 #pragma unroll
-        for (int f = 0; f < 2; ++f)
+        for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-          for (int x = 0; x < 4; ++x) partial[((wset * (KW - 1) + kpart - 1) * 8 + f * 4 + x) * 64 + lane] = acc[f][0][x];
+          for (int f = 0; f < 2; ++f)
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+              partial[(((wset * (KW - 1) + kpart - 1) * MI + mi) * 8 + f * 4 + x) * 64 + lane] = acc[f][mi][x];
       }
       __syncthreads();
       if (kpart == 0) {
 #pragma unroll
         for (int v = 0; v < KW - 1; ++v)
 #pragma unroll
-          for (int f = 0; f < 2; ++f)
+          for (int mi = 0; mi < MI; ++mi)
 #pragma unroll
-            for (int x = 0; x < 4; ++x) acc[f][0][x] += partial[((wset * (KW - 1) + v) * 8 + f * 4 + x) * 64 + lane];
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+              for (int x = 0; x < 4; ++x) acc[f][mi][x] += partial[(((wset * (KW - 1) + v) * MI + mi) * 8 + f * 4 + x) * 64 + lane];
       }
       __syncthreads();                                             // the next pass writes the array again
       if (kpart) continue;
@@ -281,33 +288,36 @@ __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
 }
 
 namespace {
-template <bool SPLITK>
+template <int SPLIT, int MI>                                       // SPLIT: 0 = whole-K waves, 1 = K split over waves
 void launch_stream(const GemmArgs& g, unsigned ny, hipStream_t s) {
   const dim3 block(256);
-  constexpr int K16 = SPLITK ? 4 : 0, K8 = SPLITK ? 2 : 0;          // waves per row set: 16-bit inputs, fp8
-  const dim3 grid16((unsigned)(g.N / (SPLITK ? 32 : 128)), ny), grid8((unsigned)(g.N / (SPLITK ? 64 : 128)), ny);
+  constexpr int K16 = SPLIT ? 4 : 0, K8 = SPLIT ? 2 : 0;            // waves per row set: 16-bit inputs, fp8
+  const dim3 grid16((unsigned)(g.N / (SPLIT ? 32 : 128)), ny), grid8((unsigned)(g.N / (SPLIT ? 64 : 128)), ny);
   switch ((g.fp8 ? 4 : (g.f16 ? 2 : 0)) + (g.gated ? 1 : 0)) {
-    case 0: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, false, K16>), grid16, block, 0, s, g); break;
-    case 1: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, true, K16>), grid16, block, 0, s, g); break;
-    case 2: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, false, K16>), grid16, block, 0, s, g); break;
-    case 3: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, true, K16>), grid16, block, 0, s, g); break;
-    case 4: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, false, K8>), grid8, block, 0, s, g); break;
-    default: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, true, K8>), grid8, block, 0, s, g); break;
+    case 0: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, false, K16, MI>), grid16, block, 0, s, g); break;
+    case 1: hipLaunchKernelGGL((gemm_grouped_stream_kernel<0, true, K16, MI>), grid16, block, 0, s, g); break;
+    case 2: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, false, K16, MI>), grid16, block, 0, s, g); break;
+    case 3: hipLaunchKernelGGL((gemm_grouped_stream_kernel<1, true, K16, MI>), grid16, block, 0, s, g); break;
+    case 4: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, false, K8, MI>), grid8, block, 0, s, g); break;
+    default: hipLaunchKernelGGL((gemm_grouped_stream_kernel<2, true, K8, MI>), grid8, block, 0, s, g); break;
   }
 }
 }  // namespace
 
-// The host knows the number of rows of all groups together, not the group sizes: up to 8 rows per group on
+// The host knows the number of rows of all groups together, not the group sizes.  Up to 8 rows per group on
 // average (an MoE layer of 128 experts, 8 per token, up to 128 tokens: at most 22 rows in any group in the
 // benchmark's routing) it takes the variant that splits K over the waves and handles 16 rows per pass
-// (measured crossover between 8 and 16; AXE_GROUPED_SPLITK_ROWS overrides it for experiments).
+// (measured crossover between 8 and 16; AXE_GROUPED_SPLITK_ROWS overrides it for experiments).  Beyond that,
+// whole-K waves with 64 rows per pass -- unless that launch would have fewer than two workgroups per compute unit
+// (few groups: a dense GEMM with few rows is one group), where K is split as well.
 hipError_t launch_gemm_grouped_stream(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
   g.compact_groups = g.M < g.groups;                               // at most M groups can have rows
   const unsigned ny = (unsigned)(g.compact_groups ? g.M : g.groups);
   static const int avg = [] { const char* v = getenv("AXE_GROUPED_SPLITK_ROWS"); return v ? atoi(v) : 8; }();
-  if (g.M <= avg * (int64_t)g.groups) launch_stream<true>(g, ny, s);
-  else launch_stream<false>(g, ny, s);
+  if (g.M <= avg * (int64_t)g.groups) launch_stream<1, 1>(g, ny, s);
+  else if ((g.N / 128) * (int64_t)ny < 2 * cu_count()) launch_stream<1, 4>(g, ny, s);
+  else launch_stream<0, 4>(g, ny, s);
   return hipGetLastError();
 }
 

@@ -1169,3 +1169,20 @@ def test_gemm_grouped_is_bitwise_repeatable(kernel, gated):
     ref = R.swiglu_ref(ref) if gated else ref
     c = R.bf16_to_f64(first.cpu().numpy().view(np.uint16).reshape(g.M, NC))[rows]
     assert R.rel_frobenius(c, ref) <= BF16_TOL
+
+
+@pytest.mark.parametrize("G,N,lo,hi", [(2, 512, 40, 71),      # few groups: K split over waves, 64 rows per pass
+                                       (1, 256, 17, 18),      # one group = a dense GEMM with few rows
+                                       (300, 256, 0, 41)])    # many groups of a few dozen rows: whole-K waves
+def test_gemm_grouped_stream_kernel_choice_by_launch_size(G, N, lo, hi):
+    rng = np.random.default_rng(G)
+    sizes = rng.integers(lo, hi, G)
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    g = W.gemm_grouped_bf16(off, N, 320 if G < 300 else 64, 108)
+    assert g.M > 8 * g.G
+    Kp = 384 if G < 300 else 64
+    a = np.zeros((g.M, Kp), dtype=np.uint16); a[:, :g.K] = g.a_mk
+    b = np.zeros((g.G, N, Kp), dtype=np.uint16); b[:, :, :g.K] = g.b_gnk
+    gp = W.GroupedGemmInputs(g.M, N, Kp, g.G, a, b, g.group_rows)
+    c, raw = run_grouped(gp, kernel=B.AXE_GROUPED_STREAM)
+    check_grouped(gp, c, raw, R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_BF16))
