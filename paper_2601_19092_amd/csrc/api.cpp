@@ -357,6 +357,7 @@ struct GemmPlan {
   GemmArgs args;
   bool fp8;
   int tile;           // AXE_TILE_*
+  bool ragged;        // 256x256 tile on a shape with ragged edges (M, N no multiples of 256)
 };
 
 // A 2-D operand whose canonical memory layout is "unit stride along `inner`, pitch along
@@ -578,6 +579,10 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   const bool big_ok = big_common && (g->N % 256 == 0);
   // bf16 only: 224 columns per tile (7 fragments per wave instead of 8)
   const bool n224_ok = big_common && !fp8 && !f16 && (g->N % 224 == 0);
+  // 16-bit inputs: the 256x256 tile also on edges that do not fill a tile (a lane stores 8 columns at once; a wave's
+  // part of C and the tile's part of B are addressed through 32-bit offsets; tile columns are counted in 11 bits)
+  const bool ragged_ok = !fp8 && (g->K % 64 == 0) && (g->N % 8 == 0) && (ldc % 8 == 0) && P.args.out_bf16 && pitch_ok &&
+                         256 * ldc * 2 < (int64_t(1) << 31) && g->N <= 2048 * 256 && g->M < (int64_t(1) << 31);
   int tile = g->tile_hint;
   if (row_scaled) {                                                // only the 64 x 64 kernel folds a scale per row
     if (tile != AXE_TILE_AUTO && tile != AXE_TILE_64x64x32) {
@@ -596,6 +601,11 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   }
   if (tile == AXE_TILE_AUTO) {
     tile = big_ok ? AXE_TILE_256x256x64 : (n224_ok ? AXE_TILE_256x224x64 : AXE_TILE_64x64x32);
+    // ragged edges: the large tile once the 64 x 64 tiles of C would take more than about four rounds on the chip
+    // (measured, bf16, K = 1024 .. 4096: 1000 x 1000 12 vs 27 us, 2000 x 2000 41 vs 47 us, 4000 x 4000 388 vs 107 us --
+    //  a single large tile takes 27 - 47 us on its own, the small tiles' time grows with M x N)
+    static const int64_t ragged_min = [] { const char* v = getenv("AXE_RAGGED_MIN_ELEMS"); return v ? atoll(v) : int64_t(5) << 20; }();
+    if (tile == AXE_TILE_64x64x32 && ragged_ok && g->M * g->N >= ragged_min) tile = AXE_TILE_256x256x64;
     if (big_ok && n224_ok) {
       // both fit: the launch runs ceil(tiles / compute units) rounds of tiles one after the other,
       // each as long as the tile is wide; take the narrower tile when that is shorter in total
@@ -604,9 +614,10 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
       if (t224 < t256) tile = AXE_TILE_256x224x64;
     }
   }
-  if (tile == AXE_TILE_256x256x64 && !big_ok) {
-    set_error("axe_gemm: the 256x256 tile needs M, N multiples of 256, K a multiple of %lld, bf16 output and "
-              "row pitches below 2^31 / 256 bytes", (long long)bk);
+  P.ragged = tile == AXE_TILE_256x256x64 && !big_ok && !blocked && ragged_ok;
+  if (tile == AXE_TILE_256x256x64 && !big_ok && !P.ragged) {
+    set_error("axe_gemm: the 256x256 tile needs K a multiple of %lld, a 16-bit output, row pitches below 2^31 / 256 bytes "
+              "and, for fp8, M and N multiples of 256 (16-bit inputs: any M, N a multiple of 8)", (long long)bk);
     return AXE_EUNSUPPORTED;
   }
   if (tile == AXE_TILE_256x224x64 && !n224_ok) {
@@ -630,6 +641,7 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   P.args.b_tpb_shift = opb.rb ? ilog2(opb.rb / 256) : 0;
   P.args.a_blk_stride = opa.rb ? opa.rb_stride : bm * lda;
   P.args.b_blk_stride = opb.rb ? opb.rb_stride : bn * ldb;
+  if (P.ragged) P.args.groups = 1, P.args.tile_m = 256;            // one group of all rows, no offsets array
   if (P.args.grid_m > 65535) {
     set_error("axe_gemm: M too large for one launch");
     return AXE_EUNSUPPORTED;
@@ -847,7 +859,7 @@ int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d
   if (int rc = plan_gemm(g, d_A, d_B, d_C, P, true)) return rc;
   hipError_t e;
   if (P.tile == AXE_TILE_256x256x64 || P.tile == AXE_TILE_256x224x64)
-    e = !P.fp8 ? launch_gemm_bf16_256(P.args, (hipStream_t)stream)
+    e = !P.fp8 ? (P.ragged ? launch_gemm_bf16_256_ragged(P.args, (hipStream_t)stream) : launch_gemm_bf16_256(P.args, (hipStream_t)stream))
         // power-of-two scales (or none) ride on the matrix cores' scale operands; arbitrary fp32 scales are folded on the vector ALU
         : (P.args.scale_e8m0 || !P.args.scale_a ? launch_gemm_fp8_e8m0_256(P.args, (hipStream_t)stream)
                                                 : launch_gemm_fp8_256(P.args, (hipStream_t)stream));

@@ -22,6 +22,8 @@ hipError_t launch_gemm_small(const GemmArgs& g, bool fp8, hipStream_t s);
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s);
 // grouped (g.group_rows, g.groups, g.ldg set; g.M = rows of all groups together, any value): N % 256 == 0, K % 64 == 0
 hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s);
+// dense with ragged edges through the grouped kernel (g.groups = 1, g.group_rows null): any M, N % 8 == 0, K % 64 == 0
+hipError_t launch_gemm_bf16_256_ragged(const GemmArgs& g, hipStream_t s);
 // grouped, few rows per group: one workgroup per (group, 128 rows of B), weights streamed once, no LDS
 hipError_t launch_gemm_grouped_stream(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_fp8_256(const GemmArgs& g, hipStream_t s);

@@ -115,7 +115,7 @@ __device__ __forceinline__ uint32_t pack16(float lo, float hi) {
 __device__ __forceinline__ int desc_rows(int d) { return d & 511; }
 __device__ __forceinline__ int desc_tn(int d) { return (d >> 9) & 2047; }
 __device__ __forceinline__ int desc_group(int d) { return (int)((unsigned)d >> 20); }
-template <int TM>                                                 // rows of a tile
+template <int TM, bool ONE = false>                               // rows of a tile; ONE: a single group of all M rows, no offsets array
 __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_row0, int& t_desc) {
   const int G = g.groups, M = (int)g.M, gn = g.grid_n;
   const int* __restrict__ off = g.group_rows;
@@ -123,7 +123,11 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
   auto chunk = [&](int g0) __attribute__((always_inline)) {         // groups g0 .. g0 + 63, one per lane
     const int gi = g0 + lane;
     int a = 0, b = 0;
-    if (gi < G) a = off[gi], b = off[gi + 1];
+    if constexpr (ONE) {
+      if (gi == 0) b = M;
+    } else if (gi < G) {
+      a = off[gi], b = off[gi + 1];
+    }
     a = a < 0 ? 0 : (a > M ? M : a);
     b = b < 0 ? 0 : (b > M ? M : b);
     r0 = a;
@@ -195,8 +199,15 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 // 2 x 64 and moves half as much of A (4 pieces per wave and K-step), so that the weights stream past twice as
 // fast -- with few rows per group the time is that of reading B from HBM.  The A blocks in LDS keep their
 // places (half of each is used); loads per K-step 12 instead of 16, hence other wait counts.
-template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8>
+//
+// RAGGED: a dense GEMM whose M is no multiple of the tile height and whose N is no multiple of 256 (but of 8:
+// a lane stores 8 columns at once), run as a grouped one with a single group of all rows.  What M leaves over
+// is handled like a group's last tile; what N leaves over: the B descriptor of a tile in the last column ends
+// after the rows that exist (the others load as zero), and a lane whose 8 columns lie past N stores at an
+// offset no buffer reaches, which drops the store.
+template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
+  static_assert(!RAGGED || (GROUPED && !GATED && NB == 256), "ragged edges are handled by the grouped 256-wide kernel");
   static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
   static_assert(MR == 8 || (MR == 4 && GROUPED), "128-row tiles exist for the grouped kernel");
   constexpr int TM = 32 * MR;                                      // rows of a tile
@@ -241,7 +252,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     int rot;
   };
   int tb_row0 = 0, tb_desc = 0;                                    // grouped: lane t = the workgroup's t-th tile
-  if constexpr (GROUPED) group_tiles<TM>(g, lane, tb_row0, tb_desc);
+  if constexpr (GROUPED) group_tiles<TM, RAGGED>(g, lane, tb_row0, tb_desc);
   auto table_rows = [&](int t) __attribute__((always_inline)) -> int { return t < 64 ? desc_rows(__builtin_amdgcn_readlane(tb_desc, t)) : 0; };
   // dense: v = tile id; grouped: v = index into the workgroup's table
   auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
@@ -253,8 +264,10 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
         const int grp = desc_group(dsc), tn = desc_tn(dsc);
         const uint8_t* pa = (const uint8_t*)g.A + (int64_t)row0 * g.lda * 2;
         t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)pa, 0, (rows - 1) * a_pitch + a_span, 0x00020000);
+        int nb = NB;                                               // rows of B the tile has
+        if constexpr (RAGGED) nb = (int)g.N - tn * NB < NB ? (int)g.N - tn * NB : NB;
         t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + ((int64_t)grp * g.ldg + b_tile_off(tn)) * 2), 0,
-                                                 (NB - 1) * b_pitch + b_span, 0x00020000);
+                                                 (nb - 1) * b_pitch + b_span, 0x00020000);
         t.rot = ((row0 >> 8) + tn) & (kRot - 1);
         t.ra_words = raw_rsrc(pa, (uint32_t)((rows - 1) * a_pitch + a_span));
         return t;
@@ -359,6 +372,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   i32x4 rc;                                                        // descriptor of this wave's part of the C tile
   int c_rowblk;                                                    // bytes between fragment rows
   const int c_voff = (int)((fr * g.ldc + 4 * fq) * 2);
+  int c_cw = 0;                                                    // ragged: columns of this wave's part of the tile that exist
   auto set_output = [&](int vv) __attribute__((always_inline)) {
     if constexpr (GROUPED) {
       const int row0 = __builtin_amdgcn_readlane(tb_row0, vv), dsc = __builtin_amdgcn_readlane(tb_desc, vv);
@@ -366,8 +380,15 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
       int rows = desc_rows(dsc) - wm * (16 * MR);                    // rows of the tile that fall to this wave
       rows = rows < 0 ? 0 : (rows > 16 * MR ? 16 * MR : rows);
       constexpr int CW = GATED ? NB / 4 : NB / 2;                    // columns of C this wave writes
+      int cw = CW;
+      if constexpr (RAGGED) {
+        cw = (int)g.N - tn * NB - wn * CW;                           // ... of which exist
+        cw = cw < 0 ? 0 : (cw > CW ? CW : cw);
+        if (cw == 0) rows = 0;
+        c_cw = cw;
+      }
       rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * (16 * MR)) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
-                    rows ? (uint32_t)(((rows - 1) * g.ldc + CW) * 2) : 0u);
+                    rows ? (uint32_t)(((rows - 1) * g.ldc + cw) * 2) : 0u);
       c_rowblk = (int)(16 * g.ldc * 2);
       return;
     }
@@ -398,7 +419,18 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
                                                      pack16<F16>(acc[i][j + 1][2], acc[i][j + 1][3]), false, false);
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    // (an offset of 2^31 is past the end of every descriptor -- their ranges stay below 2^31 bytes)
+    int voff = c_voff2;
+    if constexpr (RAGGED) {
+      // the lane's first column, worked out here from the lane number (an asm statement, so that it is not
+      // hoisted above the K loops, where it would occupy a register the pipeline needs)
+      int l;
+      asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+      const int q = l >> 4;
+      const int c0 = (q & 1) ? 16 + 4 * (q - 1) : 4 * q;
+      if (j * 16 + c0 + 8 > c_cw) voff = (int)0x80000000u;
+    }
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
   };
@@ -577,6 +609,9 @@ __global__ __launch_bounds__(256, 1) void gemm_f16_256_kernel(GemmArgs g) { gemm
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, true>(g); }
 // grouped, tiles of 128 rows (small groups)
+// dense with ragged edges (any M, N a multiple of 8)
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_ragged_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, false, 8, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_256_ragged_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true, 8, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_bf16_128_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, false, 4>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_bf16_128_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, false, 4>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_128_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true, 4>(g); }
@@ -631,6 +666,23 @@ hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
     case 6: hipLaunchKernelGGL(gemm_f16_128_grouped_kernel, grid, block, 0, s, g); break;
     default: hipLaunchKernelGGL(gemm_f16_128_grouped_gated_kernel, grid, block, 0, s, g); break;
   }
+  return hipGetLastError();
+}
+
+// Dense with ragged edges: the grouped kernel's machinery with one group of all M rows (g.groups = 1, no offsets
+// array), tiles of 256 rows; the host knows the tile count exactly.
+hipError_t launch_gemm_bf16_256_ragged(const GemmArgs& g, hipStream_t s) {
+  const int64_t tiles = (g.M + kTile - 1) / kTile * (int64_t)g.grid_n;
+  const int nk = (int)(g.K / 64);
+  const int cus = cu_count();
+  const bool chain = (nk % 2 == 0) && nk >= 4;
+  int64_t nwg = chain ? std::min<int64_t>(tiles, std::max<int64_t>(cus, (tiles + 63) / 64)) : tiles;
+  nwg = (nwg + 7) / 8 * 8;
+  if (nwg > 0x7fffffff || g.groups != 1) return hipErrorInvalidValue;
+  if (g.f16)
+    hipLaunchKernelGGL(gemm_f16_256_ragged_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  else
+    hipLaunchKernelGGL(gemm_bf16_256_ragged_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 

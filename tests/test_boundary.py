@@ -122,7 +122,17 @@ def test_gemm_family_matching_and_errors():
     assert _tile_rc(_gemm_desc()) == B.AXE_TILE_256x256x64
     assert _tile_rc(_gemm_desc(M=200)) == B.AXE_TILE_64x64x32
     assert _tile_rc(_gemm_desc(out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
-    assert _tile_rc(_gemm_desc(M=200, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
+    # 16-bit inputs: the large tile takes ragged edges (any M, N a multiple of 8) -- on request, and by itself once
+    # the problem is a few tiles large; fp8 and odd N stay with whole tiles / the small tile
+    assert _tile_rc(_gemm_desc(M=200, tile=B.AXE_TILE_256x256x64)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(M=1000, N=1000)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(M=3000, N=3000)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(M=3000, N=3000, in_dtype=B.AXE_F16, out_dtype=B.AXE_F16)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(M=3000, N=3001)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(M=3000, N=3004, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(_gemm_desc(M=3000, N=3000, out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(M=200, in_dtype=B.AXE_FP8_E4M3, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(_gemm_desc(M=3000, N=3000, in_dtype=B.AXE_FP8_E4M3)) == B.AXE_TILE_64x64x32
     # the shard of a column-parallel layer: extent-1 device iter + device offset are dropped (rule D0)
     g = W.gemm_bf16(256, 512, 256, 1)
     _, Bshard, _ = W.gemm_specs(g, device_axis=True, shard=5)

@@ -3,6 +3,7 @@
 Bars: layout evaluation and relayout bit-exact; GEMM relative Frobenius error <= 5e-3 (bf16
 inputs) / 3e-2 (fp8 inputs) against the fp64 oracle on the same quantised inputs, for the whole
 matrix and for every 128 x 128 tile of it (a single wrong tile cannot hide in the global norm)."""
+import ctypes as C
 import itertools
 import random
 from math import prod
@@ -413,6 +414,48 @@ def test_gemm_bf16_large_tile(M, N, K):
     # bf16 output of the large tile equals the small tile's up to the last rounding (different k order)
     c_small = run_gemm(g, tile=B.AXE_TILE_64x64x32)
     assert R.rel_frobenius(c, c_small) < 2e-3
+
+
+# Ragged edges on the large tile (16-bit inputs): any M, N a multiple of 8.  C is pitched and followed by guard rows,
+# all filled with a pattern beforehand: nothing outside the M x N result may change.  K = 64 nk with nk = 1, 2, 3
+# (shorter than the pipeline), 4 and 8 (several tiles chained per workgroup), 11 (odd).
+@pytest.mark.parametrize("M,N,K", [(200, 136, 64), (257, 264, 128), (1000, 1000, 256), (513, 8, 192), (300, 520, 704),
+                                   (1, 256, 64), (777, 1288, 512), (255, 248, 256)])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_gemm_large_tile_ragged_edges(M, N, K, dtype):
+    g = (W.gemm_bf16 if dtype == "bf16" else W.gemm_f16)(M, N, K, 370 + M, std_b=K ** -0.5)
+    ldc, guard, fill = N + 24, 3, 0x1234
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_nk.reshape(-1))
+    dC = torch.full(((M + guard) * ldc,), fill, dtype=torch.int16, device="cuda")
+    dt = B.AXE_BF16 if dtype == "bf16" else B.AXE_F16
+    desc = B.GemmDesc(M, N, K, dt, dt, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, N)),
+                      B.Layout(W.spec([(M, ldc, "m"), (N, 1, "m")])), M * K, N * K, (M + guard) * ldc,
+                      tile_hint=B.AXE_TILE_256x256x64)
+    assert B.lib().axe_gemm_tile(C.byref(desc.c)) == B.AXE_TILE_256x256x64
+    B.axe_gemm(desc, dA, dB, dC)
+    torch.cuda.synchronize()
+    raw = dC.cpu().numpy().view(np.uint16).reshape(M + guard, ldc)
+    assert (raw[:M, N:] == fill).all() and (raw[M:] == fill).all(), "the kernel wrote outside the M x N result"
+    c = decode16(raw[:M, :N], dtype)
+    check_gemm(c, oracle_gemm(g), BF16_TOL if dtype == "bf16" else F16_TOL, tile=64)
+    g.out_dtype = dtype
+    c_small = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+    assert R.rel_frobenius(c, c_small) < (2e-3 if dtype == "bf16" else 3e-4)
+
+
+def test_gemm_large_tile_ragged_edges_many_tiles_per_workgroup():
+    # 37 x 35 tiles, the last of each ragged: more tiles than compute units, chained through the pipeline
+    g = W.gemm_bf16(9300, 8808, 256, 391, std_b=1 / 16)
+    c = run_gemm(g)
+    rows = np.array([0, 255, 256, 9215, 9216, 9299])
+    assert R.rel_frobenius(c[rows], oracle_gemm(g, rows, None)) <= BF16_TOL
+    cols = np.array([0, 8703, 8704, 8807])
+    assert R.rel_frobenius(c[:, cols], oracle_gemm(g, None, cols)) <= BF16_TOL
+    # every tile against the small kernel (same inputs, other order of the K sum)
+    c_small = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+    for i in range(0, g.M, 256):
+        for j in range(0, g.N, 256):
+            assert R.rel_frobenius(c[i:i + 256, j:j + 256], c_small[i:i + 256, j:j + 256]) < 2e-3, (i, j)
 
 
 # 224 columns per tile (7 fragments per wave along N): same K cases, N a multiple of 224

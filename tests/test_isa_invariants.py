@@ -61,6 +61,8 @@ CASES = [("kernels_gemm_bf16.hip", "gemm_bf16_256_kernel", {31, 17}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_256_grouped_kernel", {31, 17}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_256_blocked_kernel", {31, 17}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_256_grouped_gated_kernel", {31, 17}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_bf16_256_ragged_kernel", {31, 17}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_f16_256_ragged_kernel", {31, 17}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_128_grouped_kernel", {23, 13}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_128_grouped_gated_kernel", {23, 13}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_256_kernel", {31, 17}, True, 0),
