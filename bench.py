@@ -354,7 +354,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--only", default="", help="comma list of: gemm,relayout,fp8,shard,grouped,small,eval,ceilings,cpu (default all)")
+    ap.add_argument("--only", default="", help="comma list of: gemm,relayout,fp8,shard,ragged,grouped,small,eval,ceilings,cpu (default all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -379,6 +379,10 @@ def main():
     if want("shard"):
         comp["gemm_cfg4_tp_shard"], _ = bench_gemm("bf16 GEMM M=4096 K=8192 N=3584 (1 of 8 shards)", W.config4(),
                                                    args.steps, args.warmup, device_axis=True)
+    if want("ragged"):
+        comp["gemm_ragged_4000"], _ = bench_gemm("bf16 GEMM M=N=4000 K=4096 (edges that do not fill a 256x256 tile)",
+                                                 W.gemm_bf16(4000, 4000, 4096, W.SEED_BASE + 7, std_b=4096 ** -0.5),
+                                                 args.steps, args.warmup)
     g5 = W.config5() if (want("fp8") or want("ceilings")) else None
     if want("fp8"):
         comp["gemm_cfg5_fp8_block_scaled"], _ = bench_gemm("fp8 e4m3 GEMM 8192^3, fp32 128x128 block scales", g5,
