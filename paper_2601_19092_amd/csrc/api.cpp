@@ -228,6 +228,7 @@ int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank,
         p.blocks = blocks;
         const int nt = env_int("AXE_RELAYOUT_NT", -1);
         p.streaming = nt >= 0 ? nt : (2 * E * (int64_t)elem_bytes >= (int64_t(128) << 20));
+        p.diag = env_int("AXE_TRANSPOSE_DIAG", 1);
         hipError_t e = launch_relayout_transpose(p, elem_bytes, d_src, d_dst, st);
         return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_relayout");
       }

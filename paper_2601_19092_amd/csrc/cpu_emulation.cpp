@@ -101,8 +101,9 @@ hipError_t launch_relayout_transpose(const TransposePlan& p, int eb, const void*
     uint64_t b = blk;
     const int64_t ts = (int64_t)(b % p.tiles_s);
     b /= p.tiles_s;
-    const int64_t td = (int64_t)(b % p.tiles_d);
+    int64_t td = (int64_t)(b % p.tiles_d);
     b /= p.tiles_d;
+    if (p.diag > 0) td = (td + ts / p.diag) % p.tiles_d;
     int64_t sb = p.s_off, db = p.d_off;
     for (int k = 0; k < p.n; ++k) {
       sb += (int64_t)(b % p.ext[k]) * p.ss[k];

@@ -61,6 +61,7 @@ struct TransposePlan {
   uint32_t tiles_s, tiles_d;       // tiles along the source-fast and the destination-fast digit
   uint64_t blocks;                 // tiles_s * tiles_d * product of ext[]
   int32_t streaming;               // 1: non-temporal loads and stores
+  int32_t diag;                    // g > 0: tiles are walked diagonally, td = (row + ts / g) mod tiles_d; 0: row by row
 };
 
 // Fallback when the two digit systems have no common refinement: decode each side separately.

@@ -293,8 +293,7 @@ __global__ __launch_bounds__(256) void relayout_transpose_kernel(TransposePlan p
   // column, and the 16 (or more) lanes that do so for neighbouring chunks sit CE rows apart: their keys differ,
   // so they read different banks (a padded pitch cannot do that for 1- and 2-byte elements: CE x pitch is a
   // multiple of 8 words, and two of every 16 lanes met in a bank).  Measured: the conflict counter drops to
-  // zero, the throughput stays where it was (4.1 - 4.2 TB/s on 8192 x 8192 bf16) -- LDS is not what bounds
-  // this kernel; neither is the order of the tiles (8 x 8 blocks of neighbouring tiles at a time: no change).
+  // zero.
   __shared__ __attribute__((aligned(16))) uint8_t tile[T * ROWB];
   auto lds_at = [&](int row, int byte_col, int key) -> uint8_t* {
     return tile + row * ROWB + ((((byte_col >> 4) ^ key) & (CPR - 1)) << 4) + (byte_col & 15);
@@ -304,8 +303,13 @@ __global__ __launch_bounds__(256) void relayout_transpose_kernel(TransposePlan p
   uint64_t b = blockIdx.x;
   const uint32_t ts = (uint32_t)(b % p.tiles_s);
   b /= p.tiles_s;
-  const uint32_t td = (uint32_t)(b % p.tiles_d);
+  uint32_t td = (uint32_t)(b % p.tiles_d);
   b /= p.tiles_d;
+  // Row by row (ts fastest, td fixed for tiles_s workgroups in a row) the workgroups running at one time read
+  // whole rows of the source between them, but write one narrow column of the destination: short segments a row
+  // pitch apart, which with power-of-two pitches fall on a fraction of the memory channels.  Walking the tiles
+  // diagonally gives every window of workgroups many different td as well as many different ts.
+  if (p.diag > 0) td = (td + ts / (uint32_t)p.diag) % p.tiles_d;
   int64_t sb = p.s_off, db = p.d_off;
   for (int k = 0; k < p.n; ++k) {
     const uint64_t q = b / p.ext[k];
@@ -316,15 +320,29 @@ __global__ __launch_bounds__(256) void relayout_transpose_kernel(TransposePlan p
   }
   const int64_t s0 = (int64_t)ts * T, d0 = (int64_t)td * T;      // tile origin in the two digits
 
-  // HBM -> LDS: row r of the tile is destination-fast index d0 + r, its chunks run along the source
-  for (int c = threadIdx.x; c < T * CPR; c += 256) {
+  // HBM -> LDS: row r of the tile is destination-fast index d0 + r, its chunks run along the source.  All loads
+  // of a thread are issued before the first of them is waited for: with one load at a time in flight per thread
+  // the kernel was bound by the latency of HBM (4.1 - 4.2 TB/s on 8192 x 8192 bf16, whatever the LDS layout or the
+  // order of the tiles), not by its bandwidth.
+  constexpr int NL = T * CPR / 256;                              // chunks per thread
+  u32x4 held[NL];
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int c = (int)threadIdx.x + 256 * i;
     const int r = c / CPR, cc = c % CPR;
     const int64_t iD = d0 + r, iS = s0 + (int64_t)cc * CE;
-    if (iD < p.eD && iS < p.eS) {                                // extents are multiples of CE: a chunk is in or out as a whole
-      const u32x4* a = (const u32x4*)(src + (sb + iD * p.sD + iS) * EB);
-      const u32x4 v = NT ? __builtin_nontemporal_load(a) : *a;
-      *(u32x4*)lds_at(r, cc * 16, r / CE) = v;
-    }
+    // extents are multiples of CE: a chunk is in or out as a whole.  A chunk outside the tensor is replaced by the
+    // tile's first one (always inside) instead of being skipped: a load under a branch would be waited for at
+    // the end of that branch, one by one.
+    const bool in = iD < p.eD && iS < p.eS;
+    const u32x4* a = (const u32x4*)(src + (sb + (in ? iD * p.sD + iS : d0 * p.sD + s0)) * EB);
+    held[i] = NT ? __builtin_nontemporal_load(a) : *a;
+  }
+#pragma unroll
+  for (int i = 0; i < NL; ++i) {
+    const int c = (int)threadIdx.x + 256 * i;
+    const int r = c / CPR, cc = c % CPR;
+    *(u32x4*)lds_at(r, cc * 16, r / CE) = held[i];               // (chunks outside the tensor: values nobody reads)
   }
   __syncthreads();
   // LDS -> HBM: output row r is source-fast index s0 + r, its chunks run along the destination
