@@ -323,7 +323,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const i32x4 r = nx ? nxt.ra_words : cur.ra_words;
     const int soff = __builtin_amdgcn_readfirstlane(i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep);
     u32x4 v;
-    asm volatile("s_nop 4\n\tbuffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
+    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
     return v;
   };
   auto a_write = [&](int stage, int i, u32x4 v) __attribute__((always_inline)) {
@@ -482,37 +482,64 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const int wT = S == 0 ? kt + 1 : kt + 2;
     const int bT = S == 0 ? kt + 2 : kt + 3;
     const int bslot = S == 0 ? bo2 : bo0;
+    // With 256-row tiles the barrier of a K-step does not stand between the two sub-steps but two rows of MFMAs
+    // (16 of them, 256 cycles) into sub-step 1: the wave reaches it with the last LDS read of sub-step 0 long
+    // complete and a little more time for its B loads to land, instead of draining the matrix pipe while it waits
+    // for that read.  Everything that needs the barrier -- reads of step kt + 1, writes and loads into what step
+    // kt occupied -- is scheduled into rows 2..7 of sub-step 1; rows 0 and 1 only multiply what is in registers.
+    constexpr bool LATE = MR == 8;
+    auto step_barrier = [&]() __attribute__((always_inline)) {
+      // Own reads of step kt and own writes of step kt+1 are complete, and so are own B loads of step
+      // kt+1 (the 17 younger loads may still be in flight).  After the barrier step kt+1 is readable
+      // by every wave and nobody reads step kt any more.
+      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kWaitStep) : "memory");
+      wg_barrier();
+    };
+    auto a_stage = [&](int p) __attribute__((always_inline)) {
+      // the load that filled this slot was issued 4 sub-steps ago; kWaitSlot loads have been issued since
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWaitSlot) : "memory");
+      a_write(WST, p, stg[WST * NA + p]);
+      stg[WST * NA + p] = a_load(wT + 2, p, CROSS);
+    };
 #pragma unroll
     for (int i = 0; i < MR; ++i) {
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         mfma_16x16x32<F16>(acc[i][j], fb[CUR][j], fa[i]);
         __builtin_amdgcn_sched_barrier(0);
-        // (with 4 rows the reads sit earlier in the row: the last fragment is needed 9 MFMAs after row 3 ends)
-        constexpr int jb0 = MR == 8 ? 1 : 0, jb1 = MR == 8 ? 5 : 3;
-        if (i < 4 && (j == jb0 || j == jb1) && 2 * i + (j == jb1) < NJ)
-          fb[NXT][2 * i + (j == jb1)] = lds_read(pb + (2 * i + (j == jb1)) * 16 * kRow);
-        if (j == NJ - 1) fa[i] = lds_read(pa + i * 16 * kRow);
-        // four B loads per sub-step: after MFMA j = 2 of the even rows (8 rows), or of every row (4 rows)
-        if (MR == 8 ? ((i & 1) == 0 && j == 2) : j == 2) b_load(bT, (S == 0 ? 4 : 0) + (MR == 8 ? i >> 1 : i), bslot, CROSS);
-        // HA staged A pieces per sub-step: after MFMA j = 2 (8 rows) or j = 6 (4 rows) of the odd rows
-        if ((i & 1) == 1 && j == (MR == 8 ? 2 : 6)) {
-          const int p = (S == 0 ? HA : 0) + (i >> 1);
-          // the load that filled this slot was issued 4 sub-steps ago; kWaitSlot loads have been issued since
-          asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWaitSlot) : "memory");
-          a_write(WST, p, stg[WST * NA + p]);
-          stg[WST * NA + p] = a_load(wT + 2, p, CROSS);
+        if constexpr (LATE && S == 1) {
+          // side work of sub-step 1, rows 2..7 (NJ = 8, or 7 with the 224-wide tile: nothing sits at j = 7 but
+          // the reload of the row's own A fragment, which goes with the row's last MFMA)
+          if (i == 1 && j == NJ - 1) step_barrier();
+          if (i >= 2 && i < 6 && (j == 1 || j == 5) && 2 * (i - 2) + (j == 5) < NJ)
+            fb[NXT][2 * (i - 2) + (j == 5)] = lds_read(pb + (2 * (i - 2) + (j == 5)) * 16 * kRow);
+          if (i == 2 && j == 4) fa[0] = lds_read(pa);
+          if (i == 3 && j == 4) fa[1] = lds_read(pa + 16 * kRow);
+          if (i >= 2 && j == NJ - 1) fa[i] = lds_read(pa + i * 16 * kRow);
+          // four B loads and four staged A pieces
+          if (i == 2 && j == 2) b_load(bT, 0, bslot, CROSS);
+          if (i == 4 && j == 2) b_load(bT, 1, bslot, CROSS);
+          if (i == 6 && j == 2) b_load(bT, 2, bslot, CROSS);
+          if (i == 6 && j == 5) b_load(bT, 3, bslot, CROSS);
+          if (i == 2 && j == 6) a_stage(0);
+          if (i == 3 && j == 6) a_stage(1);
+          if (i == 5 && j == 2) a_stage(2);
+          if (i == 7 && j == 2) a_stage(3);
+        } else {
+          // (with 4 rows the reads sit earlier in the row: the last fragment is needed 9 MFMAs after row 3 ends)
+          constexpr int jb0 = MR == 8 ? 1 : 0, jb1 = MR == 8 ? 5 : 3;
+          if (i < 4 && (j == jb0 || j == jb1) && 2 * i + (j == jb1) < NJ)
+            fb[NXT][2 * i + (j == jb1)] = lds_read(pb + (2 * i + (j == jb1)) * 16 * kRow);
+          if (j == NJ - 1) fa[i] = lds_read(pa + i * 16 * kRow);
+          // four B loads per sub-step: after MFMA j = 2 of the even rows (8 rows), or of every row (4 rows)
+          if (MR == 8 ? ((i & 1) == 0 && j == 2) : j == 2) b_load(bT, (S == 0 ? 4 : 0) + (MR == 8 ? i >> 1 : i), bslot, CROSS);
+          // HA staged A pieces per sub-step: after MFMA j = 2 (8 rows) or j = 6 (4 rows) of the odd rows
+          if ((i & 1) == 1 && j == (MR == 8 ? 2 : 6)) a_stage((S == 0 ? HA : 0) + (i >> 1));
         }
         __builtin_amdgcn_sched_barrier(0);
       }
     }
-    if (S == 0) {
-      // Own reads of step kt and own writes of step kt+1 are complete, and so are own B loads of step
-      // kt+1 (the 17 younger loads may still be in flight).  After the barrier step kt+1 is readable
-      // by every wave and nobody reads step kt any more.
-      asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kWaitStep) : "memory");
-      wg_barrier();
-    }
+    if (S == 0 && !LATE) step_barrier();
   };
   auto step = [&](auto par_c, auto cross_c, int kt) __attribute__((always_inline)) {
     substep(par_c, I0{}, cross_c, kt);
