@@ -205,8 +205,13 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 // is handled like a group's last tile; what N leaves over: the B descriptor of a tile in the last column ends
 // after the rows that exist (the others load as zero), and a lane whose 8 columns lie past N stores at an
 // offset no buffer reaches, which drops the store.
-template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false>
+//
+// ADIR: A goes from HBM straight into LDS like B (no staging registers, no ds_write): its two LDS blocks allow a
+// load distance of one K-step -- the pieces of step kt + 2 are issued right after the barrier of step kt has
+// freed the block step kt occupied, and have to have landed at the barrier of step kt + 1.
+template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false, bool ADIR = (MR == 8)>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
+  static_assert(!ADIR || MR == 8, "direct A loads are scheduled for 256-row tiles");
   static_assert(!RAGGED || (GROUPED && !GATED && NB == 256), "ragged edges are handled by the grouped 256-wide kernel");
   static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
   static_assert(MR == 8 || (MR == 4 && GROUPED), "128-row tiles exist for the grouped kernel");
@@ -214,7 +219,9 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   constexpr int NA = MR;                                           // A pieces (8 rows x 128 bytes) per wave and K-step
   constexpr int HA = NA / 2;                                       // ... per sub-step
   constexpr int kWaitSlot = MR == 8 ? 31 : 23;                     // loads issued after the one that filled a staging slot, two K-steps later
-  constexpr int kWaitStep = MR == 8 ? 17 : 13;                     // loads issued after the last B load of the next K-step, at the barrier
+  // loads issued after the last load of the next K-step's operands, at the barrier (ADIR: the last A piece of step
+  // kt + 1 is followed by 4 B loads of its sub-step and the 4 of the next sub-step)
+  constexpr int kWaitStep = ADIR ? 8 : (MR == 8 ? 17 : 13);
   constexpr int NJ = NB / 32;                                      // fragments per wave along N
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
   const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
@@ -328,6 +335,11 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   };
   auto a_write = [&](int stage, int i, u32x4 v) __attribute__((always_inline)) {
     *(__attribute__((address_space(3))) u32x4*)(a_wr + stage * kBlk + i * 4096) = v;
+  };
+  auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // ADIR: piece i of step T into the A block of its parity
+    const bool nx = cross && T >= nk;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16,
+                                             a_voff_x, i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep, 0, 0);
   };
   auto a_direct = [&](int T, int i, int stage) {                   // prologue only
     __builtin_amdgcn_raw_ptr_buffer_load_lds(cur.ra, (lds_ptr)(lds3 + stage * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
@@ -516,15 +528,21 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
           if (i == 2 && j == 4) fa[0] = lds_read(pa);
           if (i == 3 && j == 4) fa[1] = lds_read(pa + 16 * kRow);
           if (i >= 2 && j == NJ - 1) fa[i] = lds_read(pa + i * 16 * kRow);
-          // four B loads and four staged A pieces
-          if (i == 2 && j == 2) b_load(bT, 0, bslot, CROSS);
-          if (i == 4 && j == 2) b_load(bT, 1, bslot, CROSS);
-          if (i == 6 && j == 2) b_load(bT, 2, bslot, CROSS);
-          if (i == 6 && j == 5) b_load(bT, 3, bslot, CROSS);
-          if (i == 2 && j == 6) a_stage(0);
-          if (i == 3 && j == 6) a_stage(1);
-          if (i == 5 && j == 2) a_stage(2);
-          if (i == 7 && j == 2) a_stage(3);
+          if constexpr (ADIR) {
+            // the 8 A pieces of step kt + 2 first (they have one K-step to land), then four B loads
+            if (i >= 2 && i < 6 && (j == 2 || j == 6)) a_dload(kt + 2, 2 * (i - 2) + (j == 6), CROSS);
+            if (i >= 6 && (j == 2 || j == 6)) b_load(bT, 2 * (i - 6) + (j == 6), bslot, CROSS);
+          } else {
+            // four B loads and four staged A pieces
+            if (i == 2 && j == 2) b_load(bT, 0, bslot, CROSS);
+            if (i == 4 && j == 2) b_load(bT, 1, bslot, CROSS);
+            if (i == 6 && j == 2) b_load(bT, 2, bslot, CROSS);
+            if (i == 6 && j == 5) b_load(bT, 3, bslot, CROSS);
+            if (i == 2 && j == 6) a_stage(0);
+            if (i == 3 && j == 6) a_stage(1);
+            if (i == 5 && j == 2) a_stage(2);
+            if (i == 7 && j == 2) a_stage(3);
+          }
         } else {
           // (with 4 rows the reads sit earlier in the row: the last fragment is needed 9 MFMAs after row 3 ends)
           constexpr int jb0 = MR == 8 ? 1 : 0, jb1 = MR == 8 ? 5 : 3;
@@ -534,7 +552,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
           // four B loads per sub-step: after MFMA j = 2 of the even rows (8 rows), or of every row (4 rows)
           if (MR == 8 ? ((i & 1) == 0 && j == 2) : j == 2) b_load(bT, (S == 0 ? 4 : 0) + (MR == 8 ? i >> 1 : i), bslot, CROSS);
           // HA staged A pieces per sub-step: after MFMA j = 2 (8 rows) or j = 6 (4 rows) of the odd rows
-          if ((i & 1) == 1 && j == (MR == 8 ? 2 : 6)) a_stage((S == 0 ? HA : 0) + (i >> 1));
+          if (!ADIR && (i & 1) == 1 && j == (MR == 8 ? 2 : 6)) a_stage((S == 0 ? HA : 0) + (i >> 1));
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -553,21 +571,26 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   //      the order the loop consumes them, so that the counted waits of the first steps hold as well.
 #pragma unroll
   for (int i = 0; i < NA; ++i) a_direct(0, i, 0);
-  if (nk > 1) {
+  if constexpr (ADIR) {
 #pragma unroll
-    for (int i = 0; i < HA; ++i) a_direct(1, i, 1);
-  } else {                                                         // a single K-step per tile: step 1 belongs to the next tile
+    for (int i = 0; i < NA; ++i) a_dload(1, i, true);              // (a single K-step per tile: step 1 is the next tile's step 0)
+  } else {
+    if (nk > 1) {
 #pragma unroll
-    for (int i = 0; i < HA; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(nxt.ra, (lds_ptr)(lds3 + kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                               i * a_piece + kcol(0, nxt.rot) * a_kstep, 0, 0);
+      for (int i = 0; i < HA; ++i) a_direct(1, i, 1);
+    } else {                                                       // a single K-step per tile: step 1 belongs to the next tile
+#pragma unroll
+      for (int i = 0; i < HA; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(nxt.ra, (lds_ptr)(lds3 + kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
+                                                 i * a_piece + kcol(0, nxt.rot) * a_kstep, 0, 0);
+    }
+#pragma unroll
+    for (int i = HA; i < NA; ++i) stg[NA + i] = a_load(1, i, true);
+#pragma unroll
+    for (int i = 0; i < NA; ++i) stg[i] = a_load(2, i, true);
+#pragma unroll
+    for (int i = 0; i < HA; ++i) stg[NA + i] = a_load(3, i, true);
   }
-#pragma unroll
-  for (int i = HA; i < NA; ++i) stg[NA + i] = a_load(1, i, true);
-#pragma unroll
-  for (int i = 0; i < NA; ++i) stg[i] = a_load(2, i, true);
-#pragma unroll
-  for (int i = 0; i < HA; ++i) stg[NA + i] = a_load(3, i, true);
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
 #pragma unroll

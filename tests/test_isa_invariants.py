@@ -56,18 +56,18 @@ def k_loops(lines):
 
 
 # (source, kernel, counted waits, accumulators in AGPRs, asm-issued global loads allowed in a loop)
-CASES = [("kernels_gemm_bf16.hip", "gemm_bf16_256_kernel", {31, 17}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_bf16_256x224_kernel", {31, 17}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_bf16_256_grouped_kernel", {31, 17}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_bf16_256_blocked_kernel", {31, 17}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_bf16_256_grouped_gated_kernel", {31, 17}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_bf16_256_ragged_kernel", {31, 17}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_f16_256_ragged_kernel", {31, 17}, True, 0),
+CASES = [("kernels_gemm_bf16.hip", "gemm_bf16_256_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_bf16_256x224_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_bf16_256_grouped_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_bf16_256_blocked_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_bf16_256_grouped_gated_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_bf16_256_ragged_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_f16_256_ragged_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_128_grouped_kernel", {23, 13}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_128_grouped_gated_kernel", {23, 13}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_f16_256_kernel", {31, 17}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_f16_256_grouped_kernel", {31, 17}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_f16_256_grouped_gated_kernel", {31, 17}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_f16_256_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_f16_256_grouped_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_f16_256_grouped_gated_kernel", {8}, True, 0),
          ("kernels_gemm_fp8_e8m0.hip", "gemm_fp8_e8m0_256_kernel", {31, 17}, True, 0),
          # the fp32-scale kernel prefetches the next tile's two scale words with asm-issued loads of its own
          ("kernels_gemm_fp8.hip", "gemm_fp8_256_kernel", {4}, False, 2)]
