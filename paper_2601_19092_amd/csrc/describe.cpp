@@ -74,19 +74,13 @@ int g2l_threads(const Geo& g, bool is_b, Builder& b) {
   std::vector<axe_iter_t> rows, ks;
   if (g.big) {
     // one wave instruction = 1 KiB = 8 rows of 128 bytes; wave w of NW takes row groups w, w + NW, ...:
-    // row = (NW i + w) * 8 + lr, chunk c.  A operand that travels through registers (A of the fp8 kernel on
-    // the scale path: lane = 8 lr + c, piece i in registers CE i .. CE i + CE - 1) is swizzled by the LDS write.
-    // The others are loaded straight into LDS, which such a load fills linearly in the lane id, so
-    // the swizzle shows up in which chunk a lane fetches: c ^ key(row), key = (4 (w & 1) + (lr >> 1)) & 7.
-    // That key spans the wave id, so those maps are stated on the thread id t = 64 w + lane, folded
-    // into the lane axis: key = (t >> 4) & 7.
+    // row = (NW i + w) * 8 + lr, chunk c.  Both operands are loaded straight into LDS, which such a load fills
+    // linearly in the lane id, so the swizzle shows up in which chunk a lane fetches: c ^ key(row),
+    // key = (4 (w & 1) + (lr >> 1)) & 7.  That key spans the wave id, so the maps are stated on the thread id
+    // t = 64 w + lane, folded into the lane axis: key = (t >> 4) & 7.
     const int NW = g.WM * g.WN, NI = (is_b ? g.TN : g.T) / (8 * NW);
-    if (!is_b && g.mx) {
-      rows = {{NI, g.CE, REG}, {NW, 1, WAVE}, {8, CH, LANE}};
-    } else {
-      rows = {{NI, g.CE, REG}, {NW, 64, LANE}, {8, CH, LANE}};
-      b.swz(LANE, ilog2(CH), 0, ilog2(CH) + g.key_shift);
-    }
+    rows = {{NI, g.CE, REG}, {NW, 64, LANE}, {8, CH, LANE}};
+    b.swz(LANE, ilog2(CH), 0, ilog2(CH) + g.key_shift);
     ks = {{CH, 1, LANE}, {g.CE, 1, REG}};
   } else {
     // thread t fetches chunk t (+ 256 p): row = 32 p' ..., see kernels_gemm_small.hip

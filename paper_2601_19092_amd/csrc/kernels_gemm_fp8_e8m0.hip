@@ -6,8 +6,8 @@
 //
 // Structure and measured reasons are those of the bf16 kernel (kernels_gemm_bf16.hip): workgroup tile
 // 256 x 256, one workgroup of 4 waves per CU, wave tile 128 x 128 = 8 x 8 fragments in 256 AGPRs, five
-// 32 KiB LDS blocks (A double-buffered and staged through registers two K-steps ahead, B direct to
-// LDS through a ring of three), K rotation, tiles of a workgroup chained, direct paired stores.
+// 32 KiB LDS blocks (both operands direct to LDS: A into two blocks, one K-step ahead, B through a ring of
+// three), K rotation, tiles of a workgroup chained, direct paired stores.
 // What differs:
 //   K-step      : 128 elements = one LDS row = ONE MFMA per fragment (32 cycles); a K-step is 64 MFMAs,
 //                 split in two halves by fragment rows (rows 0..3, rows 4..7), with the barrier
@@ -70,8 +70,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
   // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ... (cur and nxt, see the bf16 kernel)
   const int a_pitch = (int)g.lda, b_pitch = (int)g.ldb;            // bytes
   struct Tile {
-    __amdgpu_buffer_rsrc_t rb;
-    i32x4 ra_words;                                                // A's descriptor as the four SGPR words an asm statement takes
+    __amdgpu_buffer_rsrc_t ra, rb;
     const uint8_t *sa, *sb;                                        // E8M0 codes of this wave's row block and column block, one per K-tile
     int rot;
   };
@@ -83,12 +82,13 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * kTile * g.ldb), 0,
                                                255 * b_pitch + (int)g.K, 0x00020000);
       t.rot = (tm + tn) & (kRot - 1);                              // K rotation
-      t.ra_words = raw_rsrc((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda, (uint32_t)(255 * a_pitch + (int)g.K));
+      t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda), 0,
+                                               255 * a_pitch + (int)g.K, 0x00020000);
       t.sa = (const uint8_t*)g.scale_a + (int64_t)(2 * tm + wm) * g.nkb;
       t.sb = (const uint8_t*)g.scale_b + (int64_t)(2 * tn + wn) * g.nkb;
     } else {                                                       // no such tile: every load returns zero
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
-      t.ra_words = raw_rsrc(g.A, 0);
+      t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
       t.sa = (const uint8_t*)g.scale_a, t.sb = (const uint8_t*)g.scale_b;   // valid addresses; the codes are never used
       t.rot = 0;
     }
@@ -103,10 +103,8 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
   //      needs two codes.  A register per operand holds the codes of 64 consecutive K-steps of the
   //      walk, one per lane; v_readlane hands out one per step.  The registers for the NEXT 64 steps
   //      (of this tile, or the first of the next tile) are fetched when a block of 64 steps begins and
-  //      taken over when it ends.  These are ordinary loads: the compiler waits for them (for everything
-  //      outstanding, in fact) before the first use, once per 64 K-steps or per tile -- a register that
-  //      an asm-issued load is still filling must not live through a region where the register
-  //      allocator may decide to spill it.
+  //      taken over when it ends.  These are ordinary loads: the compiler waits for them before the first
+  //      use, once per 64 K-steps or per tile.
   uint32_t cva = 127u, cvb = 127u, nva = 127u, nvb = 127u;        // this block's and the next block's codes, lane = step % 64
   auto fetch_codes = [&](const Tile& t, int base, uint32_t& oa, uint32_t& ob) __attribute__((always_inline)) {
     if (!scaled) return;
@@ -117,39 +115,18 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
   };
   auto lane_value = [](uint32_t val, int l) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)val, l); };
 
-  // ---- HBM -> LDS / VGPR (as in the bf16 kernel; pitches and columns in bytes = elements)
+  // ---- HBM -> LDS, both operands directly (as in the bf16 kernel; pitches and columns in bytes = elements): a wave
+  //      instruction fills 8 rows x 128 bytes linearly in the lane id, so the XOR of the LDS image is applied to
+  //      the chunk a lane fetches.  A has two blocks (the steps of either parity), B a ring of three.
   const int lr = lane >> 3, lp = lane & 7;
   const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 4 i) * 8 + lr
-  const int a_voff = (w * 8 + lr) * a_pitch + lp * 16;
   const int a_voff_x = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
   const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
   const int a_piece = 32 * a_pitch, b_piece = 32 * b_pitch;        // bytes between pieces
-  const lds_u8 a_wr = lds3 + (w * 8 + lr) * kRow + ((lp ^ lkey) << 4);    // + stage * kBlk + i * 4096
-
-  u32x4 stg[16];                                                   // A staging: slot (T & 1) * 8 + i
-  auto a_load = [&](int T, int i, bool cross) __attribute__((always_inline)) -> u32x4 {
+  auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
-    const i32x4 r = nx ? nxt.ra_words : cur.ra_words;
-    const int soff = __builtin_amdgcn_readfirstlane(i * a_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow);
-    u32x4 val;
-    asm volatile("s_nop 4\n\tbuffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(val) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
-    return val;
-  };
-  auto a_write = [&](int stage, int i, u32x4 val) __attribute__((always_inline)) {
-    *(__attribute__((address_space(3))) u32x4*)(a_wr + stage * kBlk + i * 4096) = val;
-  };
-  // prologue only: A straight into LDS, through descriptors that live only there
-  auto a_rsrc = [&](int vv) __attribute__((always_inline)) -> __amdgpu_buffer_rsrc_t {
-    if (vv >= ntiles) return __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
-    int tm, tn;
-    tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
-    return __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda), 0, 255 * a_pitch + (int)g.K,
-                                             0x00020000);
-  };
-  const __amdgpu_buffer_rsrc_t ra_first = a_rsrc(v);
-  auto a_direct = [&](int T, int i, int stage) {
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(ra_first, (lds_ptr)(lds3 + stage * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                             i * a_piece + ktile(T, cur.rot) * kRow, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
+                                             i * a_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
   };
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;     // B ring: blocks of K-steps kt, kt+1, kt+2
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
@@ -209,16 +186,15 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
   using I1 = std::integral_constant<int, 1>;
 
   // Half H of K-step kt (PAR = kt & 1), in exact program order: fragment rows 4 H .. 4 H + 3, two rows at a
-  // time with j innermost: MFMAs (r, j), (r + 1, j).  After MFMAs 2, 10, 18, 26 one B load, after MFMAs
-  // 6, 14, 22, 30 one staged A piece goes to LDS and its slot is reloaded (pieces, steps and blocks as in
-  // the bf16 kernel).  The second half also reads the 16 fragments of step kt+1, each right after the
+  // time with j innermost: MFMAs (r, j), (r + 1, j).  Loads: in the first half pieces 4..7 of B of step kt + 2
+  // (after MFMAs 2, 10, 18, 26); in the second half, after the barrier has freed what step kt occupied, the 8
+  // pieces of A of step kt + 2 (after MFMAs 0, 2, .., 14: they have one K-step to land) and pieces 0..3 of B of
+  // step kt + 3 (after MFMAs 18, 22, 26, 30).  The second half also reads the 16 fragments of step kt+1, each right after the
   // last MFMA that uses the register it goes to: A fragments 0..3 during rows 4, 5; A fragments 4, 5
   // and, after MFMA (7, j), B fragment j during rows 6, 7; A fragments 6, 7 at the end.
   auto half = [&](auto par_c, auto h_c, auto cross_c, int kt, uint32_t va, uint32_t vb) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value, H = decltype(h_c)::value;
     constexpr bool CROSS = decltype(cross_c)::value != 0;
-    constexpr int WST = H == 0 ? PAR ^ 1 : PAR;
-    const int wT = H == 0 ? kt + 1 : kt + 2;
     const int bT = H == 0 ? kt + 2 : kt + 3;
     const int bslot = H == 0 ? bo2 : bo0;
     constexpr int pa = (PAR ^ 1) * kBlk;                           // step kt+1: A stage, B ring block
@@ -238,21 +214,19 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
           fa[7] = read_a(7, pa);
         }
       }
-      if ((q & 7) == 2) b_load(bT, (H == 0 ? 4 : 0) + (q >> 3), bslot, CROSS);
-      if ((q & 7) == 6) {
-        const int p = (H == 0 ? 4 : 0) + (q >> 3);
-        // the load that filled this slot was issued 4 halves ago; 31 loads have been issued since
-        asm volatile("s_waitcnt vmcnt(31)" ::: "memory");
-        a_write(WST, p, stg[WST * 8 + p]);
-        stg[WST * 8 + p] = a_load(wT + 2, p, CROSS);
+      if (H == 0) {
+        if ((q & 7) == 2) b_load(bT, 4 + (q >> 3), bslot, CROSS);
+      } else {
+        if (q < 16 && (q & 1) == 0) a_dload(kt + 2, q >> 1, CROSS);
+        if (q >= 16 && (q & 3) == 2) b_load(bT, (q - 16) >> 2, bslot, CROSS);
       }
       __builtin_amdgcn_sched_barrier(0);
     }
     if (H == 0) {
-      // Own writes of step kt+1 are complete, and so are own B loads of step kt+1 (the 17 younger loads may
-      // still be in flight); nobody has read LDS since the last barrier's second half.  After the barrier
-      // step kt+1 is readable by every wave and the blocks of step kt are free.
-      asm volatile("s_waitcnt vmcnt(17) lgkmcnt(0)" ::: "memory");
+      // Own loads of step kt+1 are complete (its last A piece was followed by 8 B loads, which may still be in
+      // flight); nobody has read LDS since the last barrier's second half.  After the barrier step kt+1 is
+      // readable by every wave and the blocks of step kt are free.
+      asm volatile("s_waitcnt vmcnt(8) lgkmcnt(0)" ::: "memory");
       wg_barrier();
     }
   };
@@ -267,24 +241,11 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
     bo0 = bo1, bo1 = bo2, bo2 = t;
   };
 
-  // ---- prologue (first tile only), as in the bf16 kernel
+  // ---- prologue (first tile only): steps 0 and 1 of A, steps 0, 1 and half of 2 of B
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a_direct(0, i, 0);
-  if (nk > 1) {
+  for (int i = 0; i < 8; ++i) a_dload(0, i, true);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) a_direct(1, i, 1);
-  } else {                                                         // a single K-step per tile: step 1 belongs to the next tile
-#pragma unroll
-    for (int i = 0; i < 4; ++i)
-      __builtin_amdgcn_raw_ptr_buffer_load_lds(a_rsrc(v + (int)gridDim.x), (lds_ptr)(lds3 + kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                               i * a_piece + ktile(0, nxt.rot) * kRow, 0, 0);
-  }
-#pragma unroll
-  for (int i = 4; i < 8; ++i) stg[8 + i] = a_load(1, i, true);
-#pragma unroll
-  for (int i = 0; i < 8; ++i) stg[i] = a_load(2, i, true);
-#pragma unroll
-  for (int i = 0; i < 4; ++i) stg[8 + i] = a_load(3, i, true);
+  for (int i = 0; i < 8; ++i) a_dload(1, i, true);                 // (a single K-step per tile: step 1 is the next tile's step 0)
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
 #pragma unroll

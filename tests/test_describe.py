@@ -58,7 +58,7 @@ GEO = {"small_bf16": dict(T=64, TN=64, BK=32, EB=2, waves=4, wn=2), "small_fp8":
        "big_fp8_mx": dict(T=256, TN=256, BK=128, EB=1, waves=4, wn=2)}
 KINDS = ["small_bf16", "small_fp8", "big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx"]
 BIG = ("big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx")
-A_VIA_REGISTERS = ("big_fp8_mx",)                                   # A staged through VGPRs and written with ds_write
+A_VIA_REGISTERS = ()                                                # (no kernel stages A through VGPRs and ds_write any more)
 PAIRED_STORES = ("big_bf16", "big_fp8_mx")
 TILE = {"small_bf16": B.AXE_TILE_64x64x32, "small_fp8": B.AXE_TILE_64x64x32, "big_bf16": B.AXE_TILE_256x256x64,
         "big_fp8": B.AXE_TILE_256x256x64, "big_bf16_n224": B.AXE_TILE_256x224x64, "big_fp8_mx": B.AXE_TILE_256x256x64}
