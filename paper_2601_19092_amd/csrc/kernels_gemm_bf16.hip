@@ -19,13 +19,13 @@
 //    sees isolated 128-byte reads scattered over rows 16 KiB apart.  Hence the K rotation below.
 //
 // Tile movements, each an Axe layout (reported by axe_gemm_describe):
-//   HBM -> LDS/VGPR : one wave instruction covers 8 rows x 128 bytes (lane = 8 * row + chunk).
+//   HBM -> LDS  : one wave instruction covers 8 rows x 128 bytes (lane = 8 * row + chunk), direct to LDS.
 //   LDS layout  : five 32 KiB blocks (one operand, one K-tile each): A double-buffered in blocks 0, 1,
 //                 B in a ring of blocks 2, 3, 4.  Rows of 128 bytes (64 bf16); 16-byte chunk c of row r
 //                 sits at chunk position c ^ key(r), key(r) = (r >> 1) & 7.  With 64 banks of 4 bytes, 16
 //                 consecutive rows reading the same logical chunk touch 16 distinct 16-byte bank groups.
-//                 A direct-to-LDS load writes LDS linearly in the lane id, so for B the XOR is applied
-//                 on the global side (lane (r, p) fetches chunk p ^ key(r)); for A on the ds_write address.
+//                 A direct-to-LDS load writes LDS linearly in the lane id, so the XOR is applied on the
+//                 global side (lane (r, p) fetches chunk p ^ key(r)).
 //   LDS -> VGPR : ds_read_b128; lane l reads row l % 16 of a fragment, K chunk 4 * s + l / 16: the MFMA
 //                 16x16x32 operand layout (8 consecutive k per lane).
 //   MFMA        : operands swapped (B fragment first) so that a lane's accumulator fragment holds 4
@@ -36,16 +36,14 @@
 //                 row; L2 merges them).  The 224-wide tile stores fragment by fragment, 8 bytes per lane.
 //
 // Schedule.  A K-step is two sub-steps of 64 MFMAs; a sub-step also reads the 16 fragments of the
-// next sub-step and moves 4 pieces of each operand.  One workgroup barrier per K-step, after sub-step
-// 0: by then every LDS read of step kt has completed, and the barrier publishes step kt+1.  With one
-// wave per SIMD nothing hides a late load, and a memory system that busy answers late (a wave's
-// loads of one K-tile complete 1500 - 2300 cycles after issue), so every load gets at least a full
-// K-step (2048 MFMA cycles), most of them one and a half to two.  160 KiB of LDS hold five 32 KiB
-// blocks, not the six that such a prefetch of both operands through LDS would take, so the
-// operands travel differently:
-//   B: buffer_load ... lds (direct to LDS) into the ring of three blocks, 1 to 1.5 K-steps ahead;
-//   A: buffer_load into 16 x 4 staging registers per lane two K-steps ahead, ds_write_b128 into the
-//      double-buffered block half a K-step to one K-step ahead of use.
+// next sub-step.  One workgroup barrier per K-step, early in sub-step 1: every LDS read of step kt has
+// completed by then, and the barrier publishes step kt+1.  With one wave per SIMD nothing hides a late
+// load, and a memory system that busy answers late (a wave's loads of one K-tile complete 1500 - 2300
+// cycles after issue, a K-step takes about 2900).  160 KiB of LDS hold five 32 KiB blocks:
+//   B: buffer_load ... lds (direct to LDS) into a ring of three blocks, 1 to 1.5 K-steps ahead;
+//   A: buffer_load ... lds into the block of its step's parity, right after the barrier that frees it:
+//      one K-step ahead.  (An earlier version gave A two K-steps by staging it through registers and
+//      ds_write_b128; the writes cost more than the distance was worth: without them 8192^3 runs 7 % faster.)
 //
 // Tile width.  The same kernel body exists with 224 instead of 256 columns of C per tile (7 instead
 // of 8 fragments per wave along N): M = 4096, N = 3584 makes 16 x 16 such tiles, one per CU, where
@@ -198,30 +196,23 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 // tile is then 128 rows x 256 columns, a wave owns 64 x 128 of it, a K-step is 2 x 32 MFMAs per wave instead of
 // 2 x 64 and moves half as much of A (4 pieces per wave and K-step), so that the weights stream past twice as
 // fast -- with few rows per group the time is that of reading B from HBM.  The A blocks in LDS keep their
-// places (half of each is used); loads per K-step 12 instead of 16, hence other wait counts.
+// places (half of each is used); loads per K-step 12 instead of 16 (the wait count at the barrier is the same).
 //
 // RAGGED: a dense GEMM whose M is no multiple of the tile height and whose N is no multiple of 256 (but of 8:
 // a lane stores 8 columns at once), run as a grouped one with a single group of all rows.  What M leaves over
 // is handled like a group's last tile; what N leaves over: the B descriptor of a tile in the last column ends
 // after the rows that exist (the others load as zero), and a lane whose 8 columns lie past N stores at an
 // offset no buffer reaches, which drops the store.
-//
-// ADIR: A goes from HBM straight into LDS like B (no staging registers, no ds_write): its two LDS blocks allow a
-// load distance of one K-step -- the pieces of step kt + 2 are issued right after the barrier of step kt has
-// freed the block step kt occupied, and have to have landed at the barrier of step kt + 1.
-template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false, bool ADIR = (MR == 8)>
+template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
-  static_assert(!ADIR || MR == 8, "direct A loads are scheduled for 256-row tiles");
   static_assert(!RAGGED || (GROUPED && !GATED && NB == 256), "ragged edges are handled by the grouped 256-wide kernel");
   static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
   static_assert(MR == 8 || (MR == 4 && GROUPED), "128-row tiles exist for the grouped kernel");
   constexpr int TM = 32 * MR;                                      // rows of a tile
   constexpr int NA = MR;                                           // A pieces (8 rows x 128 bytes) per wave and K-step
-  constexpr int HA = NA / 2;                                       // ... per sub-step
-  constexpr int kWaitSlot = MR == 8 ? 31 : 23;                     // loads issued after the one that filled a staging slot, two K-steps later
-  // loads issued after the last load of the next K-step's operands, at the barrier (ADIR: the last A piece of step
-  // kt + 1 is followed by 4 B loads of its sub-step and the 4 of the next sub-step)
-  constexpr int kWaitStep = ADIR ? 8 : (MR == 8 ? 17 : 13);
+  // loads issued after the last load of the next K-step's operands, at the barrier: the last A piece of step
+  // kt + 1 is followed by 4 B loads of its sub-step and the 4 of the next sub-step
+  constexpr int kWaitStep = 8;
   constexpr int NJ = NB / 32;                                      // fragments per wave along N
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
   const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
@@ -255,7 +246,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   };
   struct Tile {
     __amdgpu_buffer_rsrc_t ra, rb;
-    i32x4 ra_words;                                                // ra once more, as the four SGPR words an asm statement takes
     int rot;
   };
   int tb_row0 = 0, tb_desc = 0;                                    // grouped: lane t = the workgroup's t-th tile
@@ -276,7 +266,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
         t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + ((int64_t)grp * g.ldg + b_tile_off(tn)) * 2), 0,
                                                  (nb - 1) * b_pitch + b_span, 0x00020000);
         t.rot = ((row0 >> 8) + tn) & (kRot - 1);
-        t.ra_words = raw_rsrc(pa, (uint32_t)((rows - 1) * a_pitch + a_span));
         return t;
       }
     }
@@ -290,11 +279,9 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
       // lines of a row at once -- one 1 KiB burst per row -- and find the other lines in L2 during the
       // rest of the window (measured on the bare load stream: 16 -> 21.5 TB/s).
       t.rot = (tm + tn) & (kRot - 1);
-      t.ra_words = raw_rsrc((const uint8_t*)g.A + a_tile_off(tm) * 2, (uint32_t)(255 * a_pitch + a_span));
     } else {                                                       // no such tile: every load returns zero
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
-      t.ra_words = raw_rsrc(g.A, 0);
       t.rot = 0;
     }
     return t;
@@ -314,36 +301,19 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   //      piece go into the scalar offset.
   const int lr = lane >> 3, lp = lane & 7;
   const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 4 i) * 8 + lr
-  const int a_voff = (w * 8 + lr) * a_pitch + lp * 16;
   const int a_voff_x = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
   const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
   const int a_piece = 32 * a_pitch, b_piece = 32 * b_pitch;        // bytes between pieces
-  const lds_u8 a_wr = lds3 + (w * 8 + lr) * kRow + ((lp ^ lkey) << 4);    // + stage * kBlk + i * 4096
-
-  u32x4 stg[2 * NA];                                               // A staging: slot (T & 1) * NA + i
-  // cross = false: the caller knows T < nk (steady part of the K loop), nothing of the next tile is looked at
-  // The staging loads are asm statements: the compiler then keeps no wait-count bookkeeping for them
-  // (what it keeps is merged conservatively over all paths into a loop and comes out as waits for
-  // loads issued one K-step ago); the counted waits in the sub-steps are the only ones.
-  auto a_load = [&](int T, int i, bool cross) __attribute__((always_inline)) -> u32x4 {
-    const bool nx = cross && T >= nk;
-    const i32x4 r = nx ? nxt.ra_words : cur.ra_words;
-    const int soff = __builtin_amdgcn_readfirstlane(i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep);
-    u32x4 v;
-    asm volatile("buffer_load_dwordx4 %0, %1, %2, %3 offen" : "=v"(v) : "v"(a_voff), "s"(r), "s"(soff) : "memory");
-    return v;
-  };
-  auto a_write = [&](int stage, int i, u32x4 v) __attribute__((always_inline)) {
-    *(__attribute__((address_space(3))) u32x4*)(a_wr + stage * kBlk + i * 4096) = v;
-  };
-  auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // ADIR: piece i of step T into the A block of its parity
+  // Both operands go from HBM straight into LDS (no staging registers, no ds_write: a ds_write_b128 keeps its
+  // wave from issuing for about 20 cycles, and 8 of them per K-step cost 7 % of the whole kernel).  A direct
+  // load fills 1 KiB of LDS linearly in the lane id, so the XOR of the LDS image is applied to the chunk a
+  // lane fetches.  A has two blocks (the steps of either parity): the pieces of step kt + 2 are issued right
+  // after the barrier of step kt has freed the block step kt occupied, and have to have landed at the barrier
+  // of step kt + 1 -- a load distance of one K-step.  B has a ring of three blocks.
+  auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16,
                                              a_voff_x, i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep, 0, 0);
-  };
-  auto a_direct = [&](int T, int i, int stage) {                   // prologue only
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(cur.ra, (lds_ptr)(lds3 + stage * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                             i * a_piece + kcol(T, cur.rot) * a_kstep, 0, 0);
   };
   // B ring: byte offsets of the blocks that hold K-steps kt, kt+1, kt+2 (step kt+3 reuses the first)
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
@@ -476,9 +446,10 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   // Sub-step S of K-step kt (PAR = kt & 1), in exact program order (sched_barrier(0) forbids any
   // reordering across it): 8 x NJ MFMAs, (i, j) with j innermost; in rows 0..3 the B fragments of the
   // next sub-step are read into the other buffer (after MFMAs j = 1 and j = 5), and after each row i
-  // the A fragment i of the next sub-step replaces the one just used; after MFMA j = 2 of the even
-  // rows one B load, of the odd rows one staged A piece goes to LDS and its slot is reloaded.  Steps past the end of the
-  // tile are steps of the workgroup's next tile (or of none: then their loads return zero).
+  // the A fragment i of the next sub-step replaces the one just used; sub-step 0 issues four B loads (after
+  // MFMA j = 2 of the even rows), sub-step 1 the 8 A pieces and four B loads.  Sub-step 1 of the 256-row tile has
+  // its own placement (see LATE below).  Steps past the end of the tile are steps of the workgroup's next tile
+  // (or of none: then their loads return zero).
   auto substep = [&](auto par_c, auto s_c, auto cross_c, int kt) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value, S = decltype(s_c)::value;
     constexpr bool CROSS = decltype(cross_c)::value != 0;          // the loads of this step may belong to the next tile
@@ -487,31 +458,22 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     constexpr int RST = S == 0 ? PAR : PAR ^ 1;                    // A stage of that step
     const lds_u8 pa = fax[NXT] + RST * kBlk;
     const lds_u8 pb = fbx[NXT] + (S == 0 ? bo0 : bo1);
-    // A pieces written now: 4..7 of step kt+1 (sub-step 0) or 0..3 of step kt+2 (sub-step 1); the slot
-    // is reloaded with the same piece two steps later.  B pieces loaded now: 4..7 of step kt+2 into
-    // its ring block (sub-step 0) or 0..3 of step kt+3 into the block step kt has just left (sub-step 1).
-    constexpr int WST = S == 0 ? PAR ^ 1 : PAR;
-    const int wT = S == 0 ? kt + 1 : kt + 2;
+    // B pieces loaded now: 4..7 of step kt+2 into its ring block (sub-step 0) or 0..3 of step kt+3 into the
+    // block step kt has just left (sub-step 1); all A pieces of step kt+2 are loaded in sub-step 1, into the
+    // block step kt has just left.
     const int bT = S == 0 ? kt + 2 : kt + 3;
     const int bslot = S == 0 ? bo2 : bo0;
     // With 256-row tiles the barrier of a K-step does not stand between the two sub-steps but two rows of MFMAs
     // (16 of them, 256 cycles) into sub-step 1: the wave reaches it with the last LDS read of sub-step 0 long
-    // complete and a little more time for its B loads to land, instead of draining the matrix pipe while it waits
-    // for that read.  Everything that needs the barrier -- reads of step kt + 1, writes and loads into what step
-    // kt occupied -- is scheduled into rows 2..7 of sub-step 1; rows 0 and 1 only multiply what is in registers.
+    // complete and a little more time for its loads to land, instead of draining the matrix pipe while it waits
+    // for that read.  Everything that needs the barrier -- reads of step kt + 1, loads into what step kt
+    // occupied -- is scheduled into rows 2..7 of sub-step 1; rows 0 and 1 only multiply what is in registers.
     constexpr bool LATE = MR == 8;
     auto step_barrier = [&]() __attribute__((always_inline)) {
-      // Own reads of step kt and own writes of step kt+1 are complete, and so are own B loads of step
-      // kt+1 (the 17 younger loads may still be in flight).  After the barrier step kt+1 is readable
-      // by every wave and nobody reads step kt any more.
+      // Own reads of step kt are complete, and so are own loads of step kt+1 (the 8 younger loads may still
+      // be in flight).  After the barrier step kt+1 is readable by every wave and nobody reads step kt any more.
       asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)" ::"n"(kWaitStep) : "memory");
       wg_barrier();
-    };
-    auto a_stage = [&](int p) __attribute__((always_inline)) {
-      // the load that filled this slot was issued 4 sub-steps ago; kWaitSlot loads have been issued since
-      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kWaitSlot) : "memory");
-      a_write(WST, p, stg[WST * NA + p]);
-      stg[WST * NA + p] = a_load(wT + 2, p, CROSS);
     };
 #pragma unroll
     for (int i = 0; i < MR; ++i) {
@@ -528,31 +490,22 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
           if (i == 2 && j == 4) fa[0] = lds_read(pa);
           if (i == 3 && j == 4) fa[1] = lds_read(pa + 16 * kRow);
           if (i >= 2 && j == NJ - 1) fa[i] = lds_read(pa + i * 16 * kRow);
-          if constexpr (ADIR) {
-            // the 8 A pieces of step kt + 2 first (they have one K-step to land), then four B loads
-            if (i >= 2 && i < 6 && (j == 2 || j == 6)) a_dload(kt + 2, 2 * (i - 2) + (j == 6), CROSS);
-            if (i >= 6 && (j == 2 || j == 6)) b_load(bT, 2 * (i - 6) + (j == 6), bslot, CROSS);
-          } else {
-            // four B loads and four staged A pieces
-            if (i == 2 && j == 2) b_load(bT, 0, bslot, CROSS);
-            if (i == 4 && j == 2) b_load(bT, 1, bslot, CROSS);
-            if (i == 6 && j == 2) b_load(bT, 2, bslot, CROSS);
-            if (i == 6 && j == 5) b_load(bT, 3, bslot, CROSS);
-            if (i == 2 && j == 6) a_stage(0);
-            if (i == 3 && j == 6) a_stage(1);
-            if (i == 5 && j == 2) a_stage(2);
-            if (i == 7 && j == 2) a_stage(3);
-          }
+          // the 8 A pieces of step kt + 2 first (they have one K-step to land), then four B loads
+          if (i >= 2 && i < 6 && (j == 2 || j == 6)) a_dload(kt + 2, 2 * (i - 2) + (j == 6), CROSS);
+          if (i >= 6 && (j == 2 || j == 6)) b_load(bT, 2 * (i - 6) + (j == 6), bslot, CROSS);
         } else {
           // (with 4 rows the reads sit earlier in the row: the last fragment is needed 9 MFMAs after row 3 ends)
           constexpr int jb0 = MR == 8 ? 1 : 0, jb1 = MR == 8 ? 5 : 3;
           if (i < 4 && (j == jb0 || j == jb1) && 2 * i + (j == jb1) < NJ)
             fb[NXT][2 * i + (j == jb1)] = lds_read(pb + (2 * i + (j == jb1)) * 16 * kRow);
           if (j == NJ - 1) fa[i] = lds_read(pa + i * 16 * kRow);
+          if constexpr (MR == 4 && S == 1) {
+            // 128-row tiles, sub-step 1 (right after the barrier): the 4 A pieces of step kt + 2, then four B loads
+            if (i < 2 && (j == 2 || j == 6)) a_dload(kt + 2, 2 * i + (j == 6), CROSS);
+            if (i >= 2 && (j == 2 || j == 6)) b_load(bT, 2 * (i - 2) + (j == 6), bslot, CROSS);
+          } else
           // four B loads per sub-step: after MFMA j = 2 of the even rows (8 rows), or of every row (4 rows)
           if (MR == 8 ? ((i & 1) == 0 && j == 2) : j == 2) b_load(bT, (S == 0 ? 4 : 0) + (MR == 8 ? i >> 1 : i), bslot, CROSS);
-          // HA staged A pieces per sub-step: after MFMA j = 2 (8 rows) or j = 6 (4 rows) of the odd rows
-          if (!ADIR && (i & 1) == 1 && j == (MR == 8 ? 2 : 6)) a_stage((S == 0 ? HA : 0) + (i >> 1));
         }
         __builtin_amdgcn_sched_barrier(0);
       }
@@ -566,31 +519,12 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     bo0 = bo1, bo1 = bo2, bo2 = t;
   };
 
-  // ---- prologue (first tile only): what the sub-steps before (0, 0) would have done.  Step 0 and
-  //      pieces 0..3 of step 1 of A go straight to LDS; the staging slots are filled oldest first in
-  //      the order the loop consumes them, so that the counted waits of the first steps hold as well.
+  // ---- prologue (first tile only): what the sub-steps before (0, 0) would have done: steps 0 and 1 of A,
+  //      steps 0, 1 and the first half of step 2 of B.
 #pragma unroll
-  for (int i = 0; i < NA; ++i) a_direct(0, i, 0);
-  if constexpr (ADIR) {
+  for (int i = 0; i < NA; ++i) a_dload(0, i, true);
 #pragma unroll
-    for (int i = 0; i < NA; ++i) a_dload(1, i, true);              // (a single K-step per tile: step 1 is the next tile's step 0)
-  } else {
-    if (nk > 1) {
-#pragma unroll
-      for (int i = 0; i < HA; ++i) a_direct(1, i, 1);
-    } else {                                                       // a single K-step per tile: step 1 belongs to the next tile
-#pragma unroll
-      for (int i = 0; i < HA; ++i)
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(nxt.ra, (lds_ptr)(lds3 + kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                                 i * a_piece + kcol(0, nxt.rot) * a_kstep, 0, 0);
-    }
-#pragma unroll
-    for (int i = HA; i < NA; ++i) stg[NA + i] = a_load(1, i, true);
-#pragma unroll
-    for (int i = 0; i < NA; ++i) stg[i] = a_load(2, i, true);
-#pragma unroll
-    for (int i = 0; i < HA; ++i) stg[NA + i] = a_load(3, i, true);
-  }
+  for (int i = 0; i < NA; ++i) a_dload(1, i, true);                // (a single K-step per tile: step 1 is the next tile's step 0)
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
 #pragma unroll
@@ -605,9 +539,9 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   for (int f = 0; f < MR; ++f) fa[f] = lds_read(fax[0] + f * 16 * kRow);
 
   // ---- all K-steps of all tiles of this workgroup, one uninterrupted pipeline.  The host launches
-  //      more than one tile per workgroup only when nk is even (the A stage and staging slots of a
-  //      step are chosen by its parity, which must continue across the tile boundary) and at least 4
-  //      (the load side looks at most one tile ahead).
+  //      more than one tile per workgroup only when nk is even (the A block of a step is chosen by its
+  //      parity, which must continue across the tile boundary) and at least 4 (the load side looks at most
+  //      one tile ahead).
   for (;;) {
     set_output(v);
     int kt = 0;

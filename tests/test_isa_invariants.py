@@ -63,8 +63,8 @@ CASES = [("kernels_gemm_bf16.hip", "gemm_bf16_256_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_256_grouped_gated_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_256_ragged_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_256_ragged_kernel", {8}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_bf16_128_grouped_kernel", {23, 13}, True, 0),
-         ("kernels_gemm_bf16.hip", "gemm_f16_128_grouped_gated_kernel", {23, 13}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_bf16_128_grouped_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_f16_128_grouped_gated_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_256_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_256_grouped_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_256_grouped_gated_kernel", {8}, True, 0),
@@ -96,43 +96,14 @@ def test_k_loops_hold_only_the_counted_waits(isa, source, kernel, waits, agpr_ac
         assert mfma % 32 == 0 or mfma % 56 == 0, "whole K-steps of one wave"
 
 
-def sgprs_of(operand: str):
-    """SGPR numbers named by an operand like s19, s[48:51] or vcc (106, 107)."""
-    m = re.fullmatch(r"s(\d+)", operand)
-    if m:
-        return {int(m.group(1))}
-    m = re.fullmatch(r"s\[(\d+):(\d+)\]", operand)
-    if m:
-        return set(range(int(m.group(1)), int(m.group(2)) + 1))
-    return {106, 107} if operand.startswith("vcc") else set()
-
-
 @pytest.mark.parametrize("source", ["kernels_gemm_bf16.hip", "kernels_gemm_fp8.hip", "kernels_gemm_fp8_e8m0.hip"])
 def test_asm_issued_buffer_instructions_are_padded(isa, source):
-    """An SGPR written by the vector ALU must not be read by a vector-memory instruction less than 5 wait states
-    later.  The compiler pads the instructions it issues itself; the asm-issued ones either carry their own
-    s_nop 4, or (the A loads inside the K loops of the 16-bit kernel, where the padding costs issue slots) none
-    of the 5 instructions before them is a vector instruction that writes one of the SGPRs they read."""
     src = open(os.path.join(BLD.CSRC, source)).read()
     asm_buffer = re.findall(r'asm volatile\("([^"]*buffer_(?:load|store)[^"]*)"', src)
     assert asm_buffer, "the kernel issues buffer instructions as asm statements"
-    unpadded = [a for a in asm_buffer if not a.startswith("s_nop 4\\n\\t")]
-    assert all(a.startswith("buffer_load_dwordx4") for a in unpadded) and (not unpadded or source == "kernels_gemm_bf16.hip")
+    assert all(a.startswith("s_nop 4\\n\\t") for a in asm_buffer)
+    # and in the emitted ISA: each such instruction (register destination or store) directly follows the padding
     for name, lines in isa[source].items():
-        code = [l.strip() for l in lines if l.startswith("\t") and not l.strip().startswith((";", "."))]
-        for i, l in enumerate(code):
-            store = re.match(r"buffer_store_dwordx[24] ", l)
-            load = re.match(r"buffer_load_dwordx4 v\[\d+:\d+\], v\d+, (s\[\d+:\d+\]), (s\d+) offen$", l)
-            if not store and not load:
-                continue
-            if code[i - 1] == "s_nop 4":
-                continue
-            assert load and unpadded, (name, i, code[i - 1], l)
-            reads = sgprs_of(load.group(1)) | sgprs_of(load.group(2))
-            for prev in code[max(0, i - 5):i]:
-                ops = prev.replace(",", " ").split()
-                if ops[0].startswith(("v_readfirstlane", "v_readlane", "v_cmp")) or (ops[0].startswith("v_") and len(ops) > 1 and ops[1].startswith(("s", "vcc"))):
-                    written = sgprs_of(ops[1]) if len(ops) > 1 else set()
-                    if ops[0].startswith("v_cmp") and "_e32" in ops[0]:
-                        written |= {106, 107}
-                    assert not (written & reads), (name, i, prev, l)
+        for i, l in enumerate(lines):
+            if re.match(r"\tbuffer_store_dwordx[24] ", l) or re.match(r"\tbuffer_load_dwordx4 v\[\d+:\d+\], v\d+, s\[\d+:\d+\], s\d+ offen$", l):
+                assert lines[i - 1].strip() == "s_nop 4", (name, i, lines[i - 1], l)
