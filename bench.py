@@ -207,7 +207,7 @@ def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
             wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dBuse, dC, dR), steps, warmup)
             active = int((np.diff(rows) > 0).sum())
             nbytes = 2.0 * (active * f.N * f.K + M * f.K + M * NC)
-            kernel = "streaming (split K)" if M <= 8 * f.G else "tiles of 128 x 256"
+            kernel = "streaming (split K)" if M <= 8 * f.G else ("tiles of 128 x 256" if M <= 384 * f.G else "tiles of 256 x 256")
             r = {"M": M, "active_experts": active, "kernel": kernel, "kernel_ms": devms, "algorithmic_bytes": nbytes,
                  "GBps": nbytes / (devms * 1e-3) / 1e9, "tflops": 2.0 * M * f.N * f.K / (devms * 1e-3) / 1e12}
             r["frac_of_hbm_peak"] = r["GBps"] / PEAK["hbm"]

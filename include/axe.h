@@ -225,14 +225,14 @@ typedef struct {
  * passes over their weights); a kernel_hint that asks for tiles is AXE_EUNSUPPORTED. */
 
 /* Two kernels serve the same family.  AXE_GROUPED_TILES: 256 x 256 tiles of the chained GEMM pipeline, for
- * groups of hundreds of rows (of 128 x 256 unless groups average more than 1536 rows: a K-step then takes half
+ * groups of hundreds of rows (of 128 x 256 unless groups average more than 384 rows: a K-step then takes half
  * the matrix-core time and the weights stream past faster).  AXE_GROUPED_STREAM: one workgroup per (group, 128 rows of B), the group's
  * rows (64 at a time) held in registers while its weights stream by once -- for the few rows per group of
  * an MoE layer at decode batch sizes, where the time is that of reading the weights.  AUTO takes the
  * streaming kernel when M <= 8 G (the host knows M, not the group sizes; measured crossover on the
  * MoE layer of the benchmark: 8 - 16 rows per group on average). */
 enum { AXE_GROUPED_AUTO = 0, AXE_GROUPED_TILES = 1, AXE_GROUPED_STREAM = 2,
-       /* the tile kernel with tiles of 256 or 128 rows (AXE_GROUPED_TILES takes 128 while M <= 1536 G) */
+       /* the tile kernel with tiles of 256 or 128 rows (AXE_GROUPED_TILES takes 128 while M <= 384 G) */
        AXE_GROUPED_TILES_256 = 3, AXE_GROUPED_TILES_128 = 4 };
 
 /* AXE_EPI_SWIGLU: the gated activation between the two group GEMMs, fused into the first.  The logical

@@ -626,9 +626,10 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
 // otherwise one workgroup per possible tile, those without a tile leave at once.
 hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
   // tiles of 128 rows unless the groups are large on average (the host knows M, not the group sizes): measured
-  // on an MoE layer (128 groups, N = 1536, K = 2048) 128-row tiles win by 12 - 25 % up to 512 rows per group, by 5 %
-  // at 1024, and lose 3 % at 2048 (AXE_GROUPED_TILE128_ROWS overrides the threshold for experiments)
-  static const int small_avg = [] { const char* v = getenv("AXE_GROUPED_TILE128_ROWS"); return v ? atoi(v) : 1536; }();
+  // on an MoE layer (128 groups, N = 1536, K = 2048 and N = 2048, K = 768) 128-row tiles win by 2 - 11 % up to 64
+  // rows per group on average, draw at 256, and lose 3 - 4 % at 512 and 7 - 8 % from 1024 on
+  // (AXE_GROUPED_TILE128_ROWS overrides the threshold for experiments)
+  static const int small_avg = [] { const char* v = getenv("AXE_GROUPED_TILE128_ROWS"); return v ? atoi(v) : 384; }();
   const bool t128 = g.tile_m ? g.tile_m == 128 : g.M <= (int64_t)small_avg * g.groups;
   const int tm = t128 ? 128 : kTile;
   const int64_t worst = (g.M / tm + g.groups) * (int64_t)g.grid_n;
@@ -636,6 +637,8 @@ hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
   const int cus = cu_count();
   const bool chain = (nk % 2 == 0) && nk >= 4;
   int64_t nwg = chain ? std::max<int64_t>(cus, (worst + 63) / 64) : worst;
+  // more workgroups than compute units only in whole rounds (272 workgroups on 256 units take as long as 512)
+  if (chain && nwg > cus) nwg = (nwg + cus - 1) / cus * cus;
   nwg = (nwg + 7) / 8 * 8;                                         // the tile sequence is cut into 8 parts, one per XCD
   if (nwg > 0x7fffffff) return hipErrorInvalidValue;
   const dim3 grid((unsigned)nwg), block(256);
@@ -661,6 +664,7 @@ hipError_t launch_gemm_bf16_256_ragged(const GemmArgs& g, hipStream_t s) {
   const int cus = cu_count();
   const bool chain = (nk % 2 == 0) && nk >= 4;
   int64_t nwg = chain ? std::min<int64_t>(tiles, std::max<int64_t>(cus, (tiles + 63) / 64)) : tiles;
+  if (chain && nwg > cus) nwg = (nwg + cus - 1) / cus * cus;      // whole rounds of workgroups
   nwg = (nwg + 7) / 8 * 8;
   if (nwg > 0x7fffffff || g.groups != 1) return hipErrorInvalidValue;
   if (g.f16)
