@@ -310,17 +310,24 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   // lane fetches.  A has two blocks (the steps of either parity): the pieces of step kt + 2 are issued right
   // after the barrier of step kt has freed the block step kt occupied, and have to have landed at the barrier
   // of step kt + 1 -- a load distance of one K-step.  B has a ring of three blocks.
+  // (the piece goes into the per-lane offset, one register per piece, so that the scalar offset is the K-tile's
+  //  alone and shared by the 8 loads of a step: one scalar instruction less per load)
+  int a_voff_p[NA], b_voff_p[8];
+#pragma unroll
+  for (int i = 0; i < NA; ++i) a_voff_p[i] = a_voff_x + i * a_piece;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) b_voff_p[i] = b_voff + i * b_piece;
   auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16,
-                                             a_voff_x, i * a_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep, 0, 0);
+                                             a_voff_p[i], (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep, 0, 0);
   };
   // B ring: byte offsets of the blocks that hold K-steps kt, kt+1, kt+2 (step kt+3 reuses the first)
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16,
-                                             b_voff, i * b_piece + (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * b_kstep, 0, 0);
+                                             b_voff_p[i], (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * b_kstep, 0, 0);
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16

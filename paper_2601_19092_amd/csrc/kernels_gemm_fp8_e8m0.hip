@@ -123,16 +123,20 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
   const int a_voff_x = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
   const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
   const int a_piece = 32 * a_pitch, b_piece = 32 * b_pitch;        // bytes between pieces
+  // (the piece goes into the per-lane offset, one register per piece: the scalar offset is the K-tile's alone)
+  int a_voff_p[8], b_voff_p[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a_voff_p[i] = a_voff_x + i * a_piece, b_voff_p[i] = b_voff + i * b_piece;
   auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16, a_voff_x,
-                                             i * a_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16, a_voff_p[i],
+                                             (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
   };
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;     // B ring: blocks of K-steps kt, kt+1, kt+2
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16, b_voff,
-                                             i * b_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16, b_voff_p[i],
+                                             (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16, chunks q and q + 4
