@@ -105,6 +105,24 @@ def test_plan_element_sizes_transposes_replicas(hc, eb):
     assert got.tobytes() == want.tobytes()
 
 
+@pytest.mark.parametrize("diag", [0, 1, 3])
+def test_plan_transposing_tile_walks(hc, diag, monkeypatch):
+    """The order in which the tiles are walked (row by row, or diagonally with a step of 1 or 3 tiles, so that
+    concurrent workgroups spread their writes over the memory channels) is a bijection of the tile grid for any
+    grid: every element arrives, none twice.  Grids of 5 x 3, 3 x 5 and 1 x 4 tiles with clipped edges, a batch."""
+    monkeypatch.setenv("AXE_TRANSPOSE_DIAG", str(diag))
+    rng = np.random.default_rng(300 + diag)
+    T, ce = 128, 8
+    for shape in ((4 * T + ce, 3 * T), (3 * T - ce, 5 * T), (4 * ce, 4 * T), (2, 2 * T + ce, 3 * T)):
+        rows, cols = shape[-2], shape[-1]
+        s_L = ax.row_major(shape)
+        d_L = Layout.make(shape, (1, rows) if len(shape) == 2 else (rows * cols, 1, rows))
+        src = rng.integers(0, 65536, prod(shape), dtype=np.uint16)
+        got, want = host_relayout(hc, s_L, d_L, shape, src, prod(shape))
+        assert hc.axe_hostcheck_transposes() == 1, shape
+        assert got.tobytes() == want.tobytes(), shape
+
+
 @pytest.mark.parametrize("eb", [1, 2, 4, 8])
 def test_plan_transposing_path(hc, eb):
     """Source and destination contiguous along different digits: the tiled path through LDS.  Whole
