@@ -577,7 +577,10 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   // the large-tile kernels address a tile's 256 rows through 32-bit buffer offsets
   const bool pitch_ok = 256 * lda * eb < (int64_t(1) << 31) && 256 * ldb * eb < (int64_t(1) << 31);
   const bool big_common = (g->M % 256 == 0) && (g->K % bk == 0) && (ldc % 8 == 0) && P.args.out_bf16 && pitch_ok;
-  const bool big_ok = big_common && (g->N % 256 == 0);
+  // 16-bit inputs: the 256x256 tile also stores fp32 (a wave's part of C is addressed through 32-bit byte offsets)
+  const bool big_f32 = !fp8 && !P.args.out_bf16 && (g->M % 256 == 0) && (g->N % 256 == 0) && (g->K % 64 == 0) && (ldc % 4 == 0) &&
+                       pitch_ok && 256 * ldc * 4 < (int64_t(1) << 31);
+  const bool big_ok = (big_common && (g->N % 256 == 0)) || big_f32;
   // bf16 only: 224 columns per tile (7 fragments per wave instead of 8)
   const bool n224_ok = big_common && !fp8 && !f16 && (g->N % 224 == 0);
   // 16-bit inputs: the 256x256 tile also on edges that do not fill a tile (a lane stores 8 columns at once; a wave's
@@ -594,7 +597,7 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   }
   if (blocked) {
     if (fp8 || !big_ok || !block_ok(opa) || !block_ok(opb) || (tile != AXE_TILE_AUTO && tile != AXE_TILE_256x256x64)) {
-      set_error("axe_gemm: blocked operands need the bf16 256x256 tile (M, N multiples of 256, K of 64, bf16 output), "
+      set_error("axe_gemm: blocked operands need the 16-bit 256x256 tile (M, N multiples of 256, K of 64), "
                 "row blocks of 256 x 2^n rows and strides that are multiples of 16 bytes");
       return AXE_EUNSUPPORTED;
     }
@@ -602,12 +605,15 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   }
   if (tile == AXE_TILE_AUTO) {
     tile = big_ok ? AXE_TILE_256x256x64 : (n224_ok ? AXE_TILE_256x224x64 : AXE_TILE_64x64x32);
-    // ragged edges: the large tile once the 64 x 64 tiles of C would take more than about four rounds on the chip
-    // (measured, bf16, K = 1024 .. 4096: 1000 x 1000 12 vs 27 us, 2000 x 2000 41 vs 47 us, 4000 x 4000 388 vs 107 us --
-    //  a single large tile takes 27 - 47 us on its own, the small tiles' time grows with M x N)
-    static const int64_t ragged_min = [] { const char* v = getenv("AXE_RAGGED_MIN_ELEMS"); return v ? atoll(v) : int64_t(5) << 20; }();
-    if (tile == AXE_TILE_64x64x32 && ragged_ok && g->M * g->N >= ragged_min) tile = AXE_TILE_256x256x64;
-    if (big_ok && n224_ok) {
+    // 16-bit inputs: the large tile only once the 64 x 64 tiles of C would take more than about four rounds on the
+    // chip (measured, bf16, K = 1024 .. 4096: 768 x 768 12 vs 27 us, 1000 x 1000 12 vs 27 us, 2000 x 2000 41 vs 47 us,
+    // 4000 x 4000 388 vs 107 us -- a single large tile takes 27 - 47 us on its own, the small tiles' time grows
+    // with M x N); with ragged edges as well as without
+    static const int64_t large_min = [] { const char* v = getenv("AXE_LARGE_TILE_MIN_ELEMS"); return v ? atoll(v) : int64_t(5) << 20; }();
+    const bool large = g->M * g->N >= large_min;
+    if (!fp8 && !large) tile = AXE_TILE_64x64x32;
+    if (tile == AXE_TILE_64x64x32 && ragged_ok && large) tile = AXE_TILE_256x256x64;
+    if (big_ok && n224_ok && tile != AXE_TILE_64x64x32) {
       // both fit: the launch runs ceil(tiles / compute units) rounds of tiles one after the other,
       // each as long as the tile is wide; take the narrower tile when that is shorter in total
       const int64_t cus = axe::cu_count(), gm = g->M / 256;
@@ -617,8 +623,9 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   }
   P.ragged = tile == AXE_TILE_256x256x64 && !big_ok && !blocked && ragged_ok;
   if (tile == AXE_TILE_256x256x64 && !big_ok && !P.ragged) {
-    set_error("axe_gemm: the 256x256 tile needs K a multiple of %lld, a 16-bit output, row pitches below 2^31 / 256 bytes "
-              "and, for fp8, M and N multiples of 256 (16-bit inputs: any M, N a multiple of 8)", (long long)bk);
+    set_error("axe_gemm: the 256x256 tile needs K a multiple of %lld, row pitches below 2^31 / 256 bytes and M, N multiples "
+              "of 256 (16-bit inputs with a 16-bit output: any M, N a multiple of 8; an fp32 output goes with 16-bit inputs only)",
+              (long long)bk);
     return AXE_EUNSUPPORTED;
   }
   if (tile == AXE_TILE_256x224x64 && !n224_ok) {

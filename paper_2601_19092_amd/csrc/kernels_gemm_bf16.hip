@@ -203,8 +203,12 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 // is handled like a group's last tile; what N leaves over: the B descriptor of a tile in the last column ends
 // after the rows that exist (the others load as zero), and a lane whose 8 columns lie past N stores at an
 // offset no buffer reaches, which drops the store.
-template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false>
+//
+// OUT32: C is fp32 -- the accumulators are stored as they are, a fragment at a time (a lane's 4 columns are 16
+// bytes).  Dense kernel only.
+template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false, bool OUT32 = false>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
+  static_assert(!OUT32 || (!GROUPED && NB == 256), "the fp32 output exists for the dense 256-wide kernel");
   static_assert(!RAGGED || (GROUPED && !GATED && NB == 256), "ragged edges are handled by the grouped 256-wide kernel");
   static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
   static_assert(MR == 8 || (MR == 4 && GROUPED), "128-row tiles exist for the grouped kernel");
@@ -383,9 +387,20 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     }
     int tm, tn;
     tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
-    rc = raw_rsrc((uint16_t*)g.C + ((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * NB + wn * (NB / 2),
-                  (uint32_t)((127 * g.ldc + NB / 2) * 2));
-    c_rowblk = (int)(16 * g.ldc * 2);
+    constexpr int OB = OUT32 ? 4 : 2;                                // bytes per element of C
+    rc = raw_rsrc((uint8_t*)g.C + (((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * NB + wn * (NB / 2)) * OB,
+                  (uint32_t)((127 * g.ldc + NB / 2) * OB));
+    c_rowblk = (int)(16 * g.ldc * OB);
+  };
+  // fp32 output: the fragment as it is, 16 bytes per lane (columns 4 q .. 4 q + 3 of row fr), 64 bytes per row
+  const int c_voff32 = (int)((fr * g.ldc + 4 * fq) * 4);
+  auto store_fragment32 = [&](int i, int j) __attribute__((always_inline)) {
+    const f32x4 d = acc[i][j];                                     // (a copy in VGPRs: the accumulators live in AGPRs)
+    const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 64);
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff32), "s"(rc), "s"(soff) : "memory");
+#pragma unroll
+    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
+    __builtin_amdgcn_sched_barrier(0);                             // one fragment at a time: copied out of the AGPRs, stored, cleared
   };
   auto store_fragment = [&](int i, int j) __attribute__((always_inline)) {
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
@@ -567,7 +582,10 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     __builtin_amdgcn_sched_barrier(0);                             // no accumulator read may move above the padding
 #pragma unroll
     for (int i = 0; i < MR; ++i) {
-      if constexpr (GATED) {
+      if constexpr (OUT32) {
+#pragma unroll
+        for (int j = 0; j < NJ; ++j) store_fragment32(i, j);
+      } else if constexpr (GATED) {
 #pragma unroll
         for (int j = 0; j < NJ; j += 4) store_gated_quad(i, j);
       } else {
@@ -600,6 +618,9 @@ __global__ __launch_bounds__(256, 1) void gemm_f16_256_kernel(GemmArgs g) { gemm
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, true>(g); }
 // grouped, tiles of 128 rows (small groups)
+// fp32 output (plain or blocked operands)
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_f32out_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true, false, false, 8, false, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_256_f32out_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true, false, true, 8, false, true>(g); }
 // dense with ragged edges (any M, N a multiple of 8)
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_ragged_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, false, 8, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_ragged_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true, 8, true>(g); }
@@ -616,7 +637,11 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
   unsigned nwg = (unsigned)(chain ? cus : ntiles);
   const bool blocked = g.a_kstep != kRow || g.b_kstep != kRow || g.a_blk_stride != kTile * g.lda || g.b_blk_stride != g.tile_n * g.ldb;
-  if (g.f16)
+  if (!g.out_bf16) {
+    if (g.tile_n != 256) return hipErrorInvalidValue;
+    if (g.f16) hipLaunchKernelGGL(gemm_f16_256_f32out_kernel, dim3(nwg), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL(gemm_bf16_256_f32out_kernel, dim3(nwg), dim3(256), 0, s, g);
+  } else if (g.f16)
     hipLaunchKernelGGL(gemm_f16_256_kernel, dim3(nwg), dim3(256), 0, s, g);
   else if (g.tile_n == 224)
     hipLaunchKernelGGL(gemm_bf16_256x224_kernel, dim3(nwg), dim3(256), 0, s, g);

@@ -119,9 +119,21 @@ def _tile_rc(desc):
 
 
 def test_gemm_family_matching_and_errors():
-    assert _tile_rc(_gemm_desc()) == B.AXE_TILE_256x256x64
+    BIG = B.AXE_TILE_256x256x64
+    # 16-bit inputs: problems of less than 5 x 2^20 elements of C go to the 64 x 64 tiles by themselves (a single
+    # large tile takes longer than all the small ones together); the large tile can be asked for
+    assert _tile_rc(_gemm_desc()) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(tile=BIG)) == BIG
+    assert _tile_rc(_gemm_desc(M=4096, N=4096)) == BIG
     assert _tile_rc(_gemm_desc(M=200)) == B.AXE_TILE_64x64x32
+    # an fp32 output on the large tile: 16-bit inputs only, whole tiles
     assert _tile_rc(_gemm_desc(out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(out_dtype=B.AXE_F32, tile=BIG)) == BIG
+    assert _tile_rc(_gemm_desc(M=4096, N=4096, out_dtype=B.AXE_F32)) == BIG
+    assert _tile_rc(_gemm_desc(M=4096, N=4096, in_dtype=B.AXE_F16, out_dtype=B.AXE_F32)) == BIG
+    assert _tile_rc(_gemm_desc(M=4096, N=4096, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(M=4096, N=4096, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_F32, tile=BIG)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(_gemm_desc(M=4000, N=4096, out_dtype=B.AXE_F32, tile=BIG)) == B.AXE_EUNSUPPORTED
     # 16-bit inputs: the large tile takes ragged edges (any M, N a multiple of 8) -- on request, and by itself once
     # the problem is a few tiles large; fp8 and odd N stay with whole tiles / the small tile
     assert _tile_rc(_gemm_desc(M=200, tile=B.AXE_TILE_256x256x64)) == B.AXE_TILE_256x256x64
@@ -136,7 +148,7 @@ def test_gemm_family_matching_and_errors():
     # the shard of a column-parallel layer: extent-1 device iter + device offset are dropped (rule D0)
     g = W.gemm_bf16(256, 512, 256, 1)
     _, Bshard, _ = W.gemm_specs(g, device_axis=True, shard=5)
-    assert _tile_rc(_gemm_desc(N=512, Bs=Bshard)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(N=512, Bs=Bshard, tile=BIG)) == BIG
     # a weight still spread over 8 GPUs is not one GPU's tensor
     spread = W.spec([(256, 1, "m"), (8, 1, "gpuid"), (64, 256, "m")])
     assert _tile_rc(_gemm_desc(N=512, Bs=spread)) == B.AXE_EALIAS
@@ -148,14 +160,14 @@ def test_gemm_family_matching_and_errors():
     assert _tile_rc(_gemm_desc(a_elems=100)) == B.AXE_ERANGE
     assert _tile_rc(_gemm_desc(in_dtype=7)) == B.AXE_EINVAL
     # fp16 inputs go with an fp16 (or fp32) output, bf16 inputs with bf16 (or fp32)
-    assert _tile_rc(_gemm_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_F16)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_F16, tile=BIG)) == BIG
     assert _tile_rc(_gemm_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
     assert _tile_rc(_gemm_desc(in_dtype=B.AXE_F16, out_dtype=B.AXE_BF16)) == B.AXE_EUNSUPPORTED
     assert _tile_rc(_gemm_desc(in_dtype=B.AXE_BF16, out_dtype=B.AXE_F16)) == B.AXE_EUNSUPPORTED
     assert _tile_rc(_gemm_desc(M=0)) == B.AXE_EINVAL
     # pitched operands (leading dimension larger than the row) are in the family
     pitched = W.spec([(256, 264, "m"), (256, 1, "m")])
-    assert _tile_rc(_gemm_desc(A=pitched, a_elems=256 * 264)) == B.AXE_TILE_256x256x64
+    assert _tile_rc(_gemm_desc(A=pitched, a_elems=256 * 264, tile=BIG)) == BIG
     # NULL device pointers are refused by axe_gemm itself
     d = _gemm_desc()
     assert B.lib().axe_gemm(C.byref(d.c), None, None, None, None) == B.AXE_EINVAL
@@ -189,7 +201,7 @@ def test_gemm_accepts_blocked_operands():
     assert _tile_rc(_gemm_desc(A=plainA, Bs=blkB, **kw)) == B.AXE_TILE_256x256x64
     assert _tile_rc(_gemm_desc(A=blkA, Bs=plainB, **kw)) == B.AXE_TILE_256x256x64
     assert _tile_rc(_gemm_desc(A=blkA, Bs=blkB, tile=B.AXE_TILE_64x64x32, **kw)) == B.AXE_EUNSUPPORTED
-    assert _tile_rc(_gemm_desc(A=blkA, Bs=blkB, out_dtype=B.AXE_F32, **kw)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(_gemm_desc(A=blkA, Bs=blkB, out_dtype=B.AXE_F32, **kw)) == B.AXE_TILE_256x256x64   # fp32 output as well
     # row blocks of 128 rows are not a multiple of the tile
     r, k = W.blocked_iters(M, K, rb=128)
     assert _tile_rc(_gemm_desc(A=W.spec(r + k), Bs=plainB, **kw)) == B.AXE_EUNSUPPORTED

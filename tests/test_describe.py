@@ -25,9 +25,10 @@ def desc_for(kind):
     elif kind in ("big_fp8", "big_fp8_mx"):
         M, N, K, dt, out, tile = 512, 768, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_AUTO
     elif kind == "big_bf16_n224":
-        M, N, K, dt, out, tile = 512, 672, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_AUTO
+        # (problems this small go to the 64 x 64 tiles by themselves; the large tiles are asked for)
+        M, N, K, dt, out, tile = 512, 672, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_256x224x64
     else:
-        M, N, K, dt, out, tile = 512, 768, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_AUTO
+        M, N, K, dt, out, tile = 512, 768, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_256x256x64
     scales = {}
     if kind == "big_fp8":
         # fp32 block scales: the 8-wave kernel that folds on the vector ALU.  describe never touches the

@@ -416,6 +416,50 @@ def test_gemm_bf16_large_tile(M, N, K):
     assert R.rel_frobenius(c, c_small) < 2e-3
 
 
+# fp32 output of the large tile (16-bit inputs): the accumulators as they are -- only the order of the K sum differs
+# from the oracle's fp64 sum.  nk = 1, 3, 9, and 8 with 17 x 16 tiles chained; pitched C with a guard pattern.
+@pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 768, 192), (768, 512, 576), (4352, 4096, 512)])
+@pytest.mark.parametrize("dtype", ["bf16", "f16"])
+def test_gemm_large_tile_fp32_output(M, N, K, dtype):
+    g = (W.gemm_bf16 if dtype == "bf16" else W.gemm_f16)(M, N, K, 470 + K, std_b=K ** -0.5, out_dtype="f32")
+    ldc, fill = N + 12, 12345.0
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_nk.reshape(-1))
+    dC = torch.full((M * ldc,), fill, dtype=torch.float32, device="cuda")
+    dt = B.AXE_BF16 if dtype == "bf16" else B.AXE_F16
+    desc = B.GemmDesc(M, N, K, dt, B.AXE_F32, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, N)),
+                      B.Layout(W.spec([(M, ldc, "m"), (N, 1, "m")])), M * K, N * K, M * ldc, tile_hint=B.AXE_TILE_256x256x64)
+    B.axe_gemm(desc, dA, dB, dC)
+    torch.cuda.synchronize()
+    raw = dC.cpu().numpy().reshape(M, ldc)
+    assert (raw[:, N:] == fill).all(), "the kernel wrote outside the M x N result"
+    c = raw[:, :N].astype(np.float64)
+    if M * N <= 1 << 20:
+        ref = oracle_gemm(g)
+        assert np.isfinite(c).all() and R.rel_frobenius(c, ref) < 1e-5
+    else:
+        rows = np.array([0, 255, 256, M - 1])
+        assert R.rel_frobenius(c[rows], oracle_gemm(g, rows, None)) < 1e-5
+        cols = np.array([0, 255, 256, N - 1])
+        assert R.rel_frobenius(c[:, cols], oracle_gemm(g, None, cols)) < 1e-5
+        # every tile against the small kernel (same inputs, fp32 output as well)
+        c_small = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+        for i in range(0, M, 256):
+            for j in range(0, N, 256):
+                assert R.rel_frobenius(c[i:i + 256, j:j + 256], c_small[i:i + 256, j:j + 256]) < 1e-5, (i, j)
+
+
+def test_gemm_large_tile_fp32_output_blocked_operands():
+    g = W.gemm_bf16(512, 768, 256, 481, std_b=1 / 16, out_dtype="f32")
+    dA, dB = dev(W.pack_blocked(g.a_mk)), dev(W.pack_blocked(g.b_nk))
+    dC = torch.zeros(g.M * g.N, dtype=torch.float32, device="cuda")
+    desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16, B.AXE_F32, B.Layout(W.blocked_a_spec(g.M, g.K)), B.Layout(W.blocked_b_spec(g.K, g.N)),
+                      B.Layout(W.row_major_spec(g.M, g.N)), g.M * g.K, g.N * g.K, g.M * g.N)
+    B.axe_gemm(desc, dA, dB, dC)
+    torch.cuda.synchronize()
+    c = dC.cpu().numpy().reshape(g.M, g.N).astype(np.float64)
+    assert R.rel_frobenius(c, oracle_gemm(g)) < 1e-5
+
+
 # Ragged edges on the large tile (16-bit inputs): any M, N a multiple of 8.  C is pitched and followed by guard rows,
 # all filled with a pattern beforehand: nothing outside the M x N result may change.  K = 64 nk with nk = 1, 2, 3
 # (shorter than the pipeline), 4 and 8 (several tiles chained per workgroup), 11 (odd).
@@ -750,7 +794,7 @@ def run_gemm_blocked(g: W.GemmInputs, a_blocked: bool, b_blocked: bool):
     dA, dB = dev(a), dev(b)
     dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
     desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, g.N)),
-                      a.size, b.size, g.M * g.N)
+                      a.size, b.size, g.M * g.N, tile_hint=B.AXE_TILE_256x256x64)
     assert B.axe_gemm_tile(desc) == B.AXE_TILE_256x256x64
     B.axe_gemm(desc, dA, dB, dC)
     torch.cuda.synchronize()
