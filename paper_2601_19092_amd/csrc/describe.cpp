@@ -37,15 +37,17 @@ int ilog2(int64_t v) {
 struct Geo {
   bool big, fp8;
   bool mx;         // fp8 on the matrix cores' scale path (E8M0 scales or none): the 4-wave structure of the bf16 kernel
+  bool out32;      // fp32 output: fragments are stored as they are, not in exchanged pairs
   int T, TN, BK, F, ROWB, CE, EB;
   int WM, WN;      // wave grid: wave = WN * wm + wn; A rows are split over wm, B rows over wn
   int key_shift;   // swizzle key = (row >> key_shift) & (chunks per row - 1)
   int64_t b_off;   // element offset of the B block inside one LDS stage
 };
 
-Geo geometry(bool big, bool fp8, bool mx, int tile_n) {
+Geo geometry(bool big, bool fp8, bool mx, int tile_n, bool out32) {
   Geo g;
   g.big = big;
+  g.out32 = out32;
   g.fp8 = fp8;
   g.mx = big && fp8 && mx;
   g.EB = fp8 ? 1 : 2;
@@ -201,7 +203,7 @@ int c_store_layout(const Geo& g, Builder& b) {
   // The 4-wave 256 x 256 kernels (bf16, and fp8 on the scale path) pair neighbouring fragments: after an exchange between lane groups a
   // lane stores 8 consecutive columns (16 bytes).  Column = 128 wn + 32 p + 16 b + 8 h + 4 t + e is
   // stored by lane group 2 h + b from register 8 p + 4 t + e of the fragment row.
-  if (g.big && (!g.fp8 || g.mx) && g.TN == 256) {
+  if (g.big && (!g.fp8 || g.mx) && g.TN == 256 && !g.out32) {
     const int NFM = g.T / g.WM / g.F;
     b.D(g.WM, g.WN, WAVE);
     b.D(NFM, 32, REG);
@@ -232,7 +234,8 @@ extern "C" int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_la
   if (tile < 0) return tile;
   const bool big = tile != AXE_TILE_64x64x32;
   const bool mx = g->in_dtype == AXE_FP8_E4M3 && (!g->d_scale_a || g->scale_dtype == AXE_SCALE_E8M0);
-  const Geo geo = geometry(big, g->in_dtype == AXE_FP8_E4M3, mx, tile == AXE_TILE_256x224x64 ? 224 : (big ? 256 : 64));
+  const Geo geo = geometry(big, g->in_dtype == AXE_FP8_E4M3, mx, tile == AXE_TILE_256x224x64 ? 224 : (big ? 256 : 64),
+                           g->out_dtype == AXE_F32);
   Builder b;
   int rc;
   switch (which) {

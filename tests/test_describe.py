@@ -24,6 +24,8 @@ def desc_for(kind):
         M, N, K, dt, out, tile = 128, 192, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_64x64x32
     elif kind in ("big_fp8", "big_fp8_mx"):
         M, N, K, dt, out, tile = 512, 768, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_AUTO
+    elif kind == "big_bf16_f32":
+        M, N, K, dt, out, tile = 512, 768, 256, B.AXE_BF16, B.AXE_F32, B.AXE_TILE_256x256x64
     elif kind == "big_bf16_n224":
         # (problems this small go to the 64 x 64 tiles by themselves; the large tiles are asked for)
         M, N, K, dt, out, tile = 512, 672, 256, B.AXE_BF16, B.AXE_BF16, B.AXE_TILE_256x224x64
@@ -56,13 +58,15 @@ def table(L, shape):
 GEO = {"small_bf16": dict(T=64, TN=64, BK=32, EB=2, waves=4, wn=2), "small_fp8": dict(T=64, TN=64, BK=128, EB=1, waves=4, wn=2),
        "big_bf16": dict(T=256, TN=256, BK=64, EB=2, waves=4, wn=2), "big_fp8": dict(T=256, TN=256, BK=128, EB=1, waves=8, wn=4),
        "big_bf16_n224": dict(T=256, TN=224, BK=64, EB=2, waves=4, wn=2),
+       "big_bf16_f32": dict(T=256, TN=256, BK=64, EB=2, waves=4, wn=2),
        "big_fp8_mx": dict(T=256, TN=256, BK=128, EB=1, waves=4, wn=2)}
-KINDS = ["small_bf16", "small_fp8", "big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx"]
-BIG = ("big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx")
+KINDS = ["small_bf16", "small_fp8", "big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx", "big_bf16_f32"]
+BIG = ("big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx", "big_bf16_f32")
 A_VIA_REGISTERS = ()                                                # (no kernel stages A through VGPRs and ds_write any more)
 PAIRED_STORES = ("big_bf16", "big_fp8_mx")
 TILE = {"small_bf16": B.AXE_TILE_64x64x32, "small_fp8": B.AXE_TILE_64x64x32, "big_bf16": B.AXE_TILE_256x256x64,
-        "big_fp8": B.AXE_TILE_256x256x64, "big_bf16_n224": B.AXE_TILE_256x224x64, "big_fp8_mx": B.AXE_TILE_256x256x64}
+        "big_fp8": B.AXE_TILE_256x256x64, "big_bf16_n224": B.AXE_TILE_256x224x64, "big_fp8_mx": B.AXE_TILE_256x256x64,
+        "big_bf16_f32": B.AXE_TILE_256x256x64}
 
 
 @pytest.mark.parametrize("kind", KINDS)
@@ -199,7 +203,7 @@ def test_operand_reads_cover_the_tile_and_are_bank_conflict_free(kind):
             assert (worst == 1) == expect_clean, (kind, which_o, swz, worst)
 
 
-@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx"])
+@pytest.mark.parametrize("kind", ["small_bf16", "big_bf16", "big_fp8", "big_bf16_n224", "big_fp8_mx", "big_bf16_f32"])
 def test_c_store_map(kind):
     desc, _ = desc_for(kind)
     T, TN, NW, WN = GEO[kind]["T"], GEO[kind]["TN"], GEO[kind]["waves"], GEO[kind]["wn"]
