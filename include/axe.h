@@ -172,9 +172,9 @@ int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d
  * Shapes: the 64 x 64 tile takes any M and N.  The 256 x 256 tile needs K a multiple of 64 (fp8: 128); with fp8
  * inputs a 16-bit output and M and N multiples of 256; with 16-bit inputs either a 16-bit output, any M and any
  * N that is a multiple of 8 (edges that do not fill a tile are cut off by the buffer bounds; plain operands
- * only), or an fp32 output with M and N multiples of 256.  With 16-bit inputs the library takes the large tile
- * by itself once M x N reaches 5 x 2^20 elements; below that the 64 x 64 tiles are faster (a single large tile
- * takes as long as four rounds of small ones). */
+ * only), or an fp32 output with M and N multiples of 256.  Left to itself the library takes the large tile once
+ * M x N reaches 5 x 2^20 elements (fp8: 2^20); below that the 64 x 64 tiles are faster (a single large tile
+ * takes as long as several rounds of small ones). */
 int axe_gemm_tile(const axe_gemm_desc_t* g);
 
 /* ---------------------------------------------------------------------------------------------

@@ -610,8 +610,10 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
     // 4000 x 4000 388 vs 107 us -- a single large tile takes 27 - 47 us on its own, the small tiles' time grows
     // with M x N); with ragged edges as well as without
     static const int64_t large_min = [] { const char* v = getenv("AXE_LARGE_TILE_MIN_ELEMS"); return v ? atoll(v) : int64_t(5) << 20; }();
-    const bool large = g->M * g->N >= large_min;
-    if (!fp8 && !large) tile = AXE_TILE_64x64x32;
+    // (fp8: the 64 x 64 kernel is slower per tile; measured crossover near 1024 x 1024 -- 256^3: 8 vs 14 us,
+    //  1024^3: 19 vs 20 us, 2048^3: 91 vs 30 us)
+    const bool large = g->M * g->N >= (fp8 ? std::min<int64_t>(large_min, int64_t(1) << 20) : large_min);
+    if (!large) tile = AXE_TILE_64x64x32;
     if (tile == AXE_TILE_64x64x32 && ragged_ok && large) tile = AXE_TILE_256x256x64;
     if (big_ok && n224_ok && tile != AXE_TILE_64x64x32) {
       // both fit: the launch runs ceil(tiles / compute units) rounds of tiles one after the other,

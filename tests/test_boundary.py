@@ -183,7 +183,9 @@ def test_gemm_row_scaled_activations_go_to_the_small_kernel():
     def desc(rows, tile=B.AXE_TILE_AUTO, dt=B.AXE_FP8_E4M3):
         return B.GemmDesc(256, 256, 256, dt, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(Cs), 256 * 256, 256 * 256, 256 * 256,
                           FakeTensor(), FakeTensor(), tile_hint=tile, scale_a_rows=rows)
-    assert _tile_rc(desc(0)) == B.AXE_TILE_256x256x64 and _tile_rc(desc(128)) == B.AXE_TILE_256x256x64
+    BIG = B.AXE_TILE_256x256x64
+    assert _tile_rc(desc(0, tile=BIG)) == BIG and _tile_rc(desc(128, tile=BIG)) == BIG
+    assert _tile_rc(desc(0)) == B.AXE_TILE_64x64x32          # a problem this small takes the 64 x 64 tiles by itself
     assert _tile_rc(desc(1)) == B.AXE_TILE_64x64x32
     assert _tile_rc(desc(1, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
     assert _tile_rc(desc(64)) == B.AXE_EINVAL

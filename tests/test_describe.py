@@ -23,7 +23,7 @@ def desc_for(kind):
     elif kind == "small_fp8":
         M, N, K, dt, out, tile = 128, 192, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_64x64x32
     elif kind in ("big_fp8", "big_fp8_mx"):
-        M, N, K, dt, out, tile = 512, 768, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_AUTO
+        M, N, K, dt, out, tile = 512, 768, 256, B.AXE_FP8_E4M3, B.AXE_BF16, B.AXE_TILE_256x256x64
     elif kind == "big_bf16_f32":
         M, N, K, dt, out, tile = 512, 768, 256, B.AXE_BF16, B.AXE_F32, B.AXE_TILE_256x256x64
     elif kind == "big_bf16_n224":
