@@ -278,6 +278,17 @@ enum {
 int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_layout_t* out,
                       int64_t* shape, int32_t* rank, void* arena, size_t arena_bytes);
 
+/* The same for axe_gemm_grouped (Sec. 4.1, fused MoE layer; host only).  The grouped tile kernels are the dense
+ * 256-wide 16-bit kernel at a tile height of 256 or 128 rows and report its layouts at that height; AXE_DESC_ACC is
+ * the accumulator layout of one tile (where a tile lies in the problem depends on the group sizes, which only the
+ * device knows).  AXE_EUNSUPPORTED: the streaming kernel (no LDS stage; its register maps are stated in its source),
+ * and AXE_DESC_C_STORE with the gated epilogue (a stored element comes from two accumulators).
+ * axe_gemm_grouped_kernel returns the kernel axe_gemm_grouped would launch: AXE_GROUPED_STREAM,
+ * AXE_GROUPED_TILES_256 or AXE_GROUPED_TILES_128, or the error axe_gemm_grouped would return. */
+int axe_gemm_grouped_kernel(const axe_gemm_grouped_desc_t* g);
+int axe_gemm_grouped_describe(const axe_gemm_grouped_desc_t* g, int32_t which, axe_layout_t* out,
+                              int64_t* shape, int32_t* rank, void* arena, size_t arena_bytes);
+
 /* ---------------------------------------------------------------------------------------------
  * Layout operators (Sec. 3.3; Apps. A - F).  Host only: pure integer bookkeeping on (D, R, O),
  * nothing is launched.  Results are written through `out`, whose d / r / offset pointers point

@@ -24,7 +24,7 @@ AXE_SCALE_F32, AXE_SCALE_E8M0 = 0, 1
 AXE_EPI_NONE, AXE_EPI_SWIGLU = 0, 1
 AXE_GROUPED_AUTO, AXE_GROUPED_TILES, AXE_GROUPED_STREAM, AXE_GROUPED_TILES_256, AXE_GROUPED_TILES_128 = 0, 1, 2, 3, 4
 
-EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
+EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_grouped_kernel", "axe_gemm_grouped_describe", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
            "axe_last_error", "axe_version", "axe_layout_span", "axe_layout_canonicalize", "axe_layout_gap_condition",
            "axe_layout_equal", "axe_layout_group", "axe_layout_tile", "axe_layout_direct_sum", "axe_layout_tile_of",
            "axe_layout_slice"]
@@ -94,6 +94,10 @@ def lib() -> C.CDLL:
         L.axe_gemm_grouped_check.argtypes = [C.POINTER(axe_gemm_grouped_desc_t)]
         L.axe_gemm_tile.restype = C.c_int
         L.axe_gemm_tile.argtypes = [C.POINTER(axe_gemm_desc_t)]
+        L.axe_gemm_grouped_kernel.restype = C.c_int
+        L.axe_gemm_grouped_kernel.argtypes = [C.POINTER(axe_gemm_grouped_desc_t)]
+        L.axe_gemm_grouped_describe.restype = C.c_int
+        L.axe_gemm_grouped_describe.argtypes = [C.POINTER(axe_gemm_grouped_desc_t), i32, LP, C.POINTER(i64), C.POINTER(i32), vp, C.c_size_t]
         L.axe_gemm_describe.restype = C.c_int
         L.axe_gemm_describe.argtypes = [C.POINTER(axe_gemm_desc_t), i32, LP, C.POINTER(i64), C.POINTER(i32), vp,
                                         C.c_size_t]
@@ -270,6 +274,23 @@ def axe_gemm_describe(desc: GemmDesc, which: int) -> Tuple[dict, Tuple[int, ...]
     rank = C.c_int32(0)
     arena = C.create_string_buffer(4096)
     _check(lib().axe_gemm_describe(C.byref(desc.c), which, C.byref(out), shape, C.byref(rank), arena, len(arena)))
+    return _spec_of(out), tuple(shape[i] for i in range(rank.value))
+
+
+def axe_gemm_grouped_kernel(desc: GroupedGemmDesc) -> int:
+    rc = lib().axe_gemm_grouped_kernel(C.byref(desc.c))
+    if rc < 0:
+        _check(rc)
+    return rc
+
+
+def axe_gemm_grouped_describe(desc: GroupedGemmDesc, which: int) -> Tuple[dict, Tuple[int, ...]]:
+    """Returns (spec, shape): the layout of one tile movement of the grouped tile kernel as plain data."""
+    out = axe_layout_t()
+    shape = (C.c_int64 * AXE_MAX_RANK)()
+    rank = C.c_int32(0)
+    arena = C.create_string_buffer(4096)
+    _check(lib().axe_gemm_grouped_describe(C.byref(desc.c), which, C.byref(out), shape, C.byref(rank), arena, len(arena)))
     return _spec_of(out), tuple(shape[i] for i in range(rank.value))
 
 

@@ -859,6 +859,15 @@ int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const vo
   return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm_grouped");
 }
 
+// Chosen kernel, for tests and tools: AXE_GROUPED_STREAM, AXE_GROUPED_TILES_256 or AXE_GROUPED_TILES_128, or a negative error.
+int axe_gemm_grouped_kernel(const axe_gemm_grouped_desc_t* g) {
+  GemmArgs a;
+  if (int rc = plan_gemm_grouped(g, nullptr, nullptr, nullptr, nullptr, a, false)) return rc;
+  if (g->kernel_hint == AXE_GROUPED_STREAM || a.fp8 || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G))
+    return AXE_GROUPED_STREAM;
+  return grouped_tile_rows(a.M, a.groups, a.tile_m) == 128 ? AXE_GROUPED_TILES_128 : AXE_GROUPED_TILES_256;
+}
+
 int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g) {
   GemmArgs a;
   return plan_gemm_grouped(g, nullptr, nullptr, nullptr, nullptr, a, false);

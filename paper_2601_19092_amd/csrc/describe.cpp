@@ -224,6 +224,10 @@ int c_store_layout(const Geo& g, Builder& b) {
 
 }  // namespace
 
+namespace {
+int emit(const Builder& b, const char* who, axe_layout_t* out, int64_t* shape, int32_t* rank, void* arena, size_t arena_bytes);
+}
+
 extern "C" int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_layout_t* out, int64_t* shape,
                                  int32_t* rank, void* arena, size_t arena_bytes) {
   if (!g || !out || !shape || !rank || !arena) {
@@ -254,10 +258,15 @@ extern "C" int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_la
       return AXE_EINVAL;
   }
   if (rc) return rc;
-  // lay the result out in the caller's arena
+  return emit(b, "axe_gemm_describe", out, shape, rank, arena, arena_bytes);
+}
+
+namespace {
+// lay the result out in the caller's arena
+int emit(const Builder& b, const char* who, axe_layout_t* out, int64_t* shape, int32_t* rank, void* arena, size_t arena_bytes) {
   const size_t need = sizeof(axe_iter_t) * (b.d.size() + b.r.size()) + sizeof(int64_t) * NAXES + sizeof(char*) * NAXES + 16;
   if (arena_bytes < need || b.shape.size() > AXE_MAX_RANK) {
-    axe::set_error("axe_gemm_describe: arena of %zu bytes is too small (%zu needed)", arena_bytes, need);
+    axe::set_error("%s: arena of %zu bytes is too small (%zu needed)", who, arena_bytes, need);
     return AXE_ERANGE;
   }
   char* p = (char*)arena;
@@ -286,4 +295,49 @@ extern "C" int axe_gemm_describe(const axe_gemm_desc_t* g, int32_t which, axe_la
   *rank = (int32_t)b.shape.size();
   for (size_t i = 0; i < b.shape.size(); ++i) shape[i] = b.shape[i];
   return AXE_OK;
+}
+}  // namespace
+
+// The grouped tile kernels are the dense 256-wide 16-bit kernel at a tile height of 256 or 128 rows: their tile
+// movements are the same layouts (a tile's place in the problem depends on the group sizes, which only the
+// device knows, so the accumulator layout is that of one tile).
+extern "C" int axe_gemm_grouped_describe(const axe_gemm_grouped_desc_t* g, int32_t which, axe_layout_t* out, int64_t* shape,
+                                         int32_t* rank, void* arena, size_t arena_bytes) {
+  if (!g || !out || !shape || !rank || !arena) {
+    axe::set_error("axe_gemm_grouped_describe: NULL argument");
+    return AXE_EINVAL;
+  }
+  const int kernel = axe_gemm_grouped_kernel(g);
+  if (kernel < 0) return kernel;
+  if (kernel == AXE_GROUPED_STREAM) {
+    axe::set_error("axe_gemm_grouped_describe: the streaming kernel keeps no tile in LDS and its maps are not reported "
+                   "(lane l holds row l %% 16 and the 16-byte chunks l / 16 and l / 16 + 4 of a 64-wide K-tile of either operand)");
+    return AXE_EUNSUPPORTED;
+  }
+  Geo geo = geometry(true, false, false, 256, false);
+  if (kernel == AXE_GROUPED_TILES_128) geo.T = 128;               // the A blocks in LDS keep their places: b_off stays
+  Builder b;
+  int rc;
+  switch (which) {
+    case AXE_DESC_A_G2L_THREADS: rc = g2l_threads(geo, false, b); break;
+    case AXE_DESC_B_G2L_THREADS: rc = g2l_threads(geo, true, b); break;
+    case AXE_DESC_A_LDS: rc = lds_layout(geo, false, b); break;
+    case AXE_DESC_B_LDS: rc = lds_layout(geo, true, b); break;
+    case AXE_DESC_A_OPERAND: rc = operand_layout(geo, false, b); break;
+    case AXE_DESC_B_OPERAND: rc = operand_layout(geo, true, b); break;
+    case AXE_DESC_ACC: rc = acc_layout(geo, 1, 1, true, b); break;
+    case AXE_DESC_C_STORE:
+      if (g->epilogue != AXE_EPI_NONE) {
+        axe::set_error("axe_gemm_grouped_describe: the store map of the gated epilogue (two accumulators per stored element) "
+                       "is not a layout of the accumulators and is not reported");
+        return AXE_EUNSUPPORTED;
+      }
+      rc = c_store_layout(geo, b);
+      break;
+    default:
+      axe::set_error("axe_gemm_grouped_describe: unknown selector %d", which);
+      return AXE_EINVAL;
+  }
+  if (rc) return rc;
+  return emit(b, "axe_gemm_grouped_describe", out, shape, rank, arena, arena_bytes);
 }

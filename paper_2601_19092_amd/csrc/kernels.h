@@ -1,6 +1,7 @@
 // Launch entry points of the kernels (host-callable; defined in the .hip files).
 #pragma once
 #include <hip/hip_runtime.h>
+#include <stdlib.h>
 
 #include "device_types.h"
 
@@ -24,6 +25,15 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s);
 // dense with ragged edges through the grouped kernel (g.groups = 1, g.group_rows null): any M, N % 8 == 0, K % 64 == 0
 hipError_t launch_gemm_bf16_256_ragged(const GemmArgs& g, hipStream_t s);
+// rows of a tile of the grouped tile kernel: 128 unless the groups are large on average (the host knows M, not the
+// group sizes) or tile_m says otherwise.  Measured on an MoE layer (128 groups, N = 1536, K = 2048 and N = 2048,
+// K = 768): 128-row tiles win by 2 - 11 % up to 64 rows per group on average, draw at 256, and lose 3 - 4 % at 512 and
+// 7 - 8 % from 1024 on (AXE_GROUPED_TILE128_ROWS overrides the threshold for experiments).
+inline int grouped_tile_rows(int64_t M, int groups, int tile_m) {
+  static const int small_avg = [] { const char* v = getenv("AXE_GROUPED_TILE128_ROWS"); return v ? atoi(v) : 384; }();
+  if (tile_m) return tile_m == 128 ? 128 : 256;
+  return M <= (int64_t)small_avg * groups ? 128 : 256;
+}
 // grouped, few rows per group: one workgroup per (group, 128 rows of B), weights streamed once, no LDS
 hipError_t launch_gemm_grouped_stream(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_fp8_256(const GemmArgs& g, hipStream_t s);

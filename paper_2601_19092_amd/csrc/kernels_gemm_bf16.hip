@@ -657,12 +657,7 @@ hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
 // most 64 tiles, one per lane: beyond 64 x CUs tiles in the worst case more workgroups are launched);
 // otherwise one workgroup per possible tile, those without a tile leave at once.
 hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
-  // tiles of 128 rows unless the groups are large on average (the host knows M, not the group sizes): measured
-  // on an MoE layer (128 groups, N = 1536, K = 2048 and N = 2048, K = 768) 128-row tiles win by 2 - 11 % up to 64
-  // rows per group on average, draw at 256, and lose 3 - 4 % at 512 and 7 - 8 % from 1024 on
-  // (AXE_GROUPED_TILE128_ROWS overrides the threshold for experiments)
-  static const int small_avg = [] { const char* v = getenv("AXE_GROUPED_TILE128_ROWS"); return v ? atoi(v) : 384; }();
-  const bool t128 = g.tile_m ? g.tile_m == 128 : g.M <= (int64_t)small_avg * g.groups;
+  const bool t128 = grouped_tile_rows(g.M, g.groups, g.tile_m) == 128;
   const int tm = t128 ? 128 : kTile;
   const int64_t worst = (g.M / tm + g.groups) * (int64_t)g.grid_n;
   const int nk = (int)(g.K / 64);

@@ -287,3 +287,81 @@ def test_fp8_mfma_operand_layout_matches_its_statement():
                 for p in pts:
                     assert p[4] == r % 16 + 16 * ((k % 64) // 16)
                     assert p[5] % 32 == 16 * (k // 64) + k % 16
+
+
+# ----------------------------------------------------------------------------- grouped tile kernels
+def _grouped_desc(M, kernel=B.AXE_GROUPED_AUTO, epilogue=B.AXE_EPI_NONE, dt=B.AXE_BF16):
+    G, N, K = 4, 512, 256
+    NC = N // 2 if epilogue == B.AXE_EPI_SWIGLU else N
+    Bs = W.gated_b_spec(K, N, G) if epilogue == B.AXE_EPI_SWIGLU else W.spec([(G, N * K, "m"), (K, 1, "m"), (N, K, "m")])
+    return B.GroupedGemmDesc(M, N, K, G, B.Layout(W.row_major_spec(M, K)), B.Layout(Bs), B.Layout(W.row_major_spec(M, NC)),
+                             M * K, G * N * K, M * NC, in_dtype=dt, out_dtype=dt, epilogue=epilogue, kernel_hint=kernel)
+
+
+@pytest.mark.parametrize("T,hint", [(256, B.AXE_GROUPED_TILES_256), (128, B.AXE_GROUPED_TILES_128), (128, B.AXE_GROUPED_AUTO)])
+def test_grouped_tile_kernels_report_the_dense_maps_at_their_tile_height(T, hint):
+    desc = _grouped_desc(1000, hint)                       # 250 rows per group on average: tiles of 128 rows when left alone
+    assert B.axe_gemm_grouped_kernel(desc) == (B.AXE_GROUPED_TILES_256 if T == 256 else B.AXE_GROUPED_TILES_128)
+    def gget(which):
+        spec, shape = B.axe_gemm_grouped_describe(desc, which)
+        return Layout.from_spec(spec), shape
+    dense, _ = desc_for("big_bf16")
+    BK, TN, NW = 64, 256, 4
+    for which, want in ((B.AXE_DESC_A_G2L_THREADS, (T, BK)), (B.AXE_DESC_B_G2L_THREADS, (BK, TN)), (B.AXE_DESC_A_LDS, (T, BK)),
+                        (B.AXE_DESC_B_LDS, (BK, TN)), (B.AXE_DESC_A_OPERAND, (T, BK)), (B.AXE_DESC_B_OPERAND, (BK, TN)),
+                        (B.AXE_DESC_ACC, (T, TN)), (B.AXE_DESC_C_STORE, (T, TN))):
+        L, shape = gget(which)
+        assert shape == want and ax.admits(L, shape)
+        if T == 256 and which != B.AXE_DESC_ACC:           # the very layouts of the dense kernel
+            Ld, sd = get(dense, which)
+            assert sd == shape and np.array_equal(table(L, shape), table(Ld, sd))
+    # thread maps: every register of every thread exactly once; LDS: A in its block's first T rows, B behind both A blocks
+    for which_t, which_l, rows, base in ((B.AXE_DESC_A_G2L_THREADS, B.AXE_DESC_A_LDS, T, 0),
+                                        (B.AXE_DESC_B_G2L_THREADS, B.AXE_DESC_B_LDS, TN, 2 * 256 * BK)):
+        Lt, st = gget(which_t)
+        th = table(Lt, st)[:, 0, :]
+        regs = rows * BK // (64 * NW)
+        key = (th[:, 3] * 64 + th[:, 4]) * regs + th[:, 5]
+        assert np.array_equal(np.sort(key), np.arange(rows * BK))
+        Ll, sl = gget(which_l)
+        lds = table(Ll, sl)[:, 0, 1]
+        assert np.array_equal(np.sort(lds), np.arange(base, base + rows * BK))
+        first = (lds[np.argsort(key)].reshape(NW, 64, regs // 8, 8)[..., 0]) * 2       # byte address of each lane's chunk
+        for w, i in itertools.product(range(NW), range(regs // 8)):                     # direct-to-LDS: lane l writes byte 16 l of its piece
+            assert first[w, 0, i] % 1024 == 0 and np.array_equal(first[w, :, i], first[w, 0, i] + 16 * np.arange(64))
+    # operands: A rows split over the wave rows and replicated over the wave columns, conflict-free reads
+    La, sa = gget(B.AXE_DESC_A_OPERAND)
+    ta = table(La, sa)
+    assert ta.shape[1] == 2                                                             # two replicas: the waves wn = 0, 1
+    Ll, sl = gget(B.AXE_DESC_A_LDS)
+    lds_of = dict(zip(map(tuple, np.stack(np.unravel_index(np.arange(prod(sl)), sl), -1).tolist()), table(Ll, sl)[:, 0, 1].tolist()))
+    rows_a, ks = np.unravel_index(np.arange(prod(sa)), sa)
+    for frag in range(T // 2 // 16):
+        for sub in range(2):
+            addr = np.full(64, -1, dtype=np.int64)
+            sel = (ta[:, 0, 3] == 0) & (ta[:, 0, 5] // 8 == sub * (T // 2 // 16) + frag) & (ta[:, 0, 5] % 8 == 0)
+            for idx in np.nonzero(sel)[0]:
+                addr[ta[idx, 0, 4]] = lds_of[(int(rows_a[idx]), int(ks[idx]))] * 2
+            assert (addr >= 0).all() and bank_conflicts(addr) == 1
+    # accumulators and the store map of one tile: every element once
+    for which in (B.AXE_DESC_ACC, B.AXE_DESC_C_STORE):
+        L, shape = gget(which)
+        pts = table(L, shape)[:, 0, :]
+        regs = T * TN // (64 * NW)
+        key = (pts[:, 3] * 64 + pts[:, 4]) * regs + pts[:, 5]
+        assert np.array_equal(np.sort(key), np.arange(T * TN)) and np.all(pts[:, [0, 1, 2]] == 0)
+
+
+def test_grouped_describe_refusals():
+    with pytest.raises(B.AxeError) as e:
+        B.axe_gemm_grouped_describe(_grouped_desc(1000, B.AXE_GROUPED_STREAM), B.AXE_DESC_A_LDS)
+    assert e.value.code == B.AXE_EUNSUPPORTED
+    assert B.axe_gemm_grouped_kernel(_grouped_desc(16)) == B.AXE_GROUPED_STREAM        # 4 rows per group: streamed
+    gated = _grouped_desc(1000, B.AXE_GROUPED_TILES_128, B.AXE_EPI_SWIGLU)
+    B.axe_gemm_grouped_describe(gated, B.AXE_DESC_ACC)
+    with pytest.raises(B.AxeError) as e:
+        B.axe_gemm_grouped_describe(gated, B.AXE_DESC_C_STORE)
+    assert e.value.code == B.AXE_EUNSUPPORTED
+    with pytest.raises(B.AxeError) as e:
+        B.axe_gemm_grouped_describe(_grouped_desc(1000), 99)
+    assert e.value.code == B.AXE_EINVAL
