@@ -42,8 +42,8 @@
 // cycles after issue, a K-step takes about 2900).  160 KiB of LDS hold five 32 KiB blocks:
 //   B: buffer_load ... lds (direct to LDS) into a ring of three blocks, 1 to 1.5 K-steps ahead;
 //   A: buffer_load ... lds into the block of its step's parity, right after the barrier that frees it:
-//      one K-step ahead.  (An earlier version gave A two K-steps by staging it through registers and
-//      ds_write_b128; the writes cost more than the distance was worth: without them 8192^3 runs 7 % faster.)
+//      one K-step ahead.  (Staging A through registers and ds_write_b128 would give it two K-steps; measured,
+//      the writes cost more than the distance is worth: 8192^3 runs 7 % faster without them.)
 //
 // Tile width.  The same kernel body exists with 224 instead of 256 columns of C per tile (7 instead
 // of 8 fragments per wave along N): M = 4096, N = 3584 makes 16 x 16 such tiles, one per CU, where
