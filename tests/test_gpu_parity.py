@@ -416,6 +416,35 @@ def test_gemm_bf16_large_tile(M, N, K):
     assert R.rel_frobenius(c, c_small) < 2e-3
 
 
+# Left to itself the library takes the 64 x 64 tiles for problems of less than 5 x 2^20 elements of C (fp8: 2^20) and the
+# large tile beyond -- with whole tiles, ragged edges or an fp32 output alike; either way the result is the oracle's.
+@pytest.mark.parametrize("M,N,K,dtype,out,want", [(768, 768, 256, "bf16", "bf16", B.AXE_TILE_64x64x32),
+                                                  (2304, 2304, 128, "bf16", "bf16", B.AXE_TILE_256x256x64),
+                                                  (2300, 2312, 128, "f16", "f16", B.AXE_TILE_256x256x64),
+                                                  (2304, 2304, 128, "bf16", "f32", B.AXE_TILE_256x256x64),
+                                                  (512, 512, 256, "fp8", "bf16", B.AXE_TILE_64x64x32),
+                                                  (1024, 1024, 256, "fp8", "bf16", B.AXE_TILE_256x256x64)])
+def test_gemm_kernel_chosen_by_problem_size(M, N, K, dtype, out, want):
+    if dtype == "fp8":
+        g = W.gemm_fp8(M, N, K, 490 + M, scaled=True)
+    else:
+        g = (W.gemm_bf16 if dtype == "bf16" else W.gemm_f16)(M, N, K, 490 + M, std_b=K ** -0.5, out_dtype=out)
+    As, Bs, Cs = W.gemm_specs(g)
+    class _Fake:
+        def data_ptr(self):
+            return 0x1000
+    scales = dict(scale_a=_Fake(), scale_b=_Fake()) if dtype == "fp8" else {}
+    desc = B.GemmDesc(M, N, K, IN_DT[dtype], OUT_DT[out], B.Layout(As), B.Layout(Bs), B.Layout(Cs), M * K, N * K, M * N, **scales)
+    assert B.axe_gemm_tile(desc) == want
+    c = run_gemm(g)
+    rows = np.array([0, 255, 256, M - 1])
+    tol = FP8_TOL if dtype == "fp8" else (1e-5 if out == "f32" else (F16_TOL if dtype == "f16" else BF16_TOL))
+    assert R.rel_frobenius(c[rows], oracle_gemm(g, rows, None)) <= tol
+    cols = np.array([0, 255, 256, N - 1])
+    assert R.rel_frobenius(c[:, cols], oracle_gemm(g, None, cols)) <= tol
+    assert np.isfinite(c).all()
+
+
 # fp32 output of the large tile (16-bit inputs): the accumulators as they are -- only the order of the K sum differs
 # from the oracle's fp64 sum.  nk = 1, 3, 9, and 8 with 17 x 16 tiles chained; pitched C with a guard pattern.
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (512, 768, 192), (768, 512, 576), (4352, 4096, 512)])
