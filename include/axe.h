@@ -170,9 +170,9 @@ int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d
  * per workgroup, chosen when N is a multiple of 224 and the tile count then fills the compute units
  * better, e.g. N = 3584 with M = 4096), or the error axe_gemm would return.
  * Shapes: the 64 x 64 tile takes any M and N.  The 256 x 256 tile needs K a multiple of 64 (fp8: 128); with fp8
- * inputs a 16-bit output and M and N multiples of 256; with 16-bit inputs either a 16-bit output, any M and any
- * N that is a multiple of 8 (edges that do not fill a tile are cut off by the buffer bounds; plain operands
- * only), or an fp32 output with M and N multiples of 256.  Left to itself the library takes the large tile once
+ * inputs a 16-bit output and M and N multiples of 256; with 16-bit inputs a 16-bit or an fp32 output, any M and
+ * any N that is a multiple of 8 (fp32 output: of 4) -- edges that do not fill a tile are cut off by the buffer
+ * bounds (plain operands only).  Left to itself the library takes the large tile once
  * M x N reaches 5 x 2^20 elements (fp8: 2^20); below that the 64 x 64 tiles are faster (a single large tile
  * takes as long as several rounds of small ones). */
 int axe_gemm_tile(const axe_gemm_desc_t* g);

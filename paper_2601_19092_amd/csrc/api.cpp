@@ -585,8 +585,9 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   const bool n224_ok = big_common && !fp8 && !f16 && (g->N % 224 == 0);
   // 16-bit inputs: the 256x256 tile also on edges that do not fill a tile (a lane stores 8 columns at once; a wave's
   // part of C and the tile's part of B are addressed through 32-bit offsets; tile columns are counted in 11 bits)
-  const bool ragged_ok = !fp8 && (g->K % 64 == 0) && (g->N % 8 == 0) && (ldc % 8 == 0) && P.args.out_bf16 && pitch_ok &&
-                         256 * ldc * 2 < (int64_t(1) << 31) && g->N <= 2048 * 256 && g->M < (int64_t(1) << 31);
+  const int64_t cvec = P.args.out_bf16 ? 8 : 4;                    // columns a lane stores at once
+  const bool ragged_ok = !fp8 && (g->K % 64 == 0) && (g->N % cvec == 0) && (ldc % cvec == 0) && pitch_ok &&
+                         256 * ldc * ob < (int64_t(1) << 31) && g->N <= 2048 * 256 && g->M < (int64_t(1) << 31);
   int tile = g->tile_hint;
   if (row_scaled) {                                                // only the 64 x 64 kernel folds a scale per row
     if (tile != AXE_TILE_AUTO && tile != AXE_TILE_64x64x32) {
@@ -626,7 +627,7 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   P.ragged = tile == AXE_TILE_256x256x64 && !big_ok && !blocked && ragged_ok;
   if (tile == AXE_TILE_256x256x64 && !big_ok && !P.ragged) {
     set_error("axe_gemm: the 256x256 tile needs K a multiple of %lld, row pitches below 2^31 / 256 bytes and M, N multiples "
-              "of 256 (16-bit inputs with a 16-bit output: any M, N a multiple of 8; an fp32 output goes with 16-bit inputs only)",
+              "of 256 (16-bit inputs: any M, N a multiple of 8, or of 4 with an fp32 output, which goes with 16-bit inputs only)",
               (long long)bk);
     return AXE_EUNSUPPORTED;
   }

@@ -205,10 +205,10 @@ __device__ __forceinline__ void group_tiles(const GemmArgs& g, int lane, int& t_
 // offset no buffer reaches, which drops the store.
 //
 // OUT32: C is fp32 -- the accumulators are stored as they are, a fragment at a time (a lane's 4 columns are 16
-// bytes).  Dense kernel only.
+// bytes).  Dense kernels only (with ragged edges N is then a multiple of 4).
 template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false, bool OUT32 = false>
 __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
-  static_assert(!OUT32 || (!GROUPED && NB == 256), "the fp32 output exists for the dense 256-wide kernel");
+  static_assert(!OUT32 || ((!GROUPED || RAGGED) && NB == 256), "the fp32 output exists for the dense 256-wide kernels");
   static_assert(!RAGGED || (GROUPED && !GATED && NB == 256), "ragged edges are handled by the grouped 256-wide kernel");
   static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
   static_assert(MR == 8 || (MR == 4 && GROUPED), "128-row tiles exist for the grouped kernel");
@@ -380,9 +380,10 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
         if (cw == 0) rows = 0;
         c_cw = cw;
       }
-      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * (16 * MR)) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
-                    rows ? (uint32_t)(((rows - 1) * g.ldc + cw) * 2) : 0u);
-      c_rowblk = (int)(16 * g.ldc * 2);
+      constexpr int OBG = OUT32 ? 4 : 2;                             // bytes per element of C
+      rc = raw_rsrc((uint8_t*)g.C + (((int64_t)row0 + wm * (16 * MR)) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW) * OBG,
+                    rows ? (uint32_t)(((rows - 1) * g.ldc + cw) * OBG) : 0u);
+      c_rowblk = (int)(16 * g.ldc * OBG);
       return;
     }
     int tm, tn;
@@ -397,7 +398,13 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   auto store_fragment32 = [&](int i, int j) __attribute__((always_inline)) {
     const f32x4 d = acc[i][j];                                     // (a copy in VGPRs: the accumulators live in AGPRs)
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 64);
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff32), "s"(rc), "s"(soff) : "memory");
+    int voff = c_voff32;
+    if constexpr (RAGGED) {                                          // the lane's 4 columns lie past N: an offset no descriptor reaches
+      int l;
+      asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+      if (j * 16 + 4 * (l >> 4) + 4 > c_cw) voff = (int)0x80000000u;
+    }
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
     __builtin_amdgcn_sched_barrier(0);                             // one fragment at a time: copied out of the AGPRs, stored, cleared
@@ -621,6 +628,9 @@ __global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_gated_kernel(Gemm
 // fp32 output (plain or blocked operands)
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_f32out_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true, false, false, 8, false, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_f32out_kernel(GemmArgs g) { gemm_bf16_256_body<256, false, true, false, true, 8, false, true>(g); }
+// dense with ragged edges and an fp32 output (any M, N a multiple of 4)
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_ragged_f32out_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, false, 8, true, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_256_ragged_f32out_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true, 8, true, true>(g); }
 // dense with ragged edges (any M, N a multiple of 8)
 __global__ __launch_bounds__(256, 1) void gemm_bf16_256_ragged_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, false, 8, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_256_ragged_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true, 8, true>(g); }
@@ -694,7 +704,10 @@ hipError_t launch_gemm_bf16_256_ragged(const GemmArgs& g, hipStream_t s) {
   if (chain && nwg > cus) nwg = (nwg + cus - 1) / cus * cus;      // whole rounds of workgroups
   nwg = (nwg + 7) / 8 * 8;
   if (nwg > 0x7fffffff || g.groups != 1) return hipErrorInvalidValue;
-  if (g.f16)
+  if (!g.out_bf16) {
+    if (g.f16) hipLaunchKernelGGL(gemm_f16_256_ragged_f32out_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+    else hipLaunchKernelGGL(gemm_bf16_256_ragged_f32out_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  } else if (g.f16)
     hipLaunchKernelGGL(gemm_f16_256_ragged_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
   else
     hipLaunchKernelGGL(gemm_bf16_256_ragged_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);

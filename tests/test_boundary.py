@@ -133,7 +133,8 @@ def test_gemm_family_matching_and_errors():
     assert _tile_rc(_gemm_desc(M=4096, N=4096, in_dtype=B.AXE_F16, out_dtype=B.AXE_F32)) == BIG
     assert _tile_rc(_gemm_desc(M=4096, N=4096, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
     assert _tile_rc(_gemm_desc(M=4096, N=4096, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_F32, tile=BIG)) == B.AXE_EUNSUPPORTED
-    assert _tile_rc(_gemm_desc(M=4000, N=4096, out_dtype=B.AXE_F32, tile=BIG)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(_gemm_desc(M=4000, N=4100, out_dtype=B.AXE_F32, tile=BIG)) == BIG                   # ragged edges as well
+    assert _tile_rc(_gemm_desc(M=4000, N=4098, out_dtype=B.AXE_F32, tile=BIG)) == B.AXE_EUNSUPPORTED
     # 16-bit inputs: the large tile takes ragged edges (any M, N a multiple of 8) -- on request, and by itself once
     # the problem is a few tiles large; fp8 and odd N stay with whole tiles / the small tile
     assert _tile_rc(_gemm_desc(M=200, tile=B.AXE_TILE_256x256x64)) == B.AXE_TILE_256x256x64
@@ -142,7 +143,8 @@ def test_gemm_family_matching_and_errors():
     assert _tile_rc(_gemm_desc(M=3000, N=3000, in_dtype=B.AXE_F16, out_dtype=B.AXE_F16)) == B.AXE_TILE_256x256x64
     assert _tile_rc(_gemm_desc(M=3000, N=3001)) == B.AXE_TILE_64x64x32
     assert _tile_rc(_gemm_desc(M=3000, N=3004, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
-    assert _tile_rc(_gemm_desc(M=3000, N=3000, out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(_gemm_desc(M=3000, N=3000, out_dtype=B.AXE_F32)) == B.AXE_TILE_256x256x64    # fp32: N a multiple of 4
+    assert _tile_rc(_gemm_desc(M=3000, N=3002, out_dtype=B.AXE_F32)) == B.AXE_TILE_64x64x32
     assert _tile_rc(_gemm_desc(M=200, in_dtype=B.AXE_FP8_E4M3, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
     assert _tile_rc(_gemm_desc(M=3000, N=3000, in_dtype=B.AXE_FP8_E4M3)) == B.AXE_TILE_64x64x32
     # the shard of a column-parallel layer: extent-1 device iter + device offset are dropped (rule D0)

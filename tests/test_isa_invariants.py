@@ -63,6 +63,7 @@ CASES = [("kernels_gemm_bf16.hip", "gemm_bf16_256_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_256_grouped_gated_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_256_f32out_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_256_ragged_kernel", {8}, True, 0),
+         ("kernels_gemm_bf16.hip", "gemm_f16_256_ragged_f32out_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_256_ragged_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_bf16_128_grouped_kernel", {8}, True, 0),
          ("kernels_gemm_bf16.hip", "gemm_f16_128_grouped_gated_kernel", {8}, True, 0),
