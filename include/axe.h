@@ -107,9 +107,10 @@ int axe_layout_eval(const axe_layout_t* L, int32_t rank, const int64_t* shape,
  * Semantics of replication: every replica address of dst is written; src is read at its first
  * replica (all replica digits 0).  Words of dst no logical index maps to are left untouched.
  * Data are moved as raw bits (no float interpretation).
- * Errors: AXE_ESHAPE, AXE_EALIAS (dst's D part not provably injective -- the test is the
- * sufficient one: iters on the memory axis sorted by |stride| must each step over the span of
- * all smaller ones), AXE_ERANGE (some address outside [0, *_elems)), AXE_EINVAL. */
+ * Errors: AXE_ESHAPE, AXE_EALIAS (dst not provably injective, replicas included: two (logical
+ * element, replica) pairs could write one address -- the test is the sufficient one: the shard and
+ * replica iters on the memory axis, sorted by |stride|, must each step over the span of all smaller
+ * ones), AXE_ERANGE (some address outside [0, *_elems)), AXE_EINVAL. */
 int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank, const int64_t* shape,
                  int32_t elem_bytes, int32_t mem_axis,
                  const void* d_src, int64_t src_elems, void* d_dst, int64_t dst_elems, void* stream);

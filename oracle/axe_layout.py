@@ -404,44 +404,41 @@ class LayoutError(Exception):
 
 
 def group(D: Sequence[Iter], shape: Sequence[int]) -> List[List[Iter]]:
-    """Split the iters of D left to right into len(shape) consecutive blocks whose extent
-    products are shape[i]; an iter is split (e, s, a) -> (g, (e/g)s, a), (e/g, s, a) with
-    g = gcd(e, remaining) when it straddles a block boundary.  Raises LayoutError when the
-    gcd step cannot advance or the iters run out."""
+    """Grouping by a shape (App. B, Alg. 1 defines the result): refine D, without changing f_D, so that it
+    falls into len(shape) consecutive blocks with extent products shape[i].
+
+    Stated through prefix products: read left to right, the iters of D place their extents at the mixed-radix
+    positions 1, e_0, e_0 e_1, ...; block i has to end at position shape[0] ... shape[i].  An iter that ends
+    before or at the end of the open block goes into it whole; an iter inside which the block ends is cut
+    there -- (e, s, a) with e = q t becomes (q, t s, a), (t, s, a), the split lemma of App. B -- which needs
+    the block's remaining extent q to divide e.  When neither divides the other no refinement exists and a
+    LayoutError is raised (the algorithm's gcd step would reach 1).  Unit iters carry no digit; each stays in
+    the block of the piece before it (block 0 if there is none)."""
     if prod(it.extent for it in D) != prod(shape):
         raise LayoutError("shape is not admitted")
-    src = list(D)
-    j = 0
-    blocks: List[List[Iter]] = []
+    ends = []                                   # position at which block i is complete
     for T in shape:
-        blk: List[Iter] = []
-        cur = 1
-        while cur < T:
-            if j >= len(src):
-                raise LayoutError("ran out of iters")
-            it = src[j]
-            rem = T // cur
-            g = gcd(it.extent, rem)
-            if g == 1:
-                if it.extent == 1:      # a unit iter cannot advance any block; keep it here
-                    blk.append(it)
-                    j += 1
-                    continue
-                raise LayoutError(f"iter {it} cannot be split to complete a block of {T}")
-            tail = it.extent // g
-            blk.append(Iter(g, tail * it.stride, it.axis))
-            cur *= g
-            if tail > 1:
-                src[j] = Iter(tail, it.stride, it.axis)
+        ends.append((ends[-1] if ends else 1) * T)
+    blocks: List[List[Iter]] = [[] for _ in shape]
+    b, pos = 0, 1                               # block being filled, product of the extents placed so far
+    for it in D:
+        left = it.extent                        # extent of the part of this iter not placed yet
+        if left == 1:
+            blocks[b].append(it)
+            continue
+        while left > 1:
+            while pos == ends[b]:               # complete blocks (also the empty ones of unit shape entries)
+                b += 1
+            need = ends[b] // pos
+            if need % left == 0:
+                q = left
+            elif left % need == 0:
+                q = need
             else:
-                j += 1
-        # unit-extent iters directly after a completed block stay with that block
-        while j < len(src) and src[j].extent == 1 and T == cur:
-            blk.append(src[j])
-            j += 1
-        blocks.append(blk)
-    if j != len(src):
-        raise LayoutError("iters left over after the last block")
+                raise LayoutError(f"iter {it}: a block of {shape[b]} ends inside it at a position that does not divide it")
+            left //= q
+            blocks[b].append(Iter(q, left * it.stride, it.axis))
+            pos *= q
     return blocks
 
 

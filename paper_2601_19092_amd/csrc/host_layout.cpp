@@ -204,7 +204,10 @@ int check_range(const MemLayout& L, int64_t elems, const char* what) {
 }
 
 bool provably_injective(const MemLayout& L) {
+  // shard and replica iters together: every (logical element, replica) pair needs an address of its own,
+  // e.g. D = [(4, 1)], R = [(2, 2)] writes address 2 from element 0 (replica 1) and from element 2 (replica 0)
   std::vector<HIter> v = L.D;
+  v.insert(v.end(), L.R.begin(), L.R.end());
   std::sort(v.begin(), v.end(), [](const HIter& a, const HIter& b) {
     int64_t x = a.s < 0 ? -a.s : a.s, y = b.s < 0 ? -b.s : b.s;
     return x < y;

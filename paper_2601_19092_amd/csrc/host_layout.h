@@ -49,7 +49,8 @@ int check_shape(const HLayout& L, int32_t rank, const int64_t* shape, const char
 int reduce_to_memory(const HLayout& L, int mem_axis, MemLayout& out, const char* what);
 // AXE_ERANGE unless every address lies in [0, elems).
 int check_range(const MemLayout& L, int64_t elems, const char* what);
-// Sufficient test for injectivity of the D part on the memory axis.
+// Sufficient test that no two (logical element, replica) pairs share an address on the memory axis:
+// the strides of the shard and replica iters together nest.
 bool provably_injective(const MemLayout& L);
 void canon_D(std::vector<HIter>& D);
 // Common refinement of two digit systems with equal total extent; false if none exists.

@@ -277,7 +277,8 @@ hipError_t launch_relayout_joint(const RelayoutPlan& p, int unit_bytes, const vo
 // takes a T x T tile of the two digits, reads it with 16-byte loads along the source-fast digit
 // (T * EB = 128 to 512 contiguous bytes per tile row), parks it in LDS, and writes it with 16-byte
 // stores along the destination-fast digit, each store gathering its 16 / EB elements from as many
-// LDS rows.  LDS rows are padded by one word so that the gather walks over distinct banks.
+// LDS rows.  The LDS image is XOR-swizzled, not padded: 16-byte chunk c of row r sits at chunk position
+// c ^ (r / elements per chunk), which keeps the gather on distinct banks for every element size.
 // ------------------------------------------------------------------------------------------
 template <int EB, bool NT>
 __global__ __launch_bounds__(256) void relayout_transpose_kernel(TransposePlan p, const uint8_t* __restrict__ src,

@@ -89,6 +89,9 @@ def test_relayout_rejects_before_launch():
     # destination where two logical elements share an address
     alias = W.spec([(8, 4, "m"), (8, 1, "m")])
     assert _relayout_rc(rm, alias, (8, 8)) == B.AXE_EALIAS
+    # ... or a replica of one element lands on another element: element 0 writes {0, 2}, element 2 writes {2, 4}
+    rep_alias = W.spec([(4, 1, "m")], R=[(2, 2, "m")])
+    assert _relayout_rc(W.spec([(4, 1, "m")]), rep_alias, (4,), d_elems=6) == B.AXE_EALIAS
     # a sharded axis of extent > 1 cannot live on one GPU
     sharded = W.spec([(2, 1, "gpuid"), (4, 8, "m"), (8, 1, "m")])
     assert _relayout_rc(sharded, rm, (8, 8)) == B.AXE_EALIAS

@@ -219,3 +219,13 @@ def test_plan_eval_matches_oracle(hc):
         shp = (C.c_int64 * 1)(n)
         assert hc.axe_layout_eval(C.byref(bl.c), 1, shp, n, None, out.ctypes.data, None) == 0
         assert np.array_equal(out, R.evaluate_np(L, np.arange(n), L.axes()))
+
+
+def test_plan_replicated_destination_whose_replicas_step_over_the_shard_part(hc):
+    """Replica strides that nest with the shard strides are accepted and every replica is written (the aliasing
+    test looks at shard and replica iters together; the overlapping case is refused in test_boundary)."""
+    src_L = Layout.make((4,), (1,))
+    dst_L = Layout.make((4,), (1,), R=((2,), (4,)))
+    words = np.array([11, 22, 33, 44], dtype=np.uint16)
+    got, want = host_relayout(hc, src_L, dst_L, (4,), words, 8)
+    assert np.array_equal(got, want) and list(got) == [11, 22, 33, 44, 11, 22, 33, 44]
