@@ -34,12 +34,49 @@ def log(*a):
 MIN_WARM_MS = 40.0        # companions: see time_loop
 
 
+def settle(fn, max_ms=400.0, window=8, tol=0.015):
+    """Launches fn until its per-launch device time has stopped falling: after the host has been busy (generating
+    inputs) the GPU's clocks take a while to come up, and a timed region that starts inside that ramp measures
+    the ramp (the same 0.73 ms kernel reads 0.86 ms in the first 20 ms).  Stops when the means of two consecutive windows of
+    `window` launches agree within `tol`, or after max_ms.  Returns what it did, for the JSON line: it is extra
+    untimed warm-up, before the `--warmup` steps, and does no part of the timed work."""
+    import torch
+    t0 = time.perf_counter()
+    prev, n, hist = None, 0, []
+    while (time.perf_counter() - t0) * 1e3 < max_ms:
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(window + 1)]
+        evs[0].record()
+        for k in range(window):
+            fn(n + k)
+            evs[k + 1].record()
+        torch.cuda.synchronize()
+        n += window
+        cur = sum(evs[k].elapsed_time(evs[k + 1]) for k in range(window)) / window
+        hist.append(cur)
+        if prev is not None and abs(cur - prev) <= tol * prev:
+            break
+        prev = cur
+    return {"launches": n, "ms": (time.perf_counter() - t0) * 1e3, "first_window_kernel_ms": hist[0], "last_window_kernel_ms": hist[-1]}
+
+
+def per_launch(fn, steps):
+    """Device time of each of `steps` launches (one event pair per launch), after the timed region."""
+    import torch
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    evs[0].record()
+    for k in range(steps):
+        fn(k)
+        evs[k + 1].record()
+    torch.cuda.synchronize()
+    return sorted(evs[k].elapsed_time(evs[k + 1]) for k in range(steps))
+
+
 def time_loop(fn, steps, warmup, min_warm_ms=None):
     """Returns (wall ms per step, device ms per step from HIP events on the launch stream).
-    After the host has been busy for a while (generating inputs) the first 10 - 15 ms of GPU work run at lower
+    After the host has been busy for a while (generating inputs) the first 10 - 20 ms of GPU work run at lower
     clocks (measured: a 0.2 ms kernel timed after 20 warm-up launches reads 10 % slower than after 200).  The
-    headline step does exactly `warmup` untimed steps (0.8 ms each: long enough); the shorter companion
-    kernels keep warming up until min_warm_ms have passed."""
+    headline step is brought to a steady clock by settle() and then does exactly `warmup` untimed steps; the
+    companion kernels keep warming up until min_warm_ms have passed."""
     import torch
     min_warm_ms = MIN_WARM_MS if min_warm_ms is None else min_warm_ms
     t_w = time.perf_counter()
@@ -97,13 +134,21 @@ def gemm_setup(g, n_sets, device_axis=False, tile=0):
     return step, sets, desc
 
 
-def bench_gemm(name, g, steps, warmup, n_sets=2, device_axis=False, min_warm_ms=None):
+def bench_gemm(name, g, steps, warmup, n_sets=2, device_axis=False, min_warm_ms=None, headline=False):
     step, sets, desc = gemm_setup(g, n_sets, device_axis)
+    st = settle(step) if headline else None
     wall, devms = time_loop(step, steps, warmup, min_warm_ms)
     flops = 2.0 * g.M * g.N * g.K
     r = {"workload": name, "ms_per_step": wall, "kernel_ms": devms, "tflops": flops / (wall * 1e-3) / 1e12,
          "kernel_tflops": flops / (devms * 1e-3) / 1e12}
     r["frac_of_peak"] = r["kernel_tflops"] / PEAK["fp8" if g.dtype == "fp8" else "bf16"]
+    if headline:
+        pl = per_launch(step, steps)
+        r["settle"] = st
+        r["per_launch_kernel_ms"] = {"min": pl[0], "median": pl[len(pl) // 2], "max": pl[-1]}
+        log(f"[bench] {name}: clocks settled after {st['launches']} untimed launches ({st['ms']:.0f} ms; per launch "
+            f"{st['first_window_kernel_ms']:.4f} -> {st['last_window_kernel_ms']:.4f} ms); per-launch times after the timed region: "
+            f"min {pl[0]:.4f} median {pl[len(pl) // 2]:.4f} max {pl[-1]:.4f} ms")
     log(f"[bench] {name}: {wall:.4f} ms/step wall, {devms:.4f} ms device, {r['kernel_tflops']:.1f} TFLOP/s "
         f"({100 * r['frac_of_peak']:.1f}% of peak)")
     return r, sets
@@ -329,24 +374,50 @@ def bench_ceilings(g3, g5, steps=20, warmup=5):
               torch.empty(n, dtype=torch.int16, device="cuda")) for _ in range(4)]
     _, devms = time_loop(lambda i: pairs[i % 4][1].copy_(pairs[i % 4][0]), 40, 10)
     out["device_copy_GBps"] = 2.0 * n * 2 / (devms * 1e-3) / 1e9
+    # plain HBM streams with the relayout's access shape (128-bit non-temporal, four per thread), same size, same rotation
+    P.axe_probe_stream.restype = C.c_int
+    P.axe_probe_stream.argtypes = [C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    for key, kind, moved in (("stream_copy_GBps", 0, 2.0), ("stream_read_GBps", 1, 1.0), ("stream_write_GBps", 2, 1.0)):
+        def launch(i, kind=kind):
+            rc = P.axe_probe_stream(kind, pairs[i % 4][0].data_ptr(), pairs[i % 4][1].data_ptr(), n * 2, torch.cuda.current_stream().cuda_stream)
+            if rc:
+                sys.exit(f"bench.py: axe_probe_stream failed ({rc})")
+        _, devms = time_loop(launch, 40, 10)
+        out[key] = moved * n * 2 / (devms * 1e-3) / 1e9
     log(f"[bench] measured ceilings: register-only MFMA loop bf16 {out['mfma_bf16_register_only_tflops']:.0f} TFLOP/s, "
         f"fp8 {out['mfma_fp8_register_only_tflops']:.0f} TFLOP/s on samples of the inputs; "
-        f"plain device copy of 128 MiB {out['device_copy_GBps']:.0f} GB/s")
+        f"128 MiB rotating over 4 pairs: library device copy {out['device_copy_GBps']:.0f} GB/s, plain 128-bit non-temporal "
+        f"stream copy {out['stream_copy_GBps']:.0f} GB/s (read + write), read only {out['stream_read_GBps']:.0f} GB/s, "
+        f"write only {out['stream_write_GBps']:.0f} GB/s")
     return out
 
 
-def cpu_baseline(g, budget_rows=1536):
-    """The CPU oracle as it stands, on the first `budget_rows` rows of the same GEMM."""
+def cpu_baseline(g, budget_rows=2048):
+    """The CPU oracle as it stands, on the first `budget_rows` rows of the same GEMM (all rows when budget_rows is
+    None), and the oracle's relayout of the whole of configuration 2 beside it."""
     from oracle import axe_ref as R
-    rows = np.arange(budget_rows)
+    from oracle.axe_layout import Layout
+    from paper_2601_19092_amd import workloads as W
+    rows = None if budget_rows is None or budget_rows >= g.M else np.arange(budget_rows)
+    nrows = g.M if rows is None else budget_rows
     R.gemm_ref(g.a_mk[:2], g.b_nk.T[:, :2], R.AXE_BF16)        # builds / loads the C oracle outside the timing
     t0 = time.perf_counter()
     R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_BF16, rows=rows)
     dt = time.perf_counter() - t0
-    fl = 2.0 * budget_rows * g.N * g.K
+    fl = 2.0 * nrows * g.N * g.K
+    # relayout oracle (NumPy scatter through both layouts' evaluations), whole configuration 2
+    n = 8192
+    words = W.config2("uniform").reshape(-1)
+    dst = np.zeros(n * n, dtype=np.uint16)
+    t1 = time.perf_counter()
+    R.relayout_ref(Layout.from_spec(W.row_major_spec(n, n)), Layout.from_spec(W.blocked_swizzled_spec(n, n)), (n, n), words, dst)
+    dt_r = time.perf_counter() - t1
+    what = f"all {g.M} rows" if rows is None else f"rows 0..{budget_rows - 1}"
     return {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": R.oracle_threads(), "kind": "oracle",
-            "sample": f"rows 0..{budget_rows - 1} of C (all {g.N} columns, K = {g.K}) of the same bf16 GEMM, "
-                      f"plain fp64 triple loop, {dt:.1f} s"}
+            "sample": f"{what} of C (all {g.N} columns, K = {g.K}) of the same bf16 GEMM, plain fp64 triple loop, {dt:.1f} s",
+            "whole_config": rows is None,
+            "relayout_cfg2": {"value": 2.0 * n * n * 2 / dt_r / 1e9, "unit": "GB/s", "cores": 1, "kind": "oracle",
+                              "sample": f"the whole 8192 x 8192 bf16 relayout of configuration 2 (NumPy evaluation of both layouts + scatter), {dt_r:.1f} s"}}
 
 
 def main():
@@ -356,6 +427,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--only", default="", help="comma list of: gemm,relayout,fp8,shard,ragged,grouped,small,eval,ceilings,cpu (default all)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle timing")
+    ap.add_argument("--cpu-full", action="store_true", help="time the CPU oracle on the whole of configuration 3 (about 1.5 minutes on 16 cores) instead of a quarter of its rows")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding across GPUs); use --gpus 1")
@@ -371,7 +443,7 @@ def main():
     log("[bench] generating configuration 3 (bf16 GEMM 8192^3) on the host ...")
     g3 = W.config3()
     head, _ = bench_gemm("bf16 GEMM M=N=K=8192, A row-major, B column-major, bf16 out", g3, args.steps, args.warmup,
-                         min_warm_ms=0)          # the headline: exactly args.warmup untimed steps
+                         min_warm_ms=0, headline=True)   # clocks settled first, then exactly args.warmup untimed steps
     comp = {}
     if want("relayout"):
         comp["relayout_cfg2"] = bench_relayout(max(20, args.steps), args.warmup)
@@ -406,11 +478,12 @@ def main():
             c["gemm_cfg5_frac_of_measured"] = comp["gemm_cfg5_fp8_block_scaled"]["kernel_tflops"] / c["mfma_fp8_register_only_tflops"]
         if "relayout_cfg2" in comp:
             c["relayout_cfg2_frac_of_measured"] = comp["relayout_cfg2"]["rotating"]["GBps"] / c["device_copy_GBps"]
+            c["relayout_cfg2_frac_of_stream_copy"] = comp["relayout_cfg2"]["rotating"]["GBps"] / c["stream_copy_GBps"]
         comp["measured_ceilings"] = c
     cpu = None
     if not args.no_cpu and want("cpu"):
         log("[bench] timing the CPU oracle on a bounded sample ...")
-        cpu = cpu_baseline(g3)
+        cpu = cpu_baseline(g3, None if args.cpu_full else 2048)
         log(f"[bench] cpu oracle: {cpu['value'] * 1e3:.2f} GFLOP/s on {cpu['cores']} threads")
 
     flops = 2.0 * g3.M * g3.N * g3.K
@@ -423,7 +496,9 @@ def main():
                                "fp32 accumulate, bf16 output; 256x256x64 tiles described as Axe layouts"},
         "roofline": {"bound": "mfma", "achieved": head["kernel_tflops"], "peak": PEAK["bf16"], "unit": "TFLOP/s",
                      "frac": head["kernel_tflops"] / PEAK["bf16"], "traffic": None,
-                     "kernel": "gemm_bf16_256_kernel", "flops_per_launch": flops, "kernel_ms": head["kernel_ms"]},
+                     "kernel": "gemm_bf16_256_kernel", "flops_per_launch": flops, "kernel_ms": head["kernel_ms"],
+                     "per_launch_kernel_ms": head["per_launch_kernel_ms"]},
+        "clock_settle": head["settle"],           # extra untimed launches before the --warmup steps (see settle())
         "cpu_baseline": cpu,
         "companions": comp,
     }

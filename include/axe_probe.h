@@ -1,4 +1,4 @@
-/* Measurement aids of the Axe-layout GEMM path: ceilings of the matrix pipe.
+/* Measurement aids of the Axe-layout hot path: measured ceilings of the matrix pipe and of plain HBM streams.
  *
  * Not part of the hot path and not part of libaxe_hip.so: these live in libaxe_probe.so, which only
  * the benchmark's --ceilings mode loads.  They answer the question the roofline fraction alone
@@ -32,6 +32,13 @@ extern "C" {
  * argument, 2 if the launch failed.  Nothing is allocated. */
 int axe_probe_mfma(int32_t fp8, const void* sample, size_t sample_bytes, int32_t iters, float* sink, size_t sink_floats,
                    double* flops, void* stream);
+
+/* Launches, on `stream`, one pass of a plain HBM stream over `bytes` bytes (a multiple of 16; buffers 16-byte
+ * aligned): 128-bit non-temporal accesses, four per thread, the access shape of the relayout kernels without
+ * any address arithmetic.  kind 0: copy src -> dst; 1: read src only (dst may be NULL); 2: write dst only
+ * (src ignored).  The figure the relayout can be held against on the box it runs on.  Asynchronous; returns 0,
+ * 1 for a bad argument, 2 if the launch failed.  Nothing is allocated. */
+int axe_probe_stream(int32_t kind, const void* src, void* dst, size_t bytes, void* stream);
 
 #ifdef __cplusplus
 }

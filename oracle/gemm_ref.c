@@ -51,10 +51,11 @@ static double dec_e4m3(uint8_t c) {
     return s ? -v : v;
 }
 
-static double load(const void* p, int64_t idx, int dtype) {
+/* e4m3 has 256 codes: the value of each, by dec_e4m3, looked up instead of decoded again for every product */
+static double load(const void* p, int64_t idx, int dtype, const double* e4m3_values) {
     if (dtype == ORACLE_BF16) return dec_bf16(((const uint16_t*)p)[idx]);
     if (dtype == ORACLE_F16) return dec_f16(((const uint16_t*)p)[idx]);
-    return dec_e4m3(((const uint8_t*)p)[idx]);
+    return e4m3_values[((const uint8_t*)p)[idx]];
 }
 
 int axe_oracle_threads(void) {
@@ -82,6 +83,8 @@ int axe_oracle_gemm(int dtype, int64_t M, int64_t N, int64_t K,
     if (sA && (bs <= 0 || bs_am <= 0)) return -3;
     (void)M; (void)N;
     int64_t nkb = sA ? (K + bs - 1) / bs : 0;
+    double v8[256];
+    for (int c = 0; c < 256; ++c) v8[c] = dec_e4m3((uint8_t)c);
 #pragma omp parallel for collapse(2) schedule(static)
     for (int64_t r = 0; r < nrows; ++r) {
         for (int64_t c = 0; c < ncols; ++c) {
@@ -89,13 +92,13 @@ int axe_oracle_gemm(int dtype, int64_t M, int64_t N, int64_t K,
             double acc = 0.0;
             if (!sA) {
                 for (int64_t k = 0; k < K; ++k)
-                    acc += load(A, i * a_sm + k * a_sk, dtype) * load(B, k * b_sk + j * b_sn, dtype);
+                    acc += load(A, i * a_sm + k * a_sk, dtype, v8) * load(B, k * b_sk + j * b_sn, dtype, v8);
             } else {
                 for (int64_t kb = 0; kb < nkb; ++kb) {
                     double part = 0.0;
                     int64_t k1 = (kb + 1) * bs < K ? (kb + 1) * bs : K;
                     for (int64_t k = kb * bs; k < k1; ++k)
-                        part += load(A, i * a_sm + k * a_sk, dtype) * load(B, k * b_sk + j * b_sn, dtype);
+                        part += load(A, i * a_sm + k * a_sk, dtype, v8) * load(B, k * b_sk + j * b_sn, dtype, v8);
                     acc += (double)sA[(i / bs_am) * nkb + kb] * (double)sB[(j / bs) * nkb + kb] * part;
                 }
             }

@@ -71,7 +71,46 @@ __global__ __launch_bounds__(512, 1) void probe_fp8_kernel(const i32x8* __restri
     for (int j = 0; j < 4; ++j) s += acc[i][j][0] + acc[i][j][1] + acc[i][j][2] + acc[i][j][3];
   out[blockIdx.x * 512 + threadIdx.x] = s;
 }
+// HBM streams: what this machine's memory system gives a plain kernel -- 16 bytes per lane and access, four accesses per
+// thread issued together, non-temporal, one pass over the buffers.  KIND 0: copy, 1: read only (the words are
+// folded into a sum nobody needs, written only if it has an impossible value so that the loads stay), 2: write only.
+typedef __attribute__((ext_vector_type(4))) unsigned int probe_u32x4;
+template <int KIND>
+__global__ __launch_bounds__(256) void probe_stream_kernel(const probe_u32x4* __restrict__ src, probe_u32x4* __restrict__ dst, size_t n) {
+  const size_t i = (size_t)blockIdx.x * 1024 + threadIdx.x;
+  probe_u32x4 v[4];
+#pragma unroll
+  for (int u = 0; u < 4; ++u) {
+    if (KIND == 2) v[u] = probe_u32x4{(unsigned)i, 1u, 2u, 3u};
+    else if (i + u * 256 < n) v[u] = __builtin_nontemporal_load(&src[i + u * 256]);
+    else v[u] = probe_u32x4{0u, 0u, 0u, 0u};
+  }
+  if (KIND == 1) {
+    unsigned x = 0;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) x ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+    if (x == 0x9e3779b9u && n == 1) dst[0] = v[0];                 // (never with the buffers the benchmark passes)
+    return;
+  }
+#pragma unroll
+  for (int u = 0; u < 4; ++u)
+    if (i + u * 256 < n) __builtin_nontemporal_store(v[u], &dst[i + u * 256]);
+}
 }  // namespace
+
+extern "C" int axe_probe_stream(int32_t kind, const void* src, void* dst, size_t bytes, void* stream) {
+  if (kind < 0 || kind > 2 || bytes == 0 || bytes % 16 || (kind != 2 && !src) || (kind != 1 && !dst) ||
+      (((uintptr_t)src | (uintptr_t)dst) & 15))
+    return 1;
+  const size_t n = bytes / 16, nwg = (n + 1023) / 1024;
+  if (nwg > 0x7fffffffu || (kind == 1 && n < 2)) return 1;       // (n >= 2: the read-only kernel's guarded store can never happen)
+  const dim3 grid((unsigned)nwg), block(256);
+  hipStream_t st = (hipStream_t)stream;
+  if (kind == 0) hipLaunchKernelGGL(probe_stream_kernel<0>, grid, block, 0, st, (const probe_u32x4*)src, (probe_u32x4*)dst, n);
+  else if (kind == 1) hipLaunchKernelGGL(probe_stream_kernel<1>, grid, block, 0, st, (const probe_u32x4*)src, (probe_u32x4*)(dst ? dst : (void*)src), n);
+  else hipLaunchKernelGGL(probe_stream_kernel<2>, grid, block, 0, st, (const probe_u32x4*)dst, (probe_u32x4*)dst, n);
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
 
 extern "C" int axe_probe_mfma(int32_t fp8, const void* sample, size_t sample_bytes, int32_t iters, float* sink,
                               size_t sink_floats, double* flops, void* stream) {

@@ -540,17 +540,67 @@ def test_gemm_fp8_large_tile(M, N, K, scaled):
 
 
 # ----------------------------------------------------------------------------- full-size configurations
-def full_size_check(g: W.GemmInputs, tol, device_axis=False, seed=0, tile=B.AXE_TILE_AUTO):
-    """Whole C on the GPU in the launch configuration the benchmark times, against the whole fp64 C of
-    the oracle: the global bound and the bound on every 128 x 128 tile.  As extras, two randomised
-    projections (C v and u^T C, computed in fp64 from the inputs, independently of the oracle's C)."""
-    c = run_gemm(g, device_axis=device_axis, tile=tile)
-    assert np.isfinite(c).all()
-    ref = oracle_gemm(g)
-    err = check_gemm(c, ref, tol)
-    rng = np.random.default_rng(seed)
+# Whole C on the GPU in the launch configuration the benchmark times, against the whole fp64 C of the oracle:
+# the bound on every 128 x 128 tile (hence on the whole matrix: the squared errors of the tiles add up).  The oracle's
+# plain triple loop takes one to two minutes for an 8192^3 problem, so a case is checked in bands of rows, one test
+# each: the GPU result is computed once per case and kept for its bands.
+FULL_CASES = {
+    # name: (inputs, keywords of run_gemm, tolerance, bands)
+    "config3": (lambda: W.config3(), {}, BF16_TOL, 8),
+    "config4": (lambda: W.config4(), dict(device_axis=True), BF16_TOL, 2),
+    "config5": (lambda: W.config5(), {}, FP8_TOL, 8),
+    # configuration 5's shape with power-of-two (E8M0) block scales, and fp8 without scales: the matrix cores' scale path
+    "config5_e8m0": (lambda: W.gemm_fp8(8192, 8192, 8192, 19097, scaled="e8m0"), {}, FP8_TOL, 8),
+    "e8m0_17x16_tiles_66_ksteps": (lambda: W.gemm_fp8(4352, 4096, 8448, 96, scaled="e8m0"), {}, FP8_TOL, 2),   # code registers refilled
+    "fp8_unscaled_4096": (lambda: W.gemm_fp8(4096, 4096, 4096, 97, scaled=False), {}, FP8_TOL, 1),
+    # more tiles than compute units, so every workgroup walks two tiles as one pipeline, on a tile grid that is not made
+    # of 16 x 16 blocks (the other workgroup -> tile order); the last 16 workgroups get a second tile, the others do not
+    "chained_17x16_bf16": (lambda: W.gemm_bf16(4352, 4096, 512, 91), {}, BF16_TOL, 1),
+    # 224-column tiles, 17 x 16 of them (left to itself the library takes 17 x 14 tiles of 256 x 256 here)
+    "chained_17x16_bf16_224": (lambda: W.gemm_bf16(4352, 3584, 512, 93), dict(tile=B.AXE_TILE_256x224x64), BF16_TOL, 1),
+    # fp8 with fp32 scales, 66 K-steps: the register of block scales is refilled inside each chained tile
+    "chained_17x16_fp8": (lambda: W.gemm_fp8(4352, 4096, 8448, 92, scaled=True), {}, FP8_TOL, 2),
+}
+_FULL = {}
+
+
+def full_size_case(name):
+    """(inputs, C of the GPU decoded to fp64) of one case; one case is held at a time."""
+    if name not in _FULL:
+        _FULL.clear()
+        make, kw, _, _ = FULL_CASES[name]
+        g = make()
+        _FULL[name] = (g, run_gemm(g, **kw))
+    return _FULL[name]
+
+
+def band_rows(M, band, nbands):
+    per = -(-(M // 128) // nbands) * 128                       # whole 128-row tile rows per band
+    return np.arange(band * per, min(M, (band + 1) * per))
+
+
+@pytest.mark.parametrize("name,band", [(n, b) for n, c in FULL_CASES.items() for b in range(c[3])])
+def test_gemm_full_size_every_tile_against_the_oracle(name, band):
+    g, c = full_size_case(name)
+    _, _, tol, nbands = FULL_CASES[name]
+    if name == "config4":
+        # 16 x 16 tiles of 256 x 224 fill the 256 compute units; 16 x 14 tiles of 256 x 256 would leave 32 idle
+        assert B.axe_gemm_tile(gemm_desc_only(g)) == B.AXE_TILE_256x224x64
+    if name == "chained_17x16_bf16_224":
+        assert B.axe_gemm_tile(gemm_desc_only(g)) == B.AXE_TILE_256x256x64
+    rows = band_rows(g.M, band, nbands)
+    assert len(rows) > 0
+    check_gemm(c[rows], oracle_gemm(g, rows, None), tol)
+
+
+@pytest.mark.parametrize("name", ["config3", "config4", "config5"])
+def test_gemm_full_size_projections(name):
+    """An extra that does not go through the oracle's C: two randomised projections (C v and u^T C, computed in fp64
+    from the inputs with NumPy), every 256-row and 256-column block of the full matrix."""
+    g, c = full_size_case(name)
+    tol = FULL_CASES[name][2]
+    rng = np.random.default_rng(3)
     M, N = g.M, g.N
-    # projections in fp64: C v = A (B v),  u^T C = (u^T A) B, block by block
     dt = R.AXE_BF16 if g.dtype == "bf16" else R.AXE_FP8_E4M3
     A, Bm = R.decode(g.a_mk, dt), R.decode(g.b_nk, dt)          # (M,K), (N,K)
     v, u = rng.choice([-1.0, 1.0], N), rng.choice([-1.0, 1.0], M)
@@ -573,49 +623,6 @@ def full_size_check(g: W.GemmInputs, tol, device_axis=False, seed=0, tile=B.AXE_
     # (with random signs the rounding errors of a row add in quadrature, so the projection error of a
     #  correct result is about the element-wise relative error times the block's Frobenius norm)
     assert np.linalg.norm(y - y_ref) <= tol / 2 * np.linalg.norm(c)
-    return err
-
-
-def test_gemm_config3_full_size():
-    full_size_check(W.config3(), BF16_TOL, seed=3)
-
-
-def test_gemm_config4_full_size_shard():
-    g = W.config4()
-    # 16 x 16 tiles of 256 x 224 fill the 256 compute units; 16 x 14 tiles of 256 x 256 would leave 32 idle
-    assert B.axe_gemm_tile(gemm_desc_only(g)) == B.AXE_TILE_256x224x64
-    full_size_check(g, BF16_TOL, device_axis=True, seed=4)
-
-
-def test_gemm_config5_full_size_fp8_scaled():
-    full_size_check(W.config5(), FP8_TOL, seed=5)
-
-
-@pytest.mark.parametrize("M,N,K,wseed,scaled,seed", [(8192, 8192, 8192, 19097, "e8m0", 9),
-                                                     (4352, 4096, 8448, 96, "e8m0", 10),    # 17 x 16 tiles, 66 K-steps: code registers refilled
-                                                     (4096, 4096, 4096, 97, False, 11)])
-def test_gemm_config5_shape_with_e8m0_scales_and_unscaled(M, N, K, wseed, scaled, seed):
-    """Configuration 5's shape with power-of-two (E8M0) block scales, and without scales: both run on the
-    matrix cores' scale path (chained tiles, 64 K-steps)."""
-    full_size_check(W.gemm_fp8(M, N, K, wseed, scaled=scaled), FP8_TOL, seed=seed)
-
-
-@pytest.mark.parametrize("which", ["bf16_256", "bf16_224", "fp8"])
-def test_gemm_chained_tiles_on_a_grid_of_17_by_16(which):
-    """More tiles than compute units, so every workgroup walks two tiles as one pipeline, on a tile
-    grid that is not made of 16 x 16 blocks (the other workgroup -> tile order); the last 16 workgroups
-    get a second tile, the others do not.  Whole matrix against the oracle, every 128 x 128 tile."""
-    if which == "bf16_256":
-        full_size_check(W.gemm_bf16(4352, 4096, 512, 91), BF16_TOL, seed=6)
-    elif which == "bf16_224":
-        # 224-column tiles, 17 x 16 of them
-        # (left to itself the library takes 17 x 14 tiles of 256 x 256 here: one round instead of two)
-        g = W.gemm_bf16(4352, 3584, 512, 93)
-        assert B.axe_gemm_tile(gemm_desc_only(g)) == B.AXE_TILE_256x256x64
-        full_size_check(g, BF16_TOL, seed=8, tile=B.AXE_TILE_256x224x64)
-    else:
-        # fp8: 66 K-steps, so the register of block scales is refilled inside each chained tile
-        full_size_check(W.gemm_fp8(4352, 4096, 8448, 92, scaled=True), FP8_TOL, seed=7)
 
 
 @pytest.mark.parametrize("which", ["config4", "chained_256", "fp8"])
