@@ -107,7 +107,7 @@ def dev(a):
     return torch.from_numpy(a.view(view)).cuda()
 
 
-def gemm_setup(g, n_sets, device_axis=False, tile=0):
+def gemm_setup(g, n_sets, device_axis=False, tile=0, scale_a_rows=0):
     import torch
     from paper_2601_19092_amd import binding as B
     from paper_2601_19092_amd import workloads as W
@@ -127,15 +127,15 @@ def gemm_setup(g, n_sets, device_axis=False, tile=0):
                       B.AXE_F32 if g.out_dtype == "f32" else B.AXE_BF16,
                       B.Layout(As, axes), B.Layout(Bs, axes), B.Layout(Cs, axes),
                       g.M * g.K, g.N * g.K, g.M * g.N, sa, sb, tile_hint=tile,
-                      scale_dtype=B.AXE_SCALE_E8M0 if g.scale_dtype == "e8m0" else B.AXE_SCALE_F32)
+                      scale_dtype=B.AXE_SCALE_E8M0 if g.scale_dtype == "e8m0" else B.AXE_SCALE_F32, scale_a_rows=scale_a_rows)
     def step(i):
         dA, dB, dC = sets[i % n_sets]
         B.axe_gemm(desc, dA, dB, dC)
     return step, sets, desc
 
 
-def bench_gemm(name, g, steps, warmup, n_sets=2, device_axis=False, min_warm_ms=None, headline=False):
-    step, sets, desc = gemm_setup(g, n_sets, device_axis)
+def bench_gemm(name, g, steps, warmup, n_sets=2, device_axis=False, min_warm_ms=None, headline=False, scale_a_rows=0):
+    step, sets, desc = gemm_setup(g, n_sets, device_axis, scale_a_rows=scale_a_rows)
     st = settle(step) if headline else None
     wall, devms = time_loop(step, steps, warmup, min_warm_ms)
     flops = 2.0 * g.M * g.N * g.K
@@ -233,11 +233,9 @@ def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
         dB = dev(f.b_gnk.reshape(-1))
         dBblk, dBuse = torch.empty_like(dB), None
         B.axe_relayout(plainL, blkL, (f.G, f.K, f.N), dB, dBblk)
-        assert np.array_equal(dBblk[:f.N * f.K].cpu().numpy().view(np.uint16), W.pack_blocked(f.b_gnk[0]))
         if gated:
             dBuse = torch.empty_like(dB)
             B.axe_relayout(plainL, useL, (f.G, f.K, f.N), dB, dBuse)
-            assert np.array_equal(dBuse[:f.N * f.K].cpu().numpy().view(np.uint16), W.pack_blocked(W.pack_gate_up(f.b_gnk[:1]))[0])
         else:
             dBuse = dBblk
         for tokens in sweep:
@@ -294,9 +292,13 @@ def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64)):
         gated = name == "gemm1"
         NC = N // 2 if gated else N
         f = W.gemm_grouped_fp8(rows_top, N, K, W.SEED_BASE + 21 + gated, scale_dtype="e8m0")
-        img = W.pack_gate_up(f.b_gnk) if gated else f.b_gnk
-        useL = B.Layout(W.gated_b_spec(K, N, f.G) if gated else W.grouped_gemm_specs(f)[1])
-        dB = dev(img.reshape(-1))
+        plainL = B.Layout(W.grouped_gemm_specs(f)[1])
+        useL = B.Layout(W.gated_b_spec(K, N, f.G)) if gated else plainL
+        dB = dev(f.b_gnk.reshape(-1))
+        if gated:                                        # gate and up rows interleaved: packed by axe_relayout (untimed)
+            dBp = torch.empty_like(dB)
+            B.axe_relayout(plainL, useL, (f.G, K, N), dB, dBp)
+            dB = dBp
         sb = torch.from_numpy(f.scale_b).cuda()
         for tokens in sweep:
             rows = W.moe_group_rows(tokens, W.MOE_EXPERTS, W.MOE_TOPK, W.SEED_BASE + 11)
@@ -305,7 +307,7 @@ def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64)):
             dC = torch.zeros(M * NC, dtype=torch.int16, device="cuda")
             dR = torch.from_numpy(rows).cuda()
             desc = B.GroupedGemmDesc(M, N, K, f.G, B.Layout(W.row_major_spec(M, K)), useL, B.Layout(W.row_major_spec(M, NC)),
-                                     M * K, img.size, M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
+                                     M * K, f.b_gnk.size, M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
                                      epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, scale_a=sa, scale_b=sb,
                                      scale_dtype=B.AXE_SCALE_E8M0)
             wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dB, dC, dR), steps, warmup)
@@ -463,6 +465,13 @@ def main():
         comp["gemm_fp8_e8m0_block_scaled"], _ = bench_gemm(
             "fp8 e4m3 GEMM 8192^3, E8M0 (power-of-two) 128x128 block scales on the MFMA scale path",
             W.gemm_fp8(8192, 8192, 8192, W.SEED_BASE + 5, scaled="e8m0"), max(10, args.steps // 2), args.warmup)
+    if want("fp8"):
+        # activations scaled per row and 128-wide k block (one E8M0 code each), weights per 128 x 128 block
+        gr = W.gemm_fp8(8192, 8192, 8192, W.SEED_BASE + 6, scaled="e8m0")
+        gr.scale_a = np.random.default_rng(W.SEED_BASE + 6).integers(124, 131, (8192, 64)).astype(np.uint8)
+        comp["gemm_fp8_e8m0_row_scaled"], _ = bench_gemm(
+            "fp8 e4m3 GEMM 8192^3, E8M0 scales: one per row and k block of A, one per 128x128 block of B, on the MFMA scale path",
+            gr, max(10, args.steps // 2), args.warmup, scale_a_rows=1)
     if want("grouped"):
         comp["moe_grouped_gemm"] = bench_grouped(max(10, args.steps // 3), args.warmup)
         comp["moe_grouped_gemm_fp8"] = bench_grouped_fp8(max(10, args.steps // 3), args.warmup)

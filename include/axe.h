@@ -157,7 +157,9 @@ typedef struct {
   int32_t      scale_dtype; /* AXE_SCALE_F32 or AXE_SCALE_E8M0                                    */
   int32_t      scale_a_rows; /* rows of A that share a scale: 0 or 128 = square blocks; 1 = one scale per
                                 row and 128-wide k block (activations; d_scale_a is then (M, ceil(K/128)));
-                                B keeps 128 x 128 blocks.  Served by the 64 x 64 kernel only.          */
+                                B keeps 128 x 128 blocks.  Served by the 64 x 64 kernel, and with E8M0
+                                codes, K a multiple of 1024 and M, N multiples of 256 by the 256 x 256
+                                kernel on the matrix cores' scale path.                                */
 } axe_gemm_desc_t;
 
 enum { AXE_SCALE_F32 = 0, AXE_SCALE_E8M0 = 1 };

@@ -589,12 +589,19 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   const bool ragged_ok = !fp8 && (g->K % 64 == 0) && (g->N % cvec == 0) && (ldc % cvec == 0) && pitch_ok &&
                          256 * ldc * ob < (int64_t(1) << 31) && g->N <= 2048 * 256 && g->M < (int64_t(1) << 31);
   int tile = g->tile_hint;
-  if (row_scaled) {                                                // only the 64 x 64 kernel folds a scale per row
-    if (tile != AXE_TILE_AUTO && tile != AXE_TILE_64x64x32) {
-      set_error("axe_gemm: one scale per row of A is served by the 64x64 kernel only");
+  if (row_scaled) {
+    // one scale per row of A: the 64 x 64 kernel folds it per lane (fp32 or E8M0); the 256 x 256 kernel on the matrix
+    // cores' scale path takes E8M0 row codes a window of 8 K-tiles at a time (K a multiple of 1024)
+    const bool rows_big = big_ok && P.args.scale_e8m0 && g->K % 1024 == 0;
+    if (tile == AXE_TILE_256x256x64 && !rows_big) {
+      set_error("axe_gemm: one scale per row of A on the 256x256 tile needs E8M0 scales, K a multiple of 1024 and M, N multiples of 256");
       return AXE_EUNSUPPORTED;
     }
-    tile = AXE_TILE_64x64x32;
+    if (tile != AXE_TILE_AUTO && tile != AXE_TILE_64x64x32 && tile != AXE_TILE_256x256x64) {
+      set_error("axe_gemm: one scale per row of A is served by the 64x64 and the 256x256 kernels");
+      return AXE_EUNSUPPORTED;
+    }
+    if (tile == AXE_TILE_AUTO && !rows_big) tile = AXE_TILE_64x64x32;
   }
   if (blocked) {
     if (fp8 || !big_ok || !block_ok(opa) || !block_ok(opb) || (tile != AXE_TILE_AUTO && tile != AXE_TILE_256x256x64)) {

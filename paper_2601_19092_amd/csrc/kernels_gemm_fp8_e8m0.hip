@@ -19,8 +19,14 @@
 //                 fragments of step kt+1 are read in the second half of step kt; rows are processed
 //                 in pairs so that a B fragment is re-read right after its last use (row 7) and is
 //                 not needed again before 14 MFMAs later.
-//   Scales      : two bytes per K-step and wave (its 128 rows and 128 columns lie in one scale block),
-//                 fetched with scalar loads one K-step ahead and broadcast to the lanes.
+//   Scales      : two bytes per K-step and wave (its 128 rows and 128 columns lie in one scale block), kept one
+//                 per lane for 64 K-steps and broadcast to the lanes.
+//   Row scales  : (second instantiation) A carries one code per ROW and 128-wide k block -- the usual choice for
+//                 activations -- instead of one per 128 x 128 block.  The instruction takes the scale of a row
+//                 from the lanes that hold the row, so nothing changes in the matrix pipe: a lane keeps the codes
+//                 of its row of each of the 8 fragment rows for the 8 K-steps of a rotation window (8 contiguous
+//                 bytes of the row-major (M, K / 128) code array, 16 registers, plus 16 for the window being
+//                 fetched) and hands the MFMAs of a K-step one byte of each.
 #include <hip/hip_runtime.h>
 
 #include <type_traits>
@@ -54,7 +60,10 @@ __device__ __forceinline__ void mfma_scaled(f32x4& acc, i32x8 first, i32x8 secon
 }
 }  // namespace
 
-__global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
+// ROWS: one E8M0 code per row of A and k block (scale_a is (M, K / 128), K a multiple of 1024) instead of one per
+// 128 x 128 block; B's codes are per 128 x 128 block either way.
+template <bool ROWS>
+__device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
   const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
 
@@ -84,7 +93,8 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
       t.rot = (tm + tn) & (kRot - 1);                              // K rotation
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda), 0,
                                                255 * a_pitch + (int)g.K, 0x00020000);
-      t.sa = (const uint8_t*)g.scale_a + (int64_t)(2 * tm + wm) * g.nkb;
+      if constexpr (ROWS) t.sa = (const uint8_t*)g.scale_a + ((int64_t)tm * kTile + wm * 128 + (lane & 15)) * g.nkb;   // the lane's row of fragment row 0
+      else t.sa = (const uint8_t*)g.scale_a + (int64_t)(2 * tm + wm) * g.nkb;
       t.sb = (const uint8_t*)g.scale_b + (int64_t)(2 * tn + wn) * g.nkb;
     } else {                                                       // no such tile: every load returns zero
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
@@ -110,8 +120,32 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
     if (!scaled) return;
     const int T = base + lane;
     const int kt_ = ktile(T < nk ? T : nk - 1, t.rot);
-    oa = t.sa[kt_];
+    if constexpr (!ROWS) oa = t.sa[kt_];
     ob = t.sb[kt_];
+  };
+  // Row scales.  The walk visits the K-tiles of an aligned window of 8 in the order (t + rot) % 8, t = 0..7; the 8
+  // codes of a row for that window are 8 contiguous, 8-byte aligned bytes.  na: the window being fetched, as loaded;
+  // ca: the current window, rotated by the tile's rot so that step t of the window uses byte t, and moved down by
+  // one byte per step.
+  uint32_t ca[8][2], na[8][2];
+  bool more = false;                                               // the workgroup has another tile after the current one
+  auto fetch_rows = [&](const Tile& t, int win) __attribute__((always_inline)) {
+    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const u32x2 c = *(const u32x2*)(t.sa + (int64_t)i * 16 * g.nkb + win * 8);
+      na[i][0] = c[0], na[i][1] = c[1];
+    }
+  };
+  auto take_rows = [&](int rot) __attribute__((always_inline)) {
+    const bool swap = (rot & 4) != 0;
+    const uint32_t sh = (uint32_t)(rot & 3) * 8;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const uint32_t lo = swap ? na[i][1] : na[i][0], hi = swap ? na[i][0] : na[i][1];
+      ca[i][0] = __builtin_amdgcn_alignbit(hi, lo, sh);            // 64-bit rotation to the right by 8 rot bits
+      ca[i][1] = __builtin_amdgcn_alignbit(lo, hi, sh);
+    }
   };
   auto lane_value = [](uint32_t val, int l) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)val, l); };
 
@@ -196,7 +230,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
   // step kt + 3 (after MFMAs 18, 22, 26, 30).  The second half also reads the 16 fragments of step kt+1, each right after the
   // last MFMA that uses the register it goes to: A fragments 0..3 during rows 4, 5; A fragments 4, 5
   // and, after MFMA (7, j), B fragment j during rows 6, 7; A fragments 6, 7 at the end.
-  auto half = [&](auto par_c, auto h_c, auto cross_c, int kt, uint32_t va, uint32_t vb) __attribute__((always_inline)) {
+  auto half = [&](auto par_c, auto h_c, auto cross_c, int kt, const uint32_t (&va)[8], uint32_t vb, bool pref) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value, H = decltype(h_c)::value;
     constexpr bool CROSS = decltype(cross_c)::value != 0;
     const int bT = H == 0 ? kt + 2 : kt + 3;
@@ -206,8 +240,16 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
 #pragma unroll
     for (int q = 0; q < 32; ++q) {
       const int i = 4 * H + 2 * (q >> 4) + (q & 1), j = (q >> 1) & 7;
-      mfma_scaled(acc[i][j], fb[j], fa[i], vb, va);
+      mfma_scaled(acc[i][j], fb[j], fa[i], vb, va[ROWS ? i : 0]);
       __builtin_amdgcn_sched_barrier(0);
+      if constexpr (ROWS && H == 1) {
+        // the row codes of the next window of the walk (of this tile, or the first of the next tile), once per 8
+        // K-steps, before the A pieces: older than they are, so complete at the next barrier at the latest
+        if (q == 0 && pref) {
+          if (kt + 8 < nk) fetch_rows(cur, (kt >> 3) + 1);
+          else if (more) fetch_rows(nxt, 0);
+        }
+      }
       if (H == 1) {
         if (q < 16 && (q & 3) == 1) fa[q >> 2] = read_a(q >> 2, pa);
         if (q == 16) fa[4] = read_a(4, pa);
@@ -234,15 +276,39 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
       wg_barrier();
     }
   };
-  auto step = [&](auto par_c, auto cross_c, int kt) __attribute__((always_inline)) {
-    uint32_t va = lane_value(cva, kt & 63), vb = lane_value(cvb, kt & 63);
+  auto step = [&](auto par_c, auto cross_c, int kt, bool pref = false) __attribute__((always_inline)) {
+    uint32_t va[8], vb = lane_value(cvb, kt & 63);
     // the codes are now in VGPRs, written by the vector ALU; the MFMA is an asm statement, so the compiler's
     // hazard recogniser cannot pad between that write and the matrix core's read of its scale operands
-    asm volatile("s_nop 3" : "+v"(va), "+v"(vb));
-    half(par_c, I0{}, cross_c, kt, va, vb);
-    half(par_c, I1{}, cross_c, kt, va, vb);
+    if constexpr (ROWS) {
+      // step t of the window uses byte t of the rotated codes: the lowest byte now, then the 64 bits move down by one
+      // byte (no register is ever indexed by t: that would put the array into scratch memory)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) {
+        va[i] = ca[i][0] & 0xffu;
+        ca[i][0] = __builtin_amdgcn_alignbit(ca[i][1], ca[i][0], 8);
+        ca[i][1] >>= 8;
+      }
+      asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4]), "+v"(va[5]), "+v"(va[6]), "+v"(va[7]), "+v"(vb));
+    } else {
+      va[0] = lane_value(cva, kt & 63);
+      asm volatile("s_nop 3" : "+v"(va[0]), "+v"(vb));
+    }
+    half(par_c, I0{}, cross_c, kt, va, vb, pref);
+    half(par_c, I1{}, cross_c, kt, va, vb, pref);
     const int t = bo0;
     bo0 = bo1, bo1 = bo2, bo2 = t;
+  };
+  // ROWS: at the first step of a window of 8 the codes fetched during the previous window are taken over (rotated by
+  // this tile's rot) and the step fetches the next window's
+  auto window = [&](int kt) __attribute__((always_inline)) -> bool {
+    if constexpr (ROWS) {
+      if ((kt & 7) == 0) {
+        take_rows(cur.rot);
+        return true;
+      }
+    }
+    return false;
   };
 
   // ---- prologue (first tile only): steps 0 and 1 of A, steps 0, 1 and half of 2 of B
@@ -257,6 +323,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
 #pragma unroll
   for (int i = 0; i < 4; ++i) b_load(2, i, bo2, true);
   fetch_codes(cur, 0, cva, cvb);
+  if constexpr (ROWS) fetch_rows(cur, 0);
   asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   wg_barrier();
 #pragma unroll
@@ -267,7 +334,7 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
   // ---- all K-steps of all tiles of this workgroup, one uninterrupted pipeline (nk even and >= 4 when chained)
   for (;;) {
     set_output(v);
-    const bool more = v + (int)gridDim.x < ntiles;
+    more = v + (int)gridDim.x < ntiles;
     int kt = 0;
     for (int base = 0; base < nk; base += 64) {
       const int end = nk < base + 64 ? nk : base + 64;
@@ -275,11 +342,11 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
       if (end < nk) fetch_codes(cur, end, nva, nvb);
       else if (more) fetch_codes(nxt, 0, nva, nvb);
       for (; kt + 1 < end && kt + 5 < nk; kt += 2) {               // every load of these steps is of this tile (at most step kt + 5)
-        step(I0{}, I0{}, kt);
+        step(I0{}, I0{}, kt, window(kt));
         step(I1{}, I0{}, kt + 1);
       }
       for (; kt + 1 < end; kt += 2) {                              // the last steps load the next tile's first K-steps
-        step(I0{}, I1{}, kt);
+        step(I0{}, I1{}, kt, window(kt));
         step(I1{}, I1{}, kt + 1);
       }
       if (kt < end) {                                              // odd nk: only with one tile per workgroup
@@ -302,13 +369,20 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
   }
 }
 
+__global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<false>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_rows_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true>(g); }
+
 hipError_t launch_gemm_fp8_e8m0_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
   const int nk = (int)(g.K / 128);
   const int cus = cu_count();
   const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
   unsigned nwg = (unsigned)(chain ? cus : ntiles);
-  hipLaunchKernelGGL(gemm_fp8_e8m0_256_kernel, dim3(nwg), dim3(256), 0, s, g);
+  if (g.scale_a && g.scale_a_rows == 1) {
+    if (!g.scale_e8m0 || g.K % 1024) return hipErrorInvalidValue;  // a window of 8 codes per row: whole windows only
+    hipLaunchKernelGGL(gemm_fp8_e8m0_256_rows_kernel, dim3(nwg), dim3(256), 0, s, g);
+  } else
+    hipLaunchKernelGGL(gemm_fp8_e8m0_256_kernel, dim3(nwg), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 

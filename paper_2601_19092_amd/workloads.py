@@ -268,18 +268,9 @@ def grouped_gemm_specs(g: "GroupedGemmInputs", lda: Optional[int] = None, ldb: O
 
 
 # ---- operands stored in 256 x 64 blocks (rows x k), each block contiguous, blocks of one row block side by side
-def pack_blocked(rows_k: np.ndarray, rb: int = 256, kb: int = 64) -> np.ndarray:
-    """Memory image of a (R, K) matrix (unit stride along k in the plain form) stored as contiguous rb x kb
-    blocks: block (r / rb, k / kb) at ((r / rb) * (K / kb) + k / kb) * rb * kb, row-major inside the block.
-    Leading dimensions are kept: (..., R, K) -> (..., R * K)."""
-    *lead, Rn, K = rows_k.shape
-    v = rows_k.reshape(*lead, Rn // rb, rb, K // kb, kb)
-    n = len(lead)
-    return np.ascontiguousarray(v.transpose(*range(n), n, n + 2, n + 1, n + 3)).reshape(*lead, Rn * K)
-
-
 def blocked_iters(Rn: int, K: int, rb: int = 256, kb: int = 64):
-    """(row iters, k iters) of that image as Axe iters on "m"."""
+    """(row iters, k iters), as Axe iters on "m", of a (R, K) matrix stored as contiguous rb x kb blocks: block
+    (r / rb, k / kb) at ((r / rb) * (K / kb) + k / kb) * rb * kb, row-major inside the block."""
     return [(Rn // rb, rb * K, "m"), (rb, kb, "m")], [(K // kb, rb * kb, "m"), (kb, 1, "m")]
 
 
@@ -295,14 +286,9 @@ def blocked_b_spec(K: int, N: int, G: Optional[int] = None) -> dict:
 
 
 # ---- gate and up projections of an expert interleaved in runs of 16 rows (what the gated epilogue reads)
-def pack_gate_up(b_gnk: np.ndarray) -> np.ndarray:
-    """(G, N, K) with rows [gate 0 .. I-1 | up 0 .. I-1] -> rows 32 f + 16 h + i = (h ? up : gate)[16 f + i]."""
-    G, N, K = b_gnk.shape
-    return np.ascontiguousarray(b_gnk.reshape(G, 2, N // 32, 16, K).transpose(0, 2, 1, 3, 4)).reshape(G, N, K)
-
-
 def gated_b_spec(K: int, N: int, G: int, blocked: bool = False) -> dict:
-    """Layout of the logical (G, K, N) right-hand sides whose memory image is pack_gate_up (then pack_blocked)."""
+    """Layout of the logical (G, K, N) right-hand sides with gate and up rows interleaved: memory row 32 f + 16 h + i holds
+    (h ? up : gate)[16 f + i]; blocked: that image stored in contiguous 256 x 64 blocks."""
     if not blocked:
         return spec([(G, N * K, "m"), (K, 1, "m"), (2, 16 * K, "m"), (N // 32, 32 * K, "m"), (16, K, "m")])
     return spec([(G, N * K, "m"), (K // 64, 256 * 64, "m"), (64, 1, "m"),

@@ -178,7 +178,7 @@ def test_gemm_family_matching_and_errors():
     assert B.lib().axe_gemm(C.byref(d.c), None, None, None, None) == B.AXE_EINVAL
 
 
-def test_gemm_row_scaled_activations_go_to_the_small_kernel():
+def test_gemm_row_scaled_activations_kernel_choice():
     import numpy as np
     g = W.gemm_fp8(256, 256, 256, 3)
     As, Bs, Cs = W.gemm_specs(g)
@@ -192,8 +192,17 @@ def test_gemm_row_scaled_activations_go_to_the_small_kernel():
     assert _tile_rc(desc(0, tile=BIG)) == BIG and _tile_rc(desc(128, tile=BIG)) == BIG
     assert _tile_rc(desc(0)) == B.AXE_TILE_64x64x32          # a problem this small takes the 64 x 64 tiles by itself
     assert _tile_rc(desc(1)) == B.AXE_TILE_64x64x32
-    assert _tile_rc(desc(1, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(desc(1, tile=B.AXE_TILE_256x256x64)) == B.AXE_EUNSUPPORTED      # fp32 row scales: the 64 x 64 kernel only
     assert _tile_rc(desc(64)) == B.AXE_EINVAL
+    # E8M0 row codes ride on the 256 x 256 scale-path kernel when K is a multiple of 1024
+    def desc_e8(K, M=2048, tile=B.AXE_TILE_AUTO):
+        return B.GemmDesc(M, 2048, K, B.AXE_FP8_E4M3, B.AXE_BF16, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, 2048)),
+                          B.Layout(W.row_major_spec(M, 2048)), M * K, 2048 * K, M * 2048, FakeTensor(), FakeTensor(), tile_hint=tile,
+                          scale_a_rows=1, scale_dtype=B.AXE_SCALE_E8M0)
+    assert _tile_rc(desc_e8(2048)) == BIG and _tile_rc(desc_e8(1024, tile=BIG)) == BIG
+    assert _tile_rc(desc_e8(1536)) == B.AXE_TILE_64x64x32 and _tile_rc(desc_e8(1536, tile=BIG)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(desc_e8(2048, M=2000)) == B.AXE_TILE_64x64x32
+    assert _tile_rc(desc_e8(2048, tile=B.AXE_TILE_256x224x64)) == B.AXE_EUNSUPPORTED
 
 
 def test_gemm_accepts_blocked_operands():

@@ -17,6 +17,7 @@ from oracle import axe_ref as R
 from oracle.axe_layout import Iter, Layout, Swizzle
 from paper_2601_19092_amd import binding as B
 from paper_2601_19092_amd import workloads as W
+from packing import pack_blocked, pack_gate_up
 
 pytestmark = pytest.mark.gpu
 
@@ -464,7 +465,7 @@ def test_gemm_large_tile_fp32_output(M, N, K, dtype):
 
 def test_gemm_large_tile_fp32_output_blocked_operands():
     g = W.gemm_bf16(512, 768, 256, 481, std_b=1 / 16, out_dtype="f32")
-    dA, dB = dev(W.pack_blocked(g.a_mk)), dev(W.pack_blocked(g.b_nk))
+    dA, dB = dev(pack_blocked(g.a_mk)), dev(pack_blocked(g.b_nk))
     dC = torch.zeros(g.M * g.N, dtype=torch.float32, device="cuda")
     desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16, B.AXE_F32, B.Layout(W.blocked_a_spec(g.M, g.K)), B.Layout(W.blocked_b_spec(g.K, g.N)),
                       B.Layout(W.row_major_spec(g.M, g.N)), g.M * g.K, g.N * g.K, g.M * g.N)
@@ -773,8 +774,8 @@ def run_gemm_blocked(g: W.GemmInputs, a_blocked: bool, b_blocked: bool):
     reshape / transpose, layouts stated as tile products); returns C decoded to fp64."""
     As = W.blocked_a_spec(g.M, g.K) if a_blocked else W.row_major_spec(g.M, g.K)
     Bs = W.blocked_b_spec(g.K, g.N) if b_blocked else W.col_major_spec(g.K, g.N)
-    a = W.pack_blocked(g.a_mk) if a_blocked else g.a_mk.reshape(-1)
-    b = W.pack_blocked(g.b_nk) if b_blocked else g.b_nk.reshape(-1)
+    a = pack_blocked(g.a_mk) if a_blocked else g.a_mk.reshape(-1)
+    b = pack_blocked(g.b_nk) if b_blocked else g.b_nk.reshape(-1)
     dA, dB = dev(a), dev(b)
     dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
     desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, g.N)),
@@ -799,7 +800,7 @@ def test_gemm_grouped_blocked_right_hand_sides():
     off = [0, 300, 520, 1300, 1301, 2000]
     g = W.gemm_grouped_bf16(off, 768, 512, 92)
     As, _, Cs = W.grouped_gemm_specs(g)
-    b = W.pack_blocked(g.b_gnk)                              # (G, N * K): each group's image, one after the other
+    b = pack_blocked(g.b_gnk)                              # (G, N * K): each group's image, one after the other
     dA, dB = dev(g.a_mk.reshape(-1)), dev(b.reshape(-1))
     dC = torch.full((g.M * g.N,), SENTINEL, dtype=torch.int16, device="cuda")
     dR = torch.from_numpy(g.group_rows).cuda()
@@ -823,7 +824,25 @@ def test_relayout_produces_the_blocked_operand_layout():
     src, dst = dev(b_nk.reshape(-1)), torch.zeros(N * K, dtype=torch.int16, device="cuda")
     B.axe_relayout(Ls, Ld, (K, N), src, dst)
     torch.cuda.synchronize()
-    assert np.array_equal(dst.cpu().numpy().view(np.uint16), W.pack_blocked(b_nk))
+    assert np.array_equal(dst.cpu().numpy().view(np.uint16), pack_blocked(b_nk))
+
+
+@pytest.mark.parametrize("eb,blocked", [(2, False), (2, True), (1, False)])
+def test_relayout_produces_the_gate_up_interleaved_layouts(eb, blocked):
+    """What the gated epilogue reads -- each group's gate and up rows interleaved in runs of 16, plain or in 256 x 64
+    blocks -- is what axe_relayout writes from the plain (G, K, N) image, for 2-byte and 1-byte (fp8) elements."""
+    G, K, N = 3, 256, 512
+    rng = np.random.default_rng(95)
+    b_gnk = rng.integers(0, 256 ** eb, (G, N, K)).astype(np.uint16 if eb == 2 else np.uint8)
+    Ls = B.Layout(W.spec([(G, N * K, "m"), (K, 1, "m"), (N, K, "m")]))
+    Ld = B.Layout(W.gated_b_spec(K, N, G, blocked))
+    src = dev(b_gnk.reshape(-1))
+    dst = torch.zeros_like(src)
+    B.axe_relayout(Ls, Ld, (G, K, N), src, dst)
+    torch.cuda.synchronize()
+    img = pack_gate_up(b_gnk)
+    img = pack_blocked(img) if blocked else img
+    assert np.array_equal(dst.cpu().numpy().view(b_gnk.dtype), img.reshape(-1))
 
 
 @pytest.mark.parametrize("kernel", [B.AXE_GROUPED_TILES_256, B.AXE_GROUPED_TILES_128])
@@ -833,8 +852,8 @@ def test_gemm_grouped_gated_epilogue(off, N, K, blocked, kernel):
     """First group GEMM of the MoE layer with the gated activation fused: C = silu(A Wg) * (A Wu), (M, N / 2)."""
     M = off[-1] + 3
     g = W.gemm_grouped_bf16(off, N, K, 94, M=M, std_b=2.0 * K ** -0.5)      # products of a few units: silu is well off its linear part
-    img = W.pack_gate_up(g.b_gnk)
-    img = W.pack_blocked(img) if blocked else img
+    img = pack_gate_up(g.b_gnk)
+    img = pack_blocked(img) if blocked else img
     dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
     dC = torch.full((M * (N // 2),), SENTINEL, dtype=torch.int16, device="cuda")
     dR = torch.from_numpy(g.group_rows).cuda()
@@ -854,7 +873,7 @@ def test_gemm_grouped_gated_moe_layer_full_size():
     the oracle computes sampled groups and the rows at group borders."""
     g = W.moe_gemm1(4096)
     I = g.N // 2
-    img = W.pack_blocked(W.pack_gate_up(g.b_gnk))
+    img = pack_blocked(pack_gate_up(g.b_gnk))
     dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
     dC = torch.full((g.M * I,), SENTINEL, dtype=torch.int16, device="cuda")
     dR = torch.from_numpy(g.group_rows).cuda()
@@ -980,7 +999,7 @@ def test_gemm_f16_chained_and_blocked():
     cols = np.array([0, 4095])
     assert R.rel_frobenius(c[:, cols], oracle_gemm(g, None, cols)) <= F16_TOL
     # blocked operands: same kernel, same order of operations, same bits
-    dA, dB = dev(W.pack_blocked(g.a_mk)), dev(W.pack_blocked(g.b_nk))
+    dA, dB = dev(pack_blocked(g.a_mk)), dev(pack_blocked(g.b_nk))
     dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
     desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_F16, B.AXE_F16, B.Layout(W.blocked_a_spec(g.M, g.K)), B.Layout(W.blocked_b_spec(g.K, g.N)),
                       B.Layout(W.row_major_spec(g.M, g.N)), g.M * g.K, g.N * g.K, g.M * g.N)
@@ -1001,7 +1020,7 @@ def test_gemm_grouped_f16_plain_and_gated():
         assert R.rel_frobenius(c[owned], P[owned]) <= F16_TOL, kernel
         check_grouped(g, c, raw, P)
     # gated
-    img = W.pack_blocked(W.pack_gate_up(g.b_gnk))
+    img = pack_blocked(pack_gate_up(g.b_gnk))
     dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
     dC = torch.full((g.M * (N // 2),), SENTINEL, dtype=torch.int16, device="cuda")
     dR = torch.from_numpy(g.group_rows).cuda()
@@ -1026,11 +1045,11 @@ def test_gemm_grouped_stream_kernel_variants(dtype, gated, blocked):
     g = W.gemm_grouped_bf16(off, N, K, 101, M=int(off[-1]) + 2, std_b=2.0 * K ** -0.5, dtype=dtype)
     odt, tol = ORACLE_DT[dtype], (F16_TOL if dtype == "f16" else BF16_TOL)
     ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, odt)
-    img = W.pack_gate_up(g.b_gnk) if gated else g.b_gnk
+    img = pack_gate_up(g.b_gnk) if gated else g.b_gnk
     Kp = 384                                                 # K = 320 is no multiple of the K-tile: pad with zeros
     a_words = np.zeros((g.M, Kp), dtype=np.uint16); a_words[:, :K] = g.a_mk
     b_p = np.zeros((g.G, N, Kp), dtype=np.uint16); b_p[:, :, :K] = img
-    img = W.pack_blocked(b_p) if blocked else b_p
+    img = pack_blocked(b_p) if blocked else b_p
     if gated:
         Bs = W.gated_b_spec(Kp, N, g.G, blocked)
     else:
@@ -1065,7 +1084,7 @@ def test_gemm_grouped_moe_layer_at_decode_sizes(tokens):
     g1, g2 = W.moe_gemm1(tokens), W.moe_gemm2(tokens)
     I = g1.N // 2
     for g, gated in ((g1, True), (g2, False)):
-        img = W.pack_blocked(W.pack_gate_up(g.b_gnk) if gated else g.b_gnk)
+        img = pack_blocked(pack_gate_up(g.b_gnk) if gated else g.b_gnk)
         NC = I if gated else g.N
         Bs = W.gated_b_spec(g.K, g.N, g.G, True) if gated else W.blocked_b_spec(g.K, g.N, G=g.G)
         dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
@@ -1125,6 +1144,40 @@ def test_gemm_fp8_row_scaled_activations(M, N, K, scale_dtype):
         assert R.rel_frobenius(c[i:i + 16], ref[i:i + 16]) <= FP8_TOL, i
 
 
+# One E8M0 code per row of A on the 256 x 256 tile (the matrix cores' scale path): K = 1024 nw with nw = 1 (a single
+# window of 8 K-tiles), 2, 3 (odd), 9 (more than 64 K-steps: B's code registers are refilled as well); one tile, several
+# tiles with different K rotations, and 17 x 16 tiles (chained: the next tile's first window is fetched across the tile
+# boundary).  The row codes differ from row to row and from k block to k block over a range of 2^11.
+@pytest.mark.parametrize("M,N,K", [(256, 256, 1024), (512, 768, 2048), (768, 512, 3072), (256, 512, 9216), (4352, 4096, 2048)])
+def test_gemm_fp8_row_scaled_activations_large_tile(M, N, K):
+    g = W.gemm_fp8(M, N, K, 107, scaled="e8m0")
+    rng = np.random.default_rng(M + K)
+    nkb = K // 128
+    sa_rows = rng.integers(122, 133, (M, nkb)).astype(np.uint8)
+    As, Bs, Cs = W.gemm_specs(g)
+    dA, dB = dev(g.a_mk.reshape(-1)), dev(g.b_nk.reshape(-1))
+    dC = torch.zeros(M * N, dtype=torch.int16, device="cuda")
+    sa, sb = torch.from_numpy(sa_rows).cuda(), torch.from_numpy(g.scale_b).cuda()
+    desc = B.GemmDesc(M, N, K, B.AXE_FP8_E4M3, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(Cs), M * K, N * K, M * N, sa, sb,
+                      scale_dtype=B.AXE_SCALE_E8M0, scale_a_rows=1, tile_hint=B.AXE_TILE_256x256x64)
+    assert B.axe_gemm_tile(desc) == B.AXE_TILE_256x256x64
+    B.axe_gemm(desc, dA, dB, dC)
+    torch.cuda.synchronize()
+    c = R.bf16_to_f64(dC.cpu().numpy().view(np.uint16).reshape(M, N))
+    ref = R.gemm_ref(g.a_mk, g.b_nk.T, R.AXE_FP8_E4M3, R.e8m0_decode(sa_rows).astype(np.float32),
+                     R.e8m0_decode(g.scale_b).astype(np.float32), block_m_a=1)
+    check_gemm(c, ref, FP8_TOL)
+    for i in range(0, M, 16):                                # per 16 rows: a code applied to the wrong row cannot hide
+        assert R.rel_frobenius(c[i:i + 16], ref[i:i + 16]) <= FP8_TOL, i
+    # the same problem through the 64 x 64 kernel, which folds the row scales per lane: same result up to the last rounding
+    desc2 = B.GemmDesc(M, N, K, B.AXE_FP8_E4M3, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(Cs), M * K, N * K, M * N, sa, sb,
+                       scale_dtype=B.AXE_SCALE_E8M0, scale_a_rows=1, tile_hint=B.AXE_TILE_64x64x32)
+    dC2 = torch.zeros(M * N, dtype=torch.int16, device="cuda")
+    B.axe_gemm(desc2, dA, dB, dC2)
+    torch.cuda.synchronize()
+    assert R.rel_frobenius(R.bf16_to_f64(dC2.cpu().numpy().view(np.uint16).reshape(M, N)), c) < 4e-3
+
+
 @pytest.mark.parametrize("kernel", KERNELS)
 def test_gemm_grouped_largest_group_count(kernel):
     """4096 groups (the limit of the tile table's packing), most of them empty, a few large ones."""
@@ -1180,7 +1233,7 @@ def test_gemm_grouped_fp8_block_scaled(sizes, hint, gated, scale_dtype):
     ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_FP8_E4M3, scale_a=sa_o, scale_b=sb_o)
     if gated:
         ref = R.swiglu_ref(ref)
-    img = W.pack_gate_up(g.b_gnk) if gated else g.b_gnk
+    img = pack_gate_up(g.b_gnk) if gated else g.b_gnk
     Bs = W.gated_b_spec(K, N, g.G) if gated else W.spec([(g.G, N * K, "m"), (K, 1, "m"), (N, K, "m")])
     NC = N // 2 if gated else N
     dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
@@ -1214,7 +1267,7 @@ def test_gemm_grouped_is_bitwise_repeatable(kernel, gated):
     tile has its own schedule of asm-issued loads and counted waits; the streaming kernel adds partial sums in a fixed order)."""
     g = W.moe_gemm1(512)
     NC = g.N // 2 if gated else g.N
-    img = W.pack_gate_up(g.b_gnk) if gated else g.b_gnk
+    img = pack_gate_up(g.b_gnk) if gated else g.b_gnk
     Bs = W.gated_b_spec(g.K, g.N, g.G) if gated else W.grouped_gemm_specs(g)[1]
     dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
     dC = torch.zeros(g.M * NC, dtype=torch.int16, device="cuda")

@@ -229,3 +229,19 @@ def test_plan_replicated_destination_whose_replicas_step_over_the_shard_part(hc)
     words = np.array([11, 22, 33, 44], dtype=np.uint16)
     got, want = host_relayout(hc, src_L, dst_L, (4,), words, 8)
     assert np.array_equal(got, want) and list(got) == [11, 22, 33, 44, 11, 22, 33, 44]
+
+
+@pytest.mark.parametrize("eb,blocked", [(2, False), (2, True), (1, False)])
+def test_plan_gate_up_interleaved_weight_packing(hc, eb, blocked):
+    """The images the gated grouped GEMM reads, from the plain (G, K, N) one: against the oracle and against the NumPy
+    reshape / transpose construction."""
+    from packing import pack_blocked, pack_gate_up
+    G, K, N = 2, 128, 512
+    rng = np.random.default_rng(7 + eb)
+    b_gnk = rng.integers(0, 256 ** eb, (G, N, K)).astype(np.uint16 if eb == 2 else np.uint8)
+    s_L = Layout.from_spec(W.spec([(G, N * K, "m"), (K, 1, "m"), (N, K, "m")]))
+    d_L = Layout.from_spec(W.gated_b_spec(K, N, G, blocked))
+    got, want = host_relayout(hc, s_L, d_L, (G, K, N), b_gnk.reshape(-1), b_gnk.size)
+    img = pack_gate_up(b_gnk)
+    img = pack_blocked(img) if blocked else img
+    assert np.array_equal(got, want) and np.array_equal(got, img.reshape(-1))
