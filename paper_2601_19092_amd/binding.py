@@ -72,50 +72,55 @@ class AxeError(RuntimeError):
 _lib = None
 
 
+def load(path: str) -> C.CDLL:
+    """Loads a build of the library and declares its entry points (raises if it has not been built: there is no fallback)."""
+    if not os.path.exists(path):
+        raise RuntimeError(f"{path} is missing: build it with `python -m paper_2601_19092_amd.build` "
+                           "(or __graft_entry__.build()); this package has no CPU fallback")
+    L = C.CDLL(path)
+    vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
+    LP = C.POINTER(axe_layout_t)
+    L.axe_layout_eval.restype = C.c_int
+    L.axe_layout_eval.argtypes = [LP, i32, C.POINTER(i64), i64, vp, vp, vp]
+    L.axe_relayout.restype = C.c_int
+    L.axe_relayout.argtypes = [LP, LP, i32, C.POINTER(i64), i32, i32, vp, i64, vp, i64, vp]
+    L.axe_gemm.restype = C.c_int
+    L.axe_gemm.argtypes = [C.POINTER(axe_gemm_desc_t), vp, vp, vp, vp]
+    L.axe_gemm_grouped.restype = C.c_int
+    L.axe_gemm_grouped.argtypes = [C.POINTER(axe_gemm_grouped_desc_t), vp, vp, vp, vp, vp]
+    L.axe_gemm_grouped_check.restype = C.c_int
+    L.axe_gemm_grouped_check.argtypes = [C.POINTER(axe_gemm_grouped_desc_t)]
+    L.axe_gemm_tile.restype = C.c_int
+    L.axe_gemm_tile.argtypes = [C.POINTER(axe_gemm_desc_t)]
+    L.axe_gemm_grouped_kernel.restype = C.c_int
+    L.axe_gemm_grouped_kernel.argtypes = [C.POINTER(axe_gemm_grouped_desc_t)]
+    L.axe_gemm_grouped_describe.restype = C.c_int
+    L.axe_gemm_grouped_describe.argtypes = [C.POINTER(axe_gemm_grouped_desc_t), i32, LP, C.POINTER(i64), C.POINTER(i32), vp, C.c_size_t]
+    L.axe_gemm_describe.restype = C.c_int
+    L.axe_gemm_describe.argtypes = [C.POINTER(axe_gemm_desc_t), i32, LP, C.POINTER(i64), C.POINTER(i32), vp,
+                                    C.c_size_t]
+    P64, P32, sz = C.POINTER(i64), C.POINTER(i32), C.c_size_t
+    for name, args in (("axe_layout_span", [LP, P64]), ("axe_layout_canonicalize", [LP, LP, vp, sz]),
+                       ("axe_layout_gap_condition", [LP]), ("axe_layout_equal", [LP, LP]),
+                       ("axe_layout_group", [LP, i32, P64, LP, P32, vp, sz]),
+                       ("axe_layout_tile", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
+                       ("axe_layout_direct_sum", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
+                       ("axe_layout_tile_of", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
+                       ("axe_layout_slice", [LP, i32, P64, P64, P64, LP, vp, sz])):
+        getattr(L, name).restype = C.c_int
+        getattr(L, name).argtypes = args
+    L.axe_strerror.restype = C.c_char_p
+    L.axe_strerror.argtypes = [C.c_int]
+    L.axe_last_error.restype = C.c_char_p
+    L.axe_version.restype = i32
+    return L
+
+
 def lib() -> C.CDLL:
-    """Loads the HIP library (raises if it has not been built: there is no fallback)."""
+    """The HIP library, loaded on first use."""
     global _lib
     if _lib is None:
-        if not os.path.exists(LIB_PATH):
-            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2601_19092_amd.build` "
-                               "(or __graft_entry__.build()); this package has no CPU fallback")
-        L = C.CDLL(LIB_PATH)
-        vp, i64, i32 = C.c_void_p, C.c_int64, C.c_int32
-        LP = C.POINTER(axe_layout_t)
-        L.axe_layout_eval.restype = C.c_int
-        L.axe_layout_eval.argtypes = [LP, i32, C.POINTER(i64), i64, vp, vp, vp]
-        L.axe_relayout.restype = C.c_int
-        L.axe_relayout.argtypes = [LP, LP, i32, C.POINTER(i64), i32, i32, vp, i64, vp, i64, vp]
-        L.axe_gemm.restype = C.c_int
-        L.axe_gemm.argtypes = [C.POINTER(axe_gemm_desc_t), vp, vp, vp, vp]
-        L.axe_gemm_grouped.restype = C.c_int
-        L.axe_gemm_grouped.argtypes = [C.POINTER(axe_gemm_grouped_desc_t), vp, vp, vp, vp, vp]
-        L.axe_gemm_grouped_check.restype = C.c_int
-        L.axe_gemm_grouped_check.argtypes = [C.POINTER(axe_gemm_grouped_desc_t)]
-        L.axe_gemm_tile.restype = C.c_int
-        L.axe_gemm_tile.argtypes = [C.POINTER(axe_gemm_desc_t)]
-        L.axe_gemm_grouped_kernel.restype = C.c_int
-        L.axe_gemm_grouped_kernel.argtypes = [C.POINTER(axe_gemm_grouped_desc_t)]
-        L.axe_gemm_grouped_describe.restype = C.c_int
-        L.axe_gemm_grouped_describe.argtypes = [C.POINTER(axe_gemm_grouped_desc_t), i32, LP, C.POINTER(i64), C.POINTER(i32), vp, C.c_size_t]
-        L.axe_gemm_describe.restype = C.c_int
-        L.axe_gemm_describe.argtypes = [C.POINTER(axe_gemm_desc_t), i32, LP, C.POINTER(i64), C.POINTER(i32), vp,
-                                        C.c_size_t]
-        P64, P32, sz = C.POINTER(i64), C.POINTER(i32), C.c_size_t
-        for name, args in (("axe_layout_span", [LP, P64]), ("axe_layout_canonicalize", [LP, LP, vp, sz]),
-                           ("axe_layout_gap_condition", [LP]), ("axe_layout_equal", [LP, LP]),
-                           ("axe_layout_group", [LP, i32, P64, LP, P32, vp, sz]),
-                           ("axe_layout_tile", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
-                           ("axe_layout_direct_sum", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
-                           ("axe_layout_tile_of", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
-                           ("axe_layout_slice", [LP, i32, P64, P64, P64, LP, vp, sz])):
-            getattr(L, name).restype = C.c_int
-            getattr(L, name).argtypes = args
-        L.axe_strerror.restype = C.c_char_p
-        L.axe_strerror.argtypes = [C.c_int]
-        L.axe_last_error.restype = C.c_char_p
-        L.axe_version.restype = i32
-        _lib = L
+        _lib = load(LIB_PATH)
     return _lib
 
 

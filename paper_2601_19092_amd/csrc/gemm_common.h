@@ -24,6 +24,29 @@ __device__ __forceinline__ void wg_barrier() {
   asm volatile("" ::: "memory");
 }
 
+// Checking build (-DAXE_PARANOID, a library of its own that only a GPU test loads): the large-tile kernels rely on
+// counted waits, on loads and stores issued as asm statements that the compiler's own bookkeeping does not see, and on
+// one barrier per K-step.  In the checking build every load into LDS and every store is followed by a full wait, and
+// every row of MFMAs by a full wait and a workgroup barrier: nothing is in flight when anything is read.  The
+// arithmetic and its order are untouched, so both builds must produce the same bits; if they do not, the fast build
+// reads something before it has arrived.
+#ifdef AXE_PARANOID
+#define AXE_PARANOID_WAIT() asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory")
+#define AXE_PARANOID_SYNC()                                         \
+  do {                                                              \
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");     \
+    __builtin_amdgcn_s_barrier();                                   \
+    asm volatile("" ::: "memory");                                  \
+  } while (0)
+#else
+#define AXE_PARANOID_WAIT() \
+  do {                      \
+  } while (0)
+#define AXE_PARANOID_SYNC() \
+  do {                      \
+  } while (0)
+#endif
+
 __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
   typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
   bf16x2 v = {(__bf16)lo, (__bf16)hi};            // v_cvt_pk_bf16_f32, round to nearest even

@@ -325,6 +325,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16,
                                              a_voff_p[i], (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep, 0, 0);
+    AXE_PARANOID_WAIT();
   };
   // B ring: byte offsets of the blocks that hold K-steps kt, kt+1, kt+2 (step kt+3 reuses the first)
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
@@ -332,6 +333,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16,
                                              b_voff_p[i], (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * b_kstep, 0, 0);
+    AXE_PARANOID_WAIT();
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16
@@ -405,6 +407,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
       if (j * 16 + 4 * (l >> 4) + 4 > c_cw) voff = (int)0x80000000u;
     }
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
+    AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
     __builtin_amdgcn_sched_barrier(0);                             // one fragment at a time: copied out of the AGPRs, stored, cleared
@@ -414,6 +417,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const u32x2 d = {pack16<F16>(acc[i][j][0], acc[i][j][1]), pack16<F16>(acc[i][j][2], acc[i][j][3])};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
+    AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile
   };
@@ -442,6 +446,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
       if (j * 16 + c0 + 8 > c_cw) voff = (int)0x80000000u;
     }
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
+    AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
   };
@@ -463,6 +468,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 16);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    AXE_PARANOID_WAIT();
 #pragma unroll
     for (int q = 0; q < 4; ++q)
 #pragma unroll
@@ -538,6 +544,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
         }
         __builtin_amdgcn_sched_barrier(0);
       }
+      AXE_PARANOID_SYNC();
     }
     if (S == 0 && !LATE) step_barrier();
   };

@@ -128,6 +128,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + stage * kBlk + (w + 8 * i) * 1024), 16,
                                              a_voff, i * a_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+    AXE_PARANOID_WAIT();
   };
   // B ring: byte offsets of the blocks that hold tiles kt, kt+1, kt+2 (tile kt+3 reuses the first)
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
@@ -135,6 +136,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 8 * i) * 1024), 16,
                                              b_voff, i * b_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+    AXE_PARANOID_WAIT();
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16; the lane's
@@ -217,6 +219,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
         wg_barrier();
       }
       __builtin_amdgcn_sched_barrier(0);
+      if ((q & 3) == 3) AXE_PARANOID_SYNC();
     }
     const int t = bo0;
     bo0 = bo1, bo1 = bo2, bo2 = t;
@@ -241,6 +244,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
     const u32x2 d = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
+    AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile
   };

@@ -165,12 +165,14 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16, a_voff_p[i],
                                              (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+    AXE_PARANOID_WAIT();
   };
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;     // B ring: blocks of K-steps kt, kt+1, kt+2
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16, b_voff_p[i],
                                              (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+    AXE_PARANOID_WAIT();
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16, chunks q and q + 4
@@ -216,6 +218,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
   };
@@ -267,6 +270,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
         if (q >= 16 && (q & 3) == 2) b_load(bT, (q - 16) >> 2, bslot, CROSS);
       }
       __builtin_amdgcn_sched_barrier(0);
+      if ((q & 7) == 7) AXE_PARANOID_SYNC();
     }
     if (H == 0) {
       // Own loads of step kt+1 are complete (its last A piece was followed by 8 B loads, which may still be in

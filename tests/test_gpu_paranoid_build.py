@@ -1,0 +1,101 @@
+"""The fast build of the large-tile GEMM kernels against the checking build (libaxe_hip_paranoid.so: a full wait after
+every load into LDS and every store, a full wait and a workgroup barrier after every row of MFMAs).  Same arithmetic in
+the same order, so the two must agree bit for bit; a difference means that the fast build's counted waits, asm-issued
+loads and stores or single barrier per K-step let something be read before it had arrived."""
+import contextlib
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2601_19092_amd import binding as B
+from paper_2601_19092_amd import workloads as W
+
+pytestmark = pytest.mark.gpu
+
+PARANOID = os.path.join(os.path.dirname(B.LIB_PATH), "libaxe_hip_paranoid.so")
+
+
+@contextlib.contextmanager
+def library(path):
+    B.lib()
+    old = B._lib
+    B._lib = B.load(path)
+    try:
+        yield
+    finally:
+        B._lib = old
+
+
+def dev(a):
+    a = np.ascontiguousarray(a)
+    return torch.from_numpy(a.view({1: np.uint8, 2: np.int16, 4: np.int32}[a.dtype.itemsize])).cuda()
+
+
+def dense_case(which):
+    rows = 0
+    if which == "config4":
+        g, kw = W.config4(), dict(device_axis=True)
+    elif which == "bf16_chained_17x16":
+        g, kw = W.gemm_bf16(4352, 4096, 512, 91), {}
+    elif which == "bf16_ragged":
+        g, kw = W.gemm_bf16(1000, 1288, 512, 92), {}
+    elif which == "fp8_f32_scales":
+        g, kw = W.gemm_fp8(4352, 4096, 1024, 95, scaled=True), {}
+    elif which == "fp8_e8m0":
+        g, kw = W.gemm_fp8(4352, 4096, 1024, 96, scaled="e8m0"), {}
+    else:                                                  # one E8M0 code per row of A
+        g, kw = W.gemm_fp8(4352, 4096, 2048, 97, scaled="e8m0"), {}
+        g.scale_a = np.random.default_rng(5).integers(122, 133, (g.M, g.K // 128)).astype(np.uint8)
+        rows = 1
+    As, Bs, Cs = W.gemm_specs(g, shard=3, **kw)
+    axes = ["m", "gpuid"]
+    sa = torch.from_numpy(g.scale_a).cuda() if g.scale_a is not None else None
+    sb = torch.from_numpy(g.scale_b).cuda() if g.scale_b is not None else None
+    desc = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16 if g.dtype == "bf16" else B.AXE_FP8_E4M3, B.AXE_BF16,
+                      B.Layout(As, axes), B.Layout(Bs, axes), B.Layout(Cs, axes), g.M * g.K, g.N * g.K, g.M * g.N, sa, sb,
+                      scale_dtype=B.AXE_SCALE_E8M0 if g.scale_dtype == "e8m0" else B.AXE_SCALE_F32, scale_a_rows=rows,
+                      tile_hint=B.AXE_TILE_256x256x64 if which == "bf16_ragged" else B.AXE_TILE_AUTO)
+    return g, desc, dev(g.a_mk.reshape(-1)), dev(g.b_nk.reshape(-1))
+
+
+@pytest.mark.parametrize("which", ["config4", "bf16_chained_17x16", "bf16_ragged", "fp8_f32_scales", "fp8_e8m0", "fp8_e8m0_rows"])
+def test_dense_gemm_fast_build_equals_checking_build(which):
+    g, desc, dA, dB = dense_case(which)
+    assert B.axe_gemm_tile(desc) in (B.AXE_TILE_256x256x64, B.AXE_TILE_256x224x64)
+    out = []
+    for path in (B.LIB_PATH, PARANOID):
+        with library(path):
+            dC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
+            B.axe_gemm(desc, dA, dB, dC)
+            torch.cuda.synchronize()
+            out.append(dC)
+    assert torch.equal(out[0], out[1]), f"{(out[0] != out[1]).sum().item()} elements differ"
+
+
+@pytest.mark.parametrize("kernel,gated", [(B.AXE_GROUPED_TILES_256, False), (B.AXE_GROUPED_TILES_128, False), (B.AXE_GROUPED_TILES_128, True)])
+def test_grouped_gemm_fast_build_equals_checking_build(kernel, gated):
+    rng = np.random.default_rng(17)
+    off = np.concatenate([[0], np.cumsum(rng.integers(0, 400, 40))]).astype(np.int32)
+    N, K = 1536, 512
+    g = W.gemm_grouped_bf16(off, N, K, 98, std_b=2.0 * K ** -0.5)
+    NC = N // 2 if gated else N
+    plain = B.Layout(W.grouped_gemm_specs(g)[1])
+    dA, dB, dR = dev(g.a_mk.reshape(-1)), dev(g.b_gnk.reshape(-1)), torch.from_numpy(g.group_rows).cuda()
+    useL = plain
+    if gated:                                              # gate and up rows interleaved, packed by axe_relayout
+        useL = B.Layout(W.gated_b_spec(K, N, g.G, True))
+        packed = torch.empty_like(dB)
+        B.axe_relayout(plain, useL, (g.G, K, N), dB, packed)
+        dB = packed
+    desc = B.GroupedGemmDesc(g.M, N, K, g.G, B.Layout(W.row_major_spec(g.M, K)), useL, B.Layout(W.row_major_spec(g.M, NC)),
+                             g.M * K, g.b_gnk.size, g.M * NC, epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=kernel)
+    out = []
+    for path in (B.LIB_PATH, PARANOID):
+        with library(path):
+            dC = torch.zeros(g.M * NC, dtype=torch.int16, device="cuda")
+            B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+            torch.cuda.synchronize()
+            out.append(dC)
+    assert torch.equal(out[0], out[1]), f"{(out[0] != out[1]).sum().item()} elements differ"

@@ -17,7 +17,7 @@ from oracle.axe_layout import Iter, Layout, Swizzle
 from paper_2601_19092_amd import binding as B
 from paper_2601_19092_amd import workloads as W
 
-HOSTCHECK = os.path.join(os.path.dirname(B.LIB_PATH), "libaxe_hostcheck.so")
+HOSTCHECK = os.environ.get("AXE_TEST_HOST_LIB") or os.path.join(os.path.dirname(B.LIB_PATH), "libaxe_hostcheck.so")
 
 
 @pytest.fixture(scope="module")
