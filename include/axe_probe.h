@@ -33,6 +33,19 @@ extern "C" {
 int axe_probe_mfma(int32_t fp8, const void* sample, size_t sample_bytes, int32_t iters, float* sink, size_t sink_floats,
                    double* flops, void* stream);
 
+/* Launches, on `stream`, ONE matrix instruction of one wave on operand registers the caller supplies, and returns the
+ * accumulator registers: the experiment that shows which (lane, register) holds which element of the operands and of
+ * the result.  The instruction is issued as the GEMM kernels issue it (B fragment first, A fragment second, zero
+ * accumulator).  kind 0: v_mfma_f32_16x16x32_bf16, 1: v_mfma_f32_16x16x32_f16 (16 bytes per lane and operand);
+ * 2: v_mfma_f32_16x16x128_f8f6f4 with e4m3 operands (32 bytes per lane and operand), 3: the same through the scale
+ * path, with the E8M0 code of lane l's operand in byte 0 of a_scale[l] / b_scale[l].
+ *   a_regs, b_regs  device pointers, 32-byte aligned: lane l's operand registers at byte offset l * 16 (l * 32)
+ *   a_scale, b_scale  device pointers to 64 words (kind 3 only, else ignored)
+ *   acc_regs        device pointer, 32-byte aligned, to 64 x 4 floats: lane l's accumulator registers 0..3
+ * Asynchronous; returns 0, 1 for a bad argument, 2 if the launch failed.  Nothing is allocated. */
+int axe_probe_mfma_fragment(int32_t kind, const void* a_regs, const void* b_regs, const uint32_t* a_scale, const uint32_t* b_scale,
+                            float* acc_regs, void* stream);
+
 /* Launches, on `stream`, one pass of a plain HBM stream over `bytes` bytes (a multiple of 16; buffers 16-byte
  * aligned): 128-bit non-temporal accesses, four per thread, the access shape of the relayout kernels without
  * any address arithmetic.  kind 0: copy src -> dst; 1: read src only (dst may be NULL); 2: write dst only

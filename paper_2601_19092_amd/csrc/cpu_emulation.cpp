@@ -186,3 +186,99 @@ extern "C" void axe_hostcheck_set_buffers(int64_t src_bytes, int64_t dst_bytes) 
 }
 extern "C" int axe_hostcheck_violations(void) { return axe::g_violations; }
 extern "C" int axe_hostcheck_transposes(void) { return axe::g_transposes; }
+
+// ---------------------------------------------------------------------------------------------------------------
+// Test hook: a layout axe_gemm_describe reports, evaluated at every point of its tile (through axe_layout_eval and
+// the host-memory stand-in above), against the index functions of tile_maps.h that the kernels compute their
+// addresses with.  Geometry (tile T x TN x BK, element bytes, waves, wave columns, element offset of the B region in
+// an LDS stage, workgroup grid columns for the accumulator layout) comes from the caller.  Returns the number of
+// points that differ (0 = the described layout is the kernels' map), or a negative error code.
+#include "../../include/axe.h"
+#include "tile_maps.h"
+
+extern "C" int axe_hostcheck_describe_vs_tile_maps(const axe_gemm_desc_t* g, int32_t which, int32_t T, int32_t TN, int32_t BK,
+                                                   int32_t EB, int32_t NW, int32_t WN, int64_t b_off, int32_t paired_stores) {
+  namespace maps = axe::maps;
+  enum { M_ = 0, LDS = 1, WG = 2, WAVE = 3, LANE = 4, REG = 5, NAX = 6 };
+  axe_layout_t L;
+  int64_t shape[AXE_MAX_RANK];
+  int32_t rank = 0;
+  alignas(16) char arena[4096];
+  if (int rc = axe_gemm_describe(g, which, &L, shape, &rank, arena, sizeof arena)) return rc;
+  if (rank != 2 || L.n_axes != NAX) return AXE_EINVAL;
+  int64_t ER = 1;
+  for (int i = 0; i < L.n_r; ++i) ER *= L.r[i].extent;
+  const int64_t n = shape[0] * shape[1];
+  std::vector<int64_t> pts((size_t)(n * ER * NAX));
+  if (int rc = axe_layout_eval(&L, 2, shape, n, nullptr, pts.data(), nullptr)) return rc;
+  const int CE = maps::kChunkBytes / EB, CH = BK / CE, WM = NW / WN, F = maps::kFrag;
+  const bool big = T > 64, fp8 = EB == 1;
+  const bool is_b = which == AXE_DESC_B_G2L_THREADS || which == AXE_DESC_B_LDS || which == AXE_DESC_B_OPERAND;
+  int bad = 0;
+  for (int64_t x = 0; x < n; ++x) {
+    const int64_t u0 = x / shape[1], u1 = x % shape[1];
+    const int64_t* p = &pts[(size_t)(x * ER * NAX)];
+    int64_t want[NAX] = {0, 0, 0, 0, 0, 0};
+    bool replicated = false;
+    if (which <= AXE_DESC_B_OPERAND) {
+      const int r = (int)(is_b ? u1 : u0), k = (int)(is_b ? u0 : u1);   // row of the operand, k inside the K-tile
+      const int chunk = k / CE, e = k % CE;
+      if (which == AXE_DESC_A_LDS || which == AXE_DESC_B_LDS) {
+        want[LDS] = (is_b ? b_off : 0) + ((int64_t)r * CH + maps::lds_chunk_pos(r, chunk, CH)) * CE + e;
+      } else if (which == AXE_DESC_A_G2L_THREADS || which == AXE_DESC_B_G2L_THREADS) {
+        if (big) {
+          const int RPL = maps::kRowsPerLoad;
+          const int w = (r / RPL) % NW, i = r / (RPL * NW), lr = r % RPL;
+          if (maps::piece_row(w, i, lr, NW) != r) ++bad;
+          want[LANE] = 64 * w + maps::kLargeChunks * lr + maps::lds_chunk_pos(r, chunk, CH);   // thread id: wave folded into the lane axis
+          want[REG] = i * CE + e;
+        } else {
+          const int c = r * CH + chunk, t = c % 256;
+          want[WAVE] = t / 64, want[LANE] = t % 64, want[REG] = (c / 256) * CE + e;
+        }
+      } else {
+        const int WT = is_b ? TN / WN : T / WM, NF = WT / F;
+        const int wv = r / WT, f = (r % WT) / F, fr = r % F;
+        int q = -1, sub = -1;
+        for (int s = 0; s < 8 && q < 0; ++s)
+          for (int qq = 0; qq < maps::kLaneGroups; ++qq)
+            if ((fp8 ? (s < 2 ? maps::operand_chunk_fp8(s, qq) : -1) : maps::operand_chunk_16bit(s, qq)) == chunk) q = qq, sub = s;
+        if (q < 0) return AXE_EINVAL;
+        want[LANE] = fr + F * q;
+        want[REG] = fp8 ? (int64_t)f * 2 * CE + sub * CE + e : ((int64_t)sub * NF + f) * CE + e;
+        // the rows are split over one wave dimension and replicated over the other: replica t is wave ...
+        replicated = true;
+        for (int64_t t = 0; t < ER; ++t) {
+          want[WAVE] = is_b ? WN * t + wv : WN * wv + t;
+          for (int a = 0; a < NAX; ++a)
+            if (p[t * NAX + a] != want[a]) { ++bad; break; }
+        }
+        if (ER != (is_b ? WM : WN)) ++bad;
+      }
+    } else {
+      const int i = (int)u0, j = (int)u1;                  // element of C (of the padded problem for AXE_DESC_ACC)
+      const int gn = (int)(shape[1] / TN);
+      const int ti = i % T, tj = j % TN;
+      const int WTM = T / WM, WTN = TN / WN, NFN = WTN / F;
+      const int wm = ti / WTM, wn = tj / WTN, fi = (ti % WTM) / F, fj = (tj % WTN) / F;
+      want[WG] = (int64_t)(i / T) * gn + j / TN;
+      want[WAVE] = WN * wm + wn;
+      if (which == AXE_DESC_C_STORE && paired_stores) {
+        const int cc = tj % (2 * F), pair = (tj % WTN) / (2 * F);
+        int q = -1;
+        for (int qq = 0; qq < maps::kLaneGroups; ++qq)
+          if (cc >= maps::pair_store_col(qq) && cc < maps::pair_store_col(qq) + 2 * maps::kAccCols) q = qq;
+        if (q < 0) return AXE_EINVAL;
+        want[LANE] = ti % F + F * q;
+        want[REG] = ((int64_t)fi * (NFN / 2) + pair) * 2 * maps::kAccCols + (cc - maps::pair_store_col(q));
+      } else {
+        want[LANE] = ti % F + F * ((tj % F) / maps::kAccCols);
+        want[REG] = ((int64_t)fi * NFN + fj) * maps::kAccCols + tj % maps::kAccCols;
+      }
+    }
+    if (!replicated)
+      for (int a = 0; a < NAX; ++a)
+        if (p[a] != want[a]) { ++bad; break; }
+  }
+  return bad;
+}

@@ -64,11 +64,12 @@
 #include "device_types.h"
 #include "gemm_common.h"
 #include "kernels.h"
+#include "tile_maps.h"
 
 namespace axe {
 
 namespace {
-constexpr int kRow = 128;                         // bytes of K per LDS row (64 bf16)
+constexpr int kRow = maps::kLargeRowBytes;         // bytes of K per LDS row (64 bf16)
 constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-tile
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
@@ -303,11 +304,11 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   //      i = 0..7 = row groups w, w + 4, ..., w + 28.  Buffer addressing: the descriptor covers the 256
   //      rows of the tile (reads past its end return zero), the per-lane offset is fixed, K-tile and
   //      piece go into the scalar offset.
-  const int lr = lane >> 3, lp = lane & 7;
-  const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 4 i) * 8 + lr
-  const int a_voff_x = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
-  const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
-  const int a_piece = 32 * a_pitch, b_piece = 32 * b_pitch;        // bytes between pieces
+  const int lr = lane / maps::kLargeChunks, lp = lane % maps::kLargeChunks;
+  const int lrow = maps::piece_row(w, 0, lr, 4);                   // row of piece 0; piece i lies 32 i rows further (same key)
+  const int a_voff_x = lrow * a_pitch + maps::lds_chunk_pos(lrow, lp, maps::kLargeChunks) * maps::kChunkBytes;
+  const int b_voff = lrow * b_pitch + maps::lds_chunk_pos(lrow, lp, maps::kLargeChunks) * maps::kChunkBytes;
+  const int a_piece = maps::piece_row(0, 1, 0, 4) * a_pitch, b_piece = maps::piece_row(0, 1, 0, 4) * b_pitch;   // bytes between pieces
   // Both operands go from HBM straight into LDS (no staging registers, no ds_write: a ds_write_b128 keeps its
   // wave from issuing for about 20 cycles, and 8 of them per K-step cost 7 % of the whole kernel).  A direct
   // load fills 1 KiB of LDS linearly in the lane id, so the XOR of the LDS image is applied to the chunk a
@@ -323,7 +324,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   for (int i = 0; i < 8; ++i) b_voff_p[i] = b_voff + i * b_piece;
   auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16,
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + maps::piece_row(w, i, 0, 4) * kRow), 16,
                                              a_voff_p[i], (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep, 0, 0);
     AXE_PARANOID_WAIT();
   };
@@ -331,19 +332,20 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16,
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + maps::piece_row(w, i, 0, 4) * kRow), 16,
                                              b_voff_p[i], (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * b_kstep, 0, 0);
     AXE_PARANOID_WAIT();
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16
-  const int fr = lane & 15, fq = lane >> 4;
-  const int fkey = (fr >> 1) & 7;
+  const int fr = lane % maps::kFrag, fq = lane / maps::kFrag;
   lds_u8 fax[2], fbx[2];                                           // row base + swizzled chunk, per sub-step
 #pragma unroll
   for (int s = 0; s < 2; ++s) {
-    fax[s] = lds3 + (wm * (16 * MR) + fr) * kRow + (((4 * s + fq) ^ fkey) << 4);
-    fbx[s] = lds3 + (wn * (NB / 2) + fr) * kRow + (((4 * s + fq) ^ fkey) << 4);
+    // (the wave's first row is a multiple of 16 = one period of the key: the key is that of row fr)
+    const int pos = maps::lds_chunk_pos(fr, maps::operand_chunk_16bit(s, fq), maps::kLargeChunks) * maps::kChunkBytes;
+    fax[s] = lds3 + (wm * (16 * MR) + fr) * kRow + pos;
+    fbx[s] = lds3 + (wn * (NB / 2) + fr) * kRow + pos;
   }
 
   f32x4 acc[MR][NJ];
@@ -426,7 +428,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   // the first with the even lane groups of the second, after which an even group q owns columns
   // 4 q .. 4 q + 7 of fragment j and an odd group q columns 4 (q - 1) .. 4 q + 3 of fragment j + 1.
   // Half as many store instructions and write requests; 64 contiguous bytes per row and instruction.
-  const int c_voff2 = (int)((fr * g.ldc + ((fq & 1) ? 16 + 4 * (fq - 1) : 4 * fq)) * 2);
+  const int c_voff2 = (int)((fr * g.ldc + maps::pair_store_col(fq)) * 2);
   auto store_fragment_pair = [&](int i, int j) __attribute__((always_inline)) {
     const auto lo = __builtin_amdgcn_permlane16_swap(pack16<F16>(acc[i][j][0], acc[i][j][1]),
                                                      pack16<F16>(acc[i][j + 1][0], acc[i][j + 1][1]), false, false);
@@ -442,7 +444,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
       int l;
       asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
       const int q = l >> 4;
-      const int c0 = (q & 1) ? 16 + 4 * (q - 1) : 4 * q;
+      const int c0 = maps::pair_store_col(q);
       if (j * 16 + c0 + 8 > c_cw) voff = (int)0x80000000u;
     }
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
@@ -556,18 +558,20 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   };
 
   // ---- prologue (first tile only): what the sub-steps before (0, 0) would have done: steps 0 and 1 of A,
-  //      steps 0, 1 and the first half of step 2 of B.
+  //      steps 0, 1 and the first half of step 2 of B.  Step 0 of both operands first: the MFMAs start as soon as it
+  //      has landed (the NA + 12 loads of step 1 and of step 2's first half may still be in flight; the barrier of
+  //      step 0 waits for step 1 as the barrier of every step does, with step 2's eight B loads behind it).
 #pragma unroll
   for (int i = 0; i < NA; ++i) a_dload(0, i, true);
 #pragma unroll
-  for (int i = 0; i < NA; ++i) a_dload(1, i, true);                // (a single K-step per tile: step 1 is the next tile's step 0)
-#pragma unroll
   for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
+#pragma unroll
+  for (int i = 0; i < NA; ++i) a_dload(1, i, true);                // (a single K-step per tile: step 1 is the next tile's step 0)
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(1, i, bo1, true);
 #pragma unroll
   for (int i = 0; i < 4; ++i) b_load(2, i, bo2, true);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NA + 12) : "memory");
   wg_barrier();
 #pragma unroll
   for (int f = 0; f < NJ; ++f) fb[0][f] = lds_read(fbx[0] + bo0 + f * 16 * kRow);

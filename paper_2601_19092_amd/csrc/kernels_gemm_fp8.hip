@@ -49,11 +49,12 @@
 #include "device_types.h"
 #include "gemm_common.h"
 #include "kernels.h"
+#include "tile_maps.h"
 
 namespace axe {
 
 namespace {
-constexpr int kRow = 128;                         // bytes of K per LDS row (128 fp8)
+constexpr int kRow = maps::kLargeRowBytes;         // bytes of K per LDS row (128 fp8)
 constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-tile
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
@@ -119,14 +120,14 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   // ---- HBM -> LDS.  Per K-tile and operand 32 wave instructions of 8 rows; wave w issues pieces
   //      i = 0..3 = row groups w, w + 8, w + 16, w + 24.  Step T >= nk of the current tile is step
   //      T - nk of the next one (cross = false: the caller knows T < nk).
-  const int lr = lane >> 3, lp = lane & 7;
-  const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 8 i) * 8 + lr
-  const int a_voff = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
-  const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
-  const int a_piece = 64 * a_pitch, b_piece = 64 * b_pitch;        // bytes between pieces
+  const int lr = lane / maps::kLargeChunks, lp = lane % maps::kLargeChunks;
+  const int lrow = maps::piece_row(w, 0, lr, 8);                   // row of piece 0; piece i lies 64 i rows further (same key)
+  const int a_voff = lrow * a_pitch + maps::lds_chunk_pos(lrow, lp, maps::kLargeChunks) * maps::kChunkBytes;
+  const int b_voff = lrow * b_pitch + maps::lds_chunk_pos(lrow, lp, maps::kLargeChunks) * maps::kChunkBytes;
+  const int a_piece = maps::piece_row(0, 1, 0, 8) * a_pitch, b_piece = maps::piece_row(0, 1, 0, 8) * b_pitch;   // bytes between pieces
   auto a_load = [&](int T, int i, int stage, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + stage * kBlk + (w + 8 * i) * 1024), 16,
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + stage * kBlk + maps::piece_row(w, i, 0, 8) * kRow), 16,
                                              a_voff, i * a_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
     AXE_PARANOID_WAIT();
   };
@@ -134,19 +135,20 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 8 * i) * 1024), 16,
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + maps::piece_row(w, i, 0, 8) * kRow), 16,
                                              b_voff, i * b_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
     AXE_PARANOID_WAIT();
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16; the lane's
   //      32 bytes are the chunks q and q + 4 (q = lane / 16), found at positions q ^ key, (q + 4) ^ key
-  const int fr = lane & 15, fq = lane >> 4;
-  const int fkey = (fr >> 1) & 7;
-  const lds_u8 fa0 = lds3 + (wm * 128 + fr) * kRow + ((fq ^ fkey) << 4);
-  const lds_u8 fa1 = lds3 + (wm * 128 + fr) * kRow + (((fq + 4) ^ fkey) << 4);
-  const lds_u8 fb0 = lds3 + (wn * 64 + fr) * kRow + ((fq ^ fkey) << 4);
-  const lds_u8 fb1 = lds3 + (wn * 64 + fr) * kRow + (((fq + 4) ^ fkey) << 4);
+  const int fr = lane % maps::kFrag, fq = lane / maps::kFrag;
+  const int pos0 = maps::lds_chunk_pos(fr, maps::operand_chunk_fp8(0, fq), maps::kLargeChunks) * maps::kChunkBytes;
+  const int pos1 = maps::lds_chunk_pos(fr, maps::operand_chunk_fp8(1, fq), maps::kLargeChunks) * maps::kChunkBytes;
+  const lds_u8 fa0 = lds3 + (wm * 128 + fr) * kRow + pos0;
+  const lds_u8 fa1 = lds3 + (wm * 128 + fr) * kRow + pos1;
+  const lds_u8 fb0 = lds3 + (wn * 64 + fr) * kRow + pos0;
+  const lds_u8 fb1 = lds3 + (wn * 64 + fr) * kRow + pos1;
 
   f32x4 acc[8][4];
 #pragma unroll
@@ -258,7 +260,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   for (int i = 0; i < 4; ++i) a_load(1, i, 1, true);
 #pragma unroll
   for (int i = 0; i < 4; ++i) b_load(1, i, bo1, true);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(8)" ::: "memory");                  // tile 0 has landed; the 8 loads of tile 1 may still be in flight
   wg_barrier();
 #pragma unroll
   for (int f = 0; f < 4; ++f) read_b(f, bo0);

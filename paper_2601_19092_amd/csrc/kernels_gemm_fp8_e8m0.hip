@@ -34,11 +34,12 @@
 #include "device_types.h"
 #include "gemm_common.h"
 #include "kernels.h"
+#include "tile_maps.h"
 
 namespace axe {
 
 namespace {
-constexpr int kRow = 128;                         // bytes of K per LDS row (128 fp8)
+constexpr int kRow = maps::kLargeRowBytes;         // bytes of K per LDS row (128 fp8)
 constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-tile
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
@@ -152,36 +153,37 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   // ---- HBM -> LDS, both operands directly (as in the bf16 kernel; pitches and columns in bytes = elements): a wave
   //      instruction fills 8 rows x 128 bytes linearly in the lane id, so the XOR of the LDS image is applied to
   //      the chunk a lane fetches.  A has two blocks (the steps of either parity), B a ring of three.
-  const int lr = lane >> 3, lp = lane & 7;
-  const int lkey = (4 * w + (lr >> 1)) & 7;                        // key(row) of row (w + 4 i) * 8 + lr
-  const int a_voff_x = (w * 8 + lr) * a_pitch + ((lp ^ lkey) << 4);
-  const int b_voff = (w * 8 + lr) * b_pitch + ((lp ^ lkey) << 4);
-  const int a_piece = 32 * a_pitch, b_piece = 32 * b_pitch;        // bytes between pieces
+  const int lr = lane / maps::kLargeChunks, lp = lane % maps::kLargeChunks;
+  const int lrow = maps::piece_row(w, 0, lr, 4);                   // row of piece 0; piece i lies 32 i rows further (same key)
+  const int a_voff_x = lrow * a_pitch + maps::lds_chunk_pos(lrow, lp, maps::kLargeChunks) * maps::kChunkBytes;
+  const int b_voff = lrow * b_pitch + maps::lds_chunk_pos(lrow, lp, maps::kLargeChunks) * maps::kChunkBytes;
+  const int a_piece = maps::piece_row(0, 1, 0, 4) * a_pitch, b_piece = maps::piece_row(0, 1, 0, 4) * b_pitch;   // bytes between pieces
   // (the piece goes into the per-lane offset, one register per piece: the scalar offset is the K-tile's alone)
   int a_voff_p[8], b_voff_p[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) a_voff_p[i] = a_voff_x + i * a_piece, b_voff_p[i] = b_voff + i * b_piece;
   auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + (w + 4 * i) * 1024), 16, a_voff_p[i],
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + maps::piece_row(w, i, 0, 4) * kRow), 16, a_voff_p[i],
                                              (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
     AXE_PARANOID_WAIT();
   };
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;     // B ring: blocks of K-steps kt, kt+1, kt+2
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + (w + 4 * i) * 1024), 16, b_voff_p[i],
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + maps::piece_row(w, i, 0, 4) * kRow), 16, b_voff_p[i],
                                              (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
     AXE_PARANOID_WAIT();
   };
 
   // ---- LDS -> VGPR: fragment f of this wave's A (B) rows: row = base + f * 16 + lane % 16, chunks q and q + 4
-  const int fr = lane & 15, fq = lane >> 4;
-  const int fkey = (fr >> 1) & 7;
-  const lds_u8 fax0 = lds3 + (wm * 128 + fr) * kRow + ((fq ^ fkey) << 4);
-  const lds_u8 fax1 = lds3 + (wm * 128 + fr) * kRow + (((fq + 4) ^ fkey) << 4);
-  const lds_u8 fbx0 = lds3 + (wn * 128 + fr) * kRow + ((fq ^ fkey) << 4);
-  const lds_u8 fbx1 = lds3 + (wn * 128 + fr) * kRow + (((fq + 4) ^ fkey) << 4);
+  const int fr = lane % maps::kFrag, fq = lane / maps::kFrag;
+  const int pos0 = maps::lds_chunk_pos(fr, maps::operand_chunk_fp8(0, fq), maps::kLargeChunks) * maps::kChunkBytes;
+  const int pos1 = maps::lds_chunk_pos(fr, maps::operand_chunk_fp8(1, fq), maps::kLargeChunks) * maps::kChunkBytes;
+  const lds_u8 fax0 = lds3 + (wm * 128 + fr) * kRow + pos0;
+  const lds_u8 fax1 = lds3 + (wm * 128 + fr) * kRow + pos1;
+  const lds_u8 fbx0 = lds3 + (wn * 128 + fr) * kRow + pos0;
+  const lds_u8 fbx1 = lds3 + (wn * 128 + fr) * kRow + pos1;
   auto read_a = [&](int f, int off) __attribute__((always_inline)) -> i32x8 {
     return lds_read32(fax0 + off + f * 16 * kRow, fax1 + off + f * 16 * kRow);
   };
@@ -202,7 +204,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   // ---- VGPR -> HBM (as in the bf16 kernel: fragment pairs exchange halves, 16 bytes per lane)
   i32x4 rc;
   int c_rowblk;
-  const int c_voff2 = (int)((fr * g.ldc + ((fq & 1) ? 16 + 4 * (fq - 1) : 4 * fq)) * 2);
+  const int c_voff2 = (int)((fr * g.ldc + maps::pair_store_col(fq)) * 2);
   auto set_output = [&](int vv) __attribute__((always_inline)) {
     int tm, tn;
     tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
@@ -316,19 +318,21 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   };
 
   // ---- prologue (first tile only): steps 0 and 1 of A, steps 0, 1 and half of 2 of B
+  //      Step 0 of both operands and the scale codes first: the MFMAs start as soon as these have landed (the 20 loads
+  //      of step 1 and of step 2's first half may still be in flight, as at the barrier of every later step).
 #pragma unroll
   for (int i = 0; i < 8; ++i) a_dload(0, i, true);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a_dload(1, i, true);                 // (a single K-step per tile: step 1 is the next tile's step 0)
-#pragma unroll
   for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
+  fetch_codes(cur, 0, cva, cvb);
+  if constexpr (ROWS) fetch_rows(cur, 0);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a_dload(1, i, true);                 // (a single K-step per tile: step 1 is the next tile's step 0)
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(1, i, bo1, true);
 #pragma unroll
   for (int i = 0; i < 4; ++i) b_load(2, i, bo2, true);
-  fetch_codes(cur, 0, cva, cvb);
-  if constexpr (ROWS) fetch_rows(cur, 0);
-  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
   wg_barrier();
 #pragma unroll
   for (int f = 0; f < 8; ++f) fb[f] = read_b(f, bo0);

@@ -20,6 +20,7 @@
 
 #include "device_types.h"
 #include "kernels.h"
+#include "tile_maps.h"
 
 namespace axe {
 
@@ -46,7 +47,6 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
   constexpr int CH = ROWB / 16;               // 16-byte chunks per row
   constexpr int BK = ROWB / EB;               // elements per K step
   constexpr int PER = (64 * CH) / 256;        // chunks per thread per operand
-  constexpr int KEYSH = 1;                    // swizzle key = (row >> KEYSH) & (CH - 1)
 
   __shared__ __attribute__((aligned(16))) uint8_t lds[2][2][64 * ROWB];   // [stage][A|B]
 
@@ -75,7 +75,7 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
     for (int p = 0; p < PER; ++p) {
       int c = tid + p * 256;
       int row = c / CH, ch = c % CH;
-      int pc = ch ^ ((row >> KEYSH) & (CH - 1));
+      int pc = maps::lds_chunk_pos(row, ch, CH);
       *(uint4*)(&lds[st][0][row * ROWB + pc * 16]) = ra[p];
       *(uint4*)(&lds[st][1][row * ROWB + pc * 16]) = rb[p];
     }
@@ -101,9 +101,9 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
 #pragma unroll
       for (int f = 0; f < 2; ++f) {
         int r = wm * 32 + f * 16 + frow;
-        fa[f] = *(const bf16x8*)(&lds[st][0][r * ROWB + ((fgrp ^ ((r >> KEYSH) & (CH - 1))) * 16)]);
+        fa[f] = *(const bf16x8*)(&lds[st][0][r * ROWB + maps::lds_chunk_pos(r, maps::operand_chunk_16bit(0, fgrp), CH) * 16]);
         r = wn * 32 + f * 16 + frow;
-        fb[f] = *(const bf16x8*)(&lds[st][1][r * ROWB + ((fgrp ^ ((r >> KEYSH) & (CH - 1))) * 16)]);
+        fb[f] = *(const bf16x8*)(&lds[st][1][r * ROWB + maps::lds_chunk_pos(r, maps::operand_chunk_16bit(0, fgrp), CH) * 16]);
       }
 #pragma unroll
       for (int i = 0; i < 2; ++i)
@@ -121,14 +121,12 @@ __global__ __launch_bounds__(256) void gemm_small_kernel(GemmArgs g) {
 #pragma unroll
       for (int f = 0; f < 2; ++f) {
         int r = wm * 32 + f * 16 + frow;
-        int key = (r >> KEYSH) & (CH - 1);
-        i32x4 lo = *(const i32x4*)(&lds[st][0][r * ROWB + ((fgrp ^ key) * 16)]);
-        i32x4 hi = *(const i32x4*)(&lds[st][0][r * ROWB + (((fgrp + 4) ^ key) * 16)]);
+        i32x4 lo = *(const i32x4*)(&lds[st][0][r * ROWB + maps::lds_chunk_pos(r, maps::operand_chunk_fp8(0, fgrp), CH) * 16]);
+        i32x4 hi = *(const i32x4*)(&lds[st][0][r * ROWB + maps::lds_chunk_pos(r, maps::operand_chunk_fp8(1, fgrp), CH) * 16]);
         fa[f] = i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
         r = wn * 32 + f * 16 + frow;
-        key = (r >> KEYSH) & (CH - 1);
-        lo = *(const i32x4*)(&lds[st][1][r * ROWB + ((fgrp ^ key) * 16)]);
-        hi = *(const i32x4*)(&lds[st][1][r * ROWB + (((fgrp + 4) ^ key) * 16)]);
+        lo = *(const i32x4*)(&lds[st][1][r * ROWB + maps::lds_chunk_pos(r, maps::operand_chunk_fp8(0, fgrp), CH) * 16]);
+        hi = *(const i32x4*)(&lds[st][1][r * ROWB + maps::lds_chunk_pos(r, maps::operand_chunk_fp8(1, fgrp), CH) * 16]);
         fb[f] = i32x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
       }
       if (g.scale_a) {

@@ -71,6 +71,33 @@ __global__ __launch_bounds__(512, 1) void probe_fp8_kernel(const i32x8* __restri
     for (int j = 0; j < 4; ++j) s += acc[i][j][0] + acc[i][j][1] + acc[i][j][2] + acc[i][j][3];
   out[blockIdx.x * 512 + threadIdx.x] = s;
 }
+// One MFMA on operand registers the caller supplies, lane by lane: where do the products land?  The instruction is
+// issued the way the GEMM kernels issue it -- the B fragment as the first operand, the A fragment as the second, so
+// that a lane's accumulator registers hold consecutive columns of one row -- with a zero accumulator.  KIND 0:
+// v_mfma_f32_16x16x32_bf16, 1: v_mfma_f32_16x16x32_f16, 2: v_mfma_f32_16x16x128_f8f6f4 (e4m3, unscaled), 3: the
+// same on the scale path, each lane supplying the E8M0 code of its operand in byte 0 of a register.
+template <int KIND>
+__global__ __launch_bounds__(64) void probe_fragment_kernel(const uint8_t* __restrict__ a, const uint8_t* __restrict__ b,
+                                                            const uint32_t* __restrict__ sa, const uint32_t* __restrict__ sb,
+                                                            float* __restrict__ acc_out) {
+  const int lane = threadIdx.x;
+  f32x4 acc = {0.f, 0.f, 0.f, 0.f};
+  if constexpr (KIND <= 1) {
+    const bf16x8 fa = *(const bf16x8*)(a + lane * 16), fb = *(const bf16x8*)(b + lane * 16);
+    if constexpr (KIND == 0) acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(fb, fa, acc, 0, 0, 0);
+    else {
+      typedef __attribute__((ext_vector_type(8))) _Float16 f16x8;
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, fb), __builtin_bit_cast(f16x8, fa), acc, 0, 0, 0);
+    }
+  } else {
+    const i32x8 fa = *(const i32x8*)(a + lane * 32), fb = *(const i32x8*)(b + lane * 32);
+    if constexpr (KIND == 2) acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb, fa, acc, 0, 0, 0, 0, 0, 0);
+    else acc = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(fb, fa, acc, 0, 0, 0, (int)sb[lane], 0, (int)sa[lane]);
+  }
+#pragma unroll
+  for (int e = 0; e < 4; ++e) acc_out[lane * 4 + e] = acc[e];
+}
+
 // HBM streams: what this machine's memory system gives a plain kernel -- 16 bytes per lane and access, four accesses per
 // thread issued together, non-temporal, one pass over the buffers.  KIND 0: copy, 1: read only (the words are
 // folded into a sum nobody needs, written only if it has an impossible value so that the loads stay), 2: write only.
@@ -97,6 +124,22 @@ __global__ __launch_bounds__(256) void probe_stream_kernel(const probe_u32x4* __
     if (i + u * 256 < n) __builtin_nontemporal_store(v[u], &dst[i + u * 256]);
 }
 }  // namespace
+
+extern "C" int axe_probe_mfma_fragment(int32_t kind, const void* a_regs, const void* b_regs, const uint32_t* a_scale,
+                                       const uint32_t* b_scale, float* acc_regs, void* stream) {
+  if (kind < 0 || kind > 3 || !a_regs || !b_regs || !acc_regs || (kind == 3 && (!a_scale || !b_scale)) ||
+      (((uintptr_t)a_regs | (uintptr_t)b_regs | (uintptr_t)acc_regs) & 31))
+    return 1;
+  hipStream_t st = (hipStream_t)stream;
+  const uint8_t *a = (const uint8_t*)a_regs, *b = (const uint8_t*)b_regs;
+  switch (kind) {
+    case 0: hipLaunchKernelGGL(probe_fragment_kernel<0>, dim3(1), dim3(64), 0, st, a, b, a_scale, b_scale, acc_regs); break;
+    case 1: hipLaunchKernelGGL(probe_fragment_kernel<1>, dim3(1), dim3(64), 0, st, a, b, a_scale, b_scale, acc_regs); break;
+    case 2: hipLaunchKernelGGL(probe_fragment_kernel<2>, dim3(1), dim3(64), 0, st, a, b, a_scale, b_scale, acc_regs); break;
+    default: hipLaunchKernelGGL(probe_fragment_kernel<3>, dim3(1), dim3(64), 0, st, a, b, a_scale, b_scale, acc_regs); break;
+  }
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
 
 extern "C" int axe_probe_stream(int32_t kind, const void* src, void* dst, size_t bytes, void* stream) {
   if (kind < 0 || kind > 2 || bytes == 0 || bytes % 16 || (kind != 2 && !src) || (kind != 1 && !dst) ||

@@ -247,6 +247,29 @@ def test_c_store_map(kind):
             assert p[5] % 8 == 4 * ((cc % 8) // 4) + c % 4 and p[3] == 2 * (r // 128) + c // 128
 
 
+@pytest.mark.parametrize("kind", KINDS)
+def test_described_layouts_are_the_index_functions_the_kernels_compute_with(kind):
+    """csrc/tile_maps.h states, as plain integer functions, where the kernels put things: the LDS chunk position of a
+    row's chunk, the row a wave instruction's lane fetches, the chunk a lane group reads for its MFMA operand, the
+    columns a lane stores.  The kernels call these functions; here every described layout, evaluated at every point of
+    its tile by the host layer, must give the same coordinates as the functions (a test-only routine of the host
+    library does the comparison in C++ against the header itself)."""
+    import ctypes as C
+    import os
+    hc = C.CDLL(os.environ.get("AXE_TEST_HOST_LIB") or os.path.join(os.path.dirname(B.LIB_PATH), "libaxe_hostcheck.so"))
+    fn = hc.axe_hostcheck_describe_vs_tile_maps
+    fn.restype = C.c_int
+    fn.argtypes = [C.POINTER(B.axe_gemm_desc_t)] + [C.c_int32] * 7 + [C.c_int64, C.c_int32]
+    hc.axe_last_error.restype = C.c_char_p
+    desc, _ = desc_for(kind)
+    geo = GEO[kind]
+    b_off = geo["T"] * geo["BK"] * (2 if kind in BIG else 1)
+    for which in range(8):
+        rc = fn(C.byref(desc.c), which, geo["T"], geo["TN"], geo["BK"], geo["EB"], geo["waves"], geo["wn"], b_off,
+                int(kind in PAIRED_STORES))
+        assert rc == 0, (kind, which, rc, hc.axe_last_error().decode())
+
+
 def test_mfma_operand_layout_matches_its_statement():
     """MFMA 16x16x32 bf16: lane = row + 16 * (k // 8), 8 consecutive k per lane."""
     desc, _ = desc_for("big_bf16")
