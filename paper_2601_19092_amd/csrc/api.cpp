@@ -359,7 +359,63 @@ struct GemmPlan {
   bool fp8;
   int tile;           // AXE_TILE_*
   bool ragged;        // 256x256 tile on a shape with ragged edges (M, N no multiples of 256)
+  int64_t oa, ob, oc; // element offsets of the operands inside their buffers
+  int eb, cb;         // bytes per element of A / B and of C
 };
+
+// Checks of the device pointers (they change from call to call; everything else of a plan depends on the descriptor
+// alone) and the operand addresses.
+int bind_gemm_pointers(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC, GemmPlan& P) {
+  if (!dA || !dB || !dC) {
+    set_error("axe_gemm: NULL device pointer");
+    return AXE_EINVAL;
+  }
+  if (((uintptr_t)dA | (uintptr_t)dB | (uintptr_t)dC) & 15) {
+    set_error("axe_gemm: device buffers must be 16-byte aligned");
+    return AXE_EINVAL;
+  }
+  const char* c0 = (const char*)dC;
+  const char* c1 = c0 + g->c_elems * P.cb;
+  const char* a0 = (const char*)dA;
+  const char* b0 = (const char*)dB;
+  if ((a0 < c1 && c0 < a0 + g->a_elems * P.eb) || (b0 < c1 && c0 < b0 + g->b_elems * P.eb)) {
+    set_error("axe_gemm: C overlaps an input buffer");
+    return AXE_EINVAL;
+  }
+  P.args.A = (const char*)dA + P.oa * P.eb;
+  P.args.B = (const char*)dB + P.ob * P.eb;
+  P.args.C = (char*)dC + P.oc * P.cb;
+  return AXE_OK;
+}
+
+// The contents of a descriptor as a flat run of words: what a plan depends on, device pointers aside (of the scale
+// pointers only whether they are given and their alignment matter).  False when the descriptor is malformed in a way
+// that makes its arrays unreadable: the planner then reports the error.
+constexpr int kKeyWords = 24 + 3 * (12 + 3 * (AXE_MAX_D + AXE_MAX_R) + AXE_MAX_AXES);
+struct PlanKey {
+  int64_t w[kKeyWords];
+  int n = 0;
+  void put(int64_t v) { w[n++] = v; }
+};
+bool key_of_layout(const axe_layout_t& L, PlanKey& k) {
+  if (L.n_axes < 1 || L.n_axes > AXE_MAX_AXES || L.n_d < 1 || L.n_d > AXE_MAX_D || L.n_r < 0 || L.n_r > AXE_MAX_R || !L.d ||
+      (L.n_r && !L.r))
+    return false;
+  k.put(L.n_axes), k.put(L.n_d), k.put(L.n_r);
+  for (int i = 0; i < L.n_d; ++i) k.put(L.d[i].extent), k.put(L.d[i].stride), k.put(L.d[i].axis);
+  for (int i = 0; i < L.n_r; ++i) k.put(L.r[i].extent), k.put(L.r[i].stride), k.put(L.r[i].axis);
+  for (int a = 0; a < L.n_axes; ++a) k.put(L.offset ? L.offset[a] : 0);
+  k.put(L.swz_axis), k.put(L.swz_bits), k.put(L.swz_base), k.put(L.swz_shift);
+  return true;
+}
+bool key_of_gemm(const axe_gemm_desc_t* g, PlanKey& k) {
+  k.n = 0;
+  k.put(g->M), k.put(g->N), k.put(g->K), k.put(g->in_dtype), k.put(g->out_dtype), k.put(g->mem_axis);
+  k.put(g->a_elems), k.put(g->b_elems), k.put(g->c_elems), k.put(g->scale_block), k.put(g->tile_hint), k.put(g->scale_dtype);
+  k.put(g->scale_a_rows), k.put(g->d_scale_a != nullptr), k.put(g->d_scale_b != nullptr);
+  k.put((int64_t)(((uintptr_t)g->d_scale_a | (uintptr_t)g->d_scale_b) & 3));
+  return key_of_layout(g->A, k) && key_of_layout(g->B, k) && key_of_layout(g->C, k);
+}
 
 // A 2-D operand whose canonical memory layout is "unit stride along `inner`, pitch along
 // `outer`": returns pitch and offset.  `outer_first` tells which logical dim comes first.
@@ -537,29 +593,12 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
     set_error("axe_gemm: offset of C must keep 16-byte alignment");
     return AXE_EUNSUPPORTED;
   }
-  if (need_ptrs) {
-    if (!dA || !dB || !dC) {
-      set_error("axe_gemm: NULL device pointer");
-      return AXE_EINVAL;
-    }
-    if (((uintptr_t)dA | (uintptr_t)dB | (uintptr_t)dC) & 15) {
-      set_error("axe_gemm: device buffers must be 16-byte aligned");
-      return AXE_EINVAL;
-    }
-    const char* c0 = (const char*)dC;
-    const char* c1 = c0 + g->c_elems * ob;
-    const char* a0 = (const char*)dA;
-    const char* b0 = (const char*)dB;
-    if ((a0 < c1 && c0 < a0 + g->a_elems * eb) || (b0 < c1 && c0 < b0 + g->b_elems * eb)) {
-      set_error("axe_gemm: C overlaps an input buffer");
-      return AXE_EINVAL;
-    }
-  }
   memset(&P.args, 0, sizeof P.args);
   P.fp8 = fp8;
-  P.args.A = (const char*)dA + oa * eb;
-  P.args.B = (const char*)dB + ob_ * eb;
-  P.args.C = (char*)dC + oc * ob;
+  P.oa = oa, P.ob = ob_, P.oc = oc, P.eb = eb, P.cb = ob;
+  if (need_ptrs) {
+    if (int rc = bind_gemm_pointers(g, dA, dB, dC, P)) return rc;
+  }
   P.args.M = g->M;
   P.args.N = g->N;
   P.args.K = g->K;
@@ -882,8 +921,24 @@ int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g) {
 }
 
 int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d_C, void* stream) {
+  // The plan of the last descriptor this thread launched is kept: a caller that launches the same GEMM again (same
+  // shape, types and layouts, compared word by word; other buffers are fine) skips the layout analysis -- a few
+  // microseconds, as much as a small problem's kernel takes.
+  static thread_local PlanKey last_key;
+  static thread_local GemmPlan last_plan;
+  static thread_local bool have_last = false;
   GemmPlan P;
-  if (int rc = plan_gemm(g, d_A, d_B, d_C, P, true)) return rc;
+  PlanKey key;
+  const bool keyed = g && key_of_gemm(g, key);
+  if (keyed && have_last && key.n == last_key.n && memcmp(key.w, last_key.w, sizeof(int64_t) * key.n) == 0) {
+    P = last_plan;
+    P.args.scale_a = (const float*)g->d_scale_a;
+    P.args.scale_b = (const float*)g->d_scale_b;
+    if (int rc = bind_gemm_pointers(g, d_A, d_B, d_C, P)) return rc;
+  } else {
+    if (int rc = plan_gemm(g, d_A, d_B, d_C, P, true)) return rc;
+    if (keyed) last_key = key, last_plan = P, have_last = true;
+  }
   hipError_t e;
   if (P.tile == AXE_TILE_256x256x64 || P.tile == AXE_TILE_256x224x64)
     e = !P.fp8 ? (P.ragged ? launch_gemm_bf16_256_ragged(P.args, (hipStream_t)stream) : launch_gemm_bf16_256(P.args, (hipStream_t)stream))

@@ -369,6 +369,21 @@ def test_gemm_bf16_small_tile_ragged(M, N, K, out):
     check_gemm(c, oracle_gemm(g), BF16_TOL, tile=64)
 
 
+# Short K and few whole tiles: the 64 x 64 kernel's burst variant (all K-tiles requested up front, one block of LDS per
+# K-tile).  nkt = 1, 2, 4, 7, 8 K-tiles; 1, 6, 16 and 60 tiles; bf16 and fp16, fp32 and 16-bit output; pitched A, B, C.
+# K = 576 (9 K-tiles) and 17 x 16 tiles (more tiles than compute units) take the regular variant: same answers.
+@pytest.mark.parametrize("M,N,K", [(64, 64, 64), (128, 192, 128), (256, 256, 256), (384, 640, 448), (64, 128, 512),
+                                   (128, 128, 576), (1088, 1024, 256)])
+@pytest.mark.parametrize("dtype,out", [("bf16", "f32"), ("bf16", "bf16"), ("f16", "f16")])
+def test_gemm_small_tile_short_k(M, N, K, dtype, out):
+    g = (W.gemm_bf16 if dtype == "bf16" else W.gemm_f16)(M, N, K, 30 + K, std_b=K ** -0.5, out_dtype=out)
+    tol = 1e-5 if out == "f32" else (F16_TOL if dtype == "f16" else BF16_TOL)
+    c = run_gemm(g, tile=B.AXE_TILE_64x64x32)
+    check_gemm(c, oracle_gemm(g), tol, tile=64)
+    c = run_gemm(g, tile=B.AXE_TILE_64x64x32, lda=K + 8, ldb=K + 24, ldc=N + 4)
+    check_gemm(c, oracle_gemm(g), tol, tile=64)
+
+
 def test_gemm_identity_and_pitched_operands():
     K = N = 128
     g = W.gemm_bf16(K, N, K, 50, out_dtype="f32")

@@ -245,3 +245,27 @@ def test_plan_gate_up_interleaved_weight_packing(hc, eb, blocked):
     img = pack_gate_up(b_gnk)
     img = pack_blocked(img) if blocked else img
     assert np.array_equal(got, want) and np.array_equal(got, img.reshape(-1))
+
+
+def test_gemm_plan_is_reused_only_for_an_identical_descriptor(hc):
+    """axe_gemm keeps the plan of the last descriptor a thread launched.  A descriptor that differs in any word must be
+    planned afresh: after a successful plan, the same descriptor with a changed stride, shape or dtype has to be judged
+    on its own (the host-check library's GEMM launch stand-ins return 'not supported', so a plan that passes ends
+    in AXE_EHIP and nothing is launched)."""
+    hc.axe_gemm.argtypes = [C.POINTER(B.axe_gemm_desc_t), C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+    M = N = K = 256
+    def desc(lda=None, K_=K, dt=B.AXE_BF16):
+        lda = lda or K_
+        return B.GemmDesc(M, N, K_, dt, B.AXE_F32, B.Layout(W.spec([(M, lda, "m"), (K_, 1, "m")])), B.Layout(W.col_major_spec(K_, N)),
+                          B.Layout(W.row_major_spec(M, N)), M * lda, N * K_, M * N)
+    def call(d, pa=0x10000, pb=0x200000, pc=0x400000):
+        return hc.axe_gemm(C.byref(d.c), pa, pb, pc, None)
+    good = desc()
+    assert call(good) == B.AXE_EHIP and call(good) == B.AXE_EHIP            # planned, then reused
+    assert call(desc(lda=K + 3)) == B.AXE_EUNSUPPORTED                      # pitch no multiple of 16 bytes: not the cached plan
+    assert call(good) == B.AXE_EHIP
+    assert call(desc(K_=K + 4)) == B.AXE_EUNSUPPORTED
+    assert call(desc(dt=99)) == B.AXE_EINVAL
+    assert call(good, pa=0x10001) == B.AXE_EINVAL                           # pointer checks run on a reused plan as well
+    assert call(good, pc=0x10000) == B.AXE_EINVAL                           # C overlaps A
+    assert call(good) == B.AXE_EHIP
