@@ -165,10 +165,22 @@ class Layout:
         return self.axes.index(name)
 
 
+_raw_stream = None
+
+
 def _stream_ptr(stream=None) -> int:
+    """The hipStream_t to launch on: the given torch stream (or raw handle), else torch's current stream of the current
+    device.  (torch.cuda.current_stream() builds a Python object per call, 2.5 us -- as much as a small launch; the raw
+    getter it is built on is used when the installed torch has it.)"""
+    global _raw_stream
+    if stream is not None:
+        return stream if isinstance(stream, int) else int(stream.cuda_stream)
     import torch
-    s = stream if stream is not None else torch.cuda.current_stream()
-    return int(s.cuda_stream)
+    if _raw_stream is None:
+        _raw_stream = getattr(torch._C, "_cuda_getCurrentRawStream", False)
+    if _raw_stream:
+        return int(_raw_stream(torch.cuda.current_device()))
+    return int(torch.cuda.current_stream().cuda_stream)
 
 
 def _shape_arr(shape: Sequence[int]):
