@@ -630,10 +630,10 @@ int plan_gemm(const axe_gemm_desc_t* g, const void* dA, const void* dB, void* dC
   int tile = g->tile_hint;
   if (row_scaled) {
     // one scale per row of A: the 64 x 64 kernel folds it per lane (fp32 or E8M0); the 256 x 256 kernel on the matrix
-    // cores' scale path takes E8M0 row codes a window of 8 K-tiles at a time (K a multiple of 1024)
-    const bool rows_big = big_ok && P.args.scale_e8m0 && g->K % 1024 == 0;
+    // cores' scale path takes E8M0 row codes a window of 8 K-tiles at a time
+    const bool rows_big = big_ok && P.args.scale_e8m0 && g->M * (int64_t)P.args.nkb < (int64_t(1) << 30);
     if (tile == AXE_TILE_256x256x64 && !rows_big) {
-      set_error("axe_gemm: one scale per row of A on the 256x256 tile needs E8M0 scales, K a multiple of 1024 and M, N multiples of 256");
+      set_error("axe_gemm: one scale per row of A on the 256x256 tile needs E8M0 scales, K a multiple of 128 and M, N multiples of 256");
       return AXE_EUNSUPPORTED;
     }
     if (tile != AXE_TILE_AUTO && tile != AXE_TILE_64x64x32 && tile != AXE_TILE_256x256x64) {
@@ -833,8 +833,16 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     return AXE_EINVAL;
   }
   const bool tiles_forced = g->kernel_hint == AXE_GROUPED_TILES || g->kernel_hint == AXE_GROUPED_TILES_256 || g->kernel_hint == AXE_GROUPED_TILES_128;
-  if (fp8 && (tiles_forced || g->K % 128 || opb.kt_stride || opb.rb)) {
-    set_error("%s: fp8 inputs are served by the streaming kernel only, with K a multiple of 128 and each B[e] column-major", fn);
+  if (fp8 && (g->K % 128 || opb.kt_stride || opb.rb)) {
+    set_error("%s: fp8 inputs need K a multiple of 128 and each B[e] column-major (not blocked)", fn);
+    return AXE_EUNSUPPORTED;
+  }
+  // fp8 on the tile kernel (the matrix cores' scale path, tiles of 256 rows): E8M0 scales or none; with the gated
+  // epilogue the gate and the up half must each be whole 128-wide scale blocks; the row codes are addressed in 32 bits
+  const bool fp8_tiles_ok = fp8 && (!g->d_scale_a || (g->scale_dtype == AXE_SCALE_E8M0 && (!gated || (g->N / 2) % 128 == 0) &&
+                                                       g->M * ((g->K + 127) / 128) >= 8 && g->M * ((g->K + 127) / 128) < (int64_t(1) << 30)));
+  if (fp8 && tiles_forced && (!fp8_tiles_ok || g->kernel_hint == AXE_GROUPED_TILES_128)) {
+    set_error("%s: the fp8 tile kernel has tiles of 256 rows and takes E8M0 scales or none (gated: N / 2 a multiple of 128)", fn);
     return AXE_EUNSUPPORTED;
   }
   if (g->G > 4096 || g->N % 256 || g->N / 256 > 2048 || g->K % 64 || g->M >= (int64_t(1) << 31) ||
@@ -892,7 +900,22 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
   a.groups = g->G;
   a.gated = gated;
   a.tile_m = g->kernel_hint == AXE_GROUPED_TILES_256 ? 256 : (g->kernel_hint == AXE_GROUPED_TILES_128 ? 128 : 0);
+  if (fp8) a.tile_m = fp8_tiles_ok ? 256 : -1;                     // -1: only the streaming kernel serves this problem
   return AXE_OK;
+}
+
+// Which kernel a planned grouped problem goes to.  16-bit inputs: the streaming kernel up to 8 rows per group on
+// average.  fp8: the streaming kernel takes a group 64 rows at a time and re-reads the group's weights for every
+// further pass, so from an average of 96 rows per group on the tile kernel (256-row tiles on the scale path) takes over.
+bool grouped_goes_to_stream(const axe_gemm_grouped_desc_t* g, const GemmArgs& a) {
+  if (g->kernel_hint == AXE_GROUPED_STREAM) return true;
+  if (a.fp8) {
+    if (a.tile_m < 0) return true;
+    if (g->kernel_hint != AXE_GROUPED_AUTO) return false;          // tiles asked for
+    static const int64_t min_rows = [] { const char* v = getenv("AXE_GROUPED_FP8_TILE_ROWS"); return v ? atoll(v) : int64_t(96); }();
+    return g->M < min_rows * (int64_t)g->G;
+  }
+  return g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G;
 }
 
 }  // namespace
@@ -901,8 +924,9 @@ int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const vo
                      const int32_t* d_group_rows, void* stream) {
   GemmArgs a;
   if (int rc = plan_gemm_grouped(g, d_A, d_B, d_C, d_group_rows, a, true)) return rc;
-  const bool stream_kernel = g->kernel_hint == AXE_GROUPED_STREAM || a.fp8 || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G);
-  hipError_t e = stream_kernel ? launch_gemm_grouped_stream(a, (hipStream_t)stream) : launch_gemm_bf16_256_grouped(a, (hipStream_t)stream);
+  hipError_t e = grouped_goes_to_stream(g, a) ? launch_gemm_grouped_stream(a, (hipStream_t)stream)
+                 : a.fp8                      ? launch_gemm_fp8_e8m0_256_grouped(a, (hipStream_t)stream)
+                                              : launch_gemm_bf16_256_grouped(a, (hipStream_t)stream);
   return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm_grouped");
 }
 
@@ -910,8 +934,8 @@ int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const vo
 int axe_gemm_grouped_kernel(const axe_gemm_grouped_desc_t* g) {
   GemmArgs a;
   if (int rc = plan_gemm_grouped(g, nullptr, nullptr, nullptr, nullptr, a, false)) return rc;
-  if (g->kernel_hint == AXE_GROUPED_STREAM || a.fp8 || (g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G))
-    return AXE_GROUPED_STREAM;
+  if (grouped_goes_to_stream(g, a)) return AXE_GROUPED_STREAM;
+  if (a.fp8) return AXE_GROUPED_TILES_256;
   return grouped_tile_rows(a.M, a.groups, a.tile_m) == 128 ? AXE_GROUPED_TILES_128 : AXE_GROUPED_TILES_256;
 }
 

@@ -174,6 +174,7 @@ hipError_t launch_gemm_bf16_256_ragged(const GemmArgs&, hipStream_t) { return hi
 hipError_t launch_gemm_grouped_stream(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_gemm_fp8_256(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_gemm_fp8_e8m0_256(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
+hipError_t launch_gemm_fp8_e8m0_256_grouped(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
 
 }  // namespace axe
 

@@ -344,7 +344,8 @@ extern "C" int axe_gemm_grouped_describe(const axe_gemm_grouped_desc_t* g, int32
                    "is not a layout of the accumulators and is not reported");
     return AXE_EUNSUPPORTED;
   }
-  Geo geo = geometry(true, false, false, 256, false);
+  // fp8 groups on the tile kernel: the 4-wave kernel of the matrix cores' scale path
+  Geo geo = g->in_dtype == AXE_FP8_E4M3 ? geometry(true, true, true, 256, false) : geometry(true, false, false, 256, false);
   if (kernel == AXE_GROUPED_TILES_128) geo.T = 128;               // the A blocks in LDS keep their places: b_off stays
   L2 b;
   if (int rc = build(geo, which, 1, 1, true, b)) return rc;

@@ -39,6 +39,7 @@ hipError_t launch_gemm_grouped_stream(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_fp8_256(const GemmArgs& g, hipStream_t s);
 // fp8 with E8M0 block scales (or none) on the matrix cores' scale path; same shape requirements
 hipError_t launch_gemm_fp8_e8m0_256(const GemmArgs& g, hipStream_t s);
+hipError_t launch_gemm_fp8_e8m0_256_grouped(const GemmArgs& g, hipStream_t s);
 
 // Compute units of the current device (host side; asked once per process).
 inline int cu_count() {

@@ -29,10 +29,12 @@
 //                 fetched) and hands the MFMAs of a K-step one byte of each.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <type_traits>
 
 #include "device_types.h"
 #include "gemm_common.h"
+#include "grouped_tiles.h"
 #include "kernels.h"
 #include "tile_maps.h"
 
@@ -61,10 +63,19 @@ __device__ __forceinline__ void mfma_scaled(f32x4& acc, i32x8 first, i32x8 secon
 }
 }  // namespace
 
-// ROWS: one E8M0 code per row of A and k block (scale_a is (M, K / 128), K a multiple of 1024) instead of one per
-// 128 x 128 block; B's codes are per 128 x 128 block either way.
-template <bool ROWS>
+// ROWS: one E8M0 code per row of A and k block (scale_a is (M, K / 128)) instead of one per 128 x 128 block; B's
+// codes are per 128 x 128 block either way.
+// GROUPED: the grouped GEMM of an MoE layer in fp8 (rows of A and C sorted by group, group e multiplies its rows with
+// its own B; offsets on the device): the tile table, the clipped buffer descriptors and the chained walk of the
+// 16-bit grouped kernel (kernels_gemm_bf16.hip), tiles of 256 rows, A scaled per row (ROWS), each group's B per
+// 128 x 128 block, or no scales at all.
+// GATED: B holds each group's gate and up rows interleaved in runs of 16, so that the wave's fragment pair (j, j + 1) is
+// (gate, up) of the same 16 outputs; the tile stores silu(gate) * up, half as wide.  The gate and the up columns of a
+// wave lie in different 128-wide blocks of the logical matrix: two B codes per K-step.
+template <bool ROWS, bool GROUPED = false, bool GATED = false>
 __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
+  static_assert(!GROUPED || ROWS, "the grouped kernel scales A per row");
+  static_assert(!GATED || GROUPED, "the gated epilogue exists for the grouped kernel");
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
   const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
 
@@ -77,16 +88,45 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   const int nk_rot = nk & ~(kRot - 1);                             // K-tiles beyond the last full rotation window keep their order
   const bool scaled = g.scale_a != nullptr;
 
-  // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ... (cur and nxt, see the bf16 kernel)
+  // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ... (cur and nxt, see the bf16 kernel);
+  //      grouped: lane t of a wave holds the workgroup's t-th tile (grouped_tiles.h)
   const int a_pitch = (int)g.lda, b_pitch = (int)g.ldb;            // bytes
   struct Tile {
     __amdgpu_buffer_rsrc_t ra, rb;
-    const uint8_t *sa, *sb;                                        // E8M0 codes of this wave's row block and column block, one per K-tile
+    const uint8_t *sa, *sb, *sb2;                                  // E8M0 codes of this wave's row block (not ROWS) and column block(s), one per K-tile
+    int sa_row;                                                    // ROWS: the lane's row of fragment row 0 (fragment row i: 16 i further)
     int rot;
   };
+  int tb_row0 = 0, tb_desc = 0;
+  if constexpr (GROUPED) group_tiles<kTile, false>(g, lane, tb_row0, tb_desc);
+  auto table_rows = [&](int t) __attribute__((always_inline)) -> int { return t < 64 ? desc_rows(__builtin_amdgcn_readlane(tb_desc, t)) : 0; };
   auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
     Tile t;
-    if (v < ntiles) {
+    t.sa = (const uint8_t*)g.scale_a, t.sb = t.sb2 = (const uint8_t*)g.scale_b;   // (valid addresses where the codes are never used)
+    t.sa_row = 0;
+    if constexpr (GROUPED) {
+      const int rows = table_rows(v);
+      if (rows > 0) {
+        const int row0 = __builtin_amdgcn_readlane(tb_row0, v), dsc = __builtin_amdgcn_readlane(tb_desc, v);
+        const int grp = desc_group(dsc), tn = desc_tn(dsc);
+        t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)row0 * g.lda), 0, (rows - 1) * a_pitch + (int)g.K, 0x00020000);
+        t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)grp * g.ldg + (int64_t)tn * kTile * g.ldb), 0,
+                                                 255 * b_pitch + (int)g.K, 0x00020000);
+        t.rot = ((row0 >> 8) + tn) & (kRot - 1);
+        t.sa_row = row0 + wm * 128 + (lane & 15);
+        const int64_t nb = g.N / 128;                              // 128-wide blocks of a group's logical columns
+        if constexpr (GATED) {
+          // memory rows 256 tn + 128 wn + 16 j + i of the group's image: j even = gate, j odd = up, of the logical columns
+          // 128 tn + 64 wn + 16 (j / 2) + i (+ N / 2 for up): block tn of the gate half, block N / 256 + tn of the up half
+          t.sb = (const uint8_t*)g.scale_b + ((int64_t)grp * nb + tn) * g.nkb;
+          t.sb2 = (const uint8_t*)g.scale_b + ((int64_t)grp * nb + nb / 2 + tn) * g.nkb;
+        } else {
+          t.sb = t.sb2 = (const uint8_t*)g.scale_b + ((int64_t)grp * nb + 2 * tn + wn) * g.nkb;
+        }
+        return t;
+      }
+    }
+    if (!GROUPED && v < ntiles) {
       int tm, tn;
       tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * kTile * g.ldb), 0,
@@ -94,19 +134,20 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
       t.rot = (tm + tn) & (kRot - 1);                              // K rotation
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda), 0,
                                                255 * a_pitch + (int)g.K, 0x00020000);
-      if constexpr (ROWS) t.sa = (const uint8_t*)g.scale_a + ((int64_t)tm * kTile + wm * 128 + (lane & 15)) * g.nkb;   // the lane's row of fragment row 0
+      if constexpr (ROWS) t.sa_row = tm * kTile + wm * 128 + (lane & 15);
       else t.sa = (const uint8_t*)g.scale_a + (int64_t)(2 * tm + wm) * g.nkb;
-      t.sb = (const uint8_t*)g.scale_b + (int64_t)(2 * tn + wn) * g.nkb;
+      t.sb = t.sb2 = (const uint8_t*)g.scale_b + (int64_t)(2 * tn + wn) * g.nkb;
     } else {                                                       // no such tile: every load returns zero
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
-      t.sa = (const uint8_t*)g.scale_a, t.sb = (const uint8_t*)g.scale_b;   // valid addresses; the codes are never used
       t.rot = 0;
     }
     return t;
   };
-  int v = blockIdx.x;
-  Tile cur = describe(v), nxt = describe(v + (int)gridDim.x);
+  int v = GROUPED ? 0 : (int)blockIdx.x;
+  const int vstep = GROUPED ? 1 : (int)gridDim.x;
+  if (GROUPED && table_rows(0) <= 0) return;                       // more workgroups than tiles (the host sizes the launch for the worst case)
+  Tile cur = describe(v), nxt = describe(v + vstep);
   // K-step T of the current tile (T >= nk: step T - nk of the next one) -> K-tile index
   auto ktile = [&](int T, int rot) -> int { return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T; };
 
@@ -117,33 +158,63 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   //      taken over when it ends.  These are ordinary loads: the compiler waits for them before the first
   //      use, once per 64 K-steps or per tile.
   uint32_t cva = 127u, cvb = 127u, nva = 127u, nvb = 127u;        // this block's and the next block's codes, lane = step % 64
-  auto fetch_codes = [&](const Tile& t, int base, uint32_t& oa, uint32_t& ob) __attribute__((always_inline)) {
+  uint32_t cvb2 = 127u, nvb2 = 127u;                               // GATED: the codes of the up half
+  auto fetch_codes = [&](const Tile& t, int base, uint32_t& oa, uint32_t& ob, uint32_t& ob2) __attribute__((always_inline)) {
     if (!scaled) return;
     const int T = base + lane;
     const int kt_ = ktile(T < nk ? T : nk - 1, t.rot);
     if constexpr (!ROWS) oa = t.sa[kt_];
     ob = t.sb[kt_];
+    if constexpr (GATED) ob2 = t.sb2[kt_];
   };
-  // Row scales.  The walk visits the K-tiles of an aligned window of 8 in the order (t + rot) % 8, t = 0..7; the 8
-  // codes of a row for that window are 8 contiguous, 8-byte aligned bytes.  na: the window being fetched, as loaded;
-  // ca: the current window, rotated by the tile's rot so that step t of the window uses byte t, and moved down by
-  // one byte per step.
+  // Row scales.  The walk visits the K-tiles of a full aligned window of 8 in the order (t + rot) % 8, t = 0..7, and
+  // those of the last, partial window (K / 128 no multiple of 8) in their own order.  The codes of a row for a window
+  // are 8 contiguous bytes of the row-major (M, K / 128) array (of a partial window fewer: the load then runs on into
+  // the next row, or, at the very end of the array, starts earlier and is shifted down).  na: the window being
+  // fetched, as loaded; ca: the current window, rotated by the tile's rot so that step t of the window uses byte t,
+  // and moved down by one byte per step.  Without scales all codes are 127 (2^0).
   uint32_t ca[8][2], na[8][2];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) ca[i][0] = ca[i][1] = na[i][0] = na[i][1] = 0x7f7f7f7fu;
   bool more = false;                                               // the workgroup has another tile after the current one
+  // where the 8 bytes of (row of fragment row i, window win) are read from, and by how many bytes that read starts
+  // early (only at the very end of the array).  32-bit arithmetic: the host admits code arrays below 2^31 bytes.
+  const int codes_total = (int)(g.M * (int64_t)g.nkb);             // bytes of the code array (at least 8)
+  const int codes_last_row = codes_total - g.nkb;
+  auto row_codes_at = [&](int sa_row, int i, int win, int& at, int& over) __attribute__((always_inline)) {
+    int off = (sa_row + 16 * i) * g.nkb;
+    off = off < codes_last_row ? off : codes_last_row;             // rows past the end belong to no group: their codes are never used
+    off += 8 * win;
+    at = off < codes_total - 8 ? off : codes_total - 8;
+    over = off - at;
+  };
   auto fetch_rows = [&](const Tile& t, int win) __attribute__((always_inline)) {
-    typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+    if (!scaled) return;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const u32x2 c = *(const u32x2*)(t.sa + (int64_t)i * 16 * g.nkb + win * 8);
-      na[i][0] = c[0], na[i][1] = c[1];
+      int at, over;
+      row_codes_at(t.sa_row, i, win, at, over);
+      uint64_t c;
+      __builtin_memcpy(&c, (const uint8_t*)g.scale_a + at, 8);
+      na[i][0] = (uint32_t)c, na[i][1] = (uint32_t)(c >> 32);      // (used 8 K-steps later: nothing here may wait for the load)
     }
   };
-  auto take_rows = [&](int rot) __attribute__((always_inline)) {
+  // na -> ca at the first step of window win of the current tile: shifted down if the read started early, rotated by rot
+  auto take_rows = [&](int rot, int win) __attribute__((always_inline)) {
+    if (!scaled) {                                                 // a fresh window of codes 127 (the steps shift them out)
+#pragma unroll
+      for (int i = 0; i < 8; ++i) ca[i][0] = ca[i][1] = 0x7f7f7f7fu;
+      return;
+    }
     const bool swap = (rot & 4) != 0;
     const uint32_t sh = (uint32_t)(rot & 3) * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      const uint32_t lo = swap ? na[i][1] : na[i][0], hi = swap ? na[i][0] : na[i][1];
+      int at, over;
+      row_codes_at(cur.sa_row, i, win, at, over);
+      const uint64_t c = (((uint64_t)na[i][1] << 32) | na[i][0]) >> (8 * over);
+      const uint32_t c0 = (uint32_t)c, c1 = (uint32_t)(c >> 32);
+      const uint32_t lo = swap ? c1 : c0, hi = swap ? c0 : c1;
       ca[i][0] = __builtin_amdgcn_alignbit(hi, lo, sh);            // 64-bit rotation to the right by 8 rot bits
       ca[i][1] = __builtin_amdgcn_alignbit(lo, hi, sh);
     }
@@ -206,6 +277,17 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   int c_rowblk;
   const int c_voff2 = (int)((fr * g.ldc + maps::pair_store_col(fq)) * 2);
   auto set_output = [&](int vv) __attribute__((always_inline)) {
+    if constexpr (GROUPED) {
+      const int row0 = __builtin_amdgcn_readlane(tb_row0, vv), dsc = __builtin_amdgcn_readlane(tb_desc, vv);
+      const int tn = desc_tn(dsc);
+      int rows = desc_rows(dsc) - wm * 128;                          // rows of the tile that fall to this wave
+      rows = rows < 0 ? 0 : (rows > 128 ? 128 : rows);
+      constexpr int CW = GATED ? 64 : 128;                           // columns of C this wave writes
+      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * 128) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
+                    rows ? (uint32_t)(((rows - 1) * g.ldc + CW) * 2) : 0u);   // the stores of rows the group does not have are dropped
+      c_rowblk = (int)(16 * g.ldc * 2);
+      return;
+    }
     int tm, tn;
     tile_of_block(vv, ntiles, g.grid_m, g.grid_n, tm, tn);
     rc = raw_rsrc((uint16_t*)g.C + ((int64_t)tm * kTile + wm * 128) * g.ldc + (int64_t)tn * kTile + wn * 128,
@@ -225,6 +307,29 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
   };
 
+  // Gated epilogue (see the 16-bit grouped kernel): h = silu(gate) * up for the fragment pairs (j, j + 1) and
+  // (j + 2, j + 3), stored like a fragment pair (32 output columns, 64 contiguous bytes per row).
+  auto store_gated_quad = [&](int i, int j) __attribute__((always_inline)) {
+    float h[2][4];
+#pragma unroll
+    for (int q = 0; q < 2; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        const float gate = acc[i][j + 2 * q][e], up = acc[i][j + 2 * q + 1][e];
+        h[q][e] = gate * __builtin_amdgcn_rcpf(1.0f + __expf(-gate)) * up;
+      }
+    const auto lo = __builtin_amdgcn_permlane16_swap(pack_bf16(h[0][0], h[0][1]), pack_bf16(h[1][0], h[1][1]), false, false);
+    const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16(h[0][2], h[0][3]), pack_bf16(h[1][2], h[1][3]), false, false);
+    const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
+    const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 16);
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    AXE_PARANOID_WAIT();
+#pragma unroll
+    for (int q = 0; q < 4; ++q)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) acc[i][j + q][e] = 0.f;
+  };
+
   using I0 = std::integral_constant<int, 0>;
   using I1 = std::integral_constant<int, 1>;
 
@@ -235,7 +340,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   // step kt + 3 (after MFMAs 18, 22, 26, 30).  The second half also reads the 16 fragments of step kt+1, each right after the
   // last MFMA that uses the register it goes to: A fragments 0..3 during rows 4, 5; A fragments 4, 5
   // and, after MFMA (7, j), B fragment j during rows 6, 7; A fragments 6, 7 at the end.
-  auto half = [&](auto par_c, auto h_c, auto cross_c, int kt, const uint32_t (&va)[8], uint32_t vb, bool pref) __attribute__((always_inline)) {
+  auto half = [&](auto par_c, auto h_c, auto cross_c, int kt, const uint32_t (&va)[8], uint32_t vb, uint32_t vb2, bool pref) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value, H = decltype(h_c)::value;
     constexpr bool CROSS = decltype(cross_c)::value != 0;
     const int bT = H == 0 ? kt + 2 : kt + 3;
@@ -245,7 +350,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
 #pragma unroll
     for (int q = 0; q < 32; ++q) {
       const int i = 4 * H + 2 * (q >> 4) + (q & 1), j = (q >> 1) & 7;
-      mfma_scaled(acc[i][j], fb[j], fa[i], vb, va[ROWS ? i : 0]);
+      mfma_scaled(acc[i][j], fb[j], fa[i], (GATED && (j & 1)) ? vb2 : vb, va[ROWS ? i : 0]);
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (ROWS && H == 1) {
         // the row codes of the next window of the walk (of this tile, or the first of the next tile), once per 8
@@ -283,7 +388,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     }
   };
   auto step = [&](auto par_c, auto cross_c, int kt, bool pref = false) __attribute__((always_inline)) {
-    uint32_t va[8], vb = lane_value(cvb, kt & 63);
+    uint32_t va[8], vb = lane_value(cvb, kt & 63), vb2 = GATED ? lane_value(cvb2, kt & 63) : 0u;
     // the codes are now in VGPRs, written by the vector ALU; the MFMA is an asm statement, so the compiler's
     // hazard recogniser cannot pad between that write and the matrix core's read of its scale operands
     if constexpr (ROWS) {
@@ -295,13 +400,16 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
         ca[i][0] = __builtin_amdgcn_alignbit(ca[i][1], ca[i][0], 8);
         ca[i][1] >>= 8;
       }
-      asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4]), "+v"(va[5]), "+v"(va[6]), "+v"(va[7]), "+v"(vb));
+      if constexpr (GATED)
+        asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4]), "+v"(va[5]), "+v"(va[6]), "+v"(va[7]), "+v"(vb), "+v"(vb2));
+      else
+        asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4]), "+v"(va[5]), "+v"(va[6]), "+v"(va[7]), "+v"(vb));
     } else {
       va[0] = lane_value(cva, kt & 63);
       asm volatile("s_nop 3" : "+v"(va[0]), "+v"(vb));
     }
-    half(par_c, I0{}, cross_c, kt, va, vb, pref);
-    half(par_c, I1{}, cross_c, kt, va, vb, pref);
+    half(par_c, I0{}, cross_c, kt, va, vb, vb2, pref);
+    half(par_c, I1{}, cross_c, kt, va, vb, vb2, pref);
     const int t = bo0;
     bo0 = bo1, bo1 = bo2, bo2 = t;
   };
@@ -310,7 +418,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   auto window = [&](int kt) __attribute__((always_inline)) -> bool {
     if constexpr (ROWS) {
       if ((kt & 7) == 0) {
-        take_rows(cur.rot);
+        take_rows(kt < nk_rot ? cur.rot : 0, kt >> 3);             // the partial last window keeps its order
         return true;
       }
     }
@@ -324,7 +432,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   for (int i = 0; i < 8; ++i) a_dload(0, i, true);
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
-  fetch_codes(cur, 0, cva, cvb);
+  fetch_codes(cur, 0, cva, cvb, cvb2);
   if constexpr (ROWS) fetch_rows(cur, 0);
 #pragma unroll
   for (int i = 0; i < 8; ++i) a_dload(1, i, true);                 // (a single K-step per tile: step 1 is the next tile's step 0)
@@ -342,13 +450,13 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   // ---- all K-steps of all tiles of this workgroup, one uninterrupted pipeline (nk even and >= 4 when chained)
   for (;;) {
     set_output(v);
-    more = v + (int)gridDim.x < ntiles;
+    more = GROUPED ? table_rows(v + 1) > 0 : v + vstep < ntiles;
     int kt = 0;
     for (int base = 0; base < nk; base += 64) {
       const int end = nk < base + 64 ? nk : base + 64;
       // the next 64 steps of the walk: of this tile, or the first of the next tile
-      if (end < nk) fetch_codes(cur, end, nva, nvb);
-      else if (more) fetch_codes(nxt, 0, nva, nvb);
+      if (end < nk) fetch_codes(cur, end, nva, nvb, nvb2);
+      else if (more) fetch_codes(nxt, 0, nva, nvb, nvb2);
       for (; kt + 1 < end && kt + 5 < nk; kt += 2) {               // every load of these steps is of this tile (at most step kt + 5)
         step(I0{}, I0{}, kt, window(kt));
         step(I1{}, I0{}, kt + 1);
@@ -358,27 +466,35 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
         step(I1{}, I1{}, kt + 1);
       }
       if (kt < end) {                                              // odd nk: only with one tile per workgroup
-        step(I0{}, I1{}, kt);
+        step(I0{}, I1{}, kt, window(kt));
         ++kt;
       }
-      if (end < nk) cva = nva, cvb = nvb;
+      if (end < nk) cva = nva, cvb = nvb, cvb2 = nvb2;
     }
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");             // the last MFMAs retire before their results are read
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
+    for (int i = 0; i < 8; ++i) {
+      if constexpr (GATED) {
 #pragma unroll
-      for (int j = 0; j < 8; j += 2) store_fragment_pair(i, j);
-    v += (int)gridDim.x;
-    if (v >= ntiles) break;
-    cva = nva, cvb = nvb;
+        for (int j = 0; j < 8; j += 4) store_gated_quad(i, j);
+      } else {
+#pragma unroll
+        for (int j = 0; j < 8; j += 2) store_fragment_pair(i, j);
+      }
+    }
+    v += vstep;
+    if (GROUPED ? table_rows(v) <= 0 : v >= ntiles) break;
+    cva = nva, cvb = nvb, cvb2 = nvb2;
     cur = nxt;
-    nxt = describe(v + (int)gridDim.x);
+    nxt = describe(v + vstep);
   }
 }
 
 __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<false>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_rows_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_grouped_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true, true>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_grouped_gated_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true, true, true>(g); }
 
 hipError_t launch_gemm_fp8_e8m0_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -387,10 +503,26 @@ hipError_t launch_gemm_fp8_e8m0_256(const GemmArgs& g, hipStream_t s) {
   const bool chain = (nk % 2 == 0) && nk >= 4 && ntiles > cus && (cus % 8 == 0);
   unsigned nwg = (unsigned)(chain ? cus : ntiles);
   if (g.scale_a && g.scale_a_rows == 1) {
-    if (!g.scale_e8m0 || g.K % 1024) return hipErrorInvalidValue;  // a window of 8 codes per row: whole windows only
+    if (!g.scale_e8m0 || g.M * (int64_t)g.nkb < 8 || g.M * (int64_t)g.nkb >= (int64_t(1) << 30)) return hipErrorInvalidValue;   // (a row's codes are fetched 8 bytes at a time, 32-bit offsets)
     hipLaunchKernelGGL(gemm_fp8_e8m0_256_rows_kernel, dim3(nwg), dim3(256), 0, s, g);
   } else
     hipLaunchKernelGGL(gemm_fp8_e8m0_256_kernel, dim3(nwg), dim3(256), 0, s, g);
+  return hipGetLastError();
+}
+
+// Grouped (see launch_gemm_bf16_256_grouped): the host knows only that sum_e ceil(rows_e / 256) <= M / 256 + groups.
+hipError_t launch_gemm_fp8_e8m0_256_grouped(const GemmArgs& g, hipStream_t s) {
+  if (g.scale_a && (!g.scale_e8m0 || g.M * (int64_t)g.nkb < 8 || g.M * (int64_t)g.nkb >= (int64_t(1) << 30))) return hipErrorInvalidValue;
+  const int64_t worst = (g.M / kTile + g.groups) * (int64_t)g.grid_n;
+  const int nk = (int)(g.K / 128);
+  const int cus = cu_count();
+  const bool chain = (nk % 2 == 0) && nk >= 4;
+  int64_t nwg = chain ? std::max<int64_t>(cus, (worst + 63) / 64) : worst;
+  if (chain && nwg > cus) nwg = (nwg + cus - 1) / cus * cus;      // more workgroups than compute units only in whole rounds
+  nwg = (nwg + 7) / 8 * 8;                                         // the tile sequence is cut into 8 parts, one per XCD
+  if (nwg > 0x7fffffff) return hipErrorInvalidValue;
+  if (g.gated) hipLaunchKernelGGL(gemm_fp8_e8m0_256_grouped_gated_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  else hipLaunchKernelGGL(gemm_fp8_e8m0_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
   return hipGetLastError();
 }
 

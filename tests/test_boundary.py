@@ -200,7 +200,8 @@ def test_gemm_row_scaled_activations_kernel_choice():
                           B.Layout(W.row_major_spec(M, 2048)), M * K, 2048 * K, M * 2048, FakeTensor(), FakeTensor(), tile_hint=tile,
                           scale_a_rows=1, scale_dtype=B.AXE_SCALE_E8M0)
     assert _tile_rc(desc_e8(2048)) == BIG and _tile_rc(desc_e8(1024, tile=BIG)) == BIG
-    assert _tile_rc(desc_e8(1536)) == B.AXE_TILE_64x64x32 and _tile_rc(desc_e8(1536, tile=BIG)) == B.AXE_EUNSUPPORTED
+    assert _tile_rc(desc_e8(1536)) == BIG and _tile_rc(desc_e8(768, tile=BIG)) == BIG     # any K that is a multiple of 128
+    assert _tile_rc(desc_e8(1088)) == B.AXE_TILE_64x64x32 and _tile_rc(desc_e8(1088, tile=BIG)) == B.AXE_EUNSUPPORTED
     assert _tile_rc(desc_e8(2048, M=2000)) == B.AXE_TILE_64x64x32
     assert _tile_rc(desc_e8(2048, tile=B.AXE_TILE_256x224x64)) == B.AXE_EUNSUPPORTED
 

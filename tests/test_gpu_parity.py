@@ -1163,7 +1163,10 @@ def test_gemm_fp8_row_scaled_activations(M, N, K, scale_dtype):
 # window of 8 K-tiles), 2, 3 (odd), 9 (more than 64 K-steps: B's code registers are refilled as well); one tile, several
 # tiles with different K rotations, and 17 x 16 tiles (chained: the next tile's first window is fetched across the tile
 # boundary).  The row codes differ from row to row and from k block to k block over a range of 2^11.
-@pytest.mark.parametrize("M,N,K", [(256, 256, 1024), (512, 768, 2048), (768, 512, 3072), (256, 512, 9216), (4352, 4096, 2048)])
+# K = 128, 768 and 1152: 1, 6 and 9 K-tiles -- a partial window of row codes only (its 8-byte reads run on into the next
+# row and, for the last rows, start early at the end of the array), and a full window followed by a partial one.
+@pytest.mark.parametrize("M,N,K", [(256, 256, 1024), (512, 768, 2048), (768, 512, 3072), (256, 512, 9216), (4352, 4096, 2048),
+                                   (256, 256, 128), (512, 256, 768), (256, 512, 1152)])
 def test_gemm_fp8_row_scaled_activations_large_tile(M, N, K):
     g = W.gemm_fp8(M, N, K, 107, scaled="e8m0")
     rng = np.random.default_rng(M + K)
@@ -1273,6 +1276,63 @@ def test_gemm_grouped_fp8_block_scaled(sizes, hint, gated, scale_dtype):
             for j in range(0, NC, 64):
                 blk = (slice(off[e], off[e + 1]), slice(j, j + 64))
                 assert R.rel_frobenius(c[blk], ref[blk]) <= FP8_TOL, (e, j)
+
+
+# fp8 on the grouped TILE kernel (the matrix cores' scale path, tiles of 256 rows): E8M0 scales (per row of A, per
+# 128 x 128 block of each group's B) or none; plain and gated epilogue.  K = 768 (6 K-tiles: no full rotation window,
+# the row codes of a window end before 8 bytes are up -- also at the very end of the code array), 1152 (9: a full window
+# and a partial one; odd, so one tile per workgroup), 2048 (16: two windows, chained tiles); groups from 1 to 700
+# rows, empty groups, rows outside every group.
+@pytest.mark.parametrize("scale_dtype", ["e8m0", None])
+@pytest.mark.parametrize("gated", [False, True])
+@pytest.mark.parametrize("sizes,N,K", [([300, 0, 33, 256, 257, 1], 512, 768), ([70, 700, 5], 768, 1152), ([130, 512, 64, 0, 300, 2], 512, 2048)])
+def test_gemm_grouped_fp8_tile_kernel(sizes, N, K, gated, scale_dtype):
+    off = np.concatenate([[0], np.cumsum(sizes)])
+    for M in (int(off[-1]) + 3, int(off[-1])):             # with and without rows behind the last group (the last row's codes end the array)
+        g = W.gemm_grouped_fp8(off, N, K, 108 + K, M=M, scale_dtype=scale_dtype or "e8m0")
+        if scale_dtype:
+            g.scale_a = np.random.default_rng(K).integers(121, 134, g.scale_a.shape).astype(np.uint8)   # codes over a range of 2^12
+        sa_o = R.e8m0_decode(g.scale_a).astype(np.float32) if scale_dtype else None
+        sb_o = R.e8m0_decode(g.scale_b).astype(np.float32) if scale_dtype else None
+        ref = R.gemm_grouped_ref(g.a_mk, g.b_gnk.transpose(0, 2, 1), off, R.AXE_FP8_E4M3, scale_a=sa_o, scale_b=sb_o)
+        if gated:
+            ref = R.swiglu_ref(ref)
+        img = pack_gate_up(g.b_gnk) if gated else g.b_gnk
+        Bs = W.gated_b_spec(K, N, g.G) if gated else W.spec([(g.G, N * K, "m"), (K, 1, "m"), (N, K, "m")])
+        NC = N // 2 if gated else N
+        dA, dB = dev(g.a_mk.reshape(-1)), dev(img.reshape(-1))
+        dC = torch.full((g.M * NC,), SENTINEL, dtype=torch.int16, device="cuda")
+        dR = torch.from_numpy(g.group_rows).cuda()
+        sa = torch.from_numpy(g.scale_a).cuda() if scale_dtype else None
+        sb = torch.from_numpy(g.scale_b).cuda() if scale_dtype else None
+        desc = B.GroupedGemmDesc(g.M, N, K, g.G, B.Layout(W.row_major_spec(g.M, K)), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, NC)),
+                                 g.a_mk.size, img.size, g.M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
+                                 epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=B.AXE_GROUPED_TILES_256,
+                                 scale_a=sa, scale_b=sb, scale_dtype=B.AXE_SCALE_E8M0)
+        assert B.axe_gemm_grouped_kernel(desc) == B.AXE_GROUPED_TILES_256
+        B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+        torch.cuda.synchronize()
+        raw = dC.cpu().numpy().view(np.uint16).reshape(g.M, NC)
+        owned = ~np.isnan(ref[:, 0])
+        assert (raw[~owned] == SENTINEL).all(), "a row outside every group was written"
+        c = R.bf16_to_f64(raw)
+        assert np.isfinite(c[owned]).all()
+        assert R.rel_frobenius(c[owned], ref[owned]) <= FP8_TOL
+        for e in range(g.G):                                   # every group, every 16-row band and 64-column block of it
+            for i in range(off[e], off[e + 1], 16):
+                for j in range(0, NC, 64):
+                    blk = (slice(i, min(i + 16, off[e + 1])), slice(j, j + 64))
+                    assert R.rel_frobenius(c[blk], ref[blk]) <= FP8_TOL, (e, i, j)
+        # the streaming kernel on the same problem: the same result up to the last rounding
+        desc2 = B.GroupedGemmDesc(g.M, N, K, g.G, B.Layout(W.row_major_spec(g.M, K)), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, NC)),
+                                  g.a_mk.size, img.size, g.M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
+                                  epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=B.AXE_GROUPED_STREAM,
+                                  scale_a=sa, scale_b=sb, scale_dtype=B.AXE_SCALE_E8M0)
+        dC2 = torch.full((g.M * NC,), SENTINEL, dtype=torch.int16, device="cuda")
+        B.axe_gemm_grouped(desc2, dA, dB, dC2, dR)
+        torch.cuda.synchronize()
+        c2 = R.bf16_to_f64(dC2.cpu().numpy().view(np.uint16).reshape(g.M, NC))
+        assert R.rel_frobenius(c2[owned], c[owned]) < 5e-3
 
 
 @pytest.mark.parametrize("kernel,gated", [(B.AXE_GROUPED_TILES_256, False), (B.AXE_GROUPED_TILES_128, False), (B.AXE_GROUPED_TILES_128, True),
