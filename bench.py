@@ -277,10 +277,11 @@ def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
     return out
 
 
-def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64)):
-    """The same layer with e4m3 weights and activations at decode sizes: E8M0 block scales (one per row and 128-wide k block
+def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64, 512, 4096)):
+    """The same layer with e4m3 weights and activations: E8M0 block scales (one per row and 128-wide k block
     for the activations, one per 128 x 128 block for the weights), bf16 output; gemm1 with the gated activation.  The
-    weights are half the bytes of the fp16 layer; bound: HBM."""
+    weights are half the bytes of the fp16 layer; bound: HBM.  Kernels chosen by the library: the weight-streaming
+    kernel at decode sizes, the tile kernel on the matrix cores' scale path from 96 rows per expert on."""
     import torch
     from paper_2601_19092_amd import binding as B
     from paper_2601_19092_amd import workloads as W
@@ -313,12 +314,14 @@ def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64)):
             wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dB, dC, dR), steps, warmup)
             active = int((np.diff(rows) > 0).sum())
             nbytes = active * N * K + M * K + 2.0 * M * NC
-            r = {"M": M, "active_experts": active, "kernel_ms": devms, "algorithmic_bytes": nbytes, "GBps": nbytes / (devms * 1e-3) / 1e9}
+            kernel = "streaming" if B.axe_gemm_grouped_kernel(desc) == B.AXE_GROUPED_STREAM else "tiles of 256 x 256"
+            r = {"M": M, "active_experts": active, "kernel": kernel, "kernel_ms": devms, "algorithmic_bytes": nbytes,
+                 "GBps": nbytes / (devms * 1e-3) / 1e9, "tflops": 2.0 * M * N * K / (devms * 1e-3) / 1e12}
             r["frac_of_hbm_peak"] = r["GBps"] / PEAK["hbm"]
             out["sweep"].setdefault(str(tokens), {})[name] = r
             layer[tokens] += devms
-            log(f"[bench] MoE {name}{' + gated activation' if gated else ''} fp8, {tokens} tokens (M={M}, {active} experts with rows, streaming): "
-                f"{devms*1e3:.1f} us, {r['GBps']:.0f} GB/s ({100*r['frac_of_hbm_peak']:.0f}% of HBM peak)")
+            log(f"[bench] MoE {name}{' + gated activation' if gated else ''} fp8, {tokens} tokens (M={M}, {active} experts with rows, {kernel}): "
+                f"{devms*1e3:.1f} us, {r['GBps']:.0f} GB/s ({100*r['frac_of_hbm_peak']:.0f}% of HBM peak), {r['tflops']:.0f} TFLOP/s")
             del dA, dC
         del dB
     for tokens in sweep:

@@ -225,8 +225,11 @@ typedef struct {
  * (G, N/128, ceil(K/128)): one per 128 x 128 block of each B[e]; fp32, or E8M0 codes (one byte, 2^(code - 127);
  * such arrays are read in aligned 4-byte words: 4-byte aligned, allocation padded to a multiple of 4 bytes).
  * Both NULL: unscaled.  K a multiple of 128; B[e] column-major (plain, or gate/up interleaved for the gated
- * epilogue).  Served by the streaming kernel only, whatever M (groups of more than 64 rows then take several
- * passes over their weights); a kernel_hint that asks for tiles is AXE_EUNSUPPORTED. */
+ * epilogue).  Two kernels: the streaming kernel (any scales; groups of more than 64 rows take several passes over
+ * their weights), and, with E8M0 scales or none, the tile kernel on the matrix cores' scale path (tiles of 256
+ * rows; kernel_hint AXE_GROUPED_TILES or AXE_GROUPED_TILES_256; gated: N / 2 a multiple of 128; AUTO takes it
+ * from 20 rows per group on average).  A hint that asks for tiles with fp32 scales, or for 128-row tiles, is
+ * AXE_EUNSUPPORTED. */
 
 /* Two kernels serve the same family.  AXE_GROUPED_TILES: 256 x 256 tiles of the chained GEMM pipeline, for
  * groups of hundreds of rows (of 128 x 256 unless groups average more than 384 rows: a K-step then takes half

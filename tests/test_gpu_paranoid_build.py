@@ -99,3 +99,33 @@ def test_grouped_gemm_fast_build_equals_checking_build(kernel, gated):
             torch.cuda.synchronize()
             out.append(dC)
     assert torch.equal(out[0], out[1]), f"{(out[0] != out[1]).sum().item()} elements differ"
+
+
+@pytest.mark.parametrize("gated", [False, True])
+def test_fp8_grouped_tile_kernel_fast_build_equals_checking_build(gated):
+    rng = np.random.default_rng(23)
+    off = np.concatenate([[0], np.cumsum(rng.integers(0, 500, 24))]).astype(np.int32)
+    N, K = 1024, 768
+    g = W.gemm_grouped_fp8(off, N, K, 99, scale_dtype="e8m0")
+    NC = N // 2 if gated else N
+    plain = B.Layout(W.grouped_gemm_specs(g)[1])
+    dA, dB, dR = dev(g.a_mk.reshape(-1)), dev(g.b_gnk.reshape(-1)), torch.from_numpy(g.group_rows).cuda()
+    useL = plain
+    if gated:
+        useL = B.Layout(W.gated_b_spec(K, N, g.G))
+        packed = torch.empty_like(dB)
+        B.axe_relayout(plain, useL, (g.G, K, N), dB, packed)
+        dB = packed
+    sa, sb = torch.from_numpy(g.scale_a).cuda(), torch.from_numpy(g.scale_b).cuda()
+    desc = B.GroupedGemmDesc(g.M, N, K, g.G, B.Layout(W.row_major_spec(g.M, K)), useL, B.Layout(W.row_major_spec(g.M, NC)),
+                             g.M * K, g.b_gnk.size, g.M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
+                             epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=B.AXE_GROUPED_TILES_256,
+                             scale_a=sa, scale_b=sb, scale_dtype=B.AXE_SCALE_E8M0)
+    out = []
+    for path in (B.LIB_PATH, PARANOID):
+        with library(path):
+            dC = torch.zeros(g.M * NC, dtype=torch.int16, device="cuda")
+            B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+            torch.cuda.synchronize()
+            out.append(dC)
+    assert torch.equal(out[0], out[1]), f"{(out[0] != out[1]).sum().item()} elements differ"
