@@ -185,21 +185,34 @@ int axe_relayout(const axe_layout_t* src, const axe_layout_t* dst, int32_t rank,
       else if (J[k].ds == 1) kD = (int)k;
     }
     const int64_t ce = elem_bytes <= 8 ? 16 / elem_bytes : 0;
-    bool ok = both < 0 && kS >= 0 && kD >= 0 && ce > 0 && md.R.empty() && !ms.swz.mask && !md.swz.mask &&
-              env_int("AXE_RELAYOUT_TRANSPOSE", 1) != 0;
-    if (ok) {
-      // a tile row is worth fetching only if it is at least 64 bytes long on both sides
-      ok = J[kS].e % ce == 0 && J[kD].e % ce == 0 && J[kS].e * elem_bytes >= 64 && J[kD].e * elem_bytes >= 64 &&
-           ms.off % ce == 0 && md.off % ce == 0 && (((uintptr_t)d_src | (uintptr_t)d_dst) & 15) == 0;
-      for (size_t k = 0; k < J.size() && ok; ++k) {
-        if ((int)k != kS && J[k].e > 1 && J[k].ss % ce) ok = false;
-        if ((int)k != kD && J[k].e > 1 && J[k].ds % ce) ok = false;
+    // the transposing case: tiles of the two digits go through LDS.  Both rows at least 64 bytes long, or the tile
+    // is not worth it (the joint loop nest below serves those)
+    bool ok = both < 0 && kS >= 0 && kD >= 0 && ce > 0 && md.E_R <= 64 && env_int("AXE_RELAYOUT_TRANSPOSE", 1) != 0 &&
+              J[kS].e * elem_bytes >= 64 && J[kD].e * elem_bytes >= 64;
+    // ... in whole 16-byte chunks when extents, strides, offsets, replica strides and buffers are chunk multiples and
+    // a swizzle stage moves whole chunks; element by element otherwise
+    bool chunks = ok;
+    if (chunks) {
+      chunks = J[kS].e % ce == 0 && J[kD].e % ce == 0 && ms.off % ce == 0 && md.off % ce == 0 &&
+               (((uintptr_t)d_src | (uintptr_t)d_dst) & 15) == 0;
+      for (size_t k = 0; k < J.size() && chunks; ++k) {
+        if ((int)k != kS && J[k].e > 1 && J[k].ss % ce) chunks = false;
+        if ((int)k != kD && J[k].e > 1 && J[k].ds % ce) chunks = false;
       }
+      for (const HIter& it : md.R)
+        if (it.s % ce) chunks = false;
+      if (ms.swz.mask && (int64_t(1) << ms.swz.base) % ce) chunks = false;
+      if (md.swz.mask && (int64_t(1) << md.swz.base) % ce) chunks = false;
     }
     if (ok) {
       TransposePlan p;
       memset(&p, 0, sizeof p);
-      const int64_t T = transpose_tile_edge(elem_bytes);
+      p.elementwise = chunks ? 0 : 1;
+      const int64_t T = chunks ? transpose_tile_edge(elem_bytes) : 64;
+      p.s_swz = ms.swz, p.d_swz = md.swz;
+      p.n_r = (int)md.R.size();
+      for (int k = 0; k < p.n_r; ++k) p.rext[k] = (int32_t)md.R[k].e, p.rstr[k] = md.R[k].s;
+      p.E_R = md.E_R;
       p.eS = J[kS].e, p.dS = J[kS].ds;
       p.eD = J[kD].e, p.sD = J[kD].ss;
       p.s_off = ms.off, p.d_off = md.off;

@@ -15,6 +15,7 @@ namespace axe {
 static int64_t g_src_bytes = 0, g_dst_bytes = 0;
 static int g_violations = 0;
 static int g_transposes = 0;      // launches of the transposing relayout since the buffers were declared
+static int g_transposes_elem = 0; // ... of which element by element (not in 16-byte chunks)
 
 static int64_t swz_apply(int64_t x, Swz z) { return x ^ (((x >> z.shift) & (int64_t)z.mask) << z.base); }
 
@@ -95,8 +96,44 @@ hipError_t launch_relayout_joint(const RelayoutPlan& p, int unit, const void* sr
 hipError_t launch_relayout_transpose(const TransposePlan& p, int eb, const void* src_, void* dst_, hipStream_t) {
   const char* src = (const char*)src_;
   char* dst = (char*)dst_;
-  const int64_t T = transpose_tile_edge(eb), CE = 16 / eb, CPR = T / CE;
   ++g_transposes;
+  auto replicas = [&](int64_t a, auto&& f) {                      // every replica address of the destination
+    for (int64_t t = 0; t < p.E_R; ++t) {
+      int64_t tr = t, ra = a;
+      for (int k = p.n_r - 1; k >= 0; --k) {
+        ra += (tr % p.rext[k]) * p.rstr[k];
+        tr /= p.rext[k];
+      }
+      f(swz_apply(ra, p.d_swz));
+    }
+  };
+  if (p.elementwise) {                                           // 64 x 64 tiles, element by element
+    ++g_transposes_elem;
+    const int64_t T = 64;
+    for (uint64_t blk = 0; blk < p.blocks; ++blk) {
+      uint64_t b = blk;
+      const int64_t ts = (int64_t)(b % p.tiles_s);
+      b /= p.tiles_s;
+      int64_t td = (int64_t)(b % p.tiles_d);
+      b /= p.tiles_d;
+      if (p.diag > 0) td = (td + ts / p.diag) % p.tiles_d;
+      int64_t sb = p.s_off, db = p.d_off;
+      for (int k = 0; k < p.n; ++k) {
+        sb += (int64_t)(b % p.ext[k]) * p.ss[k];
+        db += (int64_t)(b % p.ext[k]) * p.ds[k];
+        b /= p.ext[k];
+      }
+      for (int64_t r = 0; r < T; ++r)
+        for (int64_t c = 0; c < T; ++c) {
+          const int64_t iD = td * T + r, iS = ts * T + c;
+          if (iD >= p.eD || iS >= p.eS) continue;
+          const int64_t sa = swz_apply(sb + iD * p.sD + iS, p.s_swz);
+          replicas(db + iS * p.dS + iD, [&](int64_t da) { move(src, dst, sa, da, eb); });
+        }
+    }
+    return hipSuccess;
+  }
+  const int64_t T = transpose_tile_edge(eb), CE = 16 / eb, CPR = T / CE;
   for (uint64_t blk = 0; blk < p.blocks; ++blk) {
     uint64_t b = blk;
     const int64_t ts = (int64_t)(b % p.tiles_s);
@@ -115,7 +152,7 @@ hipError_t launch_relayout_transpose(const TransposePlan& p, int eb, const void*
     for (int64_t c = 0; c < T * CPR; ++c) {                       // HBM -> LDS
       const int64_t r = c / CPR, cc = c % CPR, iD = td * T + r, iS = ts * T + cc * CE;
       if (iD >= p.eD || iS >= p.eS) continue;
-      const int64_t a = (sb + iD * p.sD + iS) * eb;
+      const int64_t a = swz_apply(sb + iD * p.sD + iS, p.s_swz) * eb;
       if (a < 0 || a + 16 > g_src_bytes || (a & 15)) {
         ++g_violations;
         continue;
@@ -126,15 +163,17 @@ hipError_t launch_relayout_transpose(const TransposePlan& p, int eb, const void*
     for (int64_t c = 0; c < T * CPR; ++c) {                       // LDS -> HBM
       const int64_t r = c / CPR, cc = c % CPR, iS = ts * T + r, iD = td * T + cc * CE;
       if (iS >= p.eS || iD >= p.eD) continue;
-      const int64_t a = (db + iS * p.dS + iD) * eb;
-      if (a < 0 || a + 16 > g_dst_bytes || (a & 15)) {
-        ++g_violations;
-        continue;
-      }
-      for (int64_t k = 0; k < CE; ++k) {
-        if (!have[(size_t)((cc * CE + k) * T + r)]) ++g_violations;   // would store what was never loaded
-        memcpy(dst + a + k * eb, &tile[(size_t)(((cc * CE + k) * T + r) * eb)], (size_t)eb);
-      }
+      replicas(db + iS * p.dS + iD, [&](int64_t da) {
+        const int64_t a = da * eb;
+        if (a < 0 || a + 16 > g_dst_bytes || (a & 15)) {
+          ++g_violations;
+          return;
+        }
+        for (int64_t k = 0; k < CE; ++k) {
+          if (!have[(size_t)((cc * CE + k) * T + r)]) ++g_violations;   // would store what was never loaded
+          memcpy(dst + a + k * eb, &tile[(size_t)(((cc * CE + k) * T + r) * eb)], (size_t)eb);
+        }
+      });
     }
   }
   return hipSuccess;
@@ -184,9 +223,11 @@ extern "C" void axe_hostcheck_set_buffers(int64_t src_bytes, int64_t dst_bytes) 
   axe::g_dst_bytes = dst_bytes;
   axe::g_violations = 0;
   axe::g_transposes = 0;
+  axe::g_transposes_elem = 0;
 }
 extern "C" int axe_hostcheck_violations(void) { return axe::g_violations; }
 extern "C" int axe_hostcheck_transposes(void) { return axe::g_transposes; }
+extern "C" int axe_hostcheck_transposes_elementwise(void) { return axe::g_transposes_elem; }
 
 // ---------------------------------------------------------------------------------------------------------------
 // Test hook: a layout axe_gemm_describe reports, evaluated at every point of its tile (through axe_layout_eval and

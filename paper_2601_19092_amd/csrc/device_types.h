@@ -62,6 +62,12 @@ struct TransposePlan {
   uint64_t blocks;                 // tiles_s * tiles_d * product of ext[]
   int32_t streaming;               // 1: non-temporal loads and stores
   int32_t diag;                    // g > 0: tiles are walked diagonally, td = (row + ts / g) mod tiles_d; 0: row by row
+  Swz s_swz, d_swz;                // swizzle stages of the two sides (mask 0: none), applied to an access's first element
+  int32_t n_r;                     // destination replicas: every replica address is written
+  int32_t rext[kMaxR];
+  int64_t rstr[kMaxR];
+  int64_t E_R;
+  int32_t elementwise;             // 1: tiles of 64 x 64 moved element by element (no alignment requirement at all)
 };
 
 // Fallback when the two digit systems have no common refinement: decode each side separately.

@@ -336,7 +336,8 @@ __global__ __launch_bounds__(256) void relayout_transpose_kernel(TransposePlan p
     // tile's first one (always inside) instead of being skipped: a load under a branch would be waited for at
     // the end of that branch, one by one.
     const bool in = iD < p.eD && iS < p.eS;
-    const u32x4* a = (const u32x4*)(src + (sb + (in ? iD * p.sD + iS : d0 * p.sD + s0)) * EB);
+    // (a swizzle stage moves whole chunks: the host admits it here only when it leaves the bits inside a chunk alone)
+    const u32x4* a = (const u32x4*)(src + swz_apply(sb + (in ? iD * p.sD + iS : d0 * p.sD + s0), p.s_swz) * EB);
     held[i] = NT ? __builtin_nontemporal_load(a) : *a;
   }
 #pragma unroll
@@ -379,9 +380,67 @@ __global__ __launch_bounds__(256) void relayout_transpose_kernel(TransposePlan p
           v[2 * j + 1] = q[1];
         }
       }
-      u32x4* a = (u32x4*)(dst + (db + iS * p.dS + iD) * EB);
-      if (NT) __builtin_nontemporal_store(v, a);
-      else *a = v;
+      for (int64_t t = 0; t < p.E_R; ++t) {                        // every replica of the destination (usually one)
+        int64_t tr = t, ra = db + iS * p.dS + iD;
+        for (int k = p.n_r - 1; k >= 0; --k) {
+          ra += (tr % p.rext[k]) * p.rstr[k];
+          tr /= p.rext[k];
+        }
+        u32x4* a = (u32x4*)(dst + swz_apply(ra, p.d_swz) * EB);
+        if (NT) __builtin_nontemporal_store(v, a);
+        else *a = v;
+      }
+    }
+  }
+}
+
+// The same transposition element by element, for pairs of layouts the 16-byte variant cannot take: extents, strides
+// or offsets that are no multiples of a chunk, buffers that are not 16-byte aligned, a swizzle that reaches into a
+// chunk.  A workgroup moves a 64 x 64 tile: each wave instruction reads 64 consecutive elements along the
+// source-fast digit and writes 64 consecutive elements along the destination-fast digit (the per-element kernel
+// leaves one side with single elements scattered over rows); the tile is parked in LDS with a pitch of 65 words.
+template <int EB>
+__global__ __launch_bounds__(256) void relayout_transpose_elem_kernel(TransposePlan p, const void* __restrict__ src_,
+                                                                      void* __restrict__ dst_) {
+  constexpr int T = 64;
+  using W = typename Word<EB>::T;
+  const W* __restrict__ src = (const W*)src_;
+  W* __restrict__ dst = (W*)dst_;
+  __shared__ W tile[T][T + 1];
+  uint64_t b = blockIdx.x;
+  const uint32_t ts = (uint32_t)(b % p.tiles_s);
+  b /= p.tiles_s;
+  uint32_t td = (uint32_t)(b % p.tiles_d);
+  b /= p.tiles_d;
+  if (p.diag > 0) td = (td + ts / (uint32_t)p.diag) % p.tiles_d;
+  int64_t sb = p.s_off, db = p.d_off;
+  for (int k = 0; k < p.n; ++k) {
+    const uint64_t q = b / p.ext[k];
+    const int64_t dig = (int64_t)(b - q * p.ext[k]);
+    sb += dig * p.ss[k];
+    db += dig * p.ds[k];
+    b = q;
+  }
+  const int64_t s0 = (int64_t)ts * T, d0 = (int64_t)td * T;
+  const int tx = threadIdx.x & 63, ty = threadIdx.x >> 6;
+#pragma unroll 4
+  for (int r = ty; r < T; r += 4) {                              // tile row r: destination-fast index d0 + r, lanes along the source
+    const int64_t iD = d0 + r, iS = s0 + tx;
+    if (iD < p.eD && iS < p.eS) tile[r][tx] = src[swz_apply(sb + iD * p.sD + iS, p.s_swz)];
+  }
+  __syncthreads();
+  for (int r = ty; r < T; r += 4) {                              // output row r: source-fast index s0 + r, lanes along the destination
+    const int64_t iS = s0 + r, iD = d0 + tx;
+    if (iS < p.eS && iD < p.eD) {
+      const W v = tile[tx][r];
+      for (int64_t t = 0; t < p.E_R; ++t) {
+        int64_t tr = t, ra = db + iS * p.dS + iD;
+        for (int k = p.n_r - 1; k >= 0; --k) {
+          ra += (tr % p.rext[k]) * p.rstr[k];
+          tr /= p.rext[k];
+        }
+        dst[swz_apply(ra, p.d_swz)] = v;
+      }
     }
   }
 }
@@ -400,6 +459,17 @@ static hipError_t launch_transpose_e(const TransposePlan& p, const void* src, vo
 hipError_t launch_relayout_transpose(const TransposePlan& p, int elem_bytes, const void* src, void* dst, hipStream_t s) {
   if (p.blocks == 0) return hipSuccess;
   if (p.blocks > 0x7fffffffull) return hipErrorInvalidValue;
+  if (p.elementwise) {
+    const dim3 grid((unsigned)p.blocks), block(256);
+    switch (elem_bytes) {
+      case 1: hipLaunchKernelGGL(relayout_transpose_elem_kernel<1>, grid, block, 0, s, p, src, dst); break;
+      case 2: hipLaunchKernelGGL(relayout_transpose_elem_kernel<2>, grid, block, 0, s, p, src, dst); break;
+      case 4: hipLaunchKernelGGL(relayout_transpose_elem_kernel<4>, grid, block, 0, s, p, src, dst); break;
+      case 8: hipLaunchKernelGGL(relayout_transpose_elem_kernel<8>, grid, block, 0, s, p, src, dst); break;
+      default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+  }
   switch (elem_bytes) {
     case 1: return launch_transpose_e<1>(p, src, dst, s);
     case 2: return launch_transpose_e<2>(p, src, dst, s);

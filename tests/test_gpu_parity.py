@@ -220,6 +220,71 @@ def test_relayout_transposing_path(eb):
         assert back.tobytes() == wb.tobytes(), (shape, kind)
 
 
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_relayout_transposing_path_replicas_and_swizzles(eb):
+    """The tiled path with a replicated destination and with swizzle stages that move whole 16-byte chunks."""
+    rng = np.random.default_rng(300 + eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    ce = 16 // eb
+    T = {1: 128, 2: 128, 4: 128, 8: 64}[eb]
+    lg = ce.bit_length() - 1
+    for shape in [(T, T), (2 * T, T + ce), (T + 3 * ce, 2 * T), (4 * T, 6 * T)]:
+        rows, cols = shape
+        n = rows * cols
+        size = 1 << (n - 1).bit_length()
+        src = rng.integers(0, 256, n * eb, dtype=np.uint8).view(dt)
+        row, col = ax.row_major(shape), Layout.make(shape, (1, rows))
+        for R_, span in [(((2,), (n,)), 2 * n), (((2, 3), (3 * (n + ce), n + ce)), 6 * (n + ce))]:
+            got, want = relayout_both(row, Layout.make(shape, (1, rows), R=R_), shape, src, span)
+            assert got.tobytes() == want.tobytes(), (shape, R_)
+        sw_d = Swizzle("m", 3, lg, lg + 5)
+        sw_s = Swizzle("m", 2, lg + 1, lg + 4)
+        for s_L, d_L in [(row, col.with_(swizzle=sw_d)), (row.with_(swizzle=sw_s), col),
+                         (row.with_(swizzle=sw_s), col.with_(swizzle=sw_d)),
+                         (col.with_(swizzle=sw_d), row.with_(swizzle=sw_s))]:
+            src_p = rng.integers(0, 256, size * eb, dtype=np.uint8).view(dt)
+            got, want = relayout_both(s_L, d_L, shape, src_p, size)
+            assert got.tobytes() == want.tobytes(), (shape, s_L, d_L)
+        d_L = Layout.make(shape, (1, rows), R=((2,), (size,))).with_(swizzle=sw_d)
+        got, want = relayout_both(row, d_L, shape, src, 2 * size)
+        assert got.tobytes() == want.tobytes(), shape
+
+
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_relayout_transposing_path_element_by_element(eb):
+    """Transposing pairs whose rows are not whole 16-byte chunks: odd extents, pitches, offsets and replica
+    strides, swizzles inside a chunk; several tiles with clipped edges, a batch digit; both directions."""
+    rng = np.random.default_rng(400 + eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    w = max(64 // eb, 2)
+    cases = []
+    for shape in [(w + 1, 2 * w + 3), (129, 67 + w), (64, 64 + w + 1), (3, w + 5, 70 + w), (301, 515), (1000, 37 + w)]:
+        rows, cols = shape[-2], shape[-1]
+        n = prod(shape)
+        if len(shape) == 3:
+            s_L, d_L = ax.row_major(shape), Layout.make(shape, (rows * cols, 1, rows))
+        else:
+            s_L, d_L = ax.row_major(shape), Layout.make(shape, (1, rows))
+        cases.append((shape, s_L, d_L, n, n))
+    rows, cols = w + 2, 2 * w + 1
+    shape = (rows, cols)
+    cases.append((shape, Layout.make(shape, (cols + 3, 1), O={"m": 1}), Layout.make(shape, (1, rows + 5), O={"m": 3}),
+                  1 + rows * (cols + 3), 3 + cols * (rows + 5)))
+    rows, cols = 2 * w, 2 * w
+    shape = (rows, cols)
+    n = rows * cols
+    cases.append((shape, ax.row_major(shape), Layout.make(shape, (1, rows), R=((3,), (n + 1,))), n, 3 * (n + 1)))
+    cases.append((shape, ax.row_major(shape).with_(swizzle=Swizzle("m", 2, 0, 7)),
+                  Layout.make(shape, (1, rows)).with_(swizzle=Swizzle("m", 3, 1, 8)), n, n))
+    for shape, s_L, d_L, n_src, n_dst in cases:
+        src = rng.integers(0, 256, n_src * eb, dtype=np.uint8).view(dt)
+        got, want = relayout_both(s_L, d_L, shape, src, n_dst)
+        assert got.tobytes() == want.tobytes(), (shape, s_L, d_L)
+        if not d_L.R:
+            back, wb = relayout_both(d_L, s_L, shape, got, n_src)
+            assert back.tobytes() == wb.tobytes(), (shape, "back")
+
+
 @pytest.mark.parametrize("rows,cols,dtype", [(8192, 8192, np.uint16), (4096, 12288, np.uint16), (8192, 8192, np.uint32)])
 def test_relayout_transpose_full_size(rows, cols, dtype):
     """Row-major -> column-major of a matrix of the workload's size against the definition written with

@@ -156,15 +156,83 @@ def test_plan_transposing_path(hc, eb):
         assert got.tobytes() == want.tobytes(), (shape, kind)
         back, wb = host_relayout(hc, d_L, s_L, shape, got, n_src)           # and the other way round
         assert hc.axe_hostcheck_transposes() == 1 and back.tobytes() == wb.tobytes()
-    # rows that do not end on a 16-byte boundary, a swizzled side or a replicated destination stay on the other paths
-    shape = (T, T + 1)
+    assert hc.axe_hostcheck_transposes_elementwise() == 0
+
+
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_plan_transposing_path_replicas_and_swizzles(hc, eb):
+    """The 16-byte tiled path also serves a replicated destination (every replica written from the same LDS
+    tile) and a swizzle stage on either side that moves whole chunks."""
+    rng = np.random.default_rng(300 + eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    ce = 16 // eb
+    T = {1: 128, 2: 128, 4: 128, 8: 64}[eb]
+    lg = ce.bit_length() - 1
+    for shape in [(T, T), (2 * T, T + ce), (T + 3 * ce, 2 * T)]:
+        rows, cols = shape
+        n = rows * cols
+        size = 1 << (n - 1).bit_length()                                   # a swizzle permutes a power-of-two span
+        src = rng.integers(0, 256, n * eb, dtype=np.uint8).view(dt)
+        row, col = ax.row_major(shape), Layout.make(shape, (1, rows))
+        # two and 2 x 3 replicas of a transposed destination, strides multiples of a chunk
+        for R_, span in [(((2,), (n,)), 2 * n), (((2, 3), (3 * (n + ce), n + ce)), 6 * (n + ce))]:
+            got, want = host_relayout(hc, row, Layout.make(shape, (1, rows), R=R_), shape, src, span)
+            assert hc.axe_hostcheck_transposes() == 1 and hc.axe_hostcheck_transposes_elementwise() == 0
+            assert got.tobytes() == want.tobytes(), (shape, R_)
+        # swizzled destination, swizzled source, both; XOR target bits at or above a chunk
+        sw_d = Swizzle("m", 3, lg, lg + 5)
+        sw_s = Swizzle("m", 2, lg + 1, lg + 4)
+        for s_L, d_L in [(row, col.with_(swizzle=sw_d)), (row.with_(swizzle=sw_s), col),
+                         (row.with_(swizzle=sw_s), col.with_(swizzle=sw_d)),
+                         (col.with_(swizzle=sw_d), row.with_(swizzle=sw_s))]:
+            src_p = rng.integers(0, 256, size * eb, dtype=np.uint8).view(dt)
+            got, want = host_relayout(hc, s_L, d_L, shape, src_p, size)
+            assert hc.axe_hostcheck_transposes() == 1 and hc.axe_hostcheck_transposes_elementwise() == 0
+            assert got.tobytes() == want.tobytes(), (shape, s_L, d_L)
+        # replicas and a swizzle together
+        d_L = Layout.make(shape, (1, rows), R=((2,), (size,))).with_(swizzle=sw_d)
+        got, want = host_relayout(hc, row, d_L, shape, src, 2 * size)
+        assert hc.axe_hostcheck_transposes() == 1 and got.tobytes() == want.tobytes()
+
+
+@pytest.mark.parametrize("eb", [1, 2, 4, 8])
+def test_plan_transposing_path_element_by_element(hc, eb):
+    """Rows that are not whole 16-byte chunks (odd extents, odd pitches, odd offsets, odd replica strides, a swizzle
+    inside a chunk): 64 x 64 tiles through LDS, element by element; the stand-in checks every access."""
+    rng = np.random.default_rng(400 + eb)
+    dt = {1: np.uint8, 2: np.uint16, 4: np.uint32, 8: np.uint64}[eb]
+    ce = 16 // eb
+    w = max(64 // eb, 2)                                                   # shortest row the path takes
+    cases = []
+    for shape in [(w + 1, 2 * w + 3), (129, 67 + w), (64, 64 + w + 1), (3, w + 5, 70 + w)]:
+        rows, cols = shape[-2], shape[-1]
+        lead = shape[:-2]
+        n = prod(shape)
+        if lead:
+            s_L = ax.row_major(shape)
+            d_L = Layout.make(shape, (rows * cols, 1, rows))
+        else:
+            s_L, d_L = ax.row_major(shape), Layout.make(shape, (1, rows))
+        cases.append((shape, s_L, d_L, n, n))
+    rows, cols = w + 2, 2 * w + 1
+    shape = (rows, cols)
+    cases.append((shape, Layout.make(shape, (cols + 3, 1), O={"m": 1}), Layout.make(shape, (1, rows + 5), O={"m": 3}),
+                  1 + rows * (cols + 3), 3 + cols * (rows + 5)))           # odd pitches and offsets
+    rows, cols = 2 * w, 2 * w
+    shape = (rows, cols)
+    n = rows * cols
+    cases.append((shape, ax.row_major(shape), Layout.make(shape, (1, rows), R=((3,), (n + 1,))), n, 3 * (n + 1)))
+    cases.append((shape, ax.row_major(shape).with_(swizzle=Swizzle("m", 2, 0, 7)),
+                  Layout.make(shape, (1, rows)).with_(swizzle=Swizzle("m", 3, 1, 8)), n, n))
+    for shape, s_L, d_L, n_src, n_dst in cases:
+        src = rng.integers(0, 256, n_src * eb, dtype=np.uint8).view(dt)
+        got, want = host_relayout(hc, s_L, d_L, shape, src, n_dst)
+        assert hc.axe_hostcheck_transposes() == 1 and hc.axe_hostcheck_transposes_elementwise() == 1, (shape, s_L, d_L)
+        assert got.tobytes() == want.tobytes(), (shape, s_L, d_L)
+    # rows shorter than 64 bytes on either side stay on the loop-nest paths
+    shape = (w // 2, 4 * w)
     src = rng.integers(0, 256, prod(shape) * eb, dtype=np.uint8).view(dt)
-    got, want = host_relayout(hc, ax.row_major(shape), Layout.make(shape, (1, T)), shape, src, prod(shape))
-    assert hc.axe_hostcheck_transposes() == 0 and got.tobytes() == want.tobytes()
-    shape = (T, T)
-    src = rng.integers(0, 256, prod(shape) * eb, dtype=np.uint8).view(dt)
-    D2 = Layout.make(shape, (1, T), R=((2,), (T * T,)))
-    got, want = host_relayout(hc, ax.row_major(shape), D2, shape, src, 2 * T * T)
+    got, want = host_relayout(hc, ax.row_major(shape), Layout.make(shape, (1, shape[0])), shape, src, prod(shape))
     assert hc.axe_hostcheck_transposes() == 0 and got.tobytes() == want.tobytes()
 
 
