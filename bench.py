@@ -224,6 +224,7 @@ def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
     full = {"gemm1": W.moe_gemm1(top, dtype=dtype), "gemm2": W.moe_gemm2(top, dtype=dtype)}
     out = {"experts": W.MOE_EXPERTS, "experts_per_token": W.MOE_TOPK, "dtype": dtype, "sweep": {}}
     layer = {t: 0.0 for t in sweep}
+    packed = {}
     for name, f in full.items():
         gated = name == "gemm1"
         NC = f.N // 2 if gated else f.N
@@ -269,11 +270,40 @@ def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
                     f"blocked weights {r['blocked_weights_no_epilogue_ms']*1e3:.0f} us")
                 del dCw
             del dA, dC
+        packed[name] = (dBuse, useL)
         del dB, dBblk, dBuse
     for tokens in sweep:
         out["sweep"][str(tokens)]["layer_kernel_ms"] = layer[tokens]
     log("[bench] MoE layer expert compute (gemm1 + activation, gemm2), us by tokens: " +
         ", ".join(f"{t}: {layer[t]*1e3:.0f}" for t in sweep))
+    # both GEMMs as one launch (axe_gemm_grouped_pair: gemm2's row blocks start when gemm1's tiles for those rows are
+    # stored), where the library shares the launch; the two-launch time through the same entry point beside it
+    f1, f2 = full["gemm1"], full["gemm2"]
+    fused = {}
+    for tokens in sweep:
+        rows = W.moe_group_rows(tokens, W.MOE_EXPERTS, W.MOE_TOPK, W.SEED_BASE + 11)
+        M, I = int(rows[-1]), f1.N // 2
+        d1 = B.GroupedGemmDesc(M, f1.N, f1.K, f1.G, B.Layout(W.row_major_spec(M, f1.K)), packed["gemm1"][1], B.Layout(W.row_major_spec(M, I)),
+                               M * f1.K, f1.b_gnk.size, M * I, in_dtype=dt, out_dtype=dt, epilogue=B.AXE_EPI_SWIGLU)
+        d2 = B.GroupedGemmDesc(M, f2.N, f2.K, f2.G, B.Layout(W.row_major_spec(M, f2.K)), packed["gemm2"][1], B.Layout(W.row_major_spec(M, f2.N)),
+                               M * f2.K, f2.b_gnk.size, M * f2.N, in_dtype=dt, out_dtype=dt)
+        if not B.axe_gemm_grouped_pair_fused(d1, d2):
+            continue
+        dA = dev(f1.a_mk[:M].reshape(-1))
+        dH = torch.zeros(M * I, dtype=torch.int16, device="cuda")
+        dC = torch.zeros(M * f2.N, dtype=torch.int16, device="cuda")
+        dR = torch.from_numpy(rows).cuda()
+        sync = torch.zeros(M + 1, dtype=torch.int32, device="cuda")
+        _, two = time_loop(lambda i: B.axe_gemm_grouped_pair(d1, d2, dA, packed["gemm1"][0], dH, packed["gemm2"][0], dC, dR, None), steps, warmup)
+        _, one = time_loop(lambda i: B.axe_gemm_grouped_pair(d1, d2, dA, packed["gemm1"][0], dH, packed["gemm2"][0], dC, dR, sync), steps, warmup)
+        B.axe_gemm_grouped_pair_status(sync, M)
+        out["sweep"][str(tokens)]["layer_two_launches_ms"] = two
+        out["sweep"][str(tokens)]["layer_one_launch_ms"] = one
+        fused[tokens] = (two, one)
+        del dA, dH, dC
+    if fused:
+        log("[bench] MoE layer as one launch with tile-level hand-over (two launches -> one), us by tokens: " +
+            ", ".join(f"{t}: {a*1e3:.0f} -> {b*1e3:.0f}" for t, (a, b) in fused.items()))
     return out
 
 

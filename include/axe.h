@@ -50,9 +50,10 @@ enum {
   AXE_ERANGE       = -4,  /* an address falls outside the declared buffer, or arithmetic overflows    */
   AXE_EUNSUPPORTED = -5,  /* valid layouts outside the kernel families of this library               */
   AXE_EHIP         = -6,  /* HIP runtime failure (launch error)                                       */
-  AXE_ENOFORM      = -7   /* a layout operator's sufficient conditions do not hold (the paper's FAILURE
+  AXE_ENOFORM      = -7,  /* a layout operator's sufficient conditions do not hold (the paper's FAILURE
                              outcome of grouping, tile-of and slice): valid inputs, no answer of the
                              required form                                                             */
+  AXE_ETIMEOUT     = -8   /* a bounded wait inside a kernel gave up (axe_gemm_grouped_pair_status)        */
 };
 
 /* Def. 2.1: f_I(x) = (x * stride) @ axis;  extent > 0, stride != 0, 0 <= axis < n_axes. */
@@ -255,6 +256,40 @@ int axe_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* d_A, const vo
                      const int32_t* d_group_rows, void* stream);
 /* The checks of axe_gemm_grouped without a launch (host only): AXE_OK or the error it would return. */
 int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g);
+
+/* ---------------------------------------------------------------------------------------------
+ * axe_gemm_grouped_pair -- the expert computation of an MoE layer as ONE launch (Sec. 4.1, "fused MoE layer": the
+ * two group GEMMs overlap through a tile-level dependency instead of a kernel boundary):
+ *       H = epilogue1(A B1[e])   (problem g1, gated activation),      C = H B2[e]   (problem g2, no epilogue),
+ * where g2's A is g1's C: same M, G, element type and count, same layout, K2 = columns of H.  The row blocks of
+ * the second GEMM start as soon as the column tiles of the first GEMM for those rows are stored; the workgroups that
+ * run out of tiles of the first GEMM go on with the second.  d_H is an output like d_C (the intermediate activations,
+ * rounded to the 16-bit type exactly as axe_gemm_grouped stores them: the result equals two axe_gemm_grouped calls).
+ *
+ *   d_A, d_B1, d_B2, d_group_rows : DEVICE inputs, as for axe_gemm_grouped (one d_group_rows for both problems).
+ *   d_H, d_C : DEVICE outputs, disjoint from the inputs and from each other.
+ *   d_sync, sync_elems : DEVICE workspace of at least M + 1 int32 words (4-byte aligned), owned by the caller,
+ *       overwritten by every call (cleared on the stream by a small kernel, so the call may be captured into a
+ *       graph); calls that share one d_sync must not overlap in time.  NULL: the two problems run one after the
+ *       other on the stream, as they also do when they cannot share a launch -- 16-bit tile kernels of the same
+ *       tile height only, both K multiples of 128 and at least 256, first problem gated, H's rows starting on
+ *       128-byte boundaries (pitch and buffer), and few enough tiles that one workgroup per compute unit holds
+ *       them (64 per workgroup and problem).
+ *   Every wait inside the kernel is bounded (a number of polls, AXE_GROUPED_PAIR_POLLS, default 2^20, each a few
+ *   microseconds): a wait that gives up is counted in d_sync[M] and the tile is computed from what is there.
+ *   axe_gemm_grouped_pair_status(d_sync, M, stream) synchronises the stream and returns AXE_ETIMEOUT if any wait of
+ *   the last call gave up (rows of C are then invalid), else AXE_OK.  With all workgroups resident (the launch is
+ *   sized to the compute units of the device) no wait can fail to end: tiles of the first GEMM wait for nothing and
+ *   every workgroup works through its share of them before it waits.
+ *   axe_gemm_grouped_pair_fused(g1, g2): 1 if the pair would share a launch (given a workspace), 0 if not, or the
+ *   error axe_gemm_grouped_pair would return (host only).
+ * Errors: those of axe_gemm_grouped for either problem; AXE_EINVAL when g2's A is not g1's C or the workspace is
+ * too small. */
+int axe_gemm_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const void* d_A,
+                          const void* d_B1, void* d_H, const void* d_B2, void* d_C, const int32_t* d_group_rows,
+                          int32_t* d_sync, int64_t sync_elems, void* stream);
+int axe_gemm_grouped_pair_fused(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2);
+int axe_gemm_grouped_pair_status(const int32_t* d_sync, int64_t M, void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * axe_gemm_describe -- the Axe layouts of every tile movement of the kernel axe_gemm would

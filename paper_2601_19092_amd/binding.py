@@ -14,7 +14,7 @@ from typing import Dict, List, Optional, Sequence, Tuple
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libaxe_hip.so")
 
-AXE_OK, AXE_EINVAL, AXE_ESHAPE, AXE_EALIAS, AXE_ERANGE, AXE_EUNSUPPORTED, AXE_EHIP, AXE_ENOFORM = 0, -1, -2, -3, -4, -5, -6, -7
+AXE_OK, AXE_EINVAL, AXE_ESHAPE, AXE_EALIAS, AXE_ERANGE, AXE_EUNSUPPORTED, AXE_EHIP, AXE_ENOFORM, AXE_ETIMEOUT = 0, -1, -2, -3, -4, -5, -6, -7, -8
 AXE_BF16, AXE_FP8_E4M3, AXE_F32, AXE_F16 = 1, 2, 3, 4
 AXE_TILE_AUTO, AXE_TILE_64x64x32, AXE_TILE_256x256x64, AXE_TILE_256x224x64 = 0, 1, 2, 3
 (AXE_DESC_A_G2L_THREADS, AXE_DESC_B_G2L_THREADS, AXE_DESC_A_LDS, AXE_DESC_B_LDS, AXE_DESC_A_OPERAND,
@@ -24,7 +24,8 @@ AXE_SCALE_F32, AXE_SCALE_E8M0 = 0, 1
 AXE_EPI_NONE, AXE_EPI_SWIGLU = 0, 1
 AXE_GROUPED_AUTO, AXE_GROUPED_TILES, AXE_GROUPED_STREAM, AXE_GROUPED_TILES_256, AXE_GROUPED_TILES_128 = 0, 1, 2, 3, 4
 
-EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_grouped_kernel", "axe_gemm_grouped_describe", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
+EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_grouped_pair", "axe_gemm_grouped_pair_fused",
+           "axe_gemm_grouped_pair_status", "axe_gemm_grouped_kernel", "axe_gemm_grouped_describe", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
            "axe_last_error", "axe_version", "axe_layout_span", "axe_layout_canonicalize", "axe_layout_gap_condition",
            "axe_layout_equal", "axe_layout_group", "axe_layout_tile", "axe_layout_direct_sum", "axe_layout_tile_of",
            "axe_layout_slice"]
@@ -90,6 +91,13 @@ def load(path: str) -> C.CDLL:
     L.axe_gemm_grouped.argtypes = [C.POINTER(axe_gemm_grouped_desc_t), vp, vp, vp, vp, vp]
     L.axe_gemm_grouped_check.restype = C.c_int
     L.axe_gemm_grouped_check.argtypes = [C.POINTER(axe_gemm_grouped_desc_t)]
+    GP = C.POINTER(axe_gemm_grouped_desc_t)
+    L.axe_gemm_grouped_pair.restype = C.c_int
+    L.axe_gemm_grouped_pair.argtypes = [GP, GP, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+    L.axe_gemm_grouped_pair_fused.restype = C.c_int
+    L.axe_gemm_grouped_pair_fused.argtypes = [GP, GP]
+    L.axe_gemm_grouped_pair_status.restype = C.c_int
+    L.axe_gemm_grouped_pair_status.argtypes = [vp, i64, vp]
     L.axe_gemm_tile.restype = C.c_int
     L.axe_gemm_tile.argtypes = [C.POINTER(axe_gemm_desc_t)]
     L.axe_gemm_grouped_kernel.restype = C.c_int
@@ -261,6 +269,29 @@ def axe_gemm_grouped(desc: GroupedGemmDesc, A_buf, B_buf, C_buf, group_rows, str
     _check(lib().axe_gemm_grouped(C.byref(desc.c), A_buf.data_ptr(), B_buf.data_ptr(), C_buf.data_ptr(),
                                   group_rows.data_ptr(), _stream_ptr(stream)))
     return C_buf
+
+
+def axe_gemm_grouped_pair(desc1: GroupedGemmDesc, desc2: GroupedGemmDesc, A_buf, B1_buf, H_buf, B2_buf, C_buf, group_rows,
+                          sync=None, stream=None):
+    """Both grouped GEMMs of an MoE layer's expert computation; with `sync` (int32 device tensor, M + 1 words) as one launch."""
+    assert all(t.is_cuda for t in (A_buf, B1_buf, H_buf, B2_buf, C_buf, group_rows))
+    assert str(group_rows.dtype) == "torch.int32" and group_rows.numel() == desc1.c.G + 1 and group_rows.is_contiguous()
+    if sync is not None:
+        assert sync.is_cuda and str(sync.dtype) == "torch.int32" and sync.is_contiguous()
+    _check(lib().axe_gemm_grouped_pair(C.byref(desc1.c), C.byref(desc2.c), A_buf.data_ptr(), B1_buf.data_ptr(), H_buf.data_ptr(),
+                                       B2_buf.data_ptr(), C_buf.data_ptr(), group_rows.data_ptr(),
+                                       sync.data_ptr() if sync is not None else None, sync.numel() if sync is not None else 0,
+                                       _stream_ptr(stream)))
+    return C_buf
+
+
+def axe_gemm_grouped_pair_fused(desc1: GroupedGemmDesc, desc2: GroupedGemmDesc) -> bool:
+    return _flag(lib().axe_gemm_grouped_pair_fused(C.byref(desc1.c), C.byref(desc2.c)))
+
+
+def axe_gemm_grouped_pair_status(sync, M: int, stream=None) -> None:
+    """Synchronises the stream; raises if a wait inside the last fused launch that used `sync` gave up."""
+    _check(lib().axe_gemm_grouped_pair_status(sync.data_ptr(), M, _stream_ptr(stream)))
 
 
 def axe_gemm_grouped_check(desc: GroupedGemmDesc) -> None:

@@ -46,6 +46,7 @@ const char* axe_strerror(int code) {
     case AXE_EUNSUPPORTED: return "layouts outside the supported kernel families";
     case AXE_EHIP: return "HIP runtime failure";
     case AXE_ENOFORM: return "the layout operator's sufficient conditions do not hold";
+    case AXE_ETIMEOUT: return "a bounded wait inside a kernel gave up";
     default: return "unknown error code";
   }
 }
@@ -956,6 +957,83 @@ int axe_gemm_grouped_kernel(const axe_gemm_grouped_desc_t* g) {
 int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g) {
   GemmArgs a;
   return plan_gemm_grouped(g, nullptr, nullptr, nullptr, nullptr, a, false);
+}
+
+namespace {
+// The two problems of axe_gemm_grouped_pair, planned: the second must read exactly what the first writes.
+int plan_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const void* dA, const void* dB1, void* dH,
+                      const void* dB2, void* dC, const int32_t* rows, GemmArgs& a1, GemmArgs& a2, bool need_ptrs) {
+  const char* fn = "axe_gemm_grouped_pair";
+  // (a placeholder keeps the address arithmetic of the two plans comparable when no pointers are given)
+  void* h = need_ptrs ? dH : (void*)(uintptr_t)4096;
+  if (int rc = plan_gemm_grouped(g1, need_ptrs ? dA : nullptr, need_ptrs ? dB1 : nullptr, h, rows, a1, need_ptrs)) return rc;
+  if (int rc = plan_gemm_grouped(g2, h, need_ptrs ? dB2 : nullptr, need_ptrs ? dC : nullptr, rows, a2, need_ptrs)) return rc;
+  const int64_t NC1 = g1->epilogue == AXE_EPI_SWIGLU ? g1->N / 2 : g1->N;
+  if (g1->M != g2->M || g1->G != g2->G || g2->K != NC1 || g1->out_dtype != g2->in_dtype || g1->c_elems != g2->a_elems ||
+      a1.C != a2.A || a1.ldc != a2.lda) {
+    set_error("%s: the second problem's A must be the first problem's C: same M, G, element type, element count, layout, and K2 = "
+              "columns of C1", fn);
+    return AXE_EINVAL;
+  }
+  return AXE_OK;
+}
+
+bool pair_runs_fused(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const GemmArgs& a1, const GemmArgs& a2) {
+  // (rows of the intermediate matrix start on 128-byte lines: no cache line then holds rows of two row blocks, or
+  //  columns of two tiles of the first GEMM)
+  return !grouped_goes_to_stream(g1, a1) && !grouped_goes_to_stream(g2, a2) && grouped_pair_fusable(a1, a2) &&
+         (a1.ldc * 2) % 128 == 0 && ((uintptr_t)a1.C & 127) == 0 && env_int("AXE_GROUPED_PAIR_FUSE", 1) != 0;
+}
+}  // namespace
+
+int axe_gemm_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const void* d_A, const void* d_B1,
+                          void* d_H, const void* d_B2, void* d_C, const int32_t* d_group_rows, int32_t* d_sync, int64_t sync_elems,
+                          void* stream) {
+  GemmArgs a1, a2;
+  if (int rc = plan_grouped_pair(g1, g2, d_A, d_B1, d_H, d_B2, d_C, d_group_rows, a1, a2, true)) return rc;
+  if (d_sync && (sync_elems < g1->M + 1 || ((uintptr_t)d_sync & 3))) {
+    set_error("axe_gemm_grouped_pair: d_sync needs M + 1 = %lld 4-byte words, 4-byte aligned", (long long)(g1->M + 1));
+    return AXE_EINVAL;
+  }
+  hipStream_t st = (hipStream_t)stream;
+  if (d_sync && pair_runs_fused(g1, g2, a1, a2)) {
+    hipError_t e = launch_gemm_bf16_256_grouped_pair(a1, a2, d_sync, env_int("AXE_GROUPED_PAIR_POLLS", 1 << 20),
+                                                     env_int("AXE_GROUPED_PAIR_TEST_NEVER", 0) ? 1 : 0, st);
+    return e == hipSuccess ? AXE_OK : hip_fail(e, "axe_gemm_grouped_pair");
+  }
+  if (d_sync)                                                      // the status word answers for this call too
+    if (hipError_t e = launch_pair_sync_clear(d_sync + g1->M, 1, st); e != hipSuccess) return hip_fail(e, "axe_gemm_grouped_pair");
+  for (int i = 0; i < 2; ++i) {                                    // one after the other, on the stream
+    const axe_gemm_grouped_desc_t* g = i ? g2 : g1;
+    const GemmArgs& a = i ? a2 : a1;
+    hipError_t e = grouped_goes_to_stream(g, a) ? launch_gemm_grouped_stream(a, st)
+                   : a.fp8                      ? launch_gemm_fp8_e8m0_256_grouped(a, st)
+                                                : launch_gemm_bf16_256_grouped(a, st);
+    if (e != hipSuccess) return hip_fail(e, "axe_gemm_grouped_pair");
+  }
+  return AXE_OK;
+}
+
+int axe_gemm_grouped_pair_fused(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2) {
+  GemmArgs a1, a2;
+  if (int rc = plan_grouped_pair(g1, g2, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, a1, a2, false)) return rc;
+  return pair_runs_fused(g1, g2, a1, a2) ? 1 : 0;
+}
+
+int axe_gemm_grouped_pair_status(const int32_t* d_sync, int64_t M, void* stream) {
+  if (!d_sync || M <= 0) {
+    set_error("axe_gemm_grouped_pair_status: d_sync is NULL or M <= 0");
+    return AXE_EINVAL;
+  }
+  int32_t gave_up = 0;
+  hipError_t e = hipMemcpyAsync(&gave_up, d_sync + M, sizeof gave_up, hipMemcpyDeviceToHost, (hipStream_t)stream);
+  if (e == hipSuccess) e = hipStreamSynchronize((hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e, "axe_gemm_grouped_pair_status");
+  if (gave_up) {
+    set_error("axe_gemm_grouped_pair: %d waits for rows of the first GEMM gave up; the rows of C they cover are invalid", gave_up);
+    return AXE_ETIMEOUT;
+  }
+  return AXE_OK;
 }
 
 int axe_gemm(const axe_gemm_desc_t* g, const void* d_A, const void* d_B, void* d_C, void* stream) {

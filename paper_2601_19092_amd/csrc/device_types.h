@@ -115,4 +115,16 @@ struct GemmArgs {
   int64_t ldg;
 };
 
+// Hand-over between the two grouped GEMMs of a fused pair (the first GEMM's output is the second GEMM's A).  A row
+// block of the second GEMM may be read once every column tile of the first GEMM for those rows has been stored:
+// done[r] counts the stored column tiles of the row block whose first row is r (both GEMMs cut the groups into row
+// blocks of the same height, so the two agree on r); done[M] counts waits that gave up.  Device memory, M + 1
+// words, zero when the kernel starts.
+struct PairSync {
+  int32_t* done;
+  int32_t need;                    // column tiles of the first GEMM per row block
+  int32_t spin_limit;              // polls of done[r] before a wait gives up (the tile is then computed from what is there)
+  int64_t M;
+};
+
 }  // namespace axe

@@ -23,6 +23,12 @@ hipError_t launch_gemm_small(const GemmArgs& g, bool fp8, hipStream_t s);
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s);
 // grouped (g.group_rows, g.groups, g.ldg set; g.M = rows of all groups together, any value): N % 256 == 0, K % 64 == 0
 hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s);
+// two grouped problems, the second reading the first's output, as one launch with tile-level hand-over (Sec. 4.1,
+// fused MoE layer); sync = M + 1 words of device memory.  need_extra (tests only) raises the count a wait expects,
+// so that with a small spin_limit every wait gives up.
+hipError_t launch_pair_sync_clear(int32_t* p, int64_t n, hipStream_t s);   // p[0 .. n) = 0, by a small kernel
+hipError_t launch_gemm_bf16_256_grouped_pair(const GemmArgs& g1, const GemmArgs& g2, int32_t* sync, int spin_limit, int need_extra,
+                                             hipStream_t s);
 // dense with ragged edges through the grouped kernel (g.groups = 1, g.group_rows null): any M, N % 8 == 0, K % 64 == 0
 hipError_t launch_gemm_bf16_256_ragged(const GemmArgs& g, hipStream_t s);
 // rows of a tile of the grouped tile kernel: 128 unless the groups are large on average (the host knows M, not the
@@ -51,6 +57,23 @@ inline int cu_count() {
     cus = n;
   }
   return cus;
+}
+
+
+// Whether two planned grouped problems (the second reading what the first writes) can run as one launch: both on
+// the chained tile pipeline with the same tile height, and few enough tiles in the worst case that one workgroup per
+// compute unit holds them all (a wave keeps 64 per GEMM) -- the workgroups must all be resident for the waits to end.
+inline bool grouped_pair_fusable(const GemmArgs& g1, const GemmArgs& g2) {
+  const int cus = cu_count();
+  const int tm = grouped_tile_rows(g1.M, g1.groups, g1.tile_m);
+  if (g1.fp8 || g2.fp8 || g1.f16 != g2.f16 || g1.M != g2.M || g1.groups != g2.groups || !g1.gated || g2.gated || cus % 8) return false;
+  if (tm != grouped_tile_rows(g2.M, g2.groups, g2.tile_m)) return false;
+  for (const GemmArgs* g : {&g1, &g2}) {
+    const int nk = (int)(g->K / 64);
+    if (nk % 2 || nk < 4) return false;
+    if ((g->M / tm + g->groups) * (int64_t)g->grid_n > 64 * (int64_t)cus) return false;
+  }
+  return true;
 }
 
 }  // namespace axe

@@ -102,6 +102,12 @@ __device__ __forceinline__ uint32_t pack16(float lo, float hi) {
     return pack_bf16(lo, hi);
   }
 }
+// The workgroup's 160 KiB of LDS.  One array whoever asks: a kernel that runs two bodies one after the other
+// (the fused pair of grouped GEMMs) gives both the same blocks.
+__device__ __forceinline__ lds_u8 tile_lds() {
+  __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
+  return (lds_u8)lds_mem;
+}
 }  // namespace
 
 // NB = columns of C per tile (B rows per tile): 256, or 224 = 2 waves x 7 fragments for problems whose
@@ -137,8 +143,20 @@ __device__ __forceinline__ uint32_t pack16(float lo, float hi) {
 //
 // OUT32: C is fp32 -- the accumulators are stored as they are, a fragment at a time (a lane's 4 columns are 16
 // bytes).  Dense kernels only (with ragged edges N is then a multiple of 4).
-template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false, bool OUT32 = false>
-__device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
+//
+// PAIR: the body runs as one of the two grouped GEMMs of a fused pair (one launch; the first GEMM's C is the
+// second's A).  1 = the first: a tile is stored at device scope (write-through) and then published (every wave
+// waits for its stores, barrier, one count added to the row block's word).  2 = the second: before a tile's first
+// load may be issued -- a tile ahead, because the load side of the pipeline crosses into the next tile -- wave 0
+// polls the row block's word until all column tiles of the first GEMM are counted, acquires at device scope, and
+// a barrier lets the other waves on.  A workgroup works through its tiles of the first GEMM before any of the
+// second, all workgroups are resident at once (the host launches no more than there are compute units), and tiles
+// of the first GEMM wait for nothing: every wait ends.  Should one not (the limit on polls is reached), the wait
+// is counted in done[M] and the tile is computed from what is there: wrong rows, but every wave leaves the kernel.
+template <int NB, bool GROUPED, bool BLOCKED, bool GATED = false, bool F16 = false, int MR = 8, bool RAGGED = false, bool OUT32 = false,
+          int PAIR = 0>
+__device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const PairSync ps = PairSync{}) {
+  static_assert(PAIR == 0 || (GROUPED && !RAGGED && !OUT32), "a fused pair is made of two grouped kernels");
   static_assert(!OUT32 || ((!GROUPED || RAGGED) && NB == 256), "the fp32 output exists for the dense 256-wide kernels");
   static_assert(!RAGGED || (GROUPED && !GATED && NB == 256), "ragged edges are handled by the grouped 256-wide kernel");
   static_assert(!GATED || (GROUPED && NB == 256), "the gated epilogue exists for the grouped 256-wide kernel");
@@ -149,8 +167,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   // kt + 1 is followed by 4 B loads of its sub-step and the 4 of the next sub-step
   constexpr int kWaitStep = 8;
   constexpr int NJ = NB / 32;                                      // fragments per wave along N
-  __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
-  const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
+  const lds_u8 lds3 = tile_lds();                                  // 32-bit LDS addresses
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -224,6 +241,27 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
   int v = GROUPED ? 0 : (int)blockIdx.x;
   const int vstep = GROUPED ? 1 : (int)gridDim.x;
   if (GROUPED && table_rows(0) <= 0) return;                       // more workgroups than tiles (the host sizes the launch for the worst case)
+  // second GEMM of a pair: the rows of tile t of this workgroup have been produced (see PAIR above)
+  auto wait_rows = [&](int t) __attribute__((always_inline)) {
+    if constexpr (PAIR == 2) {
+      if (table_rows(t) <= 0) return;                              // (uniform over the workgroup: every wave holds the same table)
+      if (w == 0) {
+        const int32_t* word = ps.done + __builtin_amdgcn_readlane(tb_row0, t);
+        int polls = 0;
+        while (__hip_atomic_load(word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < ps.need) {
+          if (++polls > ps.spin_limit) {
+            if (lane == 0) __hip_atomic_fetch_add(ps.done + ps.M, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            break;
+          }
+          __builtin_amdgcn_s_sleep(8);
+        }
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+      }
+      wg_barrier();
+    }
+  };
+  wait_rows(0);
+  wait_rows(1);
   Tile cur = describe(v), nxt = describe(v + vstep);
   // K-step T of the current tile (T >= nk: step T - nk of the next one) -> K-tile
   auto kcol = [&](int T, int rot) -> int {
@@ -399,7 +437,12 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
     const auto hi = __builtin_amdgcn_permlane16_swap(pack16<F16>(h[0][2], h[0][3]), pack16<F16>(h[1][2], h[1][3]), false, false);
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 16);
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    // (first GEMM of a pair: the store is made at device scope -- it writes through this XCD's L2 to memory, where the
+    //  other XCDs' workgroups will read it, so that publishing the tile needs no write-back of the whole L2)
+    if constexpr (PAIR == 1)
+      asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen sc1" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    else
+      asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
 #pragma unroll
     for (int q = 0; q < 4; ++q)
@@ -547,9 +590,23 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g) {
         }
       }
     }
+    if constexpr (PAIR == 1) {
+      // first GEMM of a pair: publish the tile.  Its stores were made at device scope (written through to memory,
+      // see store_gated_quad); each wave waits until its own have been acknowledged -- they are asm statements the
+      // compiler does not count, so the wait is written out (it also covers the next tile's first loads: a pause
+      // of one load latency per tile) -- and after the barrier one lane counts the tile.  A device-scope release
+      // fence in place of the write-through stores also works, and is what the language offers; it writes back
+      // the XCD's whole L2 at every tile and made the pair slower than two launches (485 against 441 us on the
+      // benchmark's layer at 4096 tokens; this way 425).
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+      wg_barrier();
+      if (w == 0 && lane == 0)
+        __hip_atomic_fetch_add(ps.done + __builtin_amdgcn_readlane(tb_row0, v), 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
     v += vstep;
     if (GROUPED ? table_rows(v) <= 0 : v >= ntiles) break;
     cur = nxt;
+    wait_rows(v + vstep);
     nxt = describe(v + vstep);
   }
 }
@@ -579,6 +636,21 @@ __global__ __launch_bounds__(256, 1) void gemm_bf16_128_grouped_kernel(GemmArgs 
 __global__ __launch_bounds__(256, 1) void gemm_bf16_128_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, false, 4>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_128_grouped_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, false, true, 4>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_f16_128_grouped_gated_kernel(GemmArgs g) { gemm_bf16_256_body<256, true, true, true, true, 4>(g); }
+// the fused pair: both GEMMs of an MoE layer's expert computation in one launch (gated first GEMM, plain second)
+template <bool F16, int MR>
+__device__ __forceinline__ void grouped_pair_body(const GemmArgs& g1, const GemmArgs& g2, const PairSync& ps) {
+  gemm_bf16_256_body<256, true, true, true, F16, MR, false, false, 1>(g1, ps);
+  gemm_bf16_256_body<256, true, true, false, F16, MR, false, false, 2>(g2, ps);
+}
+__global__ __launch_bounds__(256, 1) void gemm_bf16_256_grouped_pair_kernel(GemmArgs g1, GemmArgs g2, PairSync ps) { grouped_pair_body<false, 8>(g1, g2, ps); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_256_grouped_pair_kernel(GemmArgs g1, GemmArgs g2, PairSync ps) { grouped_pair_body<true, 8>(g1, g2, ps); }
+__global__ __launch_bounds__(256, 1) void gemm_bf16_128_grouped_pair_kernel(GemmArgs g1, GemmArgs g2, PairSync ps) { grouped_pair_body<false, 4>(g1, g2, ps); }
+__global__ __launch_bounds__(256, 1) void gemm_f16_128_grouped_pair_kernel(GemmArgs g1, GemmArgs g2, PairSync ps) { grouped_pair_body<true, 4>(g1, g2, ps); }
+
+__global__ __launch_bounds__(256) void pair_sync_clear_kernel(int32_t* p, int64_t n) {
+  const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+  if (i < n) p[i] = 0;
+}
 
 hipError_t launch_gemm_bf16_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -630,6 +702,33 @@ hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s) {
     case 5: hipLaunchKernelGGL(gemm_bf16_128_grouped_gated_kernel, grid, block, 0, s, g); break;
     case 6: hipLaunchKernelGGL(gemm_f16_128_grouped_kernel, grid, block, 0, s, g); break;
     default: hipLaunchKernelGGL(gemm_f16_128_grouped_gated_kernel, grid, block, 0, s, g); break;
+  }
+  return hipGetLastError();
+}
+
+hipError_t launch_pair_sync_clear(int32_t* p, int64_t n, hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(pair_sync_clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
+  return hipGetLastError();
+}
+
+// sync: M + 1 words of device memory (cleared here, on the stream, by a small kernel: a caller may be capturing a graph)
+hipError_t launch_gemm_bf16_256_grouped_pair(const GemmArgs& g1, const GemmArgs& g2, int32_t* sync, int spin_limit, int need_extra,
+                                             hipStream_t s) {
+  if (!grouped_pair_fusable(g1, g2) || !sync) return hipErrorInvalidValue;
+  const bool t128 = grouped_tile_rows(g1.M, g1.groups, g1.tile_m) == 128;
+  if (hipError_t e = launch_pair_sync_clear(sync, g1.M + 1, s); e != hipSuccess) return e;
+  PairSync ps;
+  ps.done = sync;
+  ps.need = g1.grid_n + need_extra;
+  ps.spin_limit = spin_limit;
+  ps.M = g1.M;
+  const dim3 grid((unsigned)cu_count()), block(256);
+  switch ((t128 ? 2 : 0) + (g1.f16 ? 1 : 0)) {
+    case 0: hipLaunchKernelGGL(gemm_bf16_256_grouped_pair_kernel, grid, block, 0, s, g1, g2, ps); break;
+    case 1: hipLaunchKernelGGL(gemm_f16_256_grouped_pair_kernel, grid, block, 0, s, g1, g2, ps); break;
+    case 2: hipLaunchKernelGGL(gemm_bf16_128_grouped_pair_kernel, grid, block, 0, s, g1, g2, ps); break;
+    default: hipLaunchKernelGGL(gemm_f16_128_grouped_pair_kernel, grid, block, 0, s, g1, g2, ps); break;
   }
   return hipGetLastError();
 }

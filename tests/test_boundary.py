@@ -290,6 +290,51 @@ def test_grouped_gemm_gated_epilogue_needs_interleaved_gate_and_up():
     assert chk(desc(W.gated_b_spec(K, N, G), Cn=N, epi=B.AXE_EPI_NONE)) == B.AXE_EUNSUPPORTED
 
 
+def test_grouped_pair_checks_and_choice():
+    """axe_gemm_grouped_pair: the second problem must read exactly what the first writes; which pairs share a launch."""
+    fused = lambda a, b: B.lib().axe_gemm_grouped_pair_fused(C.byref(a.c), C.byref(b.c))
+    def pair(M=4000, K1=512, I=256, N2=512, G=8, dt=B.AXE_BF16, hint=B.AXE_GROUPED_TILES, M2=None, K2=None, G2=None, dt2=None, a2_pitch=None,
+             epi=B.AXE_EPI_SWIGLU, h_pitch=None):
+        M2, K2, G2, dt2 = M2 or M, K2 or I, G2 or G, dt2 or dt
+        N1 = 2 * I if epi == B.AXE_EPI_SWIGLU else I
+        b1 = W.gated_b_spec(K1, N1, G, True) if epi == B.AXE_EPI_SWIGLU else W.blocked_b_spec(K1, N1, G=G)
+        a2_pitch = a2_pitch or h_pitch
+        c1 = W.row_major_spec(M, I) if h_pitch is None else W.spec([(M, h_pitch, "m"), (I, 1, "m")])
+        d1 = B.GroupedGemmDesc(M, N1, K1, G, B.Layout(W.row_major_spec(M, K1)), B.Layout(b1),
+                               B.Layout(c1), M * K1, G * N1 * K1, M * (h_pitch or I), in_dtype=dt, out_dtype=dt,
+                               epilogue=epi, kernel_hint=hint)
+        a2 = W.row_major_spec(M2, K2) if a2_pitch is None else W.spec([(M2, a2_pitch, "m"), (K2, 1, "m")])
+        d2 = B.GroupedGemmDesc(M2, N2, K2, G2, B.Layout(a2), B.Layout(W.blocked_b_spec(K2, N2, G=G2)),
+                               B.Layout(W.row_major_spec(M2, N2)), M2 * (a2_pitch or K2), G2 * N2 * K2, M2 * N2, in_dtype=dt2, out_dtype=dt2,
+                               kernel_hint=hint)
+        return d1, d2
+    assert fused(*pair()) == 1
+    assert fused(*pair(dt=B.AXE_F16)) == 1
+    assert fused(*pair(hint=B.AXE_GROUPED_TILES_128)) == 1 and fused(*pair(hint=B.AXE_GROUPED_TILES_256)) == 1
+    # not one launch: the streaming kernel on either side, fewer than four or an odd number of K-steps, an ungated first
+    # problem, more tiles than one workgroup per compute unit can hold (64 each)
+    assert fused(*pair(M=32, hint=B.AXE_GROUPED_AUTO)) == 0
+    assert fused(*pair(I=128)) == 0
+    assert fused(*pair(K1=320)) == 0
+    assert fused(*pair(epi=B.AXE_EPI_NONE)) == 0
+    assert fused(*pair(h_pitch=320)) == 1 and fused(*pair(h_pitch=264)) == 0          # rows of H on 128-byte lines, or not
+    assert fused(*pair(M=256 * 2000, N2=2048, hint=B.AXE_GROUPED_TILES_128)) == 0
+    # the second problem's A is not the first problem's C
+    assert fused(*pair(M2=4096)) == B.AXE_EINVAL
+    assert fused(*pair(K2=512)) == B.AXE_EINVAL
+    assert fused(*pair(G2=4)) == B.AXE_EINVAL
+    assert fused(*pair(dt2=B.AXE_F16)) == B.AXE_EINVAL
+    assert fused(*pair(a2_pitch=264)) == B.AXE_EINVAL
+    # errors of either problem come through
+    d1, d2 = pair()
+    L = B.lib()
+    d2.c.kernel_hint = 77
+    assert fused(d1, d2) == L.axe_gemm_grouped_check(C.byref(d2.c)) == B.AXE_EINVAL
+    d1, d2 = pair()
+    assert L.axe_gemm_grouped_pair(C.byref(d1.c), C.byref(d2.c), None, None, None, None, None, None, None, 0, None) == B.AXE_EINVAL
+    assert L.axe_gemm_grouped_pair_status(None, 10, None) == B.AXE_EINVAL
+
+
 def test_grouped_gemm_fp8_goes_to_the_streaming_kernel_only():
     class Fake:
         def data_ptr(self):

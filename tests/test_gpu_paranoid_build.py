@@ -129,3 +129,35 @@ def test_fp8_grouped_tile_kernel_fast_build_equals_checking_build(gated):
             torch.cuda.synchronize()
             out.append(dC)
     assert torch.equal(out[0], out[1]), f"{(out[0] != out[1]).sum().item()} elements differ"
+
+
+@pytest.mark.parametrize("kernel", [B.AXE_GROUPED_TILES_256, B.AXE_GROUPED_TILES_128])
+def test_grouped_pair_fast_build_equals_checking_build(kernel):
+    """Both grouped GEMMs of a layer in one launch (tile-level hand-over through counters): H and C of the two builds."""
+    rng = np.random.default_rng(29)
+    off = np.concatenate([[0], np.cumsum(rng.integers(0, 400, 40))]).astype(np.int32)
+    K1, I, N2 = 512, 384, 768
+    g = W.gemm_grouped_bf16(off, 2 * I, K1, 101, std_b=2.0 * K1 ** -0.5)
+    M, G = g.M, g.G
+    w2 = W.to_bf16_bits(W.normal(102, (G, N2, I), I ** -0.5))
+    plain1, gated1 = B.Layout(W.grouped_gemm_specs(g)[1]), B.Layout(W.gated_b_spec(K1, 2 * I, G, True))
+    plain2, blocked2 = B.Layout(W.spec([(G, N2 * I, "m"), (I, 1, "m"), (N2, I, "m")])), B.Layout(W.blocked_b_spec(I, N2, G=G))
+    dA, dW1, dW2, dR = dev(g.a_mk.reshape(-1)), dev(g.b_gnk.reshape(-1)), dev(w2.reshape(-1)), torch.from_numpy(g.group_rows).cuda()
+    dW1p, dW2p = torch.empty_like(dW1), torch.empty_like(dW2)
+    B.axe_relayout(plain1, gated1, (G, K1, 2 * I), dW1, dW1p)
+    B.axe_relayout(plain2, blocked2, (G, I, N2), dW2, dW2p)
+    d1 = B.GroupedGemmDesc(M, 2 * I, K1, G, B.Layout(W.row_major_spec(M, K1)), gated1, B.Layout(W.row_major_spec(M, I)),
+                           M * K1, dW1.numel(), M * I, epilogue=B.AXE_EPI_SWIGLU, kernel_hint=kernel)
+    d2 = B.GroupedGemmDesc(M, N2, I, G, B.Layout(W.row_major_spec(M, I)), blocked2, B.Layout(W.row_major_spec(M, N2)),
+                           M * I, dW2.numel(), M * N2, kernel_hint=kernel)
+    assert B.axe_gemm_grouped_pair_fused(d1, d2)
+    out = []
+    for path in (B.LIB_PATH, PARANOID):
+        with library(path):
+            dH = torch.zeros(M * I, dtype=torch.int16, device="cuda")
+            dC = torch.zeros(M * N2, dtype=torch.int16, device="cuda")
+            sync = torch.zeros(M + 1, dtype=torch.int32, device="cuda")
+            B.axe_gemm_grouped_pair(d1, d2, dA, dW1p, dH, dW2p, dC, dR, sync)
+            B.axe_gemm_grouped_pair_status(sync, M)
+            out.append((dH, dC))
+    assert torch.equal(out[0][0], out[1][0]) and torch.equal(out[0][1], out[1][1])
