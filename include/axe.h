@@ -278,7 +278,7 @@ int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g);
  *   Every wait inside the kernel is bounded (a number of polls, AXE_GROUPED_PAIR_POLLS, default 2^20, each a few
  *   microseconds): a wait that gives up is counted in d_sync[M] and the tile is computed from what is there.
  *   axe_gemm_grouped_pair_status(d_sync, M, stream) synchronises the stream and returns AXE_ETIMEOUT if any wait of
- *   the last call gave up (rows of C are then invalid), else AXE_OK.  With all workgroups resident (the launch is
+ *   the last call gave up (rows of C are then invalid), else AXE_OK (d_sync NULL: see axe_gemm_grouped_pair_static).  With all workgroups resident (the launch is
  *   sized to the compute units of the device) no wait can fail to end: tiles of the first GEMM wait for nothing and
  *   every workgroup works through its share of them before it waits.
  *   axe_gemm_grouped_pair_fused(g1, g2): 1 if the pair would share a launch (given a workspace), 0 if not, or the
@@ -290,6 +290,19 @@ int axe_gemm_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grou
                           int32_t* d_sync, int64_t sync_elems, void* stream);
 int axe_gemm_grouped_pair_fused(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2);
 int axe_gemm_grouped_pair_status(const int32_t* d_sync, int64_t M, void* stream);
+
+/* axe_gemm_grouped_pair_static -- axe_gemm_grouped_pair for callers that cannot allocate device memory or hand a
+ * workspace through: code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * counters live in an array of the library's own (a __device__ array of 2^20 + 1 words, 4 MiB of every device the
+ * library runs on, held until the process ends); the call allocates nothing and frees nothing.  Same arguments
+ * and results as axe_gemm_grouped_pair without d_sync / sync_elems; M above 2^20 rows is AXE_EUNSUPPORTED.  All
+ * calls on one device share the array: calls that overlap in time on one device (different streams) race on it
+ * -- give such callers workspaces of their own through axe_gemm_grouped_pair.  The array keeps the last call's
+ * counts; every call clears the M + 1 words it uses, on the stream, with a small kernel.
+ * axe_gemm_grouped_pair_status(NULL, M, stream) reads the status word of the last such call on the current device. */
+int axe_gemm_grouped_pair_static(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const void* d_A,
+                                 const void* d_B1, void* d_H, const void* d_B2, void* d_C, const int32_t* d_group_rows,
+                                 void* stream);
 
 /* ---------------------------------------------------------------------------------------------
  * axe_gemm_describe -- the Axe layouts of every tile movement of the kernel axe_gemm would

@@ -25,7 +25,7 @@ AXE_EPI_NONE, AXE_EPI_SWIGLU = 0, 1
 AXE_GROUPED_AUTO, AXE_GROUPED_TILES, AXE_GROUPED_STREAM, AXE_GROUPED_TILES_256, AXE_GROUPED_TILES_128 = 0, 1, 2, 3, 4
 
 EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_grouped_pair", "axe_gemm_grouped_pair_fused",
-           "axe_gemm_grouped_pair_status", "axe_gemm_grouped_kernel", "axe_gemm_grouped_describe", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
+           "axe_gemm_grouped_pair_status", "axe_gemm_grouped_pair_static", "axe_gemm_grouped_kernel", "axe_gemm_grouped_describe", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
            "axe_last_error", "axe_version", "axe_layout_span", "axe_layout_canonicalize", "axe_layout_gap_condition",
            "axe_layout_equal", "axe_layout_group", "axe_layout_tile", "axe_layout_direct_sum", "axe_layout_tile_of",
            "axe_layout_slice"]
@@ -94,6 +94,8 @@ def load(path: str) -> C.CDLL:
     GP = C.POINTER(axe_gemm_grouped_desc_t)
     L.axe_gemm_grouped_pair.restype = C.c_int
     L.axe_gemm_grouped_pair.argtypes = [GP, GP, vp, vp, vp, vp, vp, vp, vp, i64, vp]
+    L.axe_gemm_grouped_pair_static.restype = C.c_int
+    L.axe_gemm_grouped_pair_static.argtypes = [GP, GP, vp, vp, vp, vp, vp, vp, vp]
     L.axe_gemm_grouped_pair_fused.restype = C.c_int
     L.axe_gemm_grouped_pair_fused.argtypes = [GP, GP]
     L.axe_gemm_grouped_pair_status.restype = C.c_int
@@ -285,13 +287,24 @@ def axe_gemm_grouped_pair(desc1: GroupedGemmDesc, desc2: GroupedGemmDesc, A_buf,
     return C_buf
 
 
+def axe_gemm_grouped_pair_static(desc1: GroupedGemmDesc, desc2: GroupedGemmDesc, A_buf, B1_buf, H_buf, B2_buf, C_buf, group_rows,
+                                 stream=None):
+    """axe_gemm_grouped_pair on the library's own workspace (nothing is allocated; calls on one device must not overlap)."""
+    assert all(t.is_cuda for t in (A_buf, B1_buf, H_buf, B2_buf, C_buf, group_rows))
+    assert str(group_rows.dtype) == "torch.int32" and group_rows.numel() == desc1.c.G + 1 and group_rows.is_contiguous()
+    _check(lib().axe_gemm_grouped_pair_static(C.byref(desc1.c), C.byref(desc2.c), A_buf.data_ptr(), B1_buf.data_ptr(), H_buf.data_ptr(),
+                                              B2_buf.data_ptr(), C_buf.data_ptr(), group_rows.data_ptr(), _stream_ptr(stream)))
+    return C_buf
+
+
 def axe_gemm_grouped_pair_fused(desc1: GroupedGemmDesc, desc2: GroupedGemmDesc) -> bool:
     return _flag(lib().axe_gemm_grouped_pair_fused(C.byref(desc1.c), C.byref(desc2.c)))
 
 
 def axe_gemm_grouped_pair_status(sync, M: int, stream=None) -> None:
-    """Synchronises the stream; raises if a wait inside the last fused launch that used `sync` gave up."""
-    _check(lib().axe_gemm_grouped_pair_status(sync.data_ptr(), M, _stream_ptr(stream)))
+    """Synchronises the stream; raises if a wait inside the last fused launch that used `sync` gave up
+    (sync None: the library's own workspace on the current device)."""
+    _check(lib().axe_gemm_grouped_pair_status(sync.data_ptr() if sync is not None else None, M, _stream_ptr(stream)))
 
 
 def axe_gemm_grouped_check(desc: GroupedGemmDesc) -> None:

@@ -1014,6 +1014,18 @@ int axe_gemm_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grou
   return AXE_OK;
 }
 
+int axe_gemm_grouped_pair_static(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const void* d_A,
+                                 const void* d_B1, void* d_H, const void* d_B2, void* d_C, const int32_t* d_group_rows, void* stream) {
+  if (g1 && g1->M > kPairStaticRows) {
+    set_error("axe_gemm_grouped_pair_static: M = %lld rows, the library's workspace serves at most %lld (use axe_gemm_grouped_pair "
+              "with a workspace of your own)", (long long)g1->M, (long long)kPairStaticRows);
+    return AXE_EUNSUPPORTED;
+  }
+  int32_t* ws = nullptr;
+  if (hipError_t e = pair_static_workspace(&ws); e != hipSuccess) return hip_fail(e, "axe_gemm_grouped_pair_static");
+  return axe_gemm_grouped_pair(g1, g2, d_A, d_B1, d_H, d_B2, d_C, d_group_rows, ws, kPairStaticRows + 1, stream);
+}
+
 int axe_gemm_grouped_pair_fused(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2) {
   GemmArgs a1, a2;
   if (int rc = plan_grouped_pair(g1, g2, nullptr, nullptr, nullptr, nullptr, nullptr, nullptr, a1, a2, false)) return rc;
@@ -1021,9 +1033,14 @@ int axe_gemm_grouped_pair_fused(const axe_gemm_grouped_desc_t* g1, const axe_gem
 }
 
 int axe_gemm_grouped_pair_status(const int32_t* d_sync, int64_t M, void* stream) {
-  if (!d_sync || M <= 0) {
-    set_error("axe_gemm_grouped_pair_status: d_sync is NULL or M <= 0");
+  if (M <= 0 || (!d_sync && M > kPairStaticRows)) {
+    set_error("axe_gemm_grouped_pair_status: M must be positive (and within the library's workspace when d_sync is NULL)");
     return AXE_EINVAL;
+  }
+  if (!d_sync) {                                                   // the library's own workspace on the current device
+    int32_t* ws = nullptr;
+    if (hipError_t e = pair_static_workspace(&ws); e != hipSuccess) return hip_fail(e, "axe_gemm_grouped_pair_status");
+    d_sync = ws;
   }
   int32_t gave_up = 0;
   hipError_t e = hipMemcpyAsync(&gave_up, d_sync + M, sizeof gave_up, hipMemcpyDeviceToHost, (hipStream_t)stream);

@@ -211,6 +211,7 @@ hipError_t launch_gemm_bf16_256(const GemmArgs&, hipStream_t) { return hipErrorN
 hipError_t launch_gemm_bf16_256_grouped(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_gemm_bf16_256_ragged(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_pair_sync_clear(int32_t*, int64_t, hipStream_t) { return hipErrorNotSupported; }
+hipError_t pair_static_workspace(int32_t**) { return hipErrorNotSupported; }
 hipError_t launch_gemm_bf16_256_grouped_pair(const GemmArgs&, const GemmArgs&, int32_t*, int, int, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_gemm_grouped_stream(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }
 hipError_t launch_gemm_fp8_256(const GemmArgs&, hipStream_t) { return hipErrorNotSupported; }

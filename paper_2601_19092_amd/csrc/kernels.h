@@ -26,6 +26,9 @@ hipError_t launch_gemm_bf16_256_grouped(const GemmArgs& g, hipStream_t s);
 // two grouped problems, the second reading the first's output, as one launch with tile-level hand-over (Sec. 4.1,
 // fused MoE layer); sync = M + 1 words of device memory.  need_extra (tests only) raises the count a wait expects,
 // so that with a small spin_limit every wait gives up.
+// rows the library's own pair workspace serves, and its address on the current device (no allocation: a __device__ array)
+constexpr int64_t kPairStaticRows = int64_t(1) << 20;
+hipError_t pair_static_workspace(int32_t** out);
 hipError_t launch_pair_sync_clear(int32_t* p, int64_t n, hipStream_t s);   // p[0 .. n) = 0, by a small kernel
 hipError_t launch_gemm_bf16_256_grouped_pair(const GemmArgs& g1, const GemmArgs& g2, int32_t* sync, int spin_limit, int need_extra,
                                              hipStream_t s);

@@ -59,6 +59,7 @@
 #include <stdlib.h>
 
 #include <algorithm>
+#include <mutex>
 #include <type_traits>
 
 #include "device_types.h"
@@ -710,6 +711,29 @@ hipError_t launch_pair_sync_clear(int32_t* p, int64_t n, hipStream_t s) {
   if (n <= 0) return hipSuccess;
   hipLaunchKernelGGL(pair_sync_clear_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, s, p, n);
   return hipGetLastError();
+}
+
+// The library's own workspace for callers that may not allocate (axe_gemm_grouped_pair_static): the counters of
+// PairSync for up to kPairStaticRows rows, 4 MiB + 4 bytes of every device the library runs on, held until the
+// process ends.  The array's name is only a handle on the host: its address on the current device is asked for
+// once per device and kept.
+static __device__ __align__(256) int32_t pair_scratch[kPairStaticRows + 1];
+
+hipError_t pair_static_workspace(int32_t** out) {
+  constexpr int kMaxDevices = 64;
+  static std::mutex mu;
+  static int32_t* ptr[kMaxDevices] = {};
+  int dev = -1;
+  if (hipError_t e = hipGetDevice(&dev); e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptr[dev]) {
+    void* p = nullptr;
+    if (hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(pair_scratch)); e != hipSuccess) return e;
+    ptr[dev] = (int32_t*)p;
+  }
+  *out = ptr[dev];
+  return hipSuccess;
 }
 
 // sync: M + 1 words of device memory (cleared here, on the stream, by a small kernel: a caller may be capturing a graph)

@@ -332,7 +332,10 @@ def test_grouped_pair_checks_and_choice():
     assert fused(d1, d2) == L.axe_gemm_grouped_check(C.byref(d2.c)) == B.AXE_EINVAL
     d1, d2 = pair()
     assert L.axe_gemm_grouped_pair(C.byref(d1.c), C.byref(d2.c), None, None, None, None, None, None, None, 0, None) == B.AXE_EINVAL
-    assert L.axe_gemm_grouped_pair_status(None, 10, None) == B.AXE_EINVAL
+    assert L.axe_gemm_grouped_pair_status(None, 0, None) == B.AXE_EINVAL
+    assert L.axe_gemm_grouped_pair_status(None, (1 << 20) + 1, None) == B.AXE_EINVAL     # beyond the library's own workspace
+    big = pair(M=(1 << 20) + 8)
+    assert L.axe_gemm_grouped_pair_static(C.byref(big[0].c), C.byref(big[1].c), None, None, None, None, None, None, None) == B.AXE_EUNSUPPORTED
 
 
 def test_grouped_gemm_fp8_goes_to_the_streaming_kernel_only():
