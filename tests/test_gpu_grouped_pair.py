@@ -228,3 +228,48 @@ def test_pair_falls_back_to_two_launches():
     h_ref, c_ref = L.oracle()
     check_blocks(L.off, decode(h_raw, "bf16"), h_raw, h_ref, TOL["bf16"], "H")
     check_blocks(L.off, decode(c_raw, "bf16"), c_raw, c_ref, TOL["bf16"], "C")
+
+
+def test_pair_can_be_captured_in_a_hip_graph():
+    """A serving loop records the layer once and replays it: the fused pair (on a caller's workspace and on the
+    library's own) clears its counters with a kernel, allocates nothing and never synchronises.  Every replay, with
+    eager work and synchronisations in between and other group sizes in the same buffers, must equal the eager result."""
+    hidden, inter, out = 512, 256, 512
+    offs = [[0, 300, 520, 1300, 1301, 2000], [0, 64, 900, 901, 1200, 2000]]
+    Ls = [Layer(o, hidden, inter, out, 550, "bf16") for o in offs]
+    want = [run_pair(L, B.AXE_GROUPED_TILES_128, fused=False)[:2] for L in Ls]
+    d1, d2 = Ls[0].descs(B.AXE_GROUPED_TILES_128)
+    M = Ls[0].M
+    dA, dW1, dW2, dR = Ls[0].device()
+    rows = [torch.from_numpy(L.off).cuda() for L in Ls]
+    dH = torch.zeros(M * inter, dtype=torch.int16, device="cuda")
+    dC = torch.zeros(M * out, dtype=torch.int16, device="cuda")
+    dH2, dC2 = torch.zeros_like(dH), torch.zeros_like(dC)
+    sync = torch.zeros(M + 1, dtype=torch.int32, device="cuda")
+
+    def layer_twice():
+        B.axe_gemm_grouped_pair(d1, d2, dA, dW1, dH, dW2, dC, dR, sync)
+        B.axe_gemm_grouped_pair_static(d1, d2, dA, dW1, dH2, dW2, dC2, dR)
+
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):                                   # warm-up on the capture stream (also takes the array's address)
+        layer_twice()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        layer_twice()
+    for rep in range(3):
+        for k in (0, 1):
+            dR.copy_(rows[k])
+            for t in (dH, dC, dH2, dC2):
+                t.fill_(SENTINEL)
+            torch.randn(1 << 20, device="cuda").sum().item()        # eager work and a synchronisation between replays
+            graph.replay()
+            torch.cuda.synchronize()
+            B.axe_gemm_grouped_pair_status(sync, M)
+            B.axe_gemm_grouped_pair_status(None, M)
+            for h, c in ((dH, dC), (dH2, dC2)):
+                assert np.array_equal(h.cpu().numpy().view(np.uint16).reshape(M, inter), want[k][0]), (rep, k)
+                assert np.array_equal(c.cpu().numpy().view(np.uint16).reshape(M, out), want[k][1]), (rep, k)
