@@ -369,6 +369,13 @@ int axe_gemm_grouped_describe(const axe_gemm_grouped_desc_t* g, int32_t which, a
  *                            2 * rank entries.  B may carry a swizzle stage if everything A adds on the
  *                            swizzled axis is a multiple of 2^(shift + bits) (else AXE_EUNSUPPORTED).
  *   axe_layout_direct_sum    App. F: as tile, without the span scaling: f(x || y) = f_A(x) + f_B(y).
+ *   axe_layout_flatten       the layout on the single axis `to_axis` that L becomes when a coordinate c on axis a is
+ *                            stored at sum_a c[a] * pitch[a] (pitch: n_axes entries): every iter (e, s @ a) of D and R
+ *                            becomes (e, s * pitch[a] @ to_axis) (Def. 2.1), the offsets add up.  It turns a
+ *                            thread-distributed layout (axes wave, lane, reg; Sec. 2.2) into the memory image
+ *                            [wave][lane][reg] that axe_relayout can write: a register layout as relayout target.
+ *                            Pitch 0 is allowed for axes that carry no iter of extent > 1; a swizzled L is
+ *                            AXE_EUNSUPPORTED.
  *   axe_layout_tile_of       Alg. 3: decides A = C (x) B and recovers C; shape_out = SA / SB (rank entries).
  *   axe_layout_slice         Alg. 4: a layout admitting `size` with f(u) = f_{L<shape>}(begin + u); per
  *                            block the greedy peel, then the no-wrap or the symmetric one-wrap form.
@@ -384,6 +391,8 @@ int axe_layout_tile(const axe_layout_t* A, int32_t rank, const int64_t* SA, cons
                     axe_layout_t* out, int64_t* shape_out, void* arena, size_t arena_bytes);
 int axe_layout_direct_sum(const axe_layout_t* A, int32_t rank, const int64_t* SA, const axe_layout_t* B,
                           const int64_t* SB, axe_layout_t* out, int64_t* shape_out, void* arena, size_t arena_bytes);
+int axe_layout_flatten(const axe_layout_t* L, const int64_t* pitch, int32_t to_axis, axe_layout_t* out, void* arena,
+                       size_t arena_bytes);
 int axe_layout_tile_of(const axe_layout_t* A, int32_t rank, const int64_t* SA, const axe_layout_t* B, const int64_t* SB,
                        axe_layout_t* out, int64_t* shape_out, void* arena, size_t arena_bytes);
 int axe_layout_slice(const axe_layout_t* L, int32_t rank, const int64_t* shape, const int64_t* begin,

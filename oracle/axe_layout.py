@@ -513,6 +513,26 @@ def scale_D(A: Layout, W: Dict[str, int]) -> Layout:
     return A.with_(D=[Iter(it.extent, it.stride * W.get(it.axis, 1), it.axis) for it in A.D])
 
 
+def flatten_axes(L: Layout, pitch: Dict[str, int], to_axis: str) -> Layout:
+    """The layout on the single axis `to_axis` that L becomes when a coordinate c on axis a is stored at
+    sum_a c[a] * pitch[a] -- how a thread-distributed layout (axes wave, lane, reg: Sec. 2.2) is laid out in a
+    linear memory, [wave][lane][reg] say.  By Def. 2.1 an iter contributes x * stride on its axis, so every iter
+    (e, s @ a) of D and R becomes (e, s * pitch[a] @ to_axis) and the offsets add up: f_flat(x) = sum_a pitch[a] f_L(x)[a]
+    for every replica.  Not defined for a swizzled L (the stage acts on one axis' coordinate, not on the sum)."""
+    if L.swizzle is not None:
+        raise LayoutError("flatten_axes is defined on (D, R, O)")
+    def conv(it: Iter) -> Iter:
+        if it.axis not in pitch or (pitch[it.axis] == 0 and it.extent > 1):
+            raise LayoutError(f"no pitch for axis {it.axis}")
+        return Iter(it.extent, it.stride * pitch[it.axis] if pitch[it.axis] else it.stride, to_axis)
+    off = 0
+    for a, v in L.O:
+        if a not in pitch:
+            raise LayoutError(f"no pitch for axis {a}")
+        off += v * pitch[a]
+    return Layout(tuple(conv(i) for i in L.D), tuple(conv(i) for i in L.R), _norm_offset({to_axis: off}))
+
+
 def tile_of(A: Layout, SA: Sequence[int], B: Layout, SB: Sequence[int]) -> Tuple[Layout, Tuple[int, ...]]:
     """Decide A = C (x) B and return (C, S_C) with S_C = SA / SB; LayoutError otherwise.
     R of A must be empty or equal to R of B (the general Minkowski decomposition of a

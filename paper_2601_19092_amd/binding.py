@@ -27,7 +27,7 @@ AXE_GROUPED_AUTO, AXE_GROUPED_TILES, AXE_GROUPED_STREAM, AXE_GROUPED_TILES_256, 
 EXPORTS = ["axe_layout_eval", "axe_relayout", "axe_gemm", "axe_gemm_grouped", "axe_gemm_grouped_check", "axe_gemm_grouped_pair", "axe_gemm_grouped_pair_fused",
            "axe_gemm_grouped_pair_status", "axe_gemm_grouped_pair_static", "axe_gemm_grouped_kernel", "axe_gemm_grouped_describe", "axe_gemm_tile", "axe_gemm_describe", "axe_strerror",
            "axe_last_error", "axe_version", "axe_layout_span", "axe_layout_canonicalize", "axe_layout_gap_condition",
-           "axe_layout_equal", "axe_layout_group", "axe_layout_tile", "axe_layout_direct_sum", "axe_layout_tile_of",
+           "axe_layout_equal", "axe_layout_group", "axe_layout_tile", "axe_layout_direct_sum", "axe_layout_flatten", "axe_layout_tile_of",
            "axe_layout_slice"]
 
 
@@ -115,6 +115,7 @@ def load(path: str) -> C.CDLL:
                        ("axe_layout_group", [LP, i32, P64, LP, P32, vp, sz]),
                        ("axe_layout_tile", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
                        ("axe_layout_direct_sum", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
+                       ("axe_layout_flatten", [LP, P64, i32, LP, vp, sz]),
                        ("axe_layout_tile_of", [LP, i32, P64, LP, P64, LP, P64, vp, sz]),
                        ("axe_layout_slice", [LP, i32, P64, P64, P64, LP, vp, sz])):
         getattr(L, name).restype = C.c_int
@@ -412,6 +413,14 @@ def layout_tile(A: Layout, SA: Sequence[int], B: Layout, SB: Sequence[int]) -> T
 
 def layout_direct_sum(A: Layout, SA: Sequence[int], B: Layout, SB: Sequence[int]) -> Tuple[dict, Tuple[int, ...]]:
     return _binary(lib().axe_layout_direct_sum, A, SA, B, SB, 2 * len(SA))
+
+
+def layout_flatten(L: Layout, pitch: Dict[str, int], to_axis: str) -> dict:
+    """All axes of L folded onto `to_axis`: coordinate c on axis a goes to c * pitch[a] (axes not named: pitch 0)."""
+    out, arena = axe_layout_t(), C.create_string_buffer(2048)
+    p = (C.c_int64 * len(L.axes))(*[int(pitch.get(a, 0)) for a in L.axes])
+    _check(lib().axe_layout_flatten(C.byref(L.c), p, L.axis(to_axis), C.byref(out), arena, len(arena)))
+    return _spec_of(out, L.axes)
 
 
 def layout_tile_of(A: Layout, SA: Sequence[int], B: Layout, SB: Sequence[int]) -> Tuple[dict, Tuple[int, ...]]:

@@ -407,6 +407,39 @@ int axe_layout_direct_sum(const axe_layout_t* A, int32_t rank, const int64_t* SA
   return combine(A, rank, SA, B, SB, false, out, shape_out, arena, arena_bytes, "axe_layout_direct_sum");
 }
 
+int axe_layout_flatten(const axe_layout_t* L, const int64_t* pitch, int32_t to_axis, axe_layout_t* out, void* arena,
+                       size_t arena_bytes) {
+  const char* what = "axe_layout_flatten";
+  HLayout h;
+  if (int rc = load_layout(L, h, what)) return rc;
+  if (!pitch || !out || to_axis < 0 || to_axis >= h.n_axes) {
+    set_error("%s: NULL argument or to_axis out of range", what);
+    return AXE_EINVAL;
+  }
+  if (int rc = no_swizzle(h, what)) return rc;
+  auto move = [&](HIter& it) -> int {
+    if (pitch[it.axis] == 0 && it.e > 1) {
+      set_error("%s: pitch 0 for axis %d, which carries an iter of extent %lld", what, it.axis, (long long)it.e);
+      return AXE_EINVAL;
+    }
+    if (pitch[it.axis] && !mul_ok(it.s, pitch[it.axis], &it.s)) return overflow(what);
+    it.axis = to_axis;
+    return AXE_OK;
+  };
+  for (HIter& it : h.D)
+    if (int rc = move(it)) return rc;
+  for (HIter& it : h.R)
+    if (int rc = move(it)) return rc;
+  int64_t off = 0;
+  for (int a = 0; a < h.n_axes; ++a) {
+    int64_t t;
+    if (!mul_ok(h.off[a], pitch[a], &t) || !add_ok(off, t, &off)) return overflow(what);
+    h.off[a] = 0;
+  }
+  h.off[to_axis] = off;
+  return emit(h, L, out, arena, arena_bytes, what);
+}
+
 int axe_layout_tile_of(const axe_layout_t* A, int32_t rank, const int64_t* SA, const axe_layout_t* B, const int64_t* SB,
                        axe_layout_t* out, int64_t* shape_out, void* arena, size_t arena_bytes) {
   const char* what = "axe_layout_tile_of";

@@ -285,6 +285,51 @@ def test_relayout_transposing_path_element_by_element(eb):
             assert back.tobytes() == wb.tobytes(), (shape, "back")
 
 
+def operand_image_layouts(M, K, which=None):
+    """(source spec, destination spec, 4-D shape, destination elements, axes): a row-major (M, K) bf16 matrix, and the
+    memory image [tile][wave][lane][reg] of the MFMA operand registers of the 256 x 256 kernel -- the operand layout
+    axe_gemm_describe reports for one (256, 64) tile, tiled over the matrix (axe_layout_tile) and folded onto the
+    memory axis (axe_layout_flatten)."""
+    which = B.AXE_DESC_A_OPERAND if which is None else which
+    desc = B.GemmDesc(M, 256, K, B.AXE_BF16, B.AXE_BF16, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, 256)),
+                      B.Layout(W.row_major_spec(M, 256)), M * K, 256 * K, M * 256, tile_hint=B.AXE_TILE_256x256x64)
+    spec, tshape = B.axe_gemm_describe(desc, which)
+    assert tshape == (256, 64)
+    axes = ["m", "lds", "wg", "wave", "lane", "reg"]
+    op = B.Layout(spec, axes)
+    gm, gk = M // 256, K // 64
+    grid = B.Layout(W.spec([(gm, gk, "wg"), (gk, 1, "wg")]), axes)
+    tiled, shape = B.layout_tile(grid, (gm, gk), op, tshape)
+    span = B.layout_span(B.Layout(tiled, axes))
+    regs, lanes, waves = span["reg"], span["lane"], span["wave"]
+    assert (lanes, waves) == (64, 4)
+    pitch = {"reg": 1, "lane": regs, "wave": lanes * regs, "wg": waves * lanes * regs}
+    dst = B.layout_flatten(B.Layout(tiled, axes), pitch, "m")
+    src = W.spec([(gm, 256 * K, "m"), (256, K, "m"), (gk, 64, "m"), (64, 1, "m")])
+    return src, dst, shape, gm * gk * waves * lanes * regs, axes
+
+
+def test_relayout_into_the_mfma_operand_register_order():
+    """A register layout as the target of a relayout (Sec. 3.2: copy between layouts of different scopes; thread axes
+    of Sec. 2.2): the rows of A in the order the lanes of the 256 x 256 kernel hold them, each wave's copy written
+    (the layout is replicated over the wave columns).  Checked against the oracle's relayout of the same two layouts."""
+    M, K = 768, 320
+    src_spec, dst_spec, shape, n_dst, axes = operand_image_layouts(M, K)
+    assert shape == (M // 256, 256, K // 64, 64)
+    words = W.to_bf16_bits(W.normal(131, (M, K))).reshape(-1)
+    want = np.full(n_dst, 0xA5A5, dtype=np.uint16)
+    R.relayout_ref(Layout.from_spec(src_spec), Layout.from_spec(dst_spec), shape, words, want)
+    assert not (want == 0xA5A5).all() and n_dst == 2 * M * K              # two wave columns: every element lands twice
+    d_dst = torch.full((n_dst,), -23131, dtype=torch.int16, device="cuda")          # 0xA5A5
+    B.axe_relayout(B.Layout(src_spec, axes), B.Layout(dst_spec, axes), shape, dev(words), d_dst)
+    got = host_words(d_dst, np.uint16)
+    assert np.array_equal(got, want)
+    # every 16-byte chunk of the image is an aligned run of 8 consecutive k of one row of A: a lane fetches its operand
+    # fragment from this image with one 16-byte load
+    void = np.dtype((np.void, 16))
+    assert np.isin(got.reshape(-1, 8).view(void).ravel(), words.reshape(-1, 8).view(void).ravel()).all()
+
+
 @pytest.mark.parametrize("rows,cols,dtype", [(8192, 8192, np.uint16), (4096, 12288, np.uint16), (8192, 8192, np.uint32)])
 def test_relayout_transpose_full_size(rows, cols, dtype):
     """Row-major -> column-major of a matrix of the workload's size against the definition written with

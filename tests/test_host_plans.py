@@ -337,3 +337,41 @@ def test_gemm_plan_is_reused_only_for_an_identical_descriptor(hc):
     assert call(good, pa=0x10001) == B.AXE_EINVAL                           # pointer checks run on a reused plan as well
     assert call(good, pc=0x10000) == B.AXE_EINVAL                           # C overlaps A
     assert call(good) == B.AXE_EHIP
+
+
+def test_plan_relayout_into_a_register_layout_image(hc):
+    """Destination = the MFMA operand layout of the 256 x 256 kernel (as axe_gemm_describe reports it), tiled over the
+    matrix and folded onto memory [tile][wave][lane][reg] by the layout operators; source row-major.  The plan the host
+    makes for it (16-byte units, a replicated destination) is executed on host memory against the oracle."""
+    M, K = 512, 192
+    desc = B.GemmDesc(M, 256, K, B.AXE_BF16, B.AXE_BF16, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, 256)),
+                      B.Layout(W.row_major_spec(M, 256)), M * K, 256 * K, M * 256, tile_hint=B.AXE_TILE_256x256x64)
+    axes = ["m", "lds", "wg", "wave", "lane", "reg"]
+    for which in (B.AXE_DESC_A_OPERAND, B.AXE_DESC_B_OPERAND):
+        spec, tshape = B.axe_gemm_describe(desc, which)
+        rows = M if which == B.AXE_DESC_A_OPERAND else 256
+        # B's tile is (k, n): the matrix image B[n][k] is row-major in n, so its logical (k, n) view has strides (1, K)
+        gr, gk = rows // 256, K // 64
+        if which == B.AXE_DESC_A_OPERAND:
+            grid, gshape = W.spec([(gr, gk, "wg"), (gk, 1, "wg")]), (gr, gk)
+            src = W.spec([(gr, 256 * K, "m"), (256, K, "m"), (gk, 64, "m"), (64, 1, "m")])
+        else:
+            grid, gshape = W.spec([(gk, 1, "wg"), (gr, gk, "wg")]), (gk, gr)
+            src = W.spec([(gk, 64, "m"), (64, 1, "m"), (gr, 256 * K, "m"), (256, K, "m")])
+        tiled, shape = B.layout_tile(B.Layout(grid, axes), gshape, B.Layout(spec, axes), tshape)
+        span = B.layout_span(B.Layout(tiled, axes))
+        regs = span["reg"]
+        pitch = {"reg": 1, "lane": regs, "wave": 64 * regs, "wg": span["wave"] * 64 * regs}
+        dst = B.layout_flatten(B.Layout(tiled, axes), pitch, "m")
+        n_dst = gr * gk * span["wave"] * 64 * regs
+        words = np.random.default_rng(7).integers(0, 1 << 16, rows * K, dtype=np.uint16)
+        want = np.full(n_dst, 0xA5A5, dtype=np.uint16)
+        R.relayout_ref(Layout.from_spec(src), Layout.from_spec(dst), shape, words, want)
+        got = np.full(n_dst, 0xA5A5, dtype=np.uint16)
+        ls, ld = B.Layout(src, axes), B.Layout(dst, axes)
+        hc.axe_hostcheck_set_buffers(words.nbytes, got.nbytes)
+        rc = hc.axe_relayout(C.byref(ls.c), C.byref(ld.c), len(shape), (C.c_int64 * len(shape))(*shape), 2, 0, words.ctypes.data,
+                             words.size, got.ctypes.data, got.size, None)
+        assert rc == 0, hc.axe_last_error().decode()
+        assert hc.axe_hostcheck_violations() == 0 and np.array_equal(got, want), which
+        assert n_dst == 2 * rows * K                               # each operand is replicated over the other wave dimension

@@ -336,3 +336,58 @@ def test_errors_are_codes_not_crashes():
     with pytest.raises(B.AxeError) as e:                                         # 24 iters do not fit a layout
         B.layout_tile(lib(big), (2 ** 12,), lib(big), (2 ** 12,))
     assert e.value.code == B.AXE_ERANGE
+
+
+# ----------------------------------------------------------------------------- flatten (a thread-distributed layout as a memory image)
+def test_flatten_is_the_weighted_sum_of_the_coordinates():
+    """Oracle pinned to the definition by brute force: every replica of every point of flatten_axes(L) is
+    sum_a pitch[a] * (coordinate of L on axis a); then the library against the oracle, as maps."""
+    rng = random.Random(41)
+    for _ in range(200):
+        L = rand_layout(rng)
+        pitch = {a: rng.choice([1, 2, 7, 64, 1000, -3]) for a in AXES}
+        to = rng.choice(AXES)
+        F = ax.flatten_axes(L, pitch, to)
+        k = AXES.index(to)
+        for x in range(L.E_D):
+            want = sorted(sum(pitch[a] * c[i] for i, a in enumerate(AXES)) for c in ax.evaluate(L, x, AXES))
+            got = sorted(c[k] for c in ax.evaluate(F, x, AXES))
+            assert got == want
+            assert all(c[i] == 0 for c in ax.evaluate(F, x, AXES) for i in range(len(AXES)) if i != k)
+        got = orc(B.layout_flatten(lib(L), pitch, to))
+        assert fmap(got) == fmap(F)
+
+
+def test_flatten_the_tensor_core_tile_of_the_paper_into_warp_lane_reg_memory():
+    """Sec. 2.2's 8 x 16 tensor-core tile on (lane, warp, reg) with its replication and offset, written to memory as
+    [warp][lane][reg] (32 lanes, 2 registers): the two replicas of the 128 elements fill exactly the 64-element
+    images of the four warps the paper lists, each address once."""
+    g = GOLDEN["tensor_core_tile"]
+    axes = ["m", "lane", "warp", "reg"]
+    L = Layout.make(tuple(g["D"]["extents"]), tuple(g["D"]["strides"]), R=(tuple(g["R"]["extents"]), tuple(g["R"]["strides"])), O=g["O"])
+    per_warp = g["lanes"] * g["regs"]
+    pitch = {"warp": per_warp, "lane": g["regs"], "reg": 1, "m": 1}
+    F = ax.flatten_axes(L, pitch, "m")
+    n = prod(g["shape"])
+    addrs = sorted(c[0] for x in range(n) for c in ax.evaluate(F, x, axes))
+    assert addrs == sorted(per_warp * w + t for w in g["warps_with_offset"] for t in range(per_warp))
+    for x in range(n):                                            # and point by point, the definition
+        for c, f in zip(sorted(ax.evaluate(L, x, axes)), sorted(ax.evaluate(F, x, axes))):
+            assert f == (per_warp * c[2] + g["regs"] * c[1] + c[3], 0, 0, 0)
+    got = Layout.from_spec(B.layout_flatten(B.Layout(spec_of(L), axes), pitch, "m"))
+    assert all(sorted(ax.evaluate(got, x, axes)) == sorted(ax.evaluate(F, x, axes)) for x in range(n))
+
+
+def test_flatten_refusals():
+    L = Layout.make((4, 8), ("1@lane", "1@reg"))
+    with pytest.raises(B.AxeError) as e:
+        B.layout_flatten(lib(L), {"lane": 8}, "m")                 # axis reg carries an iter and has no pitch
+    assert e.value.code == B.AXE_EINVAL
+    with pytest.raises(LayoutError):
+        ax.flatten_axes(L, {"lane": 8}, "m")
+    sw = Layout.make((4, 8), ("8@m", "1@m")).with_(swizzle=ax.Swizzle("m", 2, 0, 3))
+    with pytest.raises(B.AxeError) as e:
+        B.layout_flatten(lib(sw), {"m": 1}, "m")
+    assert e.value.code == B.AXE_EUNSUPPORTED
+    with pytest.raises(LayoutError):
+        ax.flatten_axes(sw, {"m": 1}, "m")
