@@ -283,8 +283,8 @@ int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g);
  *   every workgroup works through its share of them before it waits.
  *   axe_gemm_grouped_pair_fused(g1, g2): 1 if the pair would share a launch (given a workspace), 0 if not, or the
  *   error axe_gemm_grouped_pair would return (host only).
- * Errors: those of axe_gemm_grouped for either problem; AXE_EINVAL when g2's A is not g1's C or the workspace is
- * too small. */
+ * Errors: those of axe_gemm_grouped for either problem; AXE_EINVAL when g2's A is not g1's C, when H or C overlaps
+ * the other or an input of either problem, or when the workspace is too small or overlaps an operand. */
 int axe_gemm_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const void* d_A,
                           const void* d_B1, void* d_H, const void* d_B2, void* d_C, const int32_t* d_group_rows,
                           int32_t* d_sync, int64_t sync_elems, void* stream);

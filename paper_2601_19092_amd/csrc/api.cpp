@@ -975,6 +975,23 @@ int plan_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_
               "columns of C1", fn);
     return AXE_EINVAL;
   }
+  if (need_ptrs) {
+    // in one launch tiles of the second problem are stored while tiles of the first still read their inputs: the
+    // outputs (H, C) must be disjoint from each other and from every input of either problem
+    const int eb1 = g1->in_dtype == AXE_FP8_E4M3 ? 1 : 2, eb2 = g2->in_dtype == AXE_FP8_E4M3 ? 1 : 2;
+    struct Span { const char* lo; int64_t bytes; };
+    const Span in[] = {{(const char*)dA, g1->a_elems * eb1}, {(const char*)dB1, g1->b_elems * eb1}, {(const char*)dB2, g2->b_elems * eb2},
+                       {(const char*)rows, (int64_t)(g1->G + 1) * 4}};
+    const Span outp[] = {{(const char*)dH, g1->c_elems * 2}, {(const char*)dC, g2->c_elems * 2}};
+    auto meet = [](const Span& a, const Span& b) { return a.lo < b.lo + b.bytes && b.lo < a.lo + a.bytes; };
+    bool bad = meet(outp[0], outp[1]);
+    for (const Span& i : in)
+      for (const Span& o : outp) bad = bad || meet(i, o);
+    if (bad) {
+      set_error("%s: H and C must be disjoint from each other and from A, B1, B2 and group_rows", fn);
+      return AXE_EINVAL;
+    }
+  }
   return AXE_OK;
 }
 
@@ -994,6 +1011,17 @@ int axe_gemm_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grou
   if (d_sync && (sync_elems < g1->M + 1 || ((uintptr_t)d_sync & 3))) {
     set_error("axe_gemm_grouped_pair: d_sync needs M + 1 = %lld 4-byte words, 4-byte aligned", (long long)(g1->M + 1));
     return AXE_EINVAL;
+  }
+  if (d_sync) {
+    const char* s0 = (const char*)d_sync;
+    const char* s1 = s0 + (g1->M + 1) * 4;
+    auto meets = [&](const void* p, int64_t bytes) { return (const char*)p < s1 && s0 < (const char*)p + bytes; };
+    const int eb1 = g1->in_dtype == AXE_FP8_E4M3 ? 1 : 2, eb2 = g2->in_dtype == AXE_FP8_E4M3 ? 1 : 2;
+    if (meets(d_A, g1->a_elems * eb1) || meets(d_B1, g1->b_elems * eb1) || meets(d_B2, g2->b_elems * eb2) || meets(d_H, g1->c_elems * 2) ||
+        meets(d_C, g2->c_elems * 2) || meets(d_group_rows, (int64_t)(g1->G + 1) * 4)) {
+      set_error("axe_gemm_grouped_pair: d_sync overlaps an operand");
+      return AXE_EINVAL;
+    }
   }
   hipStream_t st = (hipStream_t)stream;
   if (d_sync && pair_runs_fused(g1, g2, a1, a2)) {

@@ -332,6 +332,19 @@ def test_grouped_pair_checks_and_choice():
     assert fused(d1, d2) == L.axe_gemm_grouped_check(C.byref(d2.c)) == B.AXE_EINVAL
     d1, d2 = pair()
     assert L.axe_gemm_grouped_pair(C.byref(d1.c), C.byref(d2.c), None, None, None, None, None, None, None, 0, None) == B.AXE_EINVAL
+    # aliasing (refused before anything is launched; the addresses are placeholders): H and C disjoint from each
+    # other and from every input, the workspace disjoint from all of them
+    far = {k: (i + 1) << 32 for i, k in enumerate(["A", "B1", "H", "B2", "C", "rows", "sync"])}
+    def call(**kw):
+        a = {**far, **kw}
+        return L.axe_gemm_grouped_pair(C.byref(d1.c), C.byref(d2.c), a["A"], a["B1"], a["H"], a["B2"], a["C"], a["rows"], a["sync"],
+                                       d1.c.M + 1, None)
+    assert call(C=far["H"]) == B.AXE_EINVAL and call(C=far["A"]) == B.AXE_EINVAL and call(C=far["B1"] + 64) == B.AXE_EINVAL
+    assert call(H=far["B2"]) == B.AXE_EINVAL and call(H=far["rows"] - 16) == B.AXE_EINVAL
+    assert call(sync=far["C"] + 1024) == B.AXE_EINVAL and call(sync=far["A"]) == B.AXE_EINVAL
+    assert "overlap" in L.axe_last_error().decode()
+    assert L.axe_gemm_grouped_pair(C.byref(d1.c), C.byref(d2.c), far["A"], far["B1"], far["H"], far["B2"], far["C"], far["rows"],
+                                   far["sync"], d1.c.M, None) == B.AXE_EINVAL                       # workspace one word short
     assert L.axe_gemm_grouped_pair_status(None, 0, None) == B.AXE_EINVAL
     assert L.axe_gemm_grouped_pair_status(None, (1 << 20) + 1, None) == B.AXE_EINVAL     # beyond the library's own workspace
     big = pair(M=(1 << 20) + 8)
