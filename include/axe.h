@@ -280,7 +280,9 @@ int axe_gemm_grouped_check(const axe_gemm_grouped_desc_t* g);
  *   axe_gemm_grouped_pair_status(d_sync, M, stream) synchronises the stream and returns AXE_ETIMEOUT if any wait of
  *   the last call gave up (rows of C are then invalid), else AXE_OK (d_sync NULL: see axe_gemm_grouped_pair_static).  With all workgroups resident (the launch is
  *   sized to the compute units of the device) no wait can fail to end: tiles of the first GEMM wait for nothing and
- *   every workgroup works through its share of them before it waits.
+ *   every workgroup works through its share of them before it waits.  Other work that keeps compute units from this
+ *   launch (kernels of other streams or processes) only delays the waits, unless it does so for longer than the poll
+ *   limit allows (seconds): then waits give up and the status call says so.
  *   axe_gemm_grouped_pair_fused(g1, g2): 1 if the pair would share a launch (given a workspace), 0 if not, or the
  *   error axe_gemm_grouped_pair would return (host only).
  * Errors: those of axe_gemm_grouped for either problem; AXE_EINVAL when g2's A is not g1's C, when H or C overlaps
