@@ -109,3 +109,34 @@ def test_asm_issued_buffer_instructions_are_padded(isa, source):
         for i, l in enumerate(lines):
             if re.match(r"\tbuffer_store_dwordx[24] ", l) or re.match(r"\tbuffer_load_dwordx4 v\[\d+:\d+\], v\d+, s\[\d+:\d+\], s\d+ offen$", l):
                 assert lines[i - 1].strip() == "s_nop 4", (name, i, lines[i - 1], l)
+
+
+@pytest.mark.parametrize("kernel", ["gemm_bf16_128_grouped_pair_kernel", "gemm_f16_128_grouped_pair_kernel",
+                                    "gemm_bf16_256_grouped_pair_kernel", "gemm_f16_256_grouped_pair_kernel"])
+def test_fused_pair_publishes_with_write_through_stores_and_acquires_before_it_reads(isa, kernel):
+    """The hand-over between the two grouped GEMMs of a fused pair, on the emitted ISA: the first GEMM's tiles are
+    stored at device scope (sc1: written through to memory) and the kernel holds no write-back of the whole L2 (the
+    language's device-scope release, measured slower than two launches); the polls of the row block's word are
+    device-scope loads; a device-scope invalidate stands between the polls and the second GEMM's loads; and both
+    bodies' K loops keep the invariants of the single kernels."""
+    (name, lines), = [(k, v) for k, v in isa["kernels_gemm_bf16.hip"].items() if kernel + "E" in k]
+    stores = [l for l in lines if re.match(r"\tbuffer_store_dwordx4 ", l)]
+    sc1 = [l for l in stores if l.rstrip().endswith("sc1")]
+    assert sc1 and len(sc1) < len(stores), "the first GEMM stores at device scope, the second does not"
+    assert not [l for l in lines if "buffer_wbl2" in l]
+    assert [l for l in lines if re.match(r"\tglobal_load_dword v\d+, v\d+, s\[\d+:\d+\] sc1", l)], "device-scope polls"
+    inv = [i for i, l in enumerate(lines) if "buffer_inv sc1" in l]
+    assert inv, "device-scope acquire"
+    # every poll loop (s_sleep) is followed by an invalidate before the next direct-to-LDS load
+    for i, l in enumerate(lines):
+        if "s_sleep" in l:
+            nxt_inv = min(j for j in inv if j > i)
+            nxt_lds_load = min((j for j, x in enumerate(lines) if j > i and re.search(r"buffer_load_dwordx4 .* lds$", x)), default=len(lines))
+            assert nxt_inv < nxt_lds_load, (kernel, i)
+    loops = k_loops(lines)
+    assert len(loops) >= 4, "steady and next-tile loops of both bodies"
+    for a, b in loops:
+        body = lines[a:b]
+        assert not [l for l in body if "scratch_" in l]
+        assert {int(n) for l in body for n in re.findall(r"vmcnt\((\d+)\)", l)} == {8}
+        assert not [l for l in body if "v_accvgpr" in l or "buffer_inv" in l or "s_sleep" in l]
