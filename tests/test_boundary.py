@@ -380,3 +380,41 @@ def test_python_binding_raises_axe_error():
     with pytest.raises(B.AxeError) as e:
         B._check(B.AXE_EALIAS)
     assert e.value.code == B.AXE_EALIAS
+
+
+C_PROGRAM = r"""
+#include "axe.h"
+#include "axe_probe.h"
+#include <stdio.h>
+int main(void) {
+  axe_iter_t d[2] = {{4, 8, 0}, {8, 1, 0}};
+  const char* names[1] = {"m"};
+  int64_t off[1] = {3};
+  int64_t span[1];
+  axe_layout_t L;
+  L.n_axes = 1; L.axis_names = names; L.n_d = 2; L.d = d; L.n_r = 0; L.r = 0; L.offset = off;
+  L.swz_axis = -1; L.swz_bits = 0; L.swz_base = 0; L.swz_shift = 0;
+  if (axe_layout_span(&L, span) != AXE_OK) return 1;                 /* (4, 8)(8, 1): 1 + 3 * 8 + 7 * 1 */
+  if (axe_relayout(&L, &L, 1, 0, 2, 0, 0, 0, 0, 0, 0) == AXE_OK) return 3;   /* NULL arguments are refused, nothing is launched */
+  printf("%d %lld %s\n", (int)axe_version(), (long long)span[0], axe_strerror(AXE_ETIMEOUT));
+  return span[0] == 32 ? 0 : 2;
+}
+"""
+
+
+@pytest.mark.parametrize("compiler,std", [("gcc", "-std=c99"), ("g++", "-std=c++11")])
+def test_headers_are_plain_c_and_a_c_program_links_against_the_library(tmp_path, compiler, std):
+    """The boundary is a C ABI: include/*.h compile as strict C99 (and as C++) without warnings, and a program with no
+    Python and no torch in it links against the shared library and calls it."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    libdir = os.path.dirname(B.LIB_PATH)
+    src = tmp_path / ("prog.c" if compiler == "gcc" else "prog.cpp")
+    src.write_text(C_PROGRAM)
+    exe = tmp_path / "prog"
+    subprocess.check_call([compiler, std, "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(root, "include"), str(src), "-o",
+                           str(exe), "-L", libdir, "-laxe_hip", "-Wl,-rpath," + libdir])
+    out = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert out.returncode == 0, out.stdout + out.stderr
+    version, span, msg = out.stdout.split(None, 2)
+    assert int(version) == B.lib().axe_version() and int(span) == 32 and "wait" in msg
