@@ -206,6 +206,38 @@ def bench_transpose(steps, warmup, n_pairs=4):
     r["frac_of_hbm_peak"] = r["GBps"] / PEAK["hbm"]
     log(f"[bench] relayout 8192^2 bf16 row-major -> column-major (transposing tiles): {r['GBps']:.0f} GB/s rotating "
         f"({100 * r['frac_of_hbm_peak']:.1f}% of HBM peak)")
+    del pairs
+    # the same with extents that are no multiples of a 16-byte chunk: the element-wise tiles
+    ro, co = 8191, 8193
+    Ls, Ld = B.Layout(W.row_major_spec(ro, co)), B.Layout(W.col_major_spec(ro, co))
+    pairs = [(torch.randint(-30000, 30000, (ro * co,), dtype=torch.int16, device="cuda"),
+              torch.zeros(ro * co, dtype=torch.int16, device="cuda")) for _ in range(n_pairs)]
+    _, d_odd = time_loop(lambda i: B.axe_relayout(Ls, Ld, (ro, co), *pairs[i % n_pairs]), steps, warmup)
+    assert torch.equal(pairs[0][1].view(co, ro), pairs[0][0].view(ro, co).t())
+    r["odd_extents_8191x8193"] = {"kernel_ms": d_odd, "GBps": 2.0 * ro * co * 2 / (d_odd * 1e-3) / 1e9}
+    del pairs
+    # a register layout as destination: the A operand layout of the 256 x 256 kernel (axe_gemm_describe), tiled over the
+    # matrix (axe_layout_tile) and folded onto memory as [tile][wave][lane][reg] (axe_layout_flatten); both wave copies
+    M = K = 8192
+    desc = B.GemmDesc(M, 256, K, B.AXE_BF16, B.AXE_BF16, B.Layout(W.row_major_spec(M, K)), B.Layout(W.col_major_spec(K, 256)),
+                      B.Layout(W.row_major_spec(M, 256)), M * K, 256 * K, M * 256, tile_hint=B.AXE_TILE_256x256x64)
+    axes = ["m", "lds", "wg", "wave", "lane", "reg"]
+    spec, tshape = B.axe_gemm_describe(desc, B.AXE_DESC_A_OPERAND)
+    gm, gk = M // tshape[0], K // tshape[1]
+    tiled, shape = B.layout_tile(B.Layout(W.spec([(gm, gk, "wg"), (gk, 1, "wg")]), axes), (gm, gk), B.Layout(spec, axes), tshape)
+    span = B.layout_span(B.Layout(tiled, axes))
+    regs = span["reg"]
+    dstL = B.Layout(B.layout_flatten(B.Layout(tiled, axes), {"reg": 1, "lane": regs, "wave": span["lane"] * regs,
+                                                               "wg": span["wave"] * span["lane"] * regs}, "m"), axes)
+    srcL = B.Layout(W.spec([(gm, tshape[0] * K, "m"), (tshape[0], K, "m"), (gk, tshape[1], "m"), (tshape[1], 1, "m")]), axes)
+    n_dst = gm * gk * span["wave"] * span["lane"] * regs
+    a = torch.randint(-30000, 30000, (M * K,), dtype=torch.int16, device="cuda")
+    outs = [torch.zeros(n_dst, dtype=torch.int16, device="cuda") for _ in range(2)]
+    _, d_reg = time_loop(lambda i: B.axe_relayout(srcL, dstL, shape, a, outs[i % 2]), steps, warmup)
+    r["to_mfma_operand_registers_8192"] = {"kernel_ms": d_reg, "replicas": n_dst // (M * K),
+                                           "GBps": (M * K + n_dst) * 2.0 / (d_reg * 1e-3) / 1e9}
+    log(f"[bench] relayout 8191 x 8193 bf16 row-major -> column-major (element-wise tiles): {r['odd_extents_8191x8193']['GBps']:.0f} GB/s; "
+        f"8192^2 bf16 -> MFMA operand register order, both wave copies: {r['to_mfma_operand_registers_8192']['GBps']:.0f} GB/s (read + written)")
     return r
 
 
