@@ -300,7 +300,9 @@ int axe_gemm_grouped_pair_status(const int32_t* d_sync, int64_t M, void* stream)
  * and results as axe_gemm_grouped_pair without d_sync / sync_elems; M above 2^20 rows is AXE_EUNSUPPORTED.  All
  * calls on one device share the array: calls that overlap in time on one device (different streams) race on it
  * -- give such callers workspaces of their own through axe_gemm_grouped_pair.  The array keeps the last call's
- * counts; every call clears the M + 1 words it uses, on the stream, with a small kernel.
+ * counts; every call clears the M + 1 words it uses, on the stream, with a small kernel.  The first call on a device
+ * asks the runtime for the array's address: make that call outside graph capture (the warm-up run a capture needs
+ * anyway does it).
  * axe_gemm_grouped_pair_status(NULL, M, stream) reads the status word of the last such call on the current device. */
 int axe_gemm_grouped_pair_static(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const void* d_A,
                                  const void* d_B1, void* d_H, const void* d_B2, void* d_C, const int32_t* d_group_rows,
