@@ -92,6 +92,16 @@ __device__ __forceinline__ void tile_of_block(int bid, int nwg, int grid_m, int 
 // a fragment stored over its neighbour.  Every such asm statement therefore starts with s_nop 4; the
 // MFMAs issued before keep the matrix pipe busy meanwhile.
 //
+// The other hazard of such a store is on its data: the instruction reads its data registers a little after it has
+// issued, and the compiler -- which does not know that the asm statement is a store -- lets the very next vector-ALU
+// instruction overwrite them (the gated epilogue computed the next fragment into the registers of the 16-byte store
+// just issued).  In a quiet machine the store won the race; with a copy kernel of another stream saturating the
+// memory pipeline one group of four lanes of one store in a launch of a few million did not: 32 wrong elements in a
+// quarter of the launches.  Every asm-issued store is therefore followed by wait states of its own.
+#ifndef AXE_AFTER_STORE
+#define AXE_AFTER_STORE "\n\ts_nop 3"
+#endif
+//
 // Descriptor words for a buffer store issued as an asm statement: base address, byte range, raw
 // 32-bit data format.  The words are wave-uniform by construction; readfirstlane tells the compiler so
 // (they must sit in SGPRs).

@@ -377,7 +377,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
       asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
       if (j * 16 + 4 * (l >> 4) + 4 > c_cw) voff = (int)0x80000000u;
     }
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
@@ -387,7 +387,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
     const u32x2 d = {pack16<F16>(acc[i][j][0], acc[i][j][1]), pack16<F16>(acc[i][j][2], acc[i][j][3])};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile
@@ -416,7 +416,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
       const int c0 = maps::pair_store_col(q);
       if (j * 16 + c0 + 8 > c_cw) voff = (int)0x80000000u;
     }
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
@@ -441,9 +441,9 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
     // (first GEMM of a pair: the store is made at device scope -- it writes through this XCD's L2 to memory, where the
     //  other XCDs' workgroups will read it, so that publishing the tile needs no write-back of the whole L2)
     if constexpr (PAIR == 1)
-      asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen sc1" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+      asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen sc1" AXE_AFTER_STORE ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
     else
-      asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+      asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
 #pragma unroll
     for (int q = 0; q < 4; ++q)

@@ -245,7 +245,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
     const u32x2 d = {pack_bf16(acc[i][j][0], acc[i][j][1]), pack_bf16(acc[i][j][2], acc[i][j][3])};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile

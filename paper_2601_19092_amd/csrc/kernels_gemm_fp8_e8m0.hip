@@ -301,7 +301,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
                                                      pack_bf16(acc[i][j + 1][2], acc[i][j + 1][3]), false, false);
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
 #pragma unroll
     for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
@@ -322,7 +322,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     const auto hi = __builtin_amdgcn_permlane16_swap(pack_bf16(h[0][2], h[0][3]), pack_bf16(h[1][2], h[1][3]), false, false);
     const u32x4 d = {lo[0], hi[0], lo[1], hi[1]};
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 16);
-    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
+    asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
 #pragma unroll
     for (int q = 0; q < 4; ++q)

@@ -1476,6 +1476,47 @@ def test_gemm_grouped_is_bitwise_repeatable(kernel, gated):
     assert R.rel_frobenius(c, ref) <= BF16_TOL
 
 
+@pytest.mark.parametrize("dtype", ["f16", "fp8"])
+def test_gated_grouped_gemm_keeps_its_bits_beside_a_busy_copy_stream(dtype):
+    """The layer's first GEMM at 4096 tokens with the gated activation, launched while a large device copy of another
+    stream saturates the memory pipeline: every launch gives the bits of the quiet launch.  (Regression: the gated
+    epilogue computed the next fragment into the registers of the 16-byte store it had just issued as an asm statement;
+    with the memory pipeline backed up the store now and then read four lanes of the new values.  Every asm-issued
+    store is followed by wait states since.)"""
+    rows = W.moe_group_rows(4096, W.MOE_EXPERTS, W.MOE_TOPK, W.SEED_BASE + 11)
+    M, N, K, G = int(rows[-1]), 2 * W.MOE_INTER, W.MOE_HIDDEN, W.MOE_EXPERTS
+    dR = torch.from_numpy(rows).cuda()
+    if dtype == "f16":
+        g = W.moe_gemm1(4096, dtype="f16")
+        dA = dev(g.a_mk[:M].reshape(-1))
+        dB = dev(pack_blocked(pack_gate_up(g.b_gnk)).reshape(-1))
+        desc = B.GroupedGemmDesc(M, N, K, G, B.Layout(W.row_major_spec(M, K)), B.Layout(W.gated_b_spec(K, N, G, True)),
+                                 B.Layout(W.row_major_spec(M, N // 2)), M * K, G * N * K, M * (N // 2), in_dtype=B.AXE_F16, out_dtype=B.AXE_F16,
+                                 epilogue=B.AXE_EPI_SWIGLU)
+    else:
+        f = W.gemm_grouped_fp8(rows, N, K, W.SEED_BASE + 22, scale_dtype="e8m0")
+        dA, dB = dev(f.a_mk[:M].reshape(-1)), dev(pack_gate_up(f.b_gnk).reshape(-1))
+        sa, sb = torch.from_numpy(f.scale_a[:M]).cuda(), torch.from_numpy(f.scale_b).cuda()
+        desc = B.GroupedGemmDesc(M, N, K, G, B.Layout(W.row_major_spec(M, K)), B.Layout(W.gated_b_spec(K, N, G)),
+                                 B.Layout(W.row_major_spec(M, N // 2)), M * K, G * N * K, M * (N // 2), in_dtype=B.AXE_FP8_E4M3,
+                                 out_dtype=B.AXE_BF16, epilogue=B.AXE_EPI_SWIGLU, scale_a=sa, scale_b=sb, scale_dtype=B.AXE_SCALE_E8M0)
+    dC = torch.zeros(M * (N // 2), dtype=torch.int16, device="cuda")
+    B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+    torch.cuda.synchronize()
+    quiet = dC.clone()
+    side = torch.cuda.Stream()
+    big_a = torch.empty(1 << 28, dtype=torch.uint8, device="cuda")
+    big_b = torch.empty_like(big_a)
+    for it in range(60):
+        dC.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(side):
+            big_b.copy_(big_a)
+        B.axe_gemm_grouped(desc, dA, dB, dC, dR)
+        torch.cuda.synchronize()
+        assert torch.equal(dC, quiet), f"launch {it}: {(dC != quiet).sum().item()} elements differ from the quiet launch"
+
+
 @pytest.mark.parametrize("G,N,lo,hi", [(2, 512, 40, 71),      # few groups: K split over waves, 64 rows per pass
                                        (1, 256, 17, 18),      # one group = a dense GEMM with few rows
                                        (300, 256, 0, 41)])    # many groups of a few dozen rows: whole-K waves

@@ -109,6 +109,10 @@ def test_asm_issued_buffer_instructions_are_padded(isa, source):
         for i, l in enumerate(lines):
             if re.match(r"\tbuffer_store_dwordx[24] ", l) or re.match(r"\tbuffer_load_dwordx4 v\[\d+:\d+\], v\d+, s\[\d+:\d+\], s\d+ offen$", l):
                 assert lines[i - 1].strip() == "s_nop 4", (name, i, lines[i - 1], l)
+            # ... and every store is followed by wait states of its own: the compiler does not know the asm statement
+            # reads its data registers for a while after issue, and would let the next vector-ALU instruction overwrite them
+            if re.match(r"\tbuffer_store_dwordx[24] ", l):
+                assert re.match(r"s_nop [3-9]$", lines[i + 1].strip()), (name, i, l, lines[i + 1])
 
 
 @pytest.mark.parametrize("kernel", ["gemm_bf16_128_grouped_pair_kernel", "gemm_f16_128_grouped_pair_kernel",
