@@ -273,3 +273,39 @@ def test_pair_can_be_captured_in_a_hip_graph():
             for h, c in ((dH, dC), (dH2, dC2)):
                 assert np.array_equal(h.cpu().numpy().view(np.uint16).reshape(M, inter), want[k][0]), (rep, k)
                 assert np.array_equal(c.cpu().numpy().view(np.uint16).reshape(M, out), want[k][1]), (rep, k)
+
+
+def test_pair_beside_a_dense_gemm_of_another_stream():
+    """The fused pair launched while a dense GEMM of another stream holds compute units: its workgroups then do not
+    all start together, the waits for rows last longer -- and still end (the status stays clean), and H, C and the
+    dense result are the bits of the quiet launches."""
+    g = W.gemm_bf16(4352, 4096, 2048, 91)
+    As, Bs, Cs = W.gemm_specs(g)
+    d = B.GemmDesc(g.M, g.N, g.K, B.AXE_BF16, B.AXE_BF16, B.Layout(As), B.Layout(Bs), B.Layout(Cs), g.M * g.K, g.N * g.K, g.M * g.N)
+    gA, gB = dev(g.a_mk.reshape(-1)), dev(g.b_nk.reshape(-1))
+    gC = torch.zeros(g.M * g.N, dtype=torch.int16, device="cuda")
+    off = W.moe_group_rows(2048, W.MOE_EXPERTS, W.MOE_TOPK, W.SEED_BASE + 11)
+    L = Layer(off, W.MOE_HIDDEN, W.MOE_INTER, W.MOE_HIDDEN, 560, "f16")
+    d1, d2 = L.descs(B.AXE_GROUPED_AUTO)
+    assert B.axe_gemm_grouped_pair_fused(d1, d2)
+    dA, dW1, dW2, dR = L.device()
+    dH = torch.zeros(L.M * L.I, dtype=torch.int16, device="cuda")
+    dC = torch.zeros(L.M * L.N2, dtype=torch.int16, device="cuda")
+    sync = torch.zeros(L.M + 1, dtype=torch.int32, device="cuda")
+    B.axe_gemm(d, gA, gB, gC)
+    B.axe_gemm_grouped_pair(d1, d2, dA, dW1, dH, dW2, dC, dR, sync)
+    torch.cuda.synchronize()
+    quiet = (gC.clone(), dH.clone(), dC.clone())
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    for it in range(30):
+        for t in (gC, dH, dC):
+            t.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(s1):
+            B.axe_gemm(d, gA, gB, gC)
+            B.axe_gemm(d, gA, gB, gC)
+        with torch.cuda.stream(s2):
+            B.axe_gemm_grouped_pair(d1, d2, dA, dW1, dH, dW2, dC, dR, sync)
+        torch.cuda.synchronize()
+        B.axe_gemm_grouped_pair_status(sync, L.M)
+        assert torch.equal(gC, quiet[0]) and torch.equal(dH, quiet[1]) and torch.equal(dC, quiet[2]), it
