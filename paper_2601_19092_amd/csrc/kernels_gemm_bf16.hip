@@ -339,6 +339,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
   int c_rowblk;                                                    // bytes between fragment rows
   const int c_voff = (int)((fr * g.ldc + 4 * fq) * 2);
   int c_cw = 0;                                                    // ragged: columns of this wave's part of the tile that exist
+  int c_nfr = MR;                                                  // grouped: fragment rows of this wave that hold rows of the tile
   auto set_output = [&](int vv) __attribute__((always_inline)) {
     if constexpr (GROUPED) {
       const int row0 = __builtin_amdgcn_readlane(tb_row0, vv), dsc = __builtin_amdgcn_readlane(tb_desc, vv);
@@ -353,6 +354,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
         if (cw == 0) rows = 0;
         c_cw = cw;
       }
+      c_nfr = (rows + 15) >> 4;
       constexpr int OBG = OUT32 ? 4 : 2;                             // bytes per element of C
       rc = raw_rsrc((uint8_t*)g.C + (((int64_t)row0 + wm * (16 * MR)) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW) * OBG,
                     rows ? (uint32_t)(((rows - 1) * g.ldc + cw) * OBG) : 0u);
@@ -379,9 +381,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
     }
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
-#pragma unroll
-    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
-    __builtin_amdgcn_sched_barrier(0);                             // one fragment at a time: copied out of the AGPRs, stored, cleared
+    __builtin_amdgcn_sched_barrier(0);                             // one fragment at a time: copied out of the AGPRs and stored
   };
   auto store_fragment = [&](int i, int j) __attribute__((always_inline)) {
     typedef __attribute__((ext_vector_type(2))) unsigned int u32x2;
@@ -389,8 +389,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx2 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
-#pragma unroll
-    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;                // ready for the next tile
   };
   // Two neighbouring fragments (i, j), (i, j + 1) in one 16-byte store per lane: lane groups q = l / 16
   // hold columns 4 q .. 4 q + 3 of each fragment; v_permlane16_swap exchanges the odd lane groups of
@@ -418,8 +416,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
     }
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(voff), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
-#pragma unroll
-    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
   };
 
   // Gated epilogue: h = silu(gate) * up for the fragment pairs (j, j + 1) and (j + 2, j + 3), stored like a
@@ -445,10 +441,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
     else
       asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[i][j + q][e] = 0.f;
   };
 
   using I0 = std::integral_constant<int, 0>;
@@ -574,22 +566,30 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
     __builtin_amdgcn_sched_barrier(0);                             // no accumulator read may move above the padding
 #pragma unroll
     for (int i = 0; i < MR; ++i) {
-      if constexpr (OUT32) {
+      // grouped: a fragment row without rows of the tile issues no stores (the buffer descriptor would drop them,
+      // but each would still take its turn in the memory pipeline, ahead of the next tile's loads)
+      if (!GROUPED || i < c_nfr) {
+        if constexpr (OUT32) {
 #pragma unroll
-        for (int j = 0; j < NJ; ++j) store_fragment32(i, j);
-      } else if constexpr (GATED) {
+          for (int j = 0; j < NJ; ++j) store_fragment32(i, j);
+        } else if constexpr (GATED) {
 #pragma unroll
-        for (int j = 0; j < NJ; j += 4) store_gated_quad(i, j);
-      } else {
+          for (int j = 0; j < NJ; j += 4) store_gated_quad(i, j);
+        } else {
 #pragma unroll
-        for (int j = 0; j < NJ; j += 2) {
-          if (NJ % 2 == 0) store_fragment_pair(i, j);              // (7 fragments per row do not pair up: stored one by one)
-          else {
-            store_fragment(i, j);
-            if (j + 1 < NJ) store_fragment(i, j + 1);
+          for (int j = 0; j < NJ; j += 2) {
+            if (NJ % 2 == 0) store_fragment_pair(i, j);            // (7 fragments per row do not pair up: stored one by one)
+            else {
+              store_fragment(i, j);
+              if (j + 1 < NJ) store_fragment(i, j + 1);
+            }
           }
         }
       }
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;            // ready for the next tile
     }
     if constexpr (PAIR == 1) {
       // first GEMM of a pair: publish the tile.  Its stores were made at device scope (written through to memory,

@@ -275,6 +275,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   // ---- VGPR -> HBM (as in the bf16 kernel: fragment pairs exchange halves, 16 bytes per lane)
   i32x4 rc;
   int c_rowblk;
+  int c_nfr = 8;                                                   // grouped: fragment rows of this wave that hold rows of the tile
   const int c_voff2 = (int)((fr * g.ldc + maps::pair_store_col(fq)) * 2);
   auto set_output = [&](int vv) __attribute__((always_inline)) {
     if constexpr (GROUPED) {
@@ -282,6 +283,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
       const int tn = desc_tn(dsc);
       int rows = desc_rows(dsc) - wm * 128;                          // rows of the tile that fall to this wave
       rows = rows < 0 ? 0 : (rows > 128 ? 128 : rows);
+      c_nfr = (rows + 15) >> 4;
       constexpr int CW = GATED ? 64 : 128;                           // columns of C this wave writes
       rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * 128) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
                     rows ? (uint32_t)(((rows - 1) * g.ldc + CW) * 2) : 0u);   // the stores of rows the group does not have are dropped
@@ -303,8 +305,6 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 32);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
-#pragma unroll
-    for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f, acc[i][j + 1][e] = 0.f;
   };
 
   // Gated epilogue (see the 16-bit grouped kernel): h = silu(gate) * up for the fragment pairs (j, j + 1) and
@@ -324,10 +324,6 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     const int soff = __builtin_amdgcn_readfirstlane(i * c_rowblk + j * 16);
     asm volatile("s_nop 4\n\tbuffer_store_dwordx4 %0, %1, %2, %3 offen" AXE_AFTER_STORE ::"v"(d), "v"(c_voff2), "s"(rc), "s"(soff) : "memory");
     AXE_PARANOID_WAIT();
-#pragma unroll
-    for (int q = 0; q < 4; ++q)
-#pragma unroll
-      for (int e = 0; e < 4; ++e) acc[i][j + q][e] = 0.f;
   };
 
   using I0 = std::integral_constant<int, 0>;
@@ -475,13 +471,20 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
-      if constexpr (GATED) {
+      // grouped: a fragment row without rows of the tile issues no stores (see the 16-bit kernel)
+      if (!GROUPED || i < c_nfr) {
+        if constexpr (GATED) {
 #pragma unroll
-        for (int j = 0; j < 8; j += 4) store_gated_quad(i, j);
-      } else {
+          for (int j = 0; j < 8; j += 4) store_gated_quad(i, j);
+        } else {
 #pragma unroll
-        for (int j = 0; j < 8; j += 2) store_fragment_pair(i, j);
+          for (int j = 0; j < 8; j += 2) store_fragment_pair(i, j);
+        }
       }
+#pragma unroll
+      for (int j = 0; j < 8; ++j)
+#pragma unroll
+        for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;            // ready for the next tile
     }
     v += vstep;
     if (GROUPED ? table_rows(v) <= 0 : v >= ntiles) break;
