@@ -283,7 +283,8 @@ def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
             wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dBuse, dC, dR), steps, warmup)
             active = int((np.diff(rows) > 0).sum())
             nbytes = 2.0 * (active * f.N * f.K + M * f.K + M * NC)
-            kernel = "streaming (split K)" if M <= 8 * f.G else ("tiles of 128 x 256" if M <= 384 * f.G else "tiles of 256 x 256")
+            which = B.axe_gemm_grouped_kernel(desc)
+            kernel = {B.AXE_GROUPED_STREAM: "streaming (split K)", B.AXE_GROUPED_TILES_128: "tiles of 128 x 256"}.get(which, "tiles of 256 x 256")
             r = {"M": M, "active_experts": active, "kernel": kernel, "kernel_ms": devms, "algorithmic_bytes": nbytes,
                  "GBps": nbytes / (devms * 1e-3) / 1e9, "tflops": 2.0 * M * f.N * f.K / (devms * 1e-3) / 1e12}
             r["frac_of_hbm_peak"] = r["GBps"] / PEAK["hbm"]
@@ -343,7 +344,7 @@ def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64, 512, 4096)):
     """The same layer with e4m3 weights and activations: E8M0 block scales (one per row and 128-wide k block
     for the activations, one per 128 x 128 block for the weights), bf16 output; gemm1 with the gated activation.  The
     weights are half the bytes of the fp16 layer; bound: HBM.  Kernels chosen by the library: the weight-streaming
-    kernel at decode sizes, the tile kernel on the matrix cores' scale path from 96 rows per expert on."""
+    kernel at decode sizes, the tile kernel on the matrix cores' scale path from 17 rows per expert on."""
     import torch
     from paper_2601_19092_amd import binding as B
     from paper_2601_19092_amd import workloads as W

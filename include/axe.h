@@ -229,16 +229,16 @@ typedef struct {
  * epilogue).  Two kernels: the streaming kernel (any scales; groups of more than 64 rows take several passes over
  * their weights), and, with E8M0 scales or none, the tile kernel on the matrix cores' scale path (tiles of 256
  * rows; kernel_hint AXE_GROUPED_TILES or AXE_GROUPED_TILES_256; gated: N / 2 a multiple of 128; AUTO takes it
- * from 20 rows per group on average).  A hint that asks for tiles with fp32 scales, or for 128-row tiles, is
+ * from 13 rows per group on average, 25 when K <= 1024).  A hint that asks for tiles with fp32 scales, or for 128-row tiles, is
  * AXE_EUNSUPPORTED. */
 
 /* Two kernels serve the same family.  AXE_GROUPED_TILES: 256 x 256 tiles of the chained GEMM pipeline, for
  * groups of hundreds of rows (of 128 x 256 unless groups average more than 384 rows: a K-step then takes half
  * the matrix-core time and the weights stream past faster).  AXE_GROUPED_STREAM: one workgroup per (group, 128 rows of B), the group's
- * rows (64 at a time) held in registers while its weights stream by once -- for the few rows per group of
+ * rows (16, 32 or 64 at a time) held in registers while its weights stream by once -- for the few rows per group of
  * an MoE layer at decode batch sizes, where the time is that of reading the weights.  AUTO takes the
- * streaming kernel when M <= 8 G (the host knows M, not the group sizes; measured crossover on the
- * MoE layer of the benchmark: 8 - 16 rows per group on average). */
+ * streaming kernel when M <= 13 G, or M <= 19 G when K <= 1024 (the host knows M, not the group sizes; measured
+ * crossovers on the two GEMMs of the benchmark's MoE layer).  In a pair the second GEMM follows the first. */
 enum { AXE_GROUPED_AUTO = 0, AXE_GROUPED_TILES = 1, AXE_GROUPED_STREAM = 2,
        /* the tile kernel with tiles of 256 or 128 rows (AXE_GROUPED_TILES takes 128 while M <= 384 G) */
        AXE_GROUPED_TILES_256 = 3, AXE_GROUPED_TILES_128 = 4 };

@@ -918,19 +918,24 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
   return AXE_OK;
 }
 
-// Which kernel a planned grouped problem goes to.  16-bit inputs: the streaming kernel up to 8 rows per group on
-// average.  fp8: the tile kernel (256-row tiles on the scale path) from 20 rows per group on average -- measured on
-// the MoE layer (128 groups, gemm1 + gemm2): 16 rows per group 177 (streaming) against 174 us (tiles), 32 rows 244
-// against 180, 256 rows 1373 against 302; 4 rows 104 against 169.
+// Which kernel a planned grouped problem goes to: the streaming kernel while the groups average few rows, then the
+// tile kernels.  The crossover depends on K -- a tile's fixed costs (tile table, prologue, stores) weigh more when its
+// K loop is short -- and was measured on the two GEMMs of an MoE layer (128 groups; gemm1: K = 2048, gemm2: K = 768;
+// streaming kernel against tiles, us): fp16 gemm1 at 12 rows per group 148 against 152, at 16 rows 165 against 152;
+// fp16 gemm2 at 16 rows 84 against 88, at 20 rows 92 against 90; fp8 gemm1 at 12 rows 94 against 95, at 16 rows 108
+// against 96; fp8 gemm2 at 20 rows 56 against 63, at 24 rows 62 against 64, at 28 rows 70 against 64.  Far from the
+// crossover (fp8 layer): 4 rows per group 104 against 151, 256 rows 1373 against 288.
 bool grouped_goes_to_stream(const axe_gemm_grouped_desc_t* g, const GemmArgs& a) {
   if (g->kernel_hint == AXE_GROUPED_STREAM) return true;
+  if (a.fp8 && a.tile_m < 0) return true;
+  if (g->kernel_hint != AXE_GROUPED_AUTO) return false;            // tiles asked for
+  const bool short_k = g->K <= 1024;
+  int64_t rows = a.fp8 ? (short_k ? 24 : 12) : (short_k ? 19 : 13);
   if (a.fp8) {
-    if (a.tile_m < 0) return true;
-    if (g->kernel_hint != AXE_GROUPED_AUTO) return false;          // tiles asked for
-    static const int64_t min_rows = [] { const char* v = getenv("AXE_GROUPED_FP8_TILE_ROWS"); return v ? atoll(v) : int64_t(20); }();
-    return g->M < min_rows * (int64_t)g->G;
+    static const int64_t min_rows = [] { const char* v = getenv("AXE_GROUPED_FP8_TILE_ROWS"); return v ? atoll(v) : int64_t(0); }();
+    if (min_rows > 0) rows = min_rows - 1;
   }
-  return g->kernel_hint == AXE_GROUPED_AUTO && g->M <= 8 * (int64_t)g->G;
+  return g->M <= rows * (int64_t)g->G;
 }
 
 }  // namespace
@@ -995,10 +1000,18 @@ int plan_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_
   return AXE_OK;
 }
 
+// The second GEMM of a pair: with 16-bit inputs and no hint of its own it follows the first onto the tile kernels (its
+// own crossover lies a few rows per group higher, but the shared launch is worth more: fp16 layer at 16 rows per group
+// 232 us fused against 152 + 84), so that the pair runs the same kernels with and without a workspace.
+bool pair_second_goes_to_stream(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const GemmArgs& a1, const GemmArgs& a2) {
+  if (g2->kernel_hint == AXE_GROUPED_AUTO && !a2.fp8 && !grouped_goes_to_stream(g1, a1)) return false;
+  return grouped_goes_to_stream(g2, a2);
+}
+
 bool pair_runs_fused(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grouped_desc_t* g2, const GemmArgs& a1, const GemmArgs& a2) {
   // (rows of the intermediate matrix start on 128-byte lines: no cache line then holds rows of two row blocks, or
   //  columns of two tiles of the first GEMM)
-  return !grouped_goes_to_stream(g1, a1) && !grouped_goes_to_stream(g2, a2) && grouped_pair_fusable(a1, a2) &&
+  return !grouped_goes_to_stream(g1, a1) && !pair_second_goes_to_stream(g1, g2, a1, a2) && grouped_pair_fusable(a1, a2) &&
          (a1.ldc * 2) % 128 == 0 && ((uintptr_t)a1.C & 127) == 0 && env_int("AXE_GROUPED_PAIR_FUSE", 1) != 0;
 }
 }  // namespace
@@ -1034,9 +1047,10 @@ int axe_gemm_grouped_pair(const axe_gemm_grouped_desc_t* g1, const axe_gemm_grou
   for (int i = 0; i < 2; ++i) {                                    // one after the other, on the stream
     const axe_gemm_grouped_desc_t* g = i ? g2 : g1;
     const GemmArgs& a = i ? a2 : a1;
-    hipError_t e = grouped_goes_to_stream(g, a) ? launch_gemm_grouped_stream(a, st)
-                   : a.fp8                      ? launch_gemm_fp8_e8m0_256_grouped(a, st)
-                                                : launch_gemm_bf16_256_grouped(a, st);
+    const bool streams = i ? pair_second_goes_to_stream(g1, g2, a1, a2) : grouped_goes_to_stream(g1, a1);
+    hipError_t e = streams ? launch_gemm_grouped_stream(a, st)
+                   : a.fp8 ? launch_gemm_fp8_e8m0_256_grouped(a, st)
+                           : launch_gemm_bf16_256_grouped(a, st);
     if (e != hipSuccess) return hip_fail(e, "axe_gemm_grouped_pair");
   }
   return AXE_OK;

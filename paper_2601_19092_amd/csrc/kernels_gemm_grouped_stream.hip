@@ -70,9 +70,9 @@ __device__ __forceinline__ uint32_t pack16s(float lo, float hi) {
 // KS = the number of waves that share one set of 32 B rows and split K among them: 0 = SPLITK off (every wave its
 // own rows, all of K), 4 (16-bit inputs) or 2 (fp8, whose K-tiles are twice as deep: with 4 a wave's share of K
 // would be too few K-tiles for its pipeline); a workgroup then owns 4 / KS sets of 32 rows.
-// MI = row fragments per pass (16 MI rows of the group at a time): 1 goes with split K for groups of a handful of
-// rows, 4 with whole-K waves for the general case, and 4 with split K for launches with few groups (a dense
-// GEMM with few rows is the case of one group), where only the K split yields enough workgroups.
+// MI = row fragments per pass (16 MI rows of the group at a time): 1 or 2 go with split K for groups of a handful
+// or a dozen of rows, 4 with whole-K waves for the general case, and 4 with split K for launches with few groups
+// (a dense GEMM with few rows is the case of one group), where only the K split yields enough workgroups.
 template <int DT, bool GATED, int KS, int MI>
 __global__ __launch_bounds__(256) void gemm_grouped_stream_kernel(GemmArgs g) {
   constexpr bool SPLITK = KS != 0;
@@ -304,20 +304,38 @@ void launch_stream(const GemmArgs& g, unsigned ny, hipStream_t s) {
 }
 }  // namespace
 
-// The host knows the number of rows of all groups together, not the group sizes.  Up to 8 rows per group on
-// average (an MoE layer of 128 experts, 8 per token, up to 128 tokens: at most 22 rows in any group in the
-// benchmark's routing) it takes the variant that splits K over the waves and handles 16 rows per pass
-// (measured crossover between 8 and 16; AXE_GROUPED_SPLITK_ROWS overrides it for experiments).  Beyond that,
-// whole-K waves with 64 rows per pass -- unless that launch would have fewer than two workgroups per compute unit
-// (few groups: a dense GEMM with few rows is one group), where K is split as well.
+// The host knows the number of rows of all groups together, not the group sizes.  With a handful of rows per group
+// on average it takes the variant that splits K over the waves and handles 16 rows per pass; then, up to 16 rows
+// per group (24 when K is short), the K split with 32 rows per pass (most groups still fit one pass, and the split
+// keeps four times the loads in flight); beyond that, whole-K waves with 64 rows per pass -- unless that launch would have fewer
+// than two workgroups per compute unit (few groups: a dense GEMM with few rows is one group), where K is split
+// as well.  Measured on an MoE layer of 128 experts, 8 per token (gemm1 + gemm2, us; 16 / 32 rows per pass):
+// fp16 at 64 tokens 195 / 194, 96 tokens 207 / 200, 128 tokens 217 / 207, 192 tokens 258 / 220; fp8 at 128 tokens
+// 121 / 127, 160 tokens 139 / 132, 256 tokens 183 / 156 (64 rows per pass, whole-K waves: 176); 32 rows per pass with
+// the K split against 64 with whole-K waves at 20 / 24 rows per group: K = 768 fp8 56 / 62 against 58 / 62, fp16 92 / 101
+// against 94 / 102; K = 2048 fp16 186 / 207 against 184 / 194.
+// AXE_GROUPED_SPLITK_ROWS overrides the first bound, AXE_GROUPED_STREAM_VARIANT (1: 16 rows, 2: 32 rows, 3: 64 rows
+// with the K split, 4: 64 rows, whole-K waves) the whole choice, for experiments.
 hipError_t launch_gemm_grouped_stream(const GemmArgs& g0, hipStream_t s) {
   GemmArgs g = g0;
   g.compact_groups = g.M < g.groups;                               // at most M groups can have rows
   const unsigned ny = (unsigned)(g.compact_groups ? g.M : g.groups);
-  static const int avg = [] { const char* v = getenv("AXE_GROUPED_SPLITK_ROWS"); return v ? atoi(v) : 8; }();
-  if (g.M <= avg * (int64_t)g.groups) launch_stream<1, 1>(g, ny, s);
-  else if ((g.N / 128) * (int64_t)ny < 2 * cu_count()) launch_stream<1, 4>(g, ny, s);
-  else launch_stream<0, 4>(g, ny, s);
+  static const int avg_env = [] { const char* v = getenv("AXE_GROUPED_SPLITK_ROWS"); return v ? atoi(v) : 0; }();
+  static const int force = [] { const char* v = getenv("AXE_GROUPED_STREAM_VARIANT"); return v ? atoi(v) : 0; }();
+  const int avg = avg_env > 0 ? avg_env : (g.fp8 ? 8 : 4);
+  int variant = force;
+  if (variant < 1 || variant > 4) {
+    if (g.M <= avg * (int64_t)g.groups) variant = 1;
+    else if (g.M <= (g.K <= 1024 ? 24 : 16) * (int64_t)g.groups) variant = 2;
+    else if ((g.N / 128) * (int64_t)ny < 2 * cu_count()) variant = 3;
+    else variant = 4;
+  }
+  switch (variant) {
+    case 1: launch_stream<1, 1>(g, ny, s); break;
+    case 2: launch_stream<1, 2>(g, ny, s); break;
+    case 3: launch_stream<1, 4>(g, ny, s); break;
+    default: launch_stream<0, 4>(g, ny, s); break;
+  }
   return hipGetLastError();
 }
 

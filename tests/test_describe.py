@@ -388,3 +388,22 @@ def test_grouped_describe_refusals():
     with pytest.raises(B.AxeError) as e:
         B.axe_gemm_grouped_describe(_grouped_desc(1000), 99)
     assert e.value.code == B.AXE_EINVAL
+
+
+def test_grouped_kernel_choice_follows_rows_per_group_and_k():
+    """Left alone the library streams the weights while groups average few rows and takes the tile kernels beyond; the
+    crossover lies higher when K is short (host logic only: the choice is made from M, G and K)."""
+    def choice(M, K, G=4, fp8=False):
+        N = 512
+        if fp8:
+            d = B.GroupedGemmDesc(M, N, K, G, B.Layout(W.row_major_spec(M, K)), B.Layout(W.spec([(G, N * K, "m"), (K, 1, "m"), (N, K, "m")])),
+                                  B.Layout(W.row_major_spec(M, N)), M * K, G * N * K, M * N, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16)
+        else:
+            d = B.GroupedGemmDesc(M, N, K, G, B.Layout(W.row_major_spec(M, K)), B.Layout(W.spec([(G, N * K, "m"), (K, 1, "m"), (N, K, "m")])),
+                                  B.Layout(W.row_major_spec(M, N)), M * K, G * N * K, M * N)
+        return B.axe_gemm_grouped_kernel(d)
+    S, T = B.AXE_GROUPED_STREAM, B.AXE_GROUPED_TILES_128
+    assert choice(13 * 4, 2048) == S and choice(13 * 4 + 1, 2048) == T
+    assert choice(19 * 4, 768) == S and choice(19 * 4 + 1, 768) == T
+    assert choice(12 * 4, 2048, fp8=True) == S and choice(12 * 4 + 1, 2048, fp8=True) == B.AXE_GROUPED_TILES_256
+    assert choice(24 * 4, 768, fp8=True) == S and choice(24 * 4 + 1, 768, fp8=True) == B.AXE_GROUPED_TILES_256

@@ -132,6 +132,23 @@ def test_pair_moe_layer_shapes_512_tokens():
     assert np.array_equal(h_raw, h2) and np.array_equal(c_raw, c2)
 
 
+def test_pair_second_gemm_follows_the_first_onto_the_tile_kernels():
+    """256 tokens: 16 rows per expert on average.  Alone, the second GEMM (K = 768) would still go to the streaming
+    kernel; in a pair it follows the first (K = 2048: tiles), so the pair is fused, and runs the same kernels -- same
+    bits -- with and without a workspace."""
+    off = W.moe_group_rows(256, W.MOE_EXPERTS, W.MOE_TOPK, W.SEED_BASE + 11)
+    L = Layer(off, W.MOE_HIDDEN, W.MOE_INTER, W.MOE_HIDDEN, 511, "f16")
+    d1, d2 = L.descs(B.AXE_GROUPED_AUTO)
+    assert B.axe_gemm_grouped_kernel(d1) == B.AXE_GROUPED_TILES_128 and B.axe_gemm_grouped_kernel(d2) == B.AXE_GROUPED_STREAM
+    assert B.axe_gemm_grouped_pair_fused(d1, d2)
+    h_raw, c_raw, _ = run_pair(L, B.AXE_GROUPED_AUTO)
+    h_ref, c_ref = L.oracle()
+    check_blocks(L.off, decode(h_raw, "f16"), h_raw, h_ref, TOL["f16"], "H")
+    check_blocks(L.off, decode(c_raw, "f16"), c_raw, c_ref, TOL["f16"], "C")
+    h2, c2, _ = run_pair(L, B.AXE_GROUPED_AUTO, fused=False)
+    assert np.array_equal(h_raw, h2) and np.array_equal(c_raw, c2)
+
+
 _FULL = {}
 
 

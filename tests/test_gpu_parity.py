@@ -1161,10 +1161,11 @@ def test_gemm_grouped_f16_plain_and_gated():
 # ----------------------------------------------------------------------------- grouped GEMM, few rows per group (decode)
 @pytest.mark.parametrize("dtype", ["bf16", "f16"])
 @pytest.mark.parametrize("gated,blocked", [(False, False), (False, True), (True, False), (True, True)])
-def test_gemm_grouped_stream_kernel_variants(dtype, gated, blocked):
-    """The streaming kernel on ragged small groups (1 .. 70 rows: up to two passes of 64 rows, every number of row
-    fragments), plain and gated, plain and blocked weights, bf16 and fp16."""
-    sizes = [1, 0, 16, 17, 33, 64, 65, 70, 3, 48]
+@pytest.mark.parametrize("sizes", [[1, 0, 16, 17, 33, 64, 65, 70, 3, 48],                  # 64 rows per pass
+                                   [1, 0, 16, 17, 33, 9, 40, 0, 3, 20, 2, 12]])            # a dozen per group: 32 per pass, K split
+def test_gemm_grouped_stream_kernel_variants(dtype, gated, blocked, sizes):
+    """The streaming kernel on ragged small groups (1 .. 70 rows: up to two passes of 64 rows, or of 32, every number
+    of row fragments), plain and gated, plain and blocked weights, bf16 and fp16."""
     off = np.concatenate([[0], np.cumsum(sizes)])
     N, K = 512, 320
     g = W.gemm_grouped_bf16(off, N, K, 101, M=int(off[-1]) + 2, std_b=2.0 * K ** -0.5, dtype=dtype)
@@ -1345,6 +1346,7 @@ def test_gemm_grouped_fewer_rows_than_groups():
 @pytest.mark.parametrize("scale_dtype", ["f32", "e8m0", None])
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("sizes,hint", [([1, 0, 3, 16, 2, 0, 7, 1] * 4, B.AXE_GROUPED_AUTO),           # M <= 8 G: the split-K variant
+                                        ([40, 0, 9, 33, 1, 17, 20, 0], B.AXE_GROUPED_AUTO),              # M <= 16 G: split K, passes of 32 rows
                                         ([70, 0, 33, 64, 17], B.AXE_GROUPED_STREAM)])                    # passes of 64 rows
 def test_gemm_grouped_fp8_block_scaled(sizes, hint, gated, scale_dtype):
     """e4m3 operands, one scale per row of A and k block, one per 128 x 128 block of each group's B (fp32 or E8M0), or none;
