@@ -5,7 +5,7 @@
 // stored in blocks, the fp16 twins, and the grouped kernels of an MoE layer (tiles of 256 or 128 rows, plain or
 // gated epilogue) -- see the template parameters of gemm_bf16_256_body.
 //
-// Three measured facts shape the kernel:
+// Two measured facts shape the kernel:
 //  * On real (random) data the chip runs into its power limit long before the matrix pipe is full,
 //    and what a flop costs depends on the instruction stream: a register-only loop of 16x16x32 MFMAs
 //    that walks the accumulators in register order, issued by a single wave per SIMD, sustains
@@ -14,9 +14,9 @@
 //  * The L2 -> CU path is the second bound: a 256 x 256 tile pulls 64 KiB per 64 K-elements, about
 //    three quarters of what the L2s deliver to all CUs at once, and only when every request is a
 //    whole 128-byte line.  Hence 64-wide K-tiles: every load instruction fetches 8 rows x 128 bytes.
-//  * The workgroups that share an A or B panel run side by side on one XCD and would ask for the
-//    same 128-byte line of every row at the same time, then for the next line one K-step later: HBM
-//    sees isolated 128-byte reads scattered over rows 16 KiB apart.  Hence the K rotation below.
+//  (An earlier version let every workgroup walk each aligned window of 8 K-tiles in an order of its own, so that
+//   the workgroups sharing a panel fetch 8 adjacent lines of a row together; that helped a bare load stream, but the
+//   finished kernel runs 2 % faster with all of them on the same K-tile: 8192^3 1549 -> 1580 TFLOP/s.)
 //
 // Tile movements, each an Axe layout (reported by axe_gemm_describe):
 //   HBM -> LDS  : one wave instruction covers 8 rows x 128 bytes (lane = 8 * row + chunk), direct to LDS.
@@ -75,7 +75,6 @@ constexpr int kRow = maps::kLargeRowBytes;         // bytes of K per LDS row (64
 constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-tile
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
-constexpr int kRot = 8;                           // K-rotation window, in K-tiles
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(3))) uint8_t* lds_u8;
@@ -176,7 +175,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
   const int wm = w >> 1, wn = w & 1;                               // wave grid 2 x 2
   const int nk = (int)(g.K / 64);
   const int ntiles = g.grid_m * g.grid_n;
-  const int nk_rot = nk & ~(kRot - 1);                             // K-tiles beyond the last full rotation window keep their order
 
   // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ...  The load side of the
   //      pipeline runs two to four K-steps ahead of the MFMAs and crosses into the next tile before
@@ -199,7 +197,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
   };
   struct Tile {
     __amdgpu_buffer_rsrc_t ra, rb;
-    int rot;
   };
   int tb_row0 = 0, tb_desc = 0;                                    // grouped: lane t = the workgroup's t-th tile
   if constexpr (GROUPED) group_tiles<TM, RAGGED>(g, lane, tb_row0, tb_desc);
@@ -218,7 +215,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
         if constexpr (RAGGED) nb = (int)g.N - tn * NB < NB ? (int)g.N - tn * NB : NB;
         t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + ((int64_t)grp * g.ldg + b_tile_off(tn)) * 2), 0,
                                                  (nb - 1) * b_pitch + b_span, 0x00020000);
-        t.rot = ((row0 >> 8) + tn) & (kRot - 1);
         return t;
       }
     }
@@ -227,15 +223,9 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
       tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + a_tile_off(tm) * 2), 0, 255 * a_pitch + a_span, 0x00020000);
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + b_tile_off(tn) * 2), 0, (NB - 1) * b_pitch + b_span, 0x00020000);
-      // K rotation: each workgroup walks every aligned window of kRot K-tiles in its own rotated order
-      // (the sum over k does not care), so that the workgroups sharing a panel fetch the kRot adjacent
-      // lines of a row at once -- one 1 KiB burst per row -- and find the other lines in L2 during the
-      // rest of the window (measured on the bare load stream: 16 -> 21.5 TB/s).
-      t.rot = (tm + tn) & (kRot - 1);
     } else {                                                       // no such tile: every load returns zero
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
-      t.rot = 0;
     }
     return t;
   };
@@ -264,10 +254,6 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
   wait_rows(0);
   wait_rows(1);
   Tile cur = describe(v), nxt = describe(v + vstep);
-  // K-step T of the current tile (T >= nk: step T - nk of the next one) -> K-tile
-  auto kcol = [&](int T, int rot) -> int {
-    return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T;
-  };
 
   // ---- HBM -> LDS.  Per K-tile and operand 32 wave instructions of 8 rows; wave w issues pieces
   //      i = 0..7 = row groups w, w + 4, ..., w + 28.  Buffer addressing: the descriptor covers the 256
@@ -294,7 +280,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
   auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + maps::piece_row(w, i, 0, 4) * kRow), 16,
-                                             a_voff_p[i], (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * a_kstep, 0, 0);
+                                             a_voff_p[i], (nx ? T - nk : T) * a_kstep, 0, 0);   // (K-step T >= nk: step T - nk of the next tile)
     AXE_PARANOID_WAIT();
   };
   // B ring: byte offsets of the blocks that hold K-steps kt, kt+1, kt+2 (step kt+3 reuses the first)
@@ -302,7 +288,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + maps::piece_row(w, i, 0, 4) * kRow), 16,
-                                             b_voff_p[i], (nx ? kcol(T - nk, nxt.rot) : kcol(T, cur.rot)) * b_kstep, 0, 0);
+                                             b_voff_p[i], (nx ? T - nk : T) * b_kstep, 0, 0);
     AXE_PARANOID_WAIT();
   };
 

@@ -35,7 +35,7 @@
 // tile kt (read at the end of step kt-1).  Between two barriers a wave issues A of tile kt+2 (into
 // the block just freed: one K-step to land, so it goes first) and then B of tile kt+3 (ring of
 // three blocks: a little more than one K-step).
-// The K rotation, the workgroup -> tile order and the chaining of a workgroup's tiles into one
+// The workgroup -> tile order and the chaining of a workgroup's tiles into one
 // pipeline are those of the bf16 kernel.  (Measured: chaining gains nothing here.  With the MFMAs
 // taken out, the loads, LDS reads and barriers of this kernel alone run at the equivalent of 4.9
 // PFLOP/s -- 19 TB/s from the L2s, about what they deliver -- and a register-only loop of the MFMAs
@@ -58,7 +58,6 @@ constexpr int kRow = maps::kLargeRowBytes;         // bytes of K per LDS row (12
 constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-tile
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
-constexpr int kRot = 8;                           // K-rotation window, in K-tiles
 constexpr int kFD = 3;                            // an MFMA's result is folded into the running sum kFD MFMAs later
 constexpr int kNP = 4;                            // product buffers (a power of two above kFD)
 typedef __attribute__((address_space(3))) void* lds_ptr;
@@ -80,7 +79,6 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   const int wm = w >> 2, wn = w & 3;                               // wave grid 2 x 4
   const int nk = (int)(g.K / 128);
   const int ntiles = g.grid_m * g.grid_n;
-  const int nk_rot = nk & ~(kRot - 1);                             // K-tiles beyond the last full rotation window keep their order
   const bool scaled = g.scale_a != nullptr;
 
   // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ...  The loads run two
@@ -90,7 +88,6 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   struct Tile {
     __amdgpu_buffer_rsrc_t ra, rb;
     const float *sa, *sb;                                          // block scales of this wave's rows (A) and columns (B)
-    int rot;
   };
   auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
     Tile t;
@@ -103,19 +100,15 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
                                                255 * b_pitch + (int)g.K, 0x00020000);
       t.sa = scaled ? g.scale_a + (int64_t)(2 * tm + wm) * g.nkb : nullptr;
       t.sb = scaled ? g.scale_b + (int64_t)(2 * tn + (wn >> 1)) * g.nkb : nullptr;
-      t.rot = (tm + tn) & (kRot - 1);                              // K rotation (see the bf16 kernel)
     } else {                                                       // no such tile: every load returns zero
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
       t.sa = t.sb = nullptr;
-      t.rot = 0;
     }
     return t;
   };
   int v = blockIdx.x;
   Tile cur = describe(v), nxt = describe(v + (int)gridDim.x);
-  // position T of a tile's walk -> K-tile
-  auto ktile = [&](int T, int rot) -> int { return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T; };
 
   // ---- HBM -> LDS.  Per K-tile and operand 32 wave instructions of 8 rows; wave w issues pieces
   //      i = 0..3 = row groups w, w + 8, w + 16, w + 24.  Step T >= nk of the current tile is step
@@ -128,7 +121,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   auto a_load = [&](int T, int i, int stage, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + stage * kBlk + maps::piece_row(w, i, 0, 8) * kRow), 16,
-                                             a_voff, i * a_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+                                             a_voff, i * a_piece + (nx ? T - nk : T) * kRow, 0, 0);
     AXE_PARANOID_WAIT();
   };
   // B ring: byte offsets of the blocks that hold tiles kt, kt+1, kt+2 (tile kt+3 reuses the first)
@@ -136,7 +129,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + maps::piece_row(w, i, 0, 8) * kRow), 16,
-                                             b_voff, i * b_piece + (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+                                             b_voff, i * b_piece + (nx ? T - nk : T) * kRow, 0, 0);
     AXE_PARANOID_WAIT();
   };
 
@@ -164,7 +157,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
   auto scales_from = [&](int base) -> float {
     if (!scaled) return 1.0f;
     const int T = base + lane;
-    const int t = ktile(T < nk ? T : nk - 1, cur.rot);
+    const int t = T < nk ? T : nk - 1;
     return cur.sa[t] * cur.sb[t];
   };
   auto lane_value = [](float v, int l) -> float {
@@ -294,8 +287,7 @@ __global__ __launch_bounds__(512, 1) void gemm_fp8_256_kernel(GemmArgs g) {
         // The next tile's first register of scales is fetched now and waited for after this tile's
         // stores (asm statements: a load the compiler sees would be waited for with vmcnt(0), which
         // drains the operand pipeline).
-        const int T = lane < nk ? lane : nk - 1;
-        const int t = ktile(T, nxt.rot);
+        const int t = lane < nk ? lane : nk - 1;
         asm volatile("global_load_dword %0, %1, off" : "=v"(nsa) : "v"(nxt.sa + t) : "memory");
         asm volatile("global_load_dword %0, %1, off" : "=v"(nsb) : "v"(nxt.sb + t) : "memory");
       }

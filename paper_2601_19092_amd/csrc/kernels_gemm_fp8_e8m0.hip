@@ -7,7 +7,7 @@
 // Structure and measured reasons are those of the bf16 kernel (kernels_gemm_bf16.hip): workgroup tile
 // 256 x 256, one workgroup of 4 waves per CU, wave tile 128 x 128 = 8 x 8 fragments in 256 AGPRs, five
 // 32 KiB LDS blocks (both operands direct to LDS: A into two blocks, one K-step ahead, B through a ring of
-// three), K rotation, tiles of a workgroup chained, direct paired stores.
+// three), tiles of a workgroup chained, direct paired stores.
 // What differs:
 //   K-step      : 128 elements = one LDS row = ONE MFMA per fragment (32 cycles); a K-step is 64 MFMAs,
 //                 split in two halves by fragment rows (rows 0..3, rows 4..7), with the barrier
@@ -24,9 +24,9 @@
 //   Row scales  : (second instantiation) A carries one code per ROW and 128-wide k block -- the usual choice for
 //                 activations -- instead of one per 128 x 128 block.  The instruction takes the scale of a row
 //                 from the lanes that hold the row, so nothing changes in the matrix pipe: a lane keeps the codes
-//                 of its row of each of the 8 fragment rows for the 8 K-steps of a rotation window (8 contiguous
-//                 bytes of the row-major (M, K / 128) code array, 16 registers, plus 16 for the window being
-//                 fetched) and hands the MFMAs of a K-step one byte of each.
+//                 of its row of each of the 8 fragment rows for a window of 8 K-steps (8 contiguous bytes of the
+//                 row-major (M, K / 128) code array, 16 registers, plus 16 for the window being fetched) and hands
+//                 the MFMAs of a K-step one byte of each.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
@@ -45,7 +45,6 @@ constexpr int kRow = maps::kLargeRowBytes;         // bytes of K per LDS row (12
 constexpr int kBlk = kTile * kRow;                // 32 KiB: one operand, one K-tile
 constexpr int kBoff = 2 * kBlk;                   // A: blocks 0, 1 (double buffer); B: blocks 2, 3, 4 (ring)
 constexpr int kLds = 5 * kBlk;                    // 160 KiB
-constexpr int kRot = 8;                           // K-rotation window, in K-tiles
 typedef __attribute__((ext_vector_type(4))) unsigned int u32x4;
 typedef __attribute__((address_space(3))) void* lds_ptr;
 typedef __attribute__((address_space(3))) uint8_t* lds_u8;
@@ -85,7 +84,6 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   const int wm = w >> 1, wn = w & 1;                               // wave grid 2 x 2
   const int nk = (int)(g.K / 128);
   const int ntiles = g.grid_m * g.grid_n;
-  const int nk_rot = nk & ~(kRot - 1);                             // K-tiles beyond the last full rotation window keep their order
   const bool scaled = g.scale_a != nullptr;
 
   // ---- the tiles of this workgroup: blockIdx.x, blockIdx.x + gridDim.x, ... (cur and nxt, see the bf16 kernel);
@@ -95,7 +93,6 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     __amdgpu_buffer_rsrc_t ra, rb;
     const uint8_t *sa, *sb, *sb2;                                  // E8M0 codes of this wave's row block (not ROWS) and column block(s), one per K-tile
     int sa_row;                                                    // ROWS: the lane's row of fragment row 0 (fragment row i: 16 i further)
-    int rot;
   };
   int tb_row0 = 0, tb_desc = 0;
   if constexpr (GROUPED) group_tiles<kTile, false>(g, lane, tb_row0, tb_desc);
@@ -112,7 +109,6 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
         t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)row0 * g.lda), 0, (rows - 1) * a_pitch + (int)g.K, 0x00020000);
         t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)grp * g.ldg + (int64_t)tn * kTile * g.ldb), 0,
                                                  255 * b_pitch + (int)g.K, 0x00020000);
-        t.rot = ((row0 >> 8) + tn) & (kRot - 1);
         t.sa_row = row0 + wm * 128 + (lane & 15);
         const int64_t nb = g.N / 128;                              // 128-wide blocks of a group's logical columns
         if constexpr (GATED) {
@@ -131,7 +127,6 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
       tile_of_block(v, ntiles, g.grid_m, g.grid_n, tm, tn);
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)tn * kTile * g.ldb), 0,
                                                255 * b_pitch + (int)g.K, 0x00020000);
-      t.rot = (tm + tn) & (kRot - 1);                              // K rotation
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)tm * kTile * g.lda), 0,
                                                255 * a_pitch + (int)g.K, 0x00020000);
       if constexpr (ROWS) t.sa_row = tm * kTile + wm * 128 + (lane & 15);
@@ -140,7 +135,6 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     } else {                                                       // no such tile: every load returns zero
       t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)g.B, 0, 0, 0x00020000);
       t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)g.A, 0, 0, 0x00020000);
-      t.rot = 0;
     }
     return t;
   };
@@ -148,8 +142,6 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   const int vstep = GROUPED ? 1 : (int)gridDim.x;
   if (GROUPED && table_rows(0) <= 0) return;                       // more workgroups than tiles (the host sizes the launch for the worst case)
   Tile cur = describe(v), nxt = describe(v + vstep);
-  // K-step T of the current tile (T >= nk: step T - nk of the next one) -> K-tile index
-  auto ktile = [&](int T, int rot) -> int { return T < nk_rot ? ((T & ~(kRot - 1)) | ((T + rot) & (kRot - 1))) : T; };
 
   // ---- block scales.  The wave's 128 rows and 128 columns lie in one scale block each, so a K-step
   //      needs two codes.  A register per operand holds the codes of 64 consecutive K-steps of the
@@ -162,17 +154,16 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   auto fetch_codes = [&](const Tile& t, int base, uint32_t& oa, uint32_t& ob, uint32_t& ob2) __attribute__((always_inline)) {
     if (!scaled) return;
     const int T = base + lane;
-    const int kt_ = ktile(T < nk ? T : nk - 1, t.rot);
+    const int kt_ = T < nk ? T : nk - 1;
     if constexpr (!ROWS) oa = t.sa[kt_];
     ob = t.sb[kt_];
     if constexpr (GATED) ob2 = t.sb2[kt_];
   };
-  // Row scales.  The walk visits the K-tiles of a full aligned window of 8 in the order (t + rot) % 8, t = 0..7, and
-  // those of the last, partial window (K / 128 no multiple of 8) in their own order.  The codes of a row for a window
-  // are 8 contiguous bytes of the row-major (M, K / 128) array (of a partial window fewer: the load then runs on into
-  // the next row, or, at the very end of the array, starts earlier and is shifted down).  na: the window being
-  // fetched, as loaded; ca: the current window, rotated by the tile's rot so that step t of the window uses byte t,
-  // and moved down by one byte per step.  Without scales all codes are 127 (2^0).
+  // Row scales.  The codes of a row for a window of 8 K-steps are 8 contiguous bytes of the row-major (M, K / 128)
+  // array (of the last, partial window fewer: the load then runs on into the next row, or, at the very end of the
+  // array, starts earlier and is shifted down).  na: the window being fetched, as loaded; ca: the current window,
+  // step t of the window uses byte t: the lowest byte now, moved down by one byte per step.  Without scales all
+  // codes are 127 (2^0).
   uint32_t ca[8][2], na[8][2];
 #pragma unroll
   for (int i = 0; i < 8; ++i) ca[i][0] = ca[i][1] = na[i][0] = na[i][1] = 0x7f7f7f7fu;
@@ -199,24 +190,19 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
       na[i][0] = (uint32_t)c, na[i][1] = (uint32_t)(c >> 32);      // (used 8 K-steps later: nothing here may wait for the load)
     }
   };
-  // na -> ca at the first step of window win of the current tile: shifted down if the read started early, rotated by rot
-  auto take_rows = [&](int rot, int win) __attribute__((always_inline)) {
+  // na -> ca at the first step of window win of the current tile: shifted down if the read started early
+  auto take_rows = [&](int win) __attribute__((always_inline)) {
     if (!scaled) {                                                 // a fresh window of codes 127 (the steps shift them out)
 #pragma unroll
       for (int i = 0; i < 8; ++i) ca[i][0] = ca[i][1] = 0x7f7f7f7fu;
       return;
     }
-    const bool swap = (rot & 4) != 0;
-    const uint32_t sh = (uint32_t)(rot & 3) * 8;
 #pragma unroll
     for (int i = 0; i < 8; ++i) {
       int at, over;
       row_codes_at(cur.sa_row, i, win, at, over);
       const uint64_t c = (((uint64_t)na[i][1] << 32) | na[i][0]) >> (8 * over);
-      const uint32_t c0 = (uint32_t)c, c1 = (uint32_t)(c >> 32);
-      const uint32_t lo = swap ? c1 : c0, hi = swap ? c0 : c1;
-      ca[i][0] = __builtin_amdgcn_alignbit(hi, lo, sh);            // 64-bit rotation to the right by 8 rot bits
-      ca[i][1] = __builtin_amdgcn_alignbit(lo, hi, sh);
+      ca[i][0] = (uint32_t)c, ca[i][1] = (uint32_t)(c >> 32);
     }
   };
   auto lane_value = [](uint32_t val, int l) -> uint32_t { return (uint32_t)__builtin_amdgcn_readlane((int)val, l); };
@@ -236,14 +222,14 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + maps::piece_row(w, i, 0, 4) * kRow), 16, a_voff_p[i],
-                                             (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+                                             (nx ? T - nk : T) * kRow, 0, 0);   // (K-step T >= nk: step T - nk of the next tile)
     AXE_PARANOID_WAIT();
   };
   int bo0 = kBoff, bo1 = kBoff + kBlk, bo2 = kBoff + 2 * kBlk;     // B ring: blocks of K-steps kt, kt+1, kt+2
   auto b_load = [&](int T, int i, int slot_off, bool cross) __attribute__((always_inline)) {
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.rb : cur.rb, (lds_ptr)(lds3 + slot_off + maps::piece_row(w, i, 0, 4) * kRow), 16, b_voff_p[i],
-                                             (nx ? ktile(T - nk, nxt.rot) : ktile(T, cur.rot)) * kRow, 0, 0);
+                                             (nx ? T - nk : T) * kRow, 0, 0);
     AXE_PARANOID_WAIT();
   };
 
@@ -388,7 +374,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     // the codes are now in VGPRs, written by the vector ALU; the MFMA is an asm statement, so the compiler's
     // hazard recogniser cannot pad between that write and the matrix core's read of its scale operands
     if constexpr (ROWS) {
-      // step t of the window uses byte t of the rotated codes: the lowest byte now, then the 64 bits move down by one
+      // step t of the window uses byte t of the codes: the lowest byte now, then the 64 bits move down by one
       // byte (no register is ever indexed by t: that would put the array into scratch memory)
 #pragma unroll
       for (int i = 0; i < 8; ++i) {
@@ -409,12 +395,12 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     const int t = bo0;
     bo0 = bo1, bo1 = bo2, bo2 = t;
   };
-  // ROWS: at the first step of a window of 8 the codes fetched during the previous window are taken over (rotated by
-  // this tile's rot) and the step fetches the next window's
+  // ROWS: at the first step of a window of 8 the codes fetched during the previous window are taken over and the
+  // step fetches the next window's
   auto window = [&](int kt) __attribute__((always_inline)) -> bool {
     if constexpr (ROWS) {
       if ((kt & 7) == 0) {
-        take_rows(kt < nk_rot ? cur.rot : 0, kt >> 3);             // the partial last window keeps its order
+        take_rows(kt >> 3);
         return true;
       }
     }

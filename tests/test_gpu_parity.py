@@ -529,8 +529,7 @@ def test_gemm_fp8_small_tile(M, N, K, scaled):
 
 
 # ----------------------------------------------------------------------------- large tile (256 x 256)
-# K = 64 nk: nk = 1, 2, 3 (shorter than the pipeline), 16 (two rotation windows), 11 and 9 (a window plus an
-# unrotated tail, odd number of K-steps); several tiles so that the workgroups rotate differently
+# K = 64 nk: nk = 1, 2, 3 (shorter than the pipeline), 16, 11 and 9 (odd numbers of K-steps); several tiles
 @pytest.mark.parametrize("M,N,K", [(256, 256, 64), (256, 256, 128), (512, 768, 192), (768, 256, 1024),
                                    (512, 768, 704), (768, 512, 576)])
 def test_gemm_bf16_large_tile(M, N, K):
@@ -1272,7 +1271,7 @@ def test_gemm_fp8_row_scaled_activations(M, N, K, scale_dtype):
 
 # One E8M0 code per row of A on the 256 x 256 tile (the matrix cores' scale path): K = 1024 nw with nw = 1 (a single
 # window of 8 K-tiles), 2, 3 (odd), 9 (more than 64 K-steps: B's code registers are refilled as well); one tile, several
-# tiles with different K rotations, and 17 x 16 tiles (chained: the next tile's first window is fetched across the tile
+# tiles, and 17 x 16 tiles (chained: the next tile's first window is fetched across the tile
 # boundary).  The row codes differ from row to row and from k block to k block over a range of 2^11.
 # K = 128, 768 and 1152: 1, 6 and 9 K-tiles -- a partial window of row codes only (its 8-byte reads run on into the next
 # row and, for the last rows, start early at the end of the array), and a full window followed by a partial one.
@@ -1391,7 +1390,7 @@ def test_gemm_grouped_fp8_block_scaled(sizes, hint, gated, scale_dtype):
 
 
 # fp8 on the grouped TILE kernel (the matrix cores' scale path, tiles of 256 rows): E8M0 scales (per row of A, per
-# 128 x 128 block of each group's B) or none; plain and gated epilogue.  K = 768 (6 K-tiles: no full rotation window,
+# 128 x 128 block of each group's B) or none; plain and gated epilogue.  K = 768 (6 K-tiles: no full window of row codes,
 # the row codes of a window end before 8 bytes are up -- also at the very end of the code array), 1152 (9: a full window
 # and a partial one; odd, so one tile per workgroup), 2048 (16: two windows, chained tiles); groups from 1 to 700
 # rows, empty groups, rows outside every group.
