@@ -344,7 +344,7 @@ def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64, 512, 4096)):
     """The same layer with e4m3 weights and activations: E8M0 block scales (one per row and 128-wide k block
     for the activations, one per 128 x 128 block for the weights), bf16 output; gemm1 with the gated activation.  The
     weights are half the bytes of the fp16 layer; bound: HBM.  Kernels chosen by the library: the weight-streaming
-    kernel at decode sizes, the tile kernel on the matrix cores' scale path from 17 rows per expert on."""
+    kernel at decode sizes, the tile kernel on the matrix cores' scale path from 9 - 16 rows per expert on."""
     import torch
     from paper_2601_19092_amd import binding as B
     from paper_2601_19092_amd import workloads as W
@@ -377,7 +377,7 @@ def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64, 512, 4096)):
             wall, devms = time_loop(lambda i: B.axe_gemm_grouped(desc, dA, dB, dC, dR), steps, warmup)
             active = int((np.diff(rows) > 0).sum())
             nbytes = active * N * K + M * K + 2.0 * M * NC
-            kernel = "streaming" if B.axe_gemm_grouped_kernel(desc) == B.AXE_GROUPED_STREAM else "tiles of 256 x 256"
+            kernel = {B.AXE_GROUPED_STREAM: "streaming", B.AXE_GROUPED_TILES_128: "tiles of 128 x 256"}.get(B.axe_gemm_grouped_kernel(desc), "tiles of 256 x 256")
             r = {"M": M, "active_experts": active, "kernel": kernel, "kernel_ms": devms, "algorithmic_bytes": nbytes,
                  "GBps": nbytes / (devms * 1e-3) / 1e9, "tflops": 2.0 * M * N * K / (devms * 1e-3) / 1e12}
             r["frac_of_hbm_peak"] = r["GBps"] / PEAK["hbm"]

@@ -228,9 +228,9 @@ typedef struct {
  * Both NULL: unscaled.  K a multiple of 128; B[e] column-major (plain, or gate/up interleaved for the gated
  * epilogue).  Two kernels: the streaming kernel (any scales; groups of more than 64 rows take several passes over
  * their weights), and, with E8M0 scales or none, the tile kernel on the matrix cores' scale path (tiles of 256
- * rows; kernel_hint AXE_GROUPED_TILES or AXE_GROUPED_TILES_256; gated: N / 2 a multiple of 128; AUTO takes it
- * from 13 rows per group on average, 25 when K <= 1024).  A hint that asks for tiles with fp32 scales, or for 128-row tiles, is
- * AXE_EUNSUPPORTED. */
+ * or 128 rows: kernel_hint AXE_GROUPED_TILES, _256 or _128; gated: N / 2 a multiple of 128; AUTO takes it
+ * from 9 rows per group on average, 16 when K <= 1024, with 128-row tiles up to 384 rows per group).  A hint
+ * that asks for tiles with fp32 scales is AXE_EUNSUPPORTED. */
 
 /* Two kernels serve the same family.  AXE_GROUPED_TILES: 256 x 256 tiles of the chained GEMM pipeline, for
  * groups of hundreds of rows (of 128 x 256 unless groups average more than 384 rows: a K-step then takes half

@@ -851,12 +851,12 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
     set_error("%s: fp8 inputs need K a multiple of 128 and each B[e] column-major (not blocked)", fn);
     return AXE_EUNSUPPORTED;
   }
-  // fp8 on the tile kernel (the matrix cores' scale path, tiles of 256 rows): E8M0 scales or none; with the gated
+  // fp8 on the tile kernel (the matrix cores' scale path, tiles of 256 or 128 rows): E8M0 scales or none; with the gated
   // epilogue the gate and the up half must each be whole 128-wide scale blocks; the row codes are addressed in 32 bits
   const bool fp8_tiles_ok = fp8 && (!g->d_scale_a || (g->scale_dtype == AXE_SCALE_E8M0 && (!gated || (g->N / 2) % 128 == 0) &&
                                                        g->M * ((g->K + 127) / 128) >= 8 && g->M * ((g->K + 127) / 128) < (int64_t(1) << 30)));
-  if (fp8 && tiles_forced && (!fp8_tiles_ok || g->kernel_hint == AXE_GROUPED_TILES_128)) {
-    set_error("%s: the fp8 tile kernel has tiles of 256 rows and takes E8M0 scales or none (gated: N / 2 a multiple of 128)", fn);
+  if (fp8 && tiles_forced && !fp8_tiles_ok) {
+    set_error("%s: the fp8 tile kernel takes E8M0 scales or none (gated: N / 2 a multiple of 128)", fn);
     return AXE_EUNSUPPORTED;
   }
   if (g->G > 4096 || g->N % 256 || g->N / 256 > 2048 || g->K % 64 || g->M >= (int64_t(1) << 31) ||
@@ -914,7 +914,7 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
   a.groups = g->G;
   a.gated = gated;
   a.tile_m = g->kernel_hint == AXE_GROUPED_TILES_256 ? 256 : (g->kernel_hint == AXE_GROUPED_TILES_128 ? 128 : 0);
-  if (fp8) a.tile_m = fp8_tiles_ok ? 256 : -1;                     // -1: only the streaming kernel serves this problem
+  if (fp8 && !fp8_tiles_ok) a.tile_m = -1;                         // -1: only the streaming kernel serves this problem
   return AXE_OK;
 }
 
@@ -922,15 +922,15 @@ int plan_gemm_grouped(const axe_gemm_grouped_desc_t* g, const void* dA, const vo
 // tile kernels.  The crossover depends on K -- a tile's fixed costs (tile table, prologue, stores) weigh more when its
 // K loop is short -- and was measured on the two GEMMs of an MoE layer (128 groups; gemm1: K = 2048, gemm2: K = 768;
 // streaming kernel against tiles, us): fp16 gemm1 at 12 rows per group 148 against 152, at 16 rows 165 against 152;
-// fp16 gemm2 at 16 rows 84 against 88, at 20 rows 92 against 90; fp8 gemm1 at 12 rows 94 against 95, at 16 rows 108
-// against 96; fp8 gemm2 at 20 rows 56 against 63, at 24 rows 62 against 64, at 28 rows 70 against 64.  Far from the
-// crossover (fp8 layer): 4 rows per group 104 against 151, 256 rows 1373 against 288.
+// fp16 gemm2 at 16 rows 84 against 88, at 20 rows 92 against 90; fp8 (tiles of 128 rows) gemm1 at 6 rows 78 against 84,
+// at 8 rows 84 against 85, at 10 rows 91 against 85; fp8 gemm2 at 12 rows 44 against 49, at 16 rows 50 against 50, at
+// 20 rows 55 against 50.  Far from the crossover (fp8 layer): 4 rows per group 104 against 151, 256 rows 1373 against 274.
 bool grouped_goes_to_stream(const axe_gemm_grouped_desc_t* g, const GemmArgs& a) {
   if (g->kernel_hint == AXE_GROUPED_STREAM) return true;
   if (a.fp8 && a.tile_m < 0) return true;
   if (g->kernel_hint != AXE_GROUPED_AUTO) return false;            // tiles asked for
   const bool short_k = g->K <= 1024;
-  int64_t rows = a.fp8 ? (short_k ? 24 : 12) : (short_k ? 19 : 13);
+  int64_t rows = a.fp8 ? (short_k ? 15 : 8) : (short_k ? 19 : 13);
   if (a.fp8) {
     static const int64_t min_rows = [] { const char* v = getenv("AXE_GROUPED_FP8_TILE_ROWS"); return v ? atoll(v) : int64_t(0); }();
     if (min_rows > 0) rows = min_rows - 1;
@@ -955,7 +955,7 @@ int axe_gemm_grouped_kernel(const axe_gemm_grouped_desc_t* g) {
   GemmArgs a;
   if (int rc = plan_gemm_grouped(g, nullptr, nullptr, nullptr, nullptr, a, false)) return rc;
   if (grouped_goes_to_stream(g, a)) return AXE_GROUPED_STREAM;
-  if (a.fp8) return AXE_GROUPED_TILES_256;
+  if (a.fp8) return grouped_fp8_tile_rows(a.M, a.groups, a.tile_m) == 128 ? AXE_GROUPED_TILES_128 : AXE_GROUPED_TILES_256;
   return grouped_tile_rows(a.M, a.groups, a.tile_m) == 128 ? AXE_GROUPED_TILES_128 : AXE_GROUPED_TILES_256;
 }
 

@@ -43,6 +43,15 @@ inline int grouped_tile_rows(int64_t M, int groups, int tile_m) {
   if (tile_m) return tile_m == 128 ? 128 : 256;
   return M <= (int64_t)small_avg * groups ? 128 : 256;
 }
+// The same choice for the fp8 grouped tile kernel (AXE_GROUPED_FP8_TILE128_ROWS overrides the threshold).  Measured on
+// the same layer with E8M0 scales (gemm1 + gemm2, us, 256-row against 128-row tiles): 16 rows per group 158 against 136,
+// 32 rows 163 against 140, 128 rows 224 against 190, 256 rows 281 against 274, 512 rows 429 against 439, 1024 rows 722
+// against 775.
+inline int grouped_fp8_tile_rows(int64_t M, int groups, int tile_m) {
+  static const int small_avg = [] { const char* v = getenv("AXE_GROUPED_FP8_TILE128_ROWS"); return v ? atoi(v) : 384; }();
+  if (tile_m == 128 || tile_m == 256) return tile_m;
+  return M <= (int64_t)small_avg * groups ? 128 : 256;
+}
 // grouped, few rows per group: one workgroup per (group, 128 rows of B), weights streamed once, no LDS
 hipError_t launch_gemm_grouped_stream(const GemmArgs& g, hipStream_t s);
 hipError_t launch_gemm_fp8_256(const GemmArgs& g, hipStream_t s);

@@ -71,10 +71,15 @@ __device__ __forceinline__ void mfma_scaled(f32x4& acc, i32x8 first, i32x8 secon
 // GATED: B holds each group's gate and up rows interleaved in runs of 16, so that the wave's fragment pair (j, j + 1) is
 // (gate, up) of the same 16 outputs; the tile stores silu(gate) * up, half as wide.  The gate and the up columns of a
 // wave lie in different 128-wide blocks of the logical matrix: two B codes per K-step.
-template <bool ROWS, bool GROUPED = false, bool GATED = false>
+// MR = fragment rows per wave: 8 (tiles of 256 rows), or 4 for the grouped kernel when groups are small (tiles of 128
+// rows, a wave owns 64 x 128: a K-step is 2 x 16 MFMAs per wave and moves half as much of A; as in the 16-bit kernel
+// the A blocks in LDS keep their places, half of each is used).
+template <bool ROWS, bool GROUPED = false, bool GATED = false, int MR = 8>
 __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   static_assert(!GROUPED || ROWS, "the grouped kernel scales A per row");
   static_assert(!GATED || GROUPED, "the gated epilogue exists for the grouped kernel");
+  static_assert(MR == 8 || (MR == 4 && GROUPED), "128-row tiles exist for the grouped kernel");
+  constexpr int TM = 32 * MR, WR = 16 * MR;                        // rows of a tile, of a wave's part of it
   __shared__ __attribute__((aligned(1024))) uint8_t lds_mem[kLds];
   const lds_u8 lds3 = (lds_u8)lds_mem;                             // 32-bit LDS addresses
 
@@ -95,7 +100,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     int sa_row;                                                    // ROWS: the lane's row of fragment row 0 (fragment row i: 16 i further)
   };
   int tb_row0 = 0, tb_desc = 0;
-  if constexpr (GROUPED) group_tiles<kTile, false>(g, lane, tb_row0, tb_desc);
+  if constexpr (GROUPED) group_tiles<TM, false>(g, lane, tb_row0, tb_desc);
   auto table_rows = [&](int t) __attribute__((always_inline)) -> int { return t < 64 ? desc_rows(__builtin_amdgcn_readlane(tb_desc, t)) : 0; };
   auto describe = [&](int v) __attribute__((always_inline)) -> Tile {
     Tile t;
@@ -109,7 +114,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
         t.ra = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.A + (int64_t)row0 * g.lda), 0, (rows - 1) * a_pitch + (int)g.K, 0x00020000);
         t.rb = __builtin_amdgcn_make_buffer_rsrc((void*)((const uint8_t*)g.B + (int64_t)grp * g.ldg + (int64_t)tn * kTile * g.ldb), 0,
                                                  255 * b_pitch + (int)g.K, 0x00020000);
-        t.sa_row = row0 + wm * 128 + (lane & 15);
+        t.sa_row = row0 + wm * WR + (lane & 15);
         const int64_t nb = g.N / 128;                              // 128-wide blocks of a group's logical columns
         if constexpr (GATED) {
           // memory rows 256 tn + 128 wn + 16 j + i of the group's image: j even = gate, j odd = up, of the logical columns
@@ -164,9 +169,9 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   // array, starts earlier and is shifted down).  na: the window being fetched, as loaded; ca: the current window,
   // step t of the window uses byte t: the lowest byte now, moved down by one byte per step.  Without scales all
   // codes are 127 (2^0).
-  uint32_t ca[8][2], na[8][2];
+  uint32_t ca[MR][2], na[MR][2];
 #pragma unroll
-  for (int i = 0; i < 8; ++i) ca[i][0] = ca[i][1] = na[i][0] = na[i][1] = 0x7f7f7f7fu;
+  for (int i = 0; i < MR; ++i) ca[i][0] = ca[i][1] = na[i][0] = na[i][1] = 0x7f7f7f7fu;
   bool more = false;                                               // the workgroup has another tile after the current one
   // where the 8 bytes of (row of fragment row i, window win) are read from, and by how many bytes that read starts
   // early (only at the very end of the array).  32-bit arithmetic: the host admits code arrays below 2^31 bytes.
@@ -182,7 +187,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   auto fetch_rows = [&](const Tile& t, int win) __attribute__((always_inline)) {
     if (!scaled) return;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < MR; ++i) {
       int at, over;
       row_codes_at(t.sa_row, i, win, at, over);
       uint64_t c;
@@ -194,11 +199,11 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   auto take_rows = [&](int win) __attribute__((always_inline)) {
     if (!scaled) {                                                 // a fresh window of codes 127 (the steps shift them out)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) ca[i][0] = ca[i][1] = 0x7f7f7f7fu;
+      for (int i = 0; i < MR; ++i) ca[i][0] = ca[i][1] = 0x7f7f7f7fu;
       return;
     }
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < MR; ++i) {
       int at, over;
       row_codes_at(cur.sa_row, i, win, at, over);
       const uint64_t c = (((uint64_t)na[i][1] << 32) | na[i][0]) >> (8 * over);
@@ -216,9 +221,11 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   const int b_voff = lrow * b_pitch + maps::lds_chunk_pos(lrow, lp, maps::kLargeChunks) * maps::kChunkBytes;
   const int a_piece = maps::piece_row(0, 1, 0, 4) * a_pitch, b_piece = maps::piece_row(0, 1, 0, 4) * b_pitch;   // bytes between pieces
   // (the piece goes into the per-lane offset, one register per piece: the scalar offset is the K-tile's alone)
-  int a_voff_p[8], b_voff_p[8];
+  int a_voff_p[MR], b_voff_p[8];                                   // (A: MR pieces of 8 rows per wave and K-step)
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a_voff_p[i] = a_voff_x + i * a_piece, b_voff_p[i] = b_voff + i * b_piece;
+  for (int i = 0; i < MR; ++i) a_voff_p[i] = a_voff_x + i * a_piece;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) b_voff_p[i] = b_voff + i * b_piece;
   auto a_dload = [&](int T, int i, bool cross) __attribute__((always_inline)) {   // piece i of step T into the A block of its parity
     const bool nx = cross && T >= nk;
     __builtin_amdgcn_raw_ptr_buffer_load_lds(nx ? nxt.ra : cur.ra, (lds_ptr)(lds3 + (T & 1) * kBlk + maps::piece_row(w, i, 0, 4) * kRow), 16, a_voff_p[i],
@@ -237,8 +244,8 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   const int fr = lane % maps::kFrag, fq = lane / maps::kFrag;
   const int pos0 = maps::lds_chunk_pos(fr, maps::operand_chunk_fp8(0, fq), maps::kLargeChunks) * maps::kChunkBytes;
   const int pos1 = maps::lds_chunk_pos(fr, maps::operand_chunk_fp8(1, fq), maps::kLargeChunks) * maps::kChunkBytes;
-  const lds_u8 fax0 = lds3 + (wm * 128 + fr) * kRow + pos0;
-  const lds_u8 fax1 = lds3 + (wm * 128 + fr) * kRow + pos1;
+  const lds_u8 fax0 = lds3 + (wm * WR + fr) * kRow + pos0;
+  const lds_u8 fax1 = lds3 + (wm * WR + fr) * kRow + pos1;
   const lds_u8 fbx0 = lds3 + (wn * 128 + fr) * kRow + pos0;
   const lds_u8 fbx1 = lds3 + (wn * 128 + fr) * kRow + pos1;
   auto read_a = [&](int f, int off) __attribute__((always_inline)) -> i32x8 {
@@ -248,30 +255,30 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     return lds_read32(fbx0 + off + f * 16 * kRow, fbx1 + off + f * 16 * kRow);
   };
 
-  f32x4 acc[8][8];
+  f32x4 acc[MR][8];
 #pragma unroll
-  for (int i = 0; i < 8; ++i)
+  for (int i = 0; i < MR; ++i)
 #pragma unroll
     for (int j = 0; j < 8; ++j)
 #pragma unroll
       for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  i32x8 fa[8], fb[8];      // all fragments of the current K-step; each is re-read for the next step right after its last use
+  i32x8 fa[MR], fb[8];      // all fragments of the current K-step; each is re-read for the next step right after its last use
 
   // ---- VGPR -> HBM (as in the bf16 kernel: fragment pairs exchange halves, 16 bytes per lane)
   i32x4 rc;
   int c_rowblk;
-  int c_nfr = 8;                                                   // grouped: fragment rows of this wave that hold rows of the tile
+  int c_nfr = MR;                                                  // grouped: fragment rows of this wave that hold rows of the tile
   const int c_voff2 = (int)((fr * g.ldc + maps::pair_store_col(fq)) * 2);
   auto set_output = [&](int vv) __attribute__((always_inline)) {
     if constexpr (GROUPED) {
       const int row0 = __builtin_amdgcn_readlane(tb_row0, vv), dsc = __builtin_amdgcn_readlane(tb_desc, vv);
       const int tn = desc_tn(dsc);
-      int rows = desc_rows(dsc) - wm * 128;                          // rows of the tile that fall to this wave
-      rows = rows < 0 ? 0 : (rows > 128 ? 128 : rows);
+      int rows = desc_rows(dsc) - wm * WR;                           // rows of the tile that fall to this wave
+      rows = rows < 0 ? 0 : (rows > WR ? WR : rows);
       c_nfr = (rows + 15) >> 4;
       constexpr int CW = GATED ? 64 : 128;                           // columns of C this wave writes
-      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * 128) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
+      rc = raw_rsrc((uint16_t*)g.C + ((int64_t)row0 + wm * WR) * g.ldc + (int64_t)tn * (2 * CW) + wn * CW,
                     rows ? (uint32_t)(((rows - 1) * g.ldc + CW) * 2) : 0u);   // the stores of rows the group does not have are dropped
       c_rowblk = (int)(16 * g.ldc * 2);
       return;
@@ -322,7 +329,11 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   // step kt + 3 (after MFMAs 18, 22, 26, 30).  The second half also reads the 16 fragments of step kt+1, each right after the
   // last MFMA that uses the register it goes to: A fragments 0..3 during rows 4, 5; A fragments 4, 5
   // and, after MFMA (7, j), B fragment j during rows 6, 7; A fragments 6, 7 at the end.
-  auto half = [&](auto par_c, auto h_c, auto cross_c, int kt, const uint32_t (&va)[8], uint32_t vb, uint32_t vb2, bool pref) __attribute__((always_inline)) {
+  // With 4 fragment rows per wave (MR = 4) a half is one pair of rows, 16 MFMAs: the first half loads pieces 4..7 of B
+  // of step kt + 2 (after MFMAs 2, 6, 10, 14); the second the 4 pieces of A of step kt + 2 (after MFMAs 0, 2, 4, 6) and
+  // pieces 0..3 of B of step kt + 3 (after MFMAs 8, 10, 12, 14), and reads step kt + 1: A fragments 0, 1 after MFMAs
+  // 1, 3, B fragment j after MFMA (3, j), A fragments 2, 3 at the end.
+  auto half = [&](auto par_c, auto h_c, auto cross_c, int kt, const uint32_t (&va)[MR], uint32_t vb, uint32_t vb2, bool pref) __attribute__((always_inline)) {
     constexpr int PAR = decltype(par_c)::value, H = decltype(h_c)::value;
     constexpr bool CROSS = decltype(cross_c)::value != 0;
     const int bT = H == 0 ? kt + 2 : kt + 3;
@@ -330,8 +341,8 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     constexpr int pa = (PAR ^ 1) * kBlk;                           // step kt+1: A stage, B ring block
     const int pb = bo1;
 #pragma unroll
-    for (int q = 0; q < 32; ++q) {
-      const int i = 4 * H + 2 * (q >> 4) + (q & 1), j = (q >> 1) & 7;
+    for (int q = 0; q < 4 * MR; ++q) {
+      const int i = (MR / 2) * H + 2 * (q >> 4) + (q & 1), j = (q >> 1) & 7;
       mfma_scaled(acc[i][j], fb[j], fa[i], (GATED && (j & 1)) ? vb2 : vb, va[ROWS ? i : 0]);
       __builtin_amdgcn_sched_barrier(0);
       if constexpr (ROWS && H == 1) {
@@ -342,21 +353,39 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
           else if (more) fetch_rows(nxt, 0);
         }
       }
-      if (H == 1) {
-        if (q < 16 && (q & 3) == 1) fa[q >> 2] = read_a(q >> 2, pa);
-        if (q == 16) fa[4] = read_a(4, pa);
-        if (q == 18) fa[5] = read_a(5, pa);
-        if (q >= 16 && (q & 1) == 1) fb[j] = read_b(j, pb);
-        if (q == 31) {
-          fa[6] = read_a(6, pa);
-          fa[7] = read_a(7, pa);
+      if constexpr (MR == 8) {
+        if (H == 1) {
+          if (q < 16 && (q & 3) == 1) fa[q >> 2] = read_a(q >> 2, pa);
+          if (q == 16) fa[4] = read_a(4, pa);
+          if (q == 18) fa[5] = read_a(5, pa);
+          if (q >= 16 && (q & 1) == 1) fb[j] = read_b(j, pb);
+          if (q == 31) {
+            fa[6] = read_a(6, pa);
+            fa[7] = read_a(7, pa);
+          }
         }
-      }
-      if (H == 0) {
-        if ((q & 7) == 2) b_load(bT, 4 + (q >> 3), bslot, CROSS);
+        if (H == 0) {
+          if ((q & 7) == 2) b_load(bT, 4 + (q >> 3), bslot, CROSS);
+        } else {
+          if (q < 16 && (q & 1) == 0) a_dload(kt + 2, q >> 1, CROSS);
+          if (q >= 16 && (q & 3) == 2) b_load(bT, (q - 16) >> 2, bslot, CROSS);
+        }
       } else {
-        if (q < 16 && (q & 1) == 0) a_dload(kt + 2, q >> 1, CROSS);
-        if (q >= 16 && (q & 3) == 2) b_load(bT, (q - 16) >> 2, bslot, CROSS);
+        if (H == 1) {
+          if (q == 1) fa[0] = read_a(0, pa);
+          if (q == 3) fa[1] = read_a(1, pa);
+          if ((q & 1) == 1) fb[j] = read_b(j, pb);
+          if (q == 15) {
+            fa[2] = read_a(2, pa);
+            fa[3] = read_a(3, pa);
+          }
+        }
+        if (H == 0) {
+          if ((q & 3) == 2) b_load(bT, 4 + (q >> 2), bslot, CROSS);
+        } else {
+          if (q < 8 && (q & 1) == 0) a_dload(kt + 2, q >> 1, CROSS);
+          if (q >= 8 && (q & 1) == 0) b_load(bT, (q - 8) >> 1, bslot, CROSS);
+        }
       }
       __builtin_amdgcn_sched_barrier(0);
       if ((q & 7) == 7) AXE_PARANOID_SYNC();
@@ -370,22 +399,24 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     }
   };
   auto step = [&](auto par_c, auto cross_c, int kt, bool pref = false) __attribute__((always_inline)) {
-    uint32_t va[8], vb = lane_value(cvb, kt & 63), vb2 = GATED ? lane_value(cvb2, kt & 63) : 0u;
+    uint32_t va[MR], vb = lane_value(cvb, kt & 63), vb2 = GATED ? lane_value(cvb2, kt & 63) : 0u;
     // the codes are now in VGPRs, written by the vector ALU; the MFMA is an asm statement, so the compiler's
     // hazard recogniser cannot pad between that write and the matrix core's read of its scale operands
     if constexpr (ROWS) {
       // step t of the window uses byte t of the codes: the lowest byte now, then the 64 bits move down by one
       // byte (no register is ever indexed by t: that would put the array into scratch memory)
 #pragma unroll
-      for (int i = 0; i < 8; ++i) {
+      for (int i = 0; i < MR; ++i) {
         va[i] = ca[i][0] & 0xffu;
         ca[i][0] = __builtin_amdgcn_alignbit(ca[i][1], ca[i][0], 8);
         ca[i][1] >>= 8;
       }
-      if constexpr (GATED)
-        asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4]), "+v"(va[5]), "+v"(va[6]), "+v"(va[7]), "+v"(vb), "+v"(vb2));
+      if constexpr (MR == 4)
+        asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(vb), "+v"(vb2));
+      else if constexpr (GATED)
+        asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4 % MR]), "+v"(va[5 % MR]), "+v"(va[6 % MR]), "+v"(va[7 % MR]), "+v"(vb), "+v"(vb2));
       else
-        asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4]), "+v"(va[5]), "+v"(va[6]), "+v"(va[7]), "+v"(vb));
+        asm volatile("s_nop 3" : "+v"(va[0]), "+v"(va[1]), "+v"(va[2]), "+v"(va[3]), "+v"(va[4 % MR]), "+v"(va[5 % MR]), "+v"(va[6 % MR]), "+v"(va[7 % MR]), "+v"(vb));
     } else {
       va[0] = lane_value(cva, kt & 63);
       asm volatile("s_nop 3" : "+v"(va[0]), "+v"(vb));
@@ -408,26 +439,26 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
   };
 
   // ---- prologue (first tile only): steps 0 and 1 of A, steps 0, 1 and half of 2 of B
-  //      Step 0 of both operands and the scale codes first: the MFMAs start as soon as these have landed (the 20 loads
+  //      Step 0 of both operands and the scale codes first: the MFMAs start as soon as these have landed (the MR + 12 loads
   //      of step 1 and of step 2's first half may still be in flight, as at the barrier of every later step).
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a_dload(0, i, true);
+  for (int i = 0; i < MR; ++i) a_dload(0, i, true);
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(0, i, bo0, true);
   fetch_codes(cur, 0, cva, cvb, cvb2);
   if constexpr (ROWS) fetch_rows(cur, 0);
 #pragma unroll
-  for (int i = 0; i < 8; ++i) a_dload(1, i, true);                 // (a single K-step per tile: step 1 is the next tile's step 0)
+  for (int i = 0; i < MR; ++i) a_dload(1, i, true);                // (a single K-step per tile: step 1 is the next tile's step 0)
 #pragma unroll
   for (int i = 0; i < 8; ++i) b_load(1, i, bo1, true);
 #pragma unroll
   for (int i = 0; i < 4; ++i) b_load(2, i, bo2, true);
-  asm volatile("s_waitcnt vmcnt(20)" ::: "memory");
+  asm volatile("s_waitcnt vmcnt(%0)" ::"n"(MR + 12) : "memory");
   wg_barrier();
 #pragma unroll
   for (int f = 0; f < 8; ++f) fb[f] = read_b(f, bo0);
 #pragma unroll
-  for (int f = 0; f < 8; ++f) fa[f] = read_a(f, 0);
+  for (int f = 0; f < MR; ++f) fa[f] = read_a(f, 0);
 
   // ---- all K-steps of all tiles of this workgroup, one uninterrupted pipeline (nk even and >= 4 when chained)
   for (;;) {
@@ -456,7 +487,7 @@ __device__ __forceinline__ void gemm_fp8_e8m0_256_body(const GemmArgs& g) {
     asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");             // the last MFMAs retire before their results are read
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
+    for (int i = 0; i < MR; ++i) {
       // grouped: a fragment row without rows of the tile issues no stores (see the 16-bit kernel)
       if (!GROUPED || i < c_nfr) {
         if constexpr (GATED) {
@@ -484,6 +515,9 @@ __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_kernel(GemmArgs g) {
 __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_rows_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_grouped_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true, true>(g); }
 __global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_256_grouped_gated_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true, true, true>(g); }
+// grouped, tiles of 128 rows (small groups)
+__global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_128_grouped_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true, true, false, 4>(g); }
+__global__ __launch_bounds__(256, 1) void gemm_fp8_e8m0_128_grouped_gated_kernel(GemmArgs g) { gemm_fp8_e8m0_256_body<true, true, true, 4>(g); }
 
 hipError_t launch_gemm_fp8_e8m0_256(const GemmArgs& g, hipStream_t s) {
   const int ntiles = g.grid_m * g.grid_n;
@@ -499,10 +533,11 @@ hipError_t launch_gemm_fp8_e8m0_256(const GemmArgs& g, hipStream_t s) {
   return hipGetLastError();
 }
 
-// Grouped (see launch_gemm_bf16_256_grouped): the host knows only that sum_e ceil(rows_e / 256) <= M / 256 + groups.
+// Grouped (see launch_gemm_bf16_256_grouped): the host knows only that sum_e ceil(rows_e / TM) <= M / TM + groups.
 hipError_t launch_gemm_fp8_e8m0_256_grouped(const GemmArgs& g, hipStream_t s) {
   if (g.scale_a && (!g.scale_e8m0 || g.M * (int64_t)g.nkb < 8 || g.M * (int64_t)g.nkb >= (int64_t(1) << 30))) return hipErrorInvalidValue;
-  const int64_t worst = (g.M / kTile + g.groups) * (int64_t)g.grid_n;
+  const bool t128 = grouped_fp8_tile_rows(g.M, g.groups, g.tile_m) == 128;
+  const int64_t worst = (g.M / (t128 ? 128 : kTile) + g.groups) * (int64_t)g.grid_n;
   const int nk = (int)(g.K / 128);
   const int cus = cu_count();
   const bool chain = (nk % 2 == 0) && nk >= 4;
@@ -510,8 +545,13 @@ hipError_t launch_gemm_fp8_e8m0_256_grouped(const GemmArgs& g, hipStream_t s) {
   if (chain && nwg > cus) nwg = (nwg + cus - 1) / cus * cus;      // more workgroups than compute units only in whole rounds
   nwg = (nwg + 7) / 8 * 8;                                         // the tile sequence is cut into 8 parts, one per XCD
   if (nwg > 0x7fffffff) return hipErrorInvalidValue;
-  if (g.gated) hipLaunchKernelGGL(gemm_fp8_e8m0_256_grouped_gated_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
-  else hipLaunchKernelGGL(gemm_fp8_e8m0_256_grouped_kernel, dim3((unsigned)nwg), dim3(256), 0, s, g);
+  const dim3 grid((unsigned)nwg), block(256);
+  switch ((t128 ? 2 : 0) + (g.gated ? 1 : 0)) {
+    case 0: hipLaunchKernelGGL(gemm_fp8_e8m0_256_grouped_kernel, grid, block, 0, s, g); break;
+    case 1: hipLaunchKernelGGL(gemm_fp8_e8m0_256_grouped_gated_kernel, grid, block, 0, s, g); break;
+    case 2: hipLaunchKernelGGL(gemm_fp8_e8m0_128_grouped_kernel, grid, block, 0, s, g); break;
+    default: hipLaunchKernelGGL(gemm_fp8_e8m0_128_grouped_gated_kernel, grid, block, 0, s, g); break;
+  }
   return hipGetLastError();
 }
 

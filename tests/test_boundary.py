@@ -364,7 +364,9 @@ def test_grouped_gemm_fp8_goes_to_the_streaming_kernel_only():
     assert chk(desc()) == B.AXE_OK and chk(desc(scales=False)) == B.AXE_OK and chk(desc(sd=B.AXE_SCALE_E8M0)) == B.AXE_OK
     assert chk(desc(M=4000)) == B.AXE_OK                                                  # large groups stream too (in passes of 64 rows)
     assert chk(desc(M=4000, hint=B.AXE_GROUPED_STREAM)) == B.AXE_OK
-    assert chk(desc(hint=B.AXE_GROUPED_TILES)) == B.AXE_EUNSUPPORTED
+    assert chk(desc(hint=B.AXE_GROUPED_TILES)) == B.AXE_EUNSUPPORTED                       # fp32 scales: no tile kernel
+    for hint in (B.AXE_GROUPED_TILES, B.AXE_GROUPED_TILES_256, B.AXE_GROUPED_TILES_128):   # E8M0 scales or none: tiles of either height
+        assert chk(desc(hint=hint, sd=B.AXE_SCALE_E8M0)) == B.AXE_OK and chk(desc(hint=hint, scales=False)) == B.AXE_OK
     assert chk(desc(K=192, Bs=W.spec([(64, 512 * 192, "m"), (192, 1, "m"), (512, 192, "m")]))) == B.AXE_EUNSUPPORTED   # K no multiple of 128
     assert chk(desc(out=B.AXE_F16)) == B.AXE_EUNSUPPORTED
     assert chk(desc(sd=5)) == B.AXE_EINVAL

@@ -405,5 +405,6 @@ def test_grouped_kernel_choice_follows_rows_per_group_and_k():
     S, T = B.AXE_GROUPED_STREAM, B.AXE_GROUPED_TILES_128
     assert choice(13 * 4, 2048) == S and choice(13 * 4 + 1, 2048) == T
     assert choice(19 * 4, 768) == S and choice(19 * 4 + 1, 768) == T
-    assert choice(12 * 4, 2048, fp8=True) == S and choice(12 * 4 + 1, 2048, fp8=True) == B.AXE_GROUPED_TILES_256
-    assert choice(24 * 4, 768, fp8=True) == S and choice(24 * 4 + 1, 768, fp8=True) == B.AXE_GROUPED_TILES_256
+    assert choice(8 * 4, 2048, fp8=True) == S and choice(8 * 4 + 1, 2048, fp8=True) == T
+    assert choice(15 * 4, 768, fp8=True) == S and choice(15 * 4 + 1, 768, fp8=True) == T
+    assert choice(384 * 4, 768, fp8=True) == T and choice(384 * 4 + 1, 768, fp8=True) == B.AXE_GROUPED_TILES_256

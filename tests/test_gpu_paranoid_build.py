@@ -101,8 +101,9 @@ def test_grouped_gemm_fast_build_equals_checking_build(kernel, gated):
     assert torch.equal(out[0], out[1]), f"{(out[0] != out[1]).sum().item()} elements differ"
 
 
+@pytest.mark.parametrize("tiles", [B.AXE_GROUPED_TILES_256, B.AXE_GROUPED_TILES_128])
 @pytest.mark.parametrize("gated", [False, True])
-def test_fp8_grouped_tile_kernel_fast_build_equals_checking_build(gated):
+def test_fp8_grouped_tile_kernel_fast_build_equals_checking_build(gated, tiles):
     rng = np.random.default_rng(23)
     off = np.concatenate([[0], np.cumsum(rng.integers(0, 500, 24))]).astype(np.int32)
     N, K = 1024, 768
@@ -119,7 +120,7 @@ def test_fp8_grouped_tile_kernel_fast_build_equals_checking_build(gated):
     sa, sb = torch.from_numpy(g.scale_a).cuda(), torch.from_numpy(g.scale_b).cuda()
     desc = B.GroupedGemmDesc(g.M, N, K, g.G, B.Layout(W.row_major_spec(g.M, K)), useL, B.Layout(W.row_major_spec(g.M, NC)),
                              g.M * K, g.b_gnk.size, g.M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
-                             epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=B.AXE_GROUPED_TILES_256,
+                             epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=tiles,
                              scale_a=sa, scale_b=sb, scale_dtype=B.AXE_SCALE_E8M0)
     out = []
     for path in (B.LIB_PATH, PARANOID):

@@ -1345,7 +1345,7 @@ def test_gemm_grouped_fewer_rows_than_groups():
 @pytest.mark.parametrize("scale_dtype", ["f32", "e8m0", None])
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("sizes,hint", [([1, 0, 3, 16, 2, 0, 7, 1] * 4, B.AXE_GROUPED_AUTO),           # M <= 8 G: the split-K variant
-                                        ([40, 0, 9, 33, 1, 17, 20, 0], B.AXE_GROUPED_AUTO),              # M <= 16 G: split K, passes of 32 rows
+                                        ([40, 0, 9, 33, 1, 17, 20, 0], B.AXE_GROUPED_STREAM),            # a dozen rows per group: split K, passes of 32 rows
                                         ([70, 0, 33, 64, 17], B.AXE_GROUPED_STREAM)])                    # passes of 64 rows
 def test_gemm_grouped_fp8_block_scaled(sizes, hint, gated, scale_dtype):
     """e4m3 operands, one scale per row of A and k block, one per 128 x 128 block of each group's B (fp32 or E8M0), or none;
@@ -1389,15 +1389,16 @@ def test_gemm_grouped_fp8_block_scaled(sizes, hint, gated, scale_dtype):
                 assert R.rel_frobenius(c[blk], ref[blk]) <= FP8_TOL, (e, j)
 
 
-# fp8 on the grouped TILE kernel (the matrix cores' scale path, tiles of 256 rows): E8M0 scales (per row of A, per
+# fp8 on the grouped TILE kernel (the matrix cores' scale path, tiles of 256 and of 128 rows): E8M0 scales (per row of A, per
 # 128 x 128 block of each group's B) or none; plain and gated epilogue.  K = 768 (6 K-tiles: no full window of row codes,
 # the row codes of a window end before 8 bytes are up -- also at the very end of the code array), 1152 (9: a full window
 # and a partial one; odd, so one tile per workgroup), 2048 (16: two windows, chained tiles); groups from 1 to 700
 # rows, empty groups, rows outside every group.
+@pytest.mark.parametrize("tiles", [B.AXE_GROUPED_TILES_256, B.AXE_GROUPED_TILES_128])
 @pytest.mark.parametrize("scale_dtype", ["e8m0", None])
 @pytest.mark.parametrize("gated", [False, True])
 @pytest.mark.parametrize("sizes,N,K", [([300, 0, 33, 256, 257, 1], 512, 768), ([70, 700, 5], 768, 1152), ([130, 512, 64, 0, 300, 2], 512, 2048)])
-def test_gemm_grouped_fp8_tile_kernel(sizes, N, K, gated, scale_dtype):
+def test_gemm_grouped_fp8_tile_kernel(sizes, N, K, gated, scale_dtype, tiles):
     off = np.concatenate([[0], np.cumsum(sizes)])
     for M in (int(off[-1]) + 3, int(off[-1])):             # with and without rows behind the last group (the last row's codes end the array)
         g = W.gemm_grouped_fp8(off, N, K, 108 + K, M=M, scale_dtype=scale_dtype or "e8m0")
@@ -1418,9 +1419,9 @@ def test_gemm_grouped_fp8_tile_kernel(sizes, N, K, gated, scale_dtype):
         sb = torch.from_numpy(g.scale_b).cuda() if scale_dtype else None
         desc = B.GroupedGemmDesc(g.M, N, K, g.G, B.Layout(W.row_major_spec(g.M, K)), B.Layout(Bs), B.Layout(W.row_major_spec(g.M, NC)),
                                  g.a_mk.size, img.size, g.M * NC, in_dtype=B.AXE_FP8_E4M3, out_dtype=B.AXE_BF16,
-                                 epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=B.AXE_GROUPED_TILES_256,
+                                 epilogue=B.AXE_EPI_SWIGLU if gated else B.AXE_EPI_NONE, kernel_hint=tiles,
                                  scale_a=sa, scale_b=sb, scale_dtype=B.AXE_SCALE_E8M0)
-        assert B.axe_gemm_grouped_kernel(desc) == B.AXE_GROUPED_TILES_256
+        assert B.axe_gemm_grouped_kernel(desc) == tiles
         B.axe_gemm_grouped(desc, dA, dB, dC, dR)
         torch.cuda.synchronize()
         raw = dC.cpu().numpy().view(np.uint16).reshape(g.M, NC)
