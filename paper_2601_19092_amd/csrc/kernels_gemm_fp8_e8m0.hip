@@ -66,7 +66,7 @@ __device__ __forceinline__ void mfma_scaled(f32x4& acc, i32x8 first, i32x8 secon
 // codes are per 128 x 128 block either way.
 // GROUPED: the grouped GEMM of an MoE layer in fp8 (rows of A and C sorted by group, group e multiplies its rows with
 // its own B; offsets on the device): the tile table, the clipped buffer descriptors and the chained walk of the
-// 16-bit grouped kernel (kernels_gemm_bf16.hip), tiles of 256 rows, A scaled per row (ROWS), each group's B per
+// 16-bit grouped kernel (kernels_gemm_bf16.hip), tiles of 256 or 128 rows (MR below), A scaled per row (ROWS), each group's B per
 // 128 x 128 block, or no scales at all.
 // GATED: B holds each group's gate and up rows interleaved in runs of 16, so that the wave's fragment pair (j, j + 1) is
 // (gate, up) of the same 16 outputs; the tile stores silu(gate) * up, half as wide.  The gate and the up columns of a
