@@ -241,7 +241,7 @@ def bench_transpose(steps, warmup, n_pairs=4):
     return r
 
 
-def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
+def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 256, 512, 2048, 4096)):
     """The expert computation of an MoE layer (hidden 2048, expert intermediate 768, 128 experts, 8 per token), in fp16
     like the paper's layer: gemm1 (gate and up projections, gated activation fused) and gemm2 (down projection) as
     grouped GEMMs over the routed rows sorted by expert, offsets on the device, over a sweep of token counts as in the
@@ -340,7 +340,7 @@ def bench_grouped(steps, warmup, dtype="f16", sweep=(1, 8, 64, 512, 4096)):
     return out
 
 
-def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64, 512, 4096)):
+def bench_grouped_fp8(steps, warmup, sweep=(1, 8, 64, 256, 512, 2048, 4096)):
     """The same layer with e4m3 weights and activations: E8M0 block scales (one per row and 128-wide k block
     for the activations, one per 128 x 128 block for the weights), bf16 output; gemm1 with the gated activation.  The
     weights are half the bytes of the fp16 layer; bound: HBM.  Kernels chosen by the library: the weight-streaming
