@@ -154,6 +154,33 @@ def bench_gemm(name, g, steps, warmup, n_sets=2, device_axis=False, min_warm_ms=
     return r, sets
 
 
+def graph_replay_us(step, launches=64, replays=30):
+    """Device microseconds per launch when `launches` calls of step() are recorded into one HIP graph and the graph
+    is replayed: what a launch-bound loop costs once the host is out of it.  The library allocates nothing and
+    records no memset, so its launches can be captured as they are."""
+    import torch
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step(0)                                                     # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for i in range(launches):
+            step(i)
+    for _ in range(5):
+        graph.replay()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(replays):
+        graph.replay()
+    ev1.record()
+    torch.cuda.synchronize()
+    return ev0.elapsed_time(ev1) * 1e3 / (replays * launches)
+
+
 def bench_relayout(steps, warmup, n_pairs=4):
     import torch
     from paper_2601_19092_amd import binding as B
@@ -544,6 +571,10 @@ def main():
     if want("small"):
         comp["gemm_cfg1_256"], _ = bench_gemm("bf16 GEMM 256^3, fp32 out, 64x64x32 tiles", W.config1(),
                                               max(200, args.steps), max(200, args.warmup), n_sets=1)
+        step1, _sets1, _ = gemm_setup(W.config1(), 1)
+        comp["gemm_cfg1_256"]["graph_replay_us_per_launch"] = graph_replay_us(step1)
+        log(f"[bench] bf16 GEMM 256^3 recorded 64 times into a HIP graph and replayed: "
+            f"{comp['gemm_cfg1_256']['graph_replay_us_per_launch']:.2f} us per launch")
     if want("eval"):
         comp["layout_eval"] = bench_eval(20, 5)
     if want("ceilings"):
