@@ -18,7 +18,8 @@ using axe::bf16x8;
 using axe::f32x4;
 using axe::i32x8;
 
-// bf16: one wave per SIMD (4 per workgroup), 8 x 8 fragments of v_mfma_f32_16x16x32_bf16, j innermost.
+// bf16: one wave per SIMD (4 per workgroup), 8 x 8 fragments of v_mfma_f32_16x16x32_bf16, fragment rows in pairs with j
+// innermost, as the kernel walks them (asm statements: the order issued is the order written).
 __global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __restrict__ in, float* out, int iters) {
   bf16x8 a[8], b[8];
 #pragma unroll
@@ -32,10 +33,13 @@ __global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __rest
     for (int j = 0; j < 8; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
-    for (int i = 0; i < 8; ++i)
-#pragma unroll
-      for (int j = 0; j < 8; ++j) acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(b[j], a[i], acc[i][j], 0, 0, 0);
+    for (int t = 0; t < 64; ++t) {
+      const int i = 2 * (t >> 4) + (t & 1), j = (t >> 1) & 7;
+      asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(b[j]), "v"(a[i]));
+    }
   }
+  asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");              // the MFMAs retire before their results are read
+  __builtin_amdgcn_sched_barrier(0);
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < 8; ++i)
