@@ -11,7 +11,8 @@
 //    that walks the accumulators in register order, issued by a single wave per SIMD, sustains
 //    1.9 - 2.0 PFLOP/s where 32x32x16 MFMAs, or two interleaved waves per SIMD, sustain 1.7 - 1.8.
 //    Hence one wave per SIMD, 16x16x32; and the order of the walk matters too: fragment rows in pairs,
-//    (r, j), (r + 1, j) with j innermost, draw less than row by row (2.1 against 2.05 PFLOP/s register-only).
+//    (r, j), (r + 1, j) with j innermost, every other pair backwards, draw less than row by row (2.08 against
+//    2.0 - 2.05 PFLOP/s register-only).
 //  * The L2 -> CU path is the second bound: a 256 x 256 tile pulls 64 KiB per 64 K-elements, about
 //    three quarters of what the L2s deliver to all CUs at once, and only when every request is a
 //    whole 128-byte line.  Hence 64-wide K-tiles: every load instruction fetches 8 rows x 128 bytes.
@@ -471,12 +472,14 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
 #pragma unroll
       for (int j = 0; j < NJ; ++j) {
         // (i, j) is the slot of the schedule; the fragment multiplied in it is (mi, mj): the rows are walked in pairs,
-        // (r, 0), (r + 1, 0), (r, 1), (r + 1, 1), ... -- every accumulator sees the same sequence of K-steps as in a
+        // (r, 0), (r + 1, 0), (r, 1), (r + 1, 1), ..., every other pair from the last column back to the first (so that
+        // the B fragment stays when the pair changes) -- every accumulator sees the same sequence of K-steps as in a
         // row-by-row walk (same bits), but the matrix pipe draws less power, and power bounds these kernels: a
-        // register-only loop of this MFMA on the same data sustains 2100 TFLOP/s in this order against 2050 row by
-        // row (2x2 blocks 2105, four-row blocks 2020, a diagonal walk 1975), the 8192^3 GEMM 1564 against 1539.
+        // register-only loop of this MFMA on the same data sustains 2080 TFLOP/s in this order against 2015 row by
+        // row (pairs all in the same direction 2068, four-row blocks 2020, a diagonal walk 1975), the 8192^3 GEMM
+        // 1564 against 1539 with the pairs and another 0.4 % with the alternating direction.
         const int mr = (i & 1) * NJ + j;
-        const int mi = 2 * (i >> 1) + (mr & 1), mj = mr >> 1;
+        const int mi = 2 * (i >> 1) + (mr & 1), mj = ((i >> 1) & 1) ? NJ - 1 - (mr >> 1) : (mr >> 1);
         mfma_16x16x32<F16>(acc[mi][mj], fb[CUR][mj], fa[mi]);
         __builtin_amdgcn_sched_barrier(0);
         if constexpr (LATE && S == 1) {
@@ -487,7 +490,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
             fb[NXT][2 * (i - 2) + (j == 5)] = lds_read(pb + (2 * (i - 2) + (j == 5)) * 16 * kRow);
           if (i == 2 && j == 4) fa[0] = lds_read(pa);
           if (i == 3 && j == 4) fa[1] = lds_read(pa + 16 * kRow);
-          if (mi >= 2 && mj == NJ - 1) fa[mi] = lds_read(pa + mi * 16 * kRow);
+          if (mi >= 2 && (mr >> 1) == NJ - 1) fa[mi] = lds_read(pa + mi * 16 * kRow);
           // the 8 A pieces of step kt + 2 first (they have one K-step to land), then four B loads
           if (i >= 2 && i < 6 && (j == 2 || j == 6)) a_dload(kt + 2, 2 * (i - 2) + (j == 6), CROSS);
           if (i >= 6 && (j == 2 || j == 6)) b_load(bT, 2 * (i - 6) + (j == 6), bslot, CROSS);
@@ -496,7 +499,7 @@ __device__ __forceinline__ void gemm_bf16_256_body(const GemmArgs& g, const Pair
           constexpr int jb0 = MR == 8 ? 1 : 0, jb1 = MR == 8 ? 5 : 3;
           if (i < 4 && (j == jb0 || j == jb1) && 2 * i + (j == jb1) < NJ)
             fb[NXT][2 * i + (j == jb1)] = lds_read(pb + (2 * i + (j == jb1)) * 16 * kRow);
-          if (mj == NJ - 1) fa[mi] = lds_read(pa + mi * 16 * kRow);
+          if ((mr >> 1) == NJ - 1) fa[mi] = lds_read(pa + mi * 16 * kRow);
           if constexpr (MR == 4 && S == 1) {
             // 128-row tiles, sub-step 1 (right after the barrier): the 4 A pieces of step kt + 2, then four B loads
             if (i < 2 && (j == 2 || j == 6)) a_dload(kt + 2, 2 * i + (j == 6), CROSS);

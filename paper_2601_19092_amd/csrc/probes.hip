@@ -19,7 +19,7 @@ using axe::f32x4;
 using axe::i32x8;
 
 // bf16: one wave per SIMD (4 per workgroup), 8 x 8 fragments of v_mfma_f32_16x16x32_bf16, fragment rows in pairs with j
-// innermost, as the kernel walks them (asm statements: the order issued is the order written).
+// innermost, every other pair backwards, as the kernel walks them (asm statements: the order issued is the order written).
 __global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __restrict__ in, float* out, int iters) {
   bf16x8 a[8], b[8];
 #pragma unroll
@@ -34,7 +34,7 @@ __global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __rest
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int t = 0; t < 64; ++t) {
-      const int i = 2 * (t >> 4) + (t & 1), j = (t >> 1) & 7;
+      const int i = 2 * (t >> 4) + (t & 1), j = ((t >> 4) & 1) ? 7 - ((t >> 1) & 7) : (t >> 1) & 7;
       asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(b[j]), "v"(a[i]));
     }
   }
