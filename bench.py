@@ -464,6 +464,26 @@ def bench_ceilings(g3, g5, steps=20, warmup=5):
                 sys.exit(f"bench.py: axe_probe_mfma failed ({rc})")
         _, devms = time_loop(launch, steps, warmup)
         out[key + "_register_only_tflops"] = flops.value / (devms * 1e-3) / 1e12
+    # the same bf16 loop with its MFMAs issued in other orders: what the order alone does to the sustained rate
+    P.axe_probe_mfma_walk.restype = C.c_int
+    P.axe_probe_mfma_walk.argtypes = P.axe_probe_mfma.argtypes
+    sample = dev(g3.a_mk.reshape(-1).view(np.uint8)[g3.a_mk.nbytes // 2:][:16 * 256 * 16].copy())
+    walks = {"kernel (row pairs, alternating direction)": 0, "row by row": 1, "row pairs, one direction": 2,
+             "diagonal": 3, "rows in fours": 4}
+    by_walk = {k: [] for k in walks}
+    for rnd in range(2):                                            # alternating, so that drift of the clock hits all alike
+        for name, walk in walks.items():
+            flops = C.c_double(0.0)
+            def launch(i, walk=walk):
+                rc = P.axe_probe_mfma_walk(walk, sample.data_ptr(), sample.numel(), 4000, sink.data_ptr(), sink.numel(), C.byref(flops),
+                                           torch.cuda.current_stream().cuda_stream)
+                if rc:
+                    sys.exit(f"bench.py: axe_probe_mfma_walk failed ({rc})")
+            _, devms = time_loop(launch, 20, 5)
+            by_walk[name].append(flops.value / (devms * 1e-3) / 1e12)
+    out["mfma_bf16_register_only_tflops_by_walk"] = {k: sum(v) / len(v) for k, v in by_walk.items()}
+    log("[bench] register-only bf16 MFMA loop by order of the 64 MFMAs of a pass: " +
+        ", ".join(f"{k} {v:.0f}" for k, v in out["mfma_bf16_register_only_tflops_by_walk"].items()) + " TFLOP/s")
     n = 8192 * 8192
     pairs = [(torch.randint(-30000, 30000, (n,), dtype=torch.int16, device="cuda"),
               torch.empty(n, dtype=torch.int16, device="cuda")) for _ in range(4)]

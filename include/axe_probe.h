@@ -33,6 +33,15 @@ extern "C" {
 int axe_probe_mfma(int32_t fp8, const void* sample, size_t sample_bytes, int32_t iters, float* sink, size_t sink_floats,
                    double* flops, void* stream);
 
+/* The bf16 loop of axe_probe_mfma with its 64 MFMAs per pass issued in another order (same instructions, operands and
+ * accumulators): what the order alone does to the power the matrix pipe draws, hence to the clock, hence to the rate.
+ * walk 0: the GEMM kernel's (fragment rows in pairs, every other pair from the last column back; = axe_probe_mfma),
+ * 1: row by row, 2: rows in pairs all in one direction, 3: diagonal (both operands change at every MFMA), 4: rows in
+ * blocks of four.  Arguments and return value as axe_probe_mfma (sample: AXE_PROBE_SAMPLE_BF16 bytes; sink: 256 floats
+ * per compute unit). */
+int axe_probe_mfma_walk(int32_t walk, const void* sample, size_t sample_bytes, int32_t iters, float* sink, size_t sink_floats,
+                        double* flops, void* stream);
+
 /* Launches, on `stream`, ONE matrix instruction of one wave on operand registers the caller supplies, and returns the
  * accumulator registers: the experiment that shows which (lane, register) holds which element of the operands and of
  * the result.  The instruction is issued as the GEMM kernels issue it (B fragment first, A fragment second, zero

@@ -20,7 +20,10 @@ using axe::i32x8;
 
 // bf16: one wave per SIMD (4 per workgroup), 8 x 8 fragments of v_mfma_f32_16x16x32_bf16, fragment rows in pairs with j
 // innermost, every other pair backwards, as the kernel walks them (asm statements: the order issued is the order written).
-__global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __restrict__ in, float* out, int iters) {
+// WALK: 0 = the kernel's (rows in pairs, every other pair backwards), 1 = row by row, 2 = rows in pairs all in one
+// direction, 3 = diagonal (both operands change at every MFMA), 4 = rows in blocks of four.
+template <int WALK>
+__device__ __forceinline__ void probe_bf16_body(const bf16x8* __restrict__ in, float* out, int iters) {
   bf16x8 a[8], b[8];
 #pragma unroll
   for (int i = 0; i < 8; ++i) a[i] = in[i * 256 + threadIdx.x];
@@ -34,7 +37,12 @@ __global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __rest
   for (int it = 0; it < iters; ++it) {
 #pragma unroll
     for (int t = 0; t < 64; ++t) {
-      const int i = 2 * (t >> 4) + (t & 1), j = ((t >> 4) & 1) ? 7 - ((t >> 1) & 7) : (t >> 1) & 7;
+      int i, j;
+      if (WALK == 0) i = 2 * (t >> 4) + (t & 1), j = ((t >> 4) & 1) ? 7 - ((t >> 1) & 7) : (t >> 1) & 7;
+      else if (WALK == 1) i = t >> 3, j = t & 7;
+      else if (WALK == 2) i = 2 * (t >> 4) + (t & 1), j = (t >> 1) & 7;
+      else if (WALK == 3) i = t & 7, j = ((t >> 3) + t) & 7;
+      else i = 4 * (t >> 5) + (t & 3), j = (t >> 2) & 7;
       asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+a"(acc[i][j]) : "v"(b[j]), "v"(a[i]));
     }
   }
@@ -47,6 +55,11 @@ __global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __rest
     for (int j = 0; j < 8; ++j) s += acc[i][j][0] + acc[i][j][1] + acc[i][j][2] + acc[i][j][3];
   out[blockIdx.x * 256 + threadIdx.x] = s;
 }
+__global__ __launch_bounds__(256, 1) void probe_bf16_kernel(const bf16x8* __restrict__ in, float* out, int iters) { probe_bf16_body<0>(in, out, iters); }
+__global__ __launch_bounds__(256, 1) void probe_bf16_rows_kernel(const bf16x8* __restrict__ in, float* out, int iters) { probe_bf16_body<1>(in, out, iters); }
+__global__ __launch_bounds__(256, 1) void probe_bf16_pairs_kernel(const bf16x8* __restrict__ in, float* out, int iters) { probe_bf16_body<2>(in, out, iters); }
+__global__ __launch_bounds__(256, 1) void probe_bf16_diagonal_kernel(const bf16x8* __restrict__ in, float* out, int iters) { probe_bf16_body<3>(in, out, iters); }
+__global__ __launch_bounds__(256, 1) void probe_bf16_fours_kernel(const bf16x8* __restrict__ in, float* out, int iters) { probe_bf16_body<4>(in, out, iters); }
 
 // fp8: two waves per SIMD (8 per workgroup), 8 x 4 fragments of v_mfma_f32_16x16x128_f8f6f4, j innermost.
 __global__ __launch_bounds__(512, 1) void probe_fp8_kernel(const i32x8* __restrict__ in, float* out, int iters) {
@@ -156,6 +169,26 @@ extern "C" int axe_probe_stream(int32_t kind, const void* src, void* dst, size_t
   if (kind == 0) hipLaunchKernelGGL(probe_stream_kernel<0>, grid, block, 0, st, (const probe_u32x4*)src, (probe_u32x4*)dst, n);
   else if (kind == 1) hipLaunchKernelGGL(probe_stream_kernel<1>, grid, block, 0, st, (const probe_u32x4*)src, (probe_u32x4*)(dst ? dst : (void*)src), n);
   else hipLaunchKernelGGL(probe_stream_kernel<2>, grid, block, 0, st, (const probe_u32x4*)dst, (probe_u32x4*)dst, n);
+  return hipGetLastError() == hipSuccess ? 0 : 2;
+}
+
+extern "C" int axe_probe_mfma_walk(int32_t walk, const void* sample, size_t sample_bytes, int32_t iters, float* sink, size_t sink_floats,
+                                   double* flops, void* stream) {
+  const int cus = axe::cu_count();
+  if (walk < 0 || walk > 4 || !sample || !sink || !flops || iters <= 0 || sample_bytes < AXE_PROBE_SAMPLE_BF16 ||
+      sink_floats < (size_t)cus * 256 || ((uintptr_t)sample & 31))
+    return 1;
+  const dim3 grid(cus), block(256);
+  hipStream_t st = (hipStream_t)stream;
+  const bf16x8* in = (const bf16x8*)sample;
+  switch (walk) {
+    case 0: hipLaunchKernelGGL(probe_bf16_kernel, grid, block, 0, st, in, sink, iters); break;
+    case 1: hipLaunchKernelGGL(probe_bf16_rows_kernel, grid, block, 0, st, in, sink, iters); break;
+    case 2: hipLaunchKernelGGL(probe_bf16_pairs_kernel, grid, block, 0, st, in, sink, iters); break;
+    case 3: hipLaunchKernelGGL(probe_bf16_diagonal_kernel, grid, block, 0, st, in, sink, iters); break;
+    default: hipLaunchKernelGGL(probe_bf16_fours_kernel, grid, block, 0, st, in, sink, iters); break;
+  }
+  *flops = 2.0 * 16 * 16 * 32 * 64 * (double)iters * 4 * cus;
   return hipGetLastError() == hipSuccess ? 0 : 2;
 }
 

@@ -33,7 +33,7 @@ def test_probe_library_exports_what_its_header_declares():
     text = open(os.path.join(ROOT, "include", "axe_probe.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = sorted(set(re.findall(r"\b(axe_[a-z_0-9]+)\s*\(", text)))
-    assert names == ["axe_probe_mfma", "axe_probe_mfma_fragment", "axe_probe_stream"]
+    assert names == ["axe_probe_mfma", "axe_probe_mfma_fragment", "axe_probe_mfma_walk", "axe_probe_stream"]
     P = C.CDLL(os.path.join(os.path.dirname(B.LIB_PATH), "libaxe_probe.so"))
     for n in names:
         assert getattr(P, n) is not None
