@@ -1275,8 +1275,9 @@ def test_gemm_fp8_row_scaled_activations(M, N, K, scale_dtype):
 # boundary).  The row codes differ from row to row and from k block to k block over a range of 2^11.
 # K = 128, 768 and 1152: 1, 6 and 9 K-tiles -- a partial window of row codes only (its 8-byte reads run on into the next
 # row and, for the last rows, start early at the end of the array), and a full window followed by a partial one.
+# 8192 x 8192 x 2048: the tile grid and launch of configuration 5 (32 x 32 tiles, four chained per workgroup), two windows of codes.
 @pytest.mark.parametrize("M,N,K", [(256, 256, 1024), (512, 768, 2048), (768, 512, 3072), (256, 512, 9216), (4352, 4096, 2048),
-                                   (256, 256, 128), (512, 256, 768), (256, 512, 1152)])
+                                   (256, 256, 128), (512, 256, 768), (256, 512, 1152), (8192, 8192, 2048)])
 def test_gemm_fp8_row_scaled_activations_large_tile(M, N, K):
     g = W.gemm_fp8(M, N, K, 107, scaled="e8m0")
     rng = np.random.default_rng(M + K)
